@@ -1,0 +1,265 @@
+"""CPU oracle for the offloaded sparse-decode hot path of KVDrive.
+
+TEST INFRASTRUCTURE ONLY.  This module is the slow, plain definition that the
+HIP library is checked against.  It may be imported by ``tests/``, by
+``__graft_entry__.smoke()`` and by the ``cpu_baseline`` leg of ``bench.py``,
+and by nothing else; the product path never calls it and shares no code,
+constants or helpers with it.
+
+Everything is numpy in fp64, one (layer, sequence, KV-head) *unit* at a time,
+in the order the paper gives for one decode step of one layer
+(Background, "KV Cache Offloading": (1) select critical entries through the
+index held in GPU memory, (2) fetch them, (3) compute sparse attention):
+
+  page_summaries   index entry = mean key of each page          (System Overview)
+  pooled_query     one query per KV head for the GQA group      (reading, see below)
+  page_scores      query x index                                (Background, "retrieving the Top-K")
+  select_pages     Top-K pages, sink/local pages always kept    (Background; Experiment "Baselines")
+  LruWindow        the in-GPU window of recently critical pages (Motivation "critical KV window";
+                   with LRU replacement                          Cache Management: LRU is the baseline policy)
+  attend           softmax attention over the selected tokens   (System Overview, step 3)
+
+Readings taken where the paper is silent (each one is also listed in the design
+notes of the repository):
+  * the page representative is the mean over the page's *valid* tokens, per KV
+    head, rounded once to the KV dtype (the index is stored in that dtype);
+  * the G query heads of a GQA group are mean-pooled into one query;
+  * score = pooled_query . summary / sqrt(D)   (same scale as attention logits);
+  * ties in the Top-K go to the lower page index;
+  * sink / recent pages are selected unconditionally and count inside k;
+  * every selected page gets stamp = step index; LRU victim = smallest
+    (stamp, page) among resident pages that are not selected in this step.
+
+Parity status.  select/LRU/attend/summaries are pinned in tests by brute force,
+closed forms, library routines and hand-worked fixtures (tests/golden).
+Fidelity to numbers *printed in the paper* is "parity unpinned": the paper
+prints no worked numeric example for this path.
+"""
+from __future__ import annotations
+
+import numpy as np
+
+F16 = 0
+BF16 = 1
+
+# (exponent bits, stored mantissa bits) of the two KV dtypes
+_FORMAT = {F16: (5, 10), BF16: (8, 7)}
+
+
+# --------------------------------------------------------------------------- #
+# exact dtype conversions
+# --------------------------------------------------------------------------- #
+def bits_to_f64(bits, dtype):
+    """Widen fp16 / bf16 bit patterns (uint16) to fp64.  Exact."""
+    bits = np.asarray(bits, dtype=np.uint16)
+    if dtype == F16:
+        return bits.view(np.float16).astype(np.float64)
+    if dtype == BF16:
+        return (bits.astype(np.uint32) << np.uint32(16)).view(np.float32).astype(np.float64)
+    raise ValueError("dtype")
+
+
+def round_f64(x, dtype):
+    """Round fp64 values to the nearest fp16 / bf16 value (ties to even), in one
+    rounding, and return them still as fp64.
+
+    The quantum of a binary format at magnitude 2^(e-1) <= |x| < 2^e is
+    2^(e-1-mbits), never below the subnormal quantum; x / quantum is an exact
+    power-of-two scaling, and rint rounds half to even.
+    """
+    ebits, mbits = _FORMAT[dtype]
+    bias = (1 << (ebits - 1)) - 1
+    x = np.asarray(x, dtype=np.float64)
+    _, e = np.frexp(x)                                   # |x| in [2^(e-1), 2^e)
+    qexp = np.maximum(e - 1 - mbits, 1 - bias - mbits)   # clamp at the subnormal quantum
+    q = np.ldexp(1.0, qexp)
+    r = np.rint(x / q) * q
+    max_finite = (2.0 - 2.0 ** (-mbits)) * 2.0 ** bias
+    r = np.where(np.abs(r) > max_finite, np.copysign(np.inf, r), r)
+    return np.where(np.isfinite(x), r, x)
+
+
+def f64_to_bits(x, dtype):
+    """fp64 -> fp16 / bf16 bit patterns with a single round-to-nearest-even."""
+    r = round_f64(x, dtype)
+    if dtype == F16:
+        return r.astype(np.float16).view(np.uint16)       # exact: r is representable
+    return (r.astype(np.float32).view(np.uint32) >> np.uint32(16)).astype(np.uint16)
+
+
+# --------------------------------------------------------------------------- #
+# index: page summaries
+# --------------------------------------------------------------------------- #
+def page_summaries(keys, page_size, seq_len, dtype):
+    """Mean key of each page (System Overview: "the mean key of each page is
+    used as its representative").
+
+    keys    : [T_alloc, D] fp64 keys of one unit (already widened from the KV dtype)
+    returns : [NPvalid, D] fp64, each entry rounded once to `dtype`;
+              NPvalid = ceil(seq_len / page_size); a partial last page averages
+              its valid tokens only.
+    """
+    P = int(page_size)
+    seq_len = int(seq_len)
+    n_valid = -(-seq_len // P)
+    D = keys.shape[1]
+    acc = np.zeros((n_valid, D), dtype=np.float64)
+    count = np.zeros(n_valid, dtype=np.float64)
+    first = np.arange(n_valid) * P                        # first token of each page
+    for j in range(P):                                    # token order inside the page
+        tok = first + j
+        ok = tok < seq_len
+        acc[ok] = acc[ok] + keys[tok[ok]]
+        count[ok] += 1.0
+    return round_f64(acc / count[:, None], dtype)
+
+
+# --------------------------------------------------------------------------- #
+# selection
+# --------------------------------------------------------------------------- #
+def pooled_query(q_group):
+    """One query per KV head: the mean of the group's G query heads
+    (g ascending).  q_group: [G, D] fp64."""
+    G = q_group.shape[0]
+    acc = np.zeros(q_group.shape[1], dtype=np.float64)
+    for g in range(G):
+        acc = acc + q_group[g]
+    return acc / float(G)
+
+
+def page_scores(qbar, summaries, scale):
+    """score[p] = scale * sum_d qbar[d] * summary[p, d]
+    (Background: the query is multiplied with the index representatives)."""
+    return scale * (summaries @ qbar)
+
+
+def select_pages(scores, k, sink_pages=0, recent_pages=0):
+    """Top-K pages of one unit (Background: "retrieving only the Top-K").
+
+    scores : [NPvalid] fp64.  Pages p < sink_pages and p >= NPvalid - recent_pages
+             are always kept (Experiment, Baselines: sink and local tokens stay
+             on the GPU) and count inside k.
+    Order  : larger score first, ties to the lower page index.
+    returns: int32 [k], ascending page index, padded with -1 if NPvalid < k.
+    """
+    n = int(scores.shape[0])
+    s = np.array(scores, dtype=np.float64)
+    forced = np.zeros(n, dtype=bool)
+    forced[: min(int(sink_pages), n)] = True
+    if recent_pages > 0:
+        forced[max(0, n - int(recent_pages)):] = True
+    if int(forced.sum()) > k:
+        raise ValueError("forced pages exceed k")
+    s[forced] = np.inf
+    order = sorted(range(n), key=lambda p: (-s[p], p))    # (score desc, page asc)
+    chosen = sorted(order[: min(k, n)])
+    out = np.full(k, -1, dtype=np.int32)
+    out[: len(chosen)] = chosen
+    return out
+
+
+# --------------------------------------------------------------------------- #
+# the in-GPU window with LRU replacement
+# --------------------------------------------------------------------------- #
+class LruWindow:
+    """Resident set of one unit: at most `capacity` pages, each with the step
+    index at which it was last selected (Motivation: a window of recently
+    critical entries kept in GPU memory; only entries outside it are fetched —
+    Roofline section: "only out-of-cache critical KV entries" move).
+    """
+
+    def __init__(self, capacity):
+        self.capacity = int(capacity)
+        self.stamp = {}                                   # page -> step of last selection
+
+    def warm(self, pages, stamp=-1):
+        for p in pages:
+            if len(self.stamp) >= self.capacity and p not in self.stamp:
+                raise ValueError("warm list exceeds capacity")
+            self.stamp[int(p)] = int(stamp)
+
+    def resident(self):
+        return sorted(self.stamp)
+
+    def resolve(self, sel, step):
+        """Process one step's selection.  Returns (hits, misses, evicted), each a
+        sorted list of page indices.  Misses are inserted in ascending page
+        order; when the window is full the victim is the resident page, not
+        selected in this step, with the smallest (stamp, page).
+        """
+        sel = [int(p) for p in sel if p >= 0]
+        if len(sel) > self.capacity:
+            raise ValueError("k exceeds capacity")
+        selset = set(sel)
+        hits = sorted(p for p in sel if p in self.stamp)
+        misses = sorted(p for p in sel if p not in self.stamp)
+        for p in hits:
+            self.stamp[p] = int(step)
+        evicted = []
+        for p in misses:
+            if len(self.stamp) >= self.capacity:
+                cands = [(s, r) for r, s in self.stamp.items() if r not in selset]
+                _, victim = min(cands)
+                del self.stamp[victim]
+                evicted.append(victim)
+            self.stamp[p] = int(step)
+        return hits, misses, sorted(evicted)
+
+
+# --------------------------------------------------------------------------- #
+# sparse attention
+# --------------------------------------------------------------------------- #
+def selected_tokens(sel, page_size, seq_len):
+    """Token indices covered by the selected pages, valid tokens only."""
+    toks = []
+    for p in sel:
+        if p < 0:
+            continue
+        lo, hi = int(p) * page_size, min((int(p) + 1) * page_size, int(seq_len))
+        toks.extend(range(lo, hi))
+    return np.asarray(toks, dtype=np.int64)
+
+
+def attend(q_group, keys, values, scale):
+    """Exact softmax attention of each query head of the group over the given
+    tokens (System Overview step 3: attention over resident + fetched entries).
+
+    q_group [G, D], keys [n, D], values [n, D] fp64.
+    returns out [G, D], lse [G]   with lse = log sum_i exp(scale * q.k_i).
+    """
+    G, D = q_group.shape
+    out = np.zeros((G, D), dtype=np.float64)
+    lse = np.zeros(G, dtype=np.float64)
+    for g in range(G):
+        x = scale * (keys @ q_group[g])
+        m = np.max(x)
+        w = np.exp(x - m)
+        denom = np.sum(w)
+        out[g] = (w @ values) / denom
+        lse[g] = m + np.log(denom)
+    return out, lse
+
+
+# --------------------------------------------------------------------------- #
+# one unit, one step: the three stages in the paper's order
+# --------------------------------------------------------------------------- #
+def decode_unit_step(q_group, summaries, keys, values, window, step, *, k, page_size,
+                     seq_len, scale, sink_pages=0, recent_pages=0, forced_sel=None):
+    """select -> fetch bookkeeping -> attend for one unit.
+
+    q_group   [G, D] fp64 (queries already rounded to the KV dtype by the caller)
+    summaries [NPvalid, D] fp64, keys/values [T, D] fp64 (the host store of this unit)
+    window    LruWindow carried across steps
+    forced_sel: if given, this selection replaces the oracle's own (used by the
+              parity harness after a score tie inside the 1e-6 band).
+    returns dict(scores, sel, hits, misses, evicted, out, lse)
+    """
+    qbar = pooled_query(q_group)
+    scores = page_scores(qbar, summaries, scale)
+    sel = select_pages(scores, k, sink_pages, recent_pages)
+    used = sel if forced_sel is None else np.asarray(forced_sel, dtype=np.int32)
+    hits, misses, evicted = window.resolve(used, step)
+    toks = selected_tokens(used, page_size, seq_len)
+    out, lse = attend(q_group, keys[toks], values[toks], scale)
+    return dict(scores=scores, sel=sel, used=used, hits=hits, misses=misses,
+                evicted=evicted, out=out, lse=lse)

@@ -1,0 +1,371 @@
+"""Pins for the CPU oracle: each stage is checked against something other than
+itself — hand-worked fixtures, closed forms, brute force, library routines and
+invariants — chosen so that a dropped term, a wrong sign or index, or a
+transposed operand fails at least one of them.  CPU only.
+"""
+import itertools
+import math
+
+import numpy as np
+import pytest
+import scipy.special
+import torch
+
+from oracle import kvd_oracle as orc
+from tests import helpers as H
+
+RNG = np.random.default_rng(20260518)
+
+
+# --------------------------------------------------------------------------- #
+# dtype conversions
+# --------------------------------------------------------------------------- #
+def _all_values(dtype):
+    b = np.arange(65536, dtype=np.uint32).astype(np.uint16)
+    if dtype == orc.F16:
+        v = torch.from_numpy(b.view(np.int16)).view(torch.float16).to(torch.float64).numpy()
+    else:
+        v = torch.from_numpy(b.view(np.int16)).view(torch.bfloat16).to(torch.float64).numpy()
+    return b, v
+
+
+@pytest.mark.parametrize("dtype", [orc.F16, orc.BF16])
+def test_bits_to_f64_matches_torch_widening(dtype):
+    b, v = _all_values(dtype)
+    got = orc.bits_to_f64(b, dtype)
+    same = (got == v) | (np.isnan(got) & np.isnan(v))
+    assert same.all()
+
+
+@pytest.mark.parametrize("dtype", [orc.F16, orc.BF16])
+def test_round_f64_is_nearest_even_by_brute_force(dtype):
+    """Nearest representable value found by searching the sorted table of all
+    finite values of the format; ties resolved to the even mantissa."""
+    b, v = _all_values(dtype)
+    fin = np.isfinite(v) & ~((v == 0) & (b >> 15 == 1))          # drop -0 duplicate
+    vals, pats = v[fin], b[fin]
+    order = np.argsort(vals, kind="stable")
+    vals, pats = vals[order], pats[order]
+    scale = 2.0 ** RNG.integers(-30 if dtype == orc.F16 else -140, 14, size=4000)
+    x = RNG.standard_normal(4000) * scale
+    # exact midpoints between neighbours must go to the even pattern
+    mids_i = RNG.integers(0, len(vals) - 1, size=500)
+    mids = (vals[mids_i] + vals[mids_i + 1]) / 2.0                # exact in fp64
+    x = np.concatenate([x, mids, vals[RNG.integers(0, len(vals), 200)]])
+    got = orc.round_f64(x, dtype)
+    for xi, gi in zip(x, got):
+        if abs(xi) > vals[-1]:
+            continue
+        j = np.searchsorted(vals, xi)
+        cands = [c for c in (j - 1, j) if 0 <= c < len(vals)]
+        best = min(cands, key=lambda c: (abs(vals[c] - xi), int(pats[c]) & 1))
+        assert gi == vals[best], (xi, gi, vals[best])
+
+
+def test_f16_rounding_matches_numpy_cast():
+    x = RNG.standard_normal(20000) * 2.0 ** RNG.integers(-26, 17, size=20000)
+    want = x.astype(np.float16)
+    got = orc.f64_to_bits(x, orc.F16).view(np.float16)
+    assert np.array_equal(got.view(np.uint16), want.view(np.uint16))
+
+
+def test_bf16_rounding_known_values():
+    # 1 + 2^-8 is the midpoint between 1 and 1 + 2^-7: ties to even -> 1
+    assert orc.round_f64(np.array([1.0 + 2.0 ** -8]), orc.BF16)[0] == 1.0
+    # 1 + 3*2^-8 is the midpoint between 1+2^-7 (odd) and 1+2^-6 (even)
+    assert orc.round_f64(np.array([1.0 + 3 * 2.0 ** -8]), orc.BF16)[0] == 1.0 + 2.0 ** -6
+    assert orc.round_f64(np.array([1.0 + 2.0 ** -8 + 2.0 ** -40]), orc.BF16)[0] == 1.0 + 2.0 ** -7
+    assert orc.f64_to_bits(np.array([1.0]), orc.BF16)[0] == 0x3F80
+    assert orc.f64_to_bits(np.array([-2.5]), orc.BF16)[0] == 0xC020
+    # fp32 -> bf16 of torch agrees wherever the value is an exact fp32
+    x32 = (RNG.standard_normal(20000) * 2.0 ** RNG.integers(-20, 20, size=20000)).astype(np.float32)
+    want = H.bits(torch.from_numpy(x32).to(torch.bfloat16))
+    assert np.array_equal(orc.f64_to_bits(x32.astype(np.float64), orc.BF16), want)
+
+
+# --------------------------------------------------------------------------- #
+# summaries
+# --------------------------------------------------------------------------- #
+@pytest.mark.parametrize("dtype", [orc.F16, orc.BF16])
+def test_summaries_closed_forms(dtype):
+    P, D = 16, 8
+    keys = np.zeros((3 * P, D))
+    keys[:P] = np.linspace(-2, 2, D)[None, :] * 0.5               # constant page -> the key itself
+    keys[P:2 * P] = np.where(np.arange(P)[:, None] % 2 == 0, 1.75, -1.75)   # +x,-x alternating -> 0
+    keys[2 * P:] = np.arange(P)[:, None] * np.ones(D)              # 0..15 -> 7.5
+    s = orc.page_summaries(keys, P, 3 * P, dtype)
+    assert np.array_equal(s[0], orc.round_f64(keys[0], dtype))
+    assert np.array_equal(s[1], np.zeros(D))
+    assert np.array_equal(s[2], np.full(D, 7.5))
+
+
+def test_summaries_vs_numpy_mean_and_partial_page():
+    P, D, T = 8, 16, 8 * 5 + 3                                     # ragged last page: 3 valid tokens
+    k16 = (RNG.standard_normal((48, D))).astype(np.float16)
+    keys = k16.astype(np.float64)
+    s = orc.page_summaries(keys, P, T, orc.F16)
+    assert s.shape == (6, D)
+    for p in range(6):
+        lo, hi = p * P, min((p + 1) * P, T)
+        want = np.mean(keys[lo:hi], axis=0).astype(np.float16).astype(np.float64)
+        assert np.array_equal(s[p], want)
+    # tokens beyond seq_len must not leak into the last page
+    keys2 = keys.copy()
+    keys2[T:] = 1e4
+    assert np.array_equal(orc.page_summaries(keys2, P, T, orc.F16), s)
+
+
+# --------------------------------------------------------------------------- #
+# scores
+# --------------------------------------------------------------------------- #
+def test_pooled_query_and_scores_reduce_to_dot_products():
+    G, D, T = 4, 32, 50
+    q = RNG.standard_normal((G, D))
+    k = RNG.standard_normal((T, D))
+    qbar = orc.pooled_query(q)
+    assert np.allclose(qbar, q.mean(axis=0), rtol=0, atol=1e-15)
+    # page size 1: the summary is the key, the score is the scaled dot product
+    summ = orc.page_summaries(orc.round_f64(k, orc.F16), 1, T, orc.F16)
+    scale = 1.0 / math.sqrt(D)
+    sc = orc.page_scores(qbar, summ, scale)
+    want = np.array([sum(qbar[d] * summ[t, d] for d in range(D)) * scale for t in range(T)])
+    assert np.allclose(sc, want, rtol=1e-13, atol=1e-14)
+    # linearity in the query
+    q2 = RNG.standard_normal((G, D))
+    lhs = orc.page_scores(orc.pooled_query(q + q2), summ, scale)
+    rhs = sc + orc.page_scores(orc.pooled_query(q2), summ, scale)
+    assert np.allclose(lhs, rhs, rtol=0, atol=1e-12)
+    # a transposed operand or a pooled sum instead of a mean would break this:
+    e0 = np.zeros((G, D)); e0[:, 3] = 2.0
+    assert np.allclose(orc.page_scores(orc.pooled_query(e0), summ, 1.0), 2.0 * summ[:, 3])
+
+
+# --------------------------------------------------------------------------- #
+# selection
+# --------------------------------------------------------------------------- #
+def test_select_golden_fixture():
+    for scores, k, sink, recent, want in H.read_golden("select_ties.txt"):
+        s = np.array([float(x) for x in scores.split()])
+        got = orc.select_pages(s, int(k), int(sink), int(recent))
+        assert got.tolist() == [int(x) for x in want.split()], (scores, k, sink, recent)
+
+
+def test_select_vs_lexsort_and_special_cases():
+    for n, k in [(7, 3), (64, 64), (100, 1), (257, 31), (1000, 128)]:
+        s = np.round(RNG.standard_normal(n), 1)                   # coarse grid -> many ties
+        got = orc.select_pages(s, k)
+        order = np.lexsort((np.arange(n), -s))                    # primary: -score, then page
+        assert got.tolist() == sorted(order[:k].tolist())
+        if k == 1:
+            assert got[0] == int(np.argmax(s))                     # argmax returns the first maximum
+        if k == n:
+            assert got.tolist() == list(range(n))
+    s = RNG.standard_normal(300)
+    prev = set()
+    for k in range(1, 60):
+        cur = set(orc.select_pages(s, k).tolist())
+        assert prev < cur and len(cur) == k
+        prev = cur
+
+
+def test_select_forced_pages_and_errors():
+    s = RNG.standard_normal(40)
+    got = orc.select_pages(s, 10, sink_pages=2, recent_pages=3)
+    assert {0, 1, 37, 38, 39} <= set(got.tolist())
+    rest = sorted(set(got.tolist()) - {0, 1, 37, 38, 39})
+    free = np.argsort(-s[2:37], kind="stable")[:5] + 2
+    assert rest == sorted(free.tolist())
+    with pytest.raises(ValueError):
+        orc.select_pages(s, 4, sink_pages=2, recent_pages=3)
+
+
+def test_planted_heavy_pages_are_selected_on_config1():
+    from paper_2605_18071_amd import workloads as W
+    w = W.CONFIGS[1]
+    q0 = W.initial_queries(w)
+    store = W.make_kv_store(w, q0, pin=False)
+    q = next(W.query_stream(w, q0, 1))
+    u = W.query_direction(w, q0)
+    code = H.dtype_code(w.torch_dtype)
+    scale = 1.0 / math.sqrt(w.head_dim)
+    for h in range(w.n_kv_heads):
+        keys = H.f64(store[0, 0, h, :, 0]).reshape(-1, w.head_dim)
+        summ = orc.page_summaries(keys, w.page, w.ctx, code)
+        qg = H.f64(q[0, 0, h * w.group:(h + 1) * w.group])
+        sc = orc.page_scores(orc.pooled_query(qg), summ, scale)
+        sel = set(orc.select_pages(sc, w.topk_pages).tolist())
+        # the planted pages are the ones whose mean key has a large component along u
+        proj = summ @ H.f64(u[0, 0, h])
+        heavy = set(np.nonzero(proj > 1.5)[0].tolist())
+        assert len(heavy) == w.heavy_count
+        assert heavy <= sel
+
+
+# --------------------------------------------------------------------------- #
+# LRU window
+# --------------------------------------------------------------------------- #
+def _ints(cell):
+    return [] if cell == "-" else [int(x) for x in cell.split()]
+
+
+def test_lru_golden_trace():
+    win = orc.LruWindow(3)
+    for step, sel, hits, misses, evicted, resident in H.read_golden("lru_trace_5pages.txt"):
+        h, m, e = win.resolve(_ints(sel), int(step))
+        assert (h, m, e) == (_ints(hits), _ints(misses), _ints(evicted)), step
+        want = {int(a.split(":")[0]): int(a.split(":")[1]) for a in resident.split()}
+        assert win.stamp == want, step
+
+
+def _batch_lru(resident, sel, step, cap):
+    """A different route to the same answer: the victims of a step are the
+    e = max(0, |resident| + |misses| - cap) smallest (stamp, page) among resident
+    pages outside the selection."""
+    selset = set(sel)
+    hits = sorted(p for p in sel if p in resident)
+    misses = sorted(p for p in sel if p not in resident)
+    e = max(0, len(resident) + len(misses) - cap)
+    cands = sorted((s, p) for p, s in resident.items() if p not in selset)
+    evicted = sorted(p for _, p in cands[:e])
+    for p in evicted:
+        del resident[p]
+    for p in sel:
+        resident[p] = step
+    return hits, misses, evicted
+
+
+@pytest.mark.parametrize("n_pages,k,cap", [(40, 6, 6), (40, 6, 11), (64, 8, 24), (30, 5, 30)])
+def test_lru_against_batch_formulation_and_invariants(n_pages, k, cap):
+    win = orc.LruWindow(cap)
+    shadow = {}
+    prev_sel, seen = None, set()
+    for t in range(60):
+        centre = (t // 3) % n_pages
+        weights = np.exp(-0.15 * np.abs(np.arange(n_pages) - centre)) + 0.02
+        sel = sorted(RNG.choice(n_pages, size=k, replace=False, p=weights / weights.sum()).tolist())
+        before = len(win.stamp)
+        h, m, e = win.resolve(sel, t)
+        assert (h, m, e) == _batch_lru(shadow, sel, t, cap)
+        assert win.stamp == shadow
+        assert len(h) + len(m) == k and set(h) | set(m) == set(sel)
+        assert len(win.stamp) <= cap
+        assert len(e) == max(0, before + len(m) - cap)
+        assert not (set(e) & set(sel))
+        assert all(win.stamp[p] == t for p in sel)
+        if cap == k and prev_sel is not None:                     # the "x1" window: misses = S_t \ S_{t-1}
+            assert m == sorted(set(sel) - set(prev_sel))
+        if cap == n_pages:                                        # everything fits: a page misses at most once
+            assert not (set(m) & seen) and not e
+        seen |= set(sel)
+        prev_sel = sel
+
+
+def test_lru_inclusion_property_over_capacity():
+    n_pages, k = 50, 5
+    trace = []
+    for t in range(80):
+        centre = (t // 2) % n_pages
+        w = np.exp(-0.2 * np.abs(np.arange(n_pages) - centre)) + 0.01
+        trace.append(sorted(RNG.choice(n_pages, size=k, replace=False, p=w / w.sum()).tolist()))
+    caps = [5, 8, 13, 21, 34, 50]
+    wins = [orc.LruWindow(c) for c in caps]
+    total = [0] * len(caps)
+    for t, sel in enumerate(trace):
+        for i, win in enumerate(wins):
+            total[i] += len(win.resolve(sel, t)[1])
+        for a, b in zip(wins, wins[1:]):
+            assert set(a.stamp) <= set(b.stamp)
+    assert all(x >= y for x, y in zip(total, total[1:]))
+    assert total[-1] == len(set(itertools.chain.from_iterable(trace)))
+
+
+def test_lru_rejects_k_above_capacity_and_warm():
+    win = orc.LruWindow(2)
+    with pytest.raises(ValueError):
+        win.resolve([0, 1, 2], 0)
+    win.warm([3, 4])
+    assert win.resolve([3, 5], 0) == ([3], [5], [4])
+
+
+# --------------------------------------------------------------------------- #
+# attention
+# --------------------------------------------------------------------------- #
+def test_attention_closed_form_fixture():
+    for case, q, keys, values, out, lse in H.read_golden("attention_closed_form.txt"):
+        qv = np.array([[H.parse_num(x) for x in q.split()]])
+        kv = np.array([[H.parse_num(x) for x in r.split()] for r in keys.split(";")])
+        vv = np.array([[H.parse_num(x) for x in r.split()] for r in values.split(";")])
+        o, l = orc.attend(qv, kv, vv, 1.0)
+        assert np.allclose(o[0], [H.parse_num(x) for x in out.split()], rtol=0, atol=1e-14), case
+        assert abs(l[0] - H.parse_num(lse)) < 1e-14, case
+
+
+def test_attention_equals_dense_softmax_when_all_pages_selected():
+    G, D, P, T = 4, 32, 8, 8 * 9 + 5
+    q = RNG.standard_normal((G, D))
+    k = RNG.standard_normal((80, D))
+    v = RNG.standard_normal((80, D))
+    scale = 1.0 / math.sqrt(D)
+    n_pages = -(-T // P)
+    toks = orc.selected_tokens(np.arange(n_pages), P, T)
+    assert toks.tolist() == list(range(T))                        # ragged last page masked
+    o, l = orc.attend(q, k[toks], v[toks], scale)
+    logits = scale * (q @ k[:T].T)                                # [G, T]
+    w = scipy.special.softmax(logits, axis=1)
+    assert np.allclose(o, w @ v[:T], rtol=1e-12, atol=1e-13)
+    assert np.allclose(l, scipy.special.logsumexp(logits, axis=1), rtol=0, atol=1e-12)
+
+
+def test_attention_invariants():
+    G, D, n = 1, 16, 40
+    q = RNG.standard_normal((G, D))
+    k = RNG.standard_normal((n, D))
+    v = RNG.standard_normal((n, D))
+    scale = 0.25
+    o, l = orc.attend(q, k, v, scale)
+    # shift invariance: K_i += c/(scale |q|^2) q adds c to every logit
+    c = 3.5
+    k2 = k + (c / (scale * float(q[0] @ q[0]))) * q[0]
+    o2, l2 = orc.attend(q, k2, v, scale)
+    assert np.allclose(o2, o, rtol=0, atol=1e-12) and abs(l2[0] - l[0] - c) < 1e-12
+    # constant values come back unchanged (weights sum to one)
+    oc, _ = orc.attend(q, k, np.tile(np.arange(D, dtype=float), (n, 1)), scale)
+    assert np.allclose(oc[0], np.arange(D), rtol=0, atol=1e-13)
+    # permutation of the tokens
+    perm = RNG.permutation(n)
+    op, lp = orc.attend(q, k[perm], v[perm], scale)
+    assert np.allclose(op, o, rtol=0, atol=1e-13) and abs(lp[0] - l[0]) < 1e-13
+    # one dominating key takes all the weight
+    k3 = k.copy(); k3[7] = 400.0 * q[0] / float(q[0] @ q[0]) / scale
+    od, _ = orc.attend(q, k3, v, scale)
+    assert np.allclose(od[0], v[7], rtol=0, atol=1e-9)
+    # heads are independent: a second head must not change the first
+    q2 = np.vstack([q, RNG.standard_normal((1, D))])
+    o22, _ = orc.attend(q2, k, v, scale)
+    assert np.array_equal(o22[0], o[0])
+
+
+# --------------------------------------------------------------------------- #
+# whole step
+# --------------------------------------------------------------------------- #
+def test_step_output_does_not_depend_on_cache_state():
+    G, D, P, NP = 2, 16, 4, 12
+    T = P * NP - 1
+    keys = orc.round_f64(RNG.standard_normal((P * NP, D)), orc.BF16)
+    vals = orc.round_f64(RNG.standard_normal((P * NP, D)), orc.BF16)
+    q = orc.round_f64(RNG.standard_normal((G, D)), orc.BF16)
+    summ = orc.page_summaries(keys, P, T, orc.BF16)
+    cold, warm = orc.LruWindow(6), orc.LruWindow(6)
+    kw = dict(k=4, page_size=P, seq_len=T, scale=0.25)
+    first = orc.decode_unit_step(q, summ, keys, vals, warm, 0, **kw)
+    a = orc.decode_unit_step(q, summ, keys, vals, cold, 1, **kw)
+    b = orc.decode_unit_step(q, summ, keys, vals, warm, 1, **kw)
+    assert a["misses"] == first["misses"] and b["misses"] == [] and b["hits"] == a["misses"]
+    assert np.array_equal(a["out"], b["out"]) and np.array_equal(a["sel"], b["sel"])
+    # the selected set is the brute-force top-k of the printed scores
+    order = np.lexsort((np.arange(NP), -a["scores"]))
+    assert a["sel"].tolist() == sorted(order[:4].tolist())
+    # and the attention is dense attention restricted to those pages' valid tokens
+    toks = [t for p in a["sel"] for t in range(p * P, min((p + 1) * P, T))]
+    w = scipy.special.softmax(0.25 * (q @ keys[toks].T), axis=1)
+    assert np.allclose(a["out"], w @ vals[toks], rtol=1e-12, atol=1e-13)
