@@ -1,0 +1,200 @@
+/*
+ * kvd.h — C ABI of libkvd: the per-layer decode hot path of KVDrive-style
+ * offloaded sparse attention on AMD MI355X (gfx950).
+ *
+ * One decode step of one layer is the three-stage workflow the paper states in
+ * "KV Cache Offloading" (Background) and "System Overview":
+ *   (1) select the critical KV pages through an index held in GPU memory,
+ *   (2) fetch the selected pages that are not resident from host memory,
+ *   (3) run sparse attention over resident + fetched pages.
+ * The index is the mean key of each page (System Overview); the in-GPU cache is
+ * the window of recently critical pages of "Attention-Based Cache Management",
+ * here with LRU replacement; stage (2) moves only out-of-cache pages
+ * ("Performance Analysis via Roofline Model").
+ *
+ * Notation: L layers, B sequences, Hq query heads, Hkv KV heads, G = Hq/Hkv,
+ * D = head_dim = 128, P tokens per page, NP pages per sequence, k pages selected
+ * per step, C cache pages per unit.  A *unit* is one (layer, sequence, KV head);
+ * u = b*Hkv + h indexes the units of a layer, U = B*Hkv.  KV elements are 2 bytes
+ * (fp16 or bf16); page_bytes = 2*P*D*2 (the K page followed by the V page).
+ *
+ * Conventions
+ *   - every function returns KVD_OK (0) or a negative kvd_status; nothing throws;
+ *   - "dev" pointers are device (HBM) pointers, "host" pointers are ordinary host
+ *     memory, "pinned" is page-locked host memory that the GPU can address;
+ *   - data buffers (summaries, host store, slot pool, q, out, selections) belong
+ *     to the caller and are only borrowed; the library owns its kvd_ctx (cache
+ *     directory, scratch, miss lists, one side stream, events) until kvd_destroy;
+ *   - hot-path calls enqueue work on the caller's hipStream_t (passed as void*,
+ *     NULL = the null stream) and return without waiting; outputs are valid once
+ *     that stream has been synchronised.  No decision is taken on the host
+ *     between stages, so a call sequence can be captured in a HIP graph;
+ *   - calls on one kvd_ctx must not overlap in time on different streams.
+ */
+#ifndef KVD_H
+#define KVD_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct kvd_ctx kvd_ctx;
+
+typedef enum {
+  KVD_OK = 0,
+  KVD_ERR_ARG = -1,      /* NULL / misaligned / not device-addressable pointer, bad index */
+  KVD_ERR_SHAPE = -2,    /* inconsistent or unsupported sizes */
+  KVD_ERR_CAPACITY = -3, /* k > C for some unit, forced pages > k, warm list > C */
+  KVD_ERR_DTYPE = -4,
+  KVD_ERR_HIP = -5,      /* a HIP runtime call failed; see kvd_last_hip_error */
+  KVD_ERR_STATE = -6     /* buffers not bound yet, or an imported directory breaks its invariants */
+} kvd_status;
+
+typedef enum { KVD_F16 = 0, KVD_BF16 = 1 } kvd_dtype;
+typedef enum { KVD_EVICT_LRU = 0 } kvd_policy;
+
+typedef struct {
+  int32_t n_layers;        /* L */
+  int32_t batch;           /* B */
+  int32_t n_q_heads;       /* Hq, a multiple of n_kv_heads, G = Hq/Hkv <= 8 */
+  int32_t n_kv_heads;      /* Hkv */
+  int32_t head_dim;        /* D, must be 128 */
+  int32_t page_size;       /* P, 1..256 */
+  int32_t max_pages;       /* NP: pages allocated per sequence in every buffer */
+  int32_t topk_pages;      /* k = token budget / P */
+  int32_t sink_pages;      /* first pages of a sequence, always selected, counted inside k */
+  int32_t recent_pages;    /* last valid pages of a sequence, always selected, counted inside k
+                              (Experiment, Baselines: sink and local tokens stay on the GPU) */
+  int32_t kv_dtype;        /* kvd_dtype: element type of q, summaries, host store and slot pool */
+  int32_t policy;          /* kvd_policy */
+  float   softmax_scale;   /* multiplies q.k in scoring and attention; 0 means 1/sqrt(D) */
+  int32_t capacity_max;    /* Cmax: slots allocated per unit in the slot pool */
+  const int32_t* capacity; /* host, [L*U] pages per unit (per-layer, per-head window sizes, the
+                              run-time side of "2D Window Scaling"); NULL = capacity_max everywhere.
+                              Copied by kvd_create. */
+  int32_t physical_layers; /* layers present in the host store; layer l reads store layer
+                              l % physical_layers.  0 means n_layers. */
+  int32_t micro_batches;   /* kvd_step splits the B sequences into this many groups and lets the
+                              fetch of group i overlap the selection of group i+1
+                              ("SFC Disaggregation").  0 or 1 = no split. */
+  int32_t attn_splits;     /* split-K factor of the attention kernel; 0 = chosen by the library */
+} kvd_config;
+
+typedef struct {
+  uint64_t steps;          /* layer-steps executed by kvd_step / kvd_cache_resolve */
+  uint64_t hits;           /* selected pages found resident */
+  uint64_t misses;         /* selected pages fetched from the host store */
+  uint64_t evictions;      /* pages dropped from the window */
+  uint64_t gathered_bytes; /* misses * page_bytes */
+  /* filled only while profiling is on (kvd_set_profiling): accumulated milliseconds */
+  double ms_score_select, ms_resolve, ms_gather, ms_attend, ms_total;
+  uint64_t profiled_steps;
+} kvd_stats;
+
+/* ---- life cycle ------------------------------------------------------------------------- */
+
+/* Validates cfg, allocates the directory (all units empty) and scratch on the current HIP
+ * device.  *out receives the context.  KVD_ERR_SHAPE / KVD_ERR_CAPACITY / KVD_ERR_DTYPE on a
+ * bad configuration (nothing is allocated then), KVD_ERR_HIP if an allocation fails. */
+int kvd_create(const kvd_config* cfg, kvd_ctx** out);
+int kvd_destroy(kvd_ctx* ctx);
+
+const char* kvd_strerror(int status);
+int kvd_last_hip_error(const kvd_ctx* ctx);   /* hipError_t of the last failed runtime call */
+int kvd_abi_version(void);
+
+/* ---- buffers (borrowed) ------------------------------------------------------------------ */
+
+/* Index: mean key of each page, dev, [L][B][Hkv][NP][D] kv_dtype, 16-byte aligned. */
+int kvd_bind_summaries(kvd_ctx* ctx, void* dev_summaries);
+/* Paged KV store in pinned host memory, [Lp][B][Hkv][NP][2][P][D] kv_dtype (K page, then V
+ * page).  KVD_ERR_ARG if the GPU cannot address the pointer. */
+int kvd_bind_host_store(kvd_ctx* ctx, const void* pinned_store);
+/* GPU cache tier, dev, [L][B][Hkv][Cmax][2][P][D] kv_dtype, 16-byte aligned.  Contents are
+ * managed by the library (which page sits in which slot is the directory's business). */
+int kvd_bind_slot_pool(kvd_ctx* ctx, void* dev_pool);
+/* Valid tokens per sequence, host [B], each in 1..NP*P.  Default: NP*P.  Synchronous. */
+int kvd_set_seq_lens(kvd_ctx* ctx, const int32_t* host_seq_len);
+
+/* ---- set-up helpers (not on the hot path) ------------------------------------------------- */
+
+/* Builds the index of one layer from the host store: summary[p][d] = mean over the valid tokens
+ * of page p of K[token][d], accumulated in fp64 in token order and rounded once to kv_dtype
+ * (System Overview: the mean key of each page is its representative).  Enqueued on stream. */
+int kvd_build_summaries(kvd_ctx* ctx, int32_t layer, void* stream);
+
+/* Empties the directory of every layer (cold cache).  Synchronous. */
+int kvd_cache_reset(kvd_ctx* ctx);
+/* Replaces one layer's cache content: unit u becomes resident with pages
+ * host_pages[off_u .. off_u+host_counts[u]) (off_u = sum of earlier counts), stamp -1, and the
+ * page data is copied from the host store.  KVD_ERR_CAPACITY if a count exceeds the unit's
+ * capacity, KVD_ERR_ARG on a page out of range or repeated.  Synchronous. */
+int kvd_cache_warm(kvd_ctx* ctx, int32_t layer, const int32_t* host_pages, const int32_t* host_counts);
+/* Directory of one layer as flat arrays, host, [U][Cmax] each: page in the slot (-1 = free) and
+ * the step at which it was last selected.  Synchronous. */
+int kvd_cache_export(kvd_ctx* ctx, int32_t layer, int32_t* host_slot_page, int32_t* host_slot_stamp);
+/* Installs a directory (same arrays as export) and refills the named slots from the host store.
+ * KVD_ERR_STATE if a page repeats inside a unit, is out of range, or a slot >= the unit's
+ * capacity is occupied; the cache is left unchanged then.  Synchronous. */
+int kvd_cache_import(kvd_ctx* ctx, int32_t layer, const int32_t* host_slot_page, const int32_t* host_slot_stamp);
+
+/* ---- hot path: each stage alone (all pointers dev) ----------------------------------------- */
+
+/* Stage 1, selection (Background: the query is multiplied with the index and the Top-K kept).
+ *   q          [B][Hq][D] kv_dtype.  The G query heads of a KV head are mean-pooled in fp32.
+ *   sel_pages  [B][Hkv][k] int32 out: the k pages with the largest
+ *              score = scale * pooled_q . summary, ties to the lower page; sink/recent pages
+ *              always included; ascending page order; padded with -1 when a sequence has fewer
+ *              than k valid pages.
+ *   scores     [B][Hkv][NP] fp32 out, or NULL. */
+int kvd_score_select(kvd_ctx* ctx, int32_t layer, const void* q, int32_t* sel_pages, float* scores, void* stream);
+
+/* Stage 2, cache lookup and fetch (Cache Management; Roofline section: only out-of-cache pages move).
+ *   sel_pages  [B][Hkv][k] from stage 1.
+ *   sel_slots  [B][Hkv][k] int32 out: slot of each selected page (-1 where sel_pages is -1).
+ *   hit_mask   [B][Hkv][k] int32 out or NULL: 1 = was resident, 0 = fetched.
+ *   evicted    [B][Hkv][k] int32 out or NULL: pages dropped in this step, -1 padded, unordered.
+ *   counts     [B][Hkv][3] int32 out or NULL: hits, misses, evictions.
+ * Hits are re-stamped with `step`; misses take free slots first, then the slots of the resident
+ * pages, not selected in this step, with the smallest (stamp, page).  `step` must not decrease
+ * for a layer.  With do_gather != 0 the missed pages are copied from the host store into their
+ * slots on the library's side stream, and `stream` waits for that copy before anything enqueued
+ * after this call.  With do_gather == 0 only the directory changes (slot contents are stale). */
+int kvd_cache_resolve(kvd_ctx* ctx, int32_t layer, int32_t step, const int32_t* sel_pages, int32_t* sel_slots,
+                      int32_t* hit_mask, int32_t* evicted, int32_t* counts, int32_t do_gather, void* stream);
+
+/* Stage 3, sparse attention (System Overview: attention over resident and fetched entries).
+ *   out [B][Hq][D] fp32 = softmax(scale * q K_sel^T) V_sel over the valid tokens of the selected
+ *   pages, read from the slot pool through sel_slots; fp32 accumulation, online softmax,
+ *   split over the selected pages and merged by log-sum-exp.
+ *   lse [B][Hq] fp32 out or NULL: log sum exp of the scaled logits. */
+int kvd_sparse_decode_attn(kvd_ctx* ctx, int32_t layer, const void* q, const int32_t* sel_pages,
+                           const int32_t* sel_slots, float* out, float* lse, void* stream);
+
+/* ---- hot path: the whole layer-step -------------------------------------------------------- */
+
+/* Stages 1-3 for one layer with the fetch on the side stream; with micro_batches > 1 the fetch
+ * of one group of sequences overlaps the selection of the next (SFC Disaggregation).
+ *   q [B][Hq][D] kv_dtype, out [B][Hq][D] fp32, lse [B][Hq] fp32 or NULL. */
+int kvd_step(kvd_ctx* ctx, int32_t layer, int32_t step, const void* q, float* out, float* lse, void* stream);
+
+/* Copies what the last kvd_step left behind into caller buffers (all dev, any may be NULL),
+ * asynchronously on `stream` (which must be ordered after that kvd_step): sel_pages, sel_slots,
+ * hit_mask, evicted [B][Hkv][k] int32, counts [B][Hkv][3] int32, scores [B][Hkv][NP] fp32. */
+int kvd_step_trace(kvd_ctx* ctx, int32_t* sel_pages, int32_t* sel_slots, int32_t* hit_mask, int32_t* evicted,
+                   int32_t* counts, float* scores, void* stream);
+
+/* ---- counters ------------------------------------------------------------------------------ */
+
+/* Profiling on: kvd_step brackets every stage with HIP events on the streams it uses, waits for
+ * the step and adds the stage times to the stats (the step is then synchronous). */
+int kvd_set_profiling(kvd_ctx* ctx, int32_t on);
+int kvd_get_stats(kvd_ctx* ctx, kvd_stats* host_out);   /* synchronises the device */
+int kvd_reset_stats(kvd_ctx* ctx);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* KVD_H */

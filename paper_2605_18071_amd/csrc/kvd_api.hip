@@ -1,0 +1,436 @@
+// C ABI of libkvd: argument checks, the context, and the stream choreography of one layer-step.
+// No stage is computed on the host; every hot-path entry point only enqueues kernels.
+#include <math.h>
+#include <stdlib.h>
+#include <string.h>
+
+#include <vector>
+
+#include "kvd_internal.h"
+
+#define KVD_ABI_VERSION 1
+
+#define HIP_TRY(ctx, expr)                  \
+  do {                                      \
+    hipError_t _e = (expr);                 \
+    if (_e != hipSuccess) {                 \
+      if (ctx) (ctx)->last_hip = (int)_e;   \
+      return KVD_ERR_HIP;                   \
+    }                                       \
+  } while (0)
+
+static bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+static int validate_config(const kvd_config* c) {
+  if (c == nullptr) return KVD_ERR_ARG;
+  if (c->kv_dtype != KVD_F16 && c->kv_dtype != KVD_BF16) return KVD_ERR_DTYPE;
+  if (c->policy != KVD_EVICT_LRU) return KVD_ERR_ARG;
+  if (c->n_layers < 1 || c->batch < 1 || c->n_q_heads < 1 || c->n_kv_heads < 1) return KVD_ERR_SHAPE;
+  if (c->head_dim != 128) return KVD_ERR_SHAPE;
+  if (c->n_q_heads % c->n_kv_heads != 0) return KVD_ERR_SHAPE;
+  const int G = c->n_q_heads / c->n_kv_heads;
+  if (G > KVD_MAX_GROUP) return KVD_ERR_SHAPE;
+  if (c->page_size < 1 || c->page_size > KVD_MAX_PAGE) return KVD_ERR_SHAPE;
+  if (c->max_pages < 1 || c->max_pages > (1 << 24)) return KVD_ERR_SHAPE;
+  if (c->topk_pages < 1 || c->topk_pages > KVD_MAX_TOPK) return KVD_ERR_SHAPE;
+  if (c->capacity_max < 1 || c->capacity_max > KVD_MAX_CAPACITY) return KVD_ERR_SHAPE;
+  if ((long long)c->batch * c->n_kv_heads > 65535) return KVD_ERR_SHAPE;
+  if (c->sink_pages < 0 || c->recent_pages < 0) return KVD_ERR_SHAPE;
+  if (c->physical_layers < 0 || c->physical_layers > c->n_layers) return KVD_ERR_SHAPE;
+  if (c->micro_batches < 0 || c->micro_batches > KVD_MAX_MICRO) return KVD_ERR_SHAPE;
+  if (c->attn_splits < 0 || c->attn_splits > KVD_MAX_SPLITS) return KVD_ERR_SHAPE;
+  if (!(c->softmax_scale >= 0.f) || isinf(c->softmax_scale)) return KVD_ERR_ARG;
+  if ((long long)c->sink_pages + c->recent_pages > c->topk_pages) return KVD_ERR_CAPACITY;
+  if (c->topk_pages > c->capacity_max) return KVD_ERR_CAPACITY;
+  if (c->capacity != nullptr) {
+    const long long n = (long long)c->n_layers * c->batch * c->n_kv_heads;
+    for (long long i = 0; i < n; ++i) {
+      if (c->capacity[i] > c->capacity_max) return KVD_ERR_SHAPE;
+      if (c->capacity[i] < c->topk_pages) return KVD_ERR_CAPACITY;
+    }
+  }
+  return KVD_OK;
+}
+
+static void free_ctx(kvd_ctx* c) {
+  if (c == nullptr) return;
+  void* dev[] = {c->d_capacity, c->d_seq_len, c->d_page_to_slot, c->d_slot_page, c->d_slot_stamp, c->d_resident,
+                 c->d_scores, c->d_sel_pages, c->d_sel_slots, c->d_hit_mask, c->d_evicted, c->d_counts,
+                 c->d_miss_list, c->d_miss_count, c->d_part_acc, c->d_part_ml, c->d_stats};
+  for (void* p : dev)
+    if (p) (void)hipFree(p);
+  for (int i = 0; i < KVD_MAX_MICRO; ++i) {
+    if (c->ev_sel[i]) (void)hipEventDestroy(c->ev_sel[i]);
+    if (c->ev_fetch[i]) (void)hipEventDestroy(c->ev_fetch[i]);
+  }
+  for (int i = 0; i < 8; ++i)
+    if (c->ev_prof[i]) (void)hipEventDestroy(c->ev_prof[i]);
+  if (c->side) (void)hipStreamDestroy(c->side);
+  free(c->h_capacity);
+  free(c->h_seq_len);
+  free(c);
+}
+
+template <class T>
+static hipError_t dev_alloc(T** p, size_t count) {
+  return hipMalloc(reinterpret_cast<void**>(p), (count ? count : 1) * sizeof(T));
+}
+
+static int reset_directory(kvd_ctx* c, int layer_or_all) {
+  const int l0 = layer_or_all < 0 ? 0 : layer_or_all;
+  const int nl = layer_or_all < 0 ? c->L : 1;
+  const size_t lu = (size_t)l0 * c->U, nu = (size_t)nl * c->U;
+  HIP_TRY(c, kvd_launch_fill_i32(c->d_page_to_slot + lu * c->NP, -1, nu * c->NP, nullptr));
+  HIP_TRY(c, kvd_launch_fill_i32(c->d_slot_page + lu * c->Cmax, -1, nu * c->Cmax, nullptr));
+  HIP_TRY(c, kvd_launch_fill_i32(c->d_slot_stamp + lu * c->Cmax, -1, nu * c->Cmax, nullptr));
+  HIP_TRY(c, kvd_launch_fill_i32(c->d_resident + lu, 0, nu, nullptr));
+  HIP_TRY(c, hipDeviceSynchronize());
+  return KVD_OK;
+}
+
+extern "C" {
+
+int kvd_abi_version(void) { return KVD_ABI_VERSION; }
+
+const char* kvd_strerror(int status) {
+  switch (status) {
+    case KVD_OK: return "ok";
+    case KVD_ERR_ARG: return "bad argument (NULL, misaligned, out of range, or not addressable by the GPU)";
+    case KVD_ERR_SHAPE: return "inconsistent or unsupported sizes";
+    case KVD_ERR_CAPACITY: return "capacity too small (k > C, forced pages > k, or warm list > C)";
+    case KVD_ERR_DTYPE: return "unsupported KV dtype";
+    case KVD_ERR_HIP: return "HIP runtime call failed (see kvd_last_hip_error)";
+    case KVD_ERR_STATE: return "buffers not bound, or directory invariants violated";
+    default: return "unknown status";
+  }
+}
+
+int kvd_last_hip_error(const kvd_ctx* ctx) { return ctx ? ctx->last_hip : 0; }
+
+int kvd_create(const kvd_config* cfg, kvd_ctx** out) {
+  if (out == nullptr) return KVD_ERR_ARG;
+  *out = nullptr;
+  const int v = validate_config(cfg);
+  if (v != KVD_OK) return v;
+  kvd_ctx* c = static_cast<kvd_ctx*>(calloc(1, sizeof(kvd_ctx)));
+  if (c == nullptr) return KVD_ERR_HIP;
+  c->cfg = *cfg;
+  c->cfg.capacity = nullptr;
+  c->L = cfg->n_layers; c->B = cfg->batch; c->Hq = cfg->n_q_heads; c->Hkv = cfg->n_kv_heads;
+  c->G = c->Hq / c->Hkv; c->D = cfg->head_dim; c->P = cfg->page_size; c->NP = cfg->max_pages;
+  c->k = cfg->topk_pages; c->Cmax = cfg->capacity_max;
+  c->Lp = cfg->physical_layers ? cfg->physical_layers : c->L;
+  c->U = c->B * c->Hkv;
+  c->MB = cfg->micro_batches < 1 ? 1 : cfg->micro_batches;
+  if (c->MB > c->B) c->MB = c->B;
+  c->bf16 = cfg->kv_dtype == KVD_BF16;
+  c->scale = cfg->softmax_scale > 0.f ? cfg->softmax_scale : 1.0f / sqrtf((float)c->D);
+  c->page_bytes = (size_t)2 * c->P * c->D * 2;
+  int S = cfg->attn_splits;
+  if (S == 0) {
+    S = (2048 + c->U - 1) / c->U;
+    const int cap = (c->k + 3) / 4;
+    if (S > cap) S = cap;
+    if (S > KVD_MAX_SPLITS) S = KVD_MAX_SPLITS;
+    if (S < 1) S = 1;
+  }
+  if (S > c->k) S = c->k;
+  c->S = S;
+
+  const size_t LU = (size_t)c->L * c->U;
+  c->h_capacity = static_cast<int32_t*>(malloc(LU * sizeof(int32_t)));
+  c->h_seq_len = static_cast<int32_t*>(malloc((size_t)c->B * sizeof(int32_t)));
+  if (!c->h_capacity || !c->h_seq_len) { free_ctx(c); return KVD_ERR_HIP; }
+  for (size_t i = 0; i < LU; ++i) c->h_capacity[i] = cfg->capacity ? cfg->capacity[i] : c->Cmax;
+  for (int b = 0; b < c->B; ++b) c->h_seq_len[b] = c->NP * c->P;
+
+  hipError_t e = hipSuccess;
+  auto ok = [&](hipError_t r) { if (e == hipSuccess && r != hipSuccess) e = r; return e == hipSuccess; };
+  const size_t Uk = (size_t)c->U * c->k;
+  ok(dev_alloc(&c->d_capacity, LU)) && ok(dev_alloc(&c->d_seq_len, (size_t)c->B)) &&
+      ok(dev_alloc(&c->d_page_to_slot, LU * c->NP)) && ok(dev_alloc(&c->d_slot_page, LU * c->Cmax)) &&
+      ok(dev_alloc(&c->d_slot_stamp, LU * c->Cmax)) && ok(dev_alloc(&c->d_resident, LU)) &&
+      ok(dev_alloc(&c->d_scores, (size_t)c->U * c->NP)) && ok(dev_alloc(&c->d_sel_pages, Uk)) &&
+      ok(dev_alloc(&c->d_sel_slots, Uk)) && ok(dev_alloc(&c->d_hit_mask, Uk)) && ok(dev_alloc(&c->d_evicted, Uk)) &&
+      ok(dev_alloc(&c->d_counts, (size_t)c->U * 3)) && ok(dev_alloc(&c->d_miss_list, Uk * 2)) &&
+      ok(dev_alloc(&c->d_miss_count, (size_t)c->U)) &&
+      ok(dev_alloc(&c->d_part_acc, (size_t)c->U * c->S * c->G * c->D)) &&
+      ok(dev_alloc(&c->d_part_ml, (size_t)c->U * c->S * c->G * 2)) && ok(dev_alloc(&c->d_stats, 4)) &&
+      ok(hipStreamCreateWithFlags(&c->side, hipStreamNonBlocking));
+  for (int i = 0; i < c->MB && e == hipSuccess; ++i) {
+    ok(hipEventCreateWithFlags(&c->ev_sel[i], hipEventDisableTiming));
+    ok(hipEventCreateWithFlags(&c->ev_fetch[i], hipEventDisableTiming));
+  }
+  for (int i = 0; i < 8 && e == hipSuccess; ++i) ok(hipEventCreate(&c->ev_prof[i]));
+  if (e == hipSuccess) ok(hipMemcpy(c->d_capacity, c->h_capacity, LU * sizeof(int32_t), hipMemcpyHostToDevice));
+  if (e == hipSuccess) ok(hipMemcpy(c->d_seq_len, c->h_seq_len, (size_t)c->B * sizeof(int32_t), hipMemcpyHostToDevice));
+  if (e == hipSuccess) ok(hipMemset(c->d_stats, 0, 4 * sizeof(unsigned long long)));
+  if (e == hipSuccess) ok(hipMemset(c->d_miss_count, 0, (size_t)c->U * sizeof(int32_t)));
+  if (e != hipSuccess) { free_ctx(c); return KVD_ERR_HIP; }
+  const int r = reset_directory(c, -1);
+  if (r != KVD_OK) { free_ctx(c); return r; }
+  *out = c;
+  return KVD_OK;
+}
+
+int kvd_destroy(kvd_ctx* ctx) {
+  if (ctx == nullptr) return KVD_ERR_ARG;
+  (void)hipDeviceSynchronize();
+  free_ctx(ctx);
+  return KVD_OK;
+}
+
+int kvd_bind_summaries(kvd_ctx* ctx, void* dev_summaries) {
+  if (!ctx || !dev_summaries || !aligned16(dev_summaries)) return KVD_ERR_ARG;
+  ctx->summaries = dev_summaries;
+  return KVD_OK;
+}
+
+int kvd_bind_host_store(kvd_ctx* ctx, const void* pinned_store) {
+  if (!ctx || !pinned_store || !aligned16(pinned_store)) return KVD_ERR_ARG;
+  void* dptr = nullptr;
+  hipError_t e = hipHostGetDevicePointer(&dptr, const_cast<void*>(pinned_store), 0);
+  if (e != hipSuccess || dptr == nullptr) {
+    (void)hipGetLastError();
+    ctx->last_hip = (int)e;
+    return KVD_ERR_ARG;
+  }
+  ctx->store_dev = static_cast<const char*>(dptr);
+  return KVD_OK;
+}
+
+int kvd_bind_slot_pool(kvd_ctx* ctx, void* dev_pool) {
+  if (!ctx || !dev_pool || !aligned16(dev_pool)) return KVD_ERR_ARG;
+  ctx->pool = static_cast<char*>(dev_pool);
+  return KVD_OK;
+}
+
+int kvd_set_seq_lens(kvd_ctx* ctx, const int32_t* host_seq_len) {
+  if (!ctx || !host_seq_len) return KVD_ERR_ARG;
+  for (int b = 0; b < ctx->B; ++b)
+    if (host_seq_len[b] < 1 || (long long)host_seq_len[b] > (long long)ctx->NP * ctx->P) return KVD_ERR_SHAPE;
+  memcpy(ctx->h_seq_len, host_seq_len, (size_t)ctx->B * sizeof(int32_t));
+  HIP_TRY(ctx, hipDeviceSynchronize());
+  HIP_TRY(ctx, hipMemcpy(ctx->d_seq_len, ctx->h_seq_len, (size_t)ctx->B * sizeof(int32_t), hipMemcpyHostToDevice));
+  return KVD_OK;
+}
+
+int kvd_build_summaries(kvd_ctx* ctx, int32_t layer, void* stream) {
+  if (!ctx || layer < 0 || layer >= ctx->L) return KVD_ERR_ARG;
+  if (!ctx->summaries || !ctx->store_dev) return KVD_ERR_STATE;
+  HIP_TRY(ctx, kvd_launch_build_summaries(ctx, layer, static_cast<hipStream_t>(stream)));
+  return KVD_OK;
+}
+
+int kvd_cache_reset(kvd_ctx* ctx) {
+  if (!ctx) return KVD_ERR_ARG;
+  HIP_TRY(ctx, hipDeviceSynchronize());
+  return reset_directory(ctx, -1);
+}
+
+// Checks a [U][Cmax] slot_page image and derives page_to_slot / resident from it.
+static int install_directory(kvd_ctx* c, int layer, const std::vector<int32_t>& slot_page,
+                             const std::vector<int32_t>& slot_stamp) {
+  const size_t U = c->U, NP = c->NP, Cmax = c->Cmax;
+  std::vector<int32_t> p2s(U * NP, -1), resident(U, 0);
+  for (size_t u = 0; u < U; ++u) {
+    const int cap = c->h_capacity[(size_t)layer * U + u];
+    for (size_t s = 0; s < Cmax; ++s) {
+      const int32_t p = slot_page[u * Cmax + s];
+      if (p < 0) continue;
+      if ((int)s >= cap || (size_t)p >= NP || p2s[u * NP + p] >= 0) return KVD_ERR_STATE;
+      p2s[u * NP + p] = (int32_t)s;
+      ++resident[u];
+    }
+  }
+  const size_t lu = (size_t)layer * U;
+  HIP_TRY(c, hipDeviceSynchronize());
+  HIP_TRY(c, hipMemcpy(c->d_page_to_slot + lu * NP, p2s.data(), U * NP * sizeof(int32_t), hipMemcpyHostToDevice));
+  HIP_TRY(c, hipMemcpy(c->d_slot_page + lu * Cmax, slot_page.data(), U * Cmax * sizeof(int32_t), hipMemcpyHostToDevice));
+  HIP_TRY(c, hipMemcpy(c->d_slot_stamp + lu * Cmax, slot_stamp.data(), U * Cmax * sizeof(int32_t), hipMemcpyHostToDevice));
+  HIP_TRY(c, hipMemcpy(c->d_resident + lu, resident.data(), U * sizeof(int32_t), hipMemcpyHostToDevice));
+  HIP_TRY(c, kvd_launch_refill(c, layer, nullptr));
+  HIP_TRY(c, hipDeviceSynchronize());
+  return KVD_OK;
+}
+
+int kvd_cache_warm(kvd_ctx* ctx, int32_t layer, const int32_t* host_pages, const int32_t* host_counts) {
+  if (!ctx || !host_pages || !host_counts || layer < 0 || layer >= ctx->L) return KVD_ERR_ARG;
+  if (!ctx->pool || !ctx->store_dev) return KVD_ERR_STATE;
+  const size_t U = ctx->U, Cmax = ctx->Cmax;
+  std::vector<int32_t> slot_page(U * Cmax, -1), slot_stamp(U * Cmax, -1);
+  size_t off = 0;
+  for (size_t u = 0; u < U; ++u) {
+    const int n = host_counts[u];
+    if (n < 0) return KVD_ERR_ARG;
+    if (n > ctx->h_capacity[(size_t)layer * U + u]) return KVD_ERR_CAPACITY;
+    for (int i = 0; i < n; ++i) {
+      const int32_t p = host_pages[off + i];
+      if (p < 0 || p >= ctx->NP) return KVD_ERR_ARG;
+      slot_page[u * Cmax + i] = p;
+    }
+    off += (size_t)n;
+  }
+  const int r = install_directory(ctx, layer, slot_page, slot_stamp);
+  return r == KVD_ERR_STATE ? KVD_ERR_ARG : r;       // a repeated page in a warm list is a bad argument
+}
+
+int kvd_cache_export(kvd_ctx* ctx, int32_t layer, int32_t* host_slot_page, int32_t* host_slot_stamp) {
+  if (!ctx || !host_slot_page || !host_slot_stamp || layer < 0 || layer >= ctx->L) return KVD_ERR_ARG;
+  const size_t n = (size_t)ctx->U * ctx->Cmax, lu = (size_t)layer * ctx->U;
+  HIP_TRY(ctx, hipDeviceSynchronize());
+  HIP_TRY(ctx, hipMemcpy(host_slot_page, ctx->d_slot_page + lu * ctx->Cmax, n * sizeof(int32_t), hipMemcpyDeviceToHost));
+  HIP_TRY(ctx, hipMemcpy(host_slot_stamp, ctx->d_slot_stamp + lu * ctx->Cmax, n * sizeof(int32_t), hipMemcpyDeviceToHost));
+  return KVD_OK;
+}
+
+int kvd_cache_import(kvd_ctx* ctx, int32_t layer, const int32_t* host_slot_page, const int32_t* host_slot_stamp) {
+  if (!ctx || !host_slot_page || !host_slot_stamp || layer < 0 || layer >= ctx->L) return KVD_ERR_ARG;
+  if (!ctx->pool || !ctx->store_dev) return KVD_ERR_STATE;
+  const size_t n = (size_t)ctx->U * ctx->Cmax;
+  std::vector<int32_t> slot_page(host_slot_page, host_slot_page + n), slot_stamp(host_slot_stamp, host_slot_stamp + n);
+  return install_directory(ctx, layer, slot_page, slot_stamp);
+}
+
+int kvd_score_select(kvd_ctx* ctx, int32_t layer, const void* q, int32_t* sel_pages, float* scores, void* stream) {
+  if (!ctx || !q || !sel_pages || layer < 0 || layer >= ctx->L || !aligned16(q)) return KVD_ERR_ARG;
+  if (!ctx->summaries) return KVD_ERR_STATE;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  float* sc = scores ? scores : ctx->d_scores;
+  HIP_TRY(ctx, kvd_launch_score(ctx, layer, q, sc, 0, ctx->U, s));
+  HIP_TRY(ctx, kvd_launch_select(ctx, sc, sel_pages, 0, ctx->U, s));
+  return KVD_OK;
+}
+
+int kvd_cache_resolve(kvd_ctx* ctx, int32_t layer, int32_t step, const int32_t* sel_pages, int32_t* sel_slots,
+                      int32_t* hit_mask, int32_t* evicted, int32_t* counts, int32_t do_gather, void* stream) {
+  if (!ctx || !sel_pages || !sel_slots || layer < 0 || layer >= ctx->L) return KVD_ERR_ARG;
+  if (do_gather && (!ctx->pool || !ctx->store_dev)) return KVD_ERR_STATE;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  HIP_TRY(ctx, kvd_launch_resolve(ctx, layer, step, sel_pages, sel_slots, hit_mask ? hit_mask : ctx->d_hit_mask,
+                                  evicted ? evicted : ctx->d_evicted, counts ? counts : ctx->d_counts, 0, ctx->U, s));
+  if (do_gather) {
+    HIP_TRY(ctx, hipEventRecord(ctx->ev_sel[0], s));
+    HIP_TRY(ctx, hipStreamWaitEvent(ctx->side, ctx->ev_sel[0], 0));
+    HIP_TRY(ctx, kvd_launch_gather(ctx, layer, 0, ctx->U, ctx->side));
+    HIP_TRY(ctx, hipEventRecord(ctx->ev_fetch[0], ctx->side));
+    HIP_TRY(ctx, hipStreamWaitEvent(s, ctx->ev_fetch[0], 0));
+  }
+  ++ctx->n_steps;
+  return KVD_OK;
+}
+
+int kvd_sparse_decode_attn(kvd_ctx* ctx, int32_t layer, const void* q, const int32_t* sel_pages,
+                           const int32_t* sel_slots, float* out, float* lse, void* stream) {
+  if (!ctx || !q || !sel_pages || !sel_slots || !out || layer < 0 || layer >= ctx->L || !aligned16(q))
+    return KVD_ERR_ARG;
+  if (!ctx->pool) return KVD_ERR_STATE;
+  HIP_TRY(ctx, kvd_launch_attend(ctx, layer, q, sel_pages, sel_slots, out, lse, static_cast<hipStream_t>(stream)));
+  return KVD_OK;
+}
+
+static int step_profiled(kvd_ctx* c, int layer, int step, const void* q, float* out, float* lse, hipStream_t s) {
+  hipEvent_t* ev = c->ev_prof;
+  HIP_TRY(c, hipEventRecord(ev[0], s));
+  HIP_TRY(c, kvd_launch_score(c, layer, q, c->d_scores, 0, c->U, s));
+  HIP_TRY(c, kvd_launch_select(c, c->d_scores, c->d_sel_pages, 0, c->U, s));
+  HIP_TRY(c, hipEventRecord(ev[1], s));
+  HIP_TRY(c, kvd_launch_resolve(c, layer, step, c->d_sel_pages, c->d_sel_slots, c->d_hit_mask, c->d_evicted,
+                                c->d_counts, 0, c->U, s));
+  HIP_TRY(c, hipEventRecord(ev[2], s));
+  HIP_TRY(c, hipStreamWaitEvent(c->side, ev[2], 0));
+  HIP_TRY(c, hipEventRecord(ev[3], c->side));
+  HIP_TRY(c, kvd_launch_gather(c, layer, 0, c->U, c->side));
+  HIP_TRY(c, hipEventRecord(ev[4], c->side));
+  HIP_TRY(c, hipStreamWaitEvent(s, ev[4], 0));
+  HIP_TRY(c, hipEventRecord(ev[5], s));
+  HIP_TRY(c, kvd_launch_attend(c, layer, q, c->d_sel_pages, c->d_sel_slots, out, lse, s));
+  HIP_TRY(c, hipEventRecord(ev[6], s));
+  HIP_TRY(c, hipEventSynchronize(ev[6]));
+  float ms = 0.f;
+  HIP_TRY(c, hipEventElapsedTime(&ms, ev[0], ev[1])); c->ms_score_select += ms;
+  HIP_TRY(c, hipEventElapsedTime(&ms, ev[1], ev[2])); c->ms_resolve += ms;
+  HIP_TRY(c, hipEventElapsedTime(&ms, ev[3], ev[4])); c->ms_gather += ms;
+  HIP_TRY(c, hipEventElapsedTime(&ms, ev[5], ev[6])); c->ms_attend += ms;
+  HIP_TRY(c, hipEventElapsedTime(&ms, ev[0], ev[6])); c->ms_total += ms;
+  ++c->profiled_steps;
+  return KVD_OK;
+}
+
+int kvd_step(kvd_ctx* ctx, int32_t layer, int32_t step, const void* q, float* out, float* lse, void* stream) {
+  if (!ctx || !q || !out || layer < 0 || layer >= ctx->L || !aligned16(q)) return KVD_ERR_ARG;
+  if (!ctx->summaries || !ctx->pool || !ctx->store_dev) return KVD_ERR_STATE;
+  kvd_ctx* c = ctx;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  ++c->n_steps;
+  if (c->profiling) return step_profiled(c, layer, step, q, out, lse, s);
+  for (int i = 0; i < c->MB; ++i) {
+    const int u0 = (int)(((long long)i * c->B) / c->MB) * c->Hkv;
+    const int u1 = (int)(((long long)(i + 1) * c->B) / c->MB) * c->Hkv;
+    HIP_TRY(c, kvd_launch_score(c, layer, q, c->d_scores, u0, u1, s));
+    HIP_TRY(c, kvd_launch_select(c, c->d_scores, c->d_sel_pages, u0, u1, s));
+    HIP_TRY(c, kvd_launch_resolve(c, layer, step, c->d_sel_pages, c->d_sel_slots, c->d_hit_mask, c->d_evicted,
+                                  c->d_counts, u0, u1, s));
+    HIP_TRY(c, hipEventRecord(c->ev_sel[i], s));
+    HIP_TRY(c, hipStreamWaitEvent(c->side, c->ev_sel[i], 0));
+    HIP_TRY(c, kvd_launch_gather(c, layer, u0, u1, c->side));
+    HIP_TRY(c, hipEventRecord(c->ev_fetch[i], c->side));
+  }
+  for (int i = 0; i < c->MB; ++i) HIP_TRY(c, hipStreamWaitEvent(s, c->ev_fetch[i], 0));
+  HIP_TRY(c, kvd_launch_attend(c, layer, q, c->d_sel_pages, c->d_sel_slots, out, lse, s));
+  return KVD_OK;
+}
+
+int kvd_step_trace(kvd_ctx* ctx, int32_t* sel_pages, int32_t* sel_slots, int32_t* hit_mask, int32_t* evicted,
+                   int32_t* counts, float* scores, void* stream) {
+  if (!ctx) return KVD_ERR_ARG;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  const size_t uk = (size_t)ctx->U * ctx->k * sizeof(int32_t);
+  if (sel_pages) HIP_TRY(ctx, hipMemcpyAsync(sel_pages, ctx->d_sel_pages, uk, hipMemcpyDeviceToDevice, s));
+  if (sel_slots) HIP_TRY(ctx, hipMemcpyAsync(sel_slots, ctx->d_sel_slots, uk, hipMemcpyDeviceToDevice, s));
+  if (hit_mask) HIP_TRY(ctx, hipMemcpyAsync(hit_mask, ctx->d_hit_mask, uk, hipMemcpyDeviceToDevice, s));
+  if (evicted) HIP_TRY(ctx, hipMemcpyAsync(evicted, ctx->d_evicted, uk, hipMemcpyDeviceToDevice, s));
+  if (counts)
+    HIP_TRY(ctx, hipMemcpyAsync(counts, ctx->d_counts, (size_t)ctx->U * 3 * sizeof(int32_t), hipMemcpyDeviceToDevice, s));
+  if (scores)
+    HIP_TRY(ctx, hipMemcpyAsync(scores, ctx->d_scores, (size_t)ctx->U * ctx->NP * sizeof(float), hipMemcpyDeviceToDevice, s));
+  return KVD_OK;
+}
+
+int kvd_set_profiling(kvd_ctx* ctx, int32_t on) {
+  if (!ctx) return KVD_ERR_ARG;
+  ctx->profiling = on ? 1 : 0;
+  return KVD_OK;
+}
+
+int kvd_get_stats(kvd_ctx* ctx, kvd_stats* host_out) {
+  if (!ctx || !host_out) return KVD_ERR_ARG;
+  unsigned long long raw[4] = {0, 0, 0, 0};
+  HIP_TRY(ctx, hipDeviceSynchronize());
+  HIP_TRY(ctx, hipMemcpy(raw, ctx->d_stats, sizeof(raw), hipMemcpyDeviceToHost));
+  memset(host_out, 0, sizeof(*host_out));
+  host_out->steps = ctx->n_steps;
+  host_out->hits = raw[0];
+  host_out->misses = raw[1];
+  host_out->evictions = raw[2];
+  host_out->gathered_bytes = raw[1] * (uint64_t)ctx->page_bytes;
+  host_out->ms_score_select = ctx->ms_score_select;
+  host_out->ms_resolve = ctx->ms_resolve;
+  host_out->ms_gather = ctx->ms_gather;
+  host_out->ms_attend = ctx->ms_attend;
+  host_out->ms_total = ctx->ms_total;
+  host_out->profiled_steps = ctx->profiled_steps;
+  return KVD_OK;
+}
+
+int kvd_reset_stats(kvd_ctx* ctx) {
+  if (!ctx) return KVD_ERR_ARG;
+  HIP_TRY(ctx, hipDeviceSynchronize());
+  HIP_TRY(ctx, hipMemset(ctx->d_stats, 0, 4 * sizeof(unsigned long long)));
+  ctx->n_steps = 0;
+  ctx->ms_score_select = ctx->ms_resolve = ctx->ms_gather = ctx->ms_attend = ctx->ms_total = 0.0;
+  ctx->profiled_steps = 0;
+  return KVD_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,315 @@
+// Stage 2 of the decode step: the in-GPU window of recently critical pages (Attention-Based
+// Cache Management; Motivation, "critical KV window") with LRU replacement, kept entirely on
+// the device, and the fetch of the pages that are not resident from the pinned host store
+// (Roofline section: only out-of-cache critical entries are moved).  Also the set-up kernel that
+// builds the index (System Overview: mean key of each page).
+#include "kvd_device.h"
+#include "kvd_internal.h"
+
+namespace kvd {
+
+constexpr int kResolveThreads = 256;
+constexpr int kSelPerThread = KVD_MAX_TOPK / kResolveThreads;      // 8
+constexpr int kBitmapWords = KVD_MAX_CAPACITY / 32;
+
+struct ResolveArgs {
+  const int32_t* capacity;   // [U] of the layer
+  int32_t* resident;         // [U]
+  int32_t* page_to_slot;     // [U][NP]
+  int32_t* slot_page;        // [U][Cmax]
+  int32_t* slot_stamp;       // [U][Cmax]
+  const int32_t* sel_pages;  // [U][k]
+  int32_t* sel_slots;        // [U][k]
+  int32_t* hit_mask;         // [U][k]
+  int32_t* evicted;          // [U][k]
+  int32_t* counts;           // [U][3]
+  int32_t* miss_list;        // [U][k][2]
+  int32_t* miss_count;       // [U]
+  unsigned long long* stats; // hits, misses, evictions
+  int NP, Cmax, k, step, u0;
+};
+
+// One block per unit.
+//  1. look every selected page up in page_to_slot; hits are re-stamped and flagged in an LDS bitmap;
+//  2. e = max(0, resident + misses - capacity) pages must leave: the e smallest (stamp, page)
+//     among resident slots that were not hit (exact k-th smallest on the 64-bit key);
+//  3. free slots and victim slots, in ascending slot order, are handed to the misses in ascending
+//     page order; the directory is updated and the (page, slot) miss list written for the fetch.
+__global__ __launch_bounds__(kResolveThreads) void resolve_kernel(ResolveArgs a) {
+  __shared__ SelectSmem sm;
+  __shared__ u32 hit_bitmap[kBitmapWords];
+  __shared__ int32_t assign[KVD_MAX_TOPK];
+  __shared__ int n_hits, n_evicted_out;
+  constexpr int NT = kResolveThreads;
+  const int tid = threadIdx.x;
+  const int u = blockIdx.x + a.u0;
+  const int C = a.capacity[u];
+  const int R = a.resident[u];
+  int32_t* p2s = a.page_to_slot + (size_t)u * a.NP;
+  int32_t* spage = a.slot_page + (size_t)u * a.Cmax;
+  int32_t* sstamp = a.slot_stamp + (size_t)u * a.Cmax;
+  const int32_t* sel = a.sel_pages + (size_t)u * a.k;
+  int32_t* sslots = a.sel_slots + (size_t)u * a.k;
+  int32_t* hmask = a.hit_mask + (size_t)u * a.k;
+  int32_t* evout = a.evicted + (size_t)u * a.k;
+
+  for (int i = tid; i < (C + 31) / 32; i += NT) hit_bitmap[i] = 0;
+  for (int i = tid; i < a.k; i += NT) assign[i] = -1;
+  if (tid == 0) { n_hits = 0; n_evicted_out = 0; }
+  __syncthreads();
+
+  // 1. lookup
+  const int per = (a.k + NT - 1) / NT;               // consecutive selected entries per thread (<= 8)
+  const int i0 = tid * per;
+  int32_t my_page[kSelPerThread];
+  int my_misses = 0, my_hits = 0;
+#pragma unroll
+  for (int j = 0; j < kSelPerThread; ++j) {
+    my_page[j] = -2;                                 // -2: nothing here, -1..: handled below
+    const int i = i0 + j;
+    if (j < per && i < a.k) {
+      const int p = sel[i];
+      if (p < 0 || p >= a.NP) {                        // padding (or a page the caller made up)
+        sslots[i] = -1;
+        hmask[i] = 0;
+      } else {
+        const int s = p2s[p];
+        if (s >= 0 && s < C) {
+          sstamp[s] = a.step;
+          atomicOr(&hit_bitmap[s >> 5], 1u << (s & 31));
+          sslots[i] = s;
+          hmask[i] = 1;
+          ++my_hits;
+        } else {
+          my_page[j] = p;
+          ++my_misses;
+        }
+      }
+    }
+  }
+  if (my_hits) atomicAdd(&n_hits, my_hits);
+  int m;
+  int miss_rank = block_exclusive_scan<NT>(my_misses, sm.scan, m);
+  const int e = (R + m - C) > 0 ? (R + m - C) : 0;
+
+  // 2. victims
+  auto victim_key = [&](int s, u64& key) -> bool {
+    const int p = spage[s];
+    if (p < 0 || ((hit_bitmap[s >> 5] >> (s & 31)) & 1u)) return false;
+    key = ((u64)((u32)sstamp[s] ^ 0x80000000u) << 32) | (u32)p;
+    return true;
+  };
+  u64 thr = 0;
+  if (e > 0) thr = block_kth_smallest<NT>(victim_key, C, e, sm);
+
+  // 3. hand out slots
+  const int sper = (C + NT - 1) / NT;
+  const int s0 = tid * sper;
+  const int s1 = (s0 + sper) < C ? (s0 + sper) : C;
+  int avail = 0;
+  for (int s = s0; s < s1; ++s) {
+    u64 key;
+    const bool is_free = spage[s] < 0;
+    const bool is_victim = e > 0 && victim_key(s, key) && key <= thr;
+    avail += (is_free || is_victim) ? 1 : 0;
+  }
+  int total_avail;
+  int rank = block_exclusive_scan<NT>(avail, sm.scan, total_avail);
+  for (int s = s0; s < s1; ++s) {
+    u64 key;
+    const int p = spage[s];
+    const bool is_free = p < 0;
+    const bool is_victim = e > 0 && victim_key(s, key) && key <= thr;
+    if (is_free || is_victim) {
+      if (rank < m) {
+        assign[rank] = s;
+        if (is_victim) {
+          p2s[p] = -1;
+          const int at = atomicAdd(&n_evicted_out, 1);
+          if (at < a.k) evout[at] = p;
+        }
+      }
+      ++rank;
+    }
+  }
+  __syncthreads();
+
+  // 4. install the misses
+#pragma unroll
+  for (int j = 0; j < kSelPerThread; ++j) {
+    const int p = my_page[j];
+    if (p >= 0) {
+      const int i = i0 + j;
+      const int s = assign[miss_rank];
+      sslots[i] = s;
+      hmask[i] = 0;
+      if (s >= 0) {                                    // always true while the directory is consistent
+        p2s[p] = s;
+        spage[s] = p;
+        sstamp[s] = a.step;
+      }
+      a.miss_list[((size_t)u * a.k + miss_rank) * 2] = p;
+      a.miss_list[((size_t)u * a.k + miss_rank) * 2 + 1] = s;
+      ++miss_rank;
+    }
+  }
+  for (int j = e + tid; j < a.k; j += NT) evout[j] = -1;
+  if (tid == 0) {
+    a.resident[u] = R + m - e;
+    a.miss_count[u] = m;
+    a.counts[u * 3 + 0] = n_hits;
+    a.counts[u * 3 + 1] = m;
+    a.counts[u * 3 + 2] = e;
+    atomicAdd(&a.stats[0], (unsigned long long)n_hits);
+    atomicAdd(&a.stats[1], (unsigned long long)m);
+    atomicAdd(&a.stats[2], (unsigned long long)e);
+  }
+}
+
+constexpr int kGatherThreads = 256;
+constexpr int kGatherBlocksPerUnit = 8;
+
+// Fetch: block (x, u) copies misses x, x+8, ... of unit u from the pinned host store (read across
+// the host link, 16 bytes per lane) into their slots.
+__global__ __launch_bounds__(kGatherThreads) void gather_kernel(const char* __restrict__ store,   // [U][NP] pages of the layer
+                                                               char* __restrict__ pool,          // [U][Cmax] slots of the layer
+                                                               const int32_t* __restrict__ miss_list,
+                                                               const int32_t* __restrict__ miss_count, int k, int NP,
+                                                               int Cmax, unsigned page_bytes, int u0) {
+  const int u = blockIdx.y + u0;
+  const int m = miss_count[u];
+  for (int j = blockIdx.x; j < m; j += gridDim.x) {
+    const int page = miss_list[((size_t)u * k + j) * 2];
+    const int slot = miss_list[((size_t)u * k + j) * 2 + 1];
+    if (slot < 0) continue;
+    const uint4* src = reinterpret_cast<const uint4*>(store + ((size_t)u * NP + page) * page_bytes);
+    uint4* dst = reinterpret_cast<uint4*>(pool + ((size_t)u * Cmax + slot) * page_bytes);
+    for (unsigned o = threadIdx.x; o < page_bytes / 16; o += kGatherThreads) dst[o] = src[o];
+  }
+}
+
+// Index build: one block per page, one thread per dimension; the sum runs over the page's valid
+// tokens in token order in fp64 and is rounded once to the KV dtype.
+template <bool BF16>
+__global__ __launch_bounds__(kHeadDim) void summaries_kernel(const uint16_t* __restrict__ store,   // [U][NP][2][P][D]
+                                                            uint16_t* __restrict__ summ,          // [U][NP][D]
+                                                            const int32_t* __restrict__ seq_len, int NP, int P,
+                                                            int Hkv) {
+  const int page = blockIdx.x, u = blockIdx.y, d = threadIdx.x;
+  const int b = u / Hkv;
+  int n = seq_len[b] - page * P;
+  n = n < P ? n : P;
+  uint16_t* out = summ + ((size_t)u * NP + page) * kHeadDim + d;
+  if (n <= 0) { *out = 0; return; }
+  const uint16_t* kp = store + ((size_t)u * NP + page) * (size_t)(2 * P * kHeadDim) + d;
+  double acc = 0.0;
+  for (int t0 = 0; t0 < n; t0 += 16) {
+    uint16_t raw[16];
+#pragma unroll
+    for (int j = 0; j < 16; ++j) {
+      const int t = (t0 + j) < n ? (t0 + j) : (n - 1);
+      raw[j] = kp[(size_t)t * kHeadDim];
+    }
+#pragma unroll
+    for (int j = 0; j < 16; ++j) {
+      if (t0 + j < n) {
+        float f;
+        if (BF16) {
+          f = as_f32((u32)raw[j] << 16);
+        } else {
+          f = (float)__builtin_bit_cast(_Float16, raw[j]);
+        }
+        acc += (double)f;
+      }
+    }
+  }
+  *out = f64_to_kv<BF16>(acc / (double)n);
+}
+
+// Set-up: (re)load every occupied slot of a layer from the host store, as named by slot_page.
+__global__ __launch_bounds__(kGatherThreads) void refill_kernel(const char* __restrict__ store, char* __restrict__ pool,
+                                                               const int32_t* __restrict__ slot_page, int NP, int Cmax,
+                                                               unsigned page_bytes) {
+  const int u = blockIdx.y;
+  for (int s = blockIdx.x; s < Cmax; s += gridDim.x) {
+    const int page = slot_page[(size_t)u * Cmax + s];
+    if (page < 0) continue;
+    const uint4* src = reinterpret_cast<const uint4*>(store + ((size_t)u * NP + page) * page_bytes);
+    uint4* dst = reinterpret_cast<uint4*>(pool + ((size_t)u * Cmax + s) * page_bytes);
+    for (unsigned o = threadIdx.x; o < page_bytes / 16; o += kGatherThreads) dst[o] = src[o];
+  }
+}
+
+__global__ void fill_i32_kernel(int32_t* p, int32_t v, size_t n) {
+  for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x) p[i] = v;
+}
+
+}  // namespace kvd
+
+hipError_t kvd_launch_resolve(kvd_ctx* c, int layer, int step, const int32_t* sel_pages, int32_t* sel_slots,
+                              int32_t* hit_mask, int32_t* evicted, int32_t* counts, int u0, int u1, hipStream_t s) {
+  using namespace kvd;
+  if (u1 <= u0) return hipSuccess;
+  ResolveArgs a;
+  const size_t lu = (size_t)layer * c->U;
+  a.capacity = c->d_capacity + lu;
+  a.resident = c->d_resident + lu;
+  a.page_to_slot = c->d_page_to_slot + lu * c->NP;
+  a.slot_page = c->d_slot_page + lu * c->Cmax;
+  a.slot_stamp = c->d_slot_stamp + lu * c->Cmax;
+  a.sel_pages = sel_pages;
+  a.sel_slots = sel_slots;
+  a.hit_mask = hit_mask;
+  a.evicted = evicted;
+  a.counts = counts;
+  a.miss_list = c->d_miss_list;
+  a.miss_count = c->d_miss_count;
+  a.stats = c->d_stats;
+  a.NP = c->NP; a.Cmax = c->Cmax; a.k = c->k; a.step = step; a.u0 = u0;
+  hipLaunchKernelGGL(resolve_kernel, dim3(u1 - u0), dim3(kResolveThreads), 0, s, a);
+  return hipGetLastError();
+}
+
+hipError_t kvd_launch_gather(kvd_ctx* c, int layer, int u0, int u1, hipStream_t s) {
+  using namespace kvd;
+  if (u1 <= u0) return hipSuccess;
+  const int lp = layer % c->Lp;
+  const char* store = c->store_dev + (size_t)lp * c->U * c->NP * c->page_bytes;
+  char* pool = c->pool + (size_t)layer * c->U * c->Cmax * c->page_bytes;
+  hipLaunchKernelGGL(gather_kernel, dim3(kGatherBlocksPerUnit, u1 - u0), dim3(kGatherThreads), 0, s, store, pool,
+                     c->d_miss_list, c->d_miss_count, c->k, c->NP, c->Cmax, (unsigned)c->page_bytes, u0);
+  return hipGetLastError();
+}
+
+hipError_t kvd_launch_refill(kvd_ctx* c, int layer, hipStream_t s) {
+  using namespace kvd;
+  const int lp = layer % c->Lp;
+  const char* store = c->store_dev + (size_t)lp * c->U * c->NP * c->page_bytes;
+  char* pool = c->pool + (size_t)layer * c->U * c->Cmax * c->page_bytes;
+  const int32_t* slot_page = c->d_slot_page + (size_t)layer * c->U * c->Cmax;
+  const int bx = c->Cmax < 64 ? c->Cmax : 64;
+  hipLaunchKernelGGL(refill_kernel, dim3(bx, c->U), dim3(kGatherThreads), 0, s, store, pool, slot_page, c->NP, c->Cmax,
+                     (unsigned)c->page_bytes);
+  return hipGetLastError();
+}
+
+hipError_t kvd_launch_build_summaries(kvd_ctx* c, int layer, hipStream_t s) {
+  using namespace kvd;
+  const int lp = layer % c->Lp;
+  const uint16_t* store = reinterpret_cast<const uint16_t*>(c->store_dev + (size_t)lp * c->U * c->NP * c->page_bytes);
+  uint16_t* summ = reinterpret_cast<uint16_t*>(c->summaries) + (size_t)layer * c->U * c->NP * kHeadDim;
+  dim3 grid(c->NP, c->U);
+  if (c->bf16)
+    hipLaunchKernelGGL(summaries_kernel<true>, grid, dim3(kHeadDim), 0, s, store, summ, c->d_seq_len, c->NP, c->P, c->Hkv);
+  else
+    hipLaunchKernelGGL(summaries_kernel<false>, grid, dim3(kHeadDim), 0, s, store, summ, c->d_seq_len, c->NP, c->P, c->Hkv);
+  return hipGetLastError();
+}
+
+hipError_t kvd_launch_fill_i32(int32_t* p, int32_t v, size_t n, hipStream_t s) {
+  if (n == 0) return hipSuccess;
+  size_t blocks = (n + 255) / 256;
+  if (blocks > 4096) blocks = 4096;
+  hipLaunchKernelGGL(kvd::fill_i32_kernel, dim3((unsigned)blocks), dim3(256), 0, s, p, v, n);
+  return hipGetLastError();
+}

@@ -1,0 +1,70 @@
+// Host-side internals of libkvd: the context and the kernel launchers.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "../../include/kvd.h"
+
+constexpr int KVD_MAX_GROUP = 8;        // G = Hq / Hkv
+constexpr int KVD_MAX_TOPK = 2048;      // k
+constexpr int KVD_MAX_CAPACITY = 65536; // Cmax
+constexpr int KVD_MAX_PAGE = 256;       // P
+constexpr int KVD_MAX_MICRO = 16;       // micro-batches per step
+constexpr int KVD_MAX_SPLITS = 64;      // attention split-K factor
+
+struct kvd_ctx {
+  kvd_config cfg;
+  int L, B, Hq, Hkv, G, D, P, NP, k, Cmax, Lp, U, MB, S;
+  int bf16;
+  float scale;
+  size_t page_bytes;
+
+  // borrowed
+  void* summaries;
+  const char* store_dev;    // device-visible address of the pinned host store
+  char* pool;
+
+  // owned, device
+  int32_t* d_capacity;      // [L][U]
+  int32_t* d_seq_len;       // [B]
+  int32_t* d_page_to_slot;  // [L][U][NP]   -1 = not resident
+  int32_t* d_slot_page;     // [L][U][Cmax] -1 = free
+  int32_t* d_slot_stamp;    // [L][U][Cmax]
+  int32_t* d_resident;      // [L][U]
+  float* d_scores;          // [U][NP]
+  int32_t* d_sel_pages;     // [U][k]
+  int32_t* d_sel_slots;     // [U][k]
+  int32_t* d_hit_mask;      // [U][k]
+  int32_t* d_evicted;       // [U][k]
+  int32_t* d_counts;        // [U][3]
+  int32_t* d_miss_list;     // [U][k][2]  (page, slot)
+  int32_t* d_miss_count;    // [U]
+  float* d_part_acc;        // [U][S][G][D]
+  float* d_part_ml;         // [U][S][G][2]  (max in log2 units, sum)
+  unsigned long long* d_stats;  // hits, misses, evictions
+
+  // owned, host
+  int32_t* h_capacity;      // [L][U]
+  int32_t* h_seq_len;       // [B]
+  hipStream_t side;
+  hipEvent_t ev_sel[KVD_MAX_MICRO];
+  hipEvent_t ev_fetch[KVD_MAX_MICRO];
+  hipEvent_t ev_prof[8];
+  int profiling;
+  int last_hip;
+  uint64_t n_steps;
+  double ms_score_select, ms_resolve, ms_gather, ms_attend, ms_total;
+  uint64_t profiled_steps;
+};
+
+// Kernel launchers.  u0/u1 bound the units [u0, u1) of the layer that the launch covers.
+hipError_t kvd_launch_score(kvd_ctx* c, int layer, const void* q, float* scores, int u0, int u1, hipStream_t s);
+hipError_t kvd_launch_select(kvd_ctx* c, const float* scores, int32_t* sel_pages, int u0, int u1, hipStream_t s);
+hipError_t kvd_launch_resolve(kvd_ctx* c, int layer, int step, const int32_t* sel_pages, int32_t* sel_slots,
+                              int32_t* hit_mask, int32_t* evicted, int32_t* counts, int u0, int u1, hipStream_t s);
+hipError_t kvd_launch_gather(kvd_ctx* c, int layer, int u0, int u1, hipStream_t s);
+hipError_t kvd_launch_attend(kvd_ctx* c, int layer, const void* q, const int32_t* sel_pages,
+                             const int32_t* sel_slots, float* out, float* lse, hipStream_t s);
+hipError_t kvd_launch_refill(kvd_ctx* c, int layer, hipStream_t s);
+hipError_t kvd_launch_build_summaries(kvd_ctx* c, int layer, hipStream_t s);
+hipError_t kvd_launch_fill_i32(int32_t* p, int32_t v, size_t n, hipStream_t s);

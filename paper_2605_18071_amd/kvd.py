@@ -1,0 +1,240 @@
+"""ctypes binding of libkvd (see include/kvd.h).  Argument marshalling only: every
+stage of the decode step runs in the HIP kernels of the library.  Tensors are
+passed as raw device / pinned-host pointers; torch is used for memory and streams.
+
+Loading fails loudly (ImportError) if the library has not been built:
+    python -m paper_2605_18071_amd.build
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Optional, Sequence
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libkvd.so")
+
+KVD_F16, KVD_BF16 = 0, 1
+KVD_EVICT_LRU = 0
+OK, ERR_ARG, ERR_SHAPE, ERR_CAPACITY, ERR_DTYPE, ERR_HIP, ERR_STATE = 0, -1, -2, -3, -4, -5, -6
+
+
+class KvdConfig(C.Structure):
+    _fields_ = [
+        ("n_layers", C.c_int32), ("batch", C.c_int32), ("n_q_heads", C.c_int32), ("n_kv_heads", C.c_int32),
+        ("head_dim", C.c_int32), ("page_size", C.c_int32), ("max_pages", C.c_int32), ("topk_pages", C.c_int32),
+        ("sink_pages", C.c_int32), ("recent_pages", C.c_int32), ("kv_dtype", C.c_int32), ("policy", C.c_int32),
+        ("softmax_scale", C.c_float), ("capacity_max", C.c_int32), ("capacity", C.POINTER(C.c_int32)),
+        ("physical_layers", C.c_int32), ("micro_batches", C.c_int32), ("attn_splits", C.c_int32),
+    ]
+
+
+class KvdStats(C.Structure):
+    _fields_ = [
+        ("steps", C.c_uint64), ("hits", C.c_uint64), ("misses", C.c_uint64), ("evictions", C.c_uint64),
+        ("gathered_bytes", C.c_uint64),
+        ("ms_score_select", C.c_double), ("ms_resolve", C.c_double), ("ms_gather", C.c_double),
+        ("ms_attend", C.c_double), ("ms_total", C.c_double), ("profiled_steps", C.c_uint64),
+    ]
+
+
+EXPORTS = [
+    "kvd_create", "kvd_destroy", "kvd_strerror", "kvd_last_hip_error", "kvd_abi_version",
+    "kvd_bind_summaries", "kvd_bind_host_store", "kvd_bind_slot_pool", "kvd_set_seq_lens",
+    "kvd_build_summaries", "kvd_cache_reset", "kvd_cache_warm", "kvd_cache_export", "kvd_cache_import",
+    "kvd_score_select", "kvd_cache_resolve", "kvd_sparse_decode_attn", "kvd_step", "kvd_step_trace",
+    "kvd_set_profiling", "kvd_get_stats", "kvd_reset_stats",
+]
+
+_lib = None
+
+
+def load() -> C.CDLL:
+    """Loads libkvd.so once and declares the prototypes."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise ImportError(f"{LIB_PATH} is missing: build it with `python -m paper_2605_18071_amd.build`")
+    lib = C.CDLL(LIB_PATH)
+    vp, i32, i32p, f32p = C.c_void_p, C.c_int32, C.POINTER(C.c_int32), C.POINTER(C.c_float)
+    protos = {
+        "kvd_create": [C.POINTER(KvdConfig), C.POINTER(vp)],
+        "kvd_destroy": [vp],
+        "kvd_last_hip_error": [vp],
+        "kvd_abi_version": [],
+        "kvd_bind_summaries": [vp, vp],
+        "kvd_bind_host_store": [vp, vp],
+        "kvd_bind_slot_pool": [vp, vp],
+        "kvd_set_seq_lens": [vp, i32p],
+        "kvd_build_summaries": [vp, i32, vp],
+        "kvd_cache_reset": [vp],
+        "kvd_cache_warm": [vp, i32, i32p, i32p],
+        "kvd_cache_export": [vp, i32, i32p, i32p],
+        "kvd_cache_import": [vp, i32, i32p, i32p],
+        "kvd_score_select": [vp, i32, vp, vp, vp, vp],
+        "kvd_cache_resolve": [vp, i32, i32, vp, vp, vp, vp, vp, i32, vp],
+        "kvd_sparse_decode_attn": [vp, i32, vp, vp, vp, vp, vp, vp],
+        "kvd_step": [vp, i32, i32, vp, vp, vp, vp],
+        "kvd_step_trace": [vp, vp, vp, vp, vp, vp, vp, vp],
+        "kvd_set_profiling": [vp, i32],
+        "kvd_get_stats": [vp, C.POINTER(KvdStats)],
+        "kvd_reset_stats": [vp],
+    }
+    for name, args in protos.items():
+        fn = getattr(lib, name)
+        fn.argtypes = args
+        fn.restype = C.c_int
+    lib.kvd_strerror.argtypes = [C.c_int]
+    lib.kvd_strerror.restype = C.c_char_p
+    _lib = lib
+    return lib
+
+
+class KvdError(RuntimeError):
+    def __init__(self, status: int, where: str, hip: int = 0):
+        self.status = status
+        msg = load().kvd_strerror(status).decode()
+        super().__init__(f"{where}: {msg} (status {status}" + (f", hip error {hip})" if hip else ")"))
+
+
+def _ptr(t: Optional[torch.Tensor]) -> Optional[int]:
+    return None if t is None else t.data_ptr()
+
+
+def _i32_array(values: Sequence[int]):
+    arr = (C.c_int32 * len(values))(*[int(v) for v in values])
+    return arr
+
+
+def _stream_handle(stream: Optional[torch.cuda.Stream]) -> Optional[int]:
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return stream.cuda_stream or None
+
+
+class Kvd:
+    """One kvd_ctx.  Methods mirror the C entry points one to one."""
+
+    def __init__(self, *, n_layers, batch, n_q_heads, n_kv_heads, page_size, max_pages, topk_pages, capacity_max,
+                 kv_dtype, head_dim=128, sink_pages=0, recent_pages=0, softmax_scale=0.0, capacity=None,
+                 physical_layers=0, micro_batches=0, attn_splits=0):
+        self.lib = load()
+        self._cap = None
+        cfg = KvdConfig()
+        cfg.n_layers, cfg.batch, cfg.n_q_heads, cfg.n_kv_heads = n_layers, batch, n_q_heads, n_kv_heads
+        cfg.head_dim, cfg.page_size, cfg.max_pages, cfg.topk_pages = head_dim, page_size, max_pages, topk_pages
+        cfg.sink_pages, cfg.recent_pages = sink_pages, recent_pages
+        cfg.kv_dtype = {torch.float16: KVD_F16, torch.bfloat16: KVD_BF16}.get(kv_dtype, kv_dtype)
+        cfg.policy = KVD_EVICT_LRU
+        cfg.softmax_scale = softmax_scale
+        cfg.capacity_max = capacity_max
+        if capacity is not None:
+            self._cap = _i32_array(list(capacity))
+            cfg.capacity = C.cast(self._cap, C.POINTER(C.c_int32))
+        cfg.physical_layers, cfg.micro_batches, cfg.attn_splits = physical_layers, micro_batches, attn_splits
+        self.cfg = cfg
+        self.ctx = C.c_void_p()
+        st = self.lib.kvd_create(C.byref(cfg), C.byref(self.ctx))
+        if st != OK:
+            self.ctx = C.c_void_p()
+            raise KvdError(st, "kvd_create")
+        self.units = batch * n_kv_heads
+        self._keep = []
+
+    def _check(self, st: int, where: str):
+        if st != OK:
+            raise KvdError(st, where, self.lib.kvd_last_hip_error(self.ctx))
+
+    def close(self):
+        if self.ctx:
+            self.lib.kvd_destroy(self.ctx)
+            self.ctx = C.c_void_p()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    # ---- buffers
+    def bind_summaries(self, t: torch.Tensor):
+        self._keep.append(t)
+        self._check(self.lib.kvd_bind_summaries(self.ctx, t.data_ptr()), "kvd_bind_summaries")
+
+    def bind_host_store(self, t: torch.Tensor):
+        self._keep.append(t)
+        self._check(self.lib.kvd_bind_host_store(self.ctx, t.data_ptr()), "kvd_bind_host_store")
+
+    def bind_slot_pool(self, t: torch.Tensor):
+        self._keep.append(t)
+        self._check(self.lib.kvd_bind_slot_pool(self.ctx, t.data_ptr()), "kvd_bind_slot_pool")
+
+    def set_seq_lens(self, seq_lens: Sequence[int]):
+        self._check(self.lib.kvd_set_seq_lens(self.ctx, _i32_array(list(seq_lens))), "kvd_set_seq_lens")
+
+    # ---- set-up helpers
+    def build_summaries(self, layer: int, stream=None):
+        self._check(self.lib.kvd_build_summaries(self.ctx, layer, _stream_handle(stream)), "kvd_build_summaries")
+
+    def cache_reset(self):
+        self._check(self.lib.kvd_cache_reset(self.ctx), "kvd_cache_reset")
+
+    def cache_warm(self, layer: int, pages: Sequence[int], counts: Sequence[int]):
+        self._check(self.lib.kvd_cache_warm(self.ctx, layer, _i32_array(list(pages)), _i32_array(list(counts))),
+                    "kvd_cache_warm")
+
+    def cache_export(self, layer: int):
+        n = self.units * self.cfg.capacity_max
+        page = torch.empty(n, dtype=torch.int32)
+        stamp = torch.empty(n, dtype=torch.int32)
+        self._check(self.lib.kvd_cache_export(self.ctx, layer, C.cast(page.data_ptr(), C.POINTER(C.c_int32)),
+                                              C.cast(stamp.data_ptr(), C.POINTER(C.c_int32))), "kvd_cache_export")
+        shape = (self.units, self.cfg.capacity_max)
+        return page.view(shape), stamp.view(shape)
+
+    def cache_import(self, layer: int, slot_page: torch.Tensor, slot_stamp: torch.Tensor):
+        sp = slot_page.to(torch.int32).contiguous()
+        ss = slot_stamp.to(torch.int32).contiguous()
+        self._check(self.lib.kvd_cache_import(self.ctx, layer, C.cast(sp.data_ptr(), C.POINTER(C.c_int32)),
+                                              C.cast(ss.data_ptr(), C.POINTER(C.c_int32))), "kvd_cache_import")
+
+    # ---- hot path
+    def score_select(self, layer: int, q: torch.Tensor, sel_pages: torch.Tensor, scores: Optional[torch.Tensor] = None,
+                     stream=None):
+        self._check(self.lib.kvd_score_select(self.ctx, layer, q.data_ptr(), sel_pages.data_ptr(), _ptr(scores),
+                                              _stream_handle(stream)), "kvd_score_select")
+
+    def cache_resolve(self, layer: int, step: int, sel_pages, sel_slots, hit_mask=None, evicted=None, counts=None,
+                      do_gather: bool = True, stream=None):
+        self._check(self.lib.kvd_cache_resolve(self.ctx, layer, step, sel_pages.data_ptr(), sel_slots.data_ptr(),
+                                               _ptr(hit_mask), _ptr(evicted), _ptr(counts), 1 if do_gather else 0,
+                                               _stream_handle(stream)), "kvd_cache_resolve")
+
+    def sparse_decode_attn(self, layer: int, q, sel_pages, sel_slots, out, lse=None, stream=None):
+        self._check(self.lib.kvd_sparse_decode_attn(self.ctx, layer, q.data_ptr(), sel_pages.data_ptr(),
+                                                    sel_slots.data_ptr(), out.data_ptr(), _ptr(lse),
+                                                    _stream_handle(stream)), "kvd_sparse_decode_attn")
+
+    def step(self, layer: int, step: int, q, out, lse=None, stream=None):
+        self._check(self.lib.kvd_step(self.ctx, layer, step, q.data_ptr(), out.data_ptr(), _ptr(lse),
+                                      _stream_handle(stream)), "kvd_step")
+
+    def step_trace(self, sel_pages=None, sel_slots=None, hit_mask=None, evicted=None, counts=None, scores=None,
+                   stream=None):
+        self._check(self.lib.kvd_step_trace(self.ctx, _ptr(sel_pages), _ptr(sel_slots), _ptr(hit_mask), _ptr(evicted),
+                                            _ptr(counts), _ptr(scores), _stream_handle(stream)), "kvd_step_trace")
+
+    # ---- counters
+    def set_profiling(self, on: bool):
+        self._check(self.lib.kvd_set_profiling(self.ctx, 1 if on else 0), "kvd_set_profiling")
+
+    def stats(self) -> KvdStats:
+        st = KvdStats()
+        self._check(self.lib.kvd_get_stats(self.ctx, C.byref(st)), "kvd_get_stats")
+        return st
+
+    def reset_stats(self):
+        self._check(self.lib.kvd_reset_stats(self.ctx), "kvd_reset_stats")

@@ -1,0 +1,248 @@
+"""GPU test rig: builds a workload on the device, a kvd context bound to it, and
+per-unit oracle mirrors, and compares the two after every step.
+
+The HIP path is driven only through the C-ABI binding; the oracle only through
+oracle/kvd_oracle.py; the inputs come from paper_2605_18071_amd/workloads.py.
+"""
+from __future__ import annotations
+
+import math
+from typing import Iterable, List, Optional, Sequence, Tuple
+
+import numpy as np
+import torch
+
+from oracle import kvd_oracle as orc
+from paper_2605_18071_amd import kvd as K
+from paper_2605_18071_amd import workloads as W
+from tests import helpers as H
+
+DEV = "cuda"
+
+
+class Rig:
+    def __init__(self, w: W.Workload, *, seq_lens: Optional[Sequence[int]] = None, capacity: Optional[Sequence[int]] = None,
+                 micro_batches: int = 0, attn_splits: int = 0, build_index: bool = True):
+        self.w = w
+        self.q0 = W.initial_queries(w, DEV)
+        self.store = W.make_kv_store(w, self.q0, DEV)                      # pinned host
+        L, B, Hkv, NP, P, D = w.n_layers, w.batch, w.n_kv_heads, w.n_pages, w.page, w.head_dim
+        self.summaries = torch.zeros((L, B, Hkv, NP, D), dtype=w.torch_dtype, device=DEV)
+        self.pool = torch.zeros((L, B, Hkv, w.capacity, 2, P, D), dtype=w.torch_dtype, device=DEV)
+        self.kvd = K.Kvd(n_layers=L, batch=B, n_q_heads=w.n_q_heads, n_kv_heads=Hkv, page_size=P, max_pages=NP,
+                         topk_pages=w.topk_pages, capacity_max=w.capacity, kv_dtype=w.torch_dtype,
+                         sink_pages=w.sink_pages, recent_pages=w.recent_pages, capacity=capacity,
+                         physical_layers=w.physical_layers, micro_batches=micro_batches, attn_splits=attn_splits)
+        self.kvd.bind_summaries(self.summaries)
+        self.kvd.bind_host_store(self.store)
+        self.kvd.bind_slot_pool(self.pool)
+        self.seq_lens = list(seq_lens) if seq_lens is not None else [w.ctx] * B
+        self.kvd.set_seq_lens(self.seq_lens)
+        self.capacity = capacity
+        if build_index:
+            for l in range(L):
+                self.kvd.build_summaries(l)
+            torch.cuda.synchronize()
+        self.warm()
+        U, k = w.units, w.topk_pages
+        i32 = dict(dtype=torch.int32, device=DEV)
+        self.sel_pages = torch.empty((U, k), **i32)
+        self.sel_slots = torch.empty((U, k), **i32)
+        self.hit_mask = torch.empty((U, k), **i32)
+        self.evicted = torch.empty((U, k), **i32)
+        self.counts = torch.empty((U, 3), **i32)
+        self.scores = torch.empty((U, NP), dtype=torch.float32, device=DEV)
+        self.out = torch.empty((B, w.n_q_heads, D), dtype=torch.float32, device=DEV)
+        self.lse = torch.empty((B, w.n_q_heads), dtype=torch.float32, device=DEV)
+
+    def warm_list(self, b: int) -> List[int]:
+        pages = W.warm_pages(self.w)
+        if pages is None:
+            return []
+        if self.w.warm == "recent":
+            n_valid = -(-self.seq_lens[b] // self.w.page)
+            return list(range(n_valid - self.w.recent_pages, n_valid))
+        return pages.tolist()
+
+    def warm(self):
+        w = self.w
+        self.kvd.cache_reset()
+        if w.warm == "cold":
+            return
+        for l in range(w.n_layers):
+            pages, counts = [], []
+            for u in range(w.units):
+                lst = self.warm_list(u // w.n_kv_heads)
+                pages.extend(lst)
+                counts.append(len(lst))
+            self.kvd.cache_warm(l, pages, counts)
+
+    def cap(self, layer: int, u: int) -> int:
+        if self.capacity is None:
+            return self.w.capacity
+        return int(self.capacity[layer * self.w.units + u])
+
+    def step(self, layer: int, t: int, q_layer: torch.Tensor):
+        """One fused layer-step through kvd_step; trace copied into the rig's buffers."""
+        self.kvd.step(layer, t, q_layer, self.out, self.lse)
+        self.kvd.step_trace(self.sel_pages, self.sel_slots, self.hit_mask, self.evicted, self.counts, self.scores)
+        torch.cuda.synchronize()
+        self.n_sel_pages = self.sel_pages.cpu().numpy()
+        self.n_sel_slots = self.sel_slots.cpu().numpy()
+        self.n_hit_mask = self.hit_mask.cpu().numpy()
+        self.n_evicted = self.evicted.cpu().numpy()
+        self.n_counts = self.counts.cpu().numpy()
+        self.n_scores = self.scores.cpu().numpy()
+        self.n_out = self.out.cpu().numpy()
+        self.n_lse = self.lse.cpu().numpy()
+
+    def close(self):
+        self.kvd.close()
+
+
+class OracleUnit:
+    """The oracle's view of one (layer, b, h): its slice of the host store, its own
+    summaries, and its LRU window carried across steps."""
+
+    def __init__(self, rig: Rig, layer: int, b: int, h: int):
+        w = rig.w
+        self.rig, self.layer, self.b, self.h = rig, layer, b, h
+        self.u = b * w.n_kv_heads + h
+        lp = layer % w.phys_layers
+        kv = rig.store[lp, b, h]                                            # [NP, 2, P, D]
+        self.keys = H.f64(kv[:, 0]).reshape(-1, w.head_dim)
+        self.values = H.f64(kv[:, 1]).reshape(-1, w.head_dim)
+        self.seq_len = rig.seq_lens[b]
+        self.code = H.dtype_code(w.torch_dtype)
+        self.summ = orc.page_summaries(self.keys, w.page, self.seq_len, self.code)
+        self.window = orc.LruWindow(rig.cap(layer, self.u))
+        self.window.warm(rig.warm_list(b), stamp=-1)
+        self.scale = 1.0 / math.sqrt(w.head_dim)
+
+    def step(self, t: int, q_layer: torch.Tensor, forced_sel=None):
+        w = self.rig.w
+        qg = H.f64(q_layer[self.b, self.h * w.group:(self.h + 1) * w.group])
+        return orc.decode_unit_step(qg, self.summ, self.keys, self.values, self.window, t, k=w.topk_pages,
+                                    page_size=w.page, seq_len=self.seq_len, scale=self.scale,
+                                    sink_pages=w.sink_pages, recent_pages=w.recent_pages, forced_sel=forced_sel)
+
+
+class StepReport:
+    def __init__(self):
+        self.tie_divergences = 0
+        self.max_attn_err = 0.0
+        self.max_lse_err = 0.0
+        self.max_score_err = 0.0
+        self.hits = 0
+        self.misses = 0
+        self.unit_steps = 0
+
+
+def score_bound(ou: OracleUnit, q_layer: torch.Tensor) -> np.ndarray:
+    """fp32 forward-error bound of the kernel's score per page:
+    (8 sequential fma + 4 tree adds + pooled-query rounding) ~ 20 eps * scale * sum_d |qbar_d s_pd|."""
+    w = ou.rig.w
+    qbar = orc.pooled_query(H.f64(q_layer[ou.b, ou.h * w.group:(ou.h + 1) * w.group]))
+    return 20.0 * 2.0 ** -24 * ou.scale * (np.abs(ou.summ) @ np.abs(qbar)) + 1e-12
+
+
+def compare_unit(rig: Rig, ou: OracleUnit, t: int, q_layer: torch.Tensor, rep: StepReport, check_scores: bool = True):
+    """Compare what kvd_step left in the rig's buffers for unit `ou` with the oracle's
+    step.  A GPU selection that differs from the oracle's only inside the tie band is
+    adopted by the oracle for this step (and counted), so that traces stay comparable."""
+    w = rig.w
+    u, k = ou.u, w.topk_pages
+    g_sel = rig.n_sel_pages[u]
+    qg = H.f64(q_layer[ou.b, ou.h * w.group:(ou.h + 1) * w.group])
+    o_scores = orc.page_scores(orc.pooled_query(qg), ou.summ, ou.scale)
+    o_sel = orc.select_pages(o_scores, k, w.sink_pages, w.recent_pages)
+    n_valid = o_scores.shape[0]
+    if check_scores:
+        g_scores = rig.n_scores[u, :n_valid].astype(np.float64)
+        err = np.abs(g_scores - o_scores)
+        bound = score_bound(ou, q_layer)
+        assert np.all(err <= bound), f"score error {err.max():.3e} above fp32 bound at unit {u} step {t}"
+        rep.max_score_err = max(rep.max_score_err, float(err.max()))
+    forced = None
+    if not np.array_equal(g_sel, o_sel):
+        ok, msg = H.selection_is_valid(o_scores, g_sel, k, w.sink_pages, w.recent_pages)
+        assert ok, f"selection differs outside the tie band at unit {u} step {t}: {msg}"
+        rep.tie_divergences += 1
+        forced = g_sel
+    want = ou.step(t, q_layer, forced_sel=forced)
+
+    # cache trace: hit / miss / evicted sets, bit-exact
+    hm = rig.n_hit_mask[u]
+    valid = g_sel >= 0
+    g_hits = sorted(g_sel[valid & (hm == 1)].tolist())
+    g_miss = sorted(g_sel[valid & (hm == 0)].tolist())
+    ev = rig.n_evicted[u]
+    g_ev = sorted(ev[ev >= 0].tolist())
+    assert g_hits == want["hits"], f"hit set differs at unit {u} step {t}"
+    assert g_miss == want["misses"], f"miss set differs at unit {u} step {t}"
+    assert g_ev == want["evicted"], f"evicted set differs at unit {u} step {t}"
+    cnt = rig.n_counts[u].tolist()
+    assert cnt == [len(g_hits), len(g_miss), len(g_ev)], f"counts differ at unit {u} step {t}: {cnt}"
+    slots = rig.n_sel_slots[u]
+    assert np.all(slots[valid] >= 0) and np.all(slots[~valid] == -1)
+    assert len(set(slots[valid].tolist())) == int(valid.sum()), "two selected pages share a slot"
+    assert slots[valid].max(initial=0) < rig.cap(ou.layer, u)
+
+    # attention output
+    G = w.group
+    g_out = rig.n_out[ou.b, ou.h * G:(ou.h + 1) * G]
+    g_lse = rig.n_lse[ou.b, ou.h * G:(ou.h + 1) * G]
+    e = H.attn_rel_err(g_out, want["out"])
+    assert e <= H.ATTN_RTOL, f"attention rel err {e:.3e} at unit {u} step {t}"
+    le = float(np.abs(g_lse - want["lse"]).max())
+    assert le <= 1e-3, f"lse abs err {le:.3e} at unit {u} step {t}"
+    rep.max_attn_err = max(rep.max_attn_err, e)
+    rep.max_lse_err = max(rep.max_lse_err, le)
+    rep.hits += len(g_hits)
+    rep.misses += len(g_miss)
+    rep.unit_steps += 1
+    return want
+
+
+def check_directory(rig: Rig, layer: int, units: Iterable[OracleUnit], check_data: bool = True):
+    """Directory invariants and contents after a step: every unit's resident set and
+    stamps equal the oracle's, pages are unique, slots stay below the capacity, and
+    (check_data) each occupied slot holds the bytes of its page in the host store."""
+    w = rig.w
+    slot_page, slot_stamp = rig.kvd.cache_export(layer)
+    for ou in units:
+        sp = slot_page[ou.u].numpy()
+        st = slot_stamp[ou.u].numpy()
+        occ = sp >= 0
+        assert not occ[rig.cap(layer, ou.u):].any()
+        pages = sp[occ].tolist()
+        assert len(pages) == len(set(pages))
+        got = {int(p): int(s) for p, s in zip(sp[occ], st[occ])}
+        assert got == ou.window.stamp, f"resident set / stamps differ at unit {ou.u}"
+        if check_data:
+            lp = layer % w.phys_layers
+            for s in np.nonzero(occ)[0][:64]:
+                a = rig.pool[layer, ou.b, ou.h, int(s)].cpu()
+                b = rig.store[lp, ou.b, ou.h, int(sp[s])]
+                assert torch.equal(a.view(torch.int16), b.view(torch.int16)), f"slot {s} of unit {ou.u} != page {sp[s]}"
+
+
+def run_steps(rig: Rig, units: List[OracleUnit], steps: int, *, layers: Optional[Sequence[int]] = None,
+              check_dir_every: int = 0, progress: str = "") -> StepReport:
+    """Drives `steps` decode steps over the given layers and compares every oracle unit
+    after each layer-step."""
+    w = rig.w
+    rep = StepReport()
+    layers = list(range(w.n_layers)) if layers is None else list(layers)
+    by_layer = {l: [ou for ou in units if ou.layer == l] for l in layers}
+    for t, q in enumerate(W.query_stream(w, rig.q0, steps, DEV)):
+        for l in layers:
+            rig.step(l, t, q[l])
+            for ou in by_layer[l]:
+                compare_unit(rig, ou, t, q[l], rep)
+            if check_dir_every and (t % check_dir_every == 0 or t == steps - 1):
+                check_directory(rig, l, by_layer[l])
+        if progress:
+            print(f"[{progress}] step {t} ok: units {rep.unit_steps} ties {rep.tie_divergences} "
+                  f"attn_err {rep.max_attn_err:.2e} hit_rate {rep.hits / max(1, rep.hits + rep.misses):.3f}", flush=True)
+    return rep

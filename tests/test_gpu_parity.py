@@ -1,0 +1,328 @@
+"""Parity of the HIP path (through the C ABI) against the CPU oracle, element by
+element, on seeded inputs small enough for the oracle to finish in seconds but
+spanning several tiles, ragged tails and the degenerate cases.  Runs on a GPU machine.
+"""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import kvd_oracle as orc
+from paper_2605_18071_amd import workloads as W
+from tests import helpers as H
+
+pytestmark = pytest.mark.gpu
+
+if torch.cuda.is_available():
+    from paper_2605_18071_amd import kvd as K
+    from tests import gpu_rig as R
+
+
+def small(name, **kw):
+    base = dict(name=name, n_layers=1, batch=2, ctx=16 * 300, page=16, n_q_heads=8, n_kv_heads=2, dtype="bf16",
+                topk_pages=24, capacity=60, steps=6, importance="planted", heavy_count=5, seed=4242)
+    base.update(kw)
+    return W.Workload(**base)
+
+
+def all_units(rig, layers=None):
+    w = rig.w
+    layers = range(w.n_layers) if layers is None else layers
+    return [R.OracleUnit(rig, l, b, h) for l in layers for b in range(w.batch) for h in range(w.n_kv_heads)]
+
+
+# --------------------------------------------------------------------------- #
+# index build
+# --------------------------------------------------------------------------- #
+@pytest.mark.parametrize("dtype,page", [("bf16", 16), ("f16", 16), ("bf16", 64), ("f16", 20)])
+def test_summaries_bit_exact(dtype, page):
+    w = small("summ", dtype=dtype, page=page, ctx=page * 37, batch=2)
+    rig = R.Rig(w, seq_lens=[w.ctx, w.ctx - page - 3])              # second sequence: ragged last page
+    got = rig.summaries.cpu()
+    for ou in all_units(rig):
+        n = ou.summ.shape[0]
+        want_bits = orc.f64_to_bits(ou.summ, ou.code)
+        assert np.array_equal(H.bits(got[0, ou.b, ou.h, :n]), want_bits), (ou.b, ou.h)
+    rig.close()
+
+
+# --------------------------------------------------------------------------- #
+# stage 1: scores and selection
+# --------------------------------------------------------------------------- #
+@pytest.mark.parametrize("kw", [
+    dict(),                                                         # 300 pages: one full 256-page block + tail
+    dict(dtype="f16", n_q_heads=14, n_kv_heads=2, topk_pages=17),   # G = 7
+    dict(ctx=16 * 1031, topk_pages=128, capacity=128),              # five blocks, ragged
+    dict(ctx=16 * 40, topk_pages=64, capacity=64),                  # fewer valid pages than k -> padding
+    dict(sink_pages=2, recent_pages=5),                             # forced pages
+    dict(n_q_heads=2, n_kv_heads=2, topk_pages=1, capacity=4),      # G = 1, k = 1 -> argmax
+])
+def test_score_select_parity(kw):
+    w = small("sel", **kw)
+    seq = [w.ctx, w.ctx - 21] if w.ctx > 16 * 64 or "sink_pages" in kw else None
+    rig = R.Rig(w, seq_lens=seq)
+    rep = R.StepReport()
+    for t, q in enumerate(W.query_stream(w, rig.q0, 3, R.DEV)):
+        rig.kvd.score_select(0, q[0], rig.sel_pages, rig.scores)
+        torch.cuda.synchronize()
+        sel = rig.sel_pages.cpu().numpy()
+        scores = rig.scores.cpu().numpy()
+        for ou in all_units(rig):
+            qg = H.f64(q[0][ou.b, ou.h * w.group:(ou.h + 1) * w.group])
+            o_scores = orc.page_scores(orc.pooled_query(qg), ou.summ, ou.scale)
+            o_sel = orc.select_pages(o_scores, w.topk_pages, w.sink_pages, w.recent_pages)
+            n = o_scores.shape[0]
+            err = np.abs(scores[ou.u, :n] - o_scores)
+            assert np.all(err <= R.score_bound(ou, q[0])), err.max()
+            if not np.array_equal(sel[ou.u], o_sel):
+                ok, msg = H.selection_is_valid(o_scores, sel[ou.u], w.topk_pages, w.sink_pages, w.recent_pages)
+                assert ok, msg
+                rep.tie_divergences += 1
+    assert rep.tie_divergences <= 1
+    rig.close()
+
+
+def test_select_exact_ties_go_to_lower_page():
+    """Identical summary rows give bit-identical scores on both sides; the choice among
+    them is then decided only by the tie rule."""
+    w = small("ties", ctx=16 * 200, topk_pages=16, capacity=32, heavy_count=0)
+    rig = R.Rig(w, build_index=False)
+    base = torch.randn(w.units, 10, w.head_dim, device=R.DEV)
+    idx = torch.randint(0, 10, (w.units, w.n_pages), device=R.DEV)
+    summ = torch.gather(base, 1, idx[:, :, None].expand(-1, -1, w.head_dim)).to(w.torch_dtype)
+    rig.summaries.copy_(summ.view(rig.summaries.shape))
+    q = next(W.query_stream(w, rig.q0, 1, R.DEV))
+    rig.kvd.score_select(0, q[0], rig.sel_pages, rig.scores)
+    torch.cuda.synchronize()
+    sel = rig.sel_pages.cpu().numpy()
+    summ64 = H.f64(summ)
+    cls = idx.cpu().numpy()
+    for b in range(w.batch):
+        for h in range(w.n_kv_heads):
+            u = b * w.n_kv_heads + h
+            qg = H.f64(q[0][b, h * w.group:(h + 1) * w.group])
+            sc = orc.page_scores(orc.pooled_query(qg), summ64[u], 1.0 / math.sqrt(w.head_dim))
+            ok, msg = H.selection_is_valid(sc, sel[u], w.topk_pages)
+            assert ok, msg
+            # pages with the same summary row tie exactly on both sides: inside such a class the
+            # selected pages must be the lowest-numbered ones
+            chosen = set(sel[u].tolist())
+            for c in range(10):
+                members = np.nonzero(cls[u] == c)[0]
+                flags = [int(p) in chosen for p in members]
+                assert flags == sorted(flags, reverse=True), (u, c)
+    # all scores equal: the k lowest pages win
+    rig.summaries.zero_()
+    rig.kvd.score_select(0, q[0], rig.sel_pages, None)
+    torch.cuda.synchronize()
+    assert np.array_equal(rig.sel_pages.cpu().numpy(), np.tile(np.arange(w.topk_pages), (w.units, 1)))
+    rig.close()
+
+
+# --------------------------------------------------------------------------- #
+# stage 2: directory + fetch
+# --------------------------------------------------------------------------- #
+@pytest.mark.parametrize("n_pages,k,cap", [(120, 8, 8), (120, 8, 19), (700, 33, 70), (64, 16, 64), (3000, 200, 333)])
+def test_resolve_trace_parity(n_pages, k, cap):
+    """Random, locality-biased selection traces straight into kvd_cache_resolve."""
+    w = small("lru", ctx=16 * n_pages, topk_pages=k, capacity=cap, batch=2, n_kv_heads=2, n_q_heads=4)
+    rig = R.Rig(w, build_index=False)
+    rng = np.random.default_rng(n_pages * 1000 + k)
+    wins = [orc.LruWindow(cap) for _ in range(w.units)]
+    for t in range(40):
+        sel = np.zeros((w.units, k), dtype=np.int32)
+        for u in range(w.units):
+            centre = (t * 3 + 17 * u) % n_pages
+            p = np.exp(-np.abs(np.arange(n_pages) - centre) / (2.0 * k)) + 1e-3
+            sel[u] = np.sort(rng.choice(n_pages, size=k, replace=False, p=p / p.sum()))
+        rig.sel_pages.copy_(torch.from_numpy(sel))
+        rig.kvd.cache_resolve(0, t, rig.sel_pages, rig.sel_slots, rig.hit_mask, rig.evicted, rig.counts, do_gather=True)
+        torch.cuda.synchronize()
+        hm = rig.hit_mask.cpu().numpy()
+        ev = rig.evicted.cpu().numpy()
+        cnt = rig.counts.cpu().numpy()
+        slots = rig.sel_slots.cpu().numpy()
+        for u in range(w.units):
+            hits, misses, evicted = wins[u].resolve(sel[u], t)
+            assert sorted(sel[u][hm[u] == 1].tolist()) == hits, (t, u)
+            assert sorted(sel[u][hm[u] == 0].tolist()) == misses, (t, u)
+            assert sorted(ev[u][ev[u] >= 0].tolist()) == evicted, (t, u)
+            assert cnt[u].tolist() == [len(hits), len(misses), len(evicted)]
+            assert len(set(slots[u].tolist())) == k and slots[u].min() >= 0 and slots[u].max() < cap
+        if t % 13 == 0 or t == 39:
+            sp, st = rig.kvd.cache_export(0)
+            for u in range(w.units):
+                occ = sp[u] >= 0
+                got = {int(p): int(s) for p, s in zip(sp[u][occ], st[u][occ])}
+                assert got == wins[u].stamp, (t, u)
+                b, h = divmod(u, w.n_kv_heads)
+                for s in np.nonzero(occ.numpy())[0]:
+                    a = rig.pool[0, b, h, int(s)].cpu().view(torch.int16)
+                    assert torch.equal(a, rig.store[0, b, h, int(sp[u][s])].view(torch.int16)), (t, u, s)
+    st = rig.kvd.stats()
+    assert st.hits + st.misses == 40 * w.units * k
+    assert st.gathered_bytes == st.misses * w.page_bytes
+    rig.close()
+
+
+def test_cache_export_import_and_warm_errors():
+    w = small("imp", ctx=16 * 100, topk_pages=4, capacity=10, batch=1, n_kv_heads=2, n_q_heads=4)
+    rig = R.Rig(w, build_index=False)
+    rig.kvd.cache_warm(0, [5, 6, 7, 9, 8], [3, 2])
+    sp, st = rig.kvd.cache_export(0)
+    assert sp[0].tolist() == [5, 6, 7] + [-1] * 7 and sp[1].tolist() == [9, 8] + [-1] * 8
+    assert st.max() == -1
+    assert torch.equal(rig.pool[0, 0, 1, 0].cpu().view(torch.int16), rig.store[0, 0, 1, 9].view(torch.int16))
+    sp2 = sp.clone(); sp2[0, 4] = 42; st2 = st.clone(); st2[0, 4] = 3
+    rig.kvd.cache_import(0, sp2, st2)
+    a, b = rig.kvd.cache_export(0)
+    assert torch.equal(a, sp2) and torch.equal(b, st2)
+    assert torch.equal(rig.pool[0, 0, 0, 4].cpu().view(torch.int16), rig.store[0, 0, 0, 42].view(torch.int16))
+    bad = sp2.clone(); bad[1, 3] = 9                                # page 9 twice in unit 1
+    with pytest.raises(K.KvdError) as e:
+        rig.kvd.cache_import(0, bad, st2)
+    assert e.value.status == K.ERR_STATE
+    bad = sp2.clone(); bad[0, 2] = 100                              # page out of range
+    with pytest.raises(K.KvdError):
+        rig.kvd.cache_import(0, bad, st2)
+    a, b = rig.kvd.cache_export(0)                                  # rejected imports leave the cache unchanged
+    assert torch.equal(a, sp2) and torch.equal(b, st2)
+    with pytest.raises(K.KvdError) as e:
+        rig.kvd.cache_warm(0, list(range(11)) + [1], [11, 1])
+    assert e.value.status == K.ERR_CAPACITY
+    with pytest.raises(K.KvdError) as e:
+        rig.kvd.cache_warm(0, [1, 1, 2], [2, 1])
+    assert e.value.status == K.ERR_ARG
+    rig.close()
+
+
+def test_unbound_buffers_and_unpinned_store_are_rejected():
+    k = K.Kvd(n_layers=1, batch=1, n_q_heads=4, n_kv_heads=1, page_size=16, max_pages=32, topk_pages=4,
+              capacity_max=8, kv_dtype=torch.float16)
+    q = torch.zeros(1, 4, 128, dtype=torch.float16, device=R.DEV)
+    out = torch.zeros(1, 4, 128, dtype=torch.float32, device=R.DEV)
+    with pytest.raises(K.KvdError) as e:
+        k.step(0, 0, q, out)
+    assert e.value.status == K.ERR_STATE
+    pageable = torch.zeros(1, 1, 1, 32, 2, 16, 128, dtype=torch.float16)
+    with pytest.raises(K.KvdError) as e:
+        k.bind_host_store(pageable)
+    assert e.value.status == K.ERR_ARG
+    with pytest.raises(K.KvdError):
+        k.set_seq_lens([16 * 32 + 1])
+    k.close()
+
+
+# --------------------------------------------------------------------------- #
+# stage 3: attention
+# --------------------------------------------------------------------------- #
+@pytest.mark.parametrize("kw,splits", [
+    (dict(), 0),
+    (dict(), 1),
+    (dict(dtype="f16"), 5),
+    (dict(n_q_heads=2, n_kv_heads=2), 0),                            # G = 1
+    (dict(n_q_heads=14, n_kv_heads=2, dtype="f16", page=32, ctx=32 * 150), 3),   # G = 7, two tiles per page
+    (dict(n_q_heads=16, n_kv_heads=2, page=64, ctx=64 * 90), 0),     # G = 8, four tiles per page
+    (dict(page=20, ctx=20 * 111, n_q_heads=6, n_kv_heads=2), 4),     # G = 3, page not a multiple of the tile
+    (dict(ctx=16 * 30, topk_pages=40, capacity=40), 0),              # k > valid pages -> padded selection
+])
+def test_attention_parity(kw, splits):
+    w = small("attn", **kw)
+    seq = [w.ctx - 5, w.ctx - w.page - 1]                            # ragged last pages
+    rig = R.Rig(w, seq_lens=seq, attn_splits=splits)
+    units = all_units(rig)
+    rng = np.random.default_rng(11)
+    q = next(W.query_stream(w, rig.q0, 1, R.DEV))[0]
+    k = w.topk_pages
+    sel = np.full((w.units, k), -1, dtype=np.int32)
+    for ou in units:
+        n_valid = ou.summ.shape[0]
+        kk = min(k, n_valid)
+        pages = rng.choice(n_valid - 1, size=kk - 1, replace=False).tolist() + [n_valid - 1]   # ragged last page included
+        sel[ou.u, :kk] = np.sort(np.asarray(pages, dtype=np.int32))
+    rig.sel_pages.copy_(torch.from_numpy(sel))
+    rig.kvd.cache_resolve(0, 0, rig.sel_pages, rig.sel_slots)
+    rig.kvd.sparse_decode_attn(0, q, rig.sel_pages, rig.sel_slots, rig.out, rig.lse)
+    torch.cuda.synchronize()
+    out, lse = rig.out.cpu().numpy(), rig.lse.cpu().numpy()
+    G = w.group
+    for ou in units:
+        toks = orc.selected_tokens(sel[ou.u], w.page, ou.seq_len)
+        qg = H.f64(q[ou.b, ou.h * G:(ou.h + 1) * G])
+        o, l = orc.attend(qg, ou.keys[toks], ou.values[toks], ou.scale)
+        e = H.attn_rel_err(out[ou.b, ou.h * G:(ou.h + 1) * G], o)
+        assert e <= H.ATTN_RTOL, (ou.b, ou.h, e)
+        assert np.abs(lse[ou.b, ou.h * G:(ou.h + 1) * G] - l).max() <= 1e-3
+    rig.close()
+
+
+def test_attention_with_all_pages_equals_dense_and_ignores_cache_state():
+    w = small("dense", ctx=16 * 48, topk_pages=48, capacity=48, dtype="f16")
+    rig = R.Rig(w, seq_lens=[w.ctx, w.ctx - 7])
+    q = next(W.query_stream(w, rig.q0, 1, R.DEV))[0]
+    rig.step(0, 0, q)                                                 # cold: everything is fetched
+    cold = rig.n_out.copy()
+    assert rig.n_counts[:, 1].sum() > 0
+    rig.step(0, 1, q)                                                 # warm: everything hits
+    assert rig.n_counts[:, 1].sum() == 0
+    assert np.array_equal(cold, rig.n_out)
+    G = w.group
+    for ou in all_units(rig):
+        T = ou.seq_len
+        qg = H.f64(q[ou.b, ou.h * G:(ou.h + 1) * G])
+        logits = ou.scale * (qg @ ou.keys[:T].T)
+        p = np.exp(logits - logits.max(axis=1, keepdims=True))
+        dense = (p / p.sum(axis=1, keepdims=True)) @ ou.values[:T]
+        assert H.attn_rel_err(cold[ou.b, ou.h * G:(ou.h + 1) * G], dense) <= H.ATTN_RTOL
+    rig.close()
+
+
+# --------------------------------------------------------------------------- #
+# the whole step, several steps, scaled-down versions of the five configurations
+# --------------------------------------------------------------------------- #
+SCALED = {
+    1: W.CONFIGS[1],                                                                    # full size already
+    2: W.CONFIGS[2].replace(n_layers=3, physical_layers=2, batch=2, ctx=16 * 520, topk_pages=32, capacity=260,
+                            heavy_count=11, steps=8),
+    3: W.CONFIGS[3].replace(batch=2, ctx=16 * 1100, topk_pages=48, capacity=275, steps=8),
+    4: W.CONFIGS[4].replace(n_layers=2, physical_layers=1, batch=3, ctx=32 * 300, topk_pages=16, capacity=60,
+                            heavy_count=3, steps=6),
+    5: W.CONFIGS[5].replace(batch=1, ctx=64 * 700, topk_pages=24, recent_pages=8, capacity=35, steps=6),
+}
+
+
+@pytest.mark.parametrize("cfg", [1, 2, 3, 4, 5])
+def test_step_parity_scaled_configs(cfg):
+    w = SCALED[cfg]
+    rig = R.Rig(w)
+    units = all_units(rig)
+    rep = R.run_steps(rig, units, w.steps, check_dir_every=3, progress=f"cfg{cfg}-scaled")
+    assert rep.unit_steps == w.steps * w.n_layers * w.units
+    assert rep.tie_divergences <= 2
+    if cfg == 1:
+        assert rep.misses == 0                                       # the cache holds every page
+    rig.close()
+
+
+def test_micro_batches_and_per_unit_capacities_give_identical_results():
+    w = SCALED[3].replace(batch=4, steps=5)
+    rng = np.random.default_rng(5)
+    caps = rng.integers(w.topk_pages, w.capacity + 1, size=w.n_layers * w.units).tolist()
+    outs = []
+    for mb in (1, 4):
+        rig = R.Rig(w, capacity=caps, micro_batches=mb)
+        units = all_units(rig) if mb == 4 else []
+        trace = []
+        for t, q in enumerate(W.query_stream(w, rig.q0, w.steps, R.DEV)):
+            rig.step(0, t, q[0])
+            rep = R.StepReport()
+            for ou in units:
+                R.compare_unit(rig, ou, t, q[0], rep)
+            trace.append((rig.n_sel_pages.copy(), rig.n_hit_mask.copy(), np.sort(rig.n_evicted, axis=1),
+                          rig.n_counts.copy(), rig.n_out.copy()))
+        outs.append(trace)
+        rig.close()
+    for a, b in zip(*outs):
+        for x, y in zip(a, b):
+            assert np.array_equal(x, y)
