@@ -1,0 +1,229 @@
+#!/usr/bin/env python3
+"""Benchmark of the offloaded sparse-decode layer-step on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 3]
+
+A "step" is one kvd_step: score -> select -> resolve -> fetch -> attend for one
+layer over the whole batch.  The workload is the benchmark definition's
+configuration 3 (1 layer, batch 16, 131072-token context, page 16, 32 q / 8 kv
+heads, bf16, budget 4096 tokens, GPU cache 25 % of the pages, the rest in pinned
+host memory) with synthetic Zipf-importance K/V; the drifting query stream is
+continued past the configuration's 32 steps when more steps are asked for.
+
+Prints one JSON line: `value` is end-to-end layer-steps/s of the K timed steps
+(fetch of missed pages from pinned host memory included, index / cache / queries
+resident in HBM).  `roofline` is for the dominant HBM-bound kernel, measured in
+the same process with HIP events around every kernel launch (a second pass over
+the same number of steps); `gpu_resident` is the fused GPU-side path (everything
+but the host-link fetch) against the HBM roofline; `cpu_baseline` is the CPU
+oracle timed on a bounded sample of the same workload on the host cores.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import math
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0
+
+
+def describe(w) -> str:
+    return (f"{w.name}: L={w.n_layers} B={w.batch} ctx={w.ctx} page={w.page} heads={w.n_q_heads}q/{w.n_kv_heads}kv "
+            f"D={w.head_dim} {w.dtype} k={w.topk_pages} pages ({w.topk_pages * w.page} tokens) "
+            f"cache={w.capacity} pages/unit ({100.0 * w.capacity / w.n_pages:.0f}%) {w.importance} importance, rho={w.rho}")
+
+
+def cpu_baseline(w, store, q_list, seconds: float):
+    """Times the oracle, as it stands, on as many (unit, step) pairs of the same workload as fit
+    in about `seconds`; returns layer-steps/s (one layer-step = all U units)."""
+    import numpy as np
+    import torch
+    from oracle import kvd_oracle as orc
+    try:
+        from threadpoolctl import threadpool_info
+        threads = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        threads = 1
+    code = orc.F16 if w.dtype == "f16" else orc.BF16
+    scale = 1.0 / math.sqrt(w.head_dim)
+    done, spent, units = 0, 0.0, 0
+    for u in range(w.units):
+        b, h = divmod(u, w.n_kv_heads)
+        kv = store[0, b, h].to(torch.float64).numpy()
+        keys, vals = kv[:, 0].reshape(-1, w.head_dim), kv[:, 1].reshape(-1, w.head_dim)
+        summ = orc.page_summaries(keys, w.page, w.ctx, code)            # set-up, not timed
+        win = orc.LruWindow(w.capacity)
+        units += 1
+        for t, q in enumerate(q_list):
+            qg = q[b, h * w.group:(h + 1) * w.group].to(torch.float64).numpy()
+            t0 = time.perf_counter()
+            orc.decode_unit_step(qg, summ, keys, vals, win, t, k=w.topk_pages, page_size=w.page, seq_len=w.ctx,
+                                 scale=scale, sink_pages=w.sink_pages, recent_pages=w.recent_pages)
+            spent += time.perf_counter() - t0
+            done += 1
+        if spent >= seconds:
+            break
+    per_unit_step = spent / max(done, 1)
+    return {
+        "value": 1.0 / (per_unit_step * w.units),
+        "unit": "layer-steps/s",
+        "cores": int(threads),
+        "kind": "oracle",
+        "sample": f"{done} unit-steps ({units} of {w.units} units x {len(q_list)} steps) in {spent:.1f} s, "
+                  f"scaled to one layer-step = {w.units} units",
+    }
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=62)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--config", type=int, default=3)
+    ap.add_argument("--micro-batches", type=int, default=0)
+    ap.add_argument("--cpu-seconds", type=float, default=12.0, help="0 skips the oracle baseline")
+    ap.add_argument("--no-profile-pass", action="store_true", help="skip the per-kernel HIP-event pass")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this path is built and measured on one GPU only (no collectives, no sharding); "
+              "run with --gpus 1", file=sys.stderr)
+        return 2
+
+    import torch
+    from paper_2605_18071_amd import kvd as K
+    from paper_2605_18071_amd import workloads as W
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 2
+    K.load()                                     # fails loudly if libkvd.so is not built
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+    w = W.CONFIGS[args.config]
+    if w.n_layers != 1:
+        # multi-layer configurations are benchmarked on one layer's worth of state at full per-layer shape
+        w = w.replace(n_layers=1, physical_layers=1)
+    L, B, Hkv, NP, P, D, U, k = w.n_layers, w.batch, w.n_kv_heads, w.n_pages, w.page, w.head_dim, w.units, w.topk_pages
+
+    t_setup = time.perf_counter()
+    q0 = W.initial_queries(w, dev)
+    store = W.make_kv_store(w, q0, dev)
+    summ = torch.zeros((L, B, Hkv, NP, D), dtype=w.torch_dtype, device=dev)
+    pool = torch.zeros((L, B, Hkv, w.capacity, 2, P, D), dtype=w.torch_dtype, device=dev)
+    ctx = K.Kvd(n_layers=L, batch=B, n_q_heads=w.n_q_heads, n_kv_heads=Hkv, page_size=P, max_pages=NP, topk_pages=k,
+                capacity_max=w.capacity, kv_dtype=w.torch_dtype, sink_pages=w.sink_pages, recent_pages=w.recent_pages,
+                physical_layers=w.physical_layers, micro_batches=args.micro_batches)
+    ctx.bind_summaries(summ)
+    ctx.bind_host_store(store)
+    ctx.bind_slot_pool(pool)
+    ctx.build_summaries(0)
+    pages = W.warm_pages(w)
+    if pages is not None:
+        ctx.cache_warm(0, pages.tolist() * U, [len(pages)] * U)
+    n_total = args.warmup + 2 * args.steps
+    queries = [q[0].contiguous() for q in W.query_stream(w, q0, n_total, dev)]
+    out = torch.empty((B, w.n_q_heads, D), dtype=torch.float32, device=dev)
+    torch.cuda.synchronize()
+    t_setup = time.perf_counter() - t_setup
+
+    stream = torch.cuda.current_stream()
+    t = 0
+    for _ in range(args.warmup):
+        ctx.step(0, t, queries[t], out, stream=stream)
+        t += 1
+    torch.cuda.synchronize()
+    ctx.reset_stats()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        ctx.step(0, t, queries[t], out, stream=stream)
+        t += 1
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    st = ctx.stats()
+    ms_per_step = 1e3 * elapsed / args.steps
+    hit_rate = st.hits / max(1, st.hits + st.misses)
+    gathered_per_step = st.gathered_bytes / args.steps
+
+    summary_bytes = U * NP * D * 2
+    selected_bytes = U * k * w.page_bytes
+    io_bytes = B * w.n_q_heads * D * (2 + 4)
+    result = {
+        "metric": "decode layer-steps/sec",
+        "value": args.steps / elapsed,
+        "unit": "layer-steps/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": ms_per_step,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": w.dtype,
+        "data": "synthetic",
+        "config": {"workload": describe(w), "micro_batches": max(1, args.micro_batches), "setup_s": round(t_setup, 1)},
+        "cache": {"hit_rate": hit_rate, "host_bytes_per_step": gathered_per_step,
+                  "host_link_GBps_if_fetch_bound": gathered_per_step / (elapsed / args.steps) / 1e9},
+    }
+
+    if not args.no_profile_pass:
+        ctx.set_profiling(True)
+        ctx.reset_stats()
+        for _ in range(args.steps):
+            ctx.step(0, t, queries[t], out, stream=stream)
+            t += 1
+        torch.cuda.synchronize()
+        ps = ctx.stats()
+        ctx.set_profiling(False)
+        n = max(1, ps.profiled_steps)
+        kern = {"score": (ps.ms_score / n, summary_bytes + U * NP * 4),
+                "select": (ps.ms_select / n, 0), "resolve": (ps.ms_resolve / n, 0),
+                "attend": (ps.ms_attend / n, selected_bytes), "combine": (ps.ms_combine / n, 0)}
+        name = "attend" if kern["attend"][0] >= kern["score"][0] else "score"
+        ms, alg = kern[name]
+        alg = selected_bytes if name == "attend" else summary_bytes
+        achieved = alg / (ms * 1e-3) / 1e9
+        result["roofline"] = {"kernel": f"{name}_kernel", "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBPS,
+                              "unit": "GB/s", "frac": achieved / HBM_PEAK_GBPS, "traffic": None,
+                              "algorithmic_bytes_per_launch": alg, "avg_launch_ms": ms}
+        gpu_ms = sum(v[0] for v in kern.values())
+        gpu_bytes = summary_bytes + selected_bytes + io_bytes
+        other = "score" if name == "attend" else "attend"
+        oms = kern[other][0]
+        oalg = summary_bytes if other == "score" else selected_bytes
+        result["gpu_resident"] = {
+            "what": "score+select+resolve+attend+combine kernel time per layer-step (fetch excluded), "
+                    "bytes = summaries + selected K/V + q/out",
+            "ms": gpu_ms, "bytes": gpu_bytes, "GBps": gpu_bytes / (gpu_ms * 1e-3) / 1e9,
+            "frac_of_hbm_peak": gpu_bytes / (gpu_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS,
+            "layer_steps_per_s": 1e3 / gpu_ms,
+            "kernel_ms": {kname: v[0] for kname, v in kern.items()},
+            f"{other}_GBps": oalg / (oms * 1e-3) / 1e9,
+        }
+        gms = ps.ms_gather / n
+        gbytes = ps.gathered_bytes / n
+        result["host_link"] = {"gather_ms": gms, "bytes_per_step": gbytes,
+                               "GBps": (gbytes / (gms * 1e-3) / 1e9) if gms > 0 else None}
+
+    if args.cpu_seconds > 0:
+        q_cpu = [q.cpu() for q in queries[:2]]
+        result["cpu_baseline"] = cpu_baseline(w, store, q_cpu, args.cpu_seconds)
+
+    # one plain device copy of known size so that a counter run of this command has a calibration kernel
+    a = torch.empty(256 << 20, dtype=torch.uint8, device=dev)
+    b = torch.empty_like(a)
+    b.copy_(a)
+    torch.cuda.synchronize()
+    ctx.close()
+    print(json.dumps(result))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -88,8 +88,9 @@ typedef struct {
   uint64_t misses;         /* selected pages fetched from the host store */
   uint64_t evictions;      /* pages dropped from the window */
   uint64_t gathered_bytes; /* misses * page_bytes */
-  /* filled only while profiling is on (kvd_set_profiling): accumulated milliseconds */
-  double ms_score_select, ms_resolve, ms_gather, ms_attend, ms_total;
+  /* filled only while profiling is on (kvd_set_profiling): accumulated milliseconds per kernel,
+     from HIP events recorded around each launch on the stream it runs on */
+  double ms_score, ms_select, ms_resolve, ms_gather, ms_attend, ms_combine, ms_total;
   uint64_t profiled_steps;
 } kvd_stats;
 

@@ -63,7 +63,7 @@ static void free_ctx(kvd_ctx* c) {
     if (c->ev_sel[i]) (void)hipEventDestroy(c->ev_sel[i]);
     if (c->ev_fetch[i]) (void)hipEventDestroy(c->ev_fetch[i]);
   }
-  for (int i = 0; i < 8; ++i)
+  for (int i = 0; i < 12; ++i)
     if (c->ev_prof[i]) (void)hipEventDestroy(c->ev_prof[i]);
   if (c->side) (void)hipStreamDestroy(c->side);
   free(c->h_capacity);
@@ -161,7 +161,7 @@ int kvd_create(const kvd_config* cfg, kvd_ctx** out) {
     ok(hipEventCreateWithFlags(&c->ev_sel[i], hipEventDisableTiming));
     ok(hipEventCreateWithFlags(&c->ev_fetch[i], hipEventDisableTiming));
   }
-  for (int i = 0; i < 8 && e == hipSuccess; ++i) ok(hipEventCreate(&c->ev_prof[i]));
+  for (int i = 0; i < 12 && e == hipSuccess; ++i) ok(hipEventCreate(&c->ev_prof[i]));
   if (e == hipSuccess) ok(hipMemcpy(c->d_capacity, c->h_capacity, LU * sizeof(int32_t), hipMemcpyHostToDevice));
   if (e == hipSuccess) ok(hipMemcpy(c->d_seq_len, c->h_seq_len, (size_t)c->B * sizeof(int32_t), hipMemcpyHostToDevice));
   if (e == hipSuccess) ok(hipMemset(c->d_stats, 0, 4 * sizeof(unsigned long long)));
@@ -325,34 +325,42 @@ int kvd_sparse_decode_attn(kvd_ctx* ctx, int32_t layer, const void* q, const int
   if (!ctx || !q || !sel_pages || !sel_slots || !out || layer < 0 || layer >= ctx->L || !aligned16(q))
     return KVD_ERR_ARG;
   if (!ctx->pool) return KVD_ERR_STATE;
-  HIP_TRY(ctx, kvd_launch_attend(ctx, layer, q, sel_pages, sel_slots, out, lse, static_cast<hipStream_t>(stream)));
+  HIP_TRY(ctx, kvd_launch_attend(ctx, layer, q, sel_pages, sel_slots, static_cast<hipStream_t>(stream)));
+  HIP_TRY(ctx, kvd_launch_combine(ctx, out, lse, static_cast<hipStream_t>(stream)));
   return KVD_OK;
 }
 
+// One layer-step with every kernel bracketed by HIP events on the stream it runs on; waits for the
+// step and accumulates the per-kernel times.  Stages run for the whole batch, one after another.
 static int step_profiled(kvd_ctx* c, int layer, int step, const void* q, float* out, float* lse, hipStream_t s) {
   hipEvent_t* ev = c->ev_prof;
   HIP_TRY(c, hipEventRecord(ev[0], s));
   HIP_TRY(c, kvd_launch_score(c, layer, q, c->d_scores, 0, c->U, s));
-  HIP_TRY(c, kvd_launch_select(c, c->d_scores, c->d_sel_pages, 0, c->U, s));
   HIP_TRY(c, hipEventRecord(ev[1], s));
+  HIP_TRY(c, kvd_launch_select(c, c->d_scores, c->d_sel_pages, 0, c->U, s));
+  HIP_TRY(c, hipEventRecord(ev[2], s));
   HIP_TRY(c, kvd_launch_resolve(c, layer, step, c->d_sel_pages, c->d_sel_slots, c->d_hit_mask, c->d_evicted,
                                 c->d_counts, 0, c->U, s));
-  HIP_TRY(c, hipEventRecord(ev[2], s));
-  HIP_TRY(c, hipStreamWaitEvent(c->side, ev[2], 0));
-  HIP_TRY(c, hipEventRecord(ev[3], c->side));
-  HIP_TRY(c, kvd_launch_gather(c, layer, 0, c->U, c->side));
+  HIP_TRY(c, hipEventRecord(ev[3], s));
+  HIP_TRY(c, hipStreamWaitEvent(c->side, ev[3], 0));
   HIP_TRY(c, hipEventRecord(ev[4], c->side));
-  HIP_TRY(c, hipStreamWaitEvent(s, ev[4], 0));
-  HIP_TRY(c, hipEventRecord(ev[5], s));
-  HIP_TRY(c, kvd_launch_attend(c, layer, q, c->d_sel_pages, c->d_sel_slots, out, lse, s));
+  HIP_TRY(c, kvd_launch_gather(c, layer, 0, c->U, c->side));
+  HIP_TRY(c, hipEventRecord(ev[5], c->side));
+  HIP_TRY(c, hipStreamWaitEvent(s, ev[5], 0));
   HIP_TRY(c, hipEventRecord(ev[6], s));
-  HIP_TRY(c, hipEventSynchronize(ev[6]));
+  HIP_TRY(c, kvd_launch_attend(c, layer, q, c->d_sel_pages, c->d_sel_slots, s));
+  HIP_TRY(c, hipEventRecord(ev[7], s));
+  HIP_TRY(c, kvd_launch_combine(c, out, lse, s));
+  HIP_TRY(c, hipEventRecord(ev[8], s));
+  HIP_TRY(c, hipEventSynchronize(ev[8]));
   float ms = 0.f;
-  HIP_TRY(c, hipEventElapsedTime(&ms, ev[0], ev[1])); c->ms_score_select += ms;
-  HIP_TRY(c, hipEventElapsedTime(&ms, ev[1], ev[2])); c->ms_resolve += ms;
-  HIP_TRY(c, hipEventElapsedTime(&ms, ev[3], ev[4])); c->ms_gather += ms;
-  HIP_TRY(c, hipEventElapsedTime(&ms, ev[5], ev[6])); c->ms_attend += ms;
-  HIP_TRY(c, hipEventElapsedTime(&ms, ev[0], ev[6])); c->ms_total += ms;
+  HIP_TRY(c, hipEventElapsedTime(&ms, ev[0], ev[1])); c->ms_score += ms;
+  HIP_TRY(c, hipEventElapsedTime(&ms, ev[1], ev[2])); c->ms_select += ms;
+  HIP_TRY(c, hipEventElapsedTime(&ms, ev[2], ev[3])); c->ms_resolve += ms;
+  HIP_TRY(c, hipEventElapsedTime(&ms, ev[4], ev[5])); c->ms_gather += ms;
+  HIP_TRY(c, hipEventElapsedTime(&ms, ev[6], ev[7])); c->ms_attend += ms;
+  HIP_TRY(c, hipEventElapsedTime(&ms, ev[7], ev[8])); c->ms_combine += ms;
+  HIP_TRY(c, hipEventElapsedTime(&ms, ev[0], ev[8])); c->ms_total += ms;
   ++c->profiled_steps;
   return KVD_OK;
 }
@@ -377,7 +385,8 @@ int kvd_step(kvd_ctx* ctx, int32_t layer, int32_t step, const void* q, float* ou
     HIP_TRY(c, hipEventRecord(c->ev_fetch[i], c->side));
   }
   for (int i = 0; i < c->MB; ++i) HIP_TRY(c, hipStreamWaitEvent(s, c->ev_fetch[i], 0));
-  HIP_TRY(c, kvd_launch_attend(c, layer, q, c->d_sel_pages, c->d_sel_slots, out, lse, s));
+  HIP_TRY(c, kvd_launch_attend(c, layer, q, c->d_sel_pages, c->d_sel_slots, s));
+  HIP_TRY(c, kvd_launch_combine(c, out, lse, s));
   return KVD_OK;
 }
 
@@ -414,10 +423,12 @@ int kvd_get_stats(kvd_ctx* ctx, kvd_stats* host_out) {
   host_out->misses = raw[1];
   host_out->evictions = raw[2];
   host_out->gathered_bytes = raw[1] * (uint64_t)ctx->page_bytes;
-  host_out->ms_score_select = ctx->ms_score_select;
+  host_out->ms_score = ctx->ms_score;
+  host_out->ms_select = ctx->ms_select;
   host_out->ms_resolve = ctx->ms_resolve;
   host_out->ms_gather = ctx->ms_gather;
   host_out->ms_attend = ctx->ms_attend;
+  host_out->ms_combine = ctx->ms_combine;
   host_out->ms_total = ctx->ms_total;
   host_out->profiled_steps = ctx->profiled_steps;
   return KVD_OK;
@@ -428,7 +439,7 @@ int kvd_reset_stats(kvd_ctx* ctx) {
   HIP_TRY(ctx, hipDeviceSynchronize());
   HIP_TRY(ctx, hipMemset(ctx->d_stats, 0, 4 * sizeof(unsigned long long)));
   ctx->n_steps = 0;
-  ctx->ms_score_select = ctx->ms_resolve = ctx->ms_gather = ctx->ms_attend = ctx->ms_total = 0.0;
+  ctx->ms_score = ctx->ms_select = ctx->ms_resolve = ctx->ms_gather = ctx->ms_attend = ctx->ms_combine = ctx->ms_total = 0.0;
   ctx->profiled_steps = 0;
   return KVD_OK;
 }

@@ -225,7 +225,7 @@ static bool dispatch_group(int G, const AttnArgs& a, dim3 grid, hipStream_t s) {
 }  // namespace kvd
 
 hipError_t kvd_launch_attend(kvd_ctx* c, int layer, const void* q, const int32_t* sel_pages,
-                             const int32_t* sel_slots, float* out, float* lse, hipStream_t s) {
+                             const int32_t* sel_slots, hipStream_t s) {
   using namespace kvd;
   AttnArgs a;
   a.q = reinterpret_cast<const uint16_t*>(q);
@@ -242,8 +242,11 @@ hipError_t kvd_launch_attend(kvd_ctx* c, int layer, const void* q, const int32_t
   dim3 grid(c->S, c->U);
   const bool ok = c->bf16 ? dispatch_group<true>(c->G, a, grid, s) : dispatch_group<false>(c->G, a, grid, s);
   if (!ok) return hipErrorInvalidValue;
-  hipError_t err = hipGetLastError();
-  if (err != hipSuccess) return err;
+  return hipGetLastError();
+}
+
+hipError_t kvd_launch_combine(kvd_ctx* c, float* out, float* lse, hipStream_t s) {
+  using namespace kvd;
   hipLaunchKernelGGL(combine_kernel, dim3(c->U), dim3(kHeadDim), 0, s, c->d_part_acc, c->d_part_ml, out, lse, c->S,
                      c->G, c->Hq, c->Hkv);
   return hipGetLastError();

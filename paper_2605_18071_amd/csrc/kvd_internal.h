@@ -49,11 +49,11 @@ struct kvd_ctx {
   hipStream_t side;
   hipEvent_t ev_sel[KVD_MAX_MICRO];
   hipEvent_t ev_fetch[KVD_MAX_MICRO];
-  hipEvent_t ev_prof[8];
+  hipEvent_t ev_prof[12];
   int profiling;
   int last_hip;
   uint64_t n_steps;
-  double ms_score_select, ms_resolve, ms_gather, ms_attend, ms_total;
+  double ms_score, ms_select, ms_resolve, ms_gather, ms_attend, ms_combine, ms_total;
   uint64_t profiled_steps;
 };
 
@@ -64,7 +64,8 @@ hipError_t kvd_launch_resolve(kvd_ctx* c, int layer, int step, const int32_t* se
                               int32_t* hit_mask, int32_t* evicted, int32_t* counts, int u0, int u1, hipStream_t s);
 hipError_t kvd_launch_gather(kvd_ctx* c, int layer, int u0, int u1, hipStream_t s);
 hipError_t kvd_launch_attend(kvd_ctx* c, int layer, const void* q, const int32_t* sel_pages,
-                             const int32_t* sel_slots, float* out, float* lse, hipStream_t s);
+                             const int32_t* sel_slots, hipStream_t s);
+hipError_t kvd_launch_combine(kvd_ctx* c, float* out, float* lse, hipStream_t s);
 hipError_t kvd_launch_refill(kvd_ctx* c, int layer, hipStream_t s);
 hipError_t kvd_launch_build_summaries(kvd_ctx* c, int layer, hipStream_t s);
 hipError_t kvd_launch_fill_i32(int32_t* p, int32_t v, size_t n, hipStream_t s);
