@@ -184,7 +184,7 @@ def main() -> int:
         n = max(1, ps.profiled_steps)
         kern = {"score": (ps.ms_score / n, summary_bytes + U * NP * 4),
                 "select": (ps.ms_select / n, 0), "resolve": (ps.ms_resolve / n, 0),
-                "attend": (ps.ms_attend / n, selected_bytes), "combine": (ps.ms_combine / n, 0)}
+                "attend": (ps.ms_attend / n, selected_bytes)}
         name = "attend" if kern["attend"][0] >= kern["score"][0] else "score"
         ms, alg = kern[name]
         alg = selected_bytes if name == "attend" else summary_bytes
@@ -198,7 +198,7 @@ def main() -> int:
         oms = kern[other][0]
         oalg = summary_bytes if other == "score" else selected_bytes
         result["gpu_resident"] = {
-            "what": "score+select+resolve+attend+combine kernel time per layer-step (fetch excluded), "
+            "what": "score+select+resolve+attend kernel time per layer-step (fetch excluded), "
                     "bytes = summaries + selected K/V + q/out",
             "ms": gpu_ms, "bytes": gpu_bytes, "GBps": gpu_bytes / (gpu_ms * 1e-3) / 1e9,
             "frac_of_hbm_peak": gpu_bytes / (gpu_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS,

@@ -90,7 +90,7 @@ typedef struct {
   uint64_t gathered_bytes; /* misses * page_bytes */
   /* filled only while profiling is on (kvd_set_profiling): accumulated milliseconds per kernel,
      from HIP events recorded around each launch on the stream it runs on */
-  double ms_score, ms_select, ms_resolve, ms_gather, ms_attend, ms_combine, ms_total;
+  double ms_score, ms_select, ms_resolve, ms_gather, ms_attend, ms_total;
   uint64_t profiled_steps;
 } kvd_stats;
 
@@ -113,8 +113,10 @@ int kvd_bind_summaries(kvd_ctx* ctx, void* dev_summaries);
 /* Paged KV store in pinned host memory, [Lp][B][Hkv][NP][2][P][D] kv_dtype (K page, then V
  * page).  KVD_ERR_ARG if the GPU cannot address the pointer. */
 int kvd_bind_host_store(kvd_ctx* ctx, const void* pinned_store);
-/* GPU cache tier, dev, [L][B][Hkv][Cmax][2][P][D] kv_dtype, 16-byte aligned.  Contents are
- * managed by the library (which page sits in which slot is the directory's business). */
+/* GPU cache tier, dev, [L][B][Hkv][Cmax] slots of page_bytes each, 16-byte aligned.  Contents are
+ * managed by the library: which page sits in which slot is the directory's business, and inside a
+ * slot the page is stored in the order the attention kernel reads it (pages of a multiple of 16
+ * tokens: 16-token tiles of MFMA-operand-ready K and transposed V; otherwise K[P][D] then V[P][D]). */
 int kvd_bind_slot_pool(kvd_ctx* ctx, void* dev_pool);
 /* Valid tokens per sequence, host [B], each in 1..NP*P.  Default: NP*P.  Synchronous. */
 int kvd_set_seq_lens(kvd_ctx* ctx, const int32_t* host_seq_len);

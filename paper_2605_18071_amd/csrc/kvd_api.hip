@@ -56,7 +56,7 @@ static void free_ctx(kvd_ctx* c) {
   if (c == nullptr) return;
   void* dev[] = {c->d_capacity, c->d_seq_len, c->d_page_to_slot, c->d_slot_page, c->d_slot_stamp, c->d_resident,
                  c->d_scores, c->d_sel_pages, c->d_sel_slots, c->d_hit_mask, c->d_evicted, c->d_counts,
-                 c->d_miss_list, c->d_miss_count, c->d_part_acc, c->d_part_ml, c->d_stats};
+                 c->d_miss_list, c->d_miss_count, c->d_part_acc, c->d_part_ml, c->d_attn_ticket, c->d_stats};
   for (void* p : dev)
     if (p) (void)hipFree(p);
   for (int i = 0; i < KVD_MAX_MICRO; ++i) {
@@ -124,6 +124,7 @@ int kvd_create(const kvd_config* cfg, kvd_ctx** out) {
   c->MB = cfg->micro_batches < 1 ? 1 : cfg->micro_batches;
   if (c->MB > c->B) c->MB = c->B;
   c->bf16 = cfg->kv_dtype == KVD_BF16;
+  c->tiled = (c->P % 16) == 0;
   c->scale = cfg->softmax_scale > 0.f ? cfg->softmax_scale : 1.0f / sqrtf((float)c->D);
   c->page_bytes = (size_t)2 * c->P * c->D * 2;
   int S = cfg->attn_splits;
@@ -156,6 +157,7 @@ int kvd_create(const kvd_config* cfg, kvd_ctx** out) {
       ok(dev_alloc(&c->d_miss_count, (size_t)c->U)) &&
       ok(dev_alloc(&c->d_part_acc, (size_t)c->U * c->S * c->G * c->D)) &&
       ok(dev_alloc(&c->d_part_ml, (size_t)c->U * c->S * c->G * 2)) && ok(dev_alloc(&c->d_stats, 4)) &&
+      ok(dev_alloc(&c->d_attn_ticket, (size_t)c->U)) &&
       ok(hipStreamCreateWithFlags(&c->side, hipStreamNonBlocking));
   for (int i = 0; i < c->MB && e == hipSuccess; ++i) {
     ok(hipEventCreateWithFlags(&c->ev_sel[i], hipEventDisableTiming));
@@ -166,6 +168,7 @@ int kvd_create(const kvd_config* cfg, kvd_ctx** out) {
   if (e == hipSuccess) ok(hipMemcpy(c->d_seq_len, c->h_seq_len, (size_t)c->B * sizeof(int32_t), hipMemcpyHostToDevice));
   if (e == hipSuccess) ok(hipMemset(c->d_stats, 0, 4 * sizeof(unsigned long long)));
   if (e == hipSuccess) ok(hipMemset(c->d_miss_count, 0, (size_t)c->U * sizeof(int32_t)));
+  if (e == hipSuccess) ok(hipMemset(c->d_attn_ticket, 0, (size_t)c->U * sizeof(int32_t)));
   if (e != hipSuccess) { free_ctx(c); return KVD_ERR_HIP; }
   const int r = reset_directory(c, -1);
   if (r != KVD_OK) { free_ctx(c); return r; }
@@ -325,8 +328,7 @@ int kvd_sparse_decode_attn(kvd_ctx* ctx, int32_t layer, const void* q, const int
   if (!ctx || !q || !sel_pages || !sel_slots || !out || layer < 0 || layer >= ctx->L || !aligned16(q))
     return KVD_ERR_ARG;
   if (!ctx->pool) return KVD_ERR_STATE;
-  HIP_TRY(ctx, kvd_launch_attend(ctx, layer, q, sel_pages, sel_slots, static_cast<hipStream_t>(stream)));
-  HIP_TRY(ctx, kvd_launch_combine(ctx, out, lse, static_cast<hipStream_t>(stream)));
+  HIP_TRY(ctx, kvd_launch_attend(ctx, layer, q, sel_pages, sel_slots, out, lse, static_cast<hipStream_t>(stream)));
   return KVD_OK;
 }
 
@@ -348,19 +350,16 @@ static int step_profiled(kvd_ctx* c, int layer, int step, const void* q, float* 
   HIP_TRY(c, hipEventRecord(ev[5], c->side));
   HIP_TRY(c, hipStreamWaitEvent(s, ev[5], 0));
   HIP_TRY(c, hipEventRecord(ev[6], s));
-  HIP_TRY(c, kvd_launch_attend(c, layer, q, c->d_sel_pages, c->d_sel_slots, s));
+  HIP_TRY(c, kvd_launch_attend(c, layer, q, c->d_sel_pages, c->d_sel_slots, out, lse, s));
   HIP_TRY(c, hipEventRecord(ev[7], s));
-  HIP_TRY(c, kvd_launch_combine(c, out, lse, s));
-  HIP_TRY(c, hipEventRecord(ev[8], s));
-  HIP_TRY(c, hipEventSynchronize(ev[8]));
+  HIP_TRY(c, hipEventSynchronize(ev[7]));
   float ms = 0.f;
   HIP_TRY(c, hipEventElapsedTime(&ms, ev[0], ev[1])); c->ms_score += ms;
   HIP_TRY(c, hipEventElapsedTime(&ms, ev[1], ev[2])); c->ms_select += ms;
   HIP_TRY(c, hipEventElapsedTime(&ms, ev[2], ev[3])); c->ms_resolve += ms;
   HIP_TRY(c, hipEventElapsedTime(&ms, ev[4], ev[5])); c->ms_gather += ms;
   HIP_TRY(c, hipEventElapsedTime(&ms, ev[6], ev[7])); c->ms_attend += ms;
-  HIP_TRY(c, hipEventElapsedTime(&ms, ev[7], ev[8])); c->ms_combine += ms;
-  HIP_TRY(c, hipEventElapsedTime(&ms, ev[0], ev[8])); c->ms_total += ms;
+  HIP_TRY(c, hipEventElapsedTime(&ms, ev[0], ev[7])); c->ms_total += ms;
   ++c->profiled_steps;
   return KVD_OK;
 }
@@ -385,8 +384,7 @@ int kvd_step(kvd_ctx* ctx, int32_t layer, int32_t step, const void* q, float* ou
     HIP_TRY(c, hipEventRecord(c->ev_fetch[i], c->side));
   }
   for (int i = 0; i < c->MB; ++i) HIP_TRY(c, hipStreamWaitEvent(s, c->ev_fetch[i], 0));
-  HIP_TRY(c, kvd_launch_attend(c, layer, q, c->d_sel_pages, c->d_sel_slots, s));
-  HIP_TRY(c, kvd_launch_combine(c, out, lse, s));
+  HIP_TRY(c, kvd_launch_attend(c, layer, q, c->d_sel_pages, c->d_sel_slots, out, lse, s));
   return KVD_OK;
 }
 
@@ -428,7 +426,6 @@ int kvd_get_stats(kvd_ctx* ctx, kvd_stats* host_out) {
   host_out->ms_resolve = ctx->ms_resolve;
   host_out->ms_gather = ctx->ms_gather;
   host_out->ms_attend = ctx->ms_attend;
-  host_out->ms_combine = ctx->ms_combine;
   host_out->ms_total = ctx->ms_total;
   host_out->profiled_steps = ctx->profiled_steps;
   return KVD_OK;
@@ -439,7 +436,7 @@ int kvd_reset_stats(kvd_ctx* ctx) {
   HIP_TRY(ctx, hipDeviceSynchronize());
   HIP_TRY(ctx, hipMemset(ctx->d_stats, 0, 4 * sizeof(unsigned long long)));
   ctx->n_steps = 0;
-  ctx->ms_score = ctx->ms_select = ctx->ms_resolve = ctx->ms_gather = ctx->ms_attend = ctx->ms_combine = ctx->ms_total = 0.0;
+  ctx->ms_score = ctx->ms_select = ctx->ms_resolve = ctx->ms_gather = ctx->ms_attend = ctx->ms_total = 0.0;
   ctx->profiled_steps = 0;
   return KVD_OK;
 }

@@ -5,6 +5,7 @@
 // builds the index (System Overview: mean key of each page).
 #include "kvd_device.h"
 #include "kvd_internal.h"
+#include "kvd_tile_layout.h"
 
 namespace kvd {
 
@@ -169,22 +170,80 @@ __global__ __launch_bounds__(kResolveThreads) void resolve_kernel(ResolveArgs a)
 constexpr int kGatherThreads = 256;
 constexpr int kGatherBlocksPerUnit = 8;
 
+// Copies one page from the host store (natural layout: K[P][D] then V[P][D]) into a slot, with all
+// 256 threads of the block.  TILED: the slot takes the tile layout of kvd_tile_layout.h — K moves
+// in 16-byte units to permuted positions, V is transposed through LDS (`vt`, 16 x 128 elements).
+template <bool TILED>
+__device__ __forceinline__ void copy_page(const char* __restrict__ src, char* __restrict__ dst, int P,
+                                          unsigned page_bytes, uint16_t* vt) {
+  const int tid = threadIdx.x;
+  if (!TILED) {
+    const uint4* s4 = reinterpret_cast<const uint4*>(src);
+    uint4* d4 = reinterpret_cast<uint4*>(dst);
+    for (unsigned o = tid; o < page_bytes / 16; o += kGatherThreads) d4[o] = s4[o];
+    return;
+  }
+  const int tiles = P / kTileTokens;
+  const int row = tid >> 4, ch = tid & 15;           // source unit: token `row` of the tile, dims 8ch..8ch+7
+  const char* ksrc = src;
+  const char* vsrc = src + (size_t)P * kRowBytes;
+  for (int t = 0; t < tiles; ++t) {
+    const uint4 kq = *reinterpret_cast<const uint4*>(ksrc + ((size_t)(t * kTileTokens + row) * kRowBytes) + ch * 16);
+    const uint4 vq = *reinterpret_cast<const uint4*>(vsrc + ((size_t)(t * kTileTokens + row) * kRowBytes) + ch * 16);
+    char* tile = dst + (size_t)t * kTileBytes;
+    // K: chunk c = ch / 4, lane = row + 16 * (ch % 4)
+    *reinterpret_cast<uint4*>(tile + ((ch >> 2) * 64 + (ch & 3) * 16 + row) * 16) = kq;
+    __syncthreads();                                   // previous tile's readers are done with vt
+    *reinterpret_cast<uint4*>(vt + row * kHeadDim + ch * 8) = vq;
+    __syncthreads();
+    // V: this thread assembles destination unit `tid` = chunk c, lane i + 16 g
+    const int c = tid >> 6, g = (tid >> 4) & 3, i = tid & 15;
+    uint16_t e[8];
+#pragma unroll
+    for (int hh = 0; hh < 2; ++hh)
+#pragma unroll
+      for (int k = 0; k < 4; ++k) e[hh * 4 + k] = vt[(4 * g + k) * kHeadDim + 32 * c + 16 * hh + i];
+    uint4 outv;
+    outv.x = (u32)e[0] | ((u32)e[1] << 16);
+    outv.y = (u32)e[2] | ((u32)e[3] << 16);
+    outv.z = (u32)e[4] | ((u32)e[5] << 16);
+    outv.w = (u32)e[6] | ((u32)e[7] << 16);
+    *reinterpret_cast<uint4*>(tile + kTilePartBytes + tid * 16) = outv;
+  }
+}
+
 // Fetch: block (x, u) copies misses x, x+8, ... of unit u from the pinned host store (read across
 // the host link, 16 bytes per lane) into their slots.
+template <bool TILED>
 __global__ __launch_bounds__(kGatherThreads) void gather_kernel(const char* __restrict__ store,   // [U][NP] pages of the layer
                                                                char* __restrict__ pool,          // [U][Cmax] slots of the layer
                                                                const int32_t* __restrict__ miss_list,
                                                                const int32_t* __restrict__ miss_count, int k, int NP,
-                                                               int Cmax, unsigned page_bytes, int u0) {
+                                                               int Cmax, int P, unsigned page_bytes, int u0) {
+  __shared__ uint16_t vt[kTileTokens * kHeadDim];
   const int u = blockIdx.y + u0;
   const int m = miss_count[u];
   for (int j = blockIdx.x; j < m; j += gridDim.x) {
     const int page = miss_list[((size_t)u * k + j) * 2];
     const int slot = miss_list[((size_t)u * k + j) * 2 + 1];
     if (slot < 0) continue;
-    const uint4* src = reinterpret_cast<const uint4*>(store + ((size_t)u * NP + page) * page_bytes);
-    uint4* dst = reinterpret_cast<uint4*>(pool + ((size_t)u * Cmax + slot) * page_bytes);
-    for (unsigned o = threadIdx.x; o < page_bytes / 16; o += kGatherThreads) dst[o] = src[o];
+    copy_page<TILED>(store + ((size_t)u * NP + page) * page_bytes, pool + ((size_t)u * Cmax + slot) * page_bytes, P,
+                     page_bytes, vt);
+  }
+}
+
+// Set-up: (re)load every occupied slot of a layer from the host store, as named by slot_page.
+template <bool TILED>
+__global__ __launch_bounds__(kGatherThreads) void refill_kernel(const char* __restrict__ store, char* __restrict__ pool,
+                                                               const int32_t* __restrict__ slot_page, int NP, int Cmax,
+                                                               int P, unsigned page_bytes) {
+  __shared__ uint16_t vt[kTileTokens * kHeadDim];
+  const int u = blockIdx.y;
+  for (int s = blockIdx.x; s < Cmax; s += gridDim.x) {
+    const int page = slot_page[(size_t)u * Cmax + s];
+    if (page < 0) continue;
+    copy_page<TILED>(store + ((size_t)u * NP + page) * page_bytes, pool + ((size_t)u * Cmax + s) * page_bytes, P,
+                     page_bytes, vt);
   }
 }
 
@@ -226,20 +285,6 @@ __global__ __launch_bounds__(kHeadDim) void summaries_kernel(const uint16_t* __r
   *out = f64_to_kv<BF16>(acc / (double)n);
 }
 
-// Set-up: (re)load every occupied slot of a layer from the host store, as named by slot_page.
-__global__ __launch_bounds__(kGatherThreads) void refill_kernel(const char* __restrict__ store, char* __restrict__ pool,
-                                                               const int32_t* __restrict__ slot_page, int NP, int Cmax,
-                                                               unsigned page_bytes) {
-  const int u = blockIdx.y;
-  for (int s = blockIdx.x; s < Cmax; s += gridDim.x) {
-    const int page = slot_page[(size_t)u * Cmax + s];
-    if (page < 0) continue;
-    const uint4* src = reinterpret_cast<const uint4*>(store + ((size_t)u * NP + page) * page_bytes);
-    uint4* dst = reinterpret_cast<uint4*>(pool + ((size_t)u * Cmax + s) * page_bytes);
-    for (unsigned o = threadIdx.x; o < page_bytes / 16; o += kGatherThreads) dst[o] = src[o];
-  }
-}
-
 __global__ void fill_i32_kernel(int32_t* p, int32_t v, size_t n) {
   for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x) p[i] = v;
 }
@@ -276,8 +321,12 @@ hipError_t kvd_launch_gather(kvd_ctx* c, int layer, int u0, int u1, hipStream_t 
   const int lp = layer % c->Lp;
   const char* store = c->store_dev + (size_t)lp * c->U * c->NP * c->page_bytes;
   char* pool = c->pool + (size_t)layer * c->U * c->Cmax * c->page_bytes;
-  hipLaunchKernelGGL(gather_kernel, dim3(kGatherBlocksPerUnit, u1 - u0), dim3(kGatherThreads), 0, s, store, pool,
-                     c->d_miss_list, c->d_miss_count, c->k, c->NP, c->Cmax, (unsigned)c->page_bytes, u0);
+  if (c->tiled)
+    hipLaunchKernelGGL(gather_kernel<true>, dim3(kGatherBlocksPerUnit, u1 - u0), dim3(kGatherThreads), 0, s, store, pool,
+                       c->d_miss_list, c->d_miss_count, c->k, c->NP, c->Cmax, c->P, (unsigned)c->page_bytes, u0);
+  else
+    hipLaunchKernelGGL(gather_kernel<false>, dim3(kGatherBlocksPerUnit, u1 - u0), dim3(kGatherThreads), 0, s, store, pool,
+                       c->d_miss_list, c->d_miss_count, c->k, c->NP, c->Cmax, c->P, (unsigned)c->page_bytes, u0);
   return hipGetLastError();
 }
 
@@ -288,8 +337,12 @@ hipError_t kvd_launch_refill(kvd_ctx* c, int layer, hipStream_t s) {
   char* pool = c->pool + (size_t)layer * c->U * c->Cmax * c->page_bytes;
   const int32_t* slot_page = c->d_slot_page + (size_t)layer * c->U * c->Cmax;
   const int bx = c->Cmax < 64 ? c->Cmax : 64;
-  hipLaunchKernelGGL(refill_kernel, dim3(bx, c->U), dim3(kGatherThreads), 0, s, store, pool, slot_page, c->NP, c->Cmax,
-                     (unsigned)c->page_bytes);
+  if (c->tiled)
+    hipLaunchKernelGGL(refill_kernel<true>, dim3(bx, c->U), dim3(kGatherThreads), 0, s, store, pool, slot_page, c->NP,
+                       c->Cmax, c->P, (unsigned)c->page_bytes);
+  else
+    hipLaunchKernelGGL(refill_kernel<false>, dim3(bx, c->U), dim3(kGatherThreads), 0, s, store, pool, slot_page, c->NP,
+                       c->Cmax, c->P, (unsigned)c->page_bytes);
   return hipGetLastError();
 }
 

@@ -16,6 +16,7 @@ struct kvd_ctx {
   kvd_config cfg;
   int L, B, Hq, Hkv, G, D, P, NP, k, Cmax, Lp, U, MB, S;
   int bf16;
+  int tiled;               // slots use the tile layout (page size a multiple of 16)
   float scale;
   size_t page_bytes;
 
@@ -41,6 +42,7 @@ struct kvd_ctx {
   int32_t* d_miss_count;    // [U]
   float* d_part_acc;        // [U][S][G][D]
   float* d_part_ml;         // [U][S][G][2]  (max in log2 units, sum)
+  int32_t* d_attn_ticket;   // [U] arrival counter of the attention splits, zero between launches
   unsigned long long* d_stats;  // hits, misses, evictions
 
   // owned, host
@@ -53,7 +55,7 @@ struct kvd_ctx {
   int profiling;
   int last_hip;
   uint64_t n_steps;
-  double ms_score, ms_select, ms_resolve, ms_gather, ms_attend, ms_combine, ms_total;
+  double ms_score, ms_select, ms_resolve, ms_gather, ms_attend, ms_total;
   uint64_t profiled_steps;
 };
 
@@ -64,8 +66,7 @@ hipError_t kvd_launch_resolve(kvd_ctx* c, int layer, int step, const int32_t* se
                               int32_t* hit_mask, int32_t* evicted, int32_t* counts, int u0, int u1, hipStream_t s);
 hipError_t kvd_launch_gather(kvd_ctx* c, int layer, int u0, int u1, hipStream_t s);
 hipError_t kvd_launch_attend(kvd_ctx* c, int layer, const void* q, const int32_t* sel_pages,
-                             const int32_t* sel_slots, hipStream_t s);
-hipError_t kvd_launch_combine(kvd_ctx* c, float* out, float* lse, hipStream_t s);
+                             const int32_t* sel_slots, float* out, float* lse, hipStream_t s);
 hipError_t kvd_launch_refill(kvd_ctx* c, int layer, hipStream_t s);
 hipError_t kvd_launch_build_summaries(kvd_ctx* c, int layer, hipStream_t s);
 hipError_t kvd_launch_fill_i32(int32_t* p, int32_t v, size_t n, hipStream_t s);

@@ -222,9 +222,9 @@ def check_directory(rig: Rig, layer: int, units: Iterable[OracleUnit], check_dat
         if check_data:
             lp = layer % w.phys_layers
             for s in np.nonzero(occ)[0][:64]:
-                a = rig.pool[layer, ou.b, ou.h, int(s)].cpu()
-                b = rig.store[lp, ou.b, ou.h, int(sp[s])]
-                assert torch.equal(a.view(torch.int16), b.view(torch.int16)), f"slot {s} of unit {ou.u} != page {sp[s]}"
+                a = rig.pool[layer, ou.b, ou.h, int(s)].cpu().view(torch.int16).reshape(-1)
+                b = H.slot_image(rig.store[lp, ou.b, ou.h, int(sp[s])])
+                assert torch.equal(a, b), f"slot {s} of unit {ou.u} != page {sp[s]}"
 
 
 def run_steps(rig: Rig, units: List[OracleUnit], steps: int, *, layers: Optional[Sequence[int]] = None,

@@ -92,3 +92,22 @@ def read_golden(name: str):
                 continue
             rows.append([c.strip() for c in line.split("|")])
     return rows
+
+
+def slot_image(page: torch.Tensor) -> torch.Tensor:
+    """The 16-bit pattern a slot must hold for a host page [2, P, D] (K then V), written here
+    from the documented slot layout: pages of a multiple of 16 tokens are stored as 16-token
+    tiles, each a K part [chunk c][group g][token i][8 dims 32c+8g+e] followed by a V part
+    [chunk c][token group g][dim i][half hh][4 tokens 4g+k] holding V[4g+k][32c+16hh+i];
+    any other page size keeps the host order."""
+    raw = page.detach().cpu().contiguous().view(torch.int16).numpy()
+    P, D = raw.shape[1], raw.shape[2]
+    if P % 16 != 0:
+        return torch.from_numpy(raw.reshape(-1).copy())
+    tiles = []
+    for t in range(P // 16):
+        k = raw[0, 16 * t:16 * t + 16].reshape(16, 4, 4, 8)           # [i, c, g, e]
+        v = raw[1, 16 * t:16 * t + 16].reshape(4, 4, 4, 2, 16)        # [g, k, c, hh, i]
+        tiles.append(k.transpose(1, 2, 0, 3).reshape(-1))             # [c, g, i, e]
+        tiles.append(v.transpose(2, 0, 4, 3, 1).reshape(-1))          # [c, g, i, hh, k]
+    return torch.from_numpy(np.concatenate(tiles).copy())

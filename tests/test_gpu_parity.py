@@ -158,8 +158,8 @@ def test_resolve_trace_parity(n_pages, k, cap):
                 assert got == wins[u].stamp, (t, u)
                 b, h = divmod(u, w.n_kv_heads)
                 for s in np.nonzero(occ.numpy())[0]:
-                    a = rig.pool[0, b, h, int(s)].cpu().view(torch.int16)
-                    assert torch.equal(a, rig.store[0, b, h, int(sp[u][s])].view(torch.int16)), (t, u, s)
+                    a = rig.pool[0, b, h, int(s)].cpu().view(torch.int16).reshape(-1)
+                    assert torch.equal(a, H.slot_image(rig.store[0, b, h, int(sp[u][s])])), (t, u, s)
     st = rig.kvd.stats()
     assert st.hits + st.misses == 40 * w.units * k
     assert st.gathered_bytes == st.misses * w.page_bytes
@@ -173,12 +173,12 @@ def test_cache_export_import_and_warm_errors():
     sp, st = rig.kvd.cache_export(0)
     assert sp[0].tolist() == [5, 6, 7] + [-1] * 7 and sp[1].tolist() == [9, 8] + [-1] * 8
     assert st.max() == -1
-    assert torch.equal(rig.pool[0, 0, 1, 0].cpu().view(torch.int16), rig.store[0, 0, 1, 9].view(torch.int16))
+    assert torch.equal(rig.pool[0, 0, 1, 0].cpu().view(torch.int16).reshape(-1), H.slot_image(rig.store[0, 0, 1, 9]))
     sp2 = sp.clone(); sp2[0, 4] = 42; st2 = st.clone(); st2[0, 4] = 3
     rig.kvd.cache_import(0, sp2, st2)
     a, b = rig.kvd.cache_export(0)
     assert torch.equal(a, sp2) and torch.equal(b, st2)
-    assert torch.equal(rig.pool[0, 0, 0, 4].cpu().view(torch.int16), rig.store[0, 0, 0, 42].view(torch.int16))
+    assert torch.equal(rig.pool[0, 0, 0, 4].cpu().view(torch.int16).reshape(-1), H.slot_image(rig.store[0, 0, 0, 42]))
     bad = sp2.clone(); bad[1, 3] = 9                                # page 9 twice in unit 1
     with pytest.raises(K.KvdError) as e:
         rig.kvd.cache_import(0, bad, st2)
