@@ -183,7 +183,7 @@ def main() -> int:
         ctx.set_profiling(False)
         n = max(1, ps.profiled_steps)
         kern = {"score": (ps.ms_score / n, summary_bytes + U * NP * 4),
-                "select": (ps.ms_select / n, 0), "resolve": (ps.ms_resolve / n, 0),
+                "select_resolve": (ps.ms_select_resolve / n, 0),
                 "attend": (ps.ms_attend / n, selected_bytes)}
         name = "attend" if kern["attend"][0] >= kern["score"][0] else "score"
         ms, alg = kern[name]

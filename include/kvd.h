@@ -90,7 +90,7 @@ typedef struct {
   uint64_t gathered_bytes; /* misses * page_bytes */
   /* filled only while profiling is on (kvd_set_profiling): accumulated milliseconds per kernel,
      from HIP events recorded around each launch on the stream it runs on */
-  double ms_score, ms_select, ms_resolve, ms_gather, ms_attend, ms_total;
+  double ms_score, ms_select_resolve, ms_gather, ms_attend, ms_total;
   uint64_t profiled_steps;
 } kvd_stats;
 
@@ -162,9 +162,9 @@ int kvd_score_select(kvd_ctx* ctx, int32_t layer, const void* q, int32_t* sel_pa
  *   counts     [B][Hkv][3] int32 out or NULL: hits, misses, evictions.
  * Hits are re-stamped with `step`; misses take free slots first, then the slots of the resident
  * pages, not selected in this step, with the smallest (stamp, page).  `step` must not decrease
- * for a layer.  With do_gather != 0 the missed pages are copied from the host store into their
- * slots on the library's side stream, and `stream` waits for that copy before anything enqueued
- * after this call.  With do_gather == 0 only the directory changes (slot contents are stale). */
+ * for a layer.  With do_gather != 0 the missed pages are then copied from the host store into
+ * their slots on `stream`.  With do_gather == 0 only the directory changes (slot contents are
+ * stale).  sel_pages must hold distinct pages in ascending order, as stage 1 writes them. */
 int kvd_cache_resolve(kvd_ctx* ctx, int32_t layer, int32_t step, const int32_t* sel_pages, int32_t* sel_slots,
                       int32_t* hit_mask, int32_t* evicted, int32_t* counts, int32_t do_gather, void* stream);
 
@@ -178,8 +178,9 @@ int kvd_sparse_decode_attn(kvd_ctx* ctx, int32_t layer, const void* q, const int
 
 /* ---- hot path: the whole layer-step -------------------------------------------------------- */
 
-/* Stages 1-3 for one layer with the fetch on the side stream; with micro_batches > 1 the fetch
- * of one group of sequences overlaps the selection of the next (SFC Disaggregation).
+/* Stages 1-3 for one layer.  With micro_batches > 1 the fetch of one group of sequences runs on
+ * the library's side stream and overlaps the selection of the next group (SFC Disaggregation);
+ * otherwise everything is enqueued on `stream`.
  *   q [B][Hq][D] kv_dtype, out [B][Hq][D] fp32, lse [B][Hq] fp32 or NULL. */
 int kvd_step(kvd_ctx* ctx, int32_t layer, int32_t step, const void* q, float* out, float* lse, void* stream);
 

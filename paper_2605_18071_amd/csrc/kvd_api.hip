@@ -125,6 +125,8 @@ int kvd_create(const kvd_config* cfg, kvd_ctx** out) {
   if (c->MB > c->B) c->MB = c->B;
   c->bf16 = cfg->kv_dtype == KVD_BF16;
   c->tiled = (c->P % 16) == 0;
+  { const char* e_ = getenv("KVD_FUSE_MERGE"); c->fuse_merge = e_ ? atoi(e_) : 0; }
+  { const char* e_ = getenv("KVD_GENERIC_SELECT"); c->generic_select = e_ ? atoi(e_) : 0; }
   c->scale = cfg->softmax_scale > 0.f ? cfg->softmax_scale : 1.0f / sqrtf((float)c->D);
   c->page_bytes = (size_t)2 * c->P * c->D * 2;
   int S = cfg->attn_splits;
@@ -301,7 +303,11 @@ int kvd_score_select(kvd_ctx* ctx, int32_t layer, const void* q, int32_t* sel_pa
   hipStream_t s = static_cast<hipStream_t>(stream);
   float* sc = scores ? scores : ctx->d_scores;
   HIP_TRY(ctx, kvd_launch_score(ctx, layer, q, sc, 0, ctx->U, s));
-  HIP_TRY(ctx, kvd_launch_select(ctx, sc, sel_pages, 0, ctx->U, s));
+  if (kvd_fast_path_ok(ctx))
+    HIP_TRY(ctx, kvd_launch_select_resolve(ctx, layer, 0, true, false, sc, sel_pages, nullptr, nullptr, nullptr, nullptr,
+                                           0, ctx->U, s));
+  else
+    HIP_TRY(ctx, kvd_launch_select(ctx, sc, sel_pages, 0, ctx->U, s));
   return KVD_OK;
 }
 
@@ -310,15 +316,15 @@ int kvd_cache_resolve(kvd_ctx* ctx, int32_t layer, int32_t step, const int32_t* 
   if (!ctx || !sel_pages || !sel_slots || layer < 0 || layer >= ctx->L) return KVD_ERR_ARG;
   if (do_gather && (!ctx->pool || !ctx->store_dev)) return KVD_ERR_STATE;
   hipStream_t s = static_cast<hipStream_t>(stream);
-  HIP_TRY(ctx, kvd_launch_resolve(ctx, layer, step, sel_pages, sel_slots, hit_mask ? hit_mask : ctx->d_hit_mask,
-                                  evicted ? evicted : ctx->d_evicted, counts ? counts : ctx->d_counts, 0, ctx->U, s));
-  if (do_gather) {
-    HIP_TRY(ctx, hipEventRecord(ctx->ev_sel[0], s));
-    HIP_TRY(ctx, hipStreamWaitEvent(ctx->side, ctx->ev_sel[0], 0));
-    HIP_TRY(ctx, kvd_launch_gather(ctx, layer, 0, ctx->U, ctx->side));
-    HIP_TRY(ctx, hipEventRecord(ctx->ev_fetch[0], ctx->side));
-    HIP_TRY(ctx, hipStreamWaitEvent(s, ctx->ev_fetch[0], 0));
-  }
+  int32_t* hm = hit_mask ? hit_mask : ctx->d_hit_mask;
+  int32_t* ev = evicted ? evicted : ctx->d_evicted;
+  int32_t* cn = counts ? counts : ctx->d_counts;
+  if (kvd_fast_path_ok(ctx))
+    HIP_TRY(ctx, kvd_launch_select_resolve(ctx, layer, step, false, true, nullptr, const_cast<int32_t*>(sel_pages),
+                                           sel_slots, hm, ev, cn, 0, ctx->U, s));
+  else
+    HIP_TRY(ctx, kvd_launch_resolve(ctx, layer, step, sel_pages, sel_slots, hm, ev, cn, 0, ctx->U, s));
+  if (do_gather) HIP_TRY(ctx, kvd_launch_gather(ctx, layer, 0, ctx->U, s));
   ++ctx->n_steps;
   return KVD_OK;
 }
@@ -332,34 +338,38 @@ int kvd_sparse_decode_attn(kvd_ctx* ctx, int32_t layer, const void* q, const int
   return KVD_OK;
 }
 
-// One layer-step with every kernel bracketed by HIP events on the stream it runs on; waits for the
-// step and accumulates the per-kernel times.  Stages run for the whole batch, one after another.
+// Selection + directory update for units [u0, u1): one fused kernel when the sizes allow the
+// register-resident path, else the two size-agnostic kernels.
+static hipError_t launch_select_resolve(kvd_ctx* c, int layer, int step, int u0, int u1, hipStream_t s) {
+  if (kvd_fast_path_ok(c))
+    return kvd_launch_select_resolve(c, layer, step, true, true, c->d_scores, c->d_sel_pages, c->d_sel_slots,
+                                     c->d_hit_mask, c->d_evicted, c->d_counts, u0, u1, s);
+  hipError_t e = kvd_launch_select(c, c->d_scores, c->d_sel_pages, u0, u1, s);
+  if (e != hipSuccess) return e;
+  return kvd_launch_resolve(c, layer, step, c->d_sel_pages, c->d_sel_slots, c->d_hit_mask, c->d_evicted, c->d_counts,
+                            u0, u1, s);
+}
+
+// One layer-step with every stage bracketed by HIP events on the caller's stream; waits for the
+// step and accumulates the per-stage times.  Stages run for the whole batch, one after another.
 static int step_profiled(kvd_ctx* c, int layer, int step, const void* q, float* out, float* lse, hipStream_t s) {
   hipEvent_t* ev = c->ev_prof;
   HIP_TRY(c, hipEventRecord(ev[0], s));
   HIP_TRY(c, kvd_launch_score(c, layer, q, c->d_scores, 0, c->U, s));
   HIP_TRY(c, hipEventRecord(ev[1], s));
-  HIP_TRY(c, kvd_launch_select(c, c->d_scores, c->d_sel_pages, 0, c->U, s));
+  HIP_TRY(c, launch_select_resolve(c, layer, step, 0, c->U, s));
   HIP_TRY(c, hipEventRecord(ev[2], s));
-  HIP_TRY(c, kvd_launch_resolve(c, layer, step, c->d_sel_pages, c->d_sel_slots, c->d_hit_mask, c->d_evicted,
-                                c->d_counts, 0, c->U, s));
+  HIP_TRY(c, kvd_launch_gather(c, layer, 0, c->U, s));
   HIP_TRY(c, hipEventRecord(ev[3], s));
-  HIP_TRY(c, hipStreamWaitEvent(c->side, ev[3], 0));
-  HIP_TRY(c, hipEventRecord(ev[4], c->side));
-  HIP_TRY(c, kvd_launch_gather(c, layer, 0, c->U, c->side));
-  HIP_TRY(c, hipEventRecord(ev[5], c->side));
-  HIP_TRY(c, hipStreamWaitEvent(s, ev[5], 0));
-  HIP_TRY(c, hipEventRecord(ev[6], s));
   HIP_TRY(c, kvd_launch_attend(c, layer, q, c->d_sel_pages, c->d_sel_slots, out, lse, s));
-  HIP_TRY(c, hipEventRecord(ev[7], s));
-  HIP_TRY(c, hipEventSynchronize(ev[7]));
+  HIP_TRY(c, hipEventRecord(ev[4], s));
+  HIP_TRY(c, hipEventSynchronize(ev[4]));
   float ms = 0.f;
   HIP_TRY(c, hipEventElapsedTime(&ms, ev[0], ev[1])); c->ms_score += ms;
-  HIP_TRY(c, hipEventElapsedTime(&ms, ev[1], ev[2])); c->ms_select += ms;
-  HIP_TRY(c, hipEventElapsedTime(&ms, ev[2], ev[3])); c->ms_resolve += ms;
-  HIP_TRY(c, hipEventElapsedTime(&ms, ev[4], ev[5])); c->ms_gather += ms;
-  HIP_TRY(c, hipEventElapsedTime(&ms, ev[6], ev[7])); c->ms_attend += ms;
-  HIP_TRY(c, hipEventElapsedTime(&ms, ev[0], ev[7])); c->ms_total += ms;
+  HIP_TRY(c, hipEventElapsedTime(&ms, ev[1], ev[2])); c->ms_select_resolve += ms;
+  HIP_TRY(c, hipEventElapsedTime(&ms, ev[2], ev[3])); c->ms_gather += ms;
+  HIP_TRY(c, hipEventElapsedTime(&ms, ev[3], ev[4])); c->ms_attend += ms;
+  HIP_TRY(c, hipEventElapsedTime(&ms, ev[0], ev[4])); c->ms_total += ms;
   ++c->profiled_steps;
   return KVD_OK;
 }
@@ -371,13 +381,20 @@ int kvd_step(kvd_ctx* ctx, int32_t layer, int32_t step, const void* q, float* ou
   hipStream_t s = static_cast<hipStream_t>(stream);
   ++c->n_steps;
   if (c->profiling) return step_profiled(c, layer, step, q, out, lse, s);
+  if (c->MB <= 1) {
+    // nothing to overlap the fetch with: one stream, no events
+    HIP_TRY(c, kvd_launch_score(c, layer, q, c->d_scores, 0, c->U, s));
+    HIP_TRY(c, launch_select_resolve(c, layer, step, 0, c->U, s));
+    HIP_TRY(c, kvd_launch_gather(c, layer, 0, c->U, s));
+    HIP_TRY(c, kvd_launch_attend(c, layer, q, c->d_sel_pages, c->d_sel_slots, out, lse, s));
+    return KVD_OK;
+  }
+  // micro-batches: the fetch of group i runs on the side stream while group i+1 is selected
   for (int i = 0; i < c->MB; ++i) {
     const int u0 = (int)(((long long)i * c->B) / c->MB) * c->Hkv;
     const int u1 = (int)(((long long)(i + 1) * c->B) / c->MB) * c->Hkv;
     HIP_TRY(c, kvd_launch_score(c, layer, q, c->d_scores, u0, u1, s));
-    HIP_TRY(c, kvd_launch_select(c, c->d_scores, c->d_sel_pages, u0, u1, s));
-    HIP_TRY(c, kvd_launch_resolve(c, layer, step, c->d_sel_pages, c->d_sel_slots, c->d_hit_mask, c->d_evicted,
-                                  c->d_counts, u0, u1, s));
+    HIP_TRY(c, launch_select_resolve(c, layer, step, u0, u1, s));
     HIP_TRY(c, hipEventRecord(c->ev_sel[i], s));
     HIP_TRY(c, hipStreamWaitEvent(c->side, c->ev_sel[i], 0));
     HIP_TRY(c, kvd_launch_gather(c, layer, u0, u1, c->side));
@@ -422,8 +439,7 @@ int kvd_get_stats(kvd_ctx* ctx, kvd_stats* host_out) {
   host_out->evictions = raw[2];
   host_out->gathered_bytes = raw[1] * (uint64_t)ctx->page_bytes;
   host_out->ms_score = ctx->ms_score;
-  host_out->ms_select = ctx->ms_select;
-  host_out->ms_resolve = ctx->ms_resolve;
+  host_out->ms_select_resolve = ctx->ms_select_resolve;
   host_out->ms_gather = ctx->ms_gather;
   host_out->ms_attend = ctx->ms_attend;
   host_out->ms_total = ctx->ms_total;
@@ -436,7 +452,7 @@ int kvd_reset_stats(kvd_ctx* ctx) {
   HIP_TRY(ctx, hipDeviceSynchronize());
   HIP_TRY(ctx, hipMemset(ctx->d_stats, 0, 4 * sizeof(unsigned long long)));
   ctx->n_steps = 0;
-  ctx->ms_score = ctx->ms_select = ctx->ms_resolve = ctx->ms_gather = ctx->ms_attend = ctx->ms_total = 0.0;
+  ctx->ms_score = ctx->ms_select_resolve = ctx->ms_gather = ctx->ms_attend = ctx->ms_total = 0.0;
   ctx->profiled_steps = 0;
   return KVD_OK;
 }

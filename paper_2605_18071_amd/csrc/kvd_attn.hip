@@ -32,7 +32,7 @@ struct AttnArgs {
   int32_t* ticket;           // [U], zero between launches
   float* out;                // [B][Hq][D]
   float* lse;                // [B][Hq] or null
-  int k, P, Cmax, Hq, Hkv, S, per_split;
+  int k, P, Cmax, Hq, Hkv, S, per_split, fuse_merge;
   unsigned page_bytes;
   float scale_log2;          // softmax scale * log2(e)
 };
@@ -44,6 +44,32 @@ struct AttnSmem {
   float l[kAttnWaves][G];
   int is_last;
 };
+
+// Log-sum-exp merge of the S split partials of unit u into out / lse, by one block.
+template <int G>
+__device__ __forceinline__ void merge_splits(const AttnArgs& a, int u) {
+  const int tid = threadIdx.x;
+  const int b = u / a.Hkv, h = u % a.Hkv;
+  for (int idx = tid; idx < G * kHeadDim; idx += kAttnThreads) {
+    const int g = idx / kHeadDim, d = idx % kHeadDim;
+    const float* ml = a.part_ml + ((size_t)u * a.S * G + g) * 2;
+    const float* pa = a.part_acc + ((size_t)u * a.S * G + g) * kHeadDim + d;
+    float M = -INFINITY;
+#pragma unroll 8
+    for (int s = 0; s < a.S; ++s) M = fmaxf(M, ml[(size_t)s * G * 2]);
+    const float Ms = M == -INFINITY ? 0.f : M;
+    float L = 0.f, A = 0.f;
+#pragma unroll 8
+    for (int s = 0; s < a.S; ++s) {
+      const float sc = exp2f(ml[(size_t)s * G * 2] - Ms);
+      L += ml[(size_t)s * G * 2 + 1] * sc;
+      A += pa[(size_t)s * G * kHeadDim] * sc;
+    }
+    const size_t row = (size_t)b * a.Hq + (size_t)h * G + g;
+    a.out[row * kHeadDim + d] = A / L;
+    if (a.lse != nullptr && d == 0) a.lse[row] = (M + log2f(L)) * kLn2;
+  }
+}
 
 // Block epilogue.  The waves have left their (max, sum, acc) in `sm`; merge them, write this
 // split's partial, and let the last split of the unit to arrive merge all S partials.
@@ -78,7 +104,7 @@ __device__ __forceinline__ void finish_split(const AttnArgs& a, AttnSmem<G>& sm,
       }
     }
   }
-  if (a.S == 1) return;
+  if (a.S == 1 || !a.fuse_merge) return;
   __threadfence();                                   // partials visible device-wide before the ticket
   __syncthreads();
   if (tid == 0) {
@@ -89,24 +115,12 @@ __device__ __forceinline__ void finish_split(const AttnArgs& a, AttnSmem<G>& sm,
   __syncthreads();
   if (!sm.is_last) return;
   __threadfence();
-  for (int idx = tid; idx < G * kHeadDim; idx += kAttnThreads) {
-    const int g = idx / kHeadDim, d = idx % kHeadDim;
-    const float* ml = a.part_ml + ((size_t)u * a.S * G + g) * 2;
-    const float* pa = a.part_acc + ((size_t)u * a.S * G + g) * kHeadDim + d;
-    float M = -INFINITY;
-    for (int s = 0; s < a.S; ++s) M = fmaxf(M, ml[(size_t)s * G * 2]);
-    const float Ms = M == -INFINITY ? 0.f : M;
-    float L = 0.f, A = 0.f;
-#pragma unroll 4
-    for (int s = 0; s < a.S; ++s) {
-      const float sc = exp2f(ml[(size_t)s * G * 2] - Ms);
-      L += ml[(size_t)s * G * 2 + 1] * sc;
-      A += pa[(size_t)s * G * kHeadDim] * sc;
-    }
-    const size_t row = (size_t)b * a.Hq + (size_t)h * G + g;
-    a.out[row * kHeadDim + d] = A / L;
-    if (a.lse != nullptr && d == 0) a.lse[row] = (M + log2f(L)) * kLn2;
-  }
+  merge_splits<G>(a, u);
+}
+
+template <int G>
+__global__ __launch_bounds__(kAttnThreads) void combine_kernel(AttnArgs a) {
+  merge_splits<G>(a, blockIdx.x);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -407,6 +421,8 @@ static void launch_attend(bool tiled, const AttnArgs& a, dim3 grid, hipStream_t 
     hipLaunchKernelGGL((attend_mfma_kernel<BF16, G>), grid, dim3(kAttnThreads), 0, s, a);
   else
     hipLaunchKernelGGL((attend_valu_kernel<BF16, G>), grid, dim3(kAttnThreads), 0, s, a);
+  if (a.S > 1 && !a.fuse_merge)
+    hipLaunchKernelGGL((combine_kernel<G>), dim3(grid.y), dim3(kAttnThreads), 0, s, a);
 }
 
 template <bool BF16>
@@ -442,6 +458,7 @@ hipError_t kvd_launch_attend(kvd_ctx* c, int layer, const void* q, const int32_t
   a.lse = lse;
   a.k = c->k; a.P = c->P; a.Cmax = c->Cmax; a.Hq = c->Hq; a.Hkv = c->Hkv; a.S = c->S;
   a.per_split = (c->k + c->S - 1) / c->S;
+  a.fuse_merge = c->fuse_merge;
   a.page_bytes = (unsigned)c->page_bytes;
   a.scale_log2 = c->scale * kLog2e;
   dim3 grid(c->S, c->U);

@@ -1,0 +1,427 @@
+// Stages 1b and 2a of the decode step in one launch: exact Top-K selection of the scored pages
+// (Background: "retrieving only the Top-K") followed by the cache-directory update for the same
+// unit (Attention-Based Cache Management with LRU replacement), one block of 1024 threads per
+// unit.  Both are "the n smallest of distinct 64-bit keys" problems and share one two-level
+// routine: an LDS histogram over a monotone bucket function narrows the answer to one bucket,
+// whose few members are ranked exactly.  The items stay in registers; only a bucket with more
+// than 1024 members (degenerate inputs, e.g. all scores equal) falls back to radix refinement.
+#include "kvd_device.h"
+#include "kvd_internal.h"
+
+namespace kvd {
+
+constexpr int kFastThreads = 1024;
+constexpr int kFastSlotsPerThread = KVD_FAST_MAX_CAPACITY / kFastThreads;   // 4
+constexpr int kFastSelPerThread = KVD_MAX_TOPK / kFastThreads;              // 2
+constexpr int kListCap = 1024;
+
+struct FastArgs {
+  const float* scores;        // [U][NP]
+  const int32_t* seq_len;     // [B]
+  int32_t* sel_pages;         // [U][k]: written by the selection, read when only resolving
+  const int32_t* capacity;    // [U] of the layer
+  int32_t* resident;          // [U]
+  int32_t* page_to_slot;      // [U][NP]
+  int32_t* slot_page;         // [U][Cmax]
+  int32_t* slot_stamp;        // [U][Cmax]
+  int32_t* sel_slots;         // [U][k]
+  int32_t* hit_mask;          // [U][k]
+  int32_t* evicted;           // [U][k]
+  int32_t* counts;            // [U][3]
+  int32_t* miss_list;         // [U][k][2]
+  int32_t* miss_count;        // [U]
+  unsigned long long* stats;  // hits, misses, evictions
+  int NP, P, k, Cmax, sink, recent, Hkv, step, u0;
+};
+
+struct FastSmem {
+  u32 hist[kRadixBins];
+  u64 cand[kListCap];
+  int scan[32];
+  float red_min[16], red_max[16];
+  int red_cnt[16];
+  u64 thr;
+  int cand_n, bin, below, n_hits, n_ev;
+  int32_t sel[KVD_MAX_TOPK];
+  int32_t assign[KVD_MAX_TOPK];
+  u32 hit_bitmap[KVD_FAST_MAX_CAPACITY / 32];
+  SelectSmem generic;
+};
+
+__device__ __forceinline__ u32 fast_descending_key(float s) {
+  const u32 x = as_u32(s + 0.0f);                    // -0 -> +0 so that the two zeros tie
+  const u32 asc = (x & 0x80000000u) ? ~x : (x | 0x80000000u);
+  return ~asc;
+}
+
+// Items j = 0..IPT-1 of every thread: bkt[j] in [0, 2047], or -1 for "not a candidate"; key[j]
+// distinct; key1 < key2 implies bkt1 <= bkt2.  Returns the need-th smallest key among the
+// candidates (1 <= need <= number of candidates).  `refine(bin, r)` is called by all threads when
+// the decisive bucket holds more than kListCap items and must return the r-th smallest key of
+// that bucket.  Ends with the block synchronised.
+template <int NT, int IPT, class Refine>
+__device__ __forceinline__ u64 two_level_select(const u64 (&key)[IPT], const int (&bkt)[IPT], int need, FastSmem& sm,
+                                                Refine refine) {
+  const int tid = threadIdx.x;
+  for (int i = tid; i < kRadixBins; i += NT) sm.hist[i] = 0;
+  if (tid == 0) sm.cand_n = 0;
+  __syncthreads();
+#pragma unroll
+  for (int j = 0; j < IPT; ++j)
+    if (bkt[j] >= 0) atomicAdd(&sm.hist[bkt[j]], 1u);
+  __syncthreads();
+  constexpr int BPT = kRadixBins / NT;
+  int local = 0;
+#pragma unroll
+  for (int j = 0; j < BPT; ++j) local += (int)sm.hist[tid * BPT + j];
+  int total;
+  int ex = block_exclusive_scan<NT>(local, sm.scan, total);
+  if (ex < need && need <= ex + local) {             // exactly one thread
+    int b = tid * BPT;
+    for (int j = 0; j < BPT; ++j, ++b) {
+      const int c = (int)sm.hist[b];
+      if (need <= ex + c) break;
+      ex += c;
+    }
+    sm.bin = b;
+    sm.below = ex;
+  }
+  __syncthreads();
+  const int bin = sm.bin;
+  const int r = need - sm.below;
+  const int m = (int)sm.hist[bin];
+  if (m > kListCap) return refine(bin, r);
+#pragma unroll
+  for (int j = 0; j < IPT; ++j)
+    if (bkt[j] == bin) sm.cand[atomicAdd(&sm.cand_n, 1)] = key[j];
+  __syncthreads();
+  for (int c = tid; c < m; c += NT) {
+    const u64 mine = sm.cand[c];
+    int rank = 0;
+    for (int x = 0; x < m; ++x) rank += sm.cand[x] < mine ? 1 : 0;
+    if (rank == r - 1) sm.thr = mine;
+  }
+  __syncthreads();
+  return sm.thr;
+}
+
+// One block per unit.  DO_SELECT: scores -> sel_pages (Top-K, ties to the lower page, sink/recent
+// pages forced, ascending page order, -1 padding).  DO_RESOLVE: sel_pages -> directory update,
+// slots, hit mask, evicted list, counts and the (page, slot) miss list for the fetch.
+template <int IPT, bool DO_SELECT, bool DO_RESOLVE>
+__global__ __launch_bounds__(kFastThreads) void select_resolve_kernel(FastArgs a) {
+  __shared__ FastSmem sm;
+  constexpr int NT = kFastThreads;
+  constexpr int CPT = kFastSlotsPerThread;
+  constexpr int KPT = kFastSelPerThread;
+  const int tid = threadIdx.x, lane = tid & (kWave - 1), w = tid / kWave;
+  const int u = blockIdx.x + a.u0;
+  const int b = u / a.Hkv;
+  const int k = a.k;
+
+  // ---- the directory slots this thread owns, fetched early so that the loads overlap the selection
+  int C = 0, R = 0;
+  int sp[CPT], ss[CPT];                               // page in slot (-1 free, -2 no such slot), stamp
+  int32_t* p2s = a.page_to_slot + (size_t)u * a.NP;
+  int32_t* spage = a.slot_page + (size_t)u * a.Cmax;
+  int32_t* sstamp = a.slot_stamp + (size_t)u * a.Cmax;
+  if (DO_RESOLVE) {
+    C = a.capacity[u];
+    R = a.resident[u];
+#pragma unroll
+    for (int j = 0; j < CPT; ++j) {
+      const int s = tid * CPT + j;
+      sp[j] = s < C ? spage[s] : -2;
+      ss[j] = s < C ? sstamp[s] : 0;
+    }
+  }
+
+  // ---- selection
+  if (DO_SELECT) {
+    int n_valid = (a.seq_len[b] + a.P - 1) / a.P;
+    n_valid = n_valid < a.NP ? n_valid : a.NP;
+    const int k_eff = k < n_valid ? k : n_valid;
+    const float* sc = a.scores + (size_t)u * a.NP;
+    const int p0 = tid * IPT;
+    const int recent_from = n_valid - a.recent;
+    float s[IPT];
+    if ((a.NP & 3) == 0) {
+#pragma unroll
+      for (int q4 = 0; q4 < IPT / 4; ++q4) {
+        float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (p0 + 4 * q4 < a.NP) v = *reinterpret_cast<const float4*>(sc + p0 + 4 * q4);
+        s[4 * q4] = v.x; s[4 * q4 + 1] = v.y; s[4 * q4 + 2] = v.z; s[4 * q4 + 3] = v.w;
+      }
+    } else {
+#pragma unroll
+      for (int j = 0; j < IPT; ++j) s[j] = (p0 + j) < a.NP ? sc[p0 + j] : 0.f;
+    }
+    float fmin = INFINITY, fmax = -INFINITY;
+    int n_forced = 0;
+#pragma unroll
+    for (int j = 0; j < IPT; ++j) {
+      const int p = p0 + j;
+      const bool valid = p < n_valid;
+      const bool forced = valid && (p < a.sink || p >= recent_from);
+      if (valid && !forced) {
+        fmin = fminf(fmin, s[j]);
+        fmax = fmaxf(fmax, s[j]);
+      }
+      n_forced += forced ? 1 : 0;
+    }
+#pragma unroll
+    for (int msk = 32; msk >= 1; msk >>= 1) {
+      fmin = fminf(fmin, __shfl_xor(fmin, msk, kWave));
+      fmax = fmaxf(fmax, __shfl_xor(fmax, msk, kWave));
+      n_forced += __shfl_xor(n_forced, msk, kWave);
+    }
+    if (lane == 0) { sm.red_min[w] = fmin; sm.red_max[w] = fmax; sm.red_cnt[w] = n_forced; }
+    __syncthreads();
+    fmin = sm.red_min[0]; fmax = sm.red_max[0]; n_forced = sm.red_cnt[0];
+#pragma unroll
+    for (int i = 1; i < NT / kWave; ++i) {
+      fmin = fminf(fmin, sm.red_min[i]);
+      fmax = fmaxf(fmax, sm.red_max[i]);
+      n_forced += sm.red_cnt[i];
+    }
+    const int k_free = k_eff - n_forced;
+    const float range = fmax - fmin;
+    const float inv = range > 0.f ? 2047.0f / range : 0.f;
+    auto bucket_of = [&](float v) -> int { return (int)fminf(fmaxf((fmax - v) * inv, 0.f), 2047.f); };
+    u64 key[IPT];
+    int bkt[IPT];
+#pragma unroll
+    for (int j = 0; j < IPT; ++j) {
+      const int p = p0 + j;
+      const bool is_free = p < n_valid && !(p < a.sink || p >= recent_from);
+      bkt[j] = is_free ? bucket_of(s[j]) : -1;
+      key[j] = ((u64)fast_descending_key(s[j]) << 32) | (u32)p;
+    }
+    u64 thr = 0;
+    if (k_free > 0) {
+      auto refine = [&](int bin, int r) -> u64 {
+        auto fn = [&](int i, u64& kk) -> bool {
+          if (i < a.sink || i >= recent_from) return false;
+          const float v = sc[i];
+          if (bucket_of(v) != bin) return false;
+          kk = ((u64)fast_descending_key(v) << 32) | (u32)i;
+          return true;
+        };
+        return block_kth_smallest<NT>(fn, n_valid, r, sm.generic);
+      };
+      thr = two_level_select<NT, IPT>(key, bkt, k_free, sm, refine);
+    }
+    int cnt = 0;
+    bool take[IPT];
+#pragma unroll
+    for (int j = 0; j < IPT; ++j) {
+      const int p = p0 + j;
+      const bool valid = p < n_valid;
+      const bool forced = valid && (p < a.sink || p >= recent_from);
+      take[j] = forced || (bkt[j] >= 0 && k_free > 0 && key[j] <= thr);
+      cnt += take[j] ? 1 : 0;
+    }
+    int total;
+    int pos = block_exclusive_scan<NT>(cnt, sm.scan, total);
+    int32_t* out = a.sel_pages + (size_t)u * k;
+#pragma unroll
+    for (int j = 0; j < IPT; ++j) {
+      if (take[j]) {
+        if (pos < k) {
+          sm.sel[pos] = p0 + j;
+          out[pos] = p0 + j;
+        }
+        ++pos;
+      }
+    }
+    for (int i = k_eff + tid; i < k; i += NT) {
+      sm.sel[i] = -1;
+      out[i] = -1;
+    }
+  } else {
+    for (int i = tid; i < k; i += NT) sm.sel[i] = a.sel_pages[(size_t)u * k + i];
+  }
+  if (!DO_RESOLVE) return;
+
+  // ---- resolve
+  for (int i = tid; i < KVD_FAST_MAX_CAPACITY / 32; i += NT) sm.hit_bitmap[i] = 0;
+  for (int i = tid; i < k; i += NT) sm.assign[i] = -1;
+  if (tid == 0) { sm.n_hits = 0; sm.n_ev = 0; }
+  __syncthreads();
+  int32_t* sslots = a.sel_slots + (size_t)u * k;
+  int32_t* hmask = a.hit_mask + (size_t)u * k;
+  int32_t* evout = a.evicted + (size_t)u * k;
+  const int per = (k + NT - 1) / NT;                  // consecutive selected entries per thread (1 or 2)
+  const int i0 = tid * per;
+  int32_t my_page[KPT];
+  int my_misses = 0, my_hits = 0;
+#pragma unroll
+  for (int j = 0; j < KPT; ++j) {
+    my_page[j] = -2;
+    const int i = i0 + j;
+    if (j < per && i < k) {
+      const int p = sm.sel[i];
+      if (p < 0 || p >= a.NP) {                       // padding (or a page the caller made up)
+        sslots[i] = -1;
+        hmask[i] = 0;
+      } else {
+        const int s = p2s[p];
+        if (s >= 0 && s < C) {
+          sstamp[s] = a.step;
+          atomicOr(&sm.hit_bitmap[s >> 5], 1u << (s & 31));
+          sslots[i] = s;
+          hmask[i] = 1;
+          ++my_hits;
+        } else {
+          my_page[j] = p;
+          ++my_misses;
+        }
+      }
+    }
+  }
+  if (my_hits) atomicAdd(&sm.n_hits, my_hits);
+  int m;
+  int miss_rank = block_exclusive_scan<NT>(my_misses, sm.scan, m);
+  const int e = (R + m - C) > 0 ? (R + m - C) : 0;
+
+  // victims: the e smallest (stamp, page) among resident slots that were not hit.  Buckets: one
+  // group of 32 per age (step - stamp) below 64, split by page range; everything older shares
+  // bucket 0; the newest class (age <= 1) shares bucket 2047.
+  u64 vkey[CPT];
+  int vb[CPT];
+#pragma unroll
+  for (int j = 0; j < CPT; ++j) {
+    const int s = tid * CPT + j;
+    vb[j] = -1;
+    vkey[j] = ~0ull;
+    if (sp[j] >= 0 && !((sm.hit_bitmap[s >> 5] >> (s & 31)) & 1u)) {
+      const long long age = (long long)a.step - (long long)ss[j];
+      const int sub = (int)(((long long)sp[j] * 32) / a.NP);
+      vb[j] = age >= 64 ? 0 : (age <= 1 ? 2047 : (int)(2048 - 32 * age) + sub);
+      vkey[j] = ((u64)((u32)ss[j] ^ 0x80000000u) << 32) | (u32)sp[j];
+    }
+  }
+  u64 vthr = 0;
+  if (e > 0) {
+    auto refine = [&](int bin, int r) -> u64 {
+      auto fn = [&](int s, u64& kk) -> bool {
+        const int p = spage[s];
+        if (p < 0 || ((sm.hit_bitmap[s >> 5] >> (s & 31)) & 1u)) return false;
+        const int st = sstamp[s];
+        const long long age = (long long)a.step - (long long)st;
+        const int sub = (int)(((long long)p * 32) / a.NP);
+        const int bb = age >= 64 ? 0 : (age <= 1 ? 2047 : (int)(2048 - 32 * age) + sub);
+        if (bb != bin) return false;
+        kk = ((u64)((u32)st ^ 0x80000000u) << 32) | (u32)p;
+        return true;
+      };
+      return block_kth_smallest<NT>(fn, C, r, sm.generic);
+    };
+    vthr = two_level_select<NT, CPT>(vkey, vb, e, sm, refine);
+  }
+
+  // hand out slots: free slots and victim slots in ascending slot order go to the misses in
+  // ascending page order
+  int avail = 0;
+  bool is_av[CPT], is_vic[CPT];
+#pragma unroll
+  for (int j = 0; j < CPT; ++j) {
+    is_vic[j] = e > 0 && vb[j] >= 0 && vkey[j] <= vthr;
+    is_av[j] = sp[j] == -1 || is_vic[j];
+    avail += is_av[j] ? 1 : 0;
+  }
+  int total_avail;
+  int rank = block_exclusive_scan<NT>(avail, sm.scan, total_avail);
+#pragma unroll
+  for (int j = 0; j < CPT; ++j) {
+    if (is_av[j]) {
+      if (rank < m) {
+        sm.assign[rank] = tid * CPT + j;
+        if (is_vic[j]) {
+          p2s[sp[j]] = -1;
+          const int at = atomicAdd(&sm.n_ev, 1);
+          if (at < k) evout[at] = sp[j];
+        }
+      }
+      ++rank;
+    }
+  }
+  __syncthreads();
+#pragma unroll
+  for (int j = 0; j < KPT; ++j) {
+    const int p = my_page[j];
+    if (p >= 0) {
+      const int i = i0 + j;
+      const int s = sm.assign[miss_rank];
+      sslots[i] = s;
+      hmask[i] = 0;
+      if (s >= 0) {                                    // always true while the directory is consistent
+        p2s[p] = s;
+        spage[s] = p;
+        sstamp[s] = a.step;
+      }
+      a.miss_list[((size_t)u * k + miss_rank) * 2] = p;
+      a.miss_list[((size_t)u * k + miss_rank) * 2 + 1] = s;
+      ++miss_rank;
+    }
+  }
+  for (int j = e + tid; j < k; j += NT) evout[j] = -1;
+  if (tid == 0) {
+    a.resident[u] = R + m - e;
+    a.miss_count[u] = m;
+    a.counts[u * 3 + 0] = sm.n_hits;
+    a.counts[u * 3 + 1] = m;
+    a.counts[u * 3 + 2] = e;
+    atomicAdd(&a.stats[0], (unsigned long long)sm.n_hits);
+    atomicAdd(&a.stats[1], (unsigned long long)m);
+    atomicAdd(&a.stats[2], (unsigned long long)e);
+  }
+}
+
+template <bool SEL, bool RES>
+static void launch_fast(int ipt, const FastArgs& a, int n_units, hipStream_t s) {
+  dim3 grid(n_units), block(kFastThreads);
+  if (ipt <= 4)
+    hipLaunchKernelGGL((select_resolve_kernel<4, SEL, RES>), grid, block, 0, s, a);
+  else if (ipt <= 8)
+    hipLaunchKernelGGL((select_resolve_kernel<8, SEL, RES>), grid, block, 0, s, a);
+  else
+    hipLaunchKernelGGL((select_resolve_kernel<16, SEL, RES>), grid, block, 0, s, a);
+}
+
+}  // namespace kvd
+
+bool kvd_fast_path_ok(const kvd_ctx* c) {
+  return !c->generic_select && c->NP <= KVD_FAST_MAX_PAGES && c->Cmax <= KVD_FAST_MAX_CAPACITY;
+}
+
+hipError_t kvd_launch_select_resolve(kvd_ctx* c, int layer, int step, bool do_select, bool do_resolve,
+                                     const float* scores, int32_t* sel_pages, int32_t* sel_slots, int32_t* hit_mask,
+                                     int32_t* evicted, int32_t* counts, int u0, int u1, hipStream_t s) {
+  using namespace kvd;
+  if (u1 <= u0) return hipSuccess;
+  FastArgs a;
+  const size_t lu = (size_t)layer * c->U;
+  a.scores = scores;
+  a.seq_len = c->d_seq_len;
+  a.sel_pages = sel_pages;
+  a.capacity = c->d_capacity + lu;
+  a.resident = c->d_resident + lu;
+  a.page_to_slot = c->d_page_to_slot + lu * c->NP;
+  a.slot_page = c->d_slot_page + lu * c->Cmax;
+  a.slot_stamp = c->d_slot_stamp + lu * c->Cmax;
+  a.sel_slots = sel_slots;
+  a.hit_mask = hit_mask;
+  a.evicted = evicted;
+  a.counts = counts;
+  a.miss_list = c->d_miss_list;
+  a.miss_count = c->d_miss_count;
+  a.stats = c->d_stats;
+  a.NP = c->NP; a.P = c->P; a.k = c->k; a.Cmax = c->Cmax;
+  a.sink = c->cfg.sink_pages; a.recent = c->cfg.recent_pages; a.Hkv = c->Hkv; a.step = step; a.u0 = u0;
+  const int ipt = (c->NP + kFastThreads - 1) / kFastThreads;
+  if (do_select && do_resolve) launch_fast<true, true>(ipt, a, u1 - u0, s);
+  else if (do_select) launch_fast<true, false>(ipt, a, u1 - u0, s);
+  else launch_fast<false, true>(4, a, u1 - u0, s);
+  return hipGetLastError();
+}

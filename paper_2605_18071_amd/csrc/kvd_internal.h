@@ -8,6 +8,8 @@
 constexpr int KVD_MAX_GROUP = 8;        // G = Hq / Hkv
 constexpr int KVD_MAX_TOPK = 2048;      // k
 constexpr int KVD_MAX_CAPACITY = 65536; // Cmax
+constexpr int KVD_FAST_MAX_PAGES = 16384;    // register-resident selection: 1024 threads x 16 pages
+constexpr int KVD_FAST_MAX_CAPACITY = 4096; // register-resident directory scan: 1024 threads x 4 slots
 constexpr int KVD_MAX_PAGE = 256;       // P
 constexpr int KVD_MAX_MICRO = 16;       // micro-batches per step
 constexpr int KVD_MAX_SPLITS = 64;      // attention split-K factor
@@ -16,6 +18,8 @@ struct kvd_ctx {
   kvd_config cfg;
   int L, B, Hq, Hkv, G, D, P, NP, k, Cmax, Lp, U, MB, S;
   int bf16;
+  int generic_select;      // force the size-agnostic select / resolve kernels (testing)
+  int fuse_merge;          // attention: last split block merges (1) or a second kernel does (0)
   int tiled;               // slots use the tile layout (page size a multiple of 16)
   float scale;
   size_t page_bytes;
@@ -55,7 +59,7 @@ struct kvd_ctx {
   int profiling;
   int last_hip;
   uint64_t n_steps;
-  double ms_score, ms_select, ms_resolve, ms_gather, ms_attend, ms_total;
+  double ms_score, ms_select_resolve, ms_gather, ms_attend, ms_total;
   uint64_t profiled_steps;
 };
 
@@ -64,6 +68,10 @@ hipError_t kvd_launch_score(kvd_ctx* c, int layer, const void* q, float* scores,
 hipError_t kvd_launch_select(kvd_ctx* c, const float* scores, int32_t* sel_pages, int u0, int u1, hipStream_t s);
 hipError_t kvd_launch_resolve(kvd_ctx* c, int layer, int step, const int32_t* sel_pages, int32_t* sel_slots,
                               int32_t* hit_mask, int32_t* evicted, int32_t* counts, int u0, int u1, hipStream_t s);
+bool kvd_fast_path_ok(const kvd_ctx* c);
+hipError_t kvd_launch_select_resolve(kvd_ctx* c, int layer, int step, bool do_select, bool do_resolve,
+                                     const float* scores, int32_t* sel_pages, int32_t* sel_slots, int32_t* hit_mask,
+                                     int32_t* evicted, int32_t* counts, int u0, int u1, hipStream_t s);
 hipError_t kvd_launch_gather(kvd_ctx* c, int layer, int u0, int u1, hipStream_t s);
 hipError_t kvd_launch_attend(kvd_ctx* c, int layer, const void* q, const int32_t* sel_pages,
                              const int32_t* sel_slots, float* out, float* lse, hipStream_t s);
