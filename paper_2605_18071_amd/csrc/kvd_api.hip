@@ -60,12 +60,14 @@ static void free_ctx(kvd_ctx* c) {
   for (void* p : dev)
     if (p) (void)hipFree(p);
   for (int i = 0; i < KVD_MAX_MICRO; ++i) {
-    if (c->ev_sel[i]) (void)hipEventDestroy(c->ev_sel[i]);
-    if (c->ev_fetch[i]) (void)hipEventDestroy(c->ev_fetch[i]);
+    if (c->ev_score[i]) (void)hipEventDestroy(c->ev_score[i]);
+    if (c->ev_done[i]) (void)hipEventDestroy(c->ev_done[i]);
   }
+  if (c->ev_fork) (void)hipEventDestroy(c->ev_fork);
   for (int i = 0; i < 12; ++i)
     if (c->ev_prof[i]) (void)hipEventDestroy(c->ev_prof[i]);
-  if (c->side) (void)hipStreamDestroy(c->side);
+  for (int i = 0; i < KVD_PIPE_STREAMS; ++i)
+    if (c->side[i]) (void)hipStreamDestroy(c->side[i]);
   free(c->h_capacity);
   free(c->h_seq_len);
   free(c);
@@ -131,8 +133,11 @@ int kvd_create(const kvd_config* cfg, kvd_ctx** out) {
   c->page_bytes = (size_t)2 * c->P * c->D * 2;
   int S = cfg->attn_splits;
   if (S == 0) {
-    S = (2048 + c->U - 1) / c->U;
-    const int cap = (c->k + 3) / 4;
+    // one round of resident blocks: 256 CUs x 2 blocks of 4 waves (the attention kernel runs at
+    // 2 waves per SIMD); every block keeps at least 8 tiles of 16 tokens
+    S = (512 + c->U / 2) / c->U;
+    const int tiles = c->k * ((c->P + 15) / 16);
+    const int cap = (tiles + 7) / 8;
     if (S > cap) S = cap;
     if (S > KVD_MAX_SPLITS) S = KVD_MAX_SPLITS;
     if (S < 1) S = 1;
@@ -160,10 +165,12 @@ int kvd_create(const kvd_config* cfg, kvd_ctx** out) {
       ok(dev_alloc(&c->d_part_acc, (size_t)c->U * c->S * c->G * c->D)) &&
       ok(dev_alloc(&c->d_part_ml, (size_t)c->U * c->S * c->G * 2)) && ok(dev_alloc(&c->d_stats, 4)) &&
       ok(dev_alloc(&c->d_attn_ticket, (size_t)c->U)) &&
-      ok(hipStreamCreateWithFlags(&c->side, hipStreamNonBlocking));
+      ok(hipEventCreateWithFlags(&c->ev_fork, hipEventDisableTiming));
+  for (int i = 0; i < KVD_PIPE_STREAMS && c->MB > 1 && e == hipSuccess; ++i)
+    ok(hipStreamCreateWithFlags(&c->side[i], hipStreamNonBlocking));
   for (int i = 0; i < c->MB && e == hipSuccess; ++i) {
-    ok(hipEventCreateWithFlags(&c->ev_sel[i], hipEventDisableTiming));
-    ok(hipEventCreateWithFlags(&c->ev_fetch[i], hipEventDisableTiming));
+    ok(hipEventCreateWithFlags(&c->ev_score[i], hipEventDisableTiming));
+    ok(hipEventCreateWithFlags(&c->ev_done[i], hipEventDisableTiming));
   }
   for (int i = 0; i < 12 && e == hipSuccess; ++i) ok(hipEventCreate(&c->ev_prof[i]));
   if (e == hipSuccess) ok(hipMemcpy(c->d_capacity, c->h_capacity, LU * sizeof(int32_t), hipMemcpyHostToDevice));
@@ -334,7 +341,7 @@ int kvd_sparse_decode_attn(kvd_ctx* ctx, int32_t layer, const void* q, const int
   if (!ctx || !q || !sel_pages || !sel_slots || !out || layer < 0 || layer >= ctx->L || !aligned16(q))
     return KVD_ERR_ARG;
   if (!ctx->pool) return KVD_ERR_STATE;
-  HIP_TRY(ctx, kvd_launch_attend(ctx, layer, q, sel_pages, sel_slots, out, lse, static_cast<hipStream_t>(stream)));
+  HIP_TRY(ctx, kvd_launch_attend(ctx, layer, q, sel_pages, sel_slots, out, lse, 0, ctx->U, static_cast<hipStream_t>(stream)));
   return KVD_OK;
 }
 
@@ -361,7 +368,7 @@ static int step_profiled(kvd_ctx* c, int layer, int step, const void* q, float* 
   HIP_TRY(c, hipEventRecord(ev[2], s));
   HIP_TRY(c, kvd_launch_gather(c, layer, 0, c->U, s));
   HIP_TRY(c, hipEventRecord(ev[3], s));
-  HIP_TRY(c, kvd_launch_attend(c, layer, q, c->d_sel_pages, c->d_sel_slots, out, lse, s));
+  HIP_TRY(c, kvd_launch_attend(c, layer, q, c->d_sel_pages, c->d_sel_slots, out, lse, 0, c->U, s));
   HIP_TRY(c, hipEventRecord(ev[4], s));
   HIP_TRY(c, hipEventSynchronize(ev[4]));
   float ms = 0.f;
@@ -382,26 +389,33 @@ int kvd_step(kvd_ctx* ctx, int32_t layer, int32_t step, const void* q, float* ou
   ++c->n_steps;
   if (c->profiling) return step_profiled(c, layer, step, q, out, lse, s);
   if (c->MB <= 1) {
-    // nothing to overlap the fetch with: one stream, no events
     HIP_TRY(c, kvd_launch_score(c, layer, q, c->d_scores, 0, c->U, s));
     HIP_TRY(c, launch_select_resolve(c, layer, step, 0, c->U, s));
     HIP_TRY(c, kvd_launch_gather(c, layer, 0, c->U, s));
-    HIP_TRY(c, kvd_launch_attend(c, layer, q, c->d_sel_pages, c->d_sel_slots, out, lse, s));
+    HIP_TRY(c, kvd_launch_attend(c, layer, q, c->d_sel_pages, c->d_sel_slots, out, lse, 0, c->U, s));
     return KVD_OK;
   }
-  // micro-batches: the fetch of group i runs on the side stream while group i+1 is selected
+  // Micro-batches (SFC Disaggregation): group i of the sequences runs select -> fetch -> attend as
+  // its own chain on pipeline stream i % (1 + KVD_PIPE_STREAMS) (stream 0 is the caller's), so the
+  // latency-bound selection and the host-link fetch of one group overlap the bandwidth-bound
+  // kernels of the others.  Scoring is chained group to group so that the groups start staggered.
+  HIP_TRY(c, hipEventRecord(c->ev_fork, s));
+  for (int i = 0; i < KVD_PIPE_STREAMS; ++i) HIP_TRY(c, hipStreamWaitEvent(c->side[i], c->ev_fork, 0));
   for (int i = 0; i < c->MB; ++i) {
     const int u0 = (int)(((long long)i * c->B) / c->MB) * c->Hkv;
     const int u1 = (int)(((long long)(i + 1) * c->B) / c->MB) * c->Hkv;
-    HIP_TRY(c, kvd_launch_score(c, layer, q, c->d_scores, u0, u1, s));
-    HIP_TRY(c, launch_select_resolve(c, layer, step, u0, u1, s));
-    HIP_TRY(c, hipEventRecord(c->ev_sel[i], s));
-    HIP_TRY(c, hipStreamWaitEvent(c->side, c->ev_sel[i], 0));
-    HIP_TRY(c, kvd_launch_gather(c, layer, u0, u1, c->side));
-    HIP_TRY(c, hipEventRecord(c->ev_fetch[i], c->side));
+    const int lane = i % (1 + KVD_PIPE_STREAMS);
+    hipStream_t st = lane == 0 ? s : c->side[lane - 1];
+    if (i > 0) HIP_TRY(c, hipStreamWaitEvent(st, c->ev_score[i - 1], 0));
+    HIP_TRY(c, kvd_launch_score(c, layer, q, c->d_scores, u0, u1, st));
+    HIP_TRY(c, hipEventRecord(c->ev_score[i], st));
+    HIP_TRY(c, launch_select_resolve(c, layer, step, u0, u1, st));
+    HIP_TRY(c, kvd_launch_gather(c, layer, u0, u1, st));
+    HIP_TRY(c, kvd_launch_attend(c, layer, q, c->d_sel_pages, c->d_sel_slots, out, lse, u0, u1, st));
+    if (lane != 0) HIP_TRY(c, hipEventRecord(c->ev_done[i], st));
   }
-  for (int i = 0; i < c->MB; ++i) HIP_TRY(c, hipStreamWaitEvent(s, c->ev_fetch[i], 0));
-  HIP_TRY(c, kvd_launch_attend(c, layer, q, c->d_sel_pages, c->d_sel_slots, out, lse, s));
+  for (int i = 0; i < c->MB; ++i)
+    if (i % (1 + KVD_PIPE_STREAMS) != 0) HIP_TRY(c, hipStreamWaitEvent(s, c->ev_done[i], 0));
   return KVD_OK;
 }
 

@@ -18,6 +18,7 @@ namespace kvd {
 
 constexpr int kAttnThreads = 256;
 constexpr int kAttnWaves = kAttnThreads / kWave;
+constexpr int kAttnIdxCap = 512;          // (page, slot) entries of a split kept in LDS
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLn2 = 0.6931471805599453f;
 
@@ -32,7 +33,7 @@ struct AttnArgs {
   int32_t* ticket;           // [U], zero between launches
   float* out;                // [B][Hq][D]
   float* lse;                // [B][Hq] or null
-  int k, P, Cmax, Hq, Hkv, S, per_split, fuse_merge;
+  int k, P, Cmax, Hq, Hkv, S, per_split, fuse_merge, u0;
   unsigned page_bytes;
   float scale_log2;          // softmax scale * log2(e)
 };
@@ -120,7 +121,7 @@ __device__ __forceinline__ void finish_split(const AttnArgs& a, AttnSmem<G>& sm,
 
 template <int G>
 __global__ __launch_bounds__(kAttnThreads) void combine_kernel(AttnArgs a) {
-  merge_splits<G>(a, blockIdx.x);
+  merge_splits<G>(a, blockIdx.x + a.u0);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -159,7 +160,8 @@ __device__ __forceinline__ f32x4 mfma_pv(const uint2& vfrag, const uint2& pfrag,
 template <bool BF16, int G>
 __global__ __launch_bounds__(kAttnThreads) void attend_mfma_kernel(AttnArgs a) {
   __shared__ AttnSmem<G> sm;
-  const int split = blockIdx.x, u = blockIdx.y;
+  __shared__ int32_t sh_page[kAttnIdxCap], sh_slot[kAttnIdxCap];
+  const int split = blockIdx.x, u = blockIdx.y + a.u0;
   const int b = u / a.Hkv, h = u % a.Hkv;
   const int tid = threadIdx.x, lane = tid & (kWave - 1), w = tid / kWave;
   const int j = lane & 15, g = lane >> 4;
@@ -188,38 +190,44 @@ __global__ __launch_bounds__(kAttnThreads) void attend_mfma_kernel(AttnArgs a) {
   const int32_t* slots = a.sel_slots + (size_t)u * a.k;
   const char* pool_u = a.pool + (size_t)u * a.Cmax * a.page_bytes;
 
-  // software pipeline: operands of the next tile are in flight while this one is computed
-  uint4 kn[4], vn[4];
-  int ntok_n = 0;
-  auto issue = [&](int t) {
-    ntok_n = 0;
+  // the split's (page, slot) entries go to LDS once, so that issuing a tile's loads never waits on
+  // a global index load
+  const int n_entries = last - first;
+  const bool idx_in_lds = n_entries <= kAttnIdxCap;
+  if (idx_in_lds) {
+    for (int i = tid; i < n_entries; i += kAttnThreads) {
+      sh_page[i] = sel[first + i];
+      sh_slot[i] = slots[first + i];
+    }
+  }
+  __syncthreads();
+
+  // software pipeline: three tile buffers rotate, so the operands of the next two tiles of this
+  // wave (16 KiB) are in flight while one tile is computed
+  struct Tile { uint4 k[4], v[4]; int ntok; };
+  auto issue = [&](Tile& tl, int t) {
+    tl.ntok = 0;
     if (t >= n_tiles) return;
-    const int e = first + t / tiles_per_page, tile = t % tiles_per_page;
-    const int page = __builtin_amdgcn_readfirstlane(sel[e]);
-    const int slot = __builtin_amdgcn_readfirstlane(slots[e]);
+    const int e = t / tiles_per_page, tile = t % tiles_per_page;
+    const int page = __builtin_amdgcn_readfirstlane(idx_in_lds ? sh_page[e] : sel[first + e]);
+    const int slot = __builtin_amdgcn_readfirstlane(idx_in_lds ? sh_slot[e] : slots[first + e]);
     if (page < 0 || slot < 0 || slot >= a.Cmax) return;
     int ntok = seq - page * a.P - tile * 16;
     ntok = ntok < 16 ? ntok : 16;
     if (ntok <= 0) return;
-    ntok_n = ntok;
+    tl.ntok = ntok;
     const uint4* tb = reinterpret_cast<const uint4*>(pool_u + (size_t)slot * a.page_bytes + (size_t)tile * kTileBytes) + lane;
 #pragma unroll
-    for (int c = 0; c < 4; ++c) kn[c] = tb[c * 64];
+    for (int c = 0; c < 4; ++c) tl.k[c] = load_stream16(tb + c * 64);
 #pragma unroll
-    for (int c = 0; c < 4; ++c) vn[c] = tb[256 + c * 64];
+    for (int c = 0; c < 4; ++c) tl.v[c] = load_stream16(tb + 256 + c * 64);
   };
-  issue(w);
-  for (int t = w; t < n_tiles; t += kAttnWaves) {
-    uint4 kc[4], vc[4];
-#pragma unroll
-    for (int c = 0; c < 4; ++c) { kc[c] = kn[c]; vc[c] = vn[c]; }
-    const int ntok = ntok_n;
-    issue(t + kAttnWaves);
-    if (ntok == 0) continue;
-
+  auto compute = [&](const Tile& tl) {
+    const int ntok = tl.ntok;
+    if (ntok == 0) return;
     f32x4 s = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-    for (int c = 0; c < 4; ++c) s = mfma_qk<BF16>(kc[c], qfrag[c], s);
+    for (int c = 0; c < 4; ++c) s = mfma_qk<BF16>(tl.k[c], qfrag[c], s);
     float x[4];
     float mx = -INFINITY;
 #pragma unroll
@@ -250,7 +258,7 @@ __global__ __launch_bounds__(kAttnThreads) void attend_mfma_kernel(AttnArgs a) {
       const uint2 ph = __builtin_bit_cast(uint2, hi), pl = __builtin_bit_cast(uint2, lo);
 #pragma unroll
       for (int c = 0; c < 4; ++c) {
-        const uint2 v0 = make_uint2(vc[c].x, vc[c].y), v1 = make_uint2(vc[c].z, vc[c].w);
+        const uint2 v0 = make_uint2(tl.v[c].x, tl.v[c].y), v1 = make_uint2(tl.v[c].z, tl.v[c].w);
         o[2 * c] = mfma_pv<true>(v0, ph, o[2 * c]);
         o[2 * c + 1] = mfma_pv<true>(v1, ph, o[2 * c + 1]);
         o[2 * c] = mfma_pv<true>(v0, pl, o[2 * c]);
@@ -261,11 +269,22 @@ __global__ __launch_bounds__(kAttnThreads) void attend_mfma_kernel(AttnArgs a) {
       const uint2 ph = __builtin_bit_cast(uint2, hp);
 #pragma unroll
       for (int c = 0; c < 4; ++c) {
-        const uint2 v0 = make_uint2(vc[c].x, vc[c].y), v1 = make_uint2(vc[c].z, vc[c].w);
+        const uint2 v0 = make_uint2(tl.v[c].x, tl.v[c].y), v1 = make_uint2(tl.v[c].z, tl.v[c].w);
         o[2 * c] = mfma_pv<false>(v0, ph, o[2 * c]);
         o[2 * c + 1] = mfma_pv<false>(v1, ph, o[2 * c + 1]);
       }
     }
+  };
+  Tile ta, tb2, tc;
+  issue(ta, w);
+  issue(tb2, w + kAttnWaves);
+  for (int t = w; t < n_tiles; t += 3 * kAttnWaves) {
+    issue(tc, t + 2 * kAttnWaves);
+    compute(ta);
+    issue(ta, t + 3 * kAttnWaves);
+    compute(tb2);
+    issue(tb2, t + 4 * kAttnWaves);
+    compute(tc);
   }
 
   // per-lane sums cover tokens 4g..4g+3 of every tile: add the four lane groups of a head
@@ -292,7 +311,7 @@ __global__ __launch_bounds__(kAttnThreads) void attend_mfma_kernel(AttnArgs a) {
 template <bool BF16, int G>
 __global__ __launch_bounds__(kAttnThreads) void attend_valu_kernel(AttnArgs a) {
   __shared__ AttnSmem<G> sm;
-  const int split = blockIdx.x, u = blockIdx.y;
+  const int split = blockIdx.x, u = blockIdx.y + a.u0;
   const int b = u / a.Hkv, h = u % a.Hkv;
   const int tid = threadIdx.x, lane = tid & (kWave - 1), w = tid / kWave;
   const int r = lane >> 4, c = lane & 15;
@@ -443,9 +462,11 @@ static bool dispatch_group(int G, bool tiled, const AttnArgs& a, dim3 grid, hipS
 }  // namespace kvd
 
 hipError_t kvd_launch_attend(kvd_ctx* c, int layer, const void* q, const int32_t* sel_pages,
-                             const int32_t* sel_slots, float* out, float* lse, hipStream_t s) {
+                             const int32_t* sel_slots, float* out, float* lse, int u0, int u1, hipStream_t s) {
   using namespace kvd;
+  if (u1 <= u0) return hipSuccess;
   AttnArgs a;
+  a.u0 = u0;
   a.q = reinterpret_cast<const uint16_t*>(q);
   a.pool = c->pool + (size_t)layer * c->U * c->Cmax * c->page_bytes;
   a.sel_pages = sel_pages;
@@ -461,7 +482,7 @@ hipError_t kvd_launch_attend(kvd_ctx* c, int layer, const void* q, const int32_t
   a.fuse_merge = c->fuse_merge;
   a.page_bytes = (unsigned)c->page_bytes;
   a.scale_log2 = c->scale * kLog2e;
-  dim3 grid(c->S, c->U);
+  dim3 grid(c->S, u1 - u0);
   const bool ok = c->bf16 ? dispatch_group<true>(c->G, c->tiled != 0, a, grid, s)
                           : dispatch_group<false>(c->G, c->tiled != 0, a, grid, s);
   if (!ok) return hipErrorInvalidValue;

@@ -17,6 +17,14 @@ constexpr int kRadixBins = 1 << kRadixBits;
 __device__ __forceinline__ float as_f32(u32 x) { return __uint_as_float(x); }
 __device__ __forceinline__ u32 as_u32(float x) { return __float_as_uint(x); }
 
+// ---- streaming 16-byte load: data that is read once per launch is fetched with the non-temporal
+// hint so that it does not displace reusable lines from the caches
+typedef u32 u32x4_t __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ uint4 load_stream16(const void* p) {
+  const u32x4_t v = __builtin_nontemporal_load(reinterpret_cast<const u32x4_t*>(p));
+  return make_uint4(v.x, v.y, v.z, v.w);
+}
+
 // ---- 16-bit -> fp32, eight elements of one 16-byte load -------------------------------------
 template <bool BF16>
 __device__ __forceinline__ void cvt8(const uint4& raw, float (&f)[8]) {

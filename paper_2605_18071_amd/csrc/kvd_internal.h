@@ -12,6 +12,7 @@ constexpr int KVD_FAST_MAX_PAGES = 16384;    // register-resident selection: 102
 constexpr int KVD_FAST_MAX_CAPACITY = 4096; // register-resident directory scan: 1024 threads x 4 slots
 constexpr int KVD_MAX_PAGE = 256;       // P
 constexpr int KVD_MAX_MICRO = 16;       // micro-batches per step
+constexpr int KVD_PIPE_STREAMS = 3;      // side streams a step may spread its micro-batches over
 constexpr int KVD_MAX_SPLITS = 64;      // attention split-K factor
 
 struct kvd_ctx {
@@ -52,9 +53,10 @@ struct kvd_ctx {
   // owned, host
   int32_t* h_capacity;      // [L][U]
   int32_t* h_seq_len;       // [B]
-  hipStream_t side;
-  hipEvent_t ev_sel[KVD_MAX_MICRO];
-  hipEvent_t ev_fetch[KVD_MAX_MICRO];
+  hipStream_t side[KVD_PIPE_STREAMS];   // pipeline streams 1.. (stream 0 is the caller's)
+  hipEvent_t ev_fork;
+  hipEvent_t ev_score[KVD_MAX_MICRO];   // scoring of micro-batch i has finished
+  hipEvent_t ev_done[KVD_MAX_MICRO];    // micro-batch i has finished
   hipEvent_t ev_prof[12];
   int profiling;
   int last_hip;
@@ -74,7 +76,7 @@ hipError_t kvd_launch_select_resolve(kvd_ctx* c, int layer, int step, bool do_se
                                      int32_t* evicted, int32_t* counts, int u0, int u1, hipStream_t s);
 hipError_t kvd_launch_gather(kvd_ctx* c, int layer, int u0, int u1, hipStream_t s);
 hipError_t kvd_launch_attend(kvd_ctx* c, int layer, const void* q, const int32_t* sel_pages,
-                             const int32_t* sel_slots, float* out, float* lse, hipStream_t s);
+                             const int32_t* sel_slots, float* out, float* lse, int u0, int u1, hipStream_t s);
 hipError_t kvd_launch_refill(kvd_ctx* c, int layer, hipStream_t s);
 hipError_t kvd_launch_build_summaries(kvd_ctx* c, int layer, hipStream_t s);
 hipError_t kvd_launch_fill_i32(int32_t* p, int32_t v, size_t n, hipStream_t s);
