@@ -128,6 +128,7 @@ int kvd_create(const kvd_config* cfg, kvd_ctx** out) {
   c->bf16 = cfg->kv_dtype == KVD_BF16;
   c->tiled = (c->P % 16) == 0;
   { const char* e_ = getenv("KVD_FUSE_MERGE"); c->fuse_merge = e_ ? atoi(e_) : 0; }
+  { const char* e_ = getenv("KVD_SCORE_BLOCKS"); c->score_blocks = e_ ? atoi(e_) : 2048; if (c->score_blocks < 1) c->score_blocks = 1; }
   { const char* e_ = getenv("KVD_GENERIC_SELECT"); c->generic_select = e_ ? atoi(e_) : 0; }
   c->scale = cfg->softmax_scale > 0.f ? cfg->softmax_scale : 1.0f / sqrtf((float)c->D);
   c->page_bytes = (size_t)2 * c->P * c->D * 2;
@@ -311,8 +312,8 @@ int kvd_score_select(kvd_ctx* ctx, int32_t layer, const void* q, int32_t* sel_pa
   float* sc = scores ? scores : ctx->d_scores;
   HIP_TRY(ctx, kvd_launch_score(ctx, layer, q, sc, 0, ctx->U, s));
   if (kvd_fast_path_ok(ctx))
-    HIP_TRY(ctx, kvd_launch_select_resolve(ctx, layer, 0, true, false, sc, sel_pages, nullptr, nullptr, nullptr, nullptr,
-                                           0, ctx->U, s));
+    HIP_TRY(ctx, kvd_launch_select_resolve(ctx, layer, 0, true, false, false, sc, sel_pages, nullptr, nullptr, nullptr,
+                                           nullptr, 0, ctx->U, s));
   else
     HIP_TRY(ctx, kvd_launch_select(ctx, sc, sel_pages, 0, ctx->U, s));
   return KVD_OK;
@@ -326,12 +327,13 @@ int kvd_cache_resolve(kvd_ctx* ctx, int32_t layer, int32_t step, const int32_t* 
   int32_t* hm = hit_mask ? hit_mask : ctx->d_hit_mask;
   int32_t* ev = evicted ? evicted : ctx->d_evicted;
   int32_t* cn = counts ? counts : ctx->d_counts;
-  if (kvd_fast_path_ok(ctx))
-    HIP_TRY(ctx, kvd_launch_select_resolve(ctx, layer, step, false, true, nullptr, const_cast<int32_t*>(sel_pages),
-                                           sel_slots, hm, ev, cn, 0, ctx->U, s));
-  else
+  if (kvd_fast_path_ok(ctx)) {
+    HIP_TRY(ctx, kvd_launch_select_resolve(ctx, layer, step, false, true, do_gather != 0, nullptr,
+                                           const_cast<int32_t*>(sel_pages), sel_slots, hm, ev, cn, 0, ctx->U, s));
+  } else {
     HIP_TRY(ctx, kvd_launch_resolve(ctx, layer, step, sel_pages, sel_slots, hm, ev, cn, 0, ctx->U, s));
-  if (do_gather) HIP_TRY(ctx, kvd_launch_gather(ctx, layer, 0, ctx->U, s));
+    if (do_gather) HIP_TRY(ctx, kvd_launch_gather(ctx, layer, 0, ctx->U, s));
+  }
   ++ctx->n_steps;
   return KVD_OK;
 }
@@ -345,16 +347,18 @@ int kvd_sparse_decode_attn(kvd_ctx* ctx, int32_t layer, const void* q, const int
   return KVD_OK;
 }
 
-// Selection + directory update for units [u0, u1): one fused kernel when the sizes allow the
-// register-resident path, else the two size-agnostic kernels.
-static hipError_t launch_select_resolve(kvd_ctx* c, int layer, int step, int u0, int u1, hipStream_t s) {
+// Selection + directory update + fetch for units [u0, u1): one fused kernel when the sizes allow
+// the register-resident path, else the three size-agnostic kernels.
+static hipError_t launch_select_resolve_fetch(kvd_ctx* c, int layer, int step, int u0, int u1, hipStream_t s) {
   if (kvd_fast_path_ok(c))
-    return kvd_launch_select_resolve(c, layer, step, true, true, c->d_scores, c->d_sel_pages, c->d_sel_slots,
+    return kvd_launch_select_resolve(c, layer, step, true, true, true, c->d_scores, c->d_sel_pages, c->d_sel_slots,
                                      c->d_hit_mask, c->d_evicted, c->d_counts, u0, u1, s);
   hipError_t e = kvd_launch_select(c, c->d_scores, c->d_sel_pages, u0, u1, s);
   if (e != hipSuccess) return e;
-  return kvd_launch_resolve(c, layer, step, c->d_sel_pages, c->d_sel_slots, c->d_hit_mask, c->d_evicted, c->d_counts,
-                            u0, u1, s);
+  e = kvd_launch_resolve(c, layer, step, c->d_sel_pages, c->d_sel_slots, c->d_hit_mask, c->d_evicted, c->d_counts, u0,
+                         u1, s);
+  if (e != hipSuccess) return e;
+  return kvd_launch_gather(c, layer, u0, u1, s);
 }
 
 // One layer-step with every stage bracketed by HIP events on the caller's stream; waits for the
@@ -364,9 +368,8 @@ static int step_profiled(kvd_ctx* c, int layer, int step, const void* q, float* 
   HIP_TRY(c, hipEventRecord(ev[0], s));
   HIP_TRY(c, kvd_launch_score(c, layer, q, c->d_scores, 0, c->U, s));
   HIP_TRY(c, hipEventRecord(ev[1], s));
-  HIP_TRY(c, launch_select_resolve(c, layer, step, 0, c->U, s));
+  HIP_TRY(c, launch_select_resolve_fetch(c, layer, step, 0, c->U, s));
   HIP_TRY(c, hipEventRecord(ev[2], s));
-  HIP_TRY(c, kvd_launch_gather(c, layer, 0, c->U, s));
   HIP_TRY(c, hipEventRecord(ev[3], s));
   HIP_TRY(c, kvd_launch_attend(c, layer, q, c->d_sel_pages, c->d_sel_slots, out, lse, 0, c->U, s));
   HIP_TRY(c, hipEventRecord(ev[4], s));
@@ -390,8 +393,7 @@ int kvd_step(kvd_ctx* ctx, int32_t layer, int32_t step, const void* q, float* ou
   if (c->profiling) return step_profiled(c, layer, step, q, out, lse, s);
   if (c->MB <= 1) {
     HIP_TRY(c, kvd_launch_score(c, layer, q, c->d_scores, 0, c->U, s));
-    HIP_TRY(c, launch_select_resolve(c, layer, step, 0, c->U, s));
-    HIP_TRY(c, kvd_launch_gather(c, layer, 0, c->U, s));
+    HIP_TRY(c, launch_select_resolve_fetch(c, layer, step, 0, c->U, s));
     HIP_TRY(c, kvd_launch_attend(c, layer, q, c->d_sel_pages, c->d_sel_slots, out, lse, 0, c->U, s));
     return KVD_OK;
   }
@@ -409,8 +411,7 @@ int kvd_step(kvd_ctx* ctx, int32_t layer, int32_t step, const void* q, float* ou
     if (i > 0) HIP_TRY(c, hipStreamWaitEvent(st, c->ev_score[i - 1], 0));
     HIP_TRY(c, kvd_launch_score(c, layer, q, c->d_scores, u0, u1, st));
     HIP_TRY(c, hipEventRecord(c->ev_score[i], st));
-    HIP_TRY(c, launch_select_resolve(c, layer, step, u0, u1, st));
-    HIP_TRY(c, kvd_launch_gather(c, layer, u0, u1, st));
+    HIP_TRY(c, launch_select_resolve_fetch(c, layer, step, u0, u1, st));
     HIP_TRY(c, kvd_launch_attend(c, layer, q, c->d_sel_pages, c->d_sel_slots, out, lse, u0, u1, st));
     if (lane != 0) HIP_TRY(c, hipEventRecord(c->ev_done[i], st));
   }

@@ -5,6 +5,7 @@
 // builds the index (System Overview: mean key of each page).
 #include "kvd_device.h"
 #include "kvd_internal.h"
+#include "kvd_page_copy.h"
 #include "kvd_tile_layout.h"
 
 namespace kvd {
@@ -38,6 +39,7 @@ struct ResolveArgs {
 //     page order; the directory is updated and the (page, slot) miss list written for the fetch.
 __global__ __launch_bounds__(kResolveThreads) void resolve_kernel(ResolveArgs a) {
   __shared__ SelectSmem sm;
+  __shared__ u32 radix_hist[kRadixBins];
   __shared__ u32 hit_bitmap[kBitmapWords];
   __shared__ int32_t assign[KVD_MAX_TOPK];
   __shared__ int n_hits, n_evicted_out;
@@ -101,7 +103,7 @@ __global__ __launch_bounds__(kResolveThreads) void resolve_kernel(ResolveArgs a)
     return true;
   };
   u64 thr = 0;
-  if (e > 0) thr = block_kth_smallest<NT>(victim_key, C, e, sm);
+  if (e > 0) thr = block_kth_smallest<NT>(victim_key, C, e, sm, radix_hist);
 
   // 3. hand out slots
   const int sper = (C + NT - 1) / NT;
@@ -184,31 +186,12 @@ __device__ __forceinline__ void copy_page(const char* __restrict__ src, char* __
     return;
   }
   const int tiles = P / kTileTokens;
-  const int row = tid >> 4, ch = tid & 15;           // source unit: token `row` of the tile, dims 8ch..8ch+7
-  const char* ksrc = src;
-  const char* vsrc = src + (size_t)P * kRowBytes;
   for (int t = 0; t < tiles; ++t) {
-    const uint4 kq = *reinterpret_cast<const uint4*>(ksrc + ((size_t)(t * kTileTokens + row) * kRowBytes) + ch * 16);
-    const uint4 vq = *reinterpret_cast<const uint4*>(vsrc + ((size_t)(t * kTileTokens + row) * kRowBytes) + ch * 16);
     char* tile = dst + (size_t)t * kTileBytes;
-    // K: chunk c = ch / 4, lane = row + 16 * (ch % 4)
-    *reinterpret_cast<uint4*>(tile + ((ch >> 2) * 64 + (ch & 3) * 16 + row) * 16) = kq;
     __syncthreads();                                   // previous tile's readers are done with vt
-    *reinterpret_cast<uint4*>(vt + row * kHeadDim + ch * 8) = vq;
+    tile_copy_phase_a(src, P, t, tile, vt, tid);
     __syncthreads();
-    // V: this thread assembles destination unit `tid` = chunk c, lane i + 16 g
-    const int c = tid >> 6, g = (tid >> 4) & 3, i = tid & 15;
-    uint16_t e[8];
-#pragma unroll
-    for (int hh = 0; hh < 2; ++hh)
-#pragma unroll
-      for (int k = 0; k < 4; ++k) e[hh * 4 + k] = vt[(4 * g + k) * kHeadDim + 32 * c + 16 * hh + i];
-    uint4 outv;
-    outv.x = (u32)e[0] | ((u32)e[1] << 16);
-    outv.y = (u32)e[2] | ((u32)e[3] << 16);
-    outv.z = (u32)e[4] | ((u32)e[5] << 16);
-    outv.w = (u32)e[6] | ((u32)e[7] << 16);
-    *reinterpret_cast<uint4*>(tile + kTilePartBytes + tid * 16) = outv;
+    tile_copy_phase_b(tile, vt, tid);
   }
 }
 

@@ -57,13 +57,20 @@ __device__ __forceinline__ float row16_allreduce_sum(float v) {
   return v;
 }
 
+// Inclusive prefix sum over the 64 lanes of a wave with DPP moves only: log-step shifts inside
+// each row of 16 lanes (lanes shifted in from outside the row read 0), then the last lane of
+// row 0 / row 2 is added to row 1 / row 3, then lane 31 to rows 2 and 3.
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ int dpp_get(int v) {
+  return __builtin_amdgcn_update_dpp(0, v, CTRL, ROW_MASK, 0xf, true);
+}
 __device__ __forceinline__ int wave_inclusive_scan(int v) {
-  const int lane = threadIdx.x & (kWave - 1);
-#pragma unroll
-  for (int d = 1; d < kWave; d <<= 1) {
-    int o = __shfl_up(v, d, kWave);
-    if (lane >= d) v += o;
-  }
+  v += dpp_get<0x111, 0xf>(v);   // row_shr:1
+  v += dpp_get<0x112, 0xf>(v);   // row_shr:2
+  v += dpp_get<0x114, 0xf>(v);   // row_shr:4
+  v += dpp_get<0x118, 0xf>(v);   // row_shr:8
+  v += dpp_get<0x142, 0xa>(v);   // row_bcast:15 into rows 1 and 3
+  v += dpp_get<0x143, 0xc>(v);   // row_bcast:31 into rows 2 and 3
   return v;
 }
 
@@ -97,7 +104,6 @@ __device__ __forceinline__ u64 shfl_xor_u64(u64 v, int m) {
 
 // ---- exact k-th smallest of distinct 64-bit keys, one block ----------------------------------
 struct SelectSmem {
-  u32 hist[kRadixBins];
   int scan[32];
   u64 red_min[16];
   u64 red_max[16];
@@ -106,12 +112,13 @@ struct SelectSmem {
   int bin, below;
 };
 
+// `hist` is an LDS array of kRadixBins counters.
 // keyfn(i, key) -> bool valid, for i in [0, n).  Keys must be distinct.  `need` is 1-based and
 // at most the number of valid items.  Returns the need-th smallest key.  All threads of the block
 // must call it with the same arguments.  Radix refinement: at most ceil(64/11) counting passes,
 // each narrowing the inclusive key range [lo, hi] to one of 2048 equal sub-ranges.
 template <int NT, class KeyFn>
-__device__ u64 block_kth_smallest(KeyFn keyfn, int n, int need, SelectSmem& sm) {
+__device__ u64 block_kth_smallest(KeyFn keyfn, int n, int need, SelectSmem& sm, u32* hist) {
   constexpr int NW = NT / kWave;
   const int tid = threadIdx.x, lane = tid & (kWave - 1), w = tid / kWave;
   u64 mn = ~0ull, mx = 0ull;
@@ -147,23 +154,23 @@ __device__ u64 block_kth_smallest(KeyFn keyfn, int n, int need, SelectSmem& sm) 
     const u64 width = hi - lo;
     const int bits = 64 - __clzll((long long)width);
     const int shift = bits > kRadixBits ? bits - kRadixBits : 0;
-    for (int i = tid; i < kRadixBins; i += NT) sm.hist[i] = 0;
+    for (int i = tid; i < kRadixBins; i += NT) hist[i] = 0;
     __syncthreads();
     for (int i = tid; i < n; i += NT) {
       u64 key;
-      if (keyfn(i, key) && key >= lo && key <= hi) atomicAdd(&sm.hist[(u32)((key - lo) >> shift)], 1u);
+      if (keyfn(i, key) && key >= lo && key <= hi) atomicAdd(&hist[(u32)((key - lo) >> shift)], 1u);
     }
     __syncthreads();
     constexpr int BPT = kRadixBins / NT;           // consecutive bins per thread
     int local = 0;
 #pragma unroll
-    for (int j = 0; j < BPT; ++j) local += (int)sm.hist[tid * BPT + j];
+    for (int j = 0; j < BPT; ++j) local += (int)hist[tid * BPT + j];
     int total;
     int ex = block_exclusive_scan<NT>(local, sm.scan, total);
     if (ex < want && want <= ex + local) {         // exactly one thread
       int b = tid * BPT;
       for (int j = 0; j < BPT; ++j, ++b) {
-        const int c = (int)sm.hist[b];
+        const int c = (int)hist[b];
         if (want <= ex + c) break;
         ex += c;
       }

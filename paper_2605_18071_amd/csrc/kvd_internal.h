@@ -19,6 +19,7 @@ struct kvd_ctx {
   kvd_config cfg;
   int L, B, Hq, Hkv, G, D, P, NP, k, Cmax, Lp, U, MB, S;
   int bf16;
+  int score_blocks;        // target number of blocks of a scoring launch
   int generic_select;      // force the size-agnostic select / resolve kernels (testing)
   int fuse_merge;          // attention: last split block merges (1) or a second kernel does (0)
   int tiled;               // slots use the tile layout (page size a multiple of 16)
@@ -71,7 +72,7 @@ hipError_t kvd_launch_select(kvd_ctx* c, const float* scores, int32_t* sel_pages
 hipError_t kvd_launch_resolve(kvd_ctx* c, int layer, int step, const int32_t* sel_pages, int32_t* sel_slots,
                               int32_t* hit_mask, int32_t* evicted, int32_t* counts, int u0, int u1, hipStream_t s);
 bool kvd_fast_path_ok(const kvd_ctx* c);
-hipError_t kvd_launch_select_resolve(kvd_ctx* c, int layer, int step, bool do_select, bool do_resolve,
+hipError_t kvd_launch_select_resolve(kvd_ctx* c, int layer, int step, bool do_select, bool do_resolve, bool do_gather,
                                      const float* scores, int32_t* sel_pages, int32_t* sel_slots, int32_t* hit_mask,
                                      int32_t* evicted, int32_t* counts, int u0, int u1, hipStream_t s);
 hipError_t kvd_launch_gather(kvd_ctx* c, int layer, int u0, int u1, hipStream_t s);

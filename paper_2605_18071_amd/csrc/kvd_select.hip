@@ -9,10 +9,10 @@
 namespace kvd {
 
 constexpr int kScoreThreads = 256;
-constexpr int kScorePagesPerWave = 128;
-constexpr int kScorePagesPerBlock = kScorePagesPerWave * (kScoreThreads / kWave);
+constexpr int kScoreWaves = kScoreThreads / kWave;
 
-// One block scores 512 consecutive pages of one unit, 128 per wave in two passes of 64.  A wave
+// One block scores 256 * passes consecutive pages of one unit, each wave 64 * passes of them in
+// passes of 64.  A wave
 // load covers 4 summary rows (4 x 256 B): lane (r, c) = (lane / 16, lane % 16) holds dims
 // 8c..8c+7 of row r.  The 16 partial dot products of a row are summed with DPP row rotations;
 // after 16 loads lane (r, c) keeps the score of page base + 4c + r and the wave stores 64
@@ -22,12 +22,12 @@ template <bool BF16>
 __global__ __launch_bounds__(kScoreThreads) void score_kernel(const uint16_t* __restrict__ summ,  // [U][NP][D] of the layer
                                                              const uint16_t* __restrict__ q,     // [B][Hq][D]
                                                              float* __restrict__ scores,         // [U][NP]
-                                                             int NP, int G, int Hq, int Hkv, float scale, int u0) {
+                                                             int NP, int G, int Hq, int Hkv, float scale, int u0, int passes) {
   const int u = blockIdx.y + u0;
   const int b = u / Hkv, h = u % Hkv;
   const int lane = threadIdx.x & (kWave - 1), w = threadIdx.x / kWave;
   const int r = lane >> 4, c = lane & 15;
-  const int wave_base = blockIdx.x * kScorePagesPerBlock + w * kScorePagesPerWave;
+  const int wave_base = (blockIdx.x * kScoreWaves + w) * 64 * passes;
   if (wave_base >= NP) return;
   const uint16_t* srow = summ + (size_t)u * NP * kHeadDim + c * 8;
 
@@ -57,8 +57,7 @@ __global__ __launch_bounds__(kScoreThreads) void score_kernel(const uint16_t* __
 #pragma unroll
   for (int e = 0; e < 8; ++e) qbar[e] = qbar[e] / fg;
 
-#pragma unroll
-  for (int pass = 0; pass < kScorePagesPerWave / 64; ++pass) {
+  for (int pass = 0; pass < passes; ++pass) {
     const int base = wave_base + pass * 64;
     if (base >= NP) break;
     float mine = 0.f;
@@ -69,7 +68,7 @@ __global__ __launch_bounds__(kScoreThreads) void score_kernel(const uint16_t* __
       for (int i = 0; i < 8; ++i) cur[i] = raw[i];
       // next batch in flight while this one is reduced
       if (half == 0) issue(base, 1);
-      else if (pass + 1 < kScorePagesPerWave / 64 && base + 64 < NP) issue(base + 64, 0);
+      else if (pass + 1 < passes && base + 64 < NP) issue(base + 64, 0);
 #pragma unroll
       for (int i = 0; i < 8; ++i) {
         float f[8];
@@ -105,6 +104,7 @@ __global__ __launch_bounds__(kSelectThreads) void select_kernel(const float* __r
                                                                int NP, int P, int k, int sink, int recent, int Hkv,
                                                                int u0) {
   __shared__ SelectSmem sm;
+  __shared__ u32 radix_hist[kRadixBins];
   const int u = blockIdx.x + u0;
   const int b = u / Hkv;
   const int tid = threadIdx.x;
@@ -121,7 +121,7 @@ __global__ __launch_bounds__(kSelectThreads) void select_kernel(const float* __r
     key = ((u64)hi << 32) | (u32)i;
     return true;
   };
-  const u64 thr = block_kth_smallest<kSelectThreads>(keyfn, n_valid, k_eff, sm);
+  const u64 thr = block_kth_smallest<kSelectThreads>(keyfn, n_valid, k_eff, sm, radix_hist);
 
   const int per = (n_valid + kSelectThreads - 1) / kSelectThreads;   // consecutive pages per thread
   const int p0 = tid * per;
@@ -151,13 +151,19 @@ hipError_t kvd_launch_score(kvd_ctx* c, int layer, const void* q, float* scores,
   using namespace kvd;
   if (u1 <= u0) return hipSuccess;
   const uint16_t* summ = reinterpret_cast<const uint16_t*>(c->summaries) + (size_t)layer * c->U * c->NP * kHeadDim;
-  dim3 grid((c->NP + kScorePagesPerBlock - 1) / kScorePagesPerBlock, u1 - u0);
+  // about c->score_blocks blocks in total, so that the grid is one round of resident blocks
+  const int n_units = u1 - u0;
+  const long long pages = (long long)c->NP * n_units;
+  int passes = (int)((pages + 256LL * c->score_blocks - 1) / (256LL * c->score_blocks));
+  if (passes < 1) passes = 1;
+  const int per_block = 256 * passes;
+  dim3 grid((c->NP + per_block - 1) / per_block, n_units);
   if (c->bf16)
     hipLaunchKernelGGL(score_kernel<true>, grid, dim3(kScoreThreads), 0, s, summ, (const uint16_t*)q, scores, c->NP,
-                       c->G, c->Hq, c->Hkv, c->scale, u0);
+                       c->G, c->Hq, c->Hkv, c->scale, u0, passes);
   else
     hipLaunchKernelGGL(score_kernel<false>, grid, dim3(kScoreThreads), 0, s, summ, (const uint16_t*)q, scores, c->NP,
-                       c->G, c->Hq, c->Hkv, c->scale, u0);
+                       c->G, c->Hq, c->Hkv, c->scale, u0, passes);
   return hipGetLastError();
 }
 
