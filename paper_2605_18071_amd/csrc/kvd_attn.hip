@@ -46,25 +46,37 @@ struct AttnSmem {
   int is_last;
 };
 
-// Log-sum-exp merge of the S split partials of unit u into out / lse, by one block.
+// Log-sum-exp merge of the S split partials of unit u into out / lse, by one block.  The
+// partials are fetched in batches of 8 splits whose loads are all issued before any is used.
 template <int G>
 __device__ __forceinline__ void merge_splits(const AttnArgs& a, int u) {
   const int tid = threadIdx.x;
   const int b = u / a.Hkv, h = u % a.Hkv;
   for (int idx = tid; idx < G * kHeadDim; idx += kAttnThreads) {
     const int g = idx / kHeadDim, d = idx % kHeadDim;
-    const float* ml = a.part_ml + ((size_t)u * a.S * G + g) * 2;
+    const float2* ml = reinterpret_cast<const float2*>(a.part_ml) + ((size_t)u * a.S * G + g);
     const float* pa = a.part_acc + ((size_t)u * a.S * G + g) * kHeadDim + d;
-    float M = -INFINITY;
-#pragma unroll 8
-    for (int s = 0; s < a.S; ++s) M = fmaxf(M, ml[(size_t)s * G * 2]);
-    const float Ms = M == -INFINITY ? 0.f : M;
-    float L = 0.f, A = 0.f;
-#pragma unroll 8
-    for (int s = 0; s < a.S; ++s) {
-      const float sc = exp2f(ml[(size_t)s * G * 2] - Ms);
-      L += ml[(size_t)s * G * 2 + 1] * sc;
-      A += pa[(size_t)s * G * kHeadDim] * sc;
+    float M = -INFINITY, L = 0.f, A = 0.f;
+    for (int s0 = 0; s0 < a.S; s0 += 8) {
+      float2 mlv[8];
+      float av[8];
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        const int s = (s0 + i) < a.S ? (s0 + i) : (a.S - 1);
+        mlv[i] = ml[(size_t)s * G];
+        av[i] = pa[(size_t)s * G * kHeadDim];
+      }
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        if (s0 + i < a.S) {
+          const float Mn = fmaxf(M, mlv[i].x);
+          const float Ms = Mn == -INFINITY ? 0.f : Mn;
+          const float so = exp2f(M - Ms), sn = exp2f(mlv[i].x - Ms);
+          L = L * so + mlv[i].y * sn;
+          A = A * so + av[i] * sn;
+          M = Mn;
+        }
+      }
     }
     const size_t row = (size_t)b * a.Hq + (size_t)h * G + g;
     a.out[row * kHeadDim + d] = A / L;

@@ -95,6 +95,25 @@ __device__ __forceinline__ int block_exclusive_scan(int v, int* smem, int& total
   return base + inc - v;
 }
 
+// min / max / sum over the 64 lanes with DPP rotations inside the rows of 16 and two cross-row
+// exchanges; every lane gets the result
+__device__ __forceinline__ float wave_allreduce_min(float v) {
+  v = fminf(v, dpp_mov<0x128>(v));
+  v = fminf(v, dpp_mov<0x124>(v));
+  v = fminf(v, dpp_mov<0x122>(v));
+  v = fminf(v, dpp_mov<0x121>(v));
+  v = fminf(v, __shfl_xor(v, 16, kWave));
+  return fminf(v, __shfl_xor(v, 32, kWave));
+}
+__device__ __forceinline__ float wave_allreduce_max(float v) {
+  v = fmaxf(v, dpp_mov<0x128>(v));
+  v = fmaxf(v, dpp_mov<0x124>(v));
+  v = fmaxf(v, dpp_mov<0x122>(v));
+  v = fmaxf(v, dpp_mov<0x121>(v));
+  v = fmaxf(v, __shfl_xor(v, 16, kWave));
+  return fmaxf(v, __shfl_xor(v, 32, kWave));
+}
+
 __device__ __forceinline__ u64 shfl_xor_u64(u64 v, int m) {
   u32 lo = (u32)v, hi = (u32)(v >> 32);
   lo = __shfl_xor((int)lo, m, kWave);

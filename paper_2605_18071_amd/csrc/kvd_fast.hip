@@ -245,12 +245,10 @@ __global__ __launch_bounds__(kFastThreads) void select_resolve_kernel(FastArgs a
       }
       n_forced += forced ? 1 : 0;
     }
-#pragma unroll
-    for (int msk = 32; msk >= 1; msk >>= 1) {
-      fmin = fminf(fmin, __shfl_xor(fmin, msk, kWave));
-      fmax = fmaxf(fmax, __shfl_xor(fmax, msk, kWave));
-      n_forced += __shfl_xor(n_forced, msk, kWave);
-    }
+    fmin = wave_allreduce_min(fmin);
+    fmax = wave_allreduce_max(fmax);
+    n_forced = wave_inclusive_scan(n_forced);          // lane 63 holds the wave's count
+    n_forced = __builtin_amdgcn_readlane(n_forced, 63);
     if (lane == 0) { sm.red_min[w] = fmin; sm.red_max[w] = fmax; sm.red_cnt[w] = n_forced; }
     __syncthreads();
     fmin = sm.red_min[0]; fmax = sm.red_max[0]; n_forced = sm.red_cnt[0];
