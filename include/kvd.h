@@ -90,7 +90,12 @@ typedef struct {
   uint64_t gathered_bytes; /* misses * page_bytes */
   /* filled only while profiling is on (kvd_set_profiling): accumulated milliseconds per kernel,
      from HIP events recorded around each launch on the stream it runs on */
-  double ms_score, ms_select_resolve, ms_gather, ms_attend, ms_total;
+  double ms_score;          /* scoring kernel */
+  double ms_select_resolve; /* selection + directory update; on the fused path also the fetch */
+  double ms_gather;         /* separate fetch kernel (size-agnostic path only) */
+  double ms_attend;         /* attention kernel */
+  double ms_merge;          /* merge of the attention splits */
+  double ms_total;
   uint64_t profiled_steps;
 } kvd_stats;
 

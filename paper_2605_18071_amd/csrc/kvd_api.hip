@@ -365,21 +365,32 @@ static hipError_t launch_select_resolve_fetch(kvd_ctx* c, int layer, int step, i
 // step and accumulates the per-stage times.  Stages run for the whole batch, one after another.
 static int step_profiled(kvd_ctx* c, int layer, int step, const void* q, float* out, float* lse, hipStream_t s) {
   hipEvent_t* ev = c->ev_prof;
+  const bool fused = kvd_fast_path_ok(c);
   HIP_TRY(c, hipEventRecord(ev[0], s));
   HIP_TRY(c, kvd_launch_score(c, layer, q, c->d_scores, 0, c->U, s));
   HIP_TRY(c, hipEventRecord(ev[1], s));
-  HIP_TRY(c, launch_select_resolve_fetch(c, layer, step, 0, c->U, s));
-  HIP_TRY(c, hipEventRecord(ev[2], s));
-  HIP_TRY(c, hipEventRecord(ev[3], s));
-  HIP_TRY(c, kvd_launch_attend(c, layer, q, c->d_sel_pages, c->d_sel_slots, out, lse, 0, c->U, s));
-  HIP_TRY(c, hipEventRecord(ev[4], s));
-  HIP_TRY(c, hipEventSynchronize(ev[4]));
+  if (fused) {
+    HIP_TRY(c, launch_select_resolve_fetch(c, layer, step, 0, c->U, s));
+    HIP_TRY(c, hipEventRecord(ev[2], s));
+    HIP_TRY(c, hipEventRecord(ev[3], s));
+  } else {
+    HIP_TRY(c, kvd_launch_select(c, c->d_scores, c->d_sel_pages, 0, c->U, s));
+    HIP_TRY(c, kvd_launch_resolve(c, layer, step, c->d_sel_pages, c->d_sel_slots, c->d_hit_mask, c->d_evicted,
+                                  c->d_counts, 0, c->U, s));
+    HIP_TRY(c, hipEventRecord(ev[2], s));
+    HIP_TRY(c, kvd_launch_gather(c, layer, 0, c->U, s));
+    HIP_TRY(c, hipEventRecord(ev[3], s));
+  }
+  HIP_TRY(c, kvd_launch_attend(c, layer, q, c->d_sel_pages, c->d_sel_slots, out, lse, 0, c->U, s, ev[4]));
+  HIP_TRY(c, hipEventRecord(ev[5], s));
+  HIP_TRY(c, hipEventSynchronize(ev[5]));
   float ms = 0.f;
   HIP_TRY(c, hipEventElapsedTime(&ms, ev[0], ev[1])); c->ms_score += ms;
   HIP_TRY(c, hipEventElapsedTime(&ms, ev[1], ev[2])); c->ms_select_resolve += ms;
   HIP_TRY(c, hipEventElapsedTime(&ms, ev[2], ev[3])); c->ms_gather += ms;
   HIP_TRY(c, hipEventElapsedTime(&ms, ev[3], ev[4])); c->ms_attend += ms;
-  HIP_TRY(c, hipEventElapsedTime(&ms, ev[0], ev[4])); c->ms_total += ms;
+  HIP_TRY(c, hipEventElapsedTime(&ms, ev[4], ev[5])); c->ms_merge += ms;
+  HIP_TRY(c, hipEventElapsedTime(&ms, ev[0], ev[5])); c->ms_total += ms;
   ++c->profiled_steps;
   return KVD_OK;
 }
@@ -457,6 +468,7 @@ int kvd_get_stats(kvd_ctx* ctx, kvd_stats* host_out) {
   host_out->ms_select_resolve = ctx->ms_select_resolve;
   host_out->ms_gather = ctx->ms_gather;
   host_out->ms_attend = ctx->ms_attend;
+  host_out->ms_merge = ctx->ms_merge;
   host_out->ms_total = ctx->ms_total;
   host_out->profiled_steps = ctx->profiled_steps;
   return KVD_OK;
@@ -467,7 +479,7 @@ int kvd_reset_stats(kvd_ctx* ctx) {
   HIP_TRY(ctx, hipDeviceSynchronize());
   HIP_TRY(ctx, hipMemset(ctx->d_stats, 0, 4 * sizeof(unsigned long long)));
   ctx->n_steps = 0;
-  ctx->ms_score = ctx->ms_select_resolve = ctx->ms_gather = ctx->ms_attend = ctx->ms_total = 0.0;
+  ctx->ms_score = ctx->ms_select_resolve = ctx->ms_gather = ctx->ms_attend = ctx->ms_merge = ctx->ms_total = 0.0;
   ctx->profiled_steps = 0;
   return KVD_OK;
 }

@@ -447,26 +447,27 @@ __global__ __launch_bounds__(kAttnThreads) void attend_valu_kernel(AttnArgs a) {
 }
 
 template <bool BF16, int G>
-static void launch_attend(bool tiled, const AttnArgs& a, dim3 grid, hipStream_t s) {
+static void launch_attend(bool tiled, const AttnArgs& a, dim3 grid, hipStream_t s, hipEvent_t between) {
   if (tiled)
     hipLaunchKernelGGL((attend_mfma_kernel<BF16, G>), grid, dim3(kAttnThreads), 0, s, a);
   else
     hipLaunchKernelGGL((attend_valu_kernel<BF16, G>), grid, dim3(kAttnThreads), 0, s, a);
+  if (between != nullptr) (void)hipEventRecord(between, s);
   if (a.S > 1 && !a.fuse_merge)
     hipLaunchKernelGGL((combine_kernel<G>), dim3(grid.y), dim3(kAttnThreads), 0, s, a);
 }
 
 template <bool BF16>
-static bool dispatch_group(int G, bool tiled, const AttnArgs& a, dim3 grid, hipStream_t s) {
+static bool dispatch_group(int G, bool tiled, const AttnArgs& a, dim3 grid, hipStream_t s, hipEvent_t between) {
   switch (G) {
-    case 1: launch_attend<BF16, 1>(tiled, a, grid, s); return true;
-    case 2: launch_attend<BF16, 2>(tiled, a, grid, s); return true;
-    case 3: launch_attend<BF16, 3>(tiled, a, grid, s); return true;
-    case 4: launch_attend<BF16, 4>(tiled, a, grid, s); return true;
-    case 5: launch_attend<BF16, 5>(tiled, a, grid, s); return true;
-    case 6: launch_attend<BF16, 6>(tiled, a, grid, s); return true;
-    case 7: launch_attend<BF16, 7>(tiled, a, grid, s); return true;
-    case 8: launch_attend<BF16, 8>(tiled, a, grid, s); return true;
+    case 1: launch_attend<BF16, 1>(tiled, a, grid, s, between); return true;
+    case 2: launch_attend<BF16, 2>(tiled, a, grid, s, between); return true;
+    case 3: launch_attend<BF16, 3>(tiled, a, grid, s, between); return true;
+    case 4: launch_attend<BF16, 4>(tiled, a, grid, s, between); return true;
+    case 5: launch_attend<BF16, 5>(tiled, a, grid, s, between); return true;
+    case 6: launch_attend<BF16, 6>(tiled, a, grid, s, between); return true;
+    case 7: launch_attend<BF16, 7>(tiled, a, grid, s, between); return true;
+    case 8: launch_attend<BF16, 8>(tiled, a, grid, s, between); return true;
     default: return false;
   }
 }
@@ -474,7 +475,8 @@ static bool dispatch_group(int G, bool tiled, const AttnArgs& a, dim3 grid, hipS
 }  // namespace kvd
 
 hipError_t kvd_launch_attend(kvd_ctx* c, int layer, const void* q, const int32_t* sel_pages,
-                             const int32_t* sel_slots, float* out, float* lse, int u0, int u1, hipStream_t s) {
+                             const int32_t* sel_slots, float* out, float* lse, int u0, int u1, hipStream_t s,
+                             hipEvent_t between) {
   using namespace kvd;
   if (u1 <= u0) return hipSuccess;
   AttnArgs a;
@@ -495,8 +497,8 @@ hipError_t kvd_launch_attend(kvd_ctx* c, int layer, const void* q, const int32_t
   a.page_bytes = (unsigned)c->page_bytes;
   a.scale_log2 = c->scale * kLog2e;
   dim3 grid(c->S, u1 - u0);
-  const bool ok = c->bf16 ? dispatch_group<true>(c->G, c->tiled != 0, a, grid, s)
-                          : dispatch_group<false>(c->G, c->tiled != 0, a, grid, s);
+  const bool ok = c->bf16 ? dispatch_group<true>(c->G, c->tiled != 0, a, grid, s, between)
+                          : dispatch_group<false>(c->G, c->tiled != 0, a, grid, s, between);
   if (!ok) return hipErrorInvalidValue;
   return hipGetLastError();
 }

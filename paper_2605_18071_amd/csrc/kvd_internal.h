@@ -62,7 +62,7 @@ struct kvd_ctx {
   int profiling;
   int last_hip;
   uint64_t n_steps;
-  double ms_score, ms_select_resolve, ms_gather, ms_attend, ms_total;
+  double ms_score, ms_select_resolve, ms_gather, ms_attend, ms_merge, ms_total;
   uint64_t profiled_steps;
 };
 
@@ -77,7 +77,8 @@ hipError_t kvd_launch_select_resolve(kvd_ctx* c, int layer, int step, bool do_se
                                      int32_t* evicted, int32_t* counts, int u0, int u1, hipStream_t s);
 hipError_t kvd_launch_gather(kvd_ctx* c, int layer, int u0, int u1, hipStream_t s);
 hipError_t kvd_launch_attend(kvd_ctx* c, int layer, const void* q, const int32_t* sel_pages,
-                             const int32_t* sel_slots, float* out, float* lse, int u0, int u1, hipStream_t s);
+                             const int32_t* sel_slots, float* out, float* lse, int u0, int u1, hipStream_t s,
+                             hipEvent_t between = nullptr);   // `between`: recorded after the attention kernel, before the merge
 hipError_t kvd_launch_refill(kvd_ctx* c, int layer, hipStream_t s);
 hipError_t kvd_launch_build_summaries(kvd_ctx* c, int layer, hipStream_t s);
 hipError_t kvd_launch_fill_i32(int32_t* p, int32_t v, size_t n, hipStream_t s);

@@ -36,7 +36,7 @@ class KvdStats(C.Structure):
         ("steps", C.c_uint64), ("hits", C.c_uint64), ("misses", C.c_uint64), ("evictions", C.c_uint64),
         ("gathered_bytes", C.c_uint64),
         ("ms_score", C.c_double), ("ms_select_resolve", C.c_double), ("ms_gather", C.c_double),
-        ("ms_attend", C.c_double), ("ms_total", C.c_double),
+        ("ms_attend", C.c_double), ("ms_merge", C.c_double), ("ms_total", C.c_double),
         ("profiled_steps", C.c_uint64),
     ]
 
