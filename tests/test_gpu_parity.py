@@ -326,3 +326,49 @@ def test_micro_batches_and_per_unit_capacities_give_identical_results():
     for a, b in zip(*outs):
         for x, y in zip(a, b):
             assert np.array_equal(x, y)
+
+
+@pytest.mark.parametrize("cfg", [2, 5])
+def test_size_agnostic_select_resolve_kernels(cfg, monkeypatch):
+    """The register-resident fused kernel covers up to 16384 pages and 4096 slots per unit; larger
+    units take separate select / resolve / fetch kernels.  Force that path on a small workload."""
+    monkeypatch.setenv("KVD_GENERIC_SELECT", "1")
+    w = SCALED[cfg]
+    rig = R.Rig(w)
+    units = all_units(rig)
+    rep = R.run_steps(rig, units, w.steps, check_dir_every=2, progress=f"cfg{cfg}-generic")
+    assert rep.unit_steps == w.steps * w.n_layers * w.units
+    assert rep.tie_divergences <= 2
+    rig.close()
+
+
+def test_degenerate_scores_take_the_radix_fallback():
+    """More than 1024 pages with exactly the same score land in one histogram bucket: the fused
+    kernel must fall back to radix refinement and still pick the lowest pages among the ties."""
+    w = small("degen", ctx=16 * 3000, topk_pages=40, capacity=64, heavy_count=0, batch=1, n_kv_heads=2, n_q_heads=4)
+    rig = R.Rig(w, build_index=False)
+    q = next(W.query_stream(w, rig.q0, 1, R.DEV))
+    # three distinct summary rows: 20 pages of a clearly best row, 2000 pages of a middle row, the rest worst
+    qbar = q[0].float().reshape(w.batch, w.n_kv_heads, w.group, w.head_dim).mean(dim=2)        # [B, Hkv, D]
+    summ = torch.zeros(w.units, w.n_pages, w.head_dim, device=R.DEV)
+    unit_q = qbar.reshape(w.units, w.head_dim)
+    best = torch.arange(100, 120, device=R.DEV)
+    mid = torch.arange(500, 2500, device=R.DEV)
+    summ[:, :, :] = (-unit_q / unit_q.norm(dim=-1, keepdim=True))[:, None, :]
+    summ[:, mid, :] = 0.0
+    summ[:, best, :] = (unit_q / unit_q.norm(dim=-1, keepdim=True))[:, None, :]
+    rig.summaries.copy_(summ.to(w.torch_dtype).view(rig.summaries.shape))
+    rig.kvd.score_select(0, q[0], rig.sel_pages, rig.scores)
+    torch.cuda.synchronize()
+    sel = rig.sel_pages.cpu().numpy()
+    want = np.concatenate([np.arange(100, 120), np.arange(500, 520)])
+    for u in range(w.units):
+        assert np.array_equal(sel[u], want), u
+    # and the whole step on it agrees with the oracle
+    s64 = H.f64(rig.summaries.view(w.units, w.n_pages, w.head_dim))
+    for u in range(w.units):
+        b, h = divmod(u, w.n_kv_heads)
+        qg = H.f64(q[0][b, h * w.group:(h + 1) * w.group])
+        sc = orc.page_scores(orc.pooled_query(qg), s64[u], 1.0 / math.sqrt(w.head_dim))
+        assert np.array_equal(orc.select_pages(sc, w.topk_pages), want)
+    rig.close()
