@@ -24,7 +24,7 @@
  *     memory, "pinned" is page-locked host memory that the GPU can address;
  *   - data buffers (summaries, host store, slot pool, q, out, selections) belong
  *     to the caller and are only borrowed; the library owns its kvd_ctx (cache
- *     directory, scratch, miss lists, one side stream, events) until kvd_destroy;
+ *     directory, scratch, miss lists, a few side streams, events) until kvd_destroy;
  *   - hot-path calls enqueue work on the caller's hipStream_t (passed as void*,
  *     NULL = the null stream) and return without waiting; outputs are valid once
  *     that stream has been synchronised.  No decision is taken on the host
@@ -76,9 +76,10 @@ typedef struct {
                               Copied by kvd_create. */
   int32_t physical_layers; /* layers present in the host store; layer l reads store layer
                               l % physical_layers.  0 means n_layers. */
-  int32_t micro_batches;   /* kvd_step splits the B sequences into this many groups and lets the
-                              fetch of group i overlap the selection of group i+1
-                              ("SFC Disaggregation").  0 or 1 = no split. */
+  int32_t micro_batches;   /* kvd_step splits the B sequences into this many groups; each group runs
+                              select -> fetch -> attend as its own chain on one of the library's
+                              streams, so the fetch of one group overlaps the kernels of the others
+                              ("SFC Disaggregation").  0 or 1 = one chain on the caller's stream. */
   int32_t attn_splits;     /* split-K factor of the attention kernel; 0 = chosen by the library */
 } kvd_config;
 
@@ -183,9 +184,10 @@ int kvd_sparse_decode_attn(kvd_ctx* ctx, int32_t layer, const void* q, const int
 
 /* ---- hot path: the whole layer-step -------------------------------------------------------- */
 
-/* Stages 1-3 for one layer.  With micro_batches > 1 the fetch of one group of sequences runs on
- * the library's side stream and overlaps the selection of the next group (SFC Disaggregation);
- * otherwise everything is enqueued on `stream`.
+/* Stages 1-3 for one layer.  With micro_batches > 1 the groups of sequences run as separate
+ * chains on the library's streams (forked from and joined back into `stream`), so that the
+ * host-link fetch of one group overlaps the kernels of the others (SFC Disaggregation); otherwise
+ * everything is enqueued on `stream`.
  *   q [B][Hq][D] kv_dtype, out [B][Hq][D] fp32, lse [B][Hq] fp32 or NULL. */
 int kvd_step(kvd_ctx* ctx, int32_t layer, int32_t step, const void* q, float* out, float* lse, void* stream);
 
