@@ -76,10 +76,15 @@ typedef struct {
                               Copied by kvd_create. */
   int32_t physical_layers; /* layers present in the host store; layer l reads store layer
                               l % physical_layers.  0 means n_layers. */
-  int32_t micro_batches;   /* kvd_step splits the B sequences into this many groups; each group runs
-                              select -> fetch -> attend as its own chain on one of the library's
-                              streams, so the fetch of one group overlaps the kernels of the others
-                              ("SFC Disaggregation").  0 or 1 = one chain on the caller's stream. */
+  int32_t micro_batches;   /* how kvd_step overlaps selection, fetch and attention ("SFC Disaggregation"):
+                              0 or 1 = one chain of kernels on the caller's stream, no overlap;
+                              n >= 2 = the B sequences are split into n groups, each running
+                                   select -> fetch -> attend as its own chain on one of the library's
+                                   streams, so the fetch of one group overlaps the kernels of the others;
+                              -1 = the whole step as one launch in which every (sequence, KV head) unit
+                                   moves through the stages on its own, synchronised by flags in
+                                   device memory (needs page_size % 16 == 0, max_pages <= 16384,
+                                   capacity_max <= 4096; other shapes run as for 0). */
   int32_t attn_splits;     /* split-K factor of the attention kernel; 0 = chosen by the library */
 } kvd_config;
 
@@ -199,9 +204,20 @@ int kvd_step_trace(kvd_ctx* ctx, int32_t* sel_pages, int32_t* sel_slots, int32_t
 
 /* ---- counters ------------------------------------------------------------------------------ */
 
-/* Profiling on: kvd_step brackets every stage with HIP events on the streams it uses, waits for
- * the step and adds the stage times to the stats (the step is then synchronous). */
-int kvd_set_profiling(kvd_ctx* ctx, int32_t on);
+/* mode 0: off.
+ * mode 1: kvd_step runs as a chain of separate kernels, brackets every stage with HIP events on the
+ *         stream, waits for the step and adds the stage times to the stats (the step is then
+ *         synchronous).
+ * mode 2: a single-launch kvd_step also records, per workgroup, four readings of the GPU's 100 MHz
+ *         wall clock (see kvd_step_timeline); the step stays asynchronous. */
+int kvd_set_profiling(kvd_ctx* ctx, int32_t mode);
+/* Timeline of the last single-launch kvd_step recorded under profiling mode 2.  Synchronises the
+ * device.  host_records [capacity][5] receives, for workgroup i < min(capacity, *n_workgroups) in
+ * dispatch order, the clock at: start, end of its wait for its inputs, end of its work, exit; and
+ * a tag: bits 0-7 the role (0 scoring, 1 selection + directory + fetch, 2 attention), bits 8-31
+ * the unit, bits 32-63 the scoring chunk or attention split.  KVD_ERR_STATE if the step does not
+ * run as one launch or none has run. */
+int kvd_step_timeline(kvd_ctx* ctx, int64_t* host_records, int32_t capacity, int32_t* n_workgroups);
 int kvd_get_stats(kvd_ctx* ctx, kvd_stats* host_out);   /* synchronises the device */
 int kvd_reset_stats(kvd_ctx* ctx);
 

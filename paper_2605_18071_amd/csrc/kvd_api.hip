@@ -37,7 +37,7 @@ static int validate_config(const kvd_config* c) {
   if ((long long)c->batch * c->n_kv_heads > 65535) return KVD_ERR_SHAPE;
   if (c->sink_pages < 0 || c->recent_pages < 0) return KVD_ERR_SHAPE;
   if (c->physical_layers < 0 || c->physical_layers > c->n_layers) return KVD_ERR_SHAPE;
-  if (c->micro_batches < 0 || c->micro_batches > KVD_MAX_MICRO) return KVD_ERR_SHAPE;
+  if (c->micro_batches < -1 || c->micro_batches > KVD_MAX_MICRO) return KVD_ERR_SHAPE;
   if (c->attn_splits < 0 || c->attn_splits > KVD_MAX_SPLITS) return KVD_ERR_SHAPE;
   if (!(c->softmax_scale >= 0.f) || isinf(c->softmax_scale)) return KVD_ERR_ARG;
   if ((long long)c->sink_pages + c->recent_pages > c->topk_pages) return KVD_ERR_CAPACITY;
@@ -56,7 +56,8 @@ static void free_ctx(kvd_ctx* c) {
   if (c == nullptr) return;
   void* dev[] = {c->d_capacity, c->d_seq_len, c->d_page_to_slot, c->d_slot_page, c->d_slot_stamp, c->d_resident,
                  c->d_scores, c->d_sel_pages, c->d_sel_slots, c->d_hit_mask, c->d_evicted, c->d_counts,
-                 c->d_miss_list, c->d_miss_count, c->d_part_acc, c->d_part_ml, c->d_attn_ticket, c->d_stats};
+                 c->d_miss_list, c->d_miss_count, c->d_part_acc, c->d_part_ml, c->d_attn_ticket, c->d_stats,
+                 c->d_score_done, c->d_sel_ready, c->d_timeline};
   for (void* p : dev)
     if (p) (void)hipFree(p);
   for (int i = 0; i < KVD_MAX_MICRO; ++i) {
@@ -68,6 +69,7 @@ static void free_ctx(kvd_ctx* c) {
     if (c->ev_prof[i]) (void)hipEventDestroy(c->ev_prof[i]);
   for (int i = 0; i < KVD_PIPE_STREAMS; ++i)
     if (c->side[i]) (void)hipStreamDestroy(c->side[i]);
+  if (c->error_host) (void)hipHostFree(c->error_host);
   free(c->h_capacity);
   free(c->h_seq_len);
   free(c);
@@ -127,7 +129,8 @@ int kvd_create(const kvd_config* cfg, kvd_ctx** out) {
   if (c->MB > c->B) c->MB = c->B;
   c->bf16 = cfg->kv_dtype == KVD_BF16;
   c->tiled = (c->P % 16) == 0;
-  { const char* e_ = getenv("KVD_FUSE_MERGE"); c->fuse_merge = e_ ? atoi(e_) : 0; }
+  c->wait_limit_ticks = 200000000LL;                // 2 s
+  { const char* e_ = getenv("KVD_FUSE_MERGE"); c->fuse_merge = e_ ? atoi(e_) : 1; }
   { const char* e_ = getenv("KVD_SCORE_BLOCKS"); c->score_blocks = e_ ? atoi(e_) : 2048; if (c->score_blocks < 1) c->score_blocks = 1; }
   { const char* e_ = getenv("KVD_GENERIC_SELECT"); c->generic_select = e_ ? atoi(e_) : 0; }
   c->scale = cfg->softmax_scale > 0.f ? cfg->softmax_scale : 1.0f / sqrtf((float)c->D);
@@ -165,7 +168,10 @@ int kvd_create(const kvd_config* cfg, kvd_ctx** out) {
       ok(dev_alloc(&c->d_miss_count, (size_t)c->U)) &&
       ok(dev_alloc(&c->d_part_acc, (size_t)c->U * c->S * c->G * c->D)) &&
       ok(dev_alloc(&c->d_part_ml, (size_t)c->U * c->S * c->G * 2)) && ok(dev_alloc(&c->d_stats, 4)) &&
-      ok(dev_alloc(&c->d_attn_ticket, (size_t)c->U)) &&
+      ok(dev_alloc(&c->d_attn_ticket, (size_t)c->U)) && ok(dev_alloc(&c->d_score_done, (size_t)c->U)) &&
+      ok(dev_alloc(&c->d_sel_ready, (size_t)c->U)) && ok(dev_alloc(&c->d_timeline, (size_t)KVD_TIMELINE_MAX * 5)) &&
+      ok(hipHostMalloc(reinterpret_cast<void**>(&c->error_host), sizeof(int32_t), hipHostMallocMapped)) &&
+      ok(hipHostGetDevicePointer(reinterpret_cast<void**>(&c->error_dev), c->error_host, 0)) &&
       ok(hipEventCreateWithFlags(&c->ev_fork, hipEventDisableTiming));
   for (int i = 0; i < KVD_PIPE_STREAMS && c->MB > 1 && e == hipSuccess; ++i)
     ok(hipStreamCreateWithFlags(&c->side[i], hipStreamNonBlocking));
@@ -179,6 +185,10 @@ int kvd_create(const kvd_config* cfg, kvd_ctx** out) {
   if (e == hipSuccess) ok(hipMemset(c->d_stats, 0, 4 * sizeof(unsigned long long)));
   if (e == hipSuccess) ok(hipMemset(c->d_miss_count, 0, (size_t)c->U * sizeof(int32_t)));
   if (e == hipSuccess) ok(hipMemset(c->d_attn_ticket, 0, (size_t)c->U * sizeof(int32_t)));
+  if (e == hipSuccess) ok(hipMemset(c->d_score_done, 0, (size_t)c->U * sizeof(int32_t)));
+  if (e == hipSuccess) ok(hipMemset(c->d_sel_ready, 0, (size_t)c->U * sizeof(int32_t)));
+  if (e == hipSuccess) *c->error_host = 0;
+  if (e == hipSuccess) c->single_launch = cfg->micro_batches == -1 && kvd_single_launch_ok(c);
   if (e != hipSuccess) { free_ctx(c); return KVD_ERR_HIP; }
   const int r = reset_directory(c, -1);
   if (r != KVD_OK) { free_ctx(c); return r; }
@@ -238,6 +248,10 @@ int kvd_build_summaries(kvd_ctx* ctx, int32_t layer, void* stream) {
 int kvd_cache_reset(kvd_ctx* ctx) {
   if (!ctx) return KVD_ERR_ARG;
   HIP_TRY(ctx, hipDeviceSynchronize());
+  HIP_TRY(ctx, hipMemset(ctx->d_attn_ticket, 0, (size_t)ctx->U * sizeof(int32_t)));
+  HIP_TRY(ctx, hipMemset(ctx->d_score_done, 0, (size_t)ctx->U * sizeof(int32_t)));
+  HIP_TRY(ctx, hipMemset(ctx->d_sel_ready, 0, (size_t)ctx->U * sizeof(int32_t)));
+  *ctx->error_host = 0;
   return reset_directory(ctx, -1);
 }
 
@@ -388,8 +402,12 @@ static int step_profiled(kvd_ctx* c, int layer, int step, const void* q, float* 
   HIP_TRY(c, hipEventElapsedTime(&ms, ev[0], ev[1])); c->ms_score += ms;
   HIP_TRY(c, hipEventElapsedTime(&ms, ev[1], ev[2])); c->ms_select_resolve += ms;
   HIP_TRY(c, hipEventElapsedTime(&ms, ev[2], ev[3])); c->ms_gather += ms;
-  HIP_TRY(c, hipEventElapsedTime(&ms, ev[3], ev[4])); c->ms_attend += ms;
-  HIP_TRY(c, hipEventElapsedTime(&ms, ev[4], ev[5])); c->ms_merge += ms;
+  if (c->fuse_merge || c->S == 1) {                  // the attention kernel merges its own splits
+    HIP_TRY(c, hipEventElapsedTime(&ms, ev[3], ev[5])); c->ms_attend += ms;
+  } else {
+    HIP_TRY(c, hipEventElapsedTime(&ms, ev[3], ev[4])); c->ms_attend += ms;
+    HIP_TRY(c, hipEventElapsedTime(&ms, ev[4], ev[5])); c->ms_merge += ms;
+  }
   HIP_TRY(c, hipEventElapsedTime(&ms, ev[0], ev[5])); c->ms_total += ms;
   ++c->profiled_steps;
   return KVD_OK;
@@ -401,7 +419,12 @@ int kvd_step(kvd_ctx* ctx, int32_t layer, int32_t step, const void* q, float* ou
   kvd_ctx* c = ctx;
   hipStream_t s = static_cast<hipStream_t>(stream);
   ++c->n_steps;
-  if (c->profiling) return step_profiled(c, layer, step, q, out, lse, s);
+  if (*c->error_host != 0) return KVD_ERR_STATE;   // an earlier single-launch step gave up waiting
+  if (c->profiling == 1) return step_profiled(c, layer, step, q, out, lse, s);
+  if (c->single_launch) {
+    HIP_TRY(c, kvd_launch_step(c, layer, step, q, out, lse, s));
+    return KVD_OK;
+  }
   if (c->MB <= 1) {
     HIP_TRY(c, kvd_launch_score(c, layer, q, c->d_scores, 0, c->U, s));
     HIP_TRY(c, launch_select_resolve_fetch(c, layer, step, 0, c->U, s));
@@ -449,7 +472,19 @@ int kvd_step_trace(kvd_ctx* ctx, int32_t* sel_pages, int32_t* sel_slots, int32_t
 
 int kvd_set_profiling(kvd_ctx* ctx, int32_t on) {
   if (!ctx) return KVD_ERR_ARG;
-  ctx->profiling = on ? 1 : 0;
+  if (on < 0 || on > 2) return KVD_ERR_ARG;
+  ctx->profiling = on;
+  return KVD_OK;
+}
+
+int kvd_step_timeline(kvd_ctx* ctx, int64_t* host_records, int32_t capacity, int32_t* n_workgroups) {
+  if (!ctx || !host_records || !n_workgroups || capacity < 0) return KVD_ERR_ARG;
+  if (!ctx->single_launch || ctx->tl_workgroups == 0) return KVD_ERR_STATE;
+  HIP_TRY(ctx, hipDeviceSynchronize());
+  *n_workgroups = ctx->tl_workgroups;
+  int n = ctx->tl_workgroups < capacity ? ctx->tl_workgroups : capacity;
+  if (n > KVD_TIMELINE_MAX) n = KVD_TIMELINE_MAX;
+  HIP_TRY(ctx, hipMemcpy(host_records, ctx->d_timeline, (size_t)n * 5 * sizeof(int64_t), hipMemcpyDeviceToHost));
   return KVD_OK;
 }
 
@@ -471,6 +506,7 @@ int kvd_get_stats(kvd_ctx* ctx, kvd_stats* host_out) {
   host_out->ms_merge = ctx->ms_merge;
   host_out->ms_total = ctx->ms_total;
   host_out->profiled_steps = ctx->profiled_steps;
+  if (*ctx->error_host != 0) return KVD_ERR_STATE;
   return KVD_OK;
 }
 

@@ -25,6 +25,45 @@ __device__ __forceinline__ uint4 load_stream16(const void* p) {
   return make_uint4(v.x, v.y, v.z, v.w);
 }
 
+// ---- data handed from one workgroup to another inside one launch ------------------------------
+// Workgroups of a launch may run on different XCDs, each with its own L2.  Values that one
+// workgroup produces and another consumes in the same launch are therefore moved with
+// device-scope accesses (written through to, and read from, the memory side), and a flag is
+// raised only after the producer's stores have been acknowledged.
+template <class T>
+__device__ __forceinline__ T load_agent(const T* p) {
+  return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+template <class T>
+__device__ __forceinline__ void store_agent(T* p, T v) {
+  __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+// All memory operations this wave has issued are complete (loads returned, stores acknowledged).
+__device__ __forceinline__ void wave_drain_memory() {
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+  __builtin_amdgcn_s_waitcnt(0);
+}
+
+// Thread 0 polls *flag until it equals `want` (device-scope loads, sleeping between polls) or
+// until `limit` ticks of the 100 MHz wall clock have passed; the verdict is shared through
+// *lds_ok.  Returns false on a time-out.  Contains a barrier: call from all threads.
+__device__ __forceinline__ bool block_wait_equal(const int32_t* flag, int32_t want, long long limit, int* lds_ok) {
+  if (threadIdx.x == 0) {
+    int ok = 1;
+    if (load_agent(flag) != want) {
+      const long long t0 = wall_clock64();
+      for (;;) {
+        __builtin_amdgcn_s_sleep(8);
+        if (load_agent(flag) == want) break;
+        if (wall_clock64() - t0 > limit) { ok = 0; break; }
+      }
+    }
+    *lds_ok = ok;
+  }
+  __syncthreads();
+  return *lds_ok != 0;
+}
+
 // ---- 16-bit -> fp32, eight elements of one 16-byte load -------------------------------------
 template <bool BF16>
 __device__ __forceinline__ void cvt8(const uint4& raw, float (&f)[8]) {

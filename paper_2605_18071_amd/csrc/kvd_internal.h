@@ -14,6 +14,12 @@ constexpr int KVD_MAX_PAGE = 256;       // P
 constexpr int KVD_MAX_MICRO = 16;       // micro-batches per step
 constexpr int KVD_PIPE_STREAMS = 3;      // side streams a step may spread its micro-batches over
 constexpr int KVD_MAX_SPLITS = 64;      // attention split-K factor
+constexpr int KVD_TIMELINE_MAX = 1 << 16; // workgroups of a single-launch step whose times can be recorded
+
+namespace kvd {
+struct FastArgs;
+struct AttnArgs;
+}  // namespace kvd
 
 struct kvd_ctx {
   kvd_config cfg;
@@ -21,7 +27,8 @@ struct kvd_ctx {
   int bf16;
   int score_blocks;        // target number of blocks of a scoring launch
   int generic_select;      // force the size-agnostic select / resolve kernels (testing)
-  int fuse_merge;          // attention: last split block merges (1) or a second kernel does (0)
+  int fuse_merge;          // attention: last split workgroup merges (1) or a second kernel does (0)
+  int single_launch;       // kvd_step runs as one kernel launch
   int tiled;               // slots use the tile layout (page size a multiple of 16)
   float scale;
   size_t page_bytes;
@@ -49,6 +56,8 @@ struct kvd_ctx {
   float* d_part_acc;        // [U][S][G][D]
   float* d_part_ml;         // [U][S][G][2]  (max in log2 units, sum)
   int32_t* d_attn_ticket;   // [U] arrival counter of the attention splits, zero between launches
+  int32_t* d_score_done;    // [U] single-launch step: scoring workgroups arrived, zero between launches
+  int32_t* d_sel_ready;     // [U] single-launch step: number of the last launch that finished the unit's selection
   unsigned long long* d_stats;  // hits, misses, evictions
 
   // owned, host
@@ -59,6 +68,12 @@ struct kvd_ctx {
   hipEvent_t ev_score[KVD_MAX_MICRO];   // scoring of micro-batch i has finished
   hipEvent_t ev_done[KVD_MAX_MICRO];    // micro-batch i has finished
   hipEvent_t ev_prof[12];
+  int32_t* error_host;      // pinned word the single-launch step raises when one of its waits runs out
+  int32_t* error_dev;       // the same word as the GPU addresses it
+  long long wait_limit_ticks;   // bound of every in-kernel wait, in ticks of the 100 MHz wall clock
+  int epoch;                // number of the last single-launch step
+  long long* d_timeline;    // [KVD_TIMELINE_MAX][5] per-workgroup record of the last single-launch step
+  int tl_workgroups;        // workgroups of that launch
   int profiling;
   int last_hip;
   uint64_t n_steps;
@@ -75,10 +90,17 @@ bool kvd_fast_path_ok(const kvd_ctx* c);
 hipError_t kvd_launch_select_resolve(kvd_ctx* c, int layer, int step, bool do_select, bool do_resolve, bool do_gather,
                                      const float* scores, int32_t* sel_pages, int32_t* sel_slots, int32_t* hit_mask,
                                      int32_t* evicted, int32_t* counts, int u0, int u1, hipStream_t s);
+kvd::FastArgs kvd_fast_args(kvd_ctx* c, int layer, int step, bool do_gather, const float* scores, int32_t* sel_pages,
+                            int32_t* sel_slots, int32_t* hit_mask, int32_t* evicted, int32_t* counts, int u0);
+kvd::AttnArgs kvd_attn_args(kvd_ctx* c, int layer, const void* q, const int32_t* sel_pages, const int32_t* sel_slots,
+                            float* out, float* lse, int u0);
 hipError_t kvd_launch_gather(kvd_ctx* c, int layer, int u0, int u1, hipStream_t s);
 hipError_t kvd_launch_attend(kvd_ctx* c, int layer, const void* q, const int32_t* sel_pages,
                              const int32_t* sel_slots, float* out, float* lse, int u0, int u1, hipStream_t s,
                              hipEvent_t between = nullptr);   // `between`: recorded after the attention kernel, before the merge
+// The whole step as one launch (kvd_step.hip); usable when kvd_single_launch_ok.
+bool kvd_single_launch_ok(const kvd_ctx* c);
+hipError_t kvd_launch_step(kvd_ctx* c, int layer, int step, const void* q, float* out, float* lse, hipStream_t s);
 hipError_t kvd_launch_refill(kvd_ctx* c, int layer, hipStream_t s);
 hipError_t kvd_launch_build_summaries(kvd_ctx* c, int layer, hipStream_t s);
 hipError_t kvd_launch_fill_i32(int32_t* p, int32_t v, size_t n, hipStream_t s);

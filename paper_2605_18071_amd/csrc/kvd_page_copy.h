@@ -7,9 +7,23 @@
 
 namespace kvd {
 
+// 16-byte store into a slot.  HANDOFF: the slot is read by another workgroup of the same launch,
+// so the bytes are written through with two 8-byte device-scope stores.
+template <bool HANDOFF>
+__device__ __forceinline__ void slot_store16(void* dst, const uint4& v) {
+  if (HANDOFF) {
+    u64* d = reinterpret_cast<u64*>(dst);
+    store_agent(d, ((u64)v.y << 32) | v.x);
+    store_agent(d + 1, ((u64)v.w << 32) | v.z);
+  } else {
+    *reinterpret_cast<uint4*>(dst) = v;
+  }
+}
+
 // Phase A (gt = thread index in the group): fetch one 16-byte unit of K and of V (token gt / 16 of
 // the tile, dims 8 (gt % 16) ..), store the K unit at its permuted place, park the V unit in LDS
 // (`vt`: 16 x 128 elements, natural order).
+template <bool HANDOFF = false>
 __device__ __forceinline__ void tile_copy_phase_a(const char* __restrict__ src_page, int P, int tile,
                                                   char* __restrict__ dst_tile, uint16_t* vt, int gt) {
   const int row = gt >> 4, ch = gt & 15;
@@ -17,12 +31,13 @@ __device__ __forceinline__ void tile_copy_phase_a(const char* __restrict__ src_p
   const uint4 kq = *reinterpret_cast<const uint4*>(ksrc);
   const uint4 vq = *reinterpret_cast<const uint4*>(ksrc + (size_t)P * kRowBytes);
   // K: chunk c = ch / 4, lane = row + 16 * (ch % 4)
-  *reinterpret_cast<uint4*>(dst_tile + ((ch >> 2) * 64 + (ch & 3) * 16 + row) * 16) = kq;
+  slot_store16<HANDOFF>(dst_tile + ((ch >> 2) * 64 + (ch & 3) * 16 + row) * 16, kq);
   *reinterpret_cast<uint4*>(vt + row * kHeadDim + ch * 8) = vq;
 }
 
 // Phase B: thread gt assembles destination unit gt of the V part (chunk c, lane i + 16 g): four
 // tokens 4g..4g+3 of dim 32c + i, then of dim 32c + 16 + i.
+template <bool HANDOFF = false>
 __device__ __forceinline__ void tile_copy_phase_b(char* __restrict__ dst_tile, const uint16_t* vt, int gt) {
   const int c = gt >> 6, g = (gt >> 4) & 3, i = gt & 15;
   uint16_t e[8];
@@ -35,7 +50,7 @@ __device__ __forceinline__ void tile_copy_phase_b(char* __restrict__ dst_tile, c
   outv.y = (u32)e[2] | ((u32)e[3] << 16);
   outv.z = (u32)e[4] | ((u32)e[5] << 16);
   outv.w = (u32)e[6] | ((u32)e[7] << 16);
-  *reinterpret_cast<uint4*>(dst_tile + kTilePartBytes + gt * 16) = outv;
+  slot_store16<HANDOFF>(dst_tile + kTilePartBytes + gt * 16, outv);
 }
 
 }  // namespace kvd

@@ -5,19 +5,15 @@
 // exact radix refinement in LDS on (score descending, page ascending) keys.
 #include "kvd_device.h"
 #include "kvd_internal.h"
+#include "kvd_score_body.h"
 
 namespace kvd {
 
 constexpr int kScoreThreads = 256;
 constexpr int kScoreWaves = kScoreThreads / kWave;
 
-// One block scores 256 * passes consecutive pages of one unit, each wave 64 * passes of them in
-// passes of 64.  A wave
-// load covers 4 summary rows (4 x 256 B): lane (r, c) = (lane / 16, lane % 16) holds dims
-// 8c..8c+7 of row r.  The 16 partial dot products of a row are summed with DPP row rotations;
-// after 16 loads lane (r, c) keeps the score of page base + 4c + r and the wave stores 64
-// consecutive scores.  The first summary loads are issued before the query is fetched, so the
-// block does not sit idle for a round trip before it starts streaming.
+// One block scores 256 * passes consecutive pages of one unit, each of its 4 waves 64 * passes of
+// them (see score_wave).
 template <bool BF16>
 __global__ __launch_bounds__(kScoreThreads) void score_kernel(const uint16_t* __restrict__ summ,  // [U][NP][D] of the layer
                                                              const uint16_t* __restrict__ q,     // [B][Hq][D]
@@ -25,64 +21,10 @@ __global__ __launch_bounds__(kScoreThreads) void score_kernel(const uint16_t* __
                                                              int NP, int G, int Hq, int Hkv, float scale, int u0, int passes) {
   const int u = blockIdx.y + u0;
   const int b = u / Hkv, h = u % Hkv;
-  const int lane = threadIdx.x & (kWave - 1), w = threadIdx.x / kWave;
-  const int r = lane >> 4, c = lane & 15;
+  const int w = threadIdx.x / kWave;
   const int wave_base = (blockIdx.x * kScoreWaves + w) * 64 * passes;
-  if (wave_base >= NP) return;
-  const uint16_t* srow = summ + (size_t)u * NP * kHeadDim + c * 8;
-
-  uint4 raw[8];
-  auto issue = [&](int base, int half) {
-#pragma unroll
-    for (int i = 0; i < 8; ++i) {
-      int page = base + 4 * (half * 8 + i) + r;
-      page = page < NP ? page : NP - 1;
-      raw[i] = load_stream16(srow + (size_t)page * kHeadDim);
-    }
-  };
-  issue(wave_base, 0);
-
-  float qbar[8];
-#pragma unroll
-  for (int e = 0; e < 8; ++e) qbar[e] = 0.f;
-  const uint16_t* qrow = q + ((size_t)b * Hq + (size_t)h * G) * kHeadDim + c * 8;
-  for (int g = 0; g < G; ++g) {
-    const uint4 qraw = *reinterpret_cast<const uint4*>(qrow + (size_t)g * kHeadDim);
-    float f[8];
-    cvt8<BF16>(qraw, f);
-#pragma unroll
-    for (int e = 0; e < 8; ++e) qbar[e] += f[e];
-  }
-  const float fg = (float)G;
-#pragma unroll
-  for (int e = 0; e < 8; ++e) qbar[e] = qbar[e] / fg;
-
-  for (int pass = 0; pass < passes; ++pass) {
-    const int base = wave_base + pass * 64;
-    if (base >= NP) break;
-    float mine = 0.f;
-#pragma unroll
-    for (int half = 0; half < 2; ++half) {
-      uint4 cur[8];
-#pragma unroll
-      for (int i = 0; i < 8; ++i) cur[i] = raw[i];
-      // next batch in flight while this one is reduced
-      if (half == 0) issue(base, 1);
-      else if (pass + 1 < passes && base + 64 < NP) issue(base + 64, 0);
-#pragma unroll
-      for (int i = 0; i < 8; ++i) {
-        float f[8];
-        cvt8<BF16>(cur[i], f);
-        float acc = 0.f;
-#pragma unroll
-        for (int e = 0; e < 8; ++e) acc = fmaf(qbar[e], f[e], acc);
-        acc = row16_allreduce_sum(acc);
-        if (c == half * 8 + i) mine = acc;
-      }
-    }
-    const int page = base + 4 * c + r;
-    if (page < NP) scores[(size_t)u * NP + page] = mine * scale;
-  }
+  score_wave<BF16, false>(summ + (size_t)u * NP * kHeadDim, q + ((size_t)b * Hq + (size_t)h * G) * kHeadDim,
+                          scores + (size_t)u * NP, NP, G, scale, wave_base, passes);
 }
 
 constexpr int kSelectThreads = 1024;

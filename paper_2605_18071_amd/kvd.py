@@ -46,7 +46,7 @@ EXPORTS = [
     "kvd_bind_summaries", "kvd_bind_host_store", "kvd_bind_slot_pool", "kvd_set_seq_lens",
     "kvd_build_summaries", "kvd_cache_reset", "kvd_cache_warm", "kvd_cache_export", "kvd_cache_import",
     "kvd_score_select", "kvd_cache_resolve", "kvd_sparse_decode_attn", "kvd_step", "kvd_step_trace",
-    "kvd_set_profiling", "kvd_get_stats", "kvd_reset_stats",
+    "kvd_set_profiling", "kvd_step_timeline", "kvd_get_stats", "kvd_reset_stats",
 ]
 
 _lib = None
@@ -81,6 +81,7 @@ def load() -> C.CDLL:
         "kvd_step": [vp, i32, i32, vp, vp, vp, vp],
         "kvd_step_trace": [vp, vp, vp, vp, vp, vp, vp, vp],
         "kvd_set_profiling": [vp, i32],
+        "kvd_step_timeline": [vp, C.POINTER(C.c_int64), i32, i32p],
         "kvd_get_stats": [vp, C.POINTER(KvdStats)],
         "kvd_reset_stats": [vp],
     }
@@ -229,8 +230,18 @@ class Kvd:
                                             _ptr(counts), _ptr(scores), _stream_handle(stream)), "kvd_step_trace")
 
     # ---- counters
-    def set_profiling(self, on: bool):
-        self._check(self.lib.kvd_set_profiling(self.ctx, 1 if on else 0), "kvd_set_profiling")
+    def set_profiling(self, mode):
+        self._check(self.lib.kvd_set_profiling(self.ctx, int(mode)), "kvd_set_profiling")
+
+    def step_timeline(self) -> torch.Tensor:
+        """[workgroups, 5] int64 records of the last single-launch step run under profiling mode 2:
+        ticks (100 MHz) at start / inputs ready / work done / exit, and the tag (see kvd.h)."""
+        n = C.c_int32()
+        probe = (C.c_int64 * 5)()
+        self._check(self.lib.kvd_step_timeline(self.ctx, probe, 0, C.byref(n)), "kvd_step_timeline")
+        buf = (C.c_int64 * (5 * n.value))()
+        self._check(self.lib.kvd_step_timeline(self.ctx, buf, n.value, C.byref(n)), "kvd_step_timeline")
+        return torch.tensor(list(buf), dtype=torch.int64).reshape(-1, 5)
 
     def stats(self) -> KvdStats:
         st = KvdStats()

@@ -24,11 +24,12 @@ FULL = {
 }
 
 
-@pytest.mark.parametrize("cfg", [3, 2, 4, 5])
-def test_full_size_sampled_parity(cfg):
+@pytest.mark.parametrize("cfg,mb", [(3, 0), (3, -1), (2, 0), (4, 0), (5, 0), (5, -1)])
+def test_full_size_sampled_parity(cfg, mb):
+    """mb = 0: the layer-step as a chain of kernels (what bench.py times); mb = -1: as one launch."""
     w, steps, sample = FULL[cfg]
     print(f"[cfg{cfg}] building workload", flush=True)
-    rig = R.Rig(w)
+    rig = R.Rig(w, micro_batches=mb)
     print(f"[cfg{cfg}] workload ready, building oracle units", flush=True)
     units = [R.OracleUnit(rig, l, b, h) for (l, b, h) in sample]
     rep = R.run_steps(rig, units, steps, check_dir_every=max(1, steps // 3), progress=f"cfg{cfg}-full")
