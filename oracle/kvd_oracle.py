@@ -17,6 +17,8 @@ index held in GPU memory, (2) fetch them, (3) compute sparse attention):
   select_pages     Top-K pages, sink/local pages always kept    (Background; Experiment "Baselines")
   LruWindow        the in-GPU window of recently critical pages (Motivation "critical KV window";
                    with LRU replacement                          Cache Management: LRU is the baseline policy)
+  LookaheadWindow  the same window with the paper's own policy:  (Cache Management, "Sliding Window w/
+                   the lowest current-step scores leave          Lookahead Eviction")
   attend           softmax attention over the selected tokens   (System Overview, step 3)
 
 Readings taken where the paper is silent (each one is also listed in the design
@@ -28,7 +30,14 @@ notes of the repository):
   * ties in the Top-K go to the lower page index;
   * sink / recent pages are selected unconditionally and count inside k;
   * every selected page gets stamp = step index; LRU victim = smallest
-    (stamp, page) among resident pages that are not selected in this step.
+    (stamp, page) among resident pages that are not selected in this step;
+  * lookahead eviction ranks resident pages by the page score of the current
+    step (the only importance known for pages outside the selection); the
+    victim is the lowest-scoring resident page not selected in this step, and
+    among equal scores the higher page index leaves first (the reverse of the
+    selection order).  The look-ahead pool of the evaluation (M = 2560 for
+    K = 2048) is read as "all scored pages": with every page score at hand a
+    finite pool only coarsens the order beyond rank M.
 
 Parity status.  select/LRU/attend/summaries are pinned in tests by brute force,
 closed forms, library routines and hand-worked fixtures (tests/golden).
@@ -181,11 +190,12 @@ class LruWindow:
     def resident(self):
         return sorted(self.stamp)
 
-    def resolve(self, sel, step):
+    def resolve(self, sel, step, scores=None, forced_evicted=None):
         """Process one step's selection.  Returns (hits, misses, evicted), each a
         sorted list of page indices.  Misses are inserted in ascending page
         order; when the window is full the victim is the resident page, not
-        selected in this step, with the smallest (stamp, page).
+        selected in this step, with the smallest (stamp, page).  `scores` and
+        `forced_evicted` are not used by this policy.
         """
         sel = [int(p) for p in sel if p >= 0]
         if len(sel) > self.capacity:
@@ -202,6 +212,56 @@ class LruWindow:
                 _, victim = min(cands)
                 del self.stamp[victim]
                 evicted.append(victim)
+            self.stamp[p] = int(step)
+        return hits, misses, sorted(evicted)
+
+
+class LookaheadWindow(LruWindow):
+    """The window with lookahead eviction (Cache Management, "Sliding Window w/
+    Lookahead Eviction": at each step the entries with the lowest current-step
+    scores are discarded, as they are least likely to be reused).  Stamps are
+    still kept (step of last selection) but play no part in the choice.
+    """
+
+    def resolve(self, sel, step, scores=None, forced_evicted=None):
+        """As LruWindow.resolve, but the victim is the resident page, not selected
+        in this step, with the lowest scores[page]; equal scores: the higher page
+        index leaves first.
+
+        scores         [NPvalid] fp64 page scores of this step.
+        forced_evicted if given, exactly these pages leave instead of the oracle's
+                       own choice (used by the parity harness after a score tie
+                       inside the 1e-6 band); they must be resident, unselected and
+                       as many as the step has to evict.
+        """
+        if scores is None:
+            raise ValueError("lookahead eviction needs the page scores of the step")
+        sel = [int(p) for p in sel if p >= 0]
+        if len(sel) > self.capacity:
+            raise ValueError("k exceeds capacity")
+        selset = set(sel)
+        hits = sorted(p for p in sel if p in self.stamp)
+        misses = sorted(p for p in sel if p not in self.stamp)
+        for p in hits:
+            self.stamp[p] = int(step)
+        evicted = []
+        if forced_evicted is not None:
+            forced = sorted(int(p) for p in forced_evicted)
+            need = max(0, len(self.stamp) + len(misses) - self.capacity)
+            if len(forced) != need or any(p not in self.stamp or p in selset for p in forced):
+                raise ValueError("forced eviction set is not admissible")
+            for p in forced:
+                del self.stamp[p]
+            evicted = forced
+            for p in misses:
+                self.stamp[p] = int(step)
+            return hits, misses, evicted
+        for p in misses:
+            if len(self.stamp) >= self.capacity:
+                cands = [(float(scores[r]), -r) for r in self.stamp if r not in selset]
+                _, neg = min(cands)
+                del self.stamp[-neg]
+                evicted.append(-neg)
             self.stamp[p] = int(step)
         return hits, misses, sorted(evicted)
 
@@ -244,7 +304,8 @@ def attend(q_group, keys, values, scale):
 # one unit, one step: the three stages in the paper's order
 # --------------------------------------------------------------------------- #
 def decode_unit_step(q_group, summaries, keys, values, window, step, *, k, page_size,
-                     seq_len, scale, sink_pages=0, recent_pages=0, forced_sel=None):
+                     seq_len, scale, sink_pages=0, recent_pages=0, forced_sel=None,
+                     forced_evicted=None):
     """select -> fetch bookkeeping -> attend for one unit.
 
     q_group   [G, D] fp64 (queries already rounded to the KV dtype by the caller)
@@ -252,13 +313,14 @@ def decode_unit_step(q_group, summaries, keys, values, window, step, *, k, page_
     window    LruWindow carried across steps
     forced_sel: if given, this selection replaces the oracle's own (used by the
               parity harness after a score tie inside the 1e-6 band).
+    forced_evicted: likewise for the victims of a LookaheadWindow.
     returns dict(scores, sel, hits, misses, evicted, out, lse)
     """
     qbar = pooled_query(q_group)
     scores = page_scores(qbar, summaries, scale)
     sel = select_pages(scores, k, sink_pages, recent_pages)
     used = sel if forced_sel is None else np.asarray(forced_sel, dtype=np.int32)
-    hits, misses, evicted = window.resolve(used, step)
+    hits, misses, evicted = window.resolve(used, step, scores=scores, forced_evicted=forced_evicted)
     toks = selected_tokens(used, page_size, seq_len)
     out, lse = attend(q_group, keys[toks], values[toks], scale)
     return dict(scores=scores, sel=sel, used=used, hits=hits, misses=misses,

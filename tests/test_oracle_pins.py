@@ -288,6 +288,73 @@ def test_lru_rejects_k_above_capacity_and_warm():
 
 
 # --------------------------------------------------------------------------- #
+# lookahead eviction
+# --------------------------------------------------------------------------- #
+def test_lookahead_golden_trace():
+    win = orc.LookaheadWindow(3)
+    for step, scores, sel, hits, misses, evicted, resident in H.read_golden("la_trace_5pages.txt"):
+        sc = np.array([float(x) for x in scores.split()])
+        assert orc.select_pages(sc, 2).tolist() == _ints(sel), step
+        h, m, e = win.resolve(_ints(sel), int(step), scores=sc)
+        assert (h, m, e) == (_ints(hits), _ints(misses), _ints(evicted)), step
+        assert win.resident() == _ints(resident), step
+
+
+def test_lookahead_with_recency_scores_is_lru():
+    """If the score of a resident page is the step at which it was last selected (plus a
+    page-increasing sliver that orders equal stamps as LRU does), "lowest score first" is
+    "least recently selected first": the policy must then reproduce the LRU trace."""
+    n_pages, k, cap = 48, 6, 15
+    la, lru = orc.LookaheadWindow(cap), orc.LruWindow(cap)
+    for t in range(80):
+        centre = (2 * t) % n_pages
+        w = np.exp(-0.2 * np.abs(np.arange(n_pages) - centre)) + 0.02
+        sel = sorted(RNG.choice(n_pages, size=k, replace=False, p=w / w.sum()).tolist())
+        recency = np.full(n_pages, -1.0)
+        for p, s in lru.stamp.items():
+            recency[p] = s
+        recency += np.arange(n_pages) * 2.0 ** -20
+        assert la.resolve(sel, t, scores=recency) == lru.resolve(sel, t)
+        assert la.stamp == lru.stamp
+
+
+@pytest.mark.parametrize("n_pages,k,cap", [(40, 6, 6), (40, 6, 11), (64, 8, 24), (30, 5, 30)])
+def test_lookahead_invariants_and_batch_formulation(n_pages, k, cap):
+    win = orc.LookaheadWindow(cap)
+    for t in range(60):
+        scores = np.round(RNG.normal(size=n_pages), 1)            # one decimal: plenty of exact ties
+        sel = orc.select_pages(scores, k).tolist()
+        before = dict(win.stamp)
+        h, m, e = win.resolve(sel, t, scores=scores)
+        need = max(0, len(before) + len(m) - cap)
+        assert len(e) == need and not (set(e) & set(sel)) and set(e) <= set(before)
+        assert len(h) + len(m) == k and len(win.stamp) <= cap
+        # a different route: rank all unselected residents once, lowest (score, -page) first
+        cands = sorted((scores[p], -p) for p in before if p not in set(sel))
+        assert e == sorted(-n for _, n in cands[:need])
+        # whoever stayed does not score below whoever left
+        kept = [p for p in before if p not in set(sel) and p not in set(e)]
+        if e and kept:
+            assert max(scores[p] for p in e) <= min(scores[p] for p in kept)
+        assert all(win.stamp[p] == t for p in sel)
+
+
+def test_lookahead_forced_eviction_and_errors():
+    win = orc.LookaheadWindow(3)
+    sc = np.array([0.5, 0.4, 0.3, 0.2, 0.1, 0.0])
+    win.warm([0, 1, 2])
+    with pytest.raises(ValueError):
+        win.resolve([3, 4], 0)                                      # no scores
+    with pytest.raises(ValueError):
+        win.resolve([3, 4], 0, scores=sc, forced_evicted=[0])       # one victim short
+    with pytest.raises(ValueError):
+        win.resolve([3, 4], 0, scores=sc, forced_evicted=[0, 5])    # page 5 is not resident
+    assert win.resolve([3, 4], 0, scores=sc, forced_evicted=[0, 1]) == ([], [3, 4], [0, 1])
+    assert win.resident() == [2, 3, 4]
+    assert win.resolve([0, 3], 1, scores=sc) == ([3], [0], [4])     # own choice: lowest score (page 4) leaves
+
+
+# --------------------------------------------------------------------------- #
 # attention
 # --------------------------------------------------------------------------- #
 def test_attention_closed_form_fixture():
