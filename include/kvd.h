@@ -53,7 +53,11 @@ typedef enum {
 } kvd_status;
 
 typedef enum { KVD_F16 = 0, KVD_BF16 = 1 } kvd_dtype;
-typedef enum { KVD_EVICT_LRU = 0 } kvd_policy;
+/* Which resident pages leave a full window (Cache Management, "Sliding Window w/ Lookahead
+ * Eviction"): LRU drops the least recently selected pages; LOOKAHEAD drops the pages with the
+ * lowest page score of the current step (equal scores: the higher page index first), the
+ * attention-derived importance that is known for every page of the index. */
+typedef enum { KVD_EVICT_LRU = 0, KVD_EVICT_LOOKAHEAD = 1 } kvd_policy;
 
 typedef struct {
   int32_t n_layers;        /* L */
@@ -172,8 +176,9 @@ int kvd_score_select(kvd_ctx* ctx, int32_t layer, const void* q, int32_t* sel_pa
  *   evicted    [B][Hkv][k] int32 out or NULL: pages dropped in this step, -1 padded, unordered.
  *   counts     [B][Hkv][3] int32 out or NULL: hits, misses, evictions.
  * Hits are re-stamped with `step`; misses take free slots first, then the slots of the resident
- * pages, not selected in this step, with the smallest (stamp, page).  `step` must not decrease
- * for a layer.  With do_gather != 0 the missed pages are then copied from the host store into
+ * pages, not selected in this step, with the smallest (stamp, page) — under KVD_EVICT_LOOKAHEAD
+ * with the smallest (score, -page), read from where the most recent kvd_score_select of this
+ * context left its scores (KVD_ERR_STATE if there was none).  `step` must not decrease for a layer.  With do_gather != 0 the missed pages are then copied from the host store into
  * their slots on `stream`.  With do_gather == 0 only the directory changes (slot contents are
  * stale).  sel_pages must hold distinct pages in ascending order, as stage 1 writes them. */
 int kvd_cache_resolve(kvd_ctx* ctx, int32_t layer, int32_t step, const int32_t* sel_pages, int32_t* sel_slots,

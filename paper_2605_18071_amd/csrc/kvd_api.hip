@@ -24,7 +24,7 @@ static bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 
 static int validate_config(const kvd_config* c) {
   if (c == nullptr) return KVD_ERR_ARG;
   if (c->kv_dtype != KVD_F16 && c->kv_dtype != KVD_BF16) return KVD_ERR_DTYPE;
-  if (c->policy != KVD_EVICT_LRU) return KVD_ERR_ARG;
+  if (c->policy != KVD_EVICT_LRU && c->policy != KVD_EVICT_LOOKAHEAD) return KVD_ERR_ARG;
   if (c->n_layers < 1 || c->batch < 1 || c->n_q_heads < 1 || c->n_kv_heads < 1) return KVD_ERR_SHAPE;
   if (c->head_dim != 128) return KVD_ERR_SHAPE;
   if (c->n_q_heads % c->n_kv_heads != 0) return KVD_ERR_SHAPE;
@@ -324,6 +324,7 @@ int kvd_score_select(kvd_ctx* ctx, int32_t layer, const void* q, int32_t* sel_pa
   if (!ctx->summaries) return KVD_ERR_STATE;
   hipStream_t s = static_cast<hipStream_t>(stream);
   float* sc = scores ? scores : ctx->d_scores;
+  ctx->last_scores = sc;
   HIP_TRY(ctx, kvd_launch_score(ctx, layer, q, sc, 0, ctx->U, s));
   if (kvd_fast_path_ok(ctx))
     HIP_TRY(ctx, kvd_launch_select_resolve(ctx, layer, 0, true, false, false, sc, sel_pages, nullptr, nullptr, nullptr,
@@ -337,12 +338,13 @@ int kvd_cache_resolve(kvd_ctx* ctx, int32_t layer, int32_t step, const int32_t* 
                       int32_t* hit_mask, int32_t* evicted, int32_t* counts, int32_t do_gather, void* stream) {
   if (!ctx || !sel_pages || !sel_slots || layer < 0 || layer >= ctx->L) return KVD_ERR_ARG;
   if (do_gather && (!ctx->pool || !ctx->store_dev)) return KVD_ERR_STATE;
+  if (ctx->cfg.policy == KVD_EVICT_LOOKAHEAD && ctx->last_scores == nullptr) return KVD_ERR_STATE;
   hipStream_t s = static_cast<hipStream_t>(stream);
   int32_t* hm = hit_mask ? hit_mask : ctx->d_hit_mask;
   int32_t* ev = evicted ? evicted : ctx->d_evicted;
   int32_t* cn = counts ? counts : ctx->d_counts;
   if (kvd_fast_path_ok(ctx)) {
-    HIP_TRY(ctx, kvd_launch_select_resolve(ctx, layer, step, false, true, do_gather != 0, nullptr,
+    HIP_TRY(ctx, kvd_launch_select_resolve(ctx, layer, step, false, true, do_gather != 0, ctx->last_scores,
                                            const_cast<int32_t*>(sel_pages), sel_slots, hm, ev, cn, 0, ctx->U, s));
   } else {
     HIP_TRY(ctx, kvd_launch_resolve(ctx, layer, step, sel_pages, sel_slots, hm, ev, cn, 0, ctx->U, s));
@@ -419,6 +421,7 @@ int kvd_step(kvd_ctx* ctx, int32_t layer, int32_t step, const void* q, float* ou
   kvd_ctx* c = ctx;
   hipStream_t s = static_cast<hipStream_t>(stream);
   ++c->n_steps;
+  c->last_scores = c->d_scores;
   if (*c->error_host != 0) return KVD_ERR_STATE;   // an earlier single-launch step gave up waiting
   if (c->profiling == 1) return step_profiled(c, layer, step, q, out, lse, s);
   if (c->single_launch) {

@@ -28,13 +28,15 @@ struct ResolveArgs {
   int32_t* miss_list;        // [U][k][2]
   int32_t* miss_count;       // [U]
   unsigned long long* stats; // hits, misses, evictions
-  int NP, Cmax, k, step, u0;
+  const float* scores;       // [U][NP] page scores of this step (lookahead eviction only)
+  int NP, Cmax, k, step, u0, lookahead;
 };
 
 // One block per unit.
 //  1. look every selected page up in page_to_slot; hits are re-stamped and flagged in an LDS bitmap;
-//  2. e = max(0, resident + misses - capacity) pages must leave: the e smallest (stamp, page)
-//     among resident slots that were not hit (exact k-th smallest on the 64-bit key);
+//  2. e = max(0, resident + misses - capacity) pages must leave: the e smallest (stamp, page) —
+//     under lookahead eviction the e smallest (score of this step, -page) — among resident slots
+//     that were not hit (exact k-th smallest on the 64-bit key);
 //  3. free slots and victim slots, in ascending slot order, are handed to the misses in ascending
 //     page order; the directory is updated and the (page, slot) miss list written for the fetch.
 __global__ __launch_bounds__(kResolveThreads) void resolve_kernel(ResolveArgs a) {
@@ -99,7 +101,14 @@ __global__ __launch_bounds__(kResolveThreads) void resolve_kernel(ResolveArgs a)
   auto victim_key = [&](int s, u64& key) -> bool {
     const int p = spage[s];
     if (p < 0 || ((hit_bitmap[s >> 5] >> (s & 31)) & 1u)) return false;
-    key = ((u64)((u32)sstamp[s] ^ 0x80000000u) << 32) | (u32)p;
+    if (a.lookahead) {
+      // ascending in (score, -page): the lowest score leaves first, among equals the higher page
+      const u32 x = as_u32(a.scores[(size_t)u * a.NP + p] + 0.0f);
+      const u32 asc = (x & 0x80000000u) ? ~x : (x | 0x80000000u);
+      key = ((u64)asc << 32) | (u32)(~(u32)p);
+    } else {
+      key = ((u64)((u32)sstamp[s] ^ 0x80000000u) << 32) | (u32)p;
+    }
     return true;
   };
   u64 thr = 0;
@@ -294,6 +303,8 @@ hipError_t kvd_launch_resolve(kvd_ctx* c, int layer, int step, const int32_t* se
   a.miss_count = c->d_miss_count;
   a.stats = c->d_stats;
   a.NP = c->NP; a.Cmax = c->Cmax; a.k = c->k; a.step = step; a.u0 = u0;
+  a.lookahead = c->cfg.policy == KVD_EVICT_LOOKAHEAD ? 1 : 0;
+  a.scores = c->last_scores;
   hipLaunchKernelGGL(resolve_kernel, dim3(u1 - u0), dim3(kResolveThreads), 0, s, a);
   return hipGetLastError();
 }

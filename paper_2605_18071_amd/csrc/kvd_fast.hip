@@ -56,6 +56,7 @@ kvd::FastArgs kvd_fast_args(kvd_ctx* c, int layer, int step, bool do_gather, con
   a.sink = c->cfg.sink_pages; a.recent = c->cfg.recent_pages; a.Hkv = c->Hkv; a.step = step; a.u0 = u0;
   a.do_gather = (do_gather && a.store && a.pool) ? 1 : 0;
   a.tiled = c->tiled;
+  a.lookahead = c->cfg.policy == KVD_EVICT_LOOKAHEAD ? 1 : 0;
   a.page_bytes = (unsigned)c->page_bytes;
   return a;
 }

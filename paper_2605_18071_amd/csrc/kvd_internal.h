@@ -46,6 +46,7 @@ struct kvd_ctx {
   int32_t* d_slot_stamp;    // [L][U][Cmax]
   int32_t* d_resident;      // [L][U]
   float* d_scores;          // [U][NP]
+  const float* last_scores; // where the scores of the most recent scoring went (d_scores or the caller's buffer)
   int32_t* d_sel_pages;     // [U][k]
   int32_t* d_sel_slots;     // [U][k]
   int32_t* d_hit_mask;      // [U][k]

@@ -40,6 +40,7 @@ struct FastArgs {
   const char* store;          // host store of the layer, [U][NP] pages (device-visible address)
   char* pool;                 // slot pool of the layer, [U][Cmax] slots
   int NP, P, k, Cmax, sink, recent, Hkv, step, u0, do_gather, tiled;
+  int lookahead;              // victims by lowest current-step score (needs `scores`) instead of by age
   unsigned page_bytes;
 };
 
@@ -62,7 +63,7 @@ struct FastSmem {
   float red_min[NW], red_max[NW];
   int red_cnt[NW];
   u64 thr;
-  int cand_n, bin, below, n_hits, n_ev;
+  int cand_n, bin, below, n_ev;
   SelectSmem generic;
 };
 
@@ -147,6 +148,14 @@ __device__ __forceinline__ u64 two_level_select(KeyOf key, BktOf bkt, int need, 
   return sm.thr;
 }
 
+// Victim key of lookahead eviction: ascending in (score, -page), so that the lowest score leaves
+// first and, among equal scores, the higher page.
+__device__ __forceinline__ u64 lookahead_victim_key(float s, int page) {
+  const u32 x = as_u32(s + 0.0f);
+  const u32 asc = (x & 0x80000000u) ? ~x : (x | 0x80000000u);
+  return ((u64)asc << 32) | (u32)(~(u32)page);
+}
+
 __device__ __forceinline__ int victim_bucket(long long age, int page, int NP) {
   // one group of 32 buckets per age (step - stamp) below 64, split by page range; everything older
   // shares bucket 0; the newest class (age <= 1) shares bucket 2047
@@ -222,14 +231,20 @@ __device__ __forceinline__ void select_resolve_body(const FastArgs& a, int u, Fa
     for (int i = tid; i < KVD_FAST_MAX_CAPACITY / 32; i += NT) sm.hit_bitmap[i] = 0;
     for (int i = tid; i < k; i += NT) sm.assign[i] = kAbsent;
   }
-  if (tid == 0) { sm.cand_n = 0; sm.n_hits = 0; sm.n_ev = 0; }
+  if (tid == 0) { sm.cand_n = 0; sm.n_ev = 0; }
   __syncthreads();
+  float vs[CPT];                                       // lookahead eviction: this step's score of the page in each slot
   if (DO_RESOLVE) {
 #pragma unroll
     for (int j = 0; j < CPT; ++j) {
       const int sl = tid * CPT + j;
       if (sl >= C && sp[j] != -2) sp[j] = -2;          // slots beyond this unit's capacity do not exist
       if (sp[j] >= 0) sm.p2s[sp[j]] = (uint16_t)sl;
+      vs[j] = 0.f;
+      if (a.lookahead && sp[j] >= 0) {
+        const float* sc = a.scores + (size_t)u * a.NP + sp[j];
+        vs[j] = HANDOFF ? load_agent(sc) : *sc;
+      }
     }
   }
 
@@ -358,9 +373,11 @@ __device__ __forceinline__ void select_resolve_body(const FastArgs& a, int u, Fa
       }
     }
   }
-  if (my_hits) atomicAdd(&sm.n_hits, my_hits);
-  int m;
-  int miss_rank = fast_scan<NT>(my_misses, sm, flip, m);   // barrier inside: the hit bitmap is complete
+  // one scan counts both: misses in the low half, hits in the high half (k <= 2048 each)
+  int mh;
+  const int packed_rank = fast_scan<NT>(my_misses | (my_hits << 16), sm, flip, mh);   // barrier inside: the hit bitmap is complete
+  const int m = mh & 0xffff, n_hits = mh >> 16;
+  int miss_rank = packed_rank & 0xffff;
   const int e = (R + m - C) > 0 ? (R + m - C) : 0;
 
   // ---- victims: the e smallest (stamp, page) among resident slots that were not hit
@@ -371,9 +388,36 @@ __device__ __forceinline__ void select_resolve_body(const FastArgs& a, int u, Fa
   u32 cand_mask = 0;
 #pragma unroll
   for (int j = 0; j < CPT; ++j) cand_mask |= is_cand(j) ? (1u << j) : 0u;
-  auto vkey_of = [&](int j) -> u64 { return ((u64)((u32)ss[j] ^ 0x80000000u) << 32) | (u32)sp[j]; };
+  // lookahead eviction buckets the candidates' scores linearly between their extremes
+  float vmin = 0.f, vinv = 0.f;
+  if (a.lookahead && e > 0) {
+    float lo = INFINITY, hi = -INFINITY;
+#pragma unroll
+    for (int j = 0; j < CPT; ++j)
+      if ((cand_mask >> j) & 1u) {
+        lo = fminf(lo, vs[j]);
+        hi = fmaxf(hi, vs[j]);
+      }
+    lo = wave_allreduce_min(lo);
+    hi = wave_allreduce_max(hi);
+    if (lane == 0) { sm.red_min[w] = lo; sm.red_max[w] = hi; }
+    __syncthreads();
+    lo = sm.red_min[0]; hi = sm.red_max[0];
+#pragma unroll
+    for (int i = 1; i < NW; ++i) {
+      lo = fminf(lo, sm.red_min[i]);
+      hi = fmaxf(hi, sm.red_max[i]);
+    }
+    vmin = lo;
+    vinv = hi > lo ? 2047.0f / (hi - lo) : 0.f;
+  }
+  auto la_bucket = [&](float v) -> int { return (int)fminf(fmaxf((v - vmin) * vinv, 0.f), 2047.f); };
+  auto vkey_of = [&](int j) -> u64 {
+    return a.lookahead ? lookahead_victim_key(vs[j], sp[j]) : ((u64)((u32)ss[j] ^ 0x80000000u) << 32) | (u32)sp[j];
+  };
   auto vbkt_of = [&](int j) -> int {
-    return ((cand_mask >> j) & 1u) ? victim_bucket((long long)a.step - (long long)ss[j], sp[j], a.NP) : -1;
+    if (!((cand_mask >> j) & 1u)) return -1;
+    return a.lookahead ? la_bucket(vs[j]) : victim_bucket((long long)a.step - (long long)ss[j], sp[j], a.NP);
   };
   u64 vthr = 0;
   if (e > 0) {
@@ -381,6 +425,13 @@ __device__ __forceinline__ void select_resolve_body(const FastArgs& a, int u, Fa
       auto fn = [&](int sl, u64& kk) -> bool {
         const int p = spage[sl];
         if (p < 0 || ((sm.hit_bitmap[sl >> 5] >> (sl & 31)) & 1u)) return false;
+        if (a.lookahead) {
+          const float* sc = a.scores + (size_t)u * a.NP + p;
+          const float v = HANDOFF ? load_agent(sc) : *sc;
+          if (la_bucket(v) != bin) return false;
+          kk = lookahead_victim_key(v, p);
+          return true;
+        }
         const int st = sstamp[sl];
         if (victim_bucket((long long)a.step - (long long)st, p, a.NP) != bin) return false;
         kk = ((u64)((u32)st ^ 0x80000000u) << 32) | (u32)p;
@@ -442,10 +493,10 @@ __device__ __forceinline__ void select_resolve_body(const FastArgs& a, int u, Fa
   if (tid == 0) {
     a.resident[u] = R + m - e;
     a.miss_count[u] = m;
-    a.counts[u * 3 + 0] = sm.n_hits;
+    a.counts[u * 3 + 0] = n_hits;
     a.counts[u * 3 + 1] = m;
     a.counts[u * 3 + 2] = e;
-    atomicAdd(&a.stats[0], (unsigned long long)sm.n_hits);
+    atomicAdd(&a.stats[0], (unsigned long long)n_hits);
     atomicAdd(&a.stats[1], (unsigned long long)m);
     atomicAdd(&a.stats[2], (unsigned long long)e);
   }

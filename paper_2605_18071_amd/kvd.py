@@ -17,7 +17,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libkvd.so")
 
 KVD_F16, KVD_BF16 = 0, 1
-KVD_EVICT_LRU = 0
+KVD_EVICT_LRU, KVD_EVICT_LOOKAHEAD = 0, 1
 OK, ERR_ARG, ERR_SHAPE, ERR_CAPACITY, ERR_DTYPE, ERR_HIP, ERR_STATE = 0, -1, -2, -3, -4, -5, -6
 
 
@@ -122,7 +122,7 @@ class Kvd:
 
     def __init__(self, *, n_layers, batch, n_q_heads, n_kv_heads, page_size, max_pages, topk_pages, capacity_max,
                  kv_dtype, head_dim=128, sink_pages=0, recent_pages=0, softmax_scale=0.0, capacity=None,
-                 physical_layers=0, micro_batches=0, attn_splits=0):
+                 physical_layers=0, micro_batches=0, attn_splits=0, policy=KVD_EVICT_LRU):
         self.lib = load()
         self._cap = None
         cfg = KvdConfig()
@@ -130,7 +130,7 @@ class Kvd:
         cfg.head_dim, cfg.page_size, cfg.max_pages, cfg.topk_pages = head_dim, page_size, max_pages, topk_pages
         cfg.sink_pages, cfg.recent_pages = sink_pages, recent_pages
         cfg.kv_dtype = {torch.float16: KVD_F16, torch.bfloat16: KVD_BF16}.get(kv_dtype, kv_dtype)
-        cfg.policy = KVD_EVICT_LRU
+        cfg.policy = {"lru": KVD_EVICT_LRU, "lookahead": KVD_EVICT_LOOKAHEAD}.get(policy, policy)
         cfg.softmax_scale = softmax_scale
         cfg.capacity_max = capacity_max
         if capacity is not None:

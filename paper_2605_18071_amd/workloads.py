@@ -59,6 +59,7 @@ class Workload:
     recent_pages: int = 0
     physical_layers: int = 0      # 0 -> n_layers
     warm: str = "cold"            # "cold" | "full" | "recent"
+    policy: str = "lru"           # cache replacement: "lru" | "lookahead"
     seed: int = 0
 
     @property

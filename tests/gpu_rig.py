@@ -32,7 +32,8 @@ class Rig:
         self.kvd = K.Kvd(n_layers=L, batch=B, n_q_heads=w.n_q_heads, n_kv_heads=Hkv, page_size=P, max_pages=NP,
                          topk_pages=w.topk_pages, capacity_max=w.capacity, kv_dtype=w.torch_dtype,
                          sink_pages=w.sink_pages, recent_pages=w.recent_pages, capacity=capacity,
-                         physical_layers=w.physical_layers, micro_batches=micro_batches, attn_splits=attn_splits)
+                         physical_layers=w.physical_layers, micro_batches=micro_batches, attn_splits=attn_splits,
+                         policy=w.policy)
         self.kvd.bind_summaries(self.summaries)
         self.kvd.bind_host_store(self.store)
         self.kvd.bind_slot_pool(self.pool)
@@ -115,21 +116,24 @@ class OracleUnit:
         self.seq_len = rig.seq_lens[b]
         self.code = H.dtype_code(w.torch_dtype)
         self.summ = orc.page_summaries(self.keys, w.page, self.seq_len, self.code)
-        self.window = orc.LruWindow(rig.cap(layer, self.u))
+        make = orc.LookaheadWindow if w.policy == "lookahead" else orc.LruWindow
+        self.window = make(rig.cap(layer, self.u))
         self.window.warm(rig.warm_list(b), stamp=-1)
         self.scale = 1.0 / math.sqrt(w.head_dim)
 
-    def step(self, t: int, q_layer: torch.Tensor, forced_sel=None):
+    def step(self, t: int, q_layer: torch.Tensor, forced_sel=None, forced_evicted=None):
         w = self.rig.w
         qg = H.f64(q_layer[self.b, self.h * w.group:(self.h + 1) * w.group])
         return orc.decode_unit_step(qg, self.summ, self.keys, self.values, self.window, t, k=w.topk_pages,
                                     page_size=w.page, seq_len=self.seq_len, scale=self.scale,
-                                    sink_pages=w.sink_pages, recent_pages=w.recent_pages, forced_sel=forced_sel)
+                                    sink_pages=w.sink_pages, recent_pages=w.recent_pages, forced_sel=forced_sel,
+                                    forced_evicted=forced_evicted)
 
 
 class StepReport:
     def __init__(self):
         self.tie_divergences = 0
+        self.victim_tie_divergences = 0
         self.max_attn_err = 0.0
         self.max_lse_err = 0.0
         self.max_score_err = 0.0
@@ -169,6 +173,7 @@ def compare_unit(rig: Rig, ou: OracleUnit, t: int, q_layer: torch.Tensor, rep: S
         assert ok, f"selection differs outside the tie band at unit {u} step {t}: {msg}"
         rep.tie_divergences += 1
         forced = g_sel
+    before = dict(ou.window.stamp)
     want = ou.step(t, q_layer, forced_sel=forced)
 
     # cache trace: hit / miss / evicted sets, bit-exact
@@ -178,6 +183,16 @@ def compare_unit(rig: Rig, ou: OracleUnit, t: int, q_layer: torch.Tensor, rep: S
     g_miss = sorted(g_sel[valid & (hm == 0)].tolist())
     ev = rig.n_evicted[u]
     g_ev = sorted(ev[ev >= 0].tolist())
+    if w.policy == "lookahead" and g_ev != want["evicted"]:
+        # victims are chosen by score: a different set is accepted only inside the tie band, and
+        # the oracle then continues from the GPU's choice
+        used = set(int(p) for p in want["used"] if p >= 0)
+        cands = [p for p in before if p not in used]
+        ok, msg = H.eviction_is_valid(o_scores, cands, g_ev, len(want["evicted"]))
+        assert ok, f"victims differ outside the tie band at unit {u} step {t}: {msg}"
+        rep.victim_tie_divergences += 1
+        ou.window.stamp = before
+        want = ou.step(t, q_layer, forced_sel=forced, forced_evicted=g_ev)
     assert g_hits == want["hits"], f"hit set differs at unit {u} step {t}"
     assert g_miss == want["misses"], f"miss set differs at unit {u} step {t}"
     assert g_ev == want["evicted"], f"evicted set differs at unit {u} step {t}"
@@ -243,6 +258,6 @@ def run_steps(rig: Rig, units: List[OracleUnit], steps: int, *, layers: Optional
             if check_dir_every and (t % check_dir_every == 0 or t == steps - 1):
                 check_directory(rig, l, by_layer[l])
         if progress:
-            print(f"[{progress}] step {t} ok: units {rep.unit_steps} ties {rep.tie_divergences} "
+            print(f"[{progress}] step {t} ok: units {rep.unit_steps} ties {rep.tie_divergences}+{rep.victim_tie_divergences} "
                   f"attn_err {rep.max_attn_err:.2e} hit_rate {rep.hits / max(1, rep.hits + rep.misses):.3f}", flush=True)
     return rep

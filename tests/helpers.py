@@ -67,6 +67,29 @@ def selection_is_valid(scores64: np.ndarray, sel: np.ndarray, k: int, sink: int 
     return True, ""
 
 
+def eviction_is_valid(scores64: np.ndarray, candidates, evicted, need: int, eps: float = TIE_EPS):
+    """The acceptance rule for the victims of lookahead eviction when they differ from the
+    oracle's at a near-tie: `need` distinct pages out of `candidates` (resident, not selected),
+    containing every candidate scoring below v* - eps and none scoring above v* + eps, where v*
+    is the need-th lowest candidate score.  Returns (ok, message)."""
+    cands = sorted(int(p) for p in candidates)
+    ev = sorted(int(p) for p in evicted)
+    if len(ev) != need or len(set(ev)) != need:
+        return False, f"{len(ev)} victims, {need} needed"
+    if not set(ev) <= set(cands):
+        return False, "a victim is not an unselected resident page"
+    if need == 0 or need == len(cands):
+        return True, ""
+    v = np.sort(np.asarray([scores64[p] for p in cands]))[need - 1]
+    must = {p for p in cands if scores64[p] < v - eps}
+    never = {p for p in cands if scores64[p] > v + eps}
+    if not must <= set(ev):
+        return False, f"pages clearly below the cut stayed: {sorted(must - set(ev))[:8]}"
+    if never & set(ev):
+        return False, f"pages clearly above the cut left: {sorted(never & set(ev))[:8]}"
+    return True, ""
+
+
 def attn_rel_err(got: np.ndarray, want: np.ndarray) -> float:
     """max over rows of ||got - want||_inf / max(||want||_inf, 1e-6)."""
     got = got.reshape(-1, got.shape[-1]).astype(np.float64)

@@ -337,6 +337,72 @@ def test_micro_batches_and_per_unit_capacities_give_identical_results():
         assert H.attn_rel_err(a[4], b[4]) <= 1e-5
 
 
+# --------------------------------------------------------------------------- #
+# lookahead eviction
+# --------------------------------------------------------------------------- #
+def _tight(cfg):
+    """A scaled configuration whose window is small enough to evict at nearly every step."""
+    w = SCALED[cfg]
+    return w.replace(policy="lookahead", capacity=w.topk_pages + w.topk_pages // 6, steps=w.steps + 6)
+
+
+@pytest.mark.parametrize("mb", [-1, 1, 2], ids=["single-launch", "kernel-chain", "two-groups"])
+@pytest.mark.parametrize("cfg", [2, 3, 5])
+def test_lookahead_step_parity(cfg, mb):
+    w = _tight(cfg)
+    rig = R.Rig(w, micro_batches=mb)
+    units = all_units(rig)
+    rep = R.run_steps(rig, units, w.steps, check_dir_every=3, progress=f"cfg{cfg}-lookahead-mb{mb}")
+    assert rep.unit_steps == w.steps * w.n_layers * w.units
+    assert rep.tie_divergences <= 2 and rep.victim_tie_divergences <= 2
+    st = rig.kvd.stats()
+    assert st.evictions > w.n_layers * w.units                          # the policy was exercised
+    rig.close()
+
+
+def test_lookahead_size_agnostic_kernels_and_separate_entry_points(monkeypatch):
+    """The same policy through the size-agnostic resolve kernel, driven stage by stage:
+    kvd_score_select leaves the scores that kvd_cache_resolve ranks the victims by."""
+    monkeypatch.setenv("KVD_GENERIC_SELECT", "1")
+    w = _tight(3)
+    rig = R.Rig(w)
+    units = all_units(rig)
+    rep = R.StepReport()
+    for t, q in enumerate(W.query_stream(w, rig.q0, w.steps, R.DEV)):
+        rig.kvd.score_select(0, q[0], rig.sel_pages, rig.scores)
+        rig.kvd.cache_resolve(0, t, rig.sel_pages, rig.sel_slots, rig.hit_mask, rig.evicted, rig.counts, do_gather=True)
+        rig.kvd.sparse_decode_attn(0, q[0], rig.sel_pages, rig.sel_slots, rig.out, rig.lse)
+        torch.cuda.synchronize()
+        rig.n_sel_pages, rig.n_sel_slots = rig.sel_pages.cpu().numpy(), rig.sel_slots.cpu().numpy()
+        rig.n_hit_mask, rig.n_evicted = rig.hit_mask.cpu().numpy(), rig.evicted.cpu().numpy()
+        rig.n_counts, rig.n_scores = rig.counts.cpu().numpy(), rig.scores.cpu().numpy()
+        rig.n_out, rig.n_lse = rig.out.cpu().numpy(), rig.lse.cpu().numpy()
+        for ou in units:
+            R.compare_unit(rig, ou, t, q[0], rep)
+    R.check_directory(rig, 0, units)
+    assert rep.tie_divergences <= 2 and rep.victim_tie_divergences <= 2
+    assert rig.kvd.stats().evictions > 0
+    rig.close()
+
+
+def test_lookahead_exact_ties_drop_the_higher_page():
+    """Pages with identical summary rows score bit-identically on both sides, so among them only
+    the tie rule decides who leaves: GPU and oracle must agree without any tolerance."""
+    w = small("la-ties", ctx=16 * 200, topk_pages=16, capacity=24, heavy_count=0, policy="lookahead", steps=10)
+    rig = R.Rig(w, build_index=False)
+    base = torch.randn(w.units, 12, w.head_dim, device=R.DEV)
+    idx = torch.randint(0, 12, (w.units, w.n_pages), device=R.DEV)
+    summ = torch.gather(base, 1, idx[:, :, None].expand(-1, -1, w.head_dim)).to(w.torch_dtype)
+    rig.summaries.copy_(summ.view(rig.summaries.shape))
+    units = all_units(rig)
+    for ou in units:                                                  # the oracle scores the same index
+        ou.summ = H.f64(rig.summaries[0, ou.b, ou.h])
+    rep = R.run_steps(rig, units, w.steps)
+    assert rep.tie_divergences == 0 and rep.victim_tie_divergences == 0
+    assert rig.kvd.stats().evictions > 0
+    rig.close()
+
+
 @pytest.mark.parametrize("cfg", [2, 5])
 def test_size_agnostic_select_resolve_kernels(cfg, monkeypatch):
     """The register-resident fused kernel covers up to 16384 pages and 4096 slots per unit; larger
