@@ -40,7 +40,7 @@ PMC_TRAFFIC_BYTES = {("cfg3", "attend"): 270482432, ("cfg3", "score"): 273769472
 def describe(w) -> str:
     return (f"{w.name}: L={w.n_layers} B={w.batch} ctx={w.ctx} page={w.page} heads={w.n_q_heads}q/{w.n_kv_heads}kv "
             f"D={w.head_dim} {w.dtype} k={w.topk_pages} pages ({w.topk_pages * w.page} tokens) "
-            f"cache={w.capacity} pages/unit ({100.0 * w.capacity / w.n_pages:.0f}%) {w.importance} importance, rho={w.rho}")
+            f"cache={w.capacity} pages/unit ({100.0 * w.capacity / w.n_pages:.0f}%, {w.policy}) {w.importance} importance, rho={w.rho}")
 
 
 def cpu_baseline(w, store, q_list, seconds: float):
@@ -62,7 +62,7 @@ def cpu_baseline(w, store, q_list, seconds: float):
         kv = store[0, b, h].to(torch.float64).numpy()
         keys, vals = kv[:, 0].reshape(-1, w.head_dim), kv[:, 1].reshape(-1, w.head_dim)
         summ = orc.page_summaries(keys, w.page, w.ctx, code)            # set-up, not timed
-        win = orc.LruWindow(w.capacity)
+        win = (orc.LookaheadWindow if w.policy == "lookahead" else orc.LruWindow)(w.capacity)
         units += 1
         for t, q in enumerate(q_list):
             qg = q[b, h * w.group:(h + 1) * w.group].to(torch.float64).numpy()
@@ -84,15 +84,43 @@ def cpu_baseline(w, store, q_list, seconds: float):
     }
 
 
+def step_timeline(ctx, t, q, out, stream):
+    """One more all-hit step of the single-launch kernel with its per-workgroup clock readings on:
+    when each role's workgroups were dispatched, how long they waited for their inputs, how long
+    they worked (microseconds from the first workgroup's start; GPU wall clock, 100 MHz)."""
+    import numpy as np
+    import torch
+    ctx.set_profiling(2)
+    ctx.step(0, t, q, out, stream=stream)
+    torch.cuda.synchronize()
+    rec = ctx.step_timeline().numpy()
+    ctx.set_profiling(0)
+    us = (rec[:, :4] - rec[:, 0].min()) / 100.0
+    role = rec[:, 4] & 0xff
+    res = {"workgroups": int(len(rec)), "kernel_us": float(us[:, 3].max())}
+    for r, name in enumerate(["score", "select_resolve", "attend"]):
+        x = us[role == r]
+        res[name] = {"workgroups": int(len(x)), "first_start_us": float(x[:, 0].min()), "last_start_us": float(x[:, 0].max()),
+                     "median_wait_us": float(np.median(x[:, 1] - x[:, 0])), "median_work_us": float(np.median(x[:, 2] - x[:, 1])),
+                     "last_end_us": float(x[:, 3].max())}
+    return res
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=62)
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--config", type=int, default=3)
-    ap.add_argument("--micro-batches", type=int, default=0)
+    ap.add_argument("--micro-batches", type=int, default=0, help="kvd_config.micro_batches (-1 = the step as one launch)")
+    ap.add_argument("--policy", choices=["lru", "lookahead"], default="lru", help="cache replacement policy")
+    ap.add_argument("--window", type=float, default=0.0,
+                    help="cache capacity as a multiple of the per-step budget k (the paper's window size); "
+                         "0 keeps the configuration's capacity")
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="0 skips the oracle baseline")
     ap.add_argument("--no-profile-pass", action="store_true", help="skip the per-kernel HIP-event pass")
+    ap.add_argument("--timeline", action="store_true",
+                    help="with --micro-batches -1: add the per-workgroup timeline of one all-hit single-launch step")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this path is built and measured on one GPU only (no collectives, no sharding); "
@@ -113,6 +141,9 @@ def main() -> int:
     if w.n_layers != 1:
         # multi-layer configurations are benchmarked on one layer's worth of state at full per-layer shape
         w = w.replace(n_layers=1, physical_layers=1)
+    if args.window > 0:
+        w = w.replace(capacity=max(w.topk_pages, int(round(args.window * w.topk_pages))))
+    w = w.replace(policy=args.policy)
     L, B, Hkv, NP, P, D, U, k = w.n_layers, w.batch, w.n_kv_heads, w.n_pages, w.page, w.head_dim, w.units, w.topk_pages
 
     t_setup = time.perf_counter()
@@ -122,7 +153,7 @@ def main() -> int:
     pool = torch.zeros((L, B, Hkv, w.capacity, 2, P, D), dtype=w.torch_dtype, device=dev)
     ctx = K.Kvd(n_layers=L, batch=B, n_q_heads=w.n_q_heads, n_kv_heads=Hkv, page_size=P, max_pages=NP, topk_pages=k,
                 capacity_max=w.capacity, kv_dtype=w.torch_dtype, sink_pages=w.sink_pages, recent_pages=w.recent_pages,
-                physical_layers=w.physical_layers, micro_batches=args.micro_batches)
+                physical_layers=w.physical_layers, micro_batches=args.micro_batches, policy=w.policy)
     ctx.bind_summaries(summ)
     ctx.bind_host_store(store)
     ctx.bind_slot_pool(pool)
@@ -170,7 +201,7 @@ def main() -> int:
         "vs_baseline": None,
         "dtype": w.dtype,
         "data": "synthetic",
-        "config": {"workload": describe(w), "micro_batches": max(1, args.micro_batches), "setup_s": round(t_setup, 1)},
+        "config": {"workload": describe(w), "micro_batches": args.micro_batches, "setup_s": round(t_setup, 1)},
         "cache": {"hit_rate": hit_rate, "host_bytes_per_step": gathered_per_step,
                   "host_link_GBps_if_fetch_bound": gathered_per_step / (elapsed / args.steps) / 1e9},
     }
@@ -223,6 +254,9 @@ def main() -> int:
             "ms_per_step": res_ms, "layer_steps_per_s": 1e3 / res_ms, "misses": int(rs.misses), "bytes": gpu_bytes,
             "GBps": gpu_bytes / (res_ms * 1e-3) / 1e9, "frac_of_hbm_peak": gpu_bytes / (res_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS,
         }
+
+    if args.timeline and args.micro_batches == -1 and not args.no_profile_pass:
+        result["timeline"] = step_timeline(ctx, t, q_last, out, stream)
 
     if args.cpu_seconds > 0:
         q_cpu = [q.cpu() for q in queries[:16]]

@@ -397,14 +397,15 @@ static int step_profiled(kvd_ctx* c, int layer, int step, const void* q, float* 
     HIP_TRY(c, kvd_launch_gather(c, layer, 0, c->U, s));
     HIP_TRY(c, hipEventRecord(ev[3], s));
   }
-  HIP_TRY(c, kvd_launch_attend(c, layer, q, c->d_sel_pages, c->d_sel_slots, out, lse, 0, c->U, s, ev[4]));
+  const bool own_merge = c->fuse_merge || c->S == 1;   // the attention kernel merges its own splits
+  HIP_TRY(c, kvd_launch_attend(c, layer, q, c->d_sel_pages, c->d_sel_slots, out, lse, 0, c->U, s, own_merge ? nullptr : ev[4]));
   HIP_TRY(c, hipEventRecord(ev[5], s));
   HIP_TRY(c, hipEventSynchronize(ev[5]));
   float ms = 0.f;
   HIP_TRY(c, hipEventElapsedTime(&ms, ev[0], ev[1])); c->ms_score += ms;
   HIP_TRY(c, hipEventElapsedTime(&ms, ev[1], ev[2])); c->ms_select_resolve += ms;
   HIP_TRY(c, hipEventElapsedTime(&ms, ev[2], ev[3])); c->ms_gather += ms;
-  if (c->fuse_merge || c->S == 1) {                  // the attention kernel merges its own splits
+  if (own_merge) {
     HIP_TRY(c, hipEventElapsedTime(&ms, ev[3], ev[5])); c->ms_attend += ms;
   } else {
     HIP_TRY(c, hipEventElapsedTime(&ms, ev[3], ev[4])); c->ms_attend += ms;
