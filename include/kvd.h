@@ -216,6 +216,11 @@ int kvd_step_trace(kvd_ctx* ctx, int32_t* sel_pages, int32_t* sel_slots, int32_t
  * mode 2: a single-launch kvd_step also records, per workgroup, four readings of the GPU's 100 MHz
  *         wall clock (see kvd_step_timeline); the step stays asynchronous. */
 int kvd_set_profiling(kvd_ctx* ctx, int32_t mode);
+/* Bound of every wait inside the one-launch kvd_step (micro_batches = -1), where workgroups wait on
+ * flags in device memory for the workgroups before them.  Default 2 s.  A wait that runs out makes
+ * its workgroup leave without output and raises a sticky error: kvd_get_stats and later kvd_step
+ * calls return KVD_ERR_STATE until kvd_cache_reset.  (A limit of 0 lets tests reach that path.) */
+int kvd_set_wait_limit_us(kvd_ctx* ctx, int64_t microseconds);
 /* Timeline of the last single-launch kvd_step recorded under profiling mode 2.  Synchronises the
  * device.  host_records [capacity][5] receives, for workgroup i < min(capacity, *n_workgroups) in
  * dispatch order, the clock at: start, end of its wait for its inputs, end of its work, exit; and

@@ -481,6 +481,12 @@ int kvd_set_profiling(kvd_ctx* ctx, int32_t on) {
   return KVD_OK;
 }
 
+int kvd_set_wait_limit_us(kvd_ctx* ctx, int64_t microseconds) {
+  if (!ctx || microseconds < 0) return KVD_ERR_ARG;
+  ctx->wait_limit_ticks = microseconds * 100;        // the GPU wall clock runs at 100 MHz
+  return KVD_OK;
+}
+
 int kvd_step_timeline(kvd_ctx* ctx, int64_t* host_records, int32_t capacity, int32_t* n_workgroups) {
   if (!ctx || !host_records || !n_workgroups || capacity < 0) return KVD_ERR_ARG;
   if (!ctx->single_launch || ctx->tl_workgroups == 0) return KVD_ERR_STATE;

@@ -337,6 +337,52 @@ def test_micro_batches_and_per_unit_capacities_give_identical_results():
         assert H.attn_rel_err(a[4], b[4]) <= 1e-5
 
 
+def test_single_launch_timeline_and_wait_limit():
+    """The one-launch step records one line per workgroup, in dispatch order and with consistent
+    clocks; a wait limit of zero makes waiting workgroups give up (every kernel still ends
+    normally), which the library reports until the cache is reset."""
+    w = SCALED[3].replace(steps=4)
+    rig = R.Rig(w, micro_batches=-1)
+    units = all_units(rig)
+    qs = [q[0] for q in W.query_stream(w, rig.q0, 4, R.DEV)]
+    rig.kvd.set_profiling(2)
+    rep = R.StepReport()
+    for t in range(2):
+        rig.step(0, t, qs[t])
+        for ou in units:
+            R.compare_unit(rig, ou, t, qs[t], rep)
+    rec = rig.kvd.step_timeline().numpy()
+    role, unit = rec[:, 4] & 0xff, (rec[:, 4] >> 8) & 0xffffff
+    assert (role == 1).sum() == w.units and (role == 2).sum() % w.units == 0 and (role == 0).sum() % w.units == 0
+    assert set(unit.tolist()) == set(range(w.units))
+    t = rec[:, :4]
+    assert np.all(np.diff(t, axis=1) >= 0)                           # start <= ready <= done <= exit
+    for u in range(w.units):                                          # a unit's stages follow one another
+        score_end = t[(role == 0) & (unit == u), 2].max()
+        sel = t[(role == 1) & (unit == u)][0]
+        assert sel[1] >= score_end and t[(role == 2) & (unit == u), 1].min() >= sel[2]
+    rig.kvd.set_profiling(0)
+
+    rig.kvd.set_wait_limit_us(0)
+    rig.kvd.step(0, 2, qs[2], rig.out, rig.lse)                       # workgroups that have to wait give up
+    torch.cuda.synchronize()
+    with pytest.raises(K.KvdError) as e:
+        rig.kvd.stats()
+    assert e.value.status == K.ERR_STATE
+    with pytest.raises(K.KvdError) as e:
+        rig.kvd.step(0, 3, qs[3], rig.out, rig.lse)
+    assert e.value.status == K.ERR_STATE
+    rig.kvd.set_wait_limit_us(2_000_000)
+    rig.kvd.cache_reset()                                             # clears the error and the flags
+    units = all_units(rig)                                            # cold again on both sides
+    rep = R.StepReport()
+    for t in range(2):
+        rig.step(0, t, qs[t])
+        for ou in units:
+            R.compare_unit(rig, ou, t, qs[t], rep)
+    rig.close()
+
+
 # --------------------------------------------------------------------------- #
 # lookahead eviction
 # --------------------------------------------------------------------------- #
