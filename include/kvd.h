@@ -192,6 +192,22 @@ int kvd_cache_resolve(kvd_ctx* ctx, int32_t layer, int32_t step, const int32_t* 
 int kvd_sparse_decode_attn(kvd_ctx* ctx, int32_t layer, const void* q, const int32_t* sel_pages,
                            const int32_t* sel_slots, float* out, float* lse, void* stream);
 
+/* ---- growth of the KV store during decoding ------------------------------------------------ */
+
+/* Appends the key and value of the token just decoded (Background, "KV Cache Basics": each decoding
+ * step appends new key and value vectors) for one layer, at position seq_len[b] of every sequence:
+ *   k_new, v_new  device, [B][Hkv][D] kv_dtype, 16-byte aligned.
+ * The token is written into the pinned host store (the library writes to the buffer given to
+ * kvd_bind_host_store), into the page's slot if the page is resident, and the page's index entry
+ * becomes the mean over its valid tokens including the new one.  seq_len does not change: call
+ * kvd_advance once every layer has appended.  Enqueued on `stream`; order it after the layer's
+ * kvd_step of this decode step and before the next one.
+ * KVD_ERR_SHAPE when a sequence already fills max_pages * page_size tokens; KVD_ERR_STATE when
+ * buffers are not bound or physical_layers < n_layers (layers sharing a stored layer cannot append). */
+int kvd_append_kv(kvd_ctx* ctx, int32_t layer, const void* k_new, const void* v_new, void* stream);
+/* seq_len[b] += 1 for every sequence (device copy on `stream`, host copy at once). */
+int kvd_advance(kvd_ctx* ctx, void* stream);
+
 /* ---- hot path: the whole layer-step -------------------------------------------------------- */
 
 /* Stages 1-3 for one layer.  With micro_batches > 1 the groups of sequences run as separate

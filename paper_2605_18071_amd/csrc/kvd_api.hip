@@ -245,6 +245,25 @@ int kvd_build_summaries(kvd_ctx* ctx, int32_t layer, void* stream) {
   return KVD_OK;
 }
 
+int kvd_append_kv(kvd_ctx* ctx, int32_t layer, const void* k_new, const void* v_new, void* stream) {
+  if (!ctx || !k_new || !v_new || layer < 0 || layer >= ctx->L || !aligned16(k_new) || !aligned16(v_new)) return KVD_ERR_ARG;
+  if (!ctx->summaries || !ctx->pool || !ctx->store_dev) return KVD_ERR_STATE;
+  if (ctx->Lp != ctx->L) return KVD_ERR_STATE;       // layers that share a stored layer cannot each append to it
+  for (int b = 0; b < ctx->B; ++b)
+    if ((long long)ctx->h_seq_len[b] >= (long long)ctx->NP * ctx->P) return KVD_ERR_SHAPE;
+  HIP_TRY(ctx, kvd_launch_append(ctx, layer, k_new, v_new, static_cast<hipStream_t>(stream)));
+  return KVD_OK;
+}
+
+int kvd_advance(kvd_ctx* ctx, void* stream) {
+  if (!ctx) return KVD_ERR_ARG;
+  for (int b = 0; b < ctx->B; ++b)
+    if ((long long)ctx->h_seq_len[b] >= (long long)ctx->NP * ctx->P) return KVD_ERR_SHAPE;
+  HIP_TRY(ctx, kvd_launch_advance(ctx, static_cast<hipStream_t>(stream)));
+  for (int b = 0; b < ctx->B; ++b) ++ctx->h_seq_len[b];
+  return KVD_OK;
+}
+
 int kvd_cache_reset(kvd_ctx* ctx) {
   if (!ctx) return KVD_ERR_ARG;
   HIP_TRY(ctx, hipDeviceSynchronize());

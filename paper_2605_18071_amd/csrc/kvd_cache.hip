@@ -277,6 +277,94 @@ __global__ __launch_bounds__(kHeadDim) void summaries_kernel(const uint16_t* __r
   *out = f64_to_kv<BF16>(acc / (double)n);
 }
 
+// Decoding appends the key and value of the token just generated to the KV store (Background,
+// "KV Cache Basics").  One block per unit: the token lands at position seq_len[b] of the host
+// store (written across the host link), in the slot of its page if that page is resident, and the
+// page's index entry is recomputed as the mean over its valid tokens including the new one (fp64,
+// token order, rounded once — the same definition as summaries_kernel).
+template <bool BF16, bool TILED>
+__global__ __launch_bounds__(256) void append_kernel(uint16_t* __restrict__ store,          // [U][NP][2][P][D] of the layer
+                                                    uint16_t* __restrict__ summ,           // [U][NP][D]
+                                                    char* __restrict__ pool,               // [U][Cmax] slots
+                                                    const int32_t* __restrict__ slot_page, // [U][Cmax]
+                                                    const int32_t* __restrict__ capacity,  // [U]
+                                                    const uint16_t* __restrict__ k_new,    // [U][D]
+                                                    const uint16_t* __restrict__ v_new,    // [U][D]
+                                                    const int32_t* __restrict__ seq_len, int NP, int P, int Cmax,
+                                                    int Hkv, unsigned page_bytes) {
+  __shared__ int found_slot;
+  const int u = blockIdx.x, tid = threadIdx.x;
+  const int b = u / Hkv;
+  const int t = seq_len[b];
+  const int page = t / P, o = t % P;
+  if (page >= NP) return;                                // no room: the host checks this before launching
+  if (tid == 0) found_slot = -1;
+  __syncthreads();
+  uint16_t* kpage = store + ((size_t)u * NP + page) * (size_t)(2 * P * kHeadDim);
+  uint16_t* vpage = kpage + (size_t)P * kHeadDim;
+  const uint16_t* kn = k_new + (size_t)u * kHeadDim;
+  const uint16_t* vn = v_new + (size_t)u * kHeadDim;
+
+  // 1. the host store: 16 lanes x 16 bytes for K, 16 for V
+  if (tid < 32) {
+    const int ch = tid & 15;
+    const uint4 val = *reinterpret_cast<const uint4*>((tid < 16 ? kn : vn) + ch * 8);
+    *reinterpret_cast<uint4*>((tid < 16 ? kpage : vpage) + (size_t)o * kHeadDim + ch * 8) = val;
+  }
+
+  // 2. is the page resident?
+  const int C = capacity[u];
+  for (int s = tid; s < C; s += 256)
+    if (slot_page[(size_t)u * Cmax + s] == page) found_slot = s;      // at most one slot holds the page
+  __syncthreads();
+  const int slot = found_slot;
+  if (slot >= 0 && tid < kHeadDim) {
+    char* sl = pool + ((size_t)u * Cmax + slot) * page_bytes;
+    const int d = tid;
+    if (TILED) {
+      // tile layout (kvd_tile_layout.h): K element [row][d] sits in chunk d/32, lane row + 16 ((d%32)/8),
+      // element d%8; V element [row][d] in chunk d/32, lane d%16 + 16 (row/4), element 4 ((d%32)/16) + row%4
+      char* tile = sl + (size_t)(o / kTileTokens) * kTileBytes;
+      const int row = o % kTileTokens;
+      const int c = d >> 5, r32 = d & 31;
+      uint16_t* kdst = reinterpret_cast<uint16_t*>(tile + (c * 64 + (r32 >> 3) * 16 + row) * 16) + (d & 7);
+      uint16_t* vdst = reinterpret_cast<uint16_t*>(tile + kTilePartBytes + (c * 64 + (row >> 2) * 16 + (d & 15)) * 16) +
+                       4 * (r32 >> 4) + (row & 3);
+      *kdst = kn[d];
+      *vdst = vn[d];
+    } else {
+      uint16_t* k16 = reinterpret_cast<uint16_t*>(sl);
+      k16[(size_t)o * kHeadDim + d] = kn[d];
+      k16[(size_t)(P + o) * kHeadDim + d] = vn[d];
+    }
+  }
+
+  // 3. the index entry of the page: tokens 0..o-1 from the host store, then the new key
+  if (tid < kHeadDim) {
+    const int d = tid;
+    double acc = 0.0;
+    for (int t0 = 0; t0 < o; t0 += 16) {
+      uint16_t raw[16];
+#pragma unroll
+      for (int j = 0; j < 16; ++j) {
+        const int tt = (t0 + j) < o ? (t0 + j) : (o - 1);
+        raw[j] = kpage[(size_t)tt * kHeadDim + d];
+      }
+#pragma unroll
+      for (int j = 0; j < 16; ++j)
+        if (t0 + j < o) acc += (double)(BF16 ? as_f32((u32)raw[j] << 16) : (float)__builtin_bit_cast(_Float16, raw[j]));
+    }
+    const uint16_t kb = kn[d];
+    acc += (double)(BF16 ? as_f32((u32)kb << 16) : (float)__builtin_bit_cast(_Float16, kb));
+    summ[((size_t)u * NP + page) * kHeadDim + d] = f64_to_kv<BF16>(acc / (double)(o + 1));
+  }
+}
+
+__global__ void advance_kernel(int32_t* seq_len, int B) {
+  const int b = blockIdx.x * blockDim.x + threadIdx.x;
+  if (b < B) seq_len[b] += 1;
+}
+
 __global__ void fill_i32_kernel(int32_t* p, int32_t v, size_t n) {
   for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x) p[i] = v;
 }
@@ -350,6 +438,31 @@ hipError_t kvd_launch_build_summaries(kvd_ctx* c, int layer, hipStream_t s) {
     hipLaunchKernelGGL(summaries_kernel<true>, grid, dim3(kHeadDim), 0, s, store, summ, c->d_seq_len, c->NP, c->P, c->Hkv);
   else
     hipLaunchKernelGGL(summaries_kernel<false>, grid, dim3(kHeadDim), 0, s, store, summ, c->d_seq_len, c->NP, c->P, c->Hkv);
+  return hipGetLastError();
+}
+
+hipError_t kvd_launch_append(kvd_ctx* c, int layer, const void* k_new, const void* v_new, hipStream_t s) {
+  using namespace kvd;
+  const size_t lu = (size_t)layer * c->U;
+  uint16_t* store = reinterpret_cast<uint16_t*>(const_cast<char*>(c->store_dev) + (size_t)layer * c->U * c->NP * c->page_bytes);
+  uint16_t* summ = reinterpret_cast<uint16_t*>(c->summaries) + lu * c->NP * kHeadDim;
+  char* pool = c->pool + lu * c->Cmax * c->page_bytes;
+  const int32_t* slot_page = c->d_slot_page + lu * c->Cmax;
+  const int32_t* cap = c->d_capacity + lu;
+  const uint16_t* kn = reinterpret_cast<const uint16_t*>(k_new);
+  const uint16_t* vn = reinterpret_cast<const uint16_t*>(v_new);
+  dim3 grid(c->U), block(256);
+#define KVD_APPEND(BF, TL)                                                                                          \
+  hipLaunchKernelGGL((append_kernel<BF, TL>), grid, block, 0, s, store, summ, pool, slot_page, cap, kn, vn, c->d_seq_len, \
+                     c->NP, c->P, c->Cmax, c->Hkv, (unsigned)c->page_bytes)
+  if (c->bf16) { if (c->tiled) KVD_APPEND(true, true); else KVD_APPEND(true, false); }
+  else { if (c->tiled) KVD_APPEND(false, true); else KVD_APPEND(false, false); }
+#undef KVD_APPEND
+  return hipGetLastError();
+}
+
+hipError_t kvd_launch_advance(kvd_ctx* c, hipStream_t s) {
+  hipLaunchKernelGGL(kvd::advance_kernel, dim3((c->B + 63) / 64), dim3(64), 0, s, c->d_seq_len, c->B);
   return hipGetLastError();
 }
 

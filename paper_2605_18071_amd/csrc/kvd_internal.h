@@ -104,4 +104,6 @@ bool kvd_single_launch_ok(const kvd_ctx* c);
 hipError_t kvd_launch_step(kvd_ctx* c, int layer, int step, const void* q, float* out, float* lse, hipStream_t s);
 hipError_t kvd_launch_refill(kvd_ctx* c, int layer, hipStream_t s);
 hipError_t kvd_launch_build_summaries(kvd_ctx* c, int layer, hipStream_t s);
+hipError_t kvd_launch_append(kvd_ctx* c, int layer, const void* k_new, const void* v_new, hipStream_t s);
+hipError_t kvd_launch_advance(kvd_ctx* c, hipStream_t s);
 hipError_t kvd_launch_fill_i32(int32_t* p, int32_t v, size_t n, hipStream_t s);

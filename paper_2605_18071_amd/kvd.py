@@ -45,7 +45,7 @@ EXPORTS = [
     "kvd_create", "kvd_destroy", "kvd_strerror", "kvd_last_hip_error", "kvd_abi_version",
     "kvd_bind_summaries", "kvd_bind_host_store", "kvd_bind_slot_pool", "kvd_set_seq_lens",
     "kvd_build_summaries", "kvd_cache_reset", "kvd_cache_warm", "kvd_cache_export", "kvd_cache_import",
-    "kvd_score_select", "kvd_cache_resolve", "kvd_sparse_decode_attn", "kvd_step", "kvd_step_trace",
+    "kvd_append_kv", "kvd_advance", "kvd_score_select", "kvd_cache_resolve", "kvd_sparse_decode_attn", "kvd_step", "kvd_step_trace",
     "kvd_set_profiling", "kvd_set_wait_limit_us", "kvd_step_timeline", "kvd_get_stats", "kvd_reset_stats",
 ]
 
@@ -75,6 +75,8 @@ def load() -> C.CDLL:
         "kvd_cache_warm": [vp, i32, i32p, i32p],
         "kvd_cache_export": [vp, i32, i32p, i32p],
         "kvd_cache_import": [vp, i32, i32p, i32p],
+        "kvd_append_kv": [vp, i32, vp, vp, vp],
+        "kvd_advance": [vp, vp],
         "kvd_score_select": [vp, i32, vp, vp, vp, vp],
         "kvd_cache_resolve": [vp, i32, i32, vp, vp, vp, vp, vp, i32, vp],
         "kvd_sparse_decode_attn": [vp, i32, vp, vp, vp, vp, vp, vp],
@@ -203,6 +205,14 @@ class Kvd:
         ss = slot_stamp.to(torch.int32).contiguous()
         self._check(self.lib.kvd_cache_import(self.ctx, layer, C.cast(sp.data_ptr(), C.POINTER(C.c_int32)),
                                               C.cast(ss.data_ptr(), C.POINTER(C.c_int32))), "kvd_cache_import")
+
+    # ---- growth of the store
+    def append_kv(self, layer: int, k_new: torch.Tensor, v_new: torch.Tensor, stream=None):
+        self._check(self.lib.kvd_append_kv(self.ctx, layer, k_new.data_ptr(), v_new.data_ptr(), _stream_handle(stream)),
+                    "kvd_append_kv")
+
+    def advance(self, stream=None):
+        self._check(self.lib.kvd_advance(self.ctx, _stream_handle(stream)), "kvd_advance")
 
     # ---- hot path
     def score_select(self, layer: int, q: torch.Tensor, sel_pages: torch.Tensor, scores: Optional[torch.Tensor] = None,

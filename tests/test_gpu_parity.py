@@ -337,6 +337,76 @@ def test_micro_batches_and_per_unit_capacities_give_identical_results():
         assert H.attn_rel_err(a[4], b[4]) <= 1e-5
 
 
+# --------------------------------------------------------------------------- #
+# growth of the store during decoding
+# --------------------------------------------------------------------------- #
+@pytest.mark.parametrize("kw,mb", [
+    (dict(), 1),                                                      # bf16, page 16 (tile layout), chain of kernels
+    (dict(), -1),                                                     # the same, one launch
+    (dict(dtype="f16", page=32, ctx=32 * 120, n_q_heads=14, n_kv_heads=2), 1),
+    (dict(page=20, ctx=20 * 90, n_q_heads=6, n_kv_heads=2), 1),      # natural slot layout
+])
+def test_append_kv_grows_store_index_and_slots(kw, mb):
+    """Each decode step appends one token per sequence: host store, resident slot and index entry
+    must follow, and the next steps must attend to the new tokens (the last pages are forced into
+    the selection so that they are resident and attended)."""
+    w = small("append", recent_pages=2, topk_pages=20, capacity=40, steps=30, **kw)
+    P = w.page
+    seq = [w.ctx - 2 * P - 5, w.ctx - 3 * P]                           # room to grow, over page boundaries
+    rig = R.Rig(w, seq_lens=seq, micro_batches=mb)
+    units = all_units(rig)
+    gen = torch.Generator(device="cpu").manual_seed(99)
+    rep = R.StepReport()
+    qs = W.query_stream(w, rig.q0, w.steps, R.DEV)
+    for t in range(w.steps):
+        q = next(qs)
+        rig.step(0, t, q[0])
+        for ou in units:
+            R.compare_unit(rig, ou, t, q[0], rep)
+        k_new = torch.randn((w.batch, w.n_kv_heads, w.head_dim), generator=gen).to(w.torch_dtype)
+        v_new = torch.randn((w.batch, w.n_kv_heads, w.head_dim), generator=gen).to(w.torch_dtype)
+        rig.kvd.append_kv(0, k_new.to(R.DEV), v_new.to(R.DEV))
+        rig.kvd.advance()
+        torch.cuda.synchronize()
+        summ = rig.summaries.cpu()
+        for ou in units:
+            pos = ou.seq_len
+            ou.keys[pos] = H.f64(k_new[ou.b, ou.h])                     # the oracle's copy of the store grows from the inputs
+            ou.values[pos] = H.f64(v_new[ou.b, ou.h])
+            ou.seq_len = pos + 1
+            ou.summ = orc.page_summaries(ou.keys, P, ou.seq_len, ou.code)
+            page, off = divmod(pos, P)
+            assert torch.equal(rig.store[0, ou.b, ou.h, page, 0, off], k_new[ou.b, ou.h])
+            assert torch.equal(rig.store[0, ou.b, ou.h, page, 1, off], v_new[ou.b, ou.h])
+            n = ou.summ.shape[0]
+            assert np.array_equal(H.bits(summ[0, ou.b, ou.h, :n]), orc.f64_to_bits(ou.summ, ou.code)), (t, ou.u)
+        rig.seq_lens = [s + 1 for s in rig.seq_lens]
+        if t % 7 == 0 or t == w.steps - 1:
+            R.check_directory(rig, 0, units)                            # slots still equal their (grown) host pages
+    assert rep.tie_divergences <= 2
+    assert any((s0 + w.steps) // P > s0 // P for s0 in seq)              # a page boundary was crossed
+    rig.close()
+
+
+def test_append_kv_errors():
+    w = small("append-err", ctx=16 * 40, topk_pages=8, capacity=16, batch=1)
+    rig = R.Rig(w)                                                      # sequences already fill every page
+    kv = torch.zeros((w.batch, w.n_kv_heads, w.head_dim), dtype=w.torch_dtype, device=R.DEV)
+    with pytest.raises(K.KvdError) as e:
+        rig.kvd.append_kv(0, kv, kv)
+    assert e.value.status == K.ERR_SHAPE
+    with pytest.raises(K.KvdError) as e:
+        rig.kvd.advance()
+    assert e.value.status == K.ERR_SHAPE
+    rig.close()
+    w2 = small("append-alias", n_layers=2, physical_layers=1, ctx=16 * 40, topk_pages=8, capacity=16, batch=1)
+    rig = R.Rig(w2, seq_lens=[16 * 30])
+    with pytest.raises(K.KvdError) as e:
+        rig.kvd.append_kv(0, kv, kv)
+    assert e.value.status == K.ERR_STATE                                # two layers share one stored layer
+    rig.close()
+
+
 def test_single_launch_timeline_and_wait_limit():
     """The one-launch step records one line per workgroup, in dispatch order and with consistent
     clocks; a wait limit of zero makes waiting workgroups give up (every kernel still ends
