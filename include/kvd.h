@@ -241,7 +241,8 @@ int kvd_set_wait_limit_us(kvd_ctx* ctx, int64_t microseconds);
  * device.  host_records [capacity][5] receives, for workgroup i < min(capacity, *n_workgroups) in
  * dispatch order, the clock at: start, end of its wait for its inputs, end of its work, exit; and
  * a tag: bits 0-7 the role (0 scoring, 1 selection + directory + fetch, 2 attention), bits 8-31
- * the unit, bits 32-63 the scoring chunk or attention split.  KVD_ERR_STATE if the step does not
+ * the unit (0 for scoring workgroups, which serve all units in turn), bits 32-63 the number of the
+ * scoring workgroup or the attention split.  KVD_ERR_STATE if the step does not
  * run as one launch or none has run. */
 int kvd_step_timeline(kvd_ctx* ctx, int64_t* host_records, int32_t capacity, int32_t* n_workgroups);
 int kvd_get_stats(kvd_ctx* ctx, kvd_stats* host_out);   /* synchronises the device */

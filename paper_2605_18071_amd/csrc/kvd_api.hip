@@ -130,6 +130,11 @@ int kvd_create(const kvd_config* cfg, kvd_ctx** out) {
   c->bf16 = cfg->kv_dtype == KVD_BF16;
   c->tiled = (c->P % 16) == 0;
   c->wait_limit_ticks = 200000000LL;                // 2 s
+  {
+    int dev = 0, cus = 0;
+    if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus < 1) cus = 256;
+    c->n_cus = cus;
+  }
   { const char* e_ = getenv("KVD_FUSE_MERGE"); c->fuse_merge = e_ ? atoi(e_) : 1; }
   { const char* e_ = getenv("KVD_SCORE_BLOCKS"); c->score_blocks = e_ ? atoi(e_) : 2048; if (c->score_blocks < 1) c->score_blocks = 1; }
   { const char* e_ = getenv("KVD_GENERIC_SELECT"); c->generic_select = e_ ? atoi(e_) : 0; }
@@ -145,6 +150,13 @@ int kvd_create(const kvd_config* cfg, kvd_ctx** out) {
     if (S > cap) S = cap;
     if (S > KVD_MAX_SPLITS) S = KVD_MAX_SPLITS;
     if (S < 1) S = 1;
+    // the one-launch step has 8 waves per attention workgroup and gains from twice as many
+    // workgroups (units become ready one after another) as long as a wave keeps 4 tiles or more
+    if (cfg->micro_batches == -1 && kvd_single_launch_ok(c)) {
+      int S2 = (1024 + c->U / 2) / c->U;
+      if (S2 > KVD_MAX_SPLITS) S2 = KVD_MAX_SPLITS;
+      if (S2 >= 1 && tiles / (S2 * 8) >= 4) S = S2;
+    }
   }
   if (S > c->k) S = c->k;
   c->S = S;
@@ -168,8 +180,8 @@ int kvd_create(const kvd_config* cfg, kvd_ctx** out) {
       ok(dev_alloc(&c->d_miss_count, (size_t)c->U)) &&
       ok(dev_alloc(&c->d_part_acc, (size_t)c->U * c->S * c->G * c->D)) &&
       ok(dev_alloc(&c->d_part_ml, (size_t)c->U * c->S * c->G * 2)) && ok(dev_alloc(&c->d_stats, 4)) &&
-      ok(dev_alloc(&c->d_attn_ticket, (size_t)c->U)) && ok(dev_alloc(&c->d_score_done, (size_t)c->U)) &&
-      ok(dev_alloc(&c->d_sel_ready, (size_t)c->U)) && ok(dev_alloc(&c->d_timeline, (size_t)KVD_TIMELINE_MAX * 5)) &&
+      ok(dev_alloc(&c->d_attn_ticket, (size_t)c->U)) && ok(dev_alloc(&c->d_score_done, (size_t)c->U * 32)) &&
+      ok(dev_alloc(&c->d_sel_ready, (size_t)c->U * 32)) && ok(dev_alloc(&c->d_timeline, (size_t)KVD_TIMELINE_MAX * 5)) &&
       ok(hipHostMalloc(reinterpret_cast<void**>(&c->error_host), sizeof(int32_t), hipHostMallocMapped)) &&
       ok(hipHostGetDevicePointer(reinterpret_cast<void**>(&c->error_dev), c->error_host, 0)) &&
       ok(hipEventCreateWithFlags(&c->ev_fork, hipEventDisableTiming));
@@ -185,8 +197,8 @@ int kvd_create(const kvd_config* cfg, kvd_ctx** out) {
   if (e == hipSuccess) ok(hipMemset(c->d_stats, 0, 4 * sizeof(unsigned long long)));
   if (e == hipSuccess) ok(hipMemset(c->d_miss_count, 0, (size_t)c->U * sizeof(int32_t)));
   if (e == hipSuccess) ok(hipMemset(c->d_attn_ticket, 0, (size_t)c->U * sizeof(int32_t)));
-  if (e == hipSuccess) ok(hipMemset(c->d_score_done, 0, (size_t)c->U * sizeof(int32_t)));
-  if (e == hipSuccess) ok(hipMemset(c->d_sel_ready, 0, (size_t)c->U * sizeof(int32_t)));
+  if (e == hipSuccess) ok(hipMemset(c->d_score_done, 0, (size_t)c->U * 32 * sizeof(int32_t)));
+  if (e == hipSuccess) ok(hipMemset(c->d_sel_ready, 0, (size_t)c->U * 32 * sizeof(int32_t)));
   if (e == hipSuccess) *c->error_host = 0;
   if (e == hipSuccess) c->single_launch = cfg->micro_batches == -1 && kvd_single_launch_ok(c);
   if (e != hipSuccess) { free_ctx(c); return KVD_ERR_HIP; }
@@ -268,8 +280,8 @@ int kvd_cache_reset(kvd_ctx* ctx) {
   if (!ctx) return KVD_ERR_ARG;
   HIP_TRY(ctx, hipDeviceSynchronize());
   HIP_TRY(ctx, hipMemset(ctx->d_attn_ticket, 0, (size_t)ctx->U * sizeof(int32_t)));
-  HIP_TRY(ctx, hipMemset(ctx->d_score_done, 0, (size_t)ctx->U * sizeof(int32_t)));
-  HIP_TRY(ctx, hipMemset(ctx->d_sel_ready, 0, (size_t)ctx->U * sizeof(int32_t)));
+  HIP_TRY(ctx, hipMemset(ctx->d_score_done, 0, (size_t)ctx->U * 32 * sizeof(int32_t)));
+  HIP_TRY(ctx, hipMemset(ctx->d_sel_ready, 0, (size_t)ctx->U * 32 * sizeof(int32_t)));
   *ctx->error_host = 0;
   return reset_directory(ctx, -1);
 }

@@ -5,11 +5,11 @@
 //
 // The grid is one-dimensional and ordered so that a workgroup depends only on workgroups with a
 // lower index:
-//     the scoring workgroups (`chunks` per unit) of units 0 .. lag-1;
-//     then for every unit u: its selection workgroup, followed by the scoring workgroups of unit
-//     u + lag (so that a selection workgroup is dispatched about when its scores are complete);
-//     then for every unit u: its S attention workgroups.
-// A selection workgroup waits until the unit's scoring workgroups have all arrived (a counter);
+//     n_score persistent scoring workgroups, which take the layer's scoring chunks in turn, unit
+//     by unit, so that the units' scores complete in unit order while scoring goes on;
+//     then one selection workgroup per unit;
+//     then S attention workgroups per unit.
+// A selection workgroup waits until the unit's scoring waves have all arrived (a counter);
 // an attention workgroup waits until the unit's selection, directory update and fetch are
 // complete (a flag carrying the launch number).  Workgroups are dispatched in index order, so
 // whatever a waiting workgroup waits for has already been dispatched and needs nothing from
@@ -40,87 +40,92 @@ struct StepArgs {
   float* scores;             // [U][NP]
   FastArgs fa;
   AttnArgs at;
-  int32_t* score_done;       // [U] scoring workgroups of the unit that have arrived; zero between launches
-  int32_t* sel_ready;        // [U] number of the last launch whose selection for the unit is complete
+  int32_t* score_done;       // [U][32] (one line per unit) scoring waves of the unit that have arrived (8 per chunk); zero between launches
+  int32_t* sel_ready;        // [U][32] (one line per unit) number of the last launch whose selection for the unit is complete
   int32_t* error;            // host-visible; set when a wait runs out
   long long* timeline;       // [workgroups][5]: wall-clock ticks at start, wait over, work done, exit; then a tag; or null
   long long wait_limit;      // ticks of the 100 MHz wall clock
   float scale;
-  int epoch, n_units, u0, chunks, passes, lag;
+  int epoch, n_units, u0, chunks, passes, n_score;
 };
 
 typedef AttnSmem<KVD_MAX_GROUP, kStepWaves> StepAttnSmem;
 typedef FastSmem<kStepThreads> StepFastSmem;
 constexpr size_t kStepSmemBytes = sizeof(StepAttnSmem) > sizeof(StepFastSmem) ? sizeof(StepAttnSmem) : sizeof(StepFastSmem);
 
-template <bool BF16, int IPT>
-__device__ __forceinline__ void step_body(const StepArgs& a, unsigned char* smem_raw, int& wait_ok) {
+// The three roles are separate functions (not inlined) so that each gets its registers allocated
+// on its own within the kernel's budget of 128 per lane.  They read the launch arguments from the
+// kernel-argument segment (constant address space, scalar loads) instead of receiving a copy.
+typedef const __attribute__((address_space(4))) StepArgs* StepArgsPtr;
+#ifdef KVD_STEP_NOINLINE
+#define KVD_ROLE_INLINE __attribute__((noinline))
+#else
+#define KVD_ROLE_INLINE __forceinline__
+#endif
+constexpr int kFlagStride = 32;   // ints between the flags of two units: one 128-byte line each
+
+// Scoring workgroup `wg` of n_score: chunks wg, wg + n_score, ... of the layer, unit by unit.
+template <bool BF16>
+__device__ KVD_ROLE_INLINE void step_score_role(StepArgsPtr ap, int wg, long long* ts) {
+  struct { const uint16_t* summ; const uint16_t* q; float* scores; int32_t* score_done; float scale;
+           int n_units, chunks, n_score, u0, passes; struct { int Hkv, NP; } fa; struct { int Hq, G; } at; } a;
+  a.summ = ap->summ; a.q = ap->q; a.scores = ap->scores; a.score_done = ap->score_done; a.scale = ap->scale;
+  a.n_units = ap->n_units; a.chunks = ap->chunks; a.n_score = ap->n_score; a.u0 = ap->u0; a.passes = ap->passes;
+  a.fa.Hkv = ap->fa.Hkv; a.fa.NP = ap->fa.NP; a.at.Hq = ap->at.Hq; a.at.G = ap->at.G;
   const int tid = threadIdx.x;
-  const int bid = blockIdx.x;
-  long long* ts = a.timeline != nullptr && tid == 0 ? a.timeline + (size_t)bid * 5 : nullptr;
-  if (ts) ts[0] = ts[1] = wall_clock64();
-  const int per_unit = a.chunks + 1;
-  const int front = a.n_units * per_unit;
-  if (bid < front) {
-    // front order: scoring of units 0..lag-1; then, for every unit u, its selection workgroup
-    // followed by the scoring workgroups of unit u + lag
-    int u, r;                                          // r < chunks: scoring workgroup r; r == chunks: selection
-    const int lead = a.lag * a.chunks;
-    if (bid < lead) {
-      u = bid / a.chunks;
-      r = bid % a.chunks;
-    } else {
-      const int j = bid - lead;
-      const int n_full = a.n_units - a.lag;            // units whose selection is followed by a later unit's scoring
-      if (j < n_full * per_unit) {
-        const int g = j / per_unit, rr = j % per_unit;
-        u = rr == 0 ? g : g + a.lag;
-        r = rr == 0 ? a.chunks : rr - 1;
-      } else {
-        u = n_full + (j - n_full * per_unit);
-        r = a.chunks;
-      }
-    }
-    u += a.u0;
-    if (ts) ts[4] = (r < a.chunks ? 0LL : 1LL) | ((long long)u << 8) | ((long long)(r < a.chunks ? r : 0) << 32);
-    if (r < a.chunks) {
-      // ---- scoring workgroup r of unit u
-      const int b = u / a.fa.Hkv, h = u % a.fa.Hkv;
-      const int w = tid / kWave;
-      const int wave_base = (r * kStepWaves + w) * 64 * a.passes;
-      score_wave<BF16, true>(a.summ + (size_t)u * a.fa.NP * kHeadDim,
-                             a.q + ((size_t)b * a.at.Hq + (size_t)h * a.at.G) * kHeadDim, a.scores + (size_t)u * a.fa.NP,
-                             a.fa.NP, a.at.G, a.scale, wave_base, a.passes);
-      if (ts) ts[2] = wall_clock64();
-      wave_drain_memory();                             // this wave's scores have been acknowledged
-      __syncthreads();
-      if (tid == 0) __hip_atomic_fetch_add(&a.score_done[u], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-      if (ts) ts[3] = wall_clock64();
-      return;
-    }
-    // ---- selection, directory update and fetch of unit u: latency-bound, so its waves go first
-    // whenever they can issue
-    __builtin_amdgcn_s_setprio(3);
-    if (!block_wait_equal(&a.score_done[u], a.chunks, a.wait_limit, &wait_ok)) {
-      if (tid == 0) __hip_atomic_store(a.error, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
-      return;
-    }
-    if (ts) ts[1] = wall_clock64();
-    if (tid == 0) store_agent(&a.score_done[u], 0);    // every arrival has been seen: ready for the next launch
-    StepFastSmem& sm = *reinterpret_cast<StepFastSmem*>(smem_raw);
-    select_resolve_body<kStepThreads, IPT, true, true, true>(a.fa, u, sm);
-    if (ts) ts[2] = wall_clock64();
-    wave_drain_memory();                               // selection, slots and fetched pages have been written through
-    __syncthreads();
-    if (tid == 0) store_agent(&a.sel_ready[u], a.epoch);
-    if (ts) ts[3] = wall_clock64();
+  const int w = tid / kWave, lane = tid & (kWave - 1);
+  if (ts) ts[4] = 0LL | ((long long)wg << 32);
+  const int total = a.n_units * a.chunks;
+  for (int c = wg; c < total; c += a.n_score) {
+    const int u = c / a.chunks + a.u0, r = c % a.chunks;
+    const int b = u / a.fa.Hkv, h = u % a.fa.Hkv;
+    const int wave_base = (r * kStepWaves + w) * 64 * a.passes;
+    score_wave<BF16, true>(a.summ + (size_t)u * a.fa.NP * kHeadDim,
+                           a.q + ((size_t)b * a.at.Hq + (size_t)h * a.at.G) * kHeadDim, a.scores + (size_t)u * a.fa.NP,
+                           a.fa.NP, a.at.G, a.scale, wave_base, a.passes);
+    wave_drain_memory();                               // this wave's scores have been acknowledged
+    if (lane == 0) __hip_atomic_fetch_add(&a.score_done[u * kFlagStride], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  }
+  if (ts) ts[2] = ts[3] = wall_clock64();
+}
+
+// Selection, directory update and fetch of unit u: latency-bound, so its waves go first whenever
+// they can issue.
+template <int IPT>
+__device__ KVD_ROLE_INLINE void step_select_role(StepArgsPtr ap, int u, unsigned char* smem_raw, int* wait_ok,
+                                                           long long* ts) {
+  struct { FastArgs fa; int32_t* score_done; int32_t* sel_ready; int32_t* error; long long wait_limit; int chunks, epoch; } a;
+  __builtin_memcpy(&a.fa, &ap->fa, sizeof(FastArgs));
+  a.score_done = ap->score_done; a.sel_ready = ap->sel_ready; a.error = ap->error;
+  a.wait_limit = ap->wait_limit; a.chunks = ap->chunks; a.epoch = ap->epoch;
+  const int tid = threadIdx.x;
+  if (ts) ts[4] = 1LL | ((long long)u << 8);
+  __builtin_amdgcn_s_setprio(3);
+  if (!block_wait_equal(&a.score_done[u * kFlagStride], a.chunks * kStepWaves, a.wait_limit, wait_ok)) {
+    if (tid == 0) __hip_atomic_store(a.error, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
     return;
   }
-  // ---- attention workgroup (u, split)
-  const int i = bid - front;
-  const int u = i / a.at.S + a.u0, split = i % a.at.S;
+  if (ts) ts[1] = wall_clock64();
+  if (tid == 0) store_agent(&a.score_done[u * kFlagStride], 0);      // every arrival has been seen: ready for the next launch
+  StepFastSmem& sm = *reinterpret_cast<StepFastSmem*>(smem_raw);
+  select_resolve_body<kStepThreads, IPT, true, true, true>(a.fa, u, sm);
+  if (ts) ts[2] = wall_clock64();
+  wave_drain_memory();                                 // selection, slots and fetched pages have been written through
+  __syncthreads();
+  if (tid == 0) store_agent(&a.sel_ready[u * kFlagStride], a.epoch);
+  if (ts) ts[3] = wall_clock64();
+}
+
+// Attention workgroup (u, split).
+template <bool BF16>
+__device__ KVD_ROLE_INLINE void step_attend_role(StepArgsPtr ap, int u, int split, unsigned char* smem_raw,
+                                                           int* wait_ok, long long* ts) {
+  struct { AttnArgs at; int32_t* sel_ready; int32_t* error; long long wait_limit; int epoch; } a;
+  __builtin_memcpy(&a.at, &ap->at, sizeof(AttnArgs));
+  a.sel_ready = ap->sel_ready; a.error = ap->error; a.wait_limit = ap->wait_limit; a.epoch = ap->epoch;
+  const int tid = threadIdx.x;
   if (ts) ts[4] = 2LL | ((long long)u << 8) | ((long long)split << 32);
-  if (!block_wait_equal(&a.sel_ready[u], a.epoch, a.wait_limit, &wait_ok)) {
+  if (!block_wait_equal(&a.sel_ready[u * kFlagStride], a.epoch, a.wait_limit, wait_ok)) {
     if (tid == 0) __hip_atomic_store(a.error, 2, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
     return;
   }
@@ -131,10 +136,29 @@ __device__ __forceinline__ void step_body(const StepArgs& a, unsigned char* smem
 }
 
 template <bool BF16, int IPT>
+__device__ __forceinline__ void step_body(StepArgsPtr ap, unsigned char* smem_raw, int& wait_ok) {
+  const int bid = blockIdx.x;
+  long long* timeline = ap->timeline;
+  long long* ts = timeline != nullptr && threadIdx.x == 0 ? timeline + (size_t)bid * 5 : nullptr;
+  if (ts) ts[0] = ts[1] = wall_clock64();
+  const int n_score = ap->n_score, n_units = ap->n_units, u0 = ap->u0, S = ap->at.S;
+  const int front = n_score + n_units;
+  if (bid < n_score) {
+    step_score_role<BF16>(ap, bid, ts);
+  } else if (bid < front) {
+    step_select_role<IPT>(ap, bid - n_score + u0, smem_raw, &wait_ok, ts);
+  } else {
+    const int i = bid - front;
+    step_attend_role<BF16>(ap, i / S + u0, i % S, smem_raw, &wait_ok, ts);
+  }
+}
+
+template <bool BF16, int IPT>
 __global__ __launch_bounds__(kStepThreads, 4) void step_kernel(StepArgs a) {
   __shared__ __align__(16) unsigned char smem_raw[kStepSmemBytes];
   __shared__ int wait_ok;
-  step_body<BF16, IPT>(a, smem_raw, wait_ok);
+  // the launch arguments are the first thing in the kernel-argument segment
+  step_body<BF16, IPT>((StepArgsPtr)__builtin_amdgcn_kernarg_segment_ptr(), smem_raw, wait_ok);
 }
 template <bool BF16>
 static void launch_step(int ipt, const StepArgs& a, int n_blocks, hipStream_t s) {
@@ -173,18 +197,28 @@ hipError_t kvd_launch_step(kvd_ctx* c, int layer, int step, const void* q, float
   a.epoch = c->epoch;
   a.n_units = c->U;
   a.u0 = 0;
-  // scoring workgroups: 8 waves x 64 pages x passes each, about 1024 of them over the layer
-  const long long pages = (long long)c->NP * c->U;
-  int passes = (int)((pages + 512LL * 1024 / 2) / (512LL * 1024));
-  if (passes < 1) passes = 1;
-  a.passes = passes;
-  a.chunks = (c->NP + 512 * passes - 1) / (512 * passes);
-  // a unit's selection workgroup is dispatched `lag` units of scoring later than its own scoring:
-  // about one round of resident workgroups (2 per CU), so that it finds its scores complete
-  a.lag = 512 / a.chunks;
-  if (a.lag < 1) a.lag = 1;
-  if (a.lag > c->U) a.lag = c->U;
-  const int n_blocks = c->U * (a.chunks + 1) + c->U * c->S;
+  // Scoring workgroups are persistent: one round of resident workgroups (2 per CU) minus the
+  // slots left to the selection workgroups that run beside them.  A chunk is 8 waves x 64 pages x
+  // passes; passes is chosen so that the chunks of the layer fill whole rounds of the scoring
+  // workgroups (time ~ rounds x passes), finer chunks winning ties.
+  const int slots = 2 * c->n_cus;
+  int reserve = slots / 8;
+  if (reserve > c->U) reserve = c->U;
+  int n_score = slots - reserve;
+  if (n_score < 1) n_score = 1;
+  int best_passes = 1;
+  long long best_cost = -1;
+  for (int passes = 1; passes <= 8; ++passes) {
+    const long long chunks = (c->NP + 512LL * passes - 1) / (512LL * passes);
+    const long long rounds = (chunks * c->U + n_score - 1) / n_score;
+    const long long cost = rounds * passes;
+    if (best_cost < 0 || cost < best_cost) { best_cost = cost; best_passes = passes; }
+  }
+  a.passes = best_passes;
+  a.chunks = (c->NP + 512 * a.passes - 1) / (512 * a.passes);
+  if (n_score > c->U * a.chunks) n_score = c->U * a.chunks;
+  a.n_score = n_score;
+  const int n_blocks = a.n_score + c->U + c->U * c->S;
   c->tl_workgroups = n_blocks;
   if (c->profiling == 2 && n_blocks <= KVD_TIMELINE_MAX) a.timeline = c->d_timeline;
   const int ipt = (c->NP + kStepThreads - 1) / kStepThreads;
