@@ -81,14 +81,16 @@ typedef struct {
   int32_t physical_layers; /* layers present in the host store; layer l reads store layer
                               l % physical_layers.  0 means n_layers. */
   int32_t micro_batches;   /* how kvd_step overlaps selection, fetch and attention ("SFC Disaggregation"):
-                              0 or 1 = one chain of kernels on the caller's stream, no overlap;
-                              n >= 2 = the B sequences are split into n groups, each running
-                                   select -> fetch -> attend as its own chain on one of the library's
-                                   streams, so the fetch of one group overlaps the kernels of the others;
                               -1 = the whole step as one launch in which every (sequence, KV head) unit
                                    moves through the stages on its own, synchronised by flags in
                                    device memory (needs page_size % 16 == 0, max_pages <= 16384,
-                                   capacity_max <= 4096; other shapes run as for 0). */
+                                   capacity_max <= 4096; other shapes run as for 1);
+                              0  = chosen by the library: the one launch where it is the faster form
+                                   (max_pages <= 8192 and at least 32 units), else as for 1;
+                              1  = one chain of kernels on the caller's stream, no overlap;
+                              n >= 2 = the B sequences are split into n groups, each running
+                                   select -> fetch -> attend as its own chain on one of the library's
+                                   streams, so the fetch of one group overlaps the kernels of the others. */
   int32_t attn_splits;     /* split-K factor of the attention kernel; 0 = chosen by the library */
 } kvd_config;
 

@@ -19,6 +19,16 @@
     }                                       \
   } while (0)
 
+// micro_batches -1 asks for the one-launch step wherever it can run; 0 leaves the choice to the
+// library, which takes it where it has measured faster than the chain of kernels: units of at most
+// 8192 pages (the selection role keeps its scores in registers at half the threads of the
+// stand-alone kernel) and enough units to keep its pipeline filled.
+static bool kvd_wants_single_launch(const kvd_ctx* c) {
+  if (!kvd_single_launch_ok(c)) return false;
+  if (c->cfg.micro_batches == -1) return true;
+  return c->cfg.micro_batches == 0 && c->NP <= 8192 && c->U >= 32;
+}
+
 static bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
 static int validate_config(const kvd_config* c) {
@@ -152,7 +162,7 @@ int kvd_create(const kvd_config* cfg, kvd_ctx** out) {
     if (S < 1) S = 1;
     // the one-launch step has 8 waves per attention workgroup and gains from twice as many
     // workgroups (units become ready one after another) as long as a wave keeps 4 tiles or more
-    if (cfg->micro_batches == -1 && kvd_single_launch_ok(c)) {
+    if (kvd_wants_single_launch(c)) {
       int S2 = (1024 + c->U / 2) / c->U;
       if (S2 > KVD_MAX_SPLITS) S2 = KVD_MAX_SPLITS;
       if (S2 >= 1 && tiles / (S2 * 8) >= 4) S = S2;
@@ -200,7 +210,7 @@ int kvd_create(const kvd_config* cfg, kvd_ctx** out) {
   if (e == hipSuccess) ok(hipMemset(c->d_score_done, 0, (size_t)c->U * 32 * sizeof(int32_t)));
   if (e == hipSuccess) ok(hipMemset(c->d_sel_ready, 0, (size_t)c->U * 32 * sizeof(int32_t)));
   if (e == hipSuccess) *c->error_host = 0;
-  if (e == hipSuccess) c->single_launch = cfg->micro_batches == -1 && kvd_single_launch_ok(c);
+  if (e == hipSuccess) c->single_launch = kvd_wants_single_launch(c);
   if (e != hipSuccess) { free_ctx(c); return KVD_ERR_HIP; }
   const int r = reset_directory(c, -1);
   if (r != KVD_OK) { free_ctx(c); return r; }

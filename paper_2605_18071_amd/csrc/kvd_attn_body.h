@@ -97,8 +97,10 @@ __device__ __forceinline__ void merge_splits(const AttnArgs& a, int u) {
 // Workgroup epilogue.  The waves have left their (max, sum, acc) in `sm`; merge them and write
 // this split's partial.  With fuse_merge the partials travel with device-scope stores and the
 // last split of the unit to arrive (a ticket counter) merges all S of them.
+// Returns true in the workgroup that completed the unit's output (with a separate merge kernel:
+// never).
 template <int GT, int NT>
-__device__ __forceinline__ void finish_split(const AttnArgs& a, AttnSmem<GroupMax<GT>::value, NT / kWave>& sm, int u,
+__device__ __forceinline__ bool finish_split(const AttnArgs& a, AttnSmem<GroupMax<GT>::value, NT / kWave>& sm, int u,
                                              int split) {
   constexpr int NW = NT / kWave;
   const int G = group_size<GT>(a);
@@ -140,7 +142,8 @@ __device__ __forceinline__ void finish_split(const AttnArgs& a, AttnSmem<GroupMa
       }
     }
   }
-  if (a.S == 1 || !fused) return;
+  if (a.S == 1) return true;
+  if (!fused) return false;
   wave_drain_memory();                               // this wave's partials have been acknowledged
   __syncthreads();
   if (tid == 0) {
@@ -149,8 +152,9 @@ __device__ __forceinline__ void finish_split(const AttnArgs& a, AttnSmem<GroupMa
     if (t == a.S - 1) store_agent(&a.ticket[u], 0);  // ready for the next launch
   }
   __syncthreads();
-  if (!sm.is_last) return;
+  if (!sm.is_last) return false;
   merge_splits<GT, NT, true>(a, u);
+  return true;
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -189,8 +193,9 @@ __device__ __forceinline__ f32x4 mfma_pv(const uint2& vfrag, const uint2& pfrag,
 // HANDOFF: the selection was written by another workgroup of the same launch.
 // LEAN: for 128 registers per lane (two workgroups of 8 waves per CU): two tile buffers instead of
 // three and the Q^T fragments re-read from LDS for every tile.
+// Returns finish_split's verdict: true in the workgroup that completed the unit's output.
 template <bool BF16, int GT, int NT, bool HANDOFF, bool LEAN = false>
-__device__ __forceinline__ void attend_mfma_body(const AttnArgs& a, AttnSmem<GroupMax<GT>::value, NT / kWave>& sm, int u,
+__device__ __forceinline__ bool attend_mfma_body(const AttnArgs& a, AttnSmem<GroupMax<GT>::value, NT / kWave>& sm, int u,
                                                  int split) {
   constexpr int NW = NT / kWave;
   const int G = group_size<GT>(a);
@@ -358,7 +363,7 @@ __device__ __forceinline__ void attend_mfma_body(const AttnArgs& a, AttnSmem<Gro
       for (int e = 0; e < 4; ++e) sm.acc[w][j][16 * c + 4 * g + e] = o[c][e];
     if (g == 0) { sm.m[w][j] = m; sm.l[w][j] = l; }
   }
-  finish_split<GT, NT>(a, sm, u, split);
+  return finish_split<GT, NT>(a, sm, u, split);
 }
 
 }  // namespace kvd

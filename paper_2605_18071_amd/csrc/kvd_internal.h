@@ -58,7 +58,7 @@ struct kvd_ctx {
   float* d_part_ml;         // [U][S][G][2]  (max in log2 units, sum)
   int32_t* d_attn_ticket;   // [U] arrival counter of the attention splits, zero between launches
   int32_t* d_score_done;    // [U][32] single-launch step: scoring waves arrived (one 128-byte line per unit), zero between launches
-  int32_t* d_sel_ready;     // [U][32] single-launch step: number of the last launch that finished the unit's selection
+  int32_t* d_sel_ready;     // [U][32] single-launch step: 1 once the unit's selection is complete, zero between launches
   unsigned long long* d_stats;  // hits, misses, evictions
 
   // owned, host
@@ -72,7 +72,6 @@ struct kvd_ctx {
   int32_t* error_host;      // pinned word the single-launch step raises when one of its waits runs out
   int32_t* error_dev;       // the same word as the GPU addresses it
   long long wait_limit_ticks;   // bound of every in-kernel wait, in ticks of the 100 MHz wall clock
-  int epoch;                // number of the last single-launch step
   int n_cus;                // compute units of the device
   long long* d_timeline;    // [KVD_TIMELINE_MAX][5] per-workgroup record of the last single-launch step
   int tl_workgroups;        // workgroups of that launch

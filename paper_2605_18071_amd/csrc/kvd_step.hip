@@ -11,7 +11,7 @@
 //     then S attention workgroups per unit.
 // A selection workgroup waits until the unit's scoring waves have all arrived (a counter);
 // an attention workgroup waits until the unit's selection, directory update and fetch are
-// complete (a flag carrying the launch number).  Workgroups are dispatched in index order, so
+// complete (a flag, lowered again by the unit's last attention workgroup).  Workgroups are dispatched in index order, so
 // whatever a waiting workgroup waits for has already been dispatched and needs nothing from
 // later workgroups: the lowest-numbered unfinished workgroup can always run to its end.  Every
 // wait is nevertheless bounded by a wall-clock limit; a wait that runs out raises an error word in
@@ -41,12 +41,12 @@ struct StepArgs {
   FastArgs fa;
   AttnArgs at;
   int32_t* score_done;       // [U][32] (one line per unit) scoring waves of the unit that have arrived (8 per chunk); zero between launches
-  int32_t* sel_ready;        // [U][32] (one line per unit) number of the last launch whose selection for the unit is complete
+  int32_t* sel_ready;        // [U][32] (one line per unit) 1 once the unit's selection, directory update and fetch are complete; zero between launches
   int32_t* error;            // host-visible; set when a wait runs out
   long long* timeline;       // [workgroups][5]: wall-clock ticks at start, wait over, work done, exit; then a tag; or null
   long long wait_limit;      // ticks of the 100 MHz wall clock
   float scale;
-  int epoch, n_units, u0, chunks, passes, n_score;
+  int n_units, u0, chunks, passes, n_score;
 };
 
 typedef AttnSmem<KVD_MAX_GROUP, kStepWaves> StepAttnSmem;
@@ -94,10 +94,10 @@ __device__ KVD_ROLE_INLINE void step_score_role(StepArgsPtr ap, int wg, long lon
 template <int IPT>
 __device__ KVD_ROLE_INLINE void step_select_role(StepArgsPtr ap, int u, unsigned char* smem_raw, int* wait_ok,
                                                            long long* ts) {
-  struct { FastArgs fa; int32_t* score_done; int32_t* sel_ready; int32_t* error; long long wait_limit; int chunks, epoch; } a;
+  struct { FastArgs fa; int32_t* score_done; int32_t* sel_ready; int32_t* error; long long wait_limit; int chunks; } a;
   __builtin_memcpy(&a.fa, &ap->fa, sizeof(FastArgs));
   a.score_done = ap->score_done; a.sel_ready = ap->sel_ready; a.error = ap->error;
-  a.wait_limit = ap->wait_limit; a.chunks = ap->chunks; a.epoch = ap->epoch;
+  a.wait_limit = ap->wait_limit; a.chunks = ap->chunks;
   const int tid = threadIdx.x;
   if (ts) ts[4] = 1LL | ((long long)u << 8);
   __builtin_amdgcn_s_setprio(3);
@@ -112,7 +112,7 @@ __device__ KVD_ROLE_INLINE void step_select_role(StepArgsPtr ap, int u, unsigned
   if (ts) ts[2] = wall_clock64();
   wave_drain_memory();                                 // selection, slots and fetched pages have been written through
   __syncthreads();
-  if (tid == 0) store_agent(&a.sel_ready[u * kFlagStride], a.epoch);
+  if (tid == 0) store_agent(&a.sel_ready[u * kFlagStride], 1);
   if (ts) ts[3] = wall_clock64();
 }
 
@@ -120,18 +120,20 @@ __device__ KVD_ROLE_INLINE void step_select_role(StepArgsPtr ap, int u, unsigned
 template <bool BF16>
 __device__ KVD_ROLE_INLINE void step_attend_role(StepArgsPtr ap, int u, int split, unsigned char* smem_raw,
                                                            int* wait_ok, long long* ts) {
-  struct { AttnArgs at; int32_t* sel_ready; int32_t* error; long long wait_limit; int epoch; } a;
+  struct { AttnArgs at; int32_t* sel_ready; int32_t* error; long long wait_limit; } a;
   __builtin_memcpy(&a.at, &ap->at, sizeof(AttnArgs));
-  a.sel_ready = ap->sel_ready; a.error = ap->error; a.wait_limit = ap->wait_limit; a.epoch = ap->epoch;
+  a.sel_ready = ap->sel_ready; a.error = ap->error; a.wait_limit = ap->wait_limit;
   const int tid = threadIdx.x;
   if (ts) ts[4] = 2LL | ((long long)u << 8) | ((long long)split << 32);
-  if (!block_wait_equal(&a.sel_ready[u * kFlagStride], a.epoch, a.wait_limit, wait_ok)) {
+  if (!block_wait_equal(&a.sel_ready[u * kFlagStride], 1, a.wait_limit, wait_ok)) {
     if (tid == 0) __hip_atomic_store(a.error, 2, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
     return;
   }
   if (ts) ts[1] = wall_clock64();
   StepAttnSmem& sm = *reinterpret_cast<StepAttnSmem*>(smem_raw);
-  attend_mfma_body<BF16, 0, kStepThreads, true, true>(a.at, sm, u, split);
+  const bool last = attend_mfma_body<BF16, 0, kStepThreads, true, true>(a.at, sm, u, split);
+  // every split of the unit has passed its wait by now: lower the flag for the next launch
+  if (last && tid == 0) store_agent(&a.sel_ready[u * kFlagStride], 0);
   if (ts) ts[2] = ts[3] = wall_clock64();
 }
 
@@ -193,8 +195,6 @@ hipError_t kvd_launch_step(kvd_ctx* c, int layer, int step, const void* q, float
   a.timeline = nullptr;
   a.wait_limit = c->wait_limit_ticks;
   a.scale = c->scale;
-  if (++c->epoch <= 0) c->epoch = 1;
-  a.epoch = c->epoch;
   a.n_units = c->U;
   a.u0 = 0;
   // Scoring workgroups are persistent: one round of resident workgroups (2 per CU) minus the

@@ -407,6 +407,42 @@ def test_append_kv_errors():
     rig.close()
 
 
+def test_single_launch_step_replayed_from_a_hip_graph():
+    """The one-launch step keeps no host-side state per launch (its flags lower themselves), so a
+    captured launch can be replayed: every replay must equal the eager step on the same inputs."""
+    w = SCALED[3].replace(steps=8)
+    eager, graphed = R.Rig(w, micro_batches=-1), R.Rig(w, micro_batches=-1)
+    qs = [q[0].contiguous() for q in W.query_stream(w, eager.q0, 8, R.DEV)]
+    for t in range(4):                                                # same history on both sides
+        eager.step(0, t, qs[t])
+        graphed.step(0, t, qs[t])
+    q_static = qs[4].clone()
+    s = torch.cuda.Stream()
+    s.wait_stream(torch.cuda.current_stream())
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g, stream=s):
+        graphed.kvd.step(0, 4, q_static, graphed.out, graphed.lse, stream=s)
+    torch.cuda.synchronize()
+    # (capturing does not run the launch; the first replay is the first execution)
+    for i, t in enumerate([4, 5, 6, 7]):
+        q_static.copy_(qs[t])
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        graphed.kvd.step_trace(graphed.sel_pages, graphed.sel_slots, graphed.hit_mask, graphed.evicted, graphed.counts,
+                               graphed.scores)
+        torch.cuda.synchronize()
+        eager.step(0, 4, qs[t])                                       # the captured launch carries step index 4
+        assert torch.equal(graphed.sel_pages.cpu(), torch.from_numpy(eager.n_sel_pages)), i
+        assert torch.equal(graphed.hit_mask.cpu(), torch.from_numpy(eager.n_hit_mask)), i
+        assert torch.equal(graphed.counts.cpu(), torch.from_numpy(eager.n_counts)), i
+        assert torch.equal(graphed.out.cpu(), torch.from_numpy(eager.n_out)), i
+        assert (torch.zeros(3) + 1).sum().item() == 3.0               # unrelated eager work between replays
+    assert graphed.kvd.stats().misses == eager.kvd.stats().misses
+    eager.close()
+    graphed.close()
+
+
 def test_single_launch_timeline_and_wait_limit():
     """The one-launch step records one line per workgroup, in dispatch order and with consistent
     clocks; a wait limit of zero makes waiting workgroups give up (every kernel still ends
