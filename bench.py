@@ -12,11 +12,14 @@ continued past the configuration's 32 steps when more steps are asked for.
 
 Prints one JSON line: `value` is end-to-end layer-steps/s of the K timed steps
 (fetch of missed pages from pinned host memory included, index / cache / queries
-resident in HBM).  `roofline` is for the dominant HBM-bound kernel, measured in
-the same process with HIP events around every kernel launch (a second pass over
-the same number of steps); `gpu_resident` is the fused GPU-side path (everything
-but the host-link fetch) against the HBM roofline; `cpu_baseline` is the CPU
-oracle timed on a bounded sample of the same workload on the host cores.
+resident in HBM).  `gpu_resident` is the same step with every selected page
+already resident (nothing crosses the host link), timed with HIP events on the
+stream, against the HBM roofline; `roofline` is for the dominant kernel: the
+one-launch `step_kernel` on those resident launches when the step runs as one
+launch, else the larger of the scoring / attention kernels of the chain, from a
+pass with HIP events around every kernel launch (`kernels_ms`, the stage
+breakdown); `cpu_baseline` is the CPU oracle timed on a bounded sample of the
+same workload on the host cores.
 """
 from __future__ import annotations
 
@@ -34,7 +37,7 @@ if ROOT not in sys.path:
 HBM_PEAK_GBPS = 8000.0
 # HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this command, scaled by
 # what the same counters read for a plain copy of known size (profiles/pmc_traffic_cfg3.md)
-PMC_TRAFFIC_BYTES = {("cfg3", "attend"): 270482432, ("cfg3", "score"): 273769472}
+PMC_TRAFFIC_BYTES = {("cfg3", "step"): 565383168, ("cfg3", "attend"): 271947776, ("cfg3", "score"): 273769472}
 
 
 def describe(w) -> str:
@@ -112,7 +115,7 @@ def main() -> int:
     ap.add_argument("--steps", type=int, default=62)
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--config", type=int, default=3)
-    ap.add_argument("--micro-batches", type=int, default=0, help="kvd_config.micro_batches (-1 = the step as one launch)")
+    ap.add_argument("--micro-batches", type=int, default=0, help="kvd_config.micro_batches (0 = library chooses, 1 = chain of kernels, -1 = one launch)")
     ap.add_argument("--policy", choices=["lru", "lookahead"], default="lru", help="cache replacement policy")
     ap.add_argument("--window", type=float, default=0.0,
                     help="cache capacity as a multiple of the per-step budget k (the paper's window size); "
@@ -120,7 +123,7 @@ def main() -> int:
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="0 skips the oracle baseline")
     ap.add_argument("--no-profile-pass", action="store_true", help="skip the per-kernel HIP-event pass")
     ap.add_argument("--timeline", action="store_true",
-                    help="with --micro-batches -1: add the per-workgroup timeline of one all-hit single-launch step")
+                    help="when the step runs as one launch: add the per-workgroup timeline of one all-hit step")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this path is built and measured on one GPU only (no collectives, no sharding); "
@@ -206,9 +209,13 @@ def main() -> int:
                   "host_link_GBps_if_fetch_bound": gathered_per_step / (elapsed / args.steps) / 1e9},
     }
 
+    single = ctx.step_form() == -1
+    result["config"]["step_form"] = "one launch (step_kernel)" if single else f"chain of kernels x {ctx.step_form()} group(s)"
+    gpu_bytes = summary_bytes + selected_bytes + io_bytes
     if not args.no_profile_pass:
-        # pass 2: the same workload continued, every kernel bracketed by HIP events on its stream
-        ctx.set_profiling(True)
+        # pass 2: the same workload continued as a chain of stand-alone kernels, every kernel
+        # bracketed by HIP events on its stream: the stage breakdown
+        ctx.set_profiling(1)
         ctx.reset_stats()
         for _ in range(args.steps):
             ctx.step(0, t, queries[t], out, stream=stream)
@@ -217,45 +224,58 @@ def main() -> int:
         ps = ctx.stats()
         n = max(1, ps.profiled_steps)
         ms_score, ms_attend = ps.ms_score / n, ps.ms_attend / n
-        name, ms, alg = ("attend", ms_attend, selected_bytes) if ms_attend >= ms_score else ("score", ms_score, summary_bytes)
-        achieved = alg / (ms * 1e-3) / 1e9
-        traffic = PMC_TRAFFIC_BYTES.get((w.name, name))
-        result["roofline"] = {"kernel": {"attend": "attend_mfma_kernel", "score": "score_kernel"}[name], "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBPS,
-                              "unit": "GB/s", "frac": achieved / HBM_PEAK_GBPS, "traffic": traffic,
-                              "algorithmic_bytes_per_launch": alg, "avg_launch_ms": ms}
-        other = ("score", ms_score, summary_bytes) if name == "attend" else ("attend", ms_attend, selected_bytes)
-        result["kernels_ms"] = {"score": ms_score, "select_resolve_fetch": ps.ms_select_resolve / n,
+        result["kernels_ms"] = {"what": "stage breakdown: the step run as a chain of stand-alone kernels, HIP events around each",
+                                "score": ms_score, "select_resolve_fetch": ps.ms_select_resolve / n,
                                 "fetch_separate": ps.ms_gather / n, "attend": ms_attend, "merge": ps.ms_merge / n,
-                                f"{other[0]}_GBps": other[2] / (other[1] * 1e-3) / 1e9}
+                                "score_GBps": summary_bytes / (ms_score * 1e-3) / 1e9,
+                                "attend_GBps": selected_bytes / (ms_attend * 1e-3) / 1e9}
         fetch_ms = (ps.ms_select_resolve + ps.ms_gather) / n
         result["host_link"] = {"bytes_per_step": ps.gathered_bytes / n,
                                "GBps_over_select_resolve_fetch": ps.gathered_bytes / n / (fetch_ms * 1e-3) / 1e9}
 
-        # pass 3: the GPU-resident path alone.  The last query is replayed, so every selected page
-        # is a hit and nothing crosses the host link: wall time per step = GPU time of
-        # score -> select -> resolve -> attend -> merge.  Bytes = summaries + selected K/V + q/out.
-        ctx.set_profiling(False)
+        # pass 3: the GPU-resident path alone, in the form the timed region used.  The last query is
+        # replayed, so every selected page is a hit and nothing crosses the host link: time per
+        # step = GPU time of score -> select -> resolve -> attend -> merge, taken with HIP events
+        # on the stream around the K launches.  Bytes = summaries + selected K/V + q/out.
+        ctx.set_profiling(0)
         q_last = queries[t - 1]
         for _ in range(3):
             ctx.step(0, t, q_last, out, stream=stream)
             t += 1
         torch.cuda.synchronize()
         ctx.reset_stats()
-        t1 = time.perf_counter()
+        ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        ev0.record(stream)
         for _ in range(args.steps):
             ctx.step(0, t, q_last, out, stream=stream)
             t += 1
+        ev1.record(stream)
         torch.cuda.synchronize()
-        res_ms = 1e3 * (time.perf_counter() - t1) / args.steps
+        res_ms = ev0.elapsed_time(ev1) / args.steps
         rs = ctx.stats()
-        gpu_bytes = summary_bytes + selected_bytes + io_bytes
         result["gpu_resident"] = {
-            "what": "all-hit replay of one query: wall time per layer-step of score+select+resolve+attend+merge",
+            "what": "all-hit replay of one query: time per layer-step of score+select+resolve+attend+merge",
             "ms_per_step": res_ms, "layer_steps_per_s": 1e3 / res_ms, "misses": int(rs.misses), "bytes": gpu_bytes,
             "GBps": gpu_bytes / (res_ms * 1e-3) / 1e9, "frac_of_hbm_peak": gpu_bytes / (res_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS,
         }
+        if single:
+            # the step is one kernel: its launch is bound by the host link while pages are missed
+            # and by HBM once they are resident; the roofline is taken on the resident launches
+            result["roofline"] = {"kernel": "step_kernel", "bound": "hbm", "achieved": gpu_bytes / (res_ms * 1e-3) / 1e9,
+                                  "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": gpu_bytes / (res_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS,
+                                  "traffic": PMC_TRAFFIC_BYTES.get((w.name, "step")), "algorithmic_bytes_per_launch": gpu_bytes,
+                                  "avg_launch_ms": res_ms,
+                                  "launches": "the all-hit launches (selected pages resident); the timed region's launches "
+                                              "also wait for the host-link fetch, see host_link"}
+        else:
+            name, ms, alg = ("attend", ms_attend, selected_bytes) if ms_attend >= ms_score else ("score", ms_score, summary_bytes)
+            achieved = alg / (ms * 1e-3) / 1e9
+            result["roofline"] = {"kernel": {"attend": "attend_mfma_kernel", "score": "score_kernel"}[name], "bound": "hbm",
+                                  "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBPS,
+                                  "traffic": PMC_TRAFFIC_BYTES.get((w.name, name)), "algorithmic_bytes_per_launch": alg,
+                                  "avg_launch_ms": ms}
 
-    if args.timeline and args.micro_batches == -1 and not args.no_profile_pass:
+    if args.timeline and single and not args.no_profile_pass:
         result["timeline"] = step_timeline(ctx, t, q_last, out, stream)
 
     if args.cpu_seconds > 0:

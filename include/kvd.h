@@ -234,6 +234,9 @@ int kvd_step_trace(kvd_ctx* ctx, int32_t* sel_pages, int32_t* sel_slots, int32_t
  * mode 2: a single-launch kvd_step also records, per workgroup, four readings of the GPU's 100 MHz
  *         wall clock (see kvd_step_timeline); the step stays asynchronous. */
 int kvd_set_profiling(kvd_ctx* ctx, int32_t mode);
+/* The form kvd_step takes for this context, in the terms of kvd_config.micro_batches: -1 one launch,
+ * 1 a chain of kernels, n >= 2 that many groups on the library's streams. */
+int kvd_step_form(const kvd_ctx* ctx);
 /* Bound of every wait inside the one-launch kvd_step (micro_batches = -1), where workgroups wait on
  * flags in device memory for the workgroups before them.  Default 2 s.  A wait that runs out makes
  * its workgroup leave without output and raises a sticky error: kvd_get_stats and later kvd_step

@@ -522,6 +522,11 @@ int kvd_set_profiling(kvd_ctx* ctx, int32_t on) {
   return KVD_OK;
 }
 
+int kvd_step_form(const kvd_ctx* ctx) {
+  if (!ctx) return KVD_ERR_ARG;
+  return ctx->single_launch ? -1 : ctx->MB;
+}
+
 int kvd_set_wait_limit_us(kvd_ctx* ctx, int64_t microseconds) {
   if (!ctx || microseconds < 0) return KVD_ERR_ARG;
   ctx->wait_limit_ticks = microseconds * 100;        // the GPU wall clock runs at 100 MHz

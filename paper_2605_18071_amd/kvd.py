@@ -46,7 +46,7 @@ EXPORTS = [
     "kvd_bind_summaries", "kvd_bind_host_store", "kvd_bind_slot_pool", "kvd_set_seq_lens",
     "kvd_build_summaries", "kvd_cache_reset", "kvd_cache_warm", "kvd_cache_export", "kvd_cache_import",
     "kvd_append_kv", "kvd_advance", "kvd_score_select", "kvd_cache_resolve", "kvd_sparse_decode_attn", "kvd_step", "kvd_step_trace",
-    "kvd_set_profiling", "kvd_set_wait_limit_us", "kvd_step_timeline", "kvd_get_stats", "kvd_reset_stats",
+    "kvd_set_profiling", "kvd_step_form", "kvd_set_wait_limit_us", "kvd_step_timeline", "kvd_get_stats", "kvd_reset_stats",
 ]
 
 _lib = None
@@ -85,6 +85,7 @@ def load() -> C.CDLL:
         "kvd_set_profiling": [vp, i32],
         "kvd_step_timeline": [vp, C.POINTER(C.c_int64), i32, i32p],
         "kvd_set_wait_limit_us": [vp, C.c_int64],
+        "kvd_step_form": [vp],
         "kvd_get_stats": [vp, C.POINTER(KvdStats)],
         "kvd_reset_stats": [vp],
     }
@@ -243,6 +244,9 @@ class Kvd:
     # ---- counters
     def set_profiling(self, mode):
         self._check(self.lib.kvd_set_profiling(self.ctx, int(mode)), "kvd_set_profiling")
+
+    def step_form(self) -> int:
+        return int(self.lib.kvd_step_form(self.ctx))
 
     def set_wait_limit_us(self, microseconds: int):
         self._check(self.lib.kvd_set_wait_limit_us(self.ctx, int(microseconds)), "kvd_set_wait_limit_us")
