@@ -170,8 +170,12 @@ __device__ __forceinline__ int victim_bucket(long long age, int page, int NP) {
 // with do_gather, the copy of the missed pages into their slots.  HANDOFF: the scores were
 // written by other workgroups of the same launch and are read with device-scope loads.
 // Needs NP <= NT * IPT, Cmax <= KVD_FAST_MAX_CAPACITY, k <= KVD_MAX_TOPK.
-template <int NT, int IPT, bool DO_SELECT, bool DO_RESOLVE, bool HANDOFF>
-__device__ __forceinline__ void select_resolve_body(const FastArgs& a, int u, FastSmem<NT>& sm) {
+// scores_ready() (HANDOFF only) is called by all threads once everything that does not depend on
+// the scores has been done; it waits for them and returns false to give up.  Returns false then.
+struct ScoresAlreadyThere { __device__ bool operator()() const { return true; } };
+template <int NT, int IPT, bool DO_SELECT, bool DO_RESOLVE, bool HANDOFF, class ScoresReady = ScoresAlreadyThere>
+__device__ __forceinline__ bool select_resolve_body(const FastArgs& a, int u, FastSmem<NT>& sm,
+                                                    ScoresReady scores_ready = ScoresReady()) {
   constexpr int CPT = KVD_FAST_MAX_CAPACITY / NT;
   constexpr int KPT = KVD_MAX_TOPK / NT;
   constexpr int NW = NT / kWave;
@@ -199,7 +203,7 @@ __device__ __forceinline__ void select_resolve_body(const FastArgs& a, int u, Fa
   const int p0 = tid * IPT;
   float s[IPT];
   int seq = 0;
-  if (DO_SELECT) {
+  auto load_scores = [&]() {
     const float* sc = a.scores + (size_t)u * a.NP;
     if (HANDOFF) {
 #pragma unroll
@@ -215,6 +219,9 @@ __device__ __forceinline__ void select_resolve_body(const FastArgs& a, int u, Fa
 #pragma unroll
       for (int j = 0; j < IPT; ++j) s[j] = (p0 + j) < a.NP ? sc[p0 + j] : 0.f;
     }
+  };
+  if (DO_SELECT) {
+    if (!HANDOFF) load_scores();                       // (with HANDOFF the scores may not be complete yet)
     seq = a.seq_len[b];
   } else {
     for (int i = tid; i < k; i += NT) {
@@ -240,6 +247,16 @@ __device__ __forceinline__ void select_resolve_body(const FastArgs& a, int u, Fa
       const int sl = tid * CPT + j;
       if (sl >= C && sp[j] != -2) sp[j] = -2;          // slots beyond this unit's capacity do not exist
       if (sp[j] >= 0) sm.p2s[sp[j]] = (uint16_t)sl;
+    }
+  }
+  if (HANDOFF) {
+    // everything that does not need the scores is done: now wait for them
+    if (!scores_ready()) return false;
+    if (DO_SELECT) load_scores();
+  }
+  if (DO_RESOLVE) {
+#pragma unroll
+    for (int j = 0; j < CPT; ++j) {
       vs[j] = 0.f;
       if (a.lookahead && sp[j] >= 0) {
         const float* sc = a.scores + (size_t)u * a.NP + sp[j];
@@ -332,7 +349,7 @@ __device__ __forceinline__ void select_resolve_body(const FastArgs& a, int u, Fa
       if (HANDOFF) store_agent(out + i, -1);
       else out[i] = -1;
     }
-    if (!DO_RESOLVE) return;
+    if (!DO_RESOLVE) return true;
     // the histogram and the candidate counter serve the victim choice next
     for (int i = tid; i < kRadixBins; i += NT) sm.a.sel.hist[i] = 0;
     if (tid == 0) sm.cand_n = 0;
@@ -500,7 +517,7 @@ __device__ __forceinline__ void select_resolve_body(const FastArgs& a, int u, Fa
     atomicAdd(&a.stats[1], (unsigned long long)m);
     atomicAdd(&a.stats[2], (unsigned long long)e);
   }
-  if (!a.do_gather || m == 0) return;
+  if (!a.do_gather || m == 0) return true;
 
   // ---- fetch the unit's missed pages: groups of 256 threads, one 16-token tile (or one page in
   // the natural layout) each per round.  Miss j is (page, sm.assign[j]); the pages are staged in
@@ -546,6 +563,7 @@ __device__ __forceinline__ void select_resolve_body(const FastArgs& a, int u, Fa
       for (unsigned o = gt; o < units; o += 256) slot_store16<HANDOFF>(d4 + o, s4[o]);
     }
   }
+  return true;
 }
 
 }  // namespace kvd

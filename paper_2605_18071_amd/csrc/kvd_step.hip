@@ -101,14 +101,18 @@ __device__ KVD_ROLE_INLINE void step_select_role(StepArgsPtr ap, int u, unsigned
   const int tid = threadIdx.x;
   if (ts) ts[4] = 1LL | ((long long)u << 8);
   __builtin_amdgcn_s_setprio(3);
-  if (!block_wait_equal(&a.score_done[u * kFlagStride], a.chunks * kStepWaves, a.wait_limit, wait_ok)) {
+  StepFastSmem& sm = *reinterpret_cast<StepFastSmem*>(smem_raw);
+  // the directory is loaded and the LDS tables are set up while the unit's scores are still coming in
+  auto scores_ready = [&]() -> bool {
+    const bool ok = block_wait_equal(&a.score_done[u * kFlagStride], a.chunks * kStepWaves, a.wait_limit, wait_ok);
+    if (ts) ts[1] = wall_clock64();
+    if (ok && tid == 0) store_agent(&a.score_done[u * kFlagStride], 0);   // every arrival has been seen: ready for the next launch
+    return ok;
+  };
+  if (!select_resolve_body<kStepThreads, IPT, true, true, true>(a.fa, u, sm, scores_ready)) {
     if (tid == 0) __hip_atomic_store(a.error, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
     return;
   }
-  if (ts) ts[1] = wall_clock64();
-  if (tid == 0) store_agent(&a.score_done[u * kFlagStride], 0);      // every arrival has been seen: ready for the next launch
-  StepFastSmem& sm = *reinterpret_cast<StepFastSmem*>(smem_raw);
-  select_resolve_body<kStepThreads, IPT, true, true, true>(a.fa, u, sm);
   if (ts) ts[2] = wall_clock64();
   wave_drain_memory();                                 // selection, slots and fetched pages have been written through
   __syncthreads();
