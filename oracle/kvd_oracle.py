@@ -20,6 +20,8 @@ index held in GPU memory, (2) fetch them, (3) compute sparse attention):
   LookaheadWindow  the same window with the paper's own policy:  (Cache Management, "Sliding Window w/
                    the lowest current-step scores leave          Lookahead Eviction")
   attend           softmax attention over the selected tokens   (System Overview, step 3)
+  kmeans_centroids the hierarchical index: page means grouped   (System Overview: the page means form
+  select_pages_hier  into centroids; selection over centroids    higher-level centroids for similarity grouping)
 
 Readings taken where the paper is silent (each one is also listed in the design
 notes of the repository):
@@ -38,6 +40,17 @@ notes of the repository):
     selection order).  The look-ahead pool of the evaluation (M = 2560 for
     K = 2048) is read as "all scored pages": with every page score at hand a
     finite pool only coarsens the order beyond rank M.
+
+  * hierarchical index: Lloyd's k-means over the page summaries of a unit (the
+    paper names k-means clustering and a number of centroids, nothing more):
+    squared Euclidean distance, ties to the lower centroid index, initial
+    centroids = the pages at evenly spaced positions, a fixed number of
+    iterations, an empty cluster keeps its centroid; a cluster's representative
+    is the mean of its pages' summaries in ascending page order, rounded once to
+    the KV dtype.  Selection ranks clusters by centroid score (ties to the lower
+    cluster) and takes whole clusters until the page budget k is used up; the
+    first cluster that does not fit gives its lowest pages; sink / recent pages
+    are in unconditionally and are left out of the clusters' count.
 
 Parity status.  select/LRU/attend/summaries are pinned in tests by brute force,
 closed forms, library routines and hand-worked fixtures (tests/golden).
@@ -164,6 +177,101 @@ def select_pages(scores, k, sink_pages=0, recent_pages=0):
     chosen = sorted(order[: min(k, n)])
     out = np.full(k, -1, dtype=np.int32)
     out[: len(chosen)] = chosen
+    return out
+
+
+# --------------------------------------------------------------------------- #
+# hierarchical index: centroids over page summaries
+# --------------------------------------------------------------------------- #
+def kmeans_init(points, n_centroids):
+    """Initial centroids: the points at evenly spaced positions
+    floor((i + 1/2) * n / n_centroids), i = 0 .. n_centroids - 1."""
+    n = points.shape[0]
+    idx = ((np.arange(n_centroids) + 0.5) * n / n_centroids).astype(np.int64)
+    return points[idx].copy()
+
+
+def kmeans_distances(points, centroids):
+    """Squared Euclidean distance of every point to every centroid, [n, n_centroids]."""
+    pn = np.sum(points * points, axis=1)
+    cn = np.sum(centroids * centroids, axis=1)
+    return pn[:, None] - 2.0 * (points @ centroids.T) + cn[None, :]
+
+
+def kmeans_assign(points, centroids):
+    """Nearest centroid of every point; equal distances go to the lower index."""
+    return np.argmin(kmeans_distances(points, centroids), axis=1).astype(np.int32)
+
+
+def kmeans_update(points, assign, centroids):
+    """New centroid = mean of the cluster's points, summed in ascending point order;
+    a cluster without points keeps its centroid."""
+    out = centroids.copy()
+    for c in range(centroids.shape[0]):
+        members = np.nonzero(assign == c)[0]
+        if len(members) == 0:
+            continue
+        acc = np.zeros(points.shape[1], dtype=np.float64)
+        for p in members:
+            acc = acc + points[p]
+        out[c] = acc / float(len(members))
+    return out
+
+
+def kmeans_centroids(points, n_centroids, iterations, dtype, forced_assign=None):
+    """The hierarchical index of one unit (System Overview: the page means form
+    higher-level centroids for similarity grouping).
+
+    points  [NPvalid, D] fp64 page summaries.  `iterations` rounds of (assign to the
+    nearest centroid, move every centroid to the mean of its pages).
+    forced_assign: optional list, one assignment array per iteration, that replaces
+            the oracle's own nearest-centroid decision (parity harness, after a
+            distance tie inside the tolerance band).
+    returns (centroids [n_centroids, D] rounded once to `dtype`,
+             assign [NPvalid] int32: the cluster of every page, used for the last move,
+             exact [n_centroids, D] the unrounded centroids)
+    """
+    cent = kmeans_init(points, n_centroids)
+    assign = np.zeros(points.shape[0], dtype=np.int32)
+    for it in range(int(iterations)):
+        assign = kmeans_assign(points, cent) if forced_assign is None else np.asarray(forced_assign[it], dtype=np.int32)
+        cent = kmeans_update(points, assign, cent)
+    return round_f64(cent, dtype), assign, cent
+
+
+def cluster_members(assign, n_centroids):
+    """Pages of every cluster in ascending order."""
+    return [np.nonzero(assign == c)[0].astype(np.int32) for c in range(n_centroids)]
+
+
+def select_pages_hier(cluster_scores, members, k, n_valid, sink_pages=0, recent_pages=0):
+    """Selection through the hierarchical index.
+
+    cluster_scores [n_centroids] fp64 (scale * pooled query . centroid); members[c] the
+    ascending pages of cluster c.  Clusters are taken in the order (score descending,
+    cluster ascending) until k pages are used: whole clusters while they fit, then the
+    lowest pages of the first one that does not.  Pages p < sink_pages and
+    p >= n_valid - recent_pages are always in, are charged first, and do not count as
+    members of their clusters.
+    returns int32 [k] ascending pages, padded with -1.
+    """
+    forced = set(range(min(int(sink_pages), n_valid)))
+    if recent_pages > 0:
+        forced |= set(range(max(0, n_valid - int(recent_pages)), n_valid))
+    if len(forced) > k:
+        raise ValueError("forced pages exceed k")
+    chosen = set(forced)
+    budget = k - len(forced)
+    order = sorted(range(len(members)), key=lambda c: (-float(cluster_scores[c]), c))
+    for c in order:
+        if budget <= 0:
+            break
+        take = [int(p) for p in members[c] if int(p) not in forced][:budget]
+        chosen |= set(take)
+        budget -= len(take)
+    out = np.full(k, -1, dtype=np.int32)
+    pages = sorted(chosen)
+    out[: len(pages)] = pages
     return out
 
 
@@ -305,7 +413,7 @@ def attend(q_group, keys, values, scale):
 # --------------------------------------------------------------------------- #
 def decode_unit_step(q_group, summaries, keys, values, window, step, *, k, page_size,
                      seq_len, scale, sink_pages=0, recent_pages=0, forced_sel=None,
-                     forced_evicted=None):
+                     forced_evicted=None, centroids=None, members=None):
     """select -> fetch bookkeeping -> attend for one unit.
 
     q_group   [G, D] fp64 (queries already rounded to the KV dtype by the caller)
@@ -314,11 +422,18 @@ def decode_unit_step(q_group, summaries, keys, values, window, step, *, k, page_
     forced_sel: if given, this selection replaces the oracle's own (used by the
               parity harness after a score tie inside the 1e-6 band).
     forced_evicted: likewise for the victims of a LookaheadWindow.
+    centroids, members: if given, selection goes through the hierarchical index
+              (cluster scores instead of page scores; `scores` in the result are then
+              the cluster scores, and lookahead eviction is not defined).
     returns dict(scores, sel, hits, misses, evicted, out, lse)
     """
     qbar = pooled_query(q_group)
-    scores = page_scores(qbar, summaries, scale)
-    sel = select_pages(scores, k, sink_pages, recent_pages)
+    if centroids is None:
+        scores = page_scores(qbar, summaries, scale)
+        sel = select_pages(scores, k, sink_pages, recent_pages)
+    else:
+        scores = page_scores(qbar, centroids, scale)
+        sel = select_pages_hier(scores, members, k, -(-int(seq_len) // int(page_size)), sink_pages, recent_pages)
     used = sel if forced_sel is None else np.asarray(forced_sel, dtype=np.int32)
     hits, misses, evicted = window.resolve(used, step, scores=scores, forced_evicted=forced_evicted)
     toks = selected_tokens(used, page_size, seq_len)

@@ -355,6 +355,111 @@ def test_lookahead_forced_eviction_and_errors():
 
 
 # --------------------------------------------------------------------------- #
+# hierarchical index
+# --------------------------------------------------------------------------- #
+def _blobs(n_blobs, per_blob, dim, spread, seed):
+    rng = np.random.default_rng(seed)
+    centres = rng.normal(size=(n_blobs, dim)) * 4.0
+    pts = np.concatenate([c + spread * rng.normal(size=(per_blob, dim)) for c in centres])
+    return orc.round_f64(pts[rng.permutation(len(pts))], orc.BF16)
+
+
+def test_kmeans_matches_sklearn_lloyd():
+    """The same initial centroids and iteration count through scikit-learn's Lloyd k-means."""
+    from sklearn.cluster import KMeans
+    pts = _blobs(12, 40, 24, 0.6, 3)
+    for n_c, iters in [(12, 5), (30, 4), (60, 7)]:
+        _, assign, exact = orc.kmeans_centroids(pts, n_c, iters, orc.BF16)
+        assert np.bincount(assign, minlength=n_c).min() > 0          # sklearn would relocate empty clusters
+        km = KMeans(n_clusters=n_c, init=orc.kmeans_init(pts, n_c), n_init=1, max_iter=iters, tol=0.0, algorithm="lloyd").fit(pts)
+        assert np.allclose(km.cluster_centers_, exact, rtol=1e-9, atol=1e-9)
+
+
+def test_kmeans_closed_forms_and_invariants():
+    rng = np.random.default_rng(8)
+    pts = orc.round_f64(rng.normal(size=(96, 16)), orc.F16)
+    # as many centroids as points: every point is its own cluster and its own centroid
+    cent, assign, _ = orc.kmeans_centroids(pts, 96, 3, orc.F16)
+    assert np.array_equal(assign, np.arange(96)) and np.array_equal(cent, pts)
+    # one centroid: the mean of everything (one rounding)
+    cent, assign, exact = orc.kmeans_centroids(pts, 1, 2, orc.F16)
+    assert np.all(assign == 0) and np.allclose(exact[0], pts.mean(axis=0), rtol=0, atol=1e-12)
+    assert np.array_equal(cent[0], orc.round_f64(exact[0], orc.F16))
+    # well separated blobs, one initial centroid inside each: the blobs are recovered
+    centres = np.eye(6, 16) * 50.0
+    blob_pts = np.concatenate([centres[i] + 0.1 * rng.normal(size=(10, 16)) for i in range(6)])   # evenly spaced init hits every blob
+    _, assign, exact = orc.kmeans_centroids(blob_pts, 6, 4, orc.BF16)
+    assert np.array_equal(assign, np.repeat(np.arange(6), 10))
+    assert np.allclose(exact, blob_pts.reshape(6, 10, 16).mean(axis=1))
+    # Lloyd never increases the within-cluster sum of squares; a centroid is the mean of its members;
+    # every point sits with a nearest centroid of the round it was assigned in
+    pts = _blobs(9, 30, 12, 1.0, 5)
+    prev = np.inf
+    for iters in range(1, 7):
+        cent, assign, exact = orc.kmeans_centroids(pts, 20, iters, orc.BF16)
+        inertia = float(np.sum((pts - exact[assign]) ** 2))
+        assert inertia <= prev + 1e-9
+        prev = inertia
+        for c in range(20):
+            members = np.nonzero(assign == c)[0]
+            if len(members):
+                assert np.allclose(exact[c], pts[members].mean(axis=0), rtol=0, atol=1e-12)
+        assert np.array_equal(cent, orc.round_f64(exact, orc.BF16))
+    before = orc.kmeans_centroids(pts, 20, 5, orc.BF16)[2]
+    d = ((pts[:, None, :] - before[None, :, :]) ** 2).sum(axis=2)                 # brute-force distances
+    _, assign6, _ = orc.kmeans_centroids(pts, 20, 6, orc.BF16)
+    assert np.allclose(d[np.arange(len(pts)), assign6], d.min(axis=1), rtol=1e-12, atol=1e-12)
+    # distance ties go to the lower centroid; an empty cluster keeps its centroid
+    pts2 = np.array([[0.0, 0.0], [2.0, 0.0], [1.0, 0.0]])
+    cents = np.array([[0.0, 0.0], [2.0, 0.0], [9.0, 9.0]])
+    assert orc.kmeans_assign(pts2, cents).tolist() == [0, 1, 0]
+    assert np.array_equal(orc.kmeans_update(pts2, np.array([0, 1, 0]), cents), np.array([[0.5, 0.0], [2.0, 0.0], [9.0, 9.0]]))
+    # forcing the assignments replaces the oracle's own decisions
+    forced = [np.array([1, 1, 0]), np.array([0, 0, 1])]
+    _, a, exact = orc.kmeans_centroids(pts2, 2, 2, orc.BF16, forced_assign=forced)
+    assert a.tolist() == [0, 0, 1] and np.array_equal(exact, np.array([[1.0, 0.0], [1.0, 0.0]]))
+
+
+def test_hier_select_golden_fixture():
+    members = [np.array(m, dtype=np.int32) for m in ([0, 1], [2, 7, 9], [], [3, 4, 5, 6], [8, 11], [10])]
+    for scores, k, sink, recent, want in H.read_golden("hier_select_6clusters.txt"):
+        sc = np.array([float(x) for x in scores.split()])
+        got = orc.select_pages_hier(sc, members, int(k), 12, int(sink), int(recent))
+        exp = _ints(want)
+        assert got.tolist() == exp + [-1] * (int(k) - len(exp)), (scores, k)
+
+
+def test_hier_select_reduces_to_flat_selection_and_brute_force():
+    rng = np.random.default_rng(21)
+    # one page per cluster, cluster c = page c: the hierarchical rule is the flat Top-K rule
+    for n, k, sink, recent in [(50, 7, 0, 0), (64, 16, 2, 3), (10, 10, 0, 0), (9, 12, 1, 1)]:
+        sc = np.round(rng.normal(size=n), 1)
+        members = [np.array([c], dtype=np.int32) for c in range(n)]
+        assert np.array_equal(orc.select_pages_hier(sc, members, k, n, sink, recent), orc.select_pages(sc, k, sink, recent))
+    # random clusters: page by page simulation of "walk the ranked clusters, one page at a time"
+    for trial in range(30):
+        n, n_c, k = 80, 23, int(rng.integers(1, 60))
+        assign = rng.integers(0, n_c, size=n)
+        members = orc.cluster_members(assign, n_c)
+        sc = np.round(rng.normal(size=n_c), 1)
+        ranked = np.lexsort((np.arange(n_c), -sc))
+        walk = [p for c in ranked for p in np.sort(np.nonzero(assign == c)[0])]
+        want = sorted(walk[:k])
+        got = orc.select_pages_hier(sc, members, k, n)
+        assert got[got >= 0].tolist() == want and len(want) == min(k, n)
+        # with forced pages: they go in first and the walk skips them
+        sink, recent = int(rng.integers(0, 3)), int(rng.integers(0, 4))
+        forced = sorted(set(range(sink)) | set(range(n - recent, n)))
+        if len(forced) <= k:
+            walk2 = [p for p in walk if p not in forced]
+            want2 = sorted(forced + walk2[:k - len(forced)])
+            got2 = orc.select_pages_hier(sc, members, k, n, sink, recent)
+            assert got2[got2 >= 0].tolist() == want2
+    with pytest.raises(ValueError):
+        orc.select_pages_hier(np.zeros(3), [np.array([0]), np.array([1]), np.array([2])], 2, 3, sink_pages=2, recent_pages=1)
+
+
+# --------------------------------------------------------------------------- #
 # attention
 # --------------------------------------------------------------------------- #
 def test_attention_closed_form_fixture():
