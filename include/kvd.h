@@ -92,6 +92,14 @@ typedef struct {
                                    select -> fetch -> attend as its own chain on one of the library's
                                    streams, so the fetch of one group overlaps the kernels of the others. */
   int32_t attn_splits;     /* split-K factor of the attention kernel; 0 = chosen by the library */
+  int32_t index_centroids; /* Nc: 0 = selection scores every page summary (flat index); > 0 = hierarchical
+                              index (System Overview: the page means form higher-level centroids): the page
+                              summaries of a unit are grouped into Nc clusters by k-means, selection scores
+                              the Nc centroids and takes whole clusters, best first, until k pages are used
+                              (the first cluster that does not fit gives its lowest pages; sink / recent pages
+                              are in first and do not count as members).  Nc <= 8192, Nc <= max_pages <= 16384;
+                              not with KVD_EVICT_LOOKAHEAD (which needs a score per page); kvd_step then runs
+                              as a chain of kernels. */
 } kvd_config;
 
 typedef struct {
@@ -193,6 +201,23 @@ int kvd_cache_resolve(kvd_ctx* ctx, int32_t layer, int32_t step, const int32_t* 
  *   lse [B][Hq] fp32 out or NULL: log sum exp of the scaled logits. */
 int kvd_sparse_decode_attn(kvd_ctx* ctx, int32_t layer, const void* q, const int32_t* sel_pages,
                            const int32_t* sel_slots, float* out, float* lse, void* stream);
+
+/* ---- hierarchical index ------------------------------------------------------------------------ */
+
+/* Buffers of the hierarchical index (index_centroids = Nc > 0), all device memory owned by the caller:
+ *   dev_centroids      [L][B][Hkv][Nc][D] kv_dtype, 16-byte aligned
+ *   dev_cluster_start  [L][B][Hkv][Nc+1] int32: cluster c owns entries [start[c], start[c+1]) of
+ *   dev_cluster_pages  [L][B][Hkv][NP] int32: the pages of every cluster, ascending inside a cluster. */
+int kvd_bind_centroids(kvd_ctx* ctx, void* dev_centroids, int32_t* dev_cluster_start, int32_t* dev_cluster_pages);
+/* Set-up helper: builds one layer's hierarchical index from its page summaries (kvd_build_summaries
+ * first) by Lloyd's k-means in fp64: initial centroids = the pages at positions
+ * floor((c + 1/2) * valid_pages / Nc); `iterations` (1..64) rounds of {nearest centroid by squared
+ * Euclidean distance, ties to the lower centroid; centroid = mean of its pages' summaries summed in
+ * ascending page order, an empty cluster keeps its centroid}; the stored centroid is rounded once to
+ * kv_dtype; the cluster lists are those of the last round.  Covers the pages valid at the time of the
+ * call.  dev_assign_trace: device [iterations][B][Hkv][NP] int32 receiving every round's assignment,
+ * or NULL.  Allocates temporary device memory and waits for `stream`. */
+int kvd_build_centroids(kvd_ctx* ctx, int32_t layer, int32_t iterations, int32_t* dev_assign_trace, void* stream);
 
 /* ---- growth of the KV store during decoding ------------------------------------------------ */
 

@@ -24,7 +24,7 @@
 // 8192 pages (the selection role keeps its scores in registers at half the threads of the
 // stand-alone kernel) and enough units to keep its pipeline filled.
 static bool kvd_wants_single_launch(const kvd_ctx* c) {
-  if (!kvd_single_launch_ok(c)) return false;
+  if (!kvd_single_launch_ok(c) || c->Nc > 0) return false;
   if (c->cfg.micro_batches == -1) return true;
   return c->cfg.micro_batches == 0 && c->NP <= 8192 && c->U >= 32;
 }
@@ -49,6 +49,9 @@ static int validate_config(const kvd_config* c) {
   if (c->physical_layers < 0 || c->physical_layers > c->n_layers) return KVD_ERR_SHAPE;
   if (c->micro_batches < -1 || c->micro_batches > KVD_MAX_MICRO) return KVD_ERR_SHAPE;
   if (c->attn_splits < 0 || c->attn_splits > KVD_MAX_SPLITS) return KVD_ERR_SHAPE;
+  if (c->index_centroids < 0 || c->index_centroids > KVD_MAX_CENTROIDS || c->index_centroids > c->max_pages) return KVD_ERR_SHAPE;
+  if (c->index_centroids > 0 && c->max_pages > KVD_FAST_MAX_PAGES) return KVD_ERR_SHAPE;
+  if (c->index_centroids > 0 && c->policy == KVD_EVICT_LOOKAHEAD) return KVD_ERR_ARG;   // needs a score per page
   if (!(c->softmax_scale >= 0.f) || isinf(c->softmax_scale)) return KVD_ERR_ARG;
   if ((long long)c->sink_pages + c->recent_pages > c->topk_pages) return KVD_ERR_CAPACITY;
   if (c->topk_pages > c->capacity_max) return KVD_ERR_CAPACITY;
@@ -132,7 +135,7 @@ int kvd_create(const kvd_config* cfg, kvd_ctx** out) {
   c->cfg.capacity = nullptr;
   c->L = cfg->n_layers; c->B = cfg->batch; c->Hq = cfg->n_q_heads; c->Hkv = cfg->n_kv_heads;
   c->G = c->Hq / c->Hkv; c->D = cfg->head_dim; c->P = cfg->page_size; c->NP = cfg->max_pages;
-  c->k = cfg->topk_pages; c->Cmax = cfg->capacity_max;
+  c->k = cfg->topk_pages; c->Cmax = cfg->capacity_max; c->Nc = cfg->index_centroids;
   c->Lp = cfg->physical_layers ? cfg->physical_layers : c->L;
   c->U = c->B * c->Hkv;
   c->MB = cfg->micro_batches < 1 ? 1 : cfg->micro_batches;
@@ -211,6 +214,7 @@ int kvd_create(const kvd_config* cfg, kvd_ctx** out) {
   if (e == hipSuccess) ok(hipMemset(c->d_sel_ready, 0, (size_t)c->U * 32 * sizeof(int32_t)));
   if (e == hipSuccess) *c->error_host = 0;
   if (e == hipSuccess) c->single_launch = kvd_wants_single_launch(c);
+  if (e == hipSuccess && c->Nc > 0) ok(kvd_prepare_cluster_select());
   if (e != hipSuccess) { free_ctx(c); return KVD_ERR_HIP; }
   const int r = reset_directory(c, -1);
   if (r != KVD_OK) { free_ctx(c); return r; }
@@ -228,6 +232,22 @@ int kvd_destroy(kvd_ctx* ctx) {
 int kvd_bind_summaries(kvd_ctx* ctx, void* dev_summaries) {
   if (!ctx || !dev_summaries || !aligned16(dev_summaries)) return KVD_ERR_ARG;
   ctx->summaries = dev_summaries;
+  return KVD_OK;
+}
+
+int kvd_bind_centroids(kvd_ctx* ctx, void* dev_centroids, int32_t* dev_cluster_start, int32_t* dev_cluster_pages) {
+  if (!ctx || !dev_centroids || !dev_cluster_start || !dev_cluster_pages || !aligned16(dev_centroids)) return KVD_ERR_ARG;
+  if (ctx->Nc == 0) return KVD_ERR_STATE;
+  ctx->centroids = dev_centroids;
+  ctx->cluster_start = dev_cluster_start;
+  ctx->cluster_pages = dev_cluster_pages;
+  return KVD_OK;
+}
+
+int kvd_build_centroids(kvd_ctx* ctx, int32_t layer, int32_t iterations, int32_t* dev_assign_trace, void* stream) {
+  if (!ctx || layer < 0 || layer >= ctx->L || iterations < 1 || iterations > 64) return KVD_ERR_ARG;
+  if (ctx->Nc == 0 || !ctx->summaries || !ctx->centroids) return KVD_ERR_STATE;
+  HIP_TRY(ctx, kvd_run_build_centroids(ctx, layer, iterations, dev_assign_trace, static_cast<hipStream_t>(stream)));
   return KVD_OK;
 }
 
@@ -362,12 +382,14 @@ int kvd_cache_import(kvd_ctx* ctx, int32_t layer, const int32_t* host_slot_page,
 
 int kvd_score_select(kvd_ctx* ctx, int32_t layer, const void* q, int32_t* sel_pages, float* scores, void* stream) {
   if (!ctx || !q || !sel_pages || layer < 0 || layer >= ctx->L || !aligned16(q)) return KVD_ERR_ARG;
-  if (!ctx->summaries) return KVD_ERR_STATE;
+  if (ctx->Nc > 0 ? !ctx->centroids : !ctx->summaries) return KVD_ERR_STATE;
   hipStream_t s = static_cast<hipStream_t>(stream);
   float* sc = scores ? scores : ctx->d_scores;
   ctx->last_scores = sc;
   HIP_TRY(ctx, kvd_launch_score(ctx, layer, q, sc, 0, ctx->U, s));
-  if (kvd_fast_path_ok(ctx))
+  if (ctx->Nc > 0)
+    HIP_TRY(ctx, kvd_launch_cluster_select(ctx, layer, sc, sel_pages, 0, ctx->U, s));
+  else if (kvd_fast_path_ok(ctx))
     HIP_TRY(ctx, kvd_launch_select_resolve(ctx, layer, 0, true, false, false, sc, sel_pages, nullptr, nullptr, nullptr,
                                            nullptr, 0, ctx->U, s));
   else
@@ -407,6 +429,18 @@ int kvd_sparse_decode_attn(kvd_ctx* ctx, int32_t layer, const void* q, const int
 // Selection + directory update + fetch for units [u0, u1): one fused kernel when the sizes allow
 // the register-resident path, else the three size-agnostic kernels.
 static hipError_t launch_select_resolve_fetch(kvd_ctx* c, int layer, int step, int u0, int u1, hipStream_t s) {
+  if (c->Nc > 0) {
+    // hierarchical index: clusters -> pages, then the directory update and the fetch
+    hipError_t e = kvd_launch_cluster_select(c, layer, c->d_scores, c->d_sel_pages, u0, u1, s);
+    if (e != hipSuccess) return e;
+    if (kvd_fast_path_ok(c))
+      return kvd_launch_select_resolve(c, layer, step, false, true, true, c->d_scores, c->d_sel_pages, c->d_sel_slots,
+                                       c->d_hit_mask, c->d_evicted, c->d_counts, u0, u1, s);
+    e = kvd_launch_resolve(c, layer, step, c->d_sel_pages, c->d_sel_slots, c->d_hit_mask, c->d_evicted, c->d_counts, u0,
+                           u1, s);
+    if (e != hipSuccess) return e;
+    return kvd_launch_gather(c, layer, u0, u1, s);
+  }
   if (kvd_fast_path_ok(c))
     return kvd_launch_select_resolve(c, layer, step, true, true, true, c->d_scores, c->d_sel_pages, c->d_sel_slots,
                                      c->d_hit_mask, c->d_evicted, c->d_counts, u0, u1, s);
@@ -422,7 +456,7 @@ static hipError_t launch_select_resolve_fetch(kvd_ctx* c, int layer, int step, i
 // step and accumulates the per-stage times.  Stages run for the whole batch, one after another.
 static int step_profiled(kvd_ctx* c, int layer, int step, const void* q, float* out, float* lse, hipStream_t s) {
   hipEvent_t* ev = c->ev_prof;
-  const bool fused = kvd_fast_path_ok(c);
+  const bool fused = kvd_fast_path_ok(c) || c->Nc > 0;
   HIP_TRY(c, hipEventRecord(ev[0], s));
   HIP_TRY(c, kvd_launch_score(c, layer, q, c->d_scores, 0, c->U, s));
   HIP_TRY(c, hipEventRecord(ev[1], s));
@@ -459,7 +493,7 @@ static int step_profiled(kvd_ctx* c, int layer, int step, const void* q, float* 
 
 int kvd_step(kvd_ctx* ctx, int32_t layer, int32_t step, const void* q, float* out, float* lse, void* stream) {
   if (!ctx || !q || !out || layer < 0 || layer >= ctx->L || !aligned16(q)) return KVD_ERR_ARG;
-  if (!ctx->summaries || !ctx->pool || !ctx->store_dev) return KVD_ERR_STATE;
+  if (!ctx->summaries || !ctx->pool || !ctx->store_dev || (ctx->Nc > 0 && !ctx->centroids)) return KVD_ERR_STATE;
   kvd_ctx* c = ctx;
   hipStream_t s = static_cast<hipStream_t>(stream);
   ++c->n_steps;

@@ -14,6 +14,7 @@ constexpr int KVD_MAX_PAGE = 256;       // P
 constexpr int KVD_MAX_MICRO = 16;       // micro-batches per step
 constexpr int KVD_PIPE_STREAMS = 3;      // side streams a step may spread its micro-batches over
 constexpr int KVD_MAX_SPLITS = 64;      // attention split-K factor
+constexpr int KVD_MAX_CENTROIDS = 8192;   // centroids per unit of the hierarchical index (16-bit cluster numbers, <= 65535 pages each)
 constexpr int KVD_TIMELINE_MAX = 1 << 16; // workgroups of a single-launch step whose times can be recorded
 
 namespace kvd {
@@ -24,6 +25,7 @@ struct AttnArgs;
 struct kvd_ctx {
   kvd_config cfg;
   int L, B, Hq, Hkv, G, D, P, NP, k, Cmax, Lp, U, MB, S;
+  int Nc;                  // centroids per unit of the hierarchical index, 0 = flat page index
   int bf16;
   int score_blocks;        // target number of blocks of a scoring launch
   int generic_select;      // force the size-agnostic select / resolve kernels (testing)
@@ -35,6 +37,9 @@ struct kvd_ctx {
 
   // borrowed
   void* summaries;
+  void* centroids;          // [L][U][Nc][D] kv dtype
+  int32_t* cluster_start;   // [L][U][Nc+1]
+  int32_t* cluster_pages;   // [L][U][NP] pages of every cluster, ascending
   const char* store_dev;    // device-visible address of the pinned host store
   char* pool;
 
@@ -104,6 +109,11 @@ bool kvd_single_launch_ok(const kvd_ctx* c);
 hipError_t kvd_launch_step(kvd_ctx* c, int layer, int step, const void* q, float* out, float* lse, hipStream_t s);
 hipError_t kvd_launch_refill(kvd_ctx* c, int layer, hipStream_t s);
 hipError_t kvd_launch_build_summaries(kvd_ctx* c, int layer, hipStream_t s);
+bool kvd_centroid_mode(const kvd_ctx* c);
+hipError_t kvd_prepare_cluster_select(void);
+hipError_t kvd_launch_cluster_select(kvd_ctx* c, int layer, const float* scores, int32_t* sel_pages, int u0, int u1,
+                                     hipStream_t s);
+hipError_t kvd_run_build_centroids(kvd_ctx* c, int layer, int iterations, int32_t* assign_trace, hipStream_t s);
 hipError_t kvd_launch_append(kvd_ctx* c, int layer, const void* k_new, const void* v_new, hipStream_t s);
 hipError_t kvd_launch_advance(kvd_ctx* c, hipStream_t s);
 hipError_t kvd_launch_fill_i32(int32_t* p, int32_t v, size_t n, hipStream_t s);

@@ -92,19 +92,21 @@ __global__ __launch_bounds__(kSelectThreads) void select_kernel(const float* __r
 hipError_t kvd_launch_score(kvd_ctx* c, int layer, const void* q, float* scores, int u0, int u1, hipStream_t s) {
   using namespace kvd;
   if (u1 <= u0) return hipSuccess;
-  const uint16_t* summ = reinterpret_cast<const uint16_t*>(c->summaries) + (size_t)layer * c->U * c->NP * kHeadDim;
+  // the index that is scored: the page summaries, or the centroids of the hierarchical index
+  const int NP = c->Nc > 0 ? c->Nc : c->NP;
+  const uint16_t* summ = reinterpret_cast<const uint16_t*>(c->Nc > 0 ? c->centroids : c->summaries) + (size_t)layer * c->U * NP * kHeadDim;
   // about c->score_blocks blocks in total, so that the grid is one round of resident blocks
   const int n_units = u1 - u0;
-  const long long pages = (long long)c->NP * n_units;
+  const long long pages = (long long)NP * n_units;
   int passes = (int)((pages + 256LL * c->score_blocks - 1) / (256LL * c->score_blocks));
   if (passes < 1) passes = 1;
   const int per_block = 256 * passes;
-  dim3 grid((c->NP + per_block - 1) / per_block, n_units);
+  dim3 grid((NP + per_block - 1) / per_block, n_units);
   if (c->bf16)
-    hipLaunchKernelGGL(score_kernel<true>, grid, dim3(kScoreThreads), 0, s, summ, (const uint16_t*)q, scores, c->NP,
+    hipLaunchKernelGGL(score_kernel<true>, grid, dim3(kScoreThreads), 0, s, summ, (const uint16_t*)q, scores, NP,
                        c->G, c->Hq, c->Hkv, c->scale, u0, passes);
   else
-    hipLaunchKernelGGL(score_kernel<false>, grid, dim3(kScoreThreads), 0, s, summ, (const uint16_t*)q, scores, c->NP,
+    hipLaunchKernelGGL(score_kernel<false>, grid, dim3(kScoreThreads), 0, s, summ, (const uint16_t*)q, scores, NP,
                        c->G, c->Hq, c->Hkv, c->scale, u0, passes);
   return hipGetLastError();
 }

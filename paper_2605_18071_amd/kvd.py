@@ -28,6 +28,7 @@ class KvdConfig(C.Structure):
         ("sink_pages", C.c_int32), ("recent_pages", C.c_int32), ("kv_dtype", C.c_int32), ("policy", C.c_int32),
         ("softmax_scale", C.c_float), ("capacity_max", C.c_int32), ("capacity", C.POINTER(C.c_int32)),
         ("physical_layers", C.c_int32), ("micro_batches", C.c_int32), ("attn_splits", C.c_int32),
+        ("index_centroids", C.c_int32),
     ]
 
 
@@ -45,7 +46,7 @@ EXPORTS = [
     "kvd_create", "kvd_destroy", "kvd_strerror", "kvd_last_hip_error", "kvd_abi_version",
     "kvd_bind_summaries", "kvd_bind_host_store", "kvd_bind_slot_pool", "kvd_set_seq_lens",
     "kvd_build_summaries", "kvd_cache_reset", "kvd_cache_warm", "kvd_cache_export", "kvd_cache_import",
-    "kvd_append_kv", "kvd_advance", "kvd_score_select", "kvd_cache_resolve", "kvd_sparse_decode_attn", "kvd_step", "kvd_step_trace",
+    "kvd_bind_centroids", "kvd_build_centroids", "kvd_append_kv", "kvd_advance", "kvd_score_select", "kvd_cache_resolve", "kvd_sparse_decode_attn", "kvd_step", "kvd_step_trace",
     "kvd_set_profiling", "kvd_step_form", "kvd_set_wait_limit_us", "kvd_step_timeline", "kvd_get_stats", "kvd_reset_stats",
 ]
 
@@ -75,6 +76,8 @@ def load() -> C.CDLL:
         "kvd_cache_warm": [vp, i32, i32p, i32p],
         "kvd_cache_export": [vp, i32, i32p, i32p],
         "kvd_cache_import": [vp, i32, i32p, i32p],
+        "kvd_bind_centroids": [vp, vp, vp, vp],
+        "kvd_build_centroids": [vp, i32, i32, vp, vp],
         "kvd_append_kv": [vp, i32, vp, vp, vp],
         "kvd_advance": [vp, vp],
         "kvd_score_select": [vp, i32, vp, vp, vp, vp],
@@ -126,7 +129,7 @@ class Kvd:
 
     def __init__(self, *, n_layers, batch, n_q_heads, n_kv_heads, page_size, max_pages, topk_pages, capacity_max,
                  kv_dtype, head_dim=128, sink_pages=0, recent_pages=0, softmax_scale=0.0, capacity=None,
-                 physical_layers=0, micro_batches=0, attn_splits=0, policy=KVD_EVICT_LRU):
+                 physical_layers=0, micro_batches=0, attn_splits=0, policy=KVD_EVICT_LRU, index_centroids=0):
         self.lib = load()
         self._cap = None
         cfg = KvdConfig()
@@ -141,6 +144,7 @@ class Kvd:
             self._cap = _i32_array(list(capacity))
             cfg.capacity = C.cast(self._cap, C.POINTER(C.c_int32))
         cfg.physical_layers, cfg.micro_batches, cfg.attn_splits = physical_layers, micro_batches, attn_splits
+        cfg.index_centroids = index_centroids
         self.cfg = cfg
         self.ctx = C.c_void_p()
         st = self.lib.kvd_create(C.byref(cfg), C.byref(self.ctx))
@@ -206,6 +210,16 @@ class Kvd:
         ss = slot_stamp.to(torch.int32).contiguous()
         self._check(self.lib.kvd_cache_import(self.ctx, layer, C.cast(sp.data_ptr(), C.POINTER(C.c_int32)),
                                               C.cast(ss.data_ptr(), C.POINTER(C.c_int32))), "kvd_cache_import")
+
+    # ---- hierarchical index
+    def bind_centroids(self, centroids: torch.Tensor, cluster_start: torch.Tensor, cluster_pages: torch.Tensor):
+        self._keep += [centroids, cluster_start, cluster_pages]
+        self._check(self.lib.kvd_bind_centroids(self.ctx, centroids.data_ptr(), cluster_start.data_ptr(),
+                                                cluster_pages.data_ptr()), "kvd_bind_centroids")
+
+    def build_centroids(self, layer: int, iterations: int, assign_trace: Optional[torch.Tensor] = None, stream=None):
+        self._check(self.lib.kvd_build_centroids(self.ctx, layer, iterations, _ptr(assign_trace), _stream_handle(stream)),
+                    "kvd_build_centroids")
 
     # ---- growth of the store
     def append_kv(self, layer: int, k_new: torch.Tensor, v_new: torch.Tensor, stream=None):

@@ -33,17 +33,30 @@ class Rig:
                          topk_pages=w.topk_pages, capacity_max=w.capacity, kv_dtype=w.torch_dtype,
                          sink_pages=w.sink_pages, recent_pages=w.recent_pages, capacity=capacity,
                          physical_layers=w.physical_layers, micro_batches=micro_batches, attn_splits=attn_splits,
-                         policy=w.policy)
+                         policy=w.policy, index_centroids=w.index_centroids)
         self.kvd.bind_summaries(self.summaries)
         self.kvd.bind_host_store(self.store)
         self.kvd.bind_slot_pool(self.pool)
         self.seq_lens = list(seq_lens) if seq_lens is not None else [w.ctx] * B
         self.kvd.set_seq_lens(self.seq_lens)
         self.capacity = capacity
+        self.hier = w.index_centroids > 0
+        if self.hier:
+            Nc = w.index_centroids
+            self.centroids = torch.zeros((L, B, Hkv, Nc, D), dtype=w.torch_dtype, device=DEV)
+            self.cluster_start = torch.zeros((L, B * Hkv, Nc + 1), dtype=torch.int32, device=DEV)
+            self.cluster_pages = torch.zeros((L, B * Hkv, NP), dtype=torch.int32, device=DEV)
+            self.assign_trace = torch.zeros((L, w.index_iterations, B * Hkv, NP), dtype=torch.int32, device=DEV)
+            self.kvd.bind_centroids(self.centroids, self.cluster_start, self.cluster_pages)
         if build_index:
             for l in range(L):
                 self.kvd.build_summaries(l)
             torch.cuda.synchronize()
+            if self.hier:
+                for l in range(L):
+                    self.kvd.build_centroids(l, w.index_iterations, self.assign_trace[l])
+                torch.cuda.synchronize()
+                self.n_assign_trace = self.assign_trace.cpu().numpy()
         self.warm()
         U, k = w.units, w.topk_pages
         i32 = dict(dtype=torch.int32, device=DEV)
@@ -94,6 +107,9 @@ class Rig:
         self.n_evicted = self.evicted.cpu().numpy()
         self.n_counts = self.counts.cpu().numpy()
         self.n_scores = self.scores.cpu().numpy()
+        if self.hier:                                              # the library packs the cluster scores as [U][Nc]
+            Nc = self.w.index_centroids
+            self.n_scores = self.n_scores.reshape(-1)[: self.w.units * Nc].reshape(self.w.units, Nc)
         self.n_out = self.out.cpu().numpy()
         self.n_lse = self.lse.cpu().numpy()
 
@@ -105,7 +121,7 @@ class OracleUnit:
     """The oracle's view of one (layer, b, h): its slice of the host store, its own
     summaries, and its LRU window carried across steps."""
 
-    def __init__(self, rig: Rig, layer: int, b: int, h: int):
+    def __init__(self, rig: Rig, layer: int, b: int, h: int, summaries: Optional[np.ndarray] = None):
         w = rig.w
         self.rig, self.layer, self.b, self.h = rig, layer, b, h
         self.u = b * w.n_kv_heads + h
@@ -116,10 +132,49 @@ class OracleUnit:
         self.seq_len = rig.seq_lens[b]
         self.code = H.dtype_code(w.torch_dtype)
         self.summ = orc.page_summaries(self.keys, w.page, self.seq_len, self.code)
+        if summaries is not None:                                  # a test planted its own index
+            self.summ = summaries[: self.summ.shape[0]]
         make = orc.LookaheadWindow if w.policy == "lookahead" else orc.LruWindow
         self.window = make(rig.cap(layer, self.u))
         self.window.warm(rig.warm_list(b), stamp=-1)
         self.scale = 1.0 / math.sqrt(w.head_dim)
+        self.centroids = self.members = None
+        self.kmeans_divergences = 0
+        if rig.hier:
+            self.build_hier_index()
+
+    def build_hier_index(self):
+        """The oracle's k-means, round by round beside the GPU's recorded assignments: a GPU
+        assignment that differs is accepted only if its centroid is as near as the nearest one to
+        within rounding of the fp64 distance, and the oracle then continues from it.  Centroids
+        and cluster lists must then agree exactly."""
+        rig, w = self.rig, self.rig.w
+        Nc = w.index_centroids
+        n = self.summ.shape[0]
+        cent = orc.kmeans_init(self.summ, Nc)
+        forced = []
+        for it in range(w.index_iterations):
+            own = orc.kmeans_assign(self.summ, cent)
+            gpu = rig.n_assign_trace[self.layer, it, self.u, :n].astype(np.int32)
+            if not np.array_equal(own, gpu):
+                d = orc.kmeans_distances(self.summ, cent)
+                rows = np.nonzero(own != gpu)[0]
+                assert np.all(gpu[rows] >= 0) and np.all(gpu[rows] < Nc)
+                dmin = d[rows].min(axis=1)
+                assert np.all(d[rows, gpu[rows]] <= dmin + 1e-9 * (1.0 + np.abs(dmin))), \
+                    f"k-means assignment differs outside rounding at unit {self.u} round {it}"
+                self.kmeans_divergences += len(rows)
+            forced.append(gpu)
+            cent = orc.kmeans_update(self.summ, gpu, cent)
+        self.centroids, assign, _ = orc.kmeans_centroids(self.summ, Nc, w.index_iterations, self.code, forced_assign=forced)
+        self.members = orc.cluster_members(assign, Nc)
+        got = rig.centroids[self.layer, self.b, self.h].cpu()
+        assert np.array_equal(H.bits(got), orc.f64_to_bits(self.centroids, self.code)), f"centroids differ at unit {self.u}"
+        start = rig.cluster_start[self.layer, self.u].cpu().numpy()
+        pages = rig.cluster_pages[self.layer, self.u].cpu().numpy()
+        assert start[0] == 0 and start[-1] == n and np.all(np.diff(start) >= 0)
+        for c in range(Nc):
+            assert np.array_equal(pages[start[c]:start[c + 1]], self.members[c]), f"cluster {c} of unit {self.u}"
 
     def step(self, t: int, q_layer: torch.Tensor, forced_sel=None, forced_evicted=None):
         w = self.rig.w
@@ -127,7 +182,7 @@ class OracleUnit:
         return orc.decode_unit_step(qg, self.summ, self.keys, self.values, self.window, t, k=w.topk_pages,
                                     page_size=w.page, seq_len=self.seq_len, scale=self.scale,
                                     sink_pages=w.sink_pages, recent_pages=w.recent_pages, forced_sel=forced_sel,
-                                    forced_evicted=forced_evicted)
+                                    forced_evicted=forced_evicted, centroids=self.centroids, members=self.members)
 
 
 class StepReport:
@@ -147,7 +202,8 @@ def score_bound(ou: OracleUnit, q_layer: torch.Tensor) -> np.ndarray:
     (8 sequential fma + 4 tree adds + pooled-query rounding) ~ 20 eps * scale * sum_d |qbar_d s_pd|."""
     w = ou.rig.w
     qbar = orc.pooled_query(H.f64(q_layer[ou.b, ou.h * w.group:(ou.h + 1) * w.group]))
-    return 20.0 * 2.0 ** -24 * ou.scale * (np.abs(ou.summ) @ np.abs(qbar)) + 1e-12
+    index = ou.centroids if ou.centroids is not None else ou.summ
+    return 20.0 * 2.0 ** -24 * ou.scale * (np.abs(index) @ np.abs(qbar)) + 1e-12
 
 
 def compare_unit(rig: Rig, ou: OracleUnit, t: int, q_layer: torch.Tensor, rep: StepReport, check_scores: bool = True):
@@ -158,8 +214,13 @@ def compare_unit(rig: Rig, ou: OracleUnit, t: int, q_layer: torch.Tensor, rep: S
     u, k = ou.u, w.topk_pages
     g_sel = rig.n_sel_pages[u]
     qg = H.f64(q_layer[ou.b, ou.h * w.group:(ou.h + 1) * w.group])
-    o_scores = orc.page_scores(orc.pooled_query(qg), ou.summ, ou.scale)
-    o_sel = orc.select_pages(o_scores, k, w.sink_pages, w.recent_pages)
+    hier = ou.centroids is not None
+    if hier:
+        o_scores = orc.page_scores(orc.pooled_query(qg), ou.centroids, ou.scale)
+        o_sel = orc.select_pages_hier(o_scores, ou.members, k, ou.summ.shape[0], w.sink_pages, w.recent_pages)
+    else:
+        o_scores = orc.page_scores(orc.pooled_query(qg), ou.summ, ou.scale)
+        o_sel = orc.select_pages(o_scores, k, w.sink_pages, w.recent_pages)
     n_valid = o_scores.shape[0]
     if check_scores:
         g_scores = rig.n_scores[u, :n_valid].astype(np.float64)
@@ -169,7 +230,10 @@ def compare_unit(rig: Rig, ou: OracleUnit, t: int, q_layer: torch.Tensor, rep: S
         rep.max_score_err = max(rep.max_score_err, float(err.max()))
     forced = None
     if not np.array_equal(g_sel, o_sel):
-        ok, msg = H.selection_is_valid(o_scores, g_sel, k, w.sink_pages, w.recent_pages)
+        if hier:
+            ok, msg = H.hier_selection_is_valid(o_scores, ou.members, g_sel, k, ou.summ.shape[0], w.sink_pages, w.recent_pages)
+        else:
+            ok, msg = H.selection_is_valid(o_scores, g_sel, k, w.sink_pages, w.recent_pages)
         assert ok, f"selection differs outside the tie band at unit {u} step {t}: {msg}"
         rep.tie_divergences += 1
         forced = g_sel

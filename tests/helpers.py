@@ -67,6 +67,48 @@ def selection_is_valid(scores64: np.ndarray, sel: np.ndarray, k: int, sink: int 
     return True, ""
 
 
+def hier_selection_is_valid(cluster_scores64, members, sel, k, n_valid, sink=0, recent=0, eps: float = TIE_EPS):
+    """The acceptance rule for a selection through the hierarchical index that differs from the
+    oracle's at a near-tie of cluster scores: ascending unique pages with -1 padding; every forced
+    page in; as many pages as the budget allows; of every cluster either all, none or (for at most
+    one cluster) the lowest of its unforced pages; and no cluster that is left out or cut scores
+    clearly (by more than 2 eps) above a cluster that has pages in.  Returns (ok, message)."""
+    got = sel[sel >= 0]
+    if np.any(np.diff(got) <= 0) or np.any(sel[len(got):] != -1):
+        return False, "not ascending / bad padding"
+    forced = set(range(min(sink, n_valid)))
+    if recent > 0:
+        forced |= set(range(max(0, n_valid - recent), n_valid))
+    gs = set(int(p) for p in got)
+    if not forced <= gs:
+        return False, "forced pages missing"
+    free = [np.array([p for p in m if int(p) not in forced], dtype=np.int64) for m in members]
+    total_free = sum(len(f) for f in free)
+    if len(gs) != min(k, len(forced) + total_free):
+        return False, f"{len(gs)} pages selected, {min(k, len(forced) + total_free)} expected"
+    owned = set(int(p) for f in free for p in f) | forced
+    if not gs <= owned:
+        return False, "a selected page belongs to no cluster"
+    partial, s_in, s_out = 0, np.inf, -np.inf
+    for c, f in enumerate(free):
+        if len(f) == 0:
+            continue
+        n_in = sum(1 for p in f if int(p) in gs)
+        if n_in:
+            s_in = min(s_in, cluster_scores64[c])
+        if n_in < len(f):
+            s_out = max(s_out, cluster_scores64[c])
+            if n_in:
+                partial += 1
+                if [int(p) for p in f[:n_in]] != sorted(int(p) for p in f if int(p) in gs):
+                    return False, f"cluster {c} is cut but does not give its lowest pages"
+    if partial > 1:
+        return False, f"{partial} clusters are cut"
+    if s_out > s_in + 2 * eps:
+        return False, "a clearly better cluster is left out"
+    return True, ""
+
+
 def eviction_is_valid(scores64: np.ndarray, candidates, evicted, need: int, eps: float = TIE_EPS):
     """The acceptance rule for the victims of lookahead eviction when they differ from the
     oracle's at a near-tie: `need` distinct pages out of `candidates` (resident, not selected),

@@ -555,6 +555,92 @@ def test_lookahead_exact_ties_drop_the_higher_page():
     rig.close()
 
 
+# --------------------------------------------------------------------------- #
+# hierarchical index
+# --------------------------------------------------------------------------- #
+@pytest.mark.parametrize("cfg,mb,kw", [
+    (3, 1, dict()),                                                   # 1100 pages -> 550 centroids, bf16
+    (3, 2, dict()),                                                   # groups on streams
+    (2, 0, dict(index_iterations=2)),                                 # 3 layers, planted heavy pages
+    (4, 1, dict()),                                                   # fp16, G = 7, page 32
+    (5, 1, dict()),                                                   # page 64, recent pages forced and pre-warmed
+])
+def test_hierarchical_index_build_and_step_parity(cfg, mb, kw):
+    """k-means build (assignments of every round, centroids, cluster lists) and decode steps whose
+    selection goes through the centroids, against the oracle."""
+    w = SCALED[cfg]
+    w = w.replace(**{**dict(index_centroids=w.n_pages // 2, index_iterations=3), **kw})
+    rig = R.Rig(w, micro_batches=mb)
+    assert rig.kvd.step_form() != -1                                 # the centroid index runs as a chain of kernels
+    units = all_units(rig)                                            # builds and checks the index of every unit
+    assert sum(ou.kmeans_divergences for ou in units) <= 4
+    rep = R.run_steps(rig, units, w.steps, check_dir_every=3, progress=f"cfg{cfg}-hier-mb{mb}")
+    assert rep.unit_steps == w.steps * w.n_layers * w.units
+    assert rep.tie_divergences <= 2
+    rig.close()
+
+
+def test_hierarchical_index_ragged_forced_and_duplicate_pages():
+    """Sequences of different lengths (the index covers the valid pages only), sink and recent
+    pages, more centroids than distinct summaries (exact distance ties, empty clusters), and the
+    stage-by-stage entry points."""
+    w = small("hier-edge", ctx=16 * 200, topk_pages=24, capacity=40, sink_pages=2, recent_pages=3, heavy_count=0,
+              index_centroids=64, index_iterations=3, steps=5)
+    rig = R.Rig(w, seq_lens=[w.ctx - 7, w.ctx - 16 * 90 - 3], build_index=False)
+    base = torch.randn(w.units, 20, w.head_dim, device=R.DEV)                     # 20 distinct rows < 64 centroids
+    idx = torch.randint(0, 20, (w.units, w.n_pages), device=R.DEV)
+    summ = torch.gather(base, 1, idx[:, :, None].expand(-1, -1, w.head_dim)).to(w.torch_dtype)
+    rig.summaries.copy_(summ.view(rig.summaries.shape))
+    rig.kvd.build_centroids(0, w.index_iterations, rig.assign_trace[0])
+    torch.cuda.synchronize()
+    rig.n_assign_trace = rig.assign_trace.cpu().numpy()
+    units = []
+    for b in range(w.batch):
+        for h in range(w.n_kv_heads):
+            ou = R.OracleUnit.__new__(R.OracleUnit)                                # the oracle indexes the same summaries
+            R.OracleUnit.__init__(ou, rig, 0, b, h, summaries=H.f64(rig.summaries[0, b, h]))
+            units.append(ou)
+    assert all(ou.kmeans_divergences == 0 for ou in units)                        # exact ties resolve identically
+    assert any(len(m) == 0 for ou in units for m in ou.members)                   # some clusters are empty
+    rep = R.StepReport()
+    for t, q in enumerate(W.query_stream(w, rig.q0, w.steps, R.DEV)):
+        rig.kvd.score_select(0, q[0], rig.sel_pages, rig.scores)
+        rig.kvd.cache_resolve(0, t, rig.sel_pages, rig.sel_slots, rig.hit_mask, rig.evicted, rig.counts, do_gather=True)
+        rig.kvd.sparse_decode_attn(0, q[0], rig.sel_pages, rig.sel_slots, rig.out, rig.lse)
+        torch.cuda.synchronize()
+        rig.n_sel_pages, rig.n_sel_slots = rig.sel_pages.cpu().numpy(), rig.sel_slots.cpu().numpy()
+        rig.n_hit_mask, rig.n_evicted = rig.hit_mask.cpu().numpy(), rig.evicted.cpu().numpy()
+        rig.n_counts = rig.counts.cpu().numpy()
+        rig.n_scores = rig.scores.cpu().numpy().reshape(-1)[: w.units * 64].reshape(w.units, 64)
+        rig.n_out, rig.n_lse = rig.out.cpu().numpy(), rig.lse.cpu().numpy()
+        for ou in units:
+            R.compare_unit(rig, ou, t, q[0], rep)
+    assert rep.tie_divergences == 0
+    rig.close()
+
+
+def test_hierarchical_index_argument_errors():
+    common = dict(n_layers=1, batch=1, n_q_heads=4, n_kv_heads=1, page_size=16, max_pages=64, topk_pages=4, capacity_max=8,
+                  kv_dtype=torch.float16)
+    with pytest.raises(K.KvdError) as e:
+        K.Kvd(index_centroids=65, **common)                           # more centroids than pages
+    assert e.value.status == K.ERR_SHAPE
+    with pytest.raises(K.KvdError) as e:
+        K.Kvd(index_centroids=16, policy="lookahead", **common)       # lookahead eviction needs page scores
+    assert e.value.status == K.ERR_ARG
+    k = K.Kvd(index_centroids=16, **common)
+    with pytest.raises(K.KvdError) as e:
+        k.build_centroids(0, 3)                                       # nothing bound yet
+    assert e.value.status == K.ERR_STATE
+    k.close()
+    k = K.Kvd(**common)
+    t = torch.zeros(64, dtype=torch.int32, device=R.DEV)
+    with pytest.raises(K.KvdError) as e:
+        k.bind_centroids(t, t, t)                                     # flat index: no centroids to bind
+    assert e.value.status == K.ERR_STATE
+    k.close()
+
+
 @pytest.mark.parametrize("cfg", [2, 5])
 def test_size_agnostic_select_resolve_kernels(cfg, monkeypatch):
     """The register-resident fused kernel covers up to 16384 pages and 4096 slots per unit; larger
