@@ -43,7 +43,7 @@ PMC_TRAFFIC_BYTES = {("cfg3", "step"): 565383168, ("cfg3", "attend"): 271947776,
 def describe(w) -> str:
     return (f"{w.name}: L={w.n_layers} B={w.batch} ctx={w.ctx} page={w.page} heads={w.n_q_heads}q/{w.n_kv_heads}kv "
             f"D={w.head_dim} {w.dtype} k={w.topk_pages} pages ({w.topk_pages * w.page} tokens) "
-            f"cache={w.capacity} pages/unit ({100.0 * w.capacity / w.n_pages:.0f}%, {w.policy}) {w.importance} importance, rho={w.rho}")
+            f"{'flat index' if w.index_centroids == 0 else str(w.index_centroids) + ' centroids'} cache={w.capacity} pages/unit ({100.0 * w.capacity / w.n_pages:.0f}%, {w.policy}) {w.importance} importance, rho={w.rho}")
 
 
 def cpu_baseline(w, store, q_list, seconds: float):
@@ -65,16 +65,21 @@ def cpu_baseline(w, store, q_list, seconds: float):
         kv = store[0, b, h].to(torch.float64).numpy()
         keys, vals = kv[:, 0].reshape(-1, w.head_dim), kv[:, 1].reshape(-1, w.head_dim)
         summ = orc.page_summaries(keys, w.page, w.ctx, code)            # set-up, not timed
+        cent = members = None
+        if w.index_centroids > 0:                                        # index build: set-up, not timed
+            cent, assign, _ = orc.kmeans_centroids(summ, w.index_centroids, w.index_iterations, code)
+            members = orc.cluster_members(assign, w.index_centroids)
         win = (orc.LookaheadWindow if w.policy == "lookahead" else orc.LruWindow)(w.capacity)
         units += 1
         for t, q in enumerate(q_list):
             qg = q[b, h * w.group:(h + 1) * w.group].to(torch.float64).numpy()
             t0 = time.perf_counter()
             orc.decode_unit_step(qg, summ, keys, vals, win, t, k=w.topk_pages, page_size=w.page, seq_len=w.ctx,
-                                 scale=scale, sink_pages=w.sink_pages, recent_pages=w.recent_pages)
+                                 scale=scale, sink_pages=w.sink_pages, recent_pages=w.recent_pages, centroids=cent,
+                                 members=members)
             spent += time.perf_counter() - t0
             done += 1
-        if spent >= seconds:
+        if spent >= seconds or (w.index_centroids > 0 and units >= 8):   # (the oracle's k-means is slow set-up)
             break
     per_unit_step = spent / max(done, 1)
     return {
@@ -117,6 +122,9 @@ def main() -> int:
     ap.add_argument("--config", type=int, default=3)
     ap.add_argument("--micro-batches", type=int, default=0, help="kvd_config.micro_batches (0 = library chooses, 1 = chain of kernels, -1 = one launch)")
     ap.add_argument("--policy", choices=["lru", "lookahead"], default="lru", help="cache replacement policy")
+    ap.add_argument("--centroids", type=int, default=0,
+                    help="hierarchical index with this many centroids per unit (0 = flat page index)")
+    ap.add_argument("--index-iterations", type=int, default=4, help="k-means rounds of the hierarchical index build")
     ap.add_argument("--window", type=float, default=0.0,
                     help="cache capacity as a multiple of the per-step budget k (the paper's window size); "
                          "0 keeps the configuration's capacity")
@@ -146,7 +154,7 @@ def main() -> int:
         w = w.replace(n_layers=1, physical_layers=1)
     if args.window > 0:
         w = w.replace(capacity=max(w.topk_pages, int(round(args.window * w.topk_pages))))
-    w = w.replace(policy=args.policy)
+    w = w.replace(policy=args.policy, index_centroids=args.centroids, index_iterations=args.index_iterations)
     L, B, Hkv, NP, P, D, U, k = w.n_layers, w.batch, w.n_kv_heads, w.n_pages, w.page, w.head_dim, w.units, w.topk_pages
 
     t_setup = time.perf_counter()
@@ -156,11 +164,22 @@ def main() -> int:
     pool = torch.zeros((L, B, Hkv, w.capacity, 2, P, D), dtype=w.torch_dtype, device=dev)
     ctx = K.Kvd(n_layers=L, batch=B, n_q_heads=w.n_q_heads, n_kv_heads=Hkv, page_size=P, max_pages=NP, topk_pages=k,
                 capacity_max=w.capacity, kv_dtype=w.torch_dtype, sink_pages=w.sink_pages, recent_pages=w.recent_pages,
-                physical_layers=w.physical_layers, micro_batches=args.micro_batches, policy=w.policy)
+                physical_layers=w.physical_layers, micro_batches=args.micro_batches, policy=w.policy,
+                index_centroids=w.index_centroids)
     ctx.bind_summaries(summ)
     ctx.bind_host_store(store)
     ctx.bind_slot_pool(pool)
     ctx.build_summaries(0)
+    if w.index_centroids > 0:
+        centroids = torch.zeros((L, B, Hkv, w.index_centroids, D), dtype=w.torch_dtype, device=dev)
+        cluster_start = torch.zeros((L, U, w.index_centroids + 1), dtype=torch.int32, device=dev)
+        cluster_pages = torch.zeros((L, U, NP), dtype=torch.int32, device=dev)
+        ctx.bind_centroids(centroids, cluster_start, cluster_pages)
+        torch.cuda.synchronize()
+        t_index = time.perf_counter()
+        ctx.build_centroids(0, w.index_iterations)
+        torch.cuda.synchronize()
+        t_index = time.perf_counter() - t_index
     pages = W.warm_pages(w)
     if pages is not None:
         ctx.cache_warm(0, pages.tolist() * U, [len(pages)] * U)
@@ -188,7 +207,8 @@ def main() -> int:
     hit_rate = st.hits / max(1, st.hits + st.misses)
     gathered_per_step = st.gathered_bytes / args.steps
 
-    summary_bytes = U * NP * D * 2
+    # index bytes a step must read: the page summaries, or the centroids plus the cluster lists
+    summary_bytes = U * NP * D * 2 if w.index_centroids == 0 else U * (w.index_centroids * D * 2 + (w.index_centroids + 1 + NP) * 4)
     selected_bytes = U * k * w.page_bytes
     io_bytes = B * w.n_q_heads * D * (2 + 4)
     result = {
@@ -209,6 +229,9 @@ def main() -> int:
                   "host_link_GBps_if_fetch_bound": gathered_per_step / (elapsed / args.steps) / 1e9},
     }
 
+    if w.index_centroids > 0:
+        result["config"]["index"] = {"centroids": w.index_centroids, "kmeans_rounds": w.index_iterations,
+                                     "build_s": round(t_index, 3)}
     single = ctx.step_form() == -1
     result["config"]["step_form"] = "one launch (step_kernel)" if single else f"chain of kernels x {ctx.step_form()} group(s)"
     gpu_bytes = summary_bytes + selected_bytes + io_bytes

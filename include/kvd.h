@@ -176,7 +176,10 @@ int kvd_cache_import(kvd_ctx* ctx, int32_t layer, const int32_t* host_slot_page,
  *              score = scale * pooled_q . summary, ties to the lower page; sink/recent pages
  *              always included; ascending page order; padded with -1 when a sequence has fewer
  *              than k valid pages.
- *   scores     [B][Hkv][NP] fp32 out, or NULL. */
+ *   scores     [B][Hkv][NP] fp32 out, or NULL.
+ * With the hierarchical index (index_centroids = Nc > 0) the centroids are scored instead and the
+ * pages come from whole clusters taken best first (see kvd_config.index_centroids); `scores` must
+ * still hold B*Hkv*NP floats and receives the cluster scores packed as [B][Hkv][Nc]. */
 int kvd_score_select(kvd_ctx* ctx, int32_t layer, const void* q, int32_t* sel_pages, float* scores, void* stream);
 
 /* Stage 2, cache lookup and fetch (Cache Management; Roofline section: only out-of-cache pages move).

@@ -24,6 +24,21 @@ FULL = {
 }
 
 
+def test_full_size_hierarchical_index():
+    """cfg3 at full size with half as many centroids as pages: index build and sampled decode parity."""
+    w = W.CONFIGS[3].replace(index_centroids=4096, index_iterations=2)
+    print("[cfg3-hier] building workload and index", flush=True)
+    rig = R.Rig(w)
+    print("[cfg3-hier] index built, checking sampled units", flush=True)
+    units = [R.OracleUnit(rig, 0, b, h) for (b, h) in [(0, 0), (7, 3), (15, 7)]]
+    print(f"[cfg3-hier] k-means assignments that differ inside rounding: {sum(o.kmeans_divergences for o in units)}", flush=True)
+    rep = R.run_steps(rig, units, 8, check_dir_every=4, progress="cfg3-hier-full")
+    assert rep.unit_steps == 8 * len(units) and rep.tie_divergences <= 2
+    rig.close()
+    del rig
+    torch.cuda.empty_cache()
+
+
 @pytest.mark.parametrize("cfg,mb", [(3, 0), (3, 1), (2, 0), (4, 0), (5, 0), (5, -1)])
 def test_full_size_sampled_parity(cfg, mb):
     """mb = 0: the form the library chooses (what bench.py times: one launch for cfg2-4, the chain of
