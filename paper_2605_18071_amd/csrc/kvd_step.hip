@@ -11,11 +11,11 @@
 //     then S attention workgroups per unit.
 // A selection workgroup waits until the unit's scoring waves have all arrived (a counter);
 // an attention workgroup waits until the unit's selection, directory update and fetch are
-// complete (a flag, lowered again by the unit's last attention workgroup).  Workgroups are dispatched in index order, so
-// whatever a waiting workgroup waits for has already been dispatched and needs nothing from
-// later workgroups: the lowest-numbered unfinished workgroup can always run to its end.  Every
-// wait is nevertheless bounded by a wall-clock limit; a wait that runs out raises an error word in
-// host memory and the workgroup leaves without output.
+// complete (a flag, lowered again by the unit's last attention workgroup).  Workgroups are
+// dispatched in index order, so whatever a waiting workgroup waits for has already been dispatched
+// and needs nothing from later workgroups: the lowest-numbered unfinished workgroup can always run
+// to its end.  Every wait is nevertheless bounded by a wall-clock limit; a wait that runs out
+// raises an error word in host memory and the workgroup leaves without output.
 //
 // Workgroups of one launch may sit on different XCDs with separate L2 caches.  Everything that
 // crosses workgroups inside the launch (scores, the selection and its slots, fetched pages, split
@@ -53,20 +53,14 @@ typedef AttnSmem<KVD_MAX_GROUP, kStepWaves> StepAttnSmem;
 typedef FastSmem<kStepThreads> StepFastSmem;
 constexpr size_t kStepSmemBytes = sizeof(StepAttnSmem) > sizeof(StepFastSmem) ? sizeof(StepAttnSmem) : sizeof(StepFastSmem);
 
-// The three roles are separate functions (not inlined) so that each gets its registers allocated
-// on its own within the kernel's budget of 128 per lane.  They read the launch arguments from the
-// kernel-argument segment (constant address space, scalar loads) instead of receiving a copy.
+// The three roles read the launch arguments from the kernel-argument segment (constant address
+// space, scalar loads) and copy only what they use.
 typedef const __attribute__((address_space(4))) StepArgs* StepArgsPtr;
-#ifdef KVD_STEP_NOINLINE
-#define KVD_ROLE_INLINE __attribute__((noinline))
-#else
-#define KVD_ROLE_INLINE __forceinline__
-#endif
 constexpr int kFlagStride = 32;   // ints between the flags of two units: one 128-byte line each
 
 // Scoring workgroup `wg` of n_score: chunks wg, wg + n_score, ... of the layer, unit by unit.
 template <bool BF16>
-__device__ KVD_ROLE_INLINE void step_score_role(StepArgsPtr ap, int wg, long long* ts) {
+__device__ __forceinline__ void step_score_role(StepArgsPtr ap, int wg, long long* ts) {
   struct { const uint16_t* summ; const uint16_t* q; float* scores; int32_t* score_done; float scale;
            int n_units, chunks, n_score, u0, passes; struct { int Hkv, NP; } fa; struct { int Hq, G; } at; } a;
   a.summ = ap->summ; a.q = ap->q; a.scores = ap->scores; a.score_done = ap->score_done; a.scale = ap->scale;
@@ -92,7 +86,7 @@ __device__ KVD_ROLE_INLINE void step_score_role(StepArgsPtr ap, int wg, long lon
 // Selection, directory update and fetch of unit u: latency-bound, so its waves go first whenever
 // they can issue.
 template <int IPT>
-__device__ KVD_ROLE_INLINE void step_select_role(StepArgsPtr ap, int u, unsigned char* smem_raw, int* wait_ok,
+__device__ __forceinline__ void step_select_role(StepArgsPtr ap, int u, unsigned char* smem_raw, int* wait_ok,
                                                            long long* ts) {
   struct { FastArgs fa; int32_t* score_done; int32_t* sel_ready; int32_t* error; long long wait_limit; int chunks; } a;
   __builtin_memcpy(&a.fa, &ap->fa, sizeof(FastArgs));
@@ -122,7 +116,7 @@ __device__ KVD_ROLE_INLINE void step_select_role(StepArgsPtr ap, int u, unsigned
 
 // Attention workgroup (u, split).
 template <bool BF16>
-__device__ KVD_ROLE_INLINE void step_attend_role(StepArgsPtr ap, int u, int split, unsigned char* smem_raw,
+__device__ __forceinline__ void step_attend_role(StepArgsPtr ap, int u, int split, unsigned char* smem_raw,
                                                            int* wait_ok, long long* ts) {
   struct { AttnArgs at; int32_t* sel_ready; int32_t* error; long long wait_limit; } a;
   __builtin_memcpy(&a.at, &ap->at, sizeof(AttnArgs));
