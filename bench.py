@@ -35,6 +35,7 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBPS = 8000.0
+HOST_LINK_PEAK_GBPS = 63.0      # PCIe Gen5 x16, one direction: 32 GT/s x 16 lanes x 128/130
 # HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this command, scaled by
 # what the same counters read for a plain copy of known size (profiles/pmc_traffic_cfg3.md)
 PMC_TRAFFIC_BYTES = {("cfg3", "step"): 565383168, ("cfg3", "attend"): 271947776, ("cfg3", "score"): 273769472}
@@ -253,8 +254,10 @@ def main() -> int:
                                 "score_GBps": summary_bytes / (ms_score * 1e-3) / 1e9,
                                 "attend_GBps": selected_bytes / (ms_attend * 1e-3) / 1e9}
         fetch_ms = (ps.ms_select_resolve + ps.ms_gather) / n
-        result["host_link"] = {"bytes_per_step": ps.gathered_bytes / n,
-                               "GBps_over_select_resolve_fetch": ps.gathered_bytes / n / (fetch_ms * 1e-3) / 1e9}
+        link = ps.gathered_bytes / n / (fetch_ms * 1e-3) / 1e9
+        result["host_link"] = {"what": "fetch of missed pages from pinned host memory inside the selection/fetch kernel (chain pass)",
+                               "bytes_per_step": ps.gathered_bytes / n, "GBps_over_select_resolve_fetch": link,
+                               "peak_GBps": HOST_LINK_PEAK_GBPS, "frac": link / HOST_LINK_PEAK_GBPS}
 
         # pass 3: the GPU-resident path alone, in the form the timed region used.  The last query is
         # replayed, so every selected page is a hit and nothing crosses the host link: time per

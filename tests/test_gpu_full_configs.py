@@ -10,6 +10,7 @@ import pytest
 import torch
 
 from paper_2605_18071_amd import workloads as W
+from tests import helpers as H
 
 pytestmark = pytest.mark.gpu
 
@@ -22,6 +23,44 @@ FULL = {
     4: (W.CONFIGS[4].replace(n_layers=2, physical_layers=2), 10, [(0, 0, 0), (0, 31, 3), (1, 13, 1), (1, 20, 2)]),
     5: (W.CONFIGS[5], 16, [(0, 0, 0), (0, 1, 4), (0, 3, 7)]),
 }
+
+
+def test_full_size_one_launch_equals_chain_over_many_steps():
+    """cfg3 at full size, 96 decode steps with the real miss stream: the one-launch step and the
+    chain of kernels, fed the same queries from the same cold start, must produce the same
+    selections, cache traces and slot contents at every step, and the same outputs up to the fp32
+    summation order of the attention."""
+    w = W.CONFIGS[3]
+    a = R.Rig(w, micro_batches=-1)
+    b = R.Rig(w, micro_batches=1, build_index=False)
+    b.summaries.copy_(a.summaries)
+    assert a.kvd.step_form() == -1 and b.kvd.step_form() == 1
+    worst = 0.0
+    for t, q in enumerate(W.query_stream(w, a.q0, 96, R.DEV)):
+        a.step(0, t, q[0])
+        b.step(0, t, q[0])
+        assert np.array_equal(a.n_sel_pages, b.n_sel_pages), t
+        assert np.array_equal(a.n_hit_mask, b.n_hit_mask), t
+        assert np.array_equal(a.n_sel_slots, b.n_sel_slots), t
+        assert np.array_equal(np.sort(a.n_evicted, axis=1), np.sort(b.n_evicted, axis=1)), t
+        assert np.array_equal(a.n_counts, b.n_counts), t
+        assert np.array_equal(a.n_scores, b.n_scores), t
+        worst = max(worst, H.attn_rel_err(a.n_out, b.n_out))
+        assert worst <= 1e-5, (t, worst)
+        if t % 24 == 23:
+            print(f"[cfg3 one launch vs chain] step {t} ok, evictions so far {int(a.kvd.stats().evictions)}, "
+                  f"max output difference {worst:.2e}", flush=True)
+    assert a.kvd.stats().evictions > 0
+    sa, _ = a.kvd.cache_export(0)
+    sb, _ = b.kvd.cache_export(0)
+    assert torch.equal(sa, sb)
+    for u in (0, 37, 127):                                            # slot contents, a few units in full
+        bb, hh = divmod(u, w.n_kv_heads)
+        assert torch.equal(a.pool[0, bb, hh].cpu().view(torch.int16), b.pool[0, bb, hh].cpu().view(torch.int16)), u
+    a.close()
+    b.close()
+    del a, b
+    torch.cuda.empty_cache()
 
 
 def test_full_size_hierarchical_index():
