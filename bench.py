@@ -131,6 +131,9 @@ def main() -> int:
                          "0 keeps the configuration's capacity")
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="0 skips the oracle baseline")
     ap.add_argument("--no-profile-pass", action="store_true", help="skip the per-kernel HIP-event pass")
+    ap.add_argument("--calibrate", type=int, default=0, metavar="STEPS",
+                    help="before the warm-up, let the library time every form of the step on STEPS real steps each "
+                         "and keep the fastest (kvd_calibrate_step_form)")
     ap.add_argument("--timeline", action="store_true",
                     help="when the step runs as one launch: add the per-workgroup timeline of one all-hit step")
     args = ap.parse_args()
@@ -184,22 +187,31 @@ def main() -> int:
     pages = W.warm_pages(w)
     if pages is not None:
         ctx.cache_warm(0, pages.tolist() * U, [len(pages)] * U)
+    n_cal = 8 * ((args.calibrate + 1) // 2 + 1) if args.calibrate > 0 else 0
     n_total = args.warmup + 2 * args.steps + 1
-    queries = [q[0].contiguous() for q in W.query_stream(w, q0, n_total, dev)]
+    stream_q = [q[0].contiguous() for q in W.query_stream(w, q0, n_cal + n_total, dev)]
+    # warm-up queries, then the calibration's, then the timed ones: one continuous drifting stream
+    q_cal = stream_q[args.warmup:args.warmup + n_cal]
+    queries = stream_q[:args.warmup] + stream_q[args.warmup + n_cal:]
     out = torch.empty((B, w.n_q_heads, D), dtype=torch.float32, device=dev)
     torch.cuda.synchronize()
     t_setup = time.perf_counter() - t_setup
 
     stream = torch.cuda.current_stream()
-    t = 0
+    t, base = 0, 0
+    calibration = None
     for _ in range(args.warmup):
-        ctx.step(0, t, queries[t], out, stream=stream)
+        ctx.step(0, base + t, queries[t], out, stream=stream)
         t += 1
     torch.cuda.synchronize()
+    if args.calibrate > 0:                       # on the warmed-up cache; its steps continue the query stream
+        chosen, ms = ctx.calibrate_step_form(0, t, torch.stack(q_cal).contiguous(), args.calibrate, out, stream=stream)
+        calibration = {"chosen_form": chosen, "ms_per_step": {str(f): v for f, v in ms.items()}}
+        base = n_cal                             # step indices go on after the calibration's
     ctx.reset_stats()
     t0 = time.perf_counter()
     for _ in range(args.steps):
-        ctx.step(0, t, queries[t], out, stream=stream)
+        ctx.step(0, base + t, queries[t], out, stream=stream)
         t += 1
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
@@ -233,6 +245,8 @@ def main() -> int:
     if w.index_centroids > 0:
         result["config"]["index"] = {"centroids": w.index_centroids, "kmeans_rounds": w.index_iterations,
                                      "build_s": round(t_index, 3)}
+    if calibration is not None:
+        result["config"]["calibration"] = calibration
     single = ctx.step_form() == -1
     result["config"]["step_form"] = "one launch (step_kernel)" if single else f"chain of kernels x {ctx.step_form()} group(s)"
     gpu_bytes = summary_bytes + selected_bytes + io_bytes
@@ -242,7 +256,7 @@ def main() -> int:
         ctx.set_profiling(1)
         ctx.reset_stats()
         for _ in range(args.steps):
-            ctx.step(0, t, queries[t], out, stream=stream)
+            ctx.step(0, base + t, queries[t], out, stream=stream)
             t += 1
         torch.cuda.synchronize()
         ps = ctx.stats()
@@ -266,14 +280,14 @@ def main() -> int:
         ctx.set_profiling(0)
         q_last = queries[t - 1]
         for _ in range(3):
-            ctx.step(0, t, q_last, out, stream=stream)
+            ctx.step(0, base + t, q_last, out, stream=stream)
             t += 1
         torch.cuda.synchronize()
         ctx.reset_stats()
         ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         ev0.record(stream)
         for _ in range(args.steps):
-            ctx.step(0, t, q_last, out, stream=stream)
+            ctx.step(0, base + t, q_last, out, stream=stream)
             t += 1
         ev1.record(stream)
         torch.cuda.synchronize()
@@ -302,7 +316,7 @@ def main() -> int:
                                   "avg_launch_ms": ms}
 
     if args.timeline and single and not args.no_profile_pass:
-        result["timeline"] = step_timeline(ctx, t, q_last, out, stream)
+        result["timeline"] = step_timeline(ctx, base + t, q_last, out, stream)
 
     if args.cpu_seconds > 0:
         q_cpu = [q.cpu() for q in queries[:16]]

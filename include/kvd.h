@@ -265,6 +265,23 @@ int kvd_set_profiling(kvd_ctx* ctx, int32_t mode);
 /* The form kvd_step takes for this context, in the terms of kvd_config.micro_batches: -1 one launch,
  * 1 a chain of kernels, n >= 2 that many groups on the library's streams. */
 int kvd_step_form(const kvd_ctx* ctx);
+/* Changes the form of kvd_step (same values as kvd_config.micro_batches).  Waits for the device.
+ * KVD_ERR_SHAPE if the context's shapes cannot run that form. */
+int kvd_set_step_form(kvd_ctx* ctx, int32_t form);
+/* Pre-run calibration (Pipeline Optimization: the micro-batch size is found by a short calibration
+ * before inference begins).  Runs real decode steps of `layer` — step indices first_step,
+ * first_step + 1, ... with the queries q_steps [n_queries][B][Hq][D] (device) taken in turn — in
+ * each form the context can run (chain of kernels, 2 groups, 4 groups, one launch).  Every form
+ * runs two blocks of 1 untimed + ceil(steps_per_form / 2) timed steps, enqueued back to back and
+ * timed with HIP events on `stream`; the blocks go through the forms in order and then in reverse
+ * order, so that a drift over the calibration weighs on all forms alike (calibrate on a warmed-up
+ * cache all the same).  The fastest form is kept and reported in *chosen_form.  ms_per_step (host,
+ * 4 floats in that order, -1 for a form that cannot run) may be NULL.  The cache advances by
+ * 8 * (ceil(steps_per_form / 2) + 1) steps at most; `out` receives the last step's output.
+ * Synchronous. */
+int kvd_calibrate_step_form(kvd_ctx* ctx, int32_t layer, int32_t first_step, const void* q_steps, int32_t n_queries,
+                            int32_t steps_per_form, float* out, void* stream, int32_t* chosen_form,
+                            float* ms_per_step);
 /* Bound of every wait inside the one-launch kvd_step (micro_batches = -1), where workgroups wait on
  * flags in device memory for the workgroups before them.  Default 2 s.  A wait that runs out makes
  * its workgroup leave without output and raises a sticky error: kvd_get_stats and later kvd_step

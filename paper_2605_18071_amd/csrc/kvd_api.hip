@@ -88,6 +88,27 @@ static void free_ctx(kvd_ctx* c) {
   free(c);
 }
 
+// Side streams and events for a step in `groups` groups; created on first need, kept until destroy.
+static hipError_t ensure_group_resources(kvd_ctx* c, int groups) {
+  if (groups <= 1) return hipSuccess;
+  for (int i = 0; i < KVD_PIPE_STREAMS; ++i)
+    if (c->side[i] == nullptr) {
+      const hipError_t e = hipStreamCreateWithFlags(&c->side[i], hipStreamNonBlocking);
+      if (e != hipSuccess) return e;
+    }
+  for (int i = 0; i < groups && i < KVD_MAX_MICRO; ++i) {
+    if (c->ev_score[i] == nullptr) {
+      const hipError_t e = hipEventCreateWithFlags(&c->ev_score[i], hipEventDisableTiming);
+      if (e != hipSuccess) return e;
+    }
+    if (c->ev_done[i] == nullptr) {
+      const hipError_t e = hipEventCreateWithFlags(&c->ev_done[i], hipEventDisableTiming);
+      if (e != hipSuccess) return e;
+    }
+  }
+  return hipSuccess;
+}
+
 template <class T>
 static hipError_t dev_alloc(T** p, size_t count) {
   return hipMalloc(reinterpret_cast<void**>(p), (count ? count : 1) * sizeof(T));
@@ -163,16 +184,20 @@ int kvd_create(const kvd_config* cfg, kvd_ctx** out) {
     if (S > cap) S = cap;
     if (S > KVD_MAX_SPLITS) S = KVD_MAX_SPLITS;
     if (S < 1) S = 1;
-    // the one-launch step has 8 waves per attention workgroup and gains from twice as many
-    // workgroups (units become ready one after another) as long as a wave keeps 4 tiles or more
-    if (kvd_wants_single_launch(c)) {
-      int S2 = (1024 + c->U / 2) / c->U;
-      if (S2 > KVD_MAX_SPLITS) S2 = KVD_MAX_SPLITS;
-      if (S2 >= 1 && tiles / (S2 * 8) >= 4) S = S2;
-    }
   }
   if (S > c->k) S = c->k;
   c->S = S;
+  // the one-launch step has 8 waves per attention workgroup and gains from twice as many
+  // workgroups (units become ready one after another) as long as a wave keeps 4 tiles or more
+  c->S1 = S;
+  if (cfg->attn_splits == 0) {
+    const int tiles = c->k * ((c->P + 15) / 16);
+    int S2 = (1024 + c->U / 2) / c->U;
+    if (S2 > KVD_MAX_SPLITS) S2 = KVD_MAX_SPLITS;
+    if (S2 > c->k) S2 = c->k;
+    if (S2 >= 1 && tiles / (S2 * 8) >= 4) c->S1 = S2;
+  }
+  const int Smax = c->S > c->S1 ? c->S : c->S1;
 
   const size_t LU = (size_t)c->L * c->U;
   c->h_capacity = static_cast<int32_t*>(malloc(LU * sizeof(int32_t)));
@@ -191,19 +216,14 @@ int kvd_create(const kvd_config* cfg, kvd_ctx** out) {
       ok(dev_alloc(&c->d_sel_slots, Uk)) && ok(dev_alloc(&c->d_hit_mask, Uk)) && ok(dev_alloc(&c->d_evicted, Uk)) &&
       ok(dev_alloc(&c->d_counts, (size_t)c->U * 3)) && ok(dev_alloc(&c->d_miss_list, Uk * 2)) &&
       ok(dev_alloc(&c->d_miss_count, (size_t)c->U)) &&
-      ok(dev_alloc(&c->d_part_acc, (size_t)c->U * c->S * c->G * c->D)) &&
-      ok(dev_alloc(&c->d_part_ml, (size_t)c->U * c->S * c->G * 2)) && ok(dev_alloc(&c->d_stats, 4)) &&
+      ok(dev_alloc(&c->d_part_acc, (size_t)c->U * Smax * c->G * c->D)) &&
+      ok(dev_alloc(&c->d_part_ml, (size_t)c->U * Smax * c->G * 2)) && ok(dev_alloc(&c->d_stats, 4)) &&
       ok(dev_alloc(&c->d_attn_ticket, (size_t)c->U)) && ok(dev_alloc(&c->d_score_done, (size_t)c->U * 32)) &&
       ok(dev_alloc(&c->d_sel_ready, (size_t)c->U * 32)) && ok(dev_alloc(&c->d_timeline, (size_t)KVD_TIMELINE_MAX * 5)) &&
       ok(hipHostMalloc(reinterpret_cast<void**>(&c->error_host), sizeof(int32_t), hipHostMallocMapped)) &&
       ok(hipHostGetDevicePointer(reinterpret_cast<void**>(&c->error_dev), c->error_host, 0)) &&
       ok(hipEventCreateWithFlags(&c->ev_fork, hipEventDisableTiming));
-  for (int i = 0; i < KVD_PIPE_STREAMS && c->MB > 1 && e == hipSuccess; ++i)
-    ok(hipStreamCreateWithFlags(&c->side[i], hipStreamNonBlocking));
-  for (int i = 0; i < c->MB && e == hipSuccess; ++i) {
-    ok(hipEventCreateWithFlags(&c->ev_score[i], hipEventDisableTiming));
-    ok(hipEventCreateWithFlags(&c->ev_done[i], hipEventDisableTiming));
-  }
+  if (e == hipSuccess) ok(ensure_group_resources(c, c->MB));
   for (int i = 0; i < 12 && e == hipSuccess; ++i) ok(hipEventCreate(&c->ev_prof[i]));
   if (e == hipSuccess) ok(hipMemcpy(c->d_capacity, c->h_capacity, LU * sizeof(int32_t), hipMemcpyHostToDevice));
   if (e == hipSuccess) ok(hipMemcpy(c->d_seq_len, c->h_seq_len, (size_t)c->B * sizeof(int32_t), hipMemcpyHostToDevice));
@@ -554,6 +574,70 @@ int kvd_set_profiling(kvd_ctx* ctx, int32_t on) {
   if (on < 0 || on > 2) return KVD_ERR_ARG;
   ctx->profiling = on;
   return KVD_OK;
+}
+
+int kvd_set_step_form(kvd_ctx* ctx, int32_t form) {
+  if (!ctx) return KVD_ERR_ARG;
+  if (form < -1 || form > KVD_MAX_MICRO) return KVD_ERR_SHAPE;
+  if (form == -1 && (!kvd_single_launch_ok(ctx) || ctx->Nc > 0)) return KVD_ERR_SHAPE;
+  HIP_TRY(ctx, hipDeviceSynchronize());
+  ctx->cfg.micro_batches = form;
+  ctx->MB = form < 1 ? 1 : form;
+  if (ctx->MB > ctx->B) ctx->MB = ctx->B;
+  HIP_TRY(ctx, ensure_group_resources(ctx, ctx->MB));
+  ctx->single_launch = kvd_wants_single_launch(ctx);
+  return KVD_OK;
+}
+
+int kvd_calibrate_step_form(kvd_ctx* ctx, int32_t layer, int32_t first_step, const void* q_steps, int32_t n_queries,
+                            int32_t steps_per_form, float* out, void* stream, int32_t* chosen_form,
+                            float* ms_per_step_or_null) {
+  if (!ctx || !q_steps || !out || !chosen_form || layer < 0 || layer >= ctx->L || n_queries < 1 || steps_per_form < 1 ||
+      !aligned16(q_steps))
+    return KVD_ERR_ARG;
+  if (!ctx->summaries || !ctx->pool || !ctx->store_dev) return KVD_ERR_STATE;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  const int candidates[4] = {1, 2, 4, -1};
+  const size_t q_bytes = (size_t)ctx->B * ctx->Hq * ctx->D * 2;
+  hipEvent_t e0 = ctx->ev_prof[10], e1 = ctx->ev_prof[11];
+  bool runs[4];
+  double total_ms[4] = {0.0, 0.0, 0.0, 0.0};
+  for (int ci = 0; ci < 4; ++ci)
+    runs[ci] = !((candidates[ci] == -1 && (!kvd_single_launch_ok(ctx) || ctx->Nc > 0)) || candidates[ci] > ctx->B);
+  // Every form runs two blocks of steps, enqueued back to back as in real use: the forms in order,
+  // then in reverse order, so that a drift of the workload over the calibration (a cache still
+  // warming up, say) weighs on all forms alike.  The first step of a block is not timed (first use
+  // of a form creates streams and loads code).
+  const int half = (steps_per_form + 1) / 2;
+  int step = first_step, qi = 0;
+  for (int pass = 0; pass < 2; ++pass) {
+    for (int k = 0; k < 4; ++k) {
+      const int ci = pass == 0 ? k : 3 - k;
+      if (!runs[ci]) continue;
+      int r = kvd_set_step_form(ctx, candidates[ci]);
+      if (r != KVD_OK) return r;
+      for (int i = 0; i <= half; ++i) {
+        if (i == 1) HIP_TRY(ctx, hipEventRecord(e0, s));
+        r = kvd_step(ctx, layer, step++, static_cast<const char*>(q_steps) + (size_t)(qi++ % n_queries) * q_bytes, out, nullptr, s);
+        if (r != KVD_OK) return r;
+      }
+      HIP_TRY(ctx, hipEventRecord(e1, s));
+      HIP_TRY(ctx, hipEventSynchronize(e1));
+      float ms = 0.f;
+      HIP_TRY(ctx, hipEventElapsedTime(&ms, e0, e1));
+      total_ms[ci] += ms;
+    }
+  }
+  steps_per_form = 2 * half;                           // timed steps per form
+  int best = 1;
+  double best_ms = -1.0;
+  for (int ci = 0; ci < 4; ++ci) {
+    const double ms = runs[ci] ? total_ms[ci] / steps_per_form : -1.0;
+    if (ms_per_step_or_null) ms_per_step_or_null[ci] = (float)ms;
+    if (runs[ci] && (best_ms < 0.0 || ms < best_ms)) { best_ms = ms; best = candidates[ci]; }
+  }
+  *chosen_form = best;
+  return kvd_set_step_form(ctx, best);
 }
 
 int kvd_step_form(const kvd_ctx* ctx) {

@@ -25,6 +25,7 @@ struct AttnArgs;
 struct kvd_ctx {
   kvd_config cfg;
   int L, B, Hq, Hkv, G, D, P, NP, k, Cmax, Lp, U, MB, S;
+  int S1;                  // attention split-K factor of the one-launch step (S: of the stand-alone kernel)
   int Nc;                  // centroids per unit of the hierarchical index, 0 = flat page index
   int bf16;
   int score_blocks;        // target number of blocks of a scoring launch

@@ -187,6 +187,8 @@ hipError_t kvd_launch_step(kvd_ctx* c, int layer, int step, const void* q, float
                        c->d_counts, 0);
   a.at = kvd_attn_args(c, layer, q, c->d_sel_pages, c->d_sel_slots, out, lse, 0);
   a.at.fuse_merge = 1;
+  a.at.S = c->S1;
+  a.at.per_split = (c->k + c->S1 - 1) / c->S1;
   a.score_done = c->d_score_done;
   a.sel_ready = c->d_sel_ready;
   a.error = c->error_dev;
@@ -216,7 +218,7 @@ hipError_t kvd_launch_step(kvd_ctx* c, int layer, int step, const void* q, float
   a.chunks = (c->NP + 512 * a.passes - 1) / (512 * a.passes);
   if (n_score > c->U * a.chunks) n_score = c->U * a.chunks;
   a.n_score = n_score;
-  const int n_blocks = a.n_score + c->U + c->U * c->S;
+  const int n_blocks = a.n_score + c->U + c->U * c->S1;
   c->tl_workgroups = n_blocks;
   if (c->profiling == 2 && n_blocks <= KVD_TIMELINE_MAX) a.timeline = c->d_timeline;
   const int ipt = (c->NP + kStepThreads - 1) / kStepThreads;

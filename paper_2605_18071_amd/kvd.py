@@ -47,7 +47,7 @@ EXPORTS = [
     "kvd_bind_summaries", "kvd_bind_host_store", "kvd_bind_slot_pool", "kvd_set_seq_lens",
     "kvd_build_summaries", "kvd_cache_reset", "kvd_cache_warm", "kvd_cache_export", "kvd_cache_import",
     "kvd_bind_centroids", "kvd_build_centroids", "kvd_append_kv", "kvd_advance", "kvd_score_select", "kvd_cache_resolve", "kvd_sparse_decode_attn", "kvd_step", "kvd_step_trace",
-    "kvd_set_profiling", "kvd_step_form", "kvd_set_wait_limit_us", "kvd_step_timeline", "kvd_get_stats", "kvd_reset_stats",
+    "kvd_set_profiling", "kvd_step_form", "kvd_set_step_form", "kvd_calibrate_step_form", "kvd_set_wait_limit_us", "kvd_step_timeline", "kvd_get_stats", "kvd_reset_stats",
 ]
 
 _lib = None
@@ -89,6 +89,8 @@ def load() -> C.CDLL:
         "kvd_step_timeline": [vp, C.POINTER(C.c_int64), i32, i32p],
         "kvd_set_wait_limit_us": [vp, C.c_int64],
         "kvd_step_form": [vp],
+        "kvd_set_step_form": [vp, i32],
+        "kvd_calibrate_step_form": [vp, i32, i32, vp, i32, i32, vp, vp, i32p, f32p],
         "kvd_get_stats": [vp, C.POINTER(KvdStats)],
         "kvd_reset_stats": [vp],
     }
@@ -261,6 +263,19 @@ class Kvd:
 
     def step_form(self) -> int:
         return int(self.lib.kvd_step_form(self.ctx))
+
+    def set_step_form(self, form: int):
+        self._check(self.lib.kvd_set_step_form(self.ctx, int(form)), "kvd_set_step_form")
+
+    def calibrate_step_form(self, layer: int, first_step: int, q_steps: torch.Tensor, steps_per_form: int,
+                            out: torch.Tensor, stream=None):
+        """Returns (chosen form, {form: ms per step}) — see kvd_calibrate_step_form."""
+        chosen = C.c_int32()
+        ms = (C.c_float * 4)()
+        self._check(self.lib.kvd_calibrate_step_form(self.ctx, layer, first_step, q_steps.data_ptr(), q_steps.shape[0],
+                                                     steps_per_form, out.data_ptr(), _stream_handle(stream),
+                                                     C.byref(chosen), ms), "kvd_calibrate_step_form")
+        return chosen.value, {f: ms[i] for i, f in enumerate((1, 2, 4, -1)) if ms[i] >= 0}
 
     def set_wait_limit_us(self, microseconds: int):
         self._check(self.lib.kvd_set_wait_limit_us(self.ctx, int(microseconds)), "kvd_set_wait_limit_us")

@@ -443,6 +443,35 @@ def test_single_launch_step_replayed_from_a_hip_graph():
     graphed.close()
 
 
+def test_calibration_picks_a_form_and_leaves_the_cache_consistent():
+    """The pre-run calibration executes real steps in every form; afterwards the cache must be
+    exactly where the oracle is after the same steps, and decoding continues in the chosen form."""
+    w = SCALED[3].replace(batch=4, steps=4)
+    rig = R.Rig(w)
+    units = all_units(rig)
+    n_q, spf = 5, 4
+    qs = torch.stack([q[0] for q in W.query_stream(w, rig.q0, n_q + 2, R.DEV)]).contiguous()
+    chosen, ms = rig.kvd.calibrate_step_form(0, 0, qs[:n_q], spf, rig.out)
+    assert set(ms) == {1, 2, 4, -1} and all(v > 0 for v in ms.values())
+    assert chosen == min(ms, key=ms.get) and rig.kvd.step_form() == chosen
+    n_run = len(ms) * 2 * (spf // 2 + 1)                              # every form: two blocks of 1 untimed + spf/2 timed steps
+    for i in range(n_run):                                            # the oracle takes the same steps
+        for ou in units:
+            ou.step(i, qs[i % n_q])
+    R.check_directory(rig, 0, units)
+    rep = R.StepReport()
+    for j in range(2):                                                # and decoding goes on from there
+        rig.step(0, n_run + j, qs[n_q + j])
+        for ou in units:
+            R.compare_unit(rig, ou, n_run + j, qs[n_q + j], rep)
+    for form in (1, 2, -1):
+        rig.kvd.set_step_form(form)
+        assert rig.kvd.step_form() == form
+    with pytest.raises(K.KvdError):
+        rig.kvd.set_step_form(99)
+    rig.close()
+
+
 def test_single_launch_timeline_and_wait_limit():
     """The one-launch step records one line per workgroup, in dispatch order and with consistent
     clocks; a wait limit of zero makes waiting workgroups give up (every kernel still ends
