@@ -22,6 +22,9 @@ index held in GPU memory, (2) fetch them, (3) compute sparse attention):
   attend           softmax attention over the selected tokens   (System Overview, step 3)
   kmeans_centroids the hierarchical index: page means grouped   (System Overview: the page means form
   select_pages_hier  into centroids; selection over centroids    higher-level centroids for similarity grouping)
+  extent_positions the third tier: the layout of the backing    (SSD-Aware Layout Planning)
+  extent_file_image  file, and which extents a step reads       (Parallel Sparse Synchronization, (b) and (c))
+  ExtentTier
 
 Readings taken where the paper is silent (each one is also listed in the design
 notes of the repository):
@@ -51,6 +54,18 @@ notes of the repository):
     cluster) and takes whole clusters until the page budget k is used up; the
     first cluster that does not fit gives its lowest pages; sink / recent pages
     are in unconditionally and are left out of the clusters' count.
+
+  * third tier: the backing file holds every page; a unit's pages sit in one
+    contiguous segment (layer-head partitioning), cut into extents of a fixed
+    number of pages; inside the segment the pages are ordered cluster by cluster
+    of the hierarchical index (cluster ascending, page ascending within; pages
+    of no cluster last), or in page order when there is no such index.  Host
+    DRAM holds a bounded pool of whole extents.  A step asks for the pages that
+    missed in the GPU window; an extent that holds one of them and is not in the
+    pool is read whole; runs of extents that are neighbours in the file, within
+    one segment, are one read, up to a maximal run length.  The paper names no
+    replacement rule for the DRAM tier: LRU over extents is used, victim =
+    smallest (stamp, extent) among pooled extents that this step does not need.
 
 Parity status.  select/LRU/attend/summaries are pinned in tests by brute force,
 closed forms, library routines and hand-worked fixtures (tests/golden).
@@ -406,6 +421,99 @@ def attend(q_group, keys, values, scale):
         out[g] = (w @ values) / denom
         lse[g] = m + np.log(denom)
     return out, lse
+
+
+# --------------------------------------------------------------------------- #
+# the third tier: backing file cut into extents, DRAM pool of extents
+# --------------------------------------------------------------------------- #
+def extent_positions(n_pages, members=None):
+    """Place of every page in its unit's segment of the backing file (SSD-Aware
+    Layout Planning: entries of one attention cluster are stored one after
+    another; every {layer, head} has a segment of its own).
+
+    members: the clusters' ascending page lists, or None for the flat index.
+    returns int32 [n_pages], a permutation of 0 .. n_pages-1.
+    """
+    if members is None:
+        return np.arange(n_pages, dtype=np.int32)
+    order = [int(p) for c in members for p in c]
+    inside = set(order)
+    order += [p for p in range(n_pages) if p not in inside]
+    if sorted(order) != list(range(n_pages)):
+        raise ValueError("cluster lists are not disjoint pages of the unit")
+    pos = np.empty(n_pages, dtype=np.int32)
+    pos[np.asarray(order, dtype=np.int64)] = np.arange(n_pages, dtype=np.int32)
+    return pos
+
+
+def extent_file_image(pages, positions, extent_pages):
+    """Bytes of the backing file for one layer.
+
+    pages [U][NP][page_bytes] uint8, positions [U][NP]; every segment is padded with
+    zero pages to a whole number of extents.
+    returns uint8 [U][NE * extent_pages][page_bytes]
+    """
+    U, NP, nbytes = pages.shape
+    n_ext = -(-NP // extent_pages)
+    image = np.zeros((U, n_ext * extent_pages, nbytes), dtype=np.uint8)
+    for u in range(U):
+        for p in range(NP):
+            image[u, int(positions[u][p])] = pages[u, p]
+    return image
+
+
+class ExtentTier:
+    """Which extents the DRAM pool holds, and what a step reads from the backing
+    file (Parallel Sparse Synchronization: only the blocks that the current
+    queries need are transferred; requests are merged into sequential reads of
+    whole extents; they land in a fixed pool of host buffers).
+
+    An extent is named by its number in the file: ((layer * U) + unit) * NE + e.
+    """
+
+    def __init__(self, n_units, n_pages, extent_pages, pool_extents, max_run_extents):
+        self.U = int(n_units)
+        self.E = int(extent_pages)
+        self.NE = -(-int(n_pages) // self.E)
+        self.pool_extents = int(pool_extents)
+        self.max_run = int(max_run_extents)
+        self.stamp = {}                                   # pooled extent -> step of last use
+
+    def extent_of(self, layer, unit, position):
+        return (int(layer) * self.U + int(unit)) * self.NE + int(position) // self.E
+
+    def fetch(self, layer, step, missed, positions):
+        """One step of one layer.  missed[u]: the pages of unit u that missed in
+        the GPU window; positions[u][p]: place of page p in the unit's segment.
+        returns dict(needed, hits, reads, evicted, runs): ascending extent numbers;
+        runs = [(first extent, count)] covering `reads` in file order.
+        """
+        needed = sorted({self.extent_of(layer, u, positions[u][int(p)])
+                         for u in range(self.U) for p in missed[u]})
+        hits = [g for g in needed if g in self.stamp]
+        reads = [g for g in needed if g not in self.stamp]
+        for g in hits:
+            self.stamp[g] = int(step)
+        n_evict = len(self.stamp) + len(reads) - self.pool_extents
+        evicted = []
+        if n_evict > 0:
+            cands = sorted((s, g) for g, s in self.stamp.items() if g not in set(needed))
+            if len(cands) < n_evict:
+                raise ValueError("the step needs more extents than the pool holds")
+            evicted = sorted(g for _, g in cands[:n_evict])
+            for g in evicted:
+                del self.stamp[g]
+        for g in reads:
+            self.stamp[g] = int(step)
+        runs = []
+        for g in reads:
+            if runs:
+                first, count = runs[-1]
+                if g == first + count and g // self.NE == first // self.NE and count < self.max_run:
+                    runs[-1] = (first, count + 1)
+                    continue
+            runs.append((g, 1))
+        return dict(needed=needed, hits=hits, reads=reads, evicted=evicted, runs=runs)
 
 
 # --------------------------------------------------------------------------- #

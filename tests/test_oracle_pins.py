@@ -541,3 +541,130 @@ def test_step_output_does_not_depend_on_cache_state():
     toks = [t for p in a["sel"] for t in range(p * P, min((p + 1) * P, T))]
     w = scipy.special.softmax(0.25 * (q @ keys[toks].T), axis=1)
     assert np.allclose(a["out"], w @ vals[toks], rtol=1e-12, atol=1e-13)
+
+
+# --------------------------------------------------------------------------- #
+# third tier: layout of the backing file, DRAM pool of extents, read plan
+# --------------------------------------------------------------------------- #
+def _tier_fixture():
+    rows = H.read_golden("tier_trace_2units.txt")
+    head = {r[0].split(":")[0].strip(): r[0].split(":")[1] for r in rows if ":" in r[0] and len(r) == 1}
+    clusters = [np.array(_ints(c), dtype=np.int32) for c in head["clusters 1"].split(";")]
+    positions = [np.array(_ints(head["position 0"])), np.array(_ints(head["position 1"]))]
+    steps = [r for r in rows if len(r) == 9]
+    return clusters, positions, steps
+
+
+def test_extent_layout_matches_hand_worked_fixture():
+    clusters, positions, _ = _tier_fixture()
+    assert orc.extent_positions(8).tolist() == positions[0].tolist()
+    assert orc.extent_positions(8, clusters).tolist() == positions[1].tolist()
+
+
+def test_extent_tier_matches_hand_worked_trace():
+    _, positions, steps = _tier_fixture()
+    tier = orc.ExtentTier(n_units=2, n_pages=8, extent_pages=2, pool_extents=3, max_run_extents=2)
+    assert len(steps) == 7
+    for step, m0, m1, needed, hits, reads, evicted, runs, pooled in steps:
+        got = tier.fetch(0, int(step), [_ints(m0), _ints(m1)], positions)
+        assert got["needed"] == _ints(needed), step
+        assert got["hits"] == _ints(hits), step
+        assert got["reads"] == _ints(reads), step
+        assert got["evicted"] == _ints(evicted), step
+        assert got["runs"] == [tuple(int(x) for x in r.split(":")) for r in runs.split()], step
+        assert sorted(tier.stamp) == _ints(pooled), step
+
+
+def test_extent_positions_keep_clusters_together():
+    n_pages = 57
+    assign = RNG.integers(0, 9, size=n_pages)
+    assign[RNG.choice(n_pages, size=5, replace=False)] = -1          # pages of no cluster (beyond the valid length)
+    members = [np.nonzero(assign == c)[0] for c in range(9)]
+    pos = orc.extent_positions(n_pages, members)
+    assert sorted(pos.tolist()) == list(range(n_pages))
+    start = 0
+    for c in range(9):                                               # cluster c fills the next len(c) places, pages ascending
+        assert pos[members[c]].tolist() == list(range(start, start + len(members[c])))
+        start += len(members[c])
+    rest = np.nonzero(assign < 0)[0]
+    assert pos[rest].tolist() == list(range(start, n_pages))
+    with pytest.raises(ValueError):
+        orc.extent_positions(4, [np.array([0, 1]), np.array([1, 2])])
+
+
+def test_extent_tier_of_single_page_extents_is_the_lru_window():
+    """Extents of one page, one unit, page order: "extent needed" is "page selected", so the
+    pool must behave exactly as the page-granular LRU window (pinned on its own above)."""
+    n_pages, cap = 40, 11
+    tier = orc.ExtentTier(1, n_pages, 1, cap, 1)
+    lru = orc.LruWindow(cap)
+    pos = [orc.extent_positions(n_pages)]
+    for t in range(80):
+        want = sorted(RNG.choice(n_pages, size=int(RNG.integers(0, 7)), replace=False).tolist())
+        got = tier.fetch(0, t, [want], pos)
+        hits, misses, evicted = lru.resolve(want, t)
+        assert (got["hits"], got["reads"], got["evicted"]) == (hits, misses, evicted)
+        assert got["runs"] == [(p, 1) for p in misses]
+        assert tier.stamp == lru.stamp
+
+
+@pytest.mark.parametrize("E,pool,max_run", [(2, 7, 3), (4, 5, 8), (3, 42, 2), (8, 4, 1)])
+def test_extent_tier_invariants_and_plan_delivers_every_missed_page(E, pool, max_run):
+    """Random traces: what the plan reads, followed literally on the file image, must put every
+    missed page's bytes into the pool; the bookkeeping obeys the cache invariants; the runs
+    are the maximal ones."""
+    L, U, NP, nbytes = 2, 3, 19, 8
+    NE = -(-NP // E)
+    pages = RNG.integers(0, 256, size=(L, U, NP, nbytes), dtype=np.uint8)
+    positions = [[orc.extent_positions(NP, [np.nonzero(a == c)[0] for c in range(4)])
+                  for a in RNG.integers(0, 4, size=(U, NP))] for _ in range(L)]
+    image = [orc.extent_file_image(pages[l], positions[l], E).reshape(U * NE, E, nbytes) for l in range(L)]
+    tier = orc.ExtentTier(U, NP, E, pool, max_run)
+    pool_bytes = {}
+    reads_of = {}
+    for t in range(60):
+        l = t % L
+        missed = []
+        budget = pool                                            # a step may not need more extents than the pool holds
+        for u in range(U):
+            n = int(RNG.integers(0, 4))
+            pg = sorted(RNG.choice(NP, size=n, replace=False).tolist())
+            ext = {positions[l][u][p] // E for p in pg}
+            if len(ext) > budget:
+                pg = []
+                ext = set()
+            budget -= len(ext)
+            missed.append(pg)
+        before = set(tier.stamp)
+        got = tier.fetch(l, t, missed, positions[l])
+        need = set(got["needed"])
+        assert set(got["hits"]) == need & before and set(got["reads"]) == need - before
+        assert set(got["evicted"]) <= before - need
+        assert len(got["evicted"]) == max(0, len(before) + len(got["reads"]) - pool)
+        assert set(tier.stamp) == (before - set(got["evicted"])) | need and len(tier.stamp) <= pool
+        assert all(tier.stamp[g] == t for g in need)
+        if got["evicted"]:                                           # nothing older stays behind
+            kept_old = [(tier.stamp[g], g) for g in set(tier.stamp) - need]
+            gone = max((s, g) for g, s in stamps_before.items() if g in got["evicted"])
+            assert all(x > gone for x in kept_old)
+        flat = [first + i for first, n in got["runs"] for i in range(n)]
+        assert flat == got["reads"]
+        for (f0, n0), (f1, n1) in zip(got["runs"], got["runs"][1:]):
+            assert not (f0 + n0 == f1 and f0 // NE == f1 // NE and n0 < max_run)
+        assert all(1 <= n <= max_run and (f // NE) == ((f + n - 1) // NE) for f, n in got["runs"])
+        for g in got["evicted"]:
+            del pool_bytes[g]
+        for first, n in got["runs"]:                                  # one sequential read of n extents
+            base = l * U * NE
+            chunk = image[l][first - base:first - base + n]
+            for i in range(n):
+                pool_bytes[first + i] = chunk[i]
+                reads_of[first + i] = reads_of.get(first + i, 0) + 1
+        for u in range(U):
+            for p in missed[u]:
+                place = positions[l][u][p]
+                g = tier.extent_of(l, u, place)
+                assert np.array_equal(pool_bytes[g][place % E], pages[l, u, p])
+        stamps_before = dict(tier.stamp)
+    if pool >= L * U * NE:
+        assert max(reads_of.values()) == 1                           # nothing is ever read twice
