@@ -253,6 +253,123 @@ int kvd_step(kvd_ctx* ctx, int32_t layer, int32_t step, const void* q, float* ou
 int kvd_step_trace(kvd_ctx* ctx, int32_t* sel_pages, int32_t* sel_slots, int32_t* hit_mask, int32_t* evicted,
                    int32_t* counts, float* scores, void* stream);
 
+/* ---- third tier: backing file on SSD, pool of extents in host DRAM --------------------------- */
+/*
+ * "Cross-tier Synergistic Storage": the backing file holds every page (the full backing store);
+ * host DRAM holds a bounded pool; the GPU window is unchanged.
+ *
+ * Layout of the file ("SSD-Aware Layout Planning").  An *extent* is a contiguous block of
+ * extent_pages pages.  Every {layer, head} unit has a segment of its own, NE = ceil(NP /
+ * extent_pages) extents long, segments in (physical layer, unit) order; extent number
+ * x = ((layer * U) + unit) * NE + e starts at byte x * extent_pages * page_bytes.  Inside a
+ * segment page p sits at place position[unit][p] (a permutation of 0..NP-1; places NP.. of the last
+ * extent are padding): pages that are attended together — one cluster of the hierarchical index —
+ * are neighbours (kvd_layout_from_clusters), else page order.  A page keeps the host store's
+ * natural layout (K[P][D] then V[P][D]).
+ *
+ * Per step ("Parallel Sparse Synchronization", (b) block-level sparse fetching and (c)
+ * hierarchical transfer): the pages that missed in the GPU window are mapped to extents; extents
+ * already in the DRAM pool are hits; the others are read whole from the file, runs of neighbouring
+ * extents of one segment as one read of at most max_run_extents extents, queue_depth reads in
+ * flight; reads land directly in the pool (a fixed set of pinned buffers, allocated once by the
+ * caller), from where the GPU copies the missed pages into their slots.  The pool is replaced LRU by
+ * extent: when it overflows, the pooled extents that the current step does not need leave in
+ * (step of last use, extent number) order.
+ *
+ * A kvd_tier is plain host code: it needs no GPU, and its pool may be any host memory (pinned
+ * memory when a GPU is to read it).  Calls on one kvd_tier must not overlap in time.
+ */
+typedef struct kvd_tier kvd_tier;
+
+typedef struct {
+  int32_t n_layers;         /* physical layers held by the file */
+  int32_t n_units;          /* U = B * Hkv */
+  int32_t max_pages;        /* NP */
+  int32_t extent_pages;     /* pages per extent, >= 1 */
+  int64_t page_bytes;       /* 2 * P * D * 2; extent bytes must be a multiple of 4096 for direct I/O */
+  int64_t pool_extents;     /* capacity of the DRAM pool, in extents */
+  int32_t queue_depth;      /* reader threads, 1..64 */
+  int32_t max_run_extents;  /* longest run of neighbouring extents merged into one read, 1..64 */
+  int32_t direct_io;        /* 1: open the file with O_DIRECT if the file system takes it (reads then
+                               bypass the page cache), falling back to buffered reads otherwise; see
+                               kvd_tier_stats.direct_io for what was taken */
+} kvd_tier_config;
+
+typedef struct {
+  uint64_t steps;           /* kvd_tier_fetch calls */
+  uint64_t pages_requested; /* missed pages handed in */
+  uint64_t extents_needed;  /* distinct extents those pages lie in, summed over the calls */
+  uint64_t extent_hits;     /* ... found in the pool */
+  uint64_t extent_reads;    /* ... read from the file */
+  uint64_t extent_evictions;
+  uint64_t reads_issued;    /* read calls after merging */
+  uint64_t bytes_read;
+  double ms_plan;           /* host time spent on lookup, replacement and planning */
+  double ms_io;             /* wall time from the first read issued to the last one done */
+  int32_t direct_io;        /* 0: buffered reads; 1: O_DIRECT straight into the pool; 2: O_DIRECT into one
+                               aligned staging buffer per reader, copied into the pool from there (taken from the
+                               first read on that the file system refuses into the pool's memory) */
+} kvd_tier_stats;
+
+/* Opens (creating and sizing it if need be) the backing file and takes `pool_host`, pool_extents *
+ * extent_pages * page_bytes bytes of caller-owned host memory, 4096-byte aligned, as the DRAM pool.
+ * The layout starts as page order for every unit; the pool starts empty.  KVD_ERR_ARG for NULL
+ * pointers, KVD_ERR_SHAPE for sizes out of range, KVD_ERR_STATE if the file cannot be opened or
+ * sized (errno is kept: kvd_tier_last_errno). */
+int kvd_tier_open(const kvd_tier_config* cfg, const char* path, void* pool_host, kvd_tier** out);
+int kvd_tier_close(kvd_tier* tier);
+int kvd_tier_last_errno(const kvd_tier* tier);
+/* Places of the pages of one physical layer: host_position [U][NP], every row a permutation of
+ * 0..NP-1 (KVD_ERR_ARG otherwise).  Set before that layer is written. */
+int kvd_tier_set_layout(kvd_tier* tier, int32_t layer, const int32_t* host_position);
+/* Set-up helper: writes the pages of one physical layer, host_pages [U][NP][page_bytes] in the host
+ * store's order, to their places in the file (buffered writes, then fsync) and drops that layer's
+ * extents from the pool. */
+int kvd_tier_write_layer(kvd_tier* tier, int32_t layer, const void* host_pages);
+/* One step of one physical layer.  host_miss_list [U][k][2] (page, slot) and host_miss_count [U] are
+ * the GPU window's misses as the resolve stage leaves them (entries with slot < 0 are skipped).
+ * On return every needed extent is in the pool and host_src_offset [U][k] holds, for entry j < count
+ * of unit u, the byte offset of that page inside the pool (-1 for skipped entries).  Synchronous.
+ * KVD_ERR_CAPACITY if the step needs more extents than the pool holds (nothing is changed),
+ * KVD_ERR_ARG for a page out of range, KVD_ERR_STATE if a read fails or comes back short. */
+int kvd_tier_fetch(kvd_tier* tier, int32_t layer, int32_t step, const int32_t* host_miss_list,
+                   const int32_t* host_miss_count, int32_t k, int64_t* host_src_offset);
+/* What the last kvd_tier_fetch did.  counts[5]: extents needed, hits, reads, evictions, read calls.
+ * runs [cap_runs][2] receives (first extent, number of extents) of the read calls in file order,
+ * evicted [cap_evicted] the evicted extents in ascending order (each list cut at its capacity;
+ * either may be NULL). */
+int kvd_tier_trace(const kvd_tier* tier, int64_t* counts, int64_t* runs, int64_t cap_runs, int64_t* evicted,
+                   int64_t cap_evicted);
+/* Which extents the pool holds: writes up to cap extent numbers in ascending order, and the number
+ * held to *n_pooled. */
+int kvd_tier_pooled(const kvd_tier* tier, int64_t* extents, int64_t cap, int64_t* n_pooled);
+int kvd_tier_drop_pool(kvd_tier* tier);          /* empties the DRAM pool (the file is untouched) */
+int kvd_tier_get_stats(const kvd_tier* tier, kvd_tier_stats* out);
+int kvd_tier_reset_stats(kvd_tier* tier);
+/* Measurement helper: reads the whole file once, front to back, in reads of max_run_extents extents
+ * with queue_depth readers into the pool's memory (the pool is dropped), and reports the rate — what
+ * this file, opened this way, gives a purely sequential reader. */
+int kvd_tier_sequential_read_gbps(kvd_tier* tier, double* gbps);
+
+/* Semantic-contiguity layout from the bound hierarchical index of `layer`: host_position [U][NP]
+ * puts the pages of a unit cluster by cluster (cluster ascending, page ascending within; pages
+ * beyond the valid length last).  Synchronises the device.  KVD_ERR_STATE without bound centroids. */
+int kvd_layout_from_clusters(kvd_ctx* ctx, int32_t layer, int32_t* host_position);
+/* Attaches a tier to the context: kvd_step_tiered then takes missed pages from it.  The tier's pool
+ * must be pinned host memory (KVD_ERR_ARG otherwise) and its sizes must match the context's (units,
+ * pages, page bytes, physical layers; KVD_ERR_SHAPE otherwise).  The tier stays the caller's and
+ * must outlive its use by the context.  NULL detaches. */
+int kvd_bind_tier(kvd_ctx* ctx, kvd_tier* tier);
+/* kvd_step with the third tier behind the window: score, select and directory update run on the
+ * GPU as in kvd_step; the miss lists are then handed to the host (this call waits for them — the
+ * host has to issue the reads), kvd_tier_fetch brings the extents into the pool, and the copy of
+ * the missed pages from the pool into their slots and the attention are enqueued on `stream`.
+ * Outputs are valid once the stream has been synchronised.  The pinned host store is not read.
+ * If the tier fails (KVD_ERR_CAPACITY: the step needs more extents than the pool holds;
+ * KVD_ERR_STATE: a read failed) no output is produced and the window of `layer` is emptied, since
+ * its directory had already been updated for pages that did not arrive. */
+int kvd_step_tiered(kvd_ctx* ctx, int32_t layer, int32_t step, const void* q, float* out, float* lse, void* stream);
+
 /* ---- counters ------------------------------------------------------------------------------ */
 
 /* mode 0: off.

@@ -17,7 +17,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libkvd.so")
-SOURCES = ["kvd_api.hip", "kvd_select.hip", "kvd_fast.hip", "kvd_cache.hip", "kvd_attn.hip", "kvd_step.hip", "kvd_centroids.hip"]
+SOURCES = ["kvd_api.hip", "kvd_select.hip", "kvd_fast.hip", "kvd_cache.hip", "kvd_attn.hip", "kvd_step.hip", "kvd_centroids.hip", "kvd_tier.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-fPIC", "-std=c++17", "-Wall", "-Wno-unused-function",
          # keep the compiler from forming packed-fp32 VALU ops
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]

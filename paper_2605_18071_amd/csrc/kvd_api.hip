@@ -83,6 +83,10 @@ static void free_ctx(kvd_ctx* c) {
   for (int i = 0; i < KVD_PIPE_STREAMS; ++i)
     if (c->side[i]) (void)hipStreamDestroy(c->side[i]);
   if (c->error_host) (void)hipHostFree(c->error_host);
+  if (c->h_miss_list) (void)hipHostFree(c->h_miss_list);
+  if (c->h_miss_count) (void)hipHostFree(c->h_miss_count);
+  if (c->h_src_offset) (void)hipHostFree(c->h_src_offset);
+  if (c->d_src_offset) (void)hipFree(c->d_src_offset);
   free(c->h_capacity);
   free(c->h_seq_len);
   free(c);
@@ -271,6 +275,56 @@ int kvd_build_centroids(kvd_ctx* ctx, int32_t layer, int32_t iterations, int32_t
   return KVD_OK;
 }
 
+int kvd_layout_from_clusters(kvd_ctx* ctx, int32_t layer, int32_t* host_position) {
+  if (!ctx || !host_position || layer < 0 || layer >= ctx->L) return KVD_ERR_ARG;
+  if (ctx->Nc == 0 || !ctx->cluster_pages) return KVD_ERR_STATE;
+  const size_t n = (size_t)ctx->U * ctx->NP;
+  std::vector<int32_t> listed(n);
+  HIP_TRY(ctx, hipDeviceSynchronize());
+  HIP_TRY(ctx, hipMemcpy(listed.data(), ctx->cluster_pages + (size_t)layer * n, n * sizeof(int32_t), hipMemcpyDeviceToHost));
+  for (int u = 0; u < ctx->U; ++u) {
+    const int32_t* lst = listed.data() + (size_t)u * ctx->NP;
+    int32_t* pos = host_position + (size_t)u * ctx->NP;
+    std::fill(pos, pos + ctx->NP, -1);
+    int place = 0;
+    for (int i = 0; i < ctx->NP; ++i) {                      // the clusters' pages, cluster by cluster
+      const int32_t p = lst[i];
+      if (p < 0) continue;
+      if (p >= ctx->NP || pos[p] >= 0) return KVD_ERR_STATE;
+      pos[p] = place++;
+    }
+    for (int p = 0; p < ctx->NP; ++p)                        // pages of no cluster
+      if (pos[p] < 0) pos[p] = place++;
+  }
+  return KVD_OK;
+}
+
+int kvd_bind_tier(kvd_ctx* ctx, kvd_tier* tier) {
+  if (!ctx) return KVD_ERR_ARG;
+  if (!tier) { ctx->tier = nullptr; ctx->tier_pool_dev = nullptr; return KVD_OK; }
+  const kvd_tier_config* tc = kvd_tier_config_of(tier);
+  if (tc->n_units != ctx->U || tc->max_pages != ctx->NP || tc->page_bytes != (int64_t)ctx->page_bytes ||
+      tc->n_layers != ctx->Lp)
+    return KVD_ERR_SHAPE;
+  void* dptr = nullptr;
+  hipError_t e = hipHostGetDevicePointer(&dptr, kvd_tier_pool_of(tier), 0);
+  if (e != hipSuccess || dptr == nullptr) {
+    (void)hipGetLastError();
+    ctx->last_hip = (int)e;
+    return KVD_ERR_ARG;
+  }
+  const size_t uk = (size_t)ctx->U * ctx->k;
+  if (!ctx->h_miss_list) {
+    HIP_TRY(ctx, hipHostMalloc(reinterpret_cast<void**>(&ctx->h_miss_list), uk * 2 * sizeof(int32_t), hipHostMallocDefault));
+    HIP_TRY(ctx, hipHostMalloc(reinterpret_cast<void**>(&ctx->h_miss_count), (size_t)ctx->U * sizeof(int32_t), hipHostMallocDefault));
+    HIP_TRY(ctx, hipHostMalloc(reinterpret_cast<void**>(&ctx->h_src_offset), uk * sizeof(int64_t), hipHostMallocDefault));
+    HIP_TRY(ctx, dev_alloc(&ctx->d_src_offset, uk));
+  }
+  ctx->tier = tier;
+  ctx->tier_pool_dev = static_cast<const char*>(dptr);
+  return KVD_OK;
+}
+
 int kvd_bind_host_store(kvd_ctx* ctx, const void* pinned_store) {
   if (!ctx || !pinned_store || !aligned16(pinned_store)) return KVD_ERR_ARG;
   void* dptr = nullptr;
@@ -448,27 +502,28 @@ int kvd_sparse_decode_attn(kvd_ctx* ctx, int32_t layer, const void* q, const int
 
 // Selection + directory update + fetch for units [u0, u1): one fused kernel when the sizes allow
 // the register-resident path, else the three size-agnostic kernels.
-static hipError_t launch_select_resolve_fetch(kvd_ctx* c, int layer, int step, int u0, int u1, hipStream_t s) {
+static hipError_t launch_select_resolve_fetch(kvd_ctx* c, int layer, int step, int u0, int u1, hipStream_t s,
+                                              bool fetch = true) {
   if (c->Nc > 0) {
     // hierarchical index: clusters -> pages, then the directory update and the fetch
     hipError_t e = kvd_launch_cluster_select(c, layer, c->d_scores, c->d_sel_pages, u0, u1, s);
     if (e != hipSuccess) return e;
     if (kvd_fast_path_ok(c))
-      return kvd_launch_select_resolve(c, layer, step, false, true, true, c->d_scores, c->d_sel_pages, c->d_sel_slots,
+      return kvd_launch_select_resolve(c, layer, step, false, true, fetch, c->d_scores, c->d_sel_pages, c->d_sel_slots,
                                        c->d_hit_mask, c->d_evicted, c->d_counts, u0, u1, s);
     e = kvd_launch_resolve(c, layer, step, c->d_sel_pages, c->d_sel_slots, c->d_hit_mask, c->d_evicted, c->d_counts, u0,
                            u1, s);
-    if (e != hipSuccess) return e;
+    if (e != hipSuccess || !fetch) return e;
     return kvd_launch_gather(c, layer, u0, u1, s);
   }
   if (kvd_fast_path_ok(c))
-    return kvd_launch_select_resolve(c, layer, step, true, true, true, c->d_scores, c->d_sel_pages, c->d_sel_slots,
+    return kvd_launch_select_resolve(c, layer, step, true, true, fetch, c->d_scores, c->d_sel_pages, c->d_sel_slots,
                                      c->d_hit_mask, c->d_evicted, c->d_counts, u0, u1, s);
   hipError_t e = kvd_launch_select(c, c->d_scores, c->d_sel_pages, u0, u1, s);
   if (e != hipSuccess) return e;
   e = kvd_launch_resolve(c, layer, step, c->d_sel_pages, c->d_sel_slots, c->d_hit_mask, c->d_evicted, c->d_counts, u0,
                          u1, s);
-  if (e != hipSuccess) return e;
+  if (e != hipSuccess || !fetch) return e;
   return kvd_launch_gather(c, layer, u0, u1, s);
 }
 
@@ -550,6 +605,34 @@ int kvd_step(kvd_ctx* ctx, int32_t layer, int32_t step, const void* q, float* ou
   }
   for (int i = 0; i < c->MB; ++i)
     if (i % (1 + KVD_PIPE_STREAMS) != 0) HIP_TRY(c, hipStreamWaitEvent(s, c->ev_done[i], 0));
+  return KVD_OK;
+}
+
+int kvd_step_tiered(kvd_ctx* ctx, int32_t layer, int32_t step, const void* q, float* out, float* lse, void* stream) {
+  if (!ctx || !q || !out || layer < 0 || layer >= ctx->L || !aligned16(q)) return KVD_ERR_ARG;
+  if (!ctx->summaries || !ctx->pool || !ctx->tier || (ctx->Nc > 0 && !ctx->centroids)) return KVD_ERR_STATE;
+  kvd_ctx* c = ctx;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  ++c->n_steps;
+  c->last_scores = c->d_scores;
+  // (1) select, and the directory update, on the GPU; nothing is fetched yet
+  HIP_TRY(c, kvd_launch_score(c, layer, q, c->d_scores, 0, c->U, s));
+  HIP_TRY(c, launch_select_resolve_fetch(c, layer, step, 0, c->U, s, false));
+  // (2) the misses go to the host, which reads the extents that hold them into its pool
+  const size_t uk = (size_t)c->U * c->k;
+  HIP_TRY(c, hipMemcpyAsync(c->h_miss_count, c->d_miss_count, (size_t)c->U * sizeof(int32_t), hipMemcpyDeviceToHost, s));
+  HIP_TRY(c, hipMemcpyAsync(c->h_miss_list, c->d_miss_list, uk * 2 * sizeof(int32_t), hipMemcpyDeviceToHost, s));
+  HIP_TRY(c, hipStreamSynchronize(s));
+  const int rc = kvd_tier_fetch(c->tier, layer % c->Lp, step, c->h_miss_list, c->h_miss_count, c->k, c->h_src_offset);
+  if (rc != KVD_OK) {
+    // the directory already names slots for pages that will not arrive: empty the layer's window
+    const int rr = reset_directory(c, layer);
+    return rr != KVD_OK ? rr : rc;
+  }
+  // (3) pool -> slots, then attention
+  HIP_TRY(c, hipMemcpyAsync(c->d_src_offset, c->h_src_offset, uk * sizeof(int64_t), hipMemcpyHostToDevice, s));
+  HIP_TRY(c, kvd_launch_gather(c, layer, 0, c->U, s, c->tier_pool_dev, c->d_src_offset));
+  HIP_TRY(c, kvd_launch_attend(c, layer, q, c->d_sel_pages, c->d_sel_slots, out, lse, 0, c->U, s));
   return KVD_OK;
 }
 

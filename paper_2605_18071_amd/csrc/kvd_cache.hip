@@ -205,12 +205,14 @@ __device__ __forceinline__ void copy_page(const char* __restrict__ src, char* __
 }
 
 // Fetch: block (x, u) copies misses x, x+8, ... of unit u from the pinned host store (read across
-// the host link, 16 bytes per lane) into their slots.
+// the host link, 16 bytes per lane) into their slots.  With src_offset the j-th miss of the unit
+// is read from store + src_offset[u][j] instead (a negative offset: nothing to copy).
 template <bool TILED>
 __global__ __launch_bounds__(kGatherThreads) void gather_kernel(const char* __restrict__ store,   // [U][NP] pages of the layer
                                                                char* __restrict__ pool,          // [U][Cmax] slots of the layer
                                                                const int32_t* __restrict__ miss_list,
-                                                               const int32_t* __restrict__ miss_count, int k, int NP,
+                                                               const int32_t* __restrict__ miss_count,
+                                                               const int64_t* __restrict__ src_offset, int k, int NP,
                                                                int Cmax, int P, unsigned page_bytes, int u0) {
   __shared__ uint16_t vt[kTileTokens * kHeadDim];
   const int u = blockIdx.y + u0;
@@ -219,8 +221,15 @@ __global__ __launch_bounds__(kGatherThreads) void gather_kernel(const char* __re
     const int page = miss_list[((size_t)u * k + j) * 2];
     const int slot = miss_list[((size_t)u * k + j) * 2 + 1];
     if (slot < 0) continue;
-    copy_page<TILED>(store + ((size_t)u * NP + page) * page_bytes, pool + ((size_t)u * Cmax + slot) * page_bytes, P,
-                     page_bytes, vt);
+    const char* src;
+    if (src_offset != nullptr) {
+      const int64_t off = src_offset[(size_t)u * k + j];
+      if (off < 0) continue;
+      src = store + off;
+    } else {
+      src = store + ((size_t)u * NP + page) * page_bytes;
+    }
+    copy_page<TILED>(src, pool + ((size_t)u * Cmax + slot) * page_bytes, P, page_bytes, vt);
   }
 }
 
@@ -397,18 +406,19 @@ hipError_t kvd_launch_resolve(kvd_ctx* c, int layer, int step, const int32_t* se
   return hipGetLastError();
 }
 
-hipError_t kvd_launch_gather(kvd_ctx* c, int layer, int u0, int u1, hipStream_t s) {
+hipError_t kvd_launch_gather(kvd_ctx* c, int layer, int u0, int u1, hipStream_t s, const char* src_base,
+                             const int64_t* src_offset) {
   using namespace kvd;
   if (u1 <= u0) return hipSuccess;
   const int lp = layer % c->Lp;
-  const char* store = c->store_dev + (size_t)lp * c->U * c->NP * c->page_bytes;
+  const char* store = src_offset ? src_base : c->store_dev + (size_t)lp * c->U * c->NP * c->page_bytes;
   char* pool = c->pool + (size_t)layer * c->U * c->Cmax * c->page_bytes;
   if (c->tiled)
     hipLaunchKernelGGL(gather_kernel<true>, dim3(kGatherBlocksPerUnit, u1 - u0), dim3(kGatherThreads), 0, s, store, pool,
-                       c->d_miss_list, c->d_miss_count, c->k, c->NP, c->Cmax, c->P, (unsigned)c->page_bytes, u0);
+                       c->d_miss_list, c->d_miss_count, src_offset, c->k, c->NP, c->Cmax, c->P, (unsigned)c->page_bytes, u0);
   else
     hipLaunchKernelGGL(gather_kernel<false>, dim3(kGatherBlocksPerUnit, u1 - u0), dim3(kGatherThreads), 0, s, store, pool,
-                       c->d_miss_list, c->d_miss_count, c->k, c->NP, c->Cmax, c->P, (unsigned)c->page_bytes, u0);
+                       c->d_miss_list, c->d_miss_count, src_offset, c->k, c->NP, c->Cmax, c->P, (unsigned)c->page_bytes, u0);
   return hipGetLastError();
 }
 

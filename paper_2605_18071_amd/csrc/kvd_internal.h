@@ -81,6 +81,13 @@ struct kvd_ctx {
   int n_cus;                // compute units of the device
   long long* d_timeline;    // [KVD_TIMELINE_MAX][5] per-workgroup record of the last single-launch step
   int tl_workgroups;        // workgroups of that launch
+  // third tier (borrowed) and what kvd_step_tiered hands across the host boundary
+  kvd_tier* tier;
+  const char* tier_pool_dev;  // the tier's pool as the GPU addresses it
+  int32_t* h_miss_list;       // pinned [U][k][2]
+  int32_t* h_miss_count;      // pinned [U]
+  int64_t* h_src_offset;      // pinned [U][k]
+  int64_t* d_src_offset;      // [U][k]
   int profiling;
   int last_hip;
   uint64_t n_steps;
@@ -101,7 +108,13 @@ kvd::FastArgs kvd_fast_args(kvd_ctx* c, int layer, int step, bool do_gather, con
                             int32_t* sel_slots, int32_t* hit_mask, int32_t* evicted, int32_t* counts, int u0);
 kvd::AttnArgs kvd_attn_args(kvd_ctx* c, int layer, const void* q, const int32_t* sel_pages, const int32_t* sel_slots,
                             float* out, float* lse, int u0);
-hipError_t kvd_launch_gather(kvd_ctx* c, int layer, int u0, int u1, hipStream_t s);
+// Copies the missed pages of units [u0, u1) into their slots: from the pinned host store, or, with
+// src_base / src_offset ([U][k] byte offsets, -1 = skip), from wherever the caller says each one is.
+hipError_t kvd_launch_gather(kvd_ctx* c, int layer, int u0, int u1, hipStream_t s, const char* src_base = nullptr,
+                             const int64_t* src_offset = nullptr);
+// kvd_tier.hip
+const kvd_tier_config* kvd_tier_config_of(const kvd_tier* t);
+void* kvd_tier_pool_of(const kvd_tier* t);
 hipError_t kvd_launch_attend(kvd_ctx* c, int layer, const void* q, const int32_t* sel_pages,
                              const int32_t* sel_slots, float* out, float* lse, int u0, int u1, hipStream_t s,
                              hipEvent_t between = nullptr);   // `between`: recorded after the attention kernel, before the merge

@@ -32,6 +32,23 @@ class KvdConfig(C.Structure):
     ]
 
 
+class KvdTierConfig(C.Structure):
+    _fields_ = [
+        ("n_layers", C.c_int32), ("n_units", C.c_int32), ("max_pages", C.c_int32), ("extent_pages", C.c_int32),
+        ("page_bytes", C.c_int64), ("pool_extents", C.c_int64), ("queue_depth", C.c_int32),
+        ("max_run_extents", C.c_int32), ("direct_io", C.c_int32),
+    ]
+
+
+class KvdTierStats(C.Structure):
+    _fields_ = [
+        ("steps", C.c_uint64), ("pages_requested", C.c_uint64), ("extents_needed", C.c_uint64),
+        ("extent_hits", C.c_uint64), ("extent_reads", C.c_uint64), ("extent_evictions", C.c_uint64),
+        ("reads_issued", C.c_uint64), ("bytes_read", C.c_uint64), ("ms_plan", C.c_double), ("ms_io", C.c_double),
+        ("direct_io", C.c_int32),
+    ]
+
+
 class KvdStats(C.Structure):
     _fields_ = [
         ("steps", C.c_uint64), ("hits", C.c_uint64), ("misses", C.c_uint64), ("evictions", C.c_uint64),
@@ -48,6 +65,10 @@ EXPORTS = [
     "kvd_build_summaries", "kvd_cache_reset", "kvd_cache_warm", "kvd_cache_export", "kvd_cache_import",
     "kvd_bind_centroids", "kvd_build_centroids", "kvd_append_kv", "kvd_advance", "kvd_score_select", "kvd_cache_resolve", "kvd_sparse_decode_attn", "kvd_step", "kvd_step_trace",
     "kvd_set_profiling", "kvd_step_form", "kvd_set_step_form", "kvd_calibrate_step_form", "kvd_set_wait_limit_us", "kvd_step_timeline", "kvd_get_stats", "kvd_reset_stats",
+    "kvd_tier_open", "kvd_tier_close", "kvd_tier_last_errno", "kvd_tier_set_layout", "kvd_tier_write_layer",
+    "kvd_tier_fetch", "kvd_tier_trace", "kvd_tier_pooled", "kvd_tier_drop_pool", "kvd_tier_get_stats",
+    "kvd_tier_reset_stats", "kvd_tier_sequential_read_gbps", "kvd_layout_from_clusters", "kvd_bind_tier",
+    "kvd_step_tiered",
 ]
 
 _lib = None
@@ -93,6 +114,21 @@ def load() -> C.CDLL:
         "kvd_calibrate_step_form": [vp, i32, i32, vp, i32, i32, vp, vp, i32p, f32p],
         "kvd_get_stats": [vp, C.POINTER(KvdStats)],
         "kvd_reset_stats": [vp],
+        "kvd_tier_open": [C.POINTER(KvdTierConfig), C.c_char_p, vp, C.POINTER(vp)],
+        "kvd_tier_close": [vp],
+        "kvd_tier_last_errno": [vp],
+        "kvd_tier_set_layout": [vp, i32, vp],
+        "kvd_tier_write_layer": [vp, i32, vp],
+        "kvd_tier_fetch": [vp, i32, i32, vp, vp, i32, vp],
+        "kvd_tier_trace": [vp, vp, vp, C.c_int64, vp, C.c_int64],
+        "kvd_tier_pooled": [vp, vp, C.c_int64, C.POINTER(C.c_int64)],
+        "kvd_tier_drop_pool": [vp],
+        "kvd_tier_get_stats": [vp, C.POINTER(KvdTierStats)],
+        "kvd_tier_reset_stats": [vp],
+        "kvd_tier_sequential_read_gbps": [vp, C.POINTER(C.c_double)],
+        "kvd_layout_from_clusters": [vp, i32, vp],
+        "kvd_bind_tier": [vp, vp],
+        "kvd_step_tiered": [vp, i32, i32, vp, vp, vp, vp],
     }
     for name, args in protos.items():
         fn = getattr(lib, name)
@@ -257,6 +293,20 @@ class Kvd:
         self._check(self.lib.kvd_step_trace(self.ctx, _ptr(sel_pages), _ptr(sel_slots), _ptr(hit_mask), _ptr(evicted),
                                             _ptr(counts), _ptr(scores), _stream_handle(stream)), "kvd_step_trace")
 
+    # ---- third tier
+    def layout_from_clusters(self, layer: int) -> torch.Tensor:
+        pos = torch.empty((self.units, self.cfg.max_pages), dtype=torch.int32)
+        self._check(self.lib.kvd_layout_from_clusters(self.ctx, layer, pos.data_ptr()), "kvd_layout_from_clusters")
+        return pos
+
+    def bind_tier(self, tier: Optional["KvdTier"]):
+        self._keep.append(tier)
+        self._check(self.lib.kvd_bind_tier(self.ctx, tier.handle if tier is not None else None), "kvd_bind_tier")
+
+    def step_tiered(self, layer: int, step: int, q, out, lse=None, stream=None):
+        self._check(self.lib.kvd_step_tiered(self.ctx, layer, step, q.data_ptr(), out.data_ptr(), _ptr(lse),
+                                             _stream_handle(stream)), "kvd_step_tiered")
+
     # ---- counters
     def set_profiling(self, mode):
         self._check(self.lib.kvd_set_profiling(self.ctx, int(mode)), "kvd_set_profiling")
@@ -297,3 +347,91 @@ class Kvd:
 
     def reset_stats(self):
         self._check(self.lib.kvd_reset_stats(self.ctx), "kvd_reset_stats")
+
+
+class KvdTier:
+    """One kvd_tier (host code only; needs no GPU).  `pool` is a uint8 CPU tensor of pool_extents *
+    extent_pages * page_bytes bytes, 4096-byte aligned; pinned if a GPU is to read it."""
+
+    def __init__(self, path: str, pool: torch.Tensor, *, n_layers, n_units, max_pages, extent_pages, page_bytes,
+                 pool_extents, queue_depth=8, max_run_extents=8, direct_io=False):
+        self.lib = load()
+        cfg = KvdTierConfig()
+        cfg.n_layers, cfg.n_units, cfg.max_pages, cfg.extent_pages = n_layers, n_units, max_pages, extent_pages
+        cfg.page_bytes, cfg.pool_extents = page_bytes, pool_extents
+        cfg.queue_depth, cfg.max_run_extents, cfg.direct_io = queue_depth, max_run_extents, 1 if direct_io else 0
+        if pool.device.type != "cpu" or pool.numel() * pool.element_size() < pool_extents * extent_pages * page_bytes:
+            raise ValueError("the pool must be CPU memory of pool_extents * extent_pages * page_bytes bytes")
+        self.cfg, self.pool, self.path = cfg, pool, path
+        self.handle = C.c_void_p()
+        st = self.lib.kvd_tier_open(C.byref(cfg), path.encode(), pool.data_ptr(), C.byref(self.handle))
+        if st != OK:
+            self.handle = C.c_void_p()
+            raise KvdError(st, "kvd_tier_open")
+
+    def _check(self, st: int, where: str):
+        if st != OK:
+            raise KvdError(st, f"{where} (errno {self.lib.kvd_tier_last_errno(self.handle)})")
+
+    def close(self):
+        if self.handle:
+            self.lib.kvd_tier_close(self.handle)
+            self.handle = C.c_void_p()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def set_layout(self, layer: int, position: torch.Tensor):
+        pos = position.to(torch.int32).contiguous()
+        self._check(self.lib.kvd_tier_set_layout(self.handle, layer, pos.data_ptr()), "kvd_tier_set_layout")
+
+    def write_layer(self, layer: int, host_pages: torch.Tensor):
+        self._check(self.lib.kvd_tier_write_layer(self.handle, layer, host_pages.data_ptr()), "kvd_tier_write_layer")
+
+    def fetch(self, layer: int, step: int, miss_list: torch.Tensor, miss_count: torch.Tensor) -> torch.Tensor:
+        """miss_list [U, k, 2] int32, miss_count [U] int32 (CPU) -> byte offsets into the pool, [U, k] int64."""
+        k = miss_list.shape[1]
+        off = torch.empty((self.cfg.n_units, k), dtype=torch.int64)
+        self._check(self.lib.kvd_tier_fetch(self.handle, layer, step, miss_list.data_ptr(), miss_count.data_ptr(), k,
+                                            off.data_ptr()), "kvd_tier_fetch")
+        return off
+
+    def trace(self):
+        """dict(needed, hits, reads, evictions, read_calls, runs [(first, count)], evicted [extents]) of the last fetch."""
+        counts = torch.zeros(5, dtype=torch.int64)
+        self._check(self.lib.kvd_tier_trace(self.handle, counts.data_ptr(), None, 0, None, 0), "kvd_tier_trace")
+        runs = torch.zeros((int(counts[4]), 2), dtype=torch.int64)
+        evicted = torch.zeros(int(counts[3]), dtype=torch.int64)
+        self._check(self.lib.kvd_tier_trace(self.handle, counts.data_ptr(), runs.data_ptr(), runs.shape[0],
+                                            evicted.data_ptr(), evicted.shape[0]), "kvd_tier_trace")
+        names = ("needed", "hits", "reads", "evictions", "read_calls")
+        out = {n: int(counts[i]) for i, n in enumerate(names)}
+        out["runs"] = [(int(a), int(b)) for a, b in runs.tolist()]
+        out["evicted"] = evicted.tolist()
+        return out
+
+    def pooled(self):
+        n = C.c_int64()
+        self._check(self.lib.kvd_tier_pooled(self.handle, None, 0, C.byref(n)), "kvd_tier_pooled")
+        ext = torch.zeros(n.value, dtype=torch.int64)
+        self._check(self.lib.kvd_tier_pooled(self.handle, ext.data_ptr(), n.value, C.byref(n)), "kvd_tier_pooled")
+        return ext.tolist()
+
+    def drop_pool(self):
+        self._check(self.lib.kvd_tier_drop_pool(self.handle), "kvd_tier_drop_pool")
+
+    def stats(self) -> KvdTierStats:
+        st = KvdTierStats()
+        self._check(self.lib.kvd_tier_get_stats(self.handle, C.byref(st)), "kvd_tier_get_stats")
+        return st
+
+    def reset_stats(self):
+        self._check(self.lib.kvd_tier_reset_stats(self.handle), "kvd_tier_reset_stats")
+
+    def sequential_read_gbps(self) -> float:
+        g = C.c_double()
+        self._check(self.lib.kvd_tier_sequential_read_gbps(self.handle, C.byref(g)), "kvd_tier_sequential_read_gbps")
+        return g.value

@@ -96,9 +96,42 @@ class Rig:
             return self.w.capacity
         return int(self.capacity[layer * self.w.units + u])
 
+    def attach_tier(self, path: str, *, extent_pages: int, pool_extents: int, max_run_extents: int = 8,
+                    queue_depth: int = 4, direct_io: bool = False, semantic: bool = False):
+        """Puts the third tier behind the window: the backing file is written from the host store,
+        kvd_step_tiered is used from now on, and the context's host store is replaced by one full
+        of NaNs, so that a page taken from there instead of the file cannot go unnoticed."""
+        w = self.w
+        pool = torch.zeros(pool_extents * extent_pages * w.page_bytes, dtype=torch.uint8).pin_memory()
+        self.tier = K.KvdTier(path, pool, n_layers=w.phys_layers, n_units=w.units, max_pages=w.n_pages,
+                              extent_pages=extent_pages, page_bytes=w.page_bytes, pool_extents=pool_extents,
+                              queue_depth=queue_depth, max_run_extents=max_run_extents, direct_io=direct_io)
+        self.tier_pool = pool
+        self.positions = []
+        for lp in range(w.phys_layers):
+            if semantic:
+                pos = self.kvd.layout_from_clusters(lp)
+                self.tier.set_layout(lp, pos)
+            else:
+                pos = torch.arange(w.n_pages, dtype=torch.int32).repeat(w.units, 1)
+            self.positions.append(pos.numpy())
+            self.tier.write_layer(lp, self.store[lp])
+        self.kvd.bind_tier(self.tier)
+        self.poison = torch.full(self.store.shape, float("nan"), dtype=self.store.dtype).pin_memory()
+        self.kvd.bind_host_store(self.poison)
+        self.tiered = True
+
     def step(self, layer: int, t: int, q_layer: torch.Tensor):
-        """One fused layer-step through kvd_step; trace copied into the rig's buffers."""
-        self.kvd.step(layer, t, q_layer, self.out, self.lse)
+        """One fused layer-step through kvd_step (kvd_step_tiered once a tier is attached); trace
+        copied into the rig's buffers."""
+        if getattr(self, "tiered", False):
+            try:
+                self.kvd.step_tiered(layer, t, q_layer, self.out, self.lse)
+            except K.KvdError as e:
+                raise AssertionError(f"{e}; tier errno {self.tier.lib.kvd_tier_last_errno(self.tier.handle)}, "
+                                     f"direct I/O mode {self.tier.stats().direct_io}") from e
+        else:
+            self.kvd.step(layer, t, q_layer, self.out, self.lse)
         self.kvd.step_trace(self.sel_pages, self.sel_slots, self.hit_mask, self.evicted, self.counts, self.scores)
         torch.cuda.synchronize()
         self.n_sel_pages = self.sel_pages.cpu().numpy()
@@ -115,6 +148,8 @@ class Rig:
 
     def close(self):
         self.kvd.close()
+        if getattr(self, "tiered", False):
+            self.tier.close()
 
 
 class OracleUnit:
