@@ -134,6 +134,16 @@ def main() -> int:
     ap.add_argument("--calibrate", type=int, default=0, metavar="STEPS",
                     help="before the warm-up, let the library time every form of the step on STEPS real steps each "
                          "and keep the fastest (kvd_calibrate_step_form)")
+    ap.add_argument("--tier", metavar="PATH", default="",
+                    help="put the third tier behind the GPU window: the K/V pages are written to a backing file at PATH "
+                         "(removed afterwards), host DRAM holds a pool of extents, and the timed steps are kvd_step_tiered")
+    ap.add_argument("--tier-extent-pages", type=int, default=8)
+    ap.add_argument("--tier-pool-frac", type=float, default=0.25, help="DRAM pool as a fraction of the file's extents")
+    ap.add_argument("--tier-queue-depth", type=int, default=16)
+    ap.add_argument("--tier-max-run", type=int, default=8)
+    ap.add_argument("--tier-buffered", action="store_true", help="read through the page cache instead of O_DIRECT")
+    ap.add_argument("--tier-layout", choices=["page", "semantic"], default="page",
+                    help="order of a unit's pages in the file: page order, or cluster by cluster (needs --centroids)")
     ap.add_argument("--timeline", action="store_true",
                     help="when the step runs as one launch: add the per-workgroup timeline of one all-hit step")
     args = ap.parse_args()
@@ -187,6 +197,22 @@ def main() -> int:
     pages = W.warm_pages(w)
     if pages is not None:
         ctx.cache_warm(0, pages.tolist() * U, [len(pages)] * U)
+    tier = None
+    if args.tier:
+        E = args.tier_extent_pages
+        n_ext = U * (-(-NP // E))
+        pool_extents = max(int(args.tier_pool_frac * n_ext), args.tier_queue_depth * args.tier_max_run)
+        tier_pool = torch.zeros(pool_extents * E * w.page_bytes, dtype=torch.uint8).pin_memory()
+        tier = K.KvdTier(args.tier, tier_pool, n_layers=1, n_units=U, max_pages=NP, extent_pages=E, page_bytes=w.page_bytes,
+                         pool_extents=pool_extents, queue_depth=args.tier_queue_depth, max_run_extents=args.tier_max_run,
+                         direct_io=not args.tier_buffered)
+        if args.tier_layout == "semantic":
+            tier.set_layout(0, ctx.layout_from_clusters(0))
+        t_write = time.perf_counter()
+        tier.write_layer(0, store[0])
+        t_write = time.perf_counter() - t_write
+        ctx.bind_tier(tier)
+    step_fn = ctx.step_tiered if tier is not None else ctx.step
     n_cal = 8 * ((args.calibrate + 1) // 2 + 1) if args.calibrate > 0 else 0
     n_total = args.warmup + 2 * args.steps + 1
     stream_q = [q[0].contiguous() for q in W.query_stream(w, q0, n_cal + n_total, dev)]
@@ -201,9 +227,11 @@ def main() -> int:
     t, base = 0, 0
     calibration = None
     for _ in range(args.warmup):
-        ctx.step(0, base + t, queries[t], out, stream=stream)
+        step_fn(0, base + t, queries[t], out, stream=stream)
         t += 1
     torch.cuda.synchronize()
+    if tier is not None:
+        tier.reset_stats()
     if args.calibrate > 0:                       # on the warmed-up cache; its steps continue the query stream
         chosen, ms = ctx.calibrate_step_form(0, t, torch.stack(q_cal).contiguous(), args.calibrate, out, stream=stream)
         calibration = {"chosen_form": chosen, "ms_per_step": {str(f): v for f, v in ms.items()}}
@@ -211,7 +239,7 @@ def main() -> int:
     ctx.reset_stats()
     t0 = time.perf_counter()
     for _ in range(args.steps):
-        ctx.step(0, base + t, queries[t], out, stream=stream)
+        step_fn(0, base + t, queries[t], out, stream=stream)
         t += 1
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
@@ -242,6 +270,29 @@ def main() -> int:
                   "host_link_GBps_if_fetch_bound": gathered_per_step / (elapsed / args.steps) / 1e9},
     }
 
+    if tier is not None:
+        ts = tier.stats()
+        seq = tier.sequential_read_gbps()                      # drops the pool; the file read front to back, same readers
+        read_gbps = ts.bytes_read / max(ts.ms_io, 1e-9) / 1e6
+        result["config"]["workload"] += f" + third tier (backing file, extents of {args.tier_extent_pages} pages, {args.tier_layout} order)"
+        result["cache"]["host_bytes_per_step"] = ts.pages_requested * w.page_bytes / args.steps
+        result["cache"].pop("host_link_GBps_if_fetch_bound")
+        result["tier"] = {
+            "extent_pages": args.tier_extent_pages, "extent_bytes": args.tier_extent_pages * w.page_bytes,
+            "pool_extents": pool_extents, "pool_frac_of_file": pool_extents / n_ext, "queue_depth": args.tier_queue_depth,
+            "max_run_extents": args.tier_max_run, "layout": args.tier_layout,
+            "direct_io_mode": ts.direct_io, "file_GiB": n_ext * args.tier_extent_pages * w.page_bytes / 2**30, "file_write_s": round(t_write, 2),
+            "missed_pages_per_step": ts.pages_requested / args.steps, "extents_needed_per_step": ts.extents_needed / args.steps,
+            "pool_hit_rate": ts.extent_hits / max(1, ts.extents_needed), "extents_read_per_step": ts.extent_reads / args.steps,
+            "read_calls_per_step": ts.reads_issued / args.steps, "file_bytes_per_step": ts.bytes_read / args.steps,
+            "read_amplification": ts.bytes_read / max(1, ts.pages_requested * w.page_bytes),
+            "ms_plan_per_step": ts.ms_plan / args.steps, "ms_io_per_step": ts.ms_io / args.steps,
+            "ms_rest_per_step": ms_per_step - (ts.ms_plan + ts.ms_io) / args.steps,
+            "read_GBps": read_gbps, "sequential_read_GBps": seq, "frac_of_sequential": read_gbps / seq if seq > 0 else None,
+        }
+        ctx.bind_tier(None)
+        tier.close()
+        os.unlink(args.tier)
     if w.index_centroids > 0:
         result["config"]["index"] = {"centroids": w.index_centroids, "kmeans_rounds": w.index_iterations,
                                      "build_s": round(t_index, 3)}

@@ -78,6 +78,49 @@ def test_full_size_hierarchical_index():
     torch.cuda.empty_cache()
 
 
+def test_full_size_third_tier(tmp_path):
+    """cfg3 at full size behind the third tier (8 GiB backing file, cluster-ordered extents of 8
+    pages, DRAM pool of a quarter of the extents, direct I/O): sampled units against the oracle as
+    usual, and the tier's trace of every step against the oracle's extent pool fed with the miss
+    sets of the whole batch."""
+    from oracle import kvd_oracle as orc
+    w = W.CONFIGS[3].replace(index_centroids=4096, index_iterations=2)
+    E, pool_extents, max_run = 8, 32768, 8
+    print("[cfg3-tier] building workload and index", flush=True)
+    rig = R.Rig(w)
+    units = [R.OracleUnit(rig, 0, b, h) for (b, h) in [(0, 0), (9, 6)]]
+    print("[cfg3-tier] writing the backing file", flush=True)
+    rig.attach_tier(str(tmp_path / "kv.bin"), extent_pages=E, pool_extents=pool_extents, max_run_extents=max_run,
+                    queue_depth=16, direct_io=True, semantic=True)
+    for ou in units:                                                  # the oracle's layout for the units it has clustered
+        assert np.array_equal(orc.extent_positions(w.n_pages, ou.members), rig.positions[0][ou.u])
+    assert all(sorted(row.tolist()) == list(range(w.n_pages)) for row in rig.positions[0][::17])
+    otier = orc.ExtentTier(w.units, w.n_pages, E, pool_extents, max_run)
+    rep = R.StepReport()
+    reads = 0
+    for t, q in enumerate(W.query_stream(w, rig.q0, 8, R.DEV)):
+        rig.step(0, t, q[0])
+        for ou in units:
+            R.compare_unit(rig, ou, t, q[0], rep)
+        valid = (rig.n_sel_pages >= 0) & (rig.n_hit_mask == 0)
+        missed = [sorted(rig.n_sel_pages[u][valid[u]].tolist()) for u in range(w.units)]
+        want = otier.fetch(0, t, missed, rig.positions[0])
+        got = rig.tier.trace()
+        assert (got["needed"], got["hits"], got["reads"]) == (len(want["needed"]), len(want["hits"]), len(want["reads"])), t
+        assert got["evicted"] == want["evicted"] and got["runs"] == want["runs"], t
+        reads += got["reads"]
+        print(f"[cfg3-tier] step {t} ok: missed pages {sum(map(len, missed))}, extents needed {got['needed']} "
+              f"read {got['reads']} in {got['read_calls']} calls, evicted {got['evictions']}", flush=True)
+    R.check_directory(rig, 0, units)
+    assert rig.tier.pooled() == sorted(otier.stamp)
+    st = rig.tier.stats()
+    assert st.extent_reads == reads and st.extent_evictions > 0 and rep.unit_steps == 8 * len(units)
+    print(f"[cfg3-tier] direct I/O mode {st.direct_io}, {st.bytes_read / 2**30:.2f} GiB in {st.ms_io:.0f} ms", flush=True)
+    rig.close()
+    del rig
+    torch.cuda.empty_cache()
+
+
 @pytest.mark.parametrize("cfg,mb", [(3, 0), (3, 1), (2, 0), (4, 0), (5, 0), (5, -1)])
 def test_full_size_sampled_parity(cfg, mb):
     """mb = 0: the form the library chooses (what bench.py times: one launch for cfg2-4, the chain of
