@@ -320,9 +320,22 @@ def main() -> int:
                                 "attend_GBps": selected_bytes / (ms_attend * 1e-3) / 1e9}
         fetch_ms = (ps.ms_select_resolve + ps.ms_gather) / n
         link = ps.gathered_bytes / n / (fetch_ms * 1e-3) / 1e9
+        # what a plain copy engine transfer of 1 GiB of the same pinned store reaches on this machine
+        flat = store.view(-1)[: (1 << 30) // store.element_size()]
+        dst = torch.empty_like(flat, device=dev)
+        memcpy_gbps = 0.0
+        for _ in range(3):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record(stream)
+            dst.copy_(flat, non_blocking=True)
+            e1.record(stream)
+            torch.cuda.synchronize()
+            memcpy_gbps = max(memcpy_gbps, flat.numel() * flat.element_size() / (e0.elapsed_time(e1) * 1e-3) / 1e9)
+        del dst
         result["host_link"] = {"what": "fetch of missed pages from pinned host memory inside the selection/fetch kernel (chain pass)",
                                "bytes_per_step": ps.gathered_bytes / n, "GBps_over_select_resolve_fetch": link,
-                               "peak_GBps": HOST_LINK_PEAK_GBPS, "frac": link / HOST_LINK_PEAK_GBPS}
+                               "peak_GBps": HOST_LINK_PEAK_GBPS, "frac": link / HOST_LINK_PEAK_GBPS,
+                               "pinned_memcpy_GBps": memcpy_gbps, "frac_of_pinned_memcpy": link / memcpy_gbps}
 
         # pass 3: the GPU-resident path alone, in the form the timed region used.  The last query is
         # replayed, so every selected page is a hit and nothing crosses the host link: time per

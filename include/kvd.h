@@ -46,10 +46,11 @@ typedef enum {
   KVD_OK = 0,
   KVD_ERR_ARG = -1,      /* NULL / misaligned / not device-addressable pointer, bad index */
   KVD_ERR_SHAPE = -2,    /* inconsistent or unsupported sizes */
-  KVD_ERR_CAPACITY = -3, /* k > C for some unit, forced pages > k, warm list > C */
+  KVD_ERR_CAPACITY = -3, /* k > C for some unit, forced pages > k, warm list > C, tier pool too small for a step */
   KVD_ERR_DTYPE = -4,
   KVD_ERR_HIP = -5,      /* a HIP runtime call failed; see kvd_last_hip_error */
-  KVD_ERR_STATE = -6     /* buffers not bound yet, or an imported directory breaks its invariants */
+  KVD_ERR_STATE = -6     /* buffers not bound yet, an imported directory breaks its invariants, an in-kernel wait
+                            ran out, or a file operation of the third tier failed */
 } kvd_status;
 
 typedef enum { KVD_F16 = 0, KVD_BF16 = 1 } kvd_dtype;

@@ -139,10 +139,10 @@ const char* kvd_strerror(int status) {
     case KVD_OK: return "ok";
     case KVD_ERR_ARG: return "bad argument (NULL, misaligned, out of range, or not addressable by the GPU)";
     case KVD_ERR_SHAPE: return "inconsistent or unsupported sizes";
-    case KVD_ERR_CAPACITY: return "capacity too small (k > C, forced pages > k, or warm list > C)";
+    case KVD_ERR_CAPACITY: return "capacity too small (k > C, forced pages > k, warm list > C, or a step needs more extents than the tier's pool holds)";
     case KVD_ERR_DTYPE: return "unsupported KV dtype";
     case KVD_ERR_HIP: return "HIP runtime call failed (see kvd_last_hip_error)";
-    case KVD_ERR_STATE: return "buffers not bound, or directory invariants violated";
+    case KVD_ERR_STATE: return "buffers not bound, directory invariants violated, an in-kernel wait ran out, or a file operation of the tier failed";
     default: return "unknown status";
   }
 }
