@@ -53,7 +53,10 @@ notes of the repository):
     the KV dtype.  Selection ranks clusters by centroid score (ties to the lower
     cluster) and takes whole clusters until the page budget k is used up; the
     first cluster that does not fit gives its lowest pages; sink / recent pages
-    are in unconditionally and are left out of the clusters' count.
+    are in unconditionally and are left out of the clusters' count.  With this
+    index a step scores clusters, not pages: lookahead eviction then takes the
+    score of a page's cluster as the page's score (equal scores, i.e. pages of
+    one cluster: the higher page leaves first, as before).
 
   * third tier: the backing file holds every page; a unit's pages sit in one
     contiguous segment (layer-head partitioning), cut into extents of a fixed
@@ -287,6 +290,18 @@ def select_pages_hier(cluster_scores, members, k, n_valid, sink_pages=0, recent_
     out = np.full(k, -1, dtype=np.int32)
     pages = sorted(chosen)
     out[: len(pages)] = pages
+    return out
+
+
+def cluster_scores_by_page(cluster_scores, members, n_pages):
+    """The importance that lookahead eviction sees for a page when the index is
+    hierarchical: the current-step score of the page's cluster (the only score the
+    step computes).  A page of no cluster gets -inf: it leaves first.
+    returns fp64 [n_pages]
+    """
+    out = np.full(int(n_pages), -np.inf)
+    for c, pages in enumerate(members):
+        out[np.asarray(pages, dtype=np.int64)] = float(cluster_scores[c])
     return out
 
 
@@ -532,19 +547,24 @@ def decode_unit_step(q_group, summaries, keys, values, window, step, *, k, page_
     forced_evicted: likewise for the victims of a LookaheadWindow.
     centroids, members: if given, selection goes through the hierarchical index
               (cluster scores instead of page scores; `scores` in the result are then
-              the cluster scores, and lookahead eviction is not defined).
-    returns dict(scores, sel, hits, misses, evicted, out, lse)
+              the cluster scores).  Lookahead eviction then ranks a resident page by
+              the score of its cluster (`evict_scores` in the result, see
+              cluster_scores_by_page).
+    returns dict(scores, evict_scores, sel, used, hits, misses, evicted, out, lse)
     """
     qbar = pooled_query(q_group)
+    n_valid = -(-int(seq_len) // int(page_size))
     if centroids is None:
         scores = page_scores(qbar, summaries, scale)
         sel = select_pages(scores, k, sink_pages, recent_pages)
+        evict_scores = scores
     else:
         scores = page_scores(qbar, centroids, scale)
-        sel = select_pages_hier(scores, members, k, -(-int(seq_len) // int(page_size)), sink_pages, recent_pages)
+        sel = select_pages_hier(scores, members, k, n_valid, sink_pages, recent_pages)
+        evict_scores = cluster_scores_by_page(scores, members, n_valid)
     used = sel if forced_sel is None else np.asarray(forced_sel, dtype=np.int32)
-    hits, misses, evicted = window.resolve(used, step, scores=scores, forced_evicted=forced_evicted)
+    hits, misses, evicted = window.resolve(used, step, scores=evict_scores, forced_evicted=forced_evicted)
     toks = selected_tokens(used, page_size, seq_len)
     out, lse = attend(q_group, keys[toks], values[toks], scale)
-    return dict(scores=scores, sel=sel, used=used, hits=hits, misses=misses,
+    return dict(scores=scores, evict_scores=evict_scores, sel=sel, used=used, hits=hits, misses=misses,
                 evicted=evicted, out=out, lse=lse)

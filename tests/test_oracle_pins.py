@@ -543,6 +543,43 @@ def test_step_output_does_not_depend_on_cache_state():
     assert np.allclose(a["out"], w @ vals[toks], rtol=1e-12, atol=1e-13)
 
 
+def test_lookahead_under_the_hierarchical_index_uses_the_cluster_score():
+    """Hand-worked: 6 pages in clusters {2,3} {0,1} {4,5} with scores 0.1, 0.9, 0.5; all but page 5
+    resident, capacity 5; page 5 comes in -> the lowest cluster score is cluster 0's, its higher
+    page 3 leaves.  Then page 3 comes back -> page 2 (cluster 0's other page) leaves; then a page of
+    no cluster (6, score -inf) is the first to go."""
+    members = [np.array([2, 3]), np.array([0, 1]), np.array([4, 5])]
+    per_page = orc.cluster_scores_by_page(np.array([0.1, 0.9, 0.5]), members, 7)
+    assert per_page.tolist() == [0.9, 0.9, 0.1, 0.1, 0.5, 0.5, -np.inf]
+    win = orc.LookaheadWindow(5)
+    win.warm([0, 1, 2, 3, 4])
+    assert win.resolve([4, 5], 0, scores=per_page) == ([4], [5], [3])
+    assert win.resolve([3, 5], 1, scores=per_page) == ([5], [3], [2])
+    win2 = orc.LookaheadWindow(3)
+    win2.warm([0, 2, 6])
+    assert win2.resolve([1], 0, scores=per_page) == ([], [1], [6])
+
+
+def test_hierarchical_step_with_one_page_per_cluster_is_the_flat_lookahead_step():
+    """Clusters of one page each, the page's summary as centroid: the step through the index
+    must be the flat step, lookahead victims included."""
+    G, D, P, NP = 2, 16, 4, 30
+    T = P * NP
+    keys = orc.round_f64(RNG.standard_normal((T, D)), orc.BF16)
+    vals = orc.round_f64(RNG.standard_normal((T, D)), orc.BF16)
+    summ = orc.page_summaries(keys, P, T, orc.BF16)
+    members = [np.array([p]) for p in range(NP)]
+    flat, hier = orc.LookaheadWindow(9), orc.LookaheadWindow(9)
+    kw = dict(k=5, page_size=P, seq_len=T, scale=0.25)
+    for t in range(12):
+        q = orc.round_f64(RNG.standard_normal((G, D)), orc.BF16)
+        a = orc.decode_unit_step(q, summ, keys, vals, flat, t, **kw)
+        b = orc.decode_unit_step(q, summ, keys, vals, hier, t, centroids=summ, members=members, **kw)
+        assert (a["hits"], a["misses"], a["evicted"]) == (b["hits"], b["misses"], b["evicted"])
+        assert np.array_equal(a["sel"], b["sel"]) and np.array_equal(a["out"], b["out"])
+    assert flat.stamp == hier.stamp and len(flat.stamp) == 9
+
+
 # --------------------------------------------------------------------------- #
 # third tier: layout of the backing file, DRAM pool of extents, read plan
 # --------------------------------------------------------------------------- #
