@@ -99,8 +99,9 @@ typedef struct {
                               the Nc centroids and takes whole clusters, best first, until k pages are used
                               (the first cluster that does not fit gives its lowest pages; sink / recent pages
                               are in first and do not count as members).  Nc <= 8192, Nc <= max_pages <= 16384;
-                              not with KVD_EVICT_LOOKAHEAD (which needs a score per page); kvd_step then runs
-                              as a chain of kernels. */
+                              kvd_step then runs as a chain of kernels.  Under KVD_EVICT_LOOKAHEAD the score
+                              of a resident page is the score of its cluster (a page of no cluster leaves
+                              first; pages of one cluster: the higher page first). */
 } kvd_config;
 
 typedef struct {
@@ -222,6 +223,10 @@ int kvd_bind_centroids(kvd_ctx* ctx, void* dev_centroids, int32_t* dev_cluster_s
  * call.  dev_assign_trace: device [iterations][B][Hkv][NP] int32 receiving every round's assignment,
  * or NULL.  Allocates temporary device memory and waits for `stream`. */
 int kvd_build_centroids(kvd_ctx* ctx, int32_t layer, int32_t iterations, int32_t* dev_assign_trace, void* stream);
+/* After the caller has written a layer's cluster lists itself (instead of kvd_build_centroids):
+ * recomputes the library's page -> cluster table from them, which lookahead eviction reads.  Enqueued
+ * on `stream`.  KVD_ERR_STATE without bound centroids. */
+int kvd_refresh_clusters(kvd_ctx* ctx, int32_t layer, void* stream);
 
 /* ---- growth of the KV store during decoding ------------------------------------------------ */
 

@@ -51,7 +51,6 @@ static int validate_config(const kvd_config* c) {
   if (c->attn_splits < 0 || c->attn_splits > KVD_MAX_SPLITS) return KVD_ERR_SHAPE;
   if (c->index_centroids < 0 || c->index_centroids > KVD_MAX_CENTROIDS || c->index_centroids > c->max_pages) return KVD_ERR_SHAPE;
   if (c->index_centroids > 0 && c->max_pages > KVD_FAST_MAX_PAGES) return KVD_ERR_SHAPE;
-  if (c->index_centroids > 0 && c->policy == KVD_EVICT_LOOKAHEAD) return KVD_ERR_ARG;   // needs a score per page
   if (!(c->softmax_scale >= 0.f) || isinf(c->softmax_scale)) return KVD_ERR_ARG;
   if ((long long)c->sink_pages + c->recent_pages > c->topk_pages) return KVD_ERR_CAPACITY;
   if (c->topk_pages > c->capacity_max) return KVD_ERR_CAPACITY;
@@ -67,7 +66,7 @@ static int validate_config(const kvd_config* c) {
 
 static void free_ctx(kvd_ctx* c) {
   if (c == nullptr) return;
-  void* dev[] = {c->d_capacity, c->d_seq_len, c->d_page_to_slot, c->d_slot_page, c->d_slot_stamp, c->d_resident,
+  void* dev[] = {c->d_capacity, c->d_seq_len, c->d_page_to_slot, c->d_slot_page, c->d_slot_stamp, c->d_resident, c->d_page_cluster,
                  c->d_scores, c->d_sel_pages, c->d_sel_slots, c->d_hit_mask, c->d_evicted, c->d_counts,
                  c->d_miss_list, c->d_miss_count, c->d_part_acc, c->d_part_ml, c->d_attn_ticket, c->d_stats,
                  c->d_score_done, c->d_sel_ready, c->d_timeline};
@@ -239,6 +238,11 @@ int kvd_create(const kvd_config* cfg, kvd_ctx** out) {
   if (e == hipSuccess) *c->error_host = 0;
   if (e == hipSuccess) c->single_launch = kvd_wants_single_launch(c);
   if (e == hipSuccess && c->Nc > 0) ok(kvd_prepare_cluster_select());
+  if (e == hipSuccess && c->Nc > 0) {
+    // no page belongs to a cluster until an index is built or announced (kvd_refresh_clusters)
+    ok(dev_alloc(&c->d_page_cluster, LU * c->NP));
+    if (e == hipSuccess) ok(hipMemset(c->d_page_cluster, 0xff, LU * c->NP * sizeof(int32_t)));
+  }
   if (e != hipSuccess) { free_ctx(c); return KVD_ERR_HIP; }
   const int r = reset_directory(c, -1);
   if (r != KVD_OK) { free_ctx(c); return r; }
@@ -322,6 +326,13 @@ int kvd_bind_tier(kvd_ctx* ctx, kvd_tier* tier) {
   }
   ctx->tier = tier;
   ctx->tier_pool_dev = static_cast<const char*>(dptr);
+  return KVD_OK;
+}
+
+int kvd_refresh_clusters(kvd_ctx* ctx, int32_t layer, void* stream) {
+  if (!ctx || layer < 0 || layer >= ctx->L) return KVD_ERR_ARG;
+  if (ctx->Nc == 0 || !ctx->cluster_start || !ctx->cluster_pages) return KVD_ERR_STATE;
+  HIP_TRY(ctx, kvd_launch_cluster_inverse(ctx, layer, static_cast<hipStream_t>(stream)));
   return KVD_OK;
 }
 

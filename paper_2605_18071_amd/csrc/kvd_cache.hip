@@ -28,8 +28,9 @@ struct ResolveArgs {
   int32_t* miss_list;        // [U][k][2]
   int32_t* miss_count;       // [U]
   unsigned long long* stats; // hits, misses, evictions
-  const float* scores;       // [U][NP] page scores of this step (lookahead eviction only)
-  int NP, Cmax, k, step, u0, lookahead;
+  const float* scores;       // [U][score_stride] scores of this step (lookahead eviction only)
+  const int32_t* page_cluster;  // [U][NP] or null: a page's score is its cluster's (hierarchical index)
+  int NP, Cmax, k, step, u0, lookahead, score_stride;
 };
 
 // One block per unit.
@@ -103,7 +104,10 @@ __global__ __launch_bounds__(kResolveThreads) void resolve_kernel(ResolveArgs a)
     if (p < 0 || ((hit_bitmap[s >> 5] >> (s & 31)) & 1u)) return false;
     if (a.lookahead) {
       // ascending in (score, -page): the lowest score leaves first, among equals the higher page
-      const u32 x = as_u32(a.scores[(size_t)u * a.NP + p] + 0.0f);
+      int at = p;
+      if (a.page_cluster != nullptr) at = a.page_cluster[(size_t)u * a.NP + p];
+      const float sc = at < 0 ? -INFINITY : a.scores[(size_t)u * a.score_stride + at];
+      const u32 x = as_u32(sc + 0.0f);
       const u32 asc = (x & 0x80000000u) ? ~x : (x | 0x80000000u);
       key = ((u64)asc << 32) | (u32)(~(u32)p);
     } else {
@@ -402,6 +406,8 @@ hipError_t kvd_launch_resolve(kvd_ctx* c, int layer, int step, const int32_t* se
   a.NP = c->NP; a.Cmax = c->Cmax; a.k = c->k; a.step = step; a.u0 = u0;
   a.lookahead = c->cfg.policy == KVD_EVICT_LOOKAHEAD ? 1 : 0;
   a.scores = c->last_scores;
+  a.page_cluster = c->Nc > 0 ? c->d_page_cluster + lu * c->NP : nullptr;
+  a.score_stride = c->Nc > 0 ? c->Nc : c->NP;
   hipLaunchKernelGGL(resolve_kernel, dim3(u1 - u0), dim3(kResolveThreads), 0, s, a);
   return hipGetLastError();
 }

@@ -364,6 +364,27 @@ __global__ __launch_bounds__(kClusterThreads) void cluster_select_kernel(const f
   for (int i = n_sel + tid; i < k; i += NT) out[i] = -1;
 }
 
+// page_cluster [NP] of unit blockIdx.x from its cluster lists: -1, then the cluster of every listed page.
+__global__ __launch_bounds__(kCsrThreads) void cluster_inverse_kernel(const int32_t* __restrict__ cluster_start,
+                                                                     const int32_t* __restrict__ cluster_pages,
+                                                                     int32_t* __restrict__ page_cluster, int NP, int Nc) {
+  const int u = blockIdx.x, tid = threadIdx.x;
+  const int32_t* start = cluster_start + (size_t)u * (Nc + 1);
+  const int32_t* pages = cluster_pages + (size_t)u * NP;
+  int32_t* pc = page_cluster + (size_t)u * NP;
+  for (int p = tid; p < NP; p += kCsrThreads) pc[p] = -1;
+  __syncthreads();
+  for (int c = tid; c < Nc; c += kCsrThreads) {
+    int b = start[c], e = start[c + 1];
+    b = b < 0 ? 0 : b;
+    e = e > NP ? NP : e;
+    for (int i = b; i < e; ++i) {
+      const int p = pages[i];
+      if (p >= 0 && p < NP) pc[p] = c;
+    }
+  }
+}
+
 }  // namespace kvd
 
 bool kvd_centroid_mode(const kvd_ctx* c) { return c->Nc > 0; }
@@ -381,6 +402,14 @@ hipError_t kvd_launch_cluster_select(kvd_ctx* c, int layer, const float* scores,
   hipLaunchKernelGGL(cluster_select_kernel, dim3(u1 - u0), dim3(kClusterThreads), sizeof(ClusterSelectSmem), s, scores,
                      c->cluster_start + lu * (c->Nc + 1), c->cluster_pages + lu * c->NP, sel_pages, c->d_seq_len, c->NP, c->Nc,
                      c->P, c->k, c->cfg.sink_pages, c->cfg.recent_pages, c->Hkv, u0);
+  return hipGetLastError();
+}
+
+hipError_t kvd_launch_cluster_inverse(kvd_ctx* c, int layer, hipStream_t s) {
+  using namespace kvd;
+  const size_t lu = (size_t)layer * c->U;
+  hipLaunchKernelGGL(cluster_inverse_kernel, dim3(c->U), dim3(kCsrThreads), 0, s, c->cluster_start + lu * (c->Nc + 1),
+                     c->cluster_pages + lu * c->NP, c->d_page_cluster + lu * c->NP, c->NP, c->Nc);
   return hipGetLastError();
 }
 
@@ -420,6 +449,7 @@ hipError_t kvd_run_build_centroids(kvd_ctx* c, int layer, int iterations, int32_
     KVD_DT(kmeans_store_kernel, per_centroid, dim3(kHeadDim), 0, s, cent64, cent, c->Nc);
 #undef KVD_DT
     if (e == hipSuccess) e = hipGetLastError();
+    if (e == hipSuccess) e = kvd_launch_cluster_inverse(c, layer, s);   // the page -> cluster table of the new lists
     const hipError_t e2 = hipStreamSynchronize(s);
     if (e == hipSuccess) e = e2;
   }

@@ -51,6 +51,7 @@ struct kvd_ctx {
   int32_t* d_slot_page;     // [L][U][Cmax] -1 = free
   int32_t* d_slot_stamp;    // [L][U][Cmax]
   int32_t* d_resident;      // [L][U]
+  int32_t* d_page_cluster;  // [L][U][NP] cluster of every page (-1 = none); hierarchical index only
   float* d_scores;          // [U][NP]
   const float* last_scores; // where the scores of the most recent scoring went (d_scores or the caller's buffer)
   int32_t* d_sel_pages;     // [U][k]
@@ -127,6 +128,7 @@ bool kvd_centroid_mode(const kvd_ctx* c);
 hipError_t kvd_prepare_cluster_select(void);
 hipError_t kvd_launch_cluster_select(kvd_ctx* c, int layer, const float* scores, int32_t* sel_pages, int u0, int u1,
                                      hipStream_t s);
+hipError_t kvd_launch_cluster_inverse(kvd_ctx* c, int layer, hipStream_t s);
 hipError_t kvd_run_build_centroids(kvd_ctx* c, int layer, int iterations, int32_t* assign_trace, hipStream_t s);
 hipError_t kvd_launch_append(kvd_ctx* c, int layer, const void* k_new, const void* v_new, hipStream_t s);
 hipError_t kvd_launch_advance(kvd_ctx* c, hipStream_t s);

@@ -41,8 +41,23 @@ struct FastArgs {
   char* pool;                 // slot pool of the layer, [U][Cmax] slots
   int NP, P, k, Cmax, sink, recent, Hkv, step, u0, do_gather, tiled;
   int lookahead;              // victims by lowest current-step score (needs `scores`) instead of by age
+  const int32_t* page_cluster;  // [U][NP] or null: the victims' scores are those of the pages' clusters
+  int score_stride;           // scores of unit u start at scores + u * score_stride (NP, or the number of centroids)
   unsigned page_bytes;
 };
+
+// This step's score of a resident page as lookahead eviction sees it: the page's own score, or with
+// the hierarchical index the score of its cluster (-inf for a page of no cluster: it leaves first).
+template <bool HANDOFF>
+__device__ __forceinline__ float victim_score(const FastArgs& a, int u, int page) {
+  int at = page;
+  if (a.page_cluster != nullptr) {
+    at = a.page_cluster[(size_t)u * a.NP + page];
+    if (at < 0) return -INFINITY;
+  }
+  const float* sc = a.scores + (size_t)u * a.score_stride + at;
+  return HANDOFF ? load_agent(sc) : *sc;
+}
 
 template <int NT>
 struct FastSmem {
@@ -258,10 +273,7 @@ __device__ __forceinline__ bool select_resolve_body(const FastArgs& a, int u, Fa
 #pragma unroll
     for (int j = 0; j < CPT; ++j) {
       vs[j] = 0.f;
-      if (a.lookahead && sp[j] >= 0) {
-        const float* sc = a.scores + (size_t)u * a.NP + sp[j];
-        vs[j] = HANDOFF ? load_agent(sc) : *sc;
-      }
+      if (a.lookahead && sp[j] >= 0) vs[j] = victim_score<HANDOFF>(a, u, sp[j]);
     }
   }
 
@@ -411,7 +423,7 @@ __device__ __forceinline__ bool select_resolve_body(const FastArgs& a, int u, Fa
     float lo = INFINITY, hi = -INFINITY;
 #pragma unroll
     for (int j = 0; j < CPT; ++j)
-      if ((cand_mask >> j) & 1u) {
+      if (((cand_mask >> j) & 1u) && vs[j] > -INFINITY) {   // (a page of no cluster scores -inf: bucket 0 whatever the range)
         lo = fminf(lo, vs[j]);
         hi = fmaxf(hi, vs[j]);
       }
@@ -443,8 +455,7 @@ __device__ __forceinline__ bool select_resolve_body(const FastArgs& a, int u, Fa
         const int p = spage[sl];
         if (p < 0 || ((sm.hit_bitmap[sl >> 5] >> (sl & 31)) & 1u)) return false;
         if (a.lookahead) {
-          const float* sc = a.scores + (size_t)u * a.NP + p;
-          const float v = HANDOFF ? load_agent(sc) : *sc;
+          const float v = victim_score<HANDOFF>(a, u, p);
           if (la_bucket(v) != bin) return false;
           kk = lookahead_victim_key(v, p);
           return true;

@@ -63,7 +63,7 @@ EXPORTS = [
     "kvd_create", "kvd_destroy", "kvd_strerror", "kvd_last_hip_error", "kvd_abi_version",
     "kvd_bind_summaries", "kvd_bind_host_store", "kvd_bind_slot_pool", "kvd_set_seq_lens",
     "kvd_build_summaries", "kvd_cache_reset", "kvd_cache_warm", "kvd_cache_export", "kvd_cache_import",
-    "kvd_bind_centroids", "kvd_build_centroids", "kvd_append_kv", "kvd_advance", "kvd_score_select", "kvd_cache_resolve", "kvd_sparse_decode_attn", "kvd_step", "kvd_step_trace",
+    "kvd_bind_centroids", "kvd_build_centroids", "kvd_refresh_clusters", "kvd_append_kv", "kvd_advance", "kvd_score_select", "kvd_cache_resolve", "kvd_sparse_decode_attn", "kvd_step", "kvd_step_trace",
     "kvd_set_profiling", "kvd_step_form", "kvd_set_step_form", "kvd_calibrate_step_form", "kvd_set_wait_limit_us", "kvd_step_timeline", "kvd_get_stats", "kvd_reset_stats",
     "kvd_tier_open", "kvd_tier_close", "kvd_tier_last_errno", "kvd_tier_set_layout", "kvd_tier_write_layer",
     "kvd_tier_fetch", "kvd_tier_trace", "kvd_tier_pooled", "kvd_tier_drop_pool", "kvd_tier_get_stats",
@@ -99,6 +99,7 @@ def load() -> C.CDLL:
         "kvd_cache_import": [vp, i32, i32p, i32p],
         "kvd_bind_centroids": [vp, vp, vp, vp],
         "kvd_build_centroids": [vp, i32, i32, vp, vp],
+        "kvd_refresh_clusters": [vp, i32, vp],
         "kvd_append_kv": [vp, i32, vp, vp, vp],
         "kvd_advance": [vp, vp],
         "kvd_score_select": [vp, i32, vp, vp, vp, vp],
@@ -258,6 +259,9 @@ class Kvd:
     def build_centroids(self, layer: int, iterations: int, assign_trace: Optional[torch.Tensor] = None, stream=None):
         self._check(self.lib.kvd_build_centroids(self.ctx, layer, iterations, _ptr(assign_trace), _stream_handle(stream)),
                     "kvd_build_centroids")
+
+    def refresh_clusters(self, layer: int, stream=None):
+        self._check(self.lib.kvd_refresh_clusters(self.ctx, layer, _stream_handle(stream)), "kvd_refresh_clusters")
 
     # ---- growth of the store
     def append_kv(self, layer: int, k_new: torch.Tensor, v_new: torch.Tensor, stream=None):

@@ -287,7 +287,7 @@ def compare_unit(rig: Rig, ou: OracleUnit, t: int, q_layer: torch.Tensor, rep: S
         # the oracle then continues from the GPU's choice
         used = set(int(p) for p in want["used"] if p >= 0)
         cands = [p for p in before if p not in used]
-        ok, msg = H.eviction_is_valid(o_scores, cands, g_ev, len(want["evicted"]))
+        ok, msg = H.eviction_is_valid(want["evict_scores"], cands, g_ev, len(want["evicted"]))
         assert ok, f"victims differ outside the tie band at unit {u} step {t}: {msg}"
         rep.victim_tie_divergences += 1
         ou.window.stamp = before

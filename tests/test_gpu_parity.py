@@ -609,6 +609,71 @@ def test_hierarchical_index_build_and_step_parity(cfg, mb, kw):
     rig.close()
 
 
+@pytest.mark.parametrize("cfg,mb,generic", [(3, 1, False), (3, 2, False), (5, 1, False), (2, 1, True)])
+def test_lookahead_eviction_under_the_hierarchical_index(cfg, mb, generic, monkeypatch):
+    """The paper's own combination: selection through the centroids, victims by the lowest
+    current-step score — here the score of the page's cluster.  Small windows, so that nearly every
+    step evicts; pages of one cluster tie exactly and leave higher page first."""
+    if generic:
+        monkeypatch.setenv("KVD_GENERIC_SELECT", "1")
+    w = _tight(cfg)
+    w = w.replace(index_centroids=w.n_pages // 4, index_iterations=2)
+    rig = R.Rig(w, micro_batches=mb)
+    units = all_units(rig)
+    rep = R.run_steps(rig, units, w.steps, check_dir_every=3, progress=f"cfg{cfg}-hier-lookahead-mb{mb}")
+    assert rep.unit_steps == w.steps * w.n_layers * w.units
+    assert rep.tie_divergences <= 2 and rep.victim_tie_divergences <= 4
+    assert rig.kvd.stats().evictions > w.n_layers * w.units
+    rig.close()
+
+
+def test_lookahead_with_cluster_lists_written_by_the_caller():
+    """The caller plants its own index (runs of 5 neighbouring pages, centroid = the run's first
+    summary; the last pages in no cluster at all) and announces it with kvd_refresh_clusters; the
+    lookahead victims must follow the planted clusters' scores, and a resident page of no cluster
+    must be the first to leave."""
+    w = small("hier-planted", ctx=16 * 203, topk_pages=20, capacity=26, heavy_count=0, policy="lookahead",
+              index_centroids=40, steps=8)
+    rig = R.Rig(w, build_index=False)
+    rig.kvd.build_summaries(0)
+    torch.cuda.synchronize()
+    NP, Nc, U = w.n_pages, w.index_centroids, w.units
+    runs = [list(range(5 * c, 5 * c + 5)) for c in range(Nc)]                    # pages 200..202 belong to no cluster
+    start = torch.tensor([5 * c for c in range(Nc + 1)], dtype=torch.int32)
+    pages = torch.full((NP,), -1, dtype=torch.int32)
+    pages[:5 * Nc] = torch.arange(5 * Nc, dtype=torch.int32)
+    rig.cluster_start[0].copy_(start.repeat(U, 1))
+    rig.cluster_pages[0].copy_(pages.repeat(U, 1))
+    rig.centroids[0].copy_(rig.summaries[0][:, :, 0:5 * Nc:5, :])
+    rig.kvd.refresh_clusters(0)
+    # pages 200 and 201 start out resident: they can only leave as victims
+    rig.kvd.cache_warm(0, [200, 201] * U, [2] * U)
+    units = []
+    for b in range(w.batch):
+        for h in range(w.n_kv_heads):
+            ou = R.OracleUnit.__new__(R.OracleUnit)
+            rig.hier = False                                                      # (no k-means to follow)
+            R.OracleUnit.__init__(ou, rig, 0, b, h)
+            rig.hier = True
+            ou.centroids = ou.summ[0:5 * Nc:5]
+            ou.members = [np.array(r, dtype=np.int32) for r in runs]
+            ou.window.warm([200, 201], stamp=-1)
+            units.append(ou)
+    rep = R.StepReport()
+    gone = {ou.u: set() for ou in units}
+    for t, q in enumerate(W.query_stream(w, rig.q0, w.steps, R.DEV)):
+        rig.step(0, t, q[0])
+        for ou in units:
+            gone[ou.u] |= set(R.compare_unit(rig, ou, t, q[0], rep)["evicted"])
+            # the clusterless pages go first: 201 with the first victim, 200 with the second
+            assert len(gone[ou.u]) < 1 or 201 in gone[ou.u]
+            assert len(gone[ou.u]) < 2 or 200 in gone[ou.u]
+    assert all(len(g) >= 2 for g in gone.values())
+    assert rep.tie_divergences <= 2 and rig.kvd.stats().evictions > 0
+    R.check_directory(rig, 0, units)
+    rig.close()
+
+
 def test_hierarchical_index_ragged_forced_and_duplicate_pages():
     """Sequences of different lengths (the index covers the valid pages only), sink and recent
     pages, more centroids than distinct summaries (exact distance ties, empty clusters), and the
@@ -654,12 +719,12 @@ def test_hierarchical_index_argument_errors():
     with pytest.raises(K.KvdError) as e:
         K.Kvd(index_centroids=65, **common)                           # more centroids than pages
     assert e.value.status == K.ERR_SHAPE
-    with pytest.raises(K.KvdError) as e:
-        K.Kvd(index_centroids=16, policy="lookahead", **common)       # lookahead eviction needs page scores
-    assert e.value.status == K.ERR_ARG
     k = K.Kvd(index_centroids=16, **common)
     with pytest.raises(K.KvdError) as e:
         k.build_centroids(0, 3)                                       # nothing bound yet
+    assert e.value.status == K.ERR_STATE
+    with pytest.raises(K.KvdError) as e:
+        k.refresh_clusters(0)
     assert e.value.status == K.ERR_STATE
     k.close()
     k = K.Kvd(**common)
