@@ -237,7 +237,10 @@ int kvd_refresh_clusters(kvd_ctx* ctx, int32_t layer, void* stream);
  * kvd_bind_host_store), into the page's slot if the page is resident, and the page's index entry
  * becomes the mean over its valid tokens including the new one.  seq_len does not change: call
  * kvd_advance once every layer has appended.  Enqueued on `stream`; order it after the layer's
- * kvd_step of this decode step and before the next one.
+ * kvd_step of this decode step and before the next one.  With a tier bound (kvd_bind_tier) the
+ * call then waits for `stream` and carries the token's two rows from the host store into the
+ * backing file and, where the page's extent is pooled, into the pool (the host store holds the
+ * growing pages; the file stays the full backing store).
  * KVD_ERR_SHAPE when a sequence already fills max_pages * page_size tokens; KVD_ERR_STATE when
  * buffers are not bound or physical_layers < n_layers (layers sharing a stored layer cannot append). */
 int kvd_append_kv(kvd_ctx* ctx, int32_t layer, const void* k_new, const void* v_new, void* stream);
@@ -332,6 +335,11 @@ int kvd_tier_set_layout(kvd_tier* tier, int32_t layer, const int32_t* host_posit
  * store's order, to their places in the file (buffered writes, then fsync) and drops that layer's
  * extents from the pool. */
 int kvd_tier_write_layer(kvd_tier* tier, int32_t layer, const void* host_pages);
+/* Growth helper: overwrites nbytes at offset_in_page of one page with host_src, in the file
+ * (buffered write; later reads of the file see it) and in the pool's copy if the page's extent is
+ * pooled.  offset_in_page + nbytes <= page_bytes. */
+int kvd_tier_patch_page(kvd_tier* tier, int32_t layer, int32_t unit, int32_t page, int64_t offset_in_page,
+                        const void* host_src, int64_t nbytes);
 /* One step of one physical layer.  host_miss_list [U][k][2] (page, slot) and host_miss_count [U] are
  * the GPU window's misses as the resolve stage leaves them (entries with slot < 0 are skipped).
  * On return every needed extent is in the pool and host_src_offset [U][k] holds, for entry j < count

@@ -346,6 +346,7 @@ int kvd_bind_host_store(kvd_ctx* ctx, const void* pinned_store) {
     return KVD_ERR_ARG;
   }
   ctx->store_dev = static_cast<const char*>(dptr);
+  ctx->store_host = static_cast<const char*>(pinned_store);
   return KVD_OK;
 }
 
@@ -379,6 +380,22 @@ int kvd_append_kv(kvd_ctx* ctx, int32_t layer, const void* k_new, const void* v_
   for (int b = 0; b < ctx->B; ++b)
     if ((long long)ctx->h_seq_len[b] >= (long long)ctx->NP * ctx->P) return KVD_ERR_SHAPE;
   HIP_TRY(ctx, kvd_launch_append(ctx, layer, k_new, v_new, static_cast<hipStream_t>(stream)));
+  if (ctx->tier != nullptr) {
+    // the backing file (and the pool's copy) must hold the token too: carry its K row and V row over
+    // from the host store, which the kernel has just written
+    HIP_TRY(ctx, hipStreamSynchronize(static_cast<hipStream_t>(stream)));
+    const size_t row = (size_t)ctx->D * 2;
+    for (int u = 0; u < ctx->U; ++u) {
+      const int t = ctx->h_seq_len[u / ctx->Hkv];
+      const int page = t / ctx->P, r = t % ctx->P;
+      const char* pg = ctx->store_host + (((size_t)layer * ctx->U + u) * ctx->NP + page) * ctx->page_bytes;
+      int rc = kvd_tier_patch_page(ctx->tier, layer, u, page, (int64_t)r * row, pg + (size_t)r * row, (int64_t)row);
+      if (rc == KVD_OK)
+        rc = kvd_tier_patch_page(ctx->tier, layer, u, page, (int64_t)(ctx->P + r) * row, pg + (size_t)(ctx->P + r) * row,
+                                 (int64_t)row);
+      if (rc != KVD_OK) return rc;
+    }
+  }
   return KVD_OK;
 }
 

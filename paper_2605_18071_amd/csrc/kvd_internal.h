@@ -42,6 +42,7 @@ struct kvd_ctx {
   int32_t* cluster_start;   // [L][U][Nc+1]
   int32_t* cluster_pages;   // [L][U][NP] pages of every cluster, ascending
   const char* store_dev;    // device-visible address of the pinned host store
+  const char* store_host;   // the same store as the host addresses it
   char* pool;
 
   // owned, device

@@ -321,6 +321,28 @@ int kvd_tier_write_layer(kvd_tier* t, int32_t layer, const void* host_pages) {
   return KVD_OK;
 }
 
+int kvd_tier_patch_page(kvd_tier* t, int32_t layer, int32_t unit, int32_t page, int64_t offset_in_page,
+                        const void* host_src, int64_t nbytes) {
+  if (!t || !host_src || layer < 0 || layer >= t->cfg.n_layers || unit < 0 || unit >= t->cfg.n_units || page < 0 ||
+      page >= t->cfg.max_pages || offset_in_page < 0 || nbytes < 0 || offset_in_page + nbytes > t->cfg.page_bytes)
+    return KVD_ERR_ARG;
+  const int U = t->cfg.n_units, NP = t->cfg.max_pages, E = t->cfg.extent_pages;
+  const int32_t place = t->position[((size_t)layer * U + unit) * NP + page];
+  const int64_t x = ((int64_t)layer * U + unit) * t->NE + place / E;
+  const int64_t in_extent = (int64_t)(place % E) * t->cfg.page_bytes + offset_in_page;
+  const char* src = static_cast<const char*>(host_src);
+  int64_t done = 0;
+  while (done < nbytes) {
+    const ssize_t w = pwrite(t->wfd, src + done, (size_t)(nbytes - done), (off_t)(x * (int64_t)t->extent_bytes + in_extent + done));
+    if (w < 0 && errno == EINTR) continue;
+    if (w <= 0) { t->last_errno = w < 0 ? errno : EIO; return KVD_ERR_STATE; }
+    done += w;
+  }
+  const int32_t slot = t->ext_slot[x];
+  if (slot >= 0) memcpy(t->pool + (size_t)slot * t->extent_bytes + in_extent, src, (size_t)nbytes);
+  return KVD_OK;
+}
+
 int kvd_tier_fetch(kvd_tier* t, int32_t layer, int32_t step, const int32_t* miss_list, const int32_t* miss_count,
                    int32_t k, int64_t* src_offset) {
   if (!t || !miss_list || !miss_count || !src_offset || layer < 0 || layer >= t->cfg.n_layers || k < 1) return KVD_ERR_ARG;

@@ -66,7 +66,7 @@ EXPORTS = [
     "kvd_bind_centroids", "kvd_build_centroids", "kvd_refresh_clusters", "kvd_append_kv", "kvd_advance", "kvd_score_select", "kvd_cache_resolve", "kvd_sparse_decode_attn", "kvd_step", "kvd_step_trace",
     "kvd_set_profiling", "kvd_step_form", "kvd_set_step_form", "kvd_calibrate_step_form", "kvd_set_wait_limit_us", "kvd_step_timeline", "kvd_get_stats", "kvd_reset_stats",
     "kvd_tier_open", "kvd_tier_close", "kvd_tier_last_errno", "kvd_tier_set_layout", "kvd_tier_write_layer",
-    "kvd_tier_fetch", "kvd_tier_trace", "kvd_tier_pooled", "kvd_tier_drop_pool", "kvd_tier_get_stats",
+    "kvd_tier_patch_page", "kvd_tier_fetch", "kvd_tier_trace", "kvd_tier_pooled", "kvd_tier_drop_pool", "kvd_tier_get_stats",
     "kvd_tier_reset_stats", "kvd_tier_sequential_read_gbps", "kvd_layout_from_clusters", "kvd_bind_tier",
     "kvd_step_tiered",
 ]
@@ -120,6 +120,7 @@ def load() -> C.CDLL:
         "kvd_tier_last_errno": [vp],
         "kvd_tier_set_layout": [vp, i32, vp],
         "kvd_tier_write_layer": [vp, i32, vp],
+        "kvd_tier_patch_page": [vp, i32, i32, i32, C.c_int64, vp, C.c_int64],
         "kvd_tier_fetch": [vp, i32, i32, vp, vp, i32, vp],
         "kvd_tier_trace": [vp, vp, vp, C.c_int64, vp, C.c_int64],
         "kvd_tier_pooled": [vp, vp, C.c_int64, C.POINTER(C.c_int64)],
@@ -394,6 +395,11 @@ class KvdTier:
 
     def write_layer(self, layer: int, host_pages: torch.Tensor):
         self._check(self.lib.kvd_tier_write_layer(self.handle, layer, host_pages.data_ptr()), "kvd_tier_write_layer")
+
+    def patch_page(self, layer: int, unit: int, page: int, offset_in_page: int, src: torch.Tensor):
+        src = src.contiguous()
+        self._check(self.lib.kvd_tier_patch_page(self.handle, layer, unit, page, offset_in_page, src.data_ptr(),
+                                                 src.numel() * src.element_size()), "kvd_tier_patch_page")
 
     def fetch(self, layer: int, step: int, miss_list: torch.Tensor, miss_count: torch.Tensor) -> torch.Tensor:
         """miss_list [U, k, 2] int32, miss_count [U] int32 (CPU) -> byte offsets into the pool, [U, k] int64."""

@@ -134,3 +134,61 @@ def test_tiered_step_equals_plain_step_and_reports_errors(tmp_path):
     unpinned.close()
     for r in (plain, tiered, small_pool):
         r.close()
+
+
+def test_append_kv_reaches_the_backing_file_and_the_pool(tmp_path):
+    """Tokens appended during decoding must arrive in the backing file and in pooled extents: half
+    way through, the GPU window and the DRAM pool are emptied, so that every page a step attends —
+    the grown ones included (they are forced into the selection) — comes from the file."""
+    w = small("tier-append", recent_pages=2, topk_pages=20, capacity=40, steps=14)
+    P = w.page
+    seq = [w.ctx - 2 * P - 5, w.ctx - 3 * P]
+    rig = R.Rig(w, seq_lens=seq, micro_batches=1)
+    units = all_units(rig)
+    rig.attach_tier(str(tmp_path / "kv.bin"), extent_pages=4, pool_extents=4000)
+    rig.kvd.bind_host_store(rig.store)                               # the growing pages live in the host store
+    gen = torch.Generator(device="cpu").manual_seed(7)
+    rep = R.StepReport()
+    qs = W.query_stream(w, rig.q0, w.steps, R.DEV)
+    for t in range(w.steps):
+        q = next(qs)
+        if t == w.steps // 2:
+            rig.kvd.cache_reset()
+            rig.tier.drop_pool()
+            for ou in units:
+                ou.window = type(ou.window)(ou.window.capacity)
+        rig.step(0, t, q[0])
+        for ou in units:
+            R.compare_unit(rig, ou, t, q[0], rep)
+        if t == w.steps // 2:
+            assert rig.tier.trace()["hits"] == 0 and rig.tier.trace()["reads"] > 0
+        k_new = torch.randn((w.batch, w.n_kv_heads, w.head_dim), generator=gen).to(w.torch_dtype)
+        v_new = torch.randn((w.batch, w.n_kv_heads, w.head_dim), generator=gen).to(w.torch_dtype)
+        rig.kvd.append_kv(0, k_new.to(R.DEV), v_new.to(R.DEV))
+        rig.kvd.advance()
+        torch.cuda.synchronize()
+        for ou in units:
+            pos = ou.seq_len
+            ou.keys[pos] = H.f64(k_new[ou.b, ou.h])
+            ou.values[pos] = H.f64(v_new[ou.b, ou.h])
+            ou.seq_len = pos + 1
+            ou.summ = orc.page_summaries(ou.keys, P, ou.seq_len, ou.code)
+        rig.seq_lens = [s + 1 for s in rig.seq_lens]
+        if t % 5 == 0 or t == w.steps - 1:
+            R.check_directory(rig, 0, units)
+    assert rep.tie_divergences <= 2 and rep.unit_steps == w.steps * w.units
+    # the file itself: every page that grew, read back through a fresh pool
+    rig.tier.drop_pool()
+    for ou in units:
+        grown = sorted({p for p in range(seq[ou.b] // P, (seq[ou.b] + w.steps - 1) // P + 1)})
+        lst = torch.full((w.units, w.topk_pages, 2), -1, dtype=torch.int32)
+        cnt = torch.zeros(w.units, dtype=torch.int32)
+        for j, p in enumerate(grown):
+            lst[ou.u, j, 0], lst[ou.u, j, 1] = p, 0
+        cnt[ou.u] = len(grown)
+        off = rig.tier.fetch(0, 1000 + ou.u, lst, cnt)
+        for j, p in enumerate(grown):
+            o = int(off[ou.u, j])
+            got = rig.tier_pool[o:o + w.page_bytes].view(torch.int16)
+            assert torch.equal(got, rig.store[0, ou.b, ou.h, p].view(torch.int16).reshape(-1)), (ou.u, p)
+    rig.close()

@@ -194,3 +194,28 @@ def test_sequential_read_covers_the_file(tmp_path):
         tier.sequential_read_gbps()
     assert e.value.status == kvd.ERR_CAPACITY
     tier.close()
+
+
+def test_patch_page_reaches_file_and_pool(tmp_path):
+    pages = RNG.integers(0, 256, size=(1, 2, 12, 4096), dtype=np.uint8)
+    positions = [[orc.extent_positions(12, [np.array([7, 1, 3]), np.array([0, 2, 4, 5, 6, 8, 9, 10, 11])]), orc.extent_positions(12)]]
+    for direct in (False, True):
+        tier, pool = _open(tmp_path, pages, positions, E=2, pool_extents=4, max_run=2, direct=direct, name=f"p{int(direct)}.bin")
+        ot = orc.ExtentTier(2, 12, 2, 4, 2)
+        _check_step(tier, pool, ot, 0, 0, [[1], [5]], positions, pages, 4)           # page 1 of unit 0 is pooled now
+        new = RNG.integers(0, 256, size=300, dtype=np.uint8)
+        for u, p, at in [(0, 1, 100), (0, 9, 0), (1, 5, 3796)]:                       # pooled, not pooled, pooled (end of page)
+            tier.patch_page(0, u, p, at, torch.from_numpy(new.copy()))
+            pages[0, u, p, at:at + 300] = new
+        _check_step(tier, pool, ot, 0, 1, [[1, 9], [5]], positions, pages, 4)        # pooled copies and the file agree
+        tier.drop_pool()
+        ot.stamp.clear()
+        _check_step(tier, pool, ot, 0, 2, [[1, 9, 3], [5, 4]], positions, pages, 4)  # and so does a fresh read
+        with pytest.raises(kvd.KvdError) as e:
+            tier.patch_page(0, 0, 1, 4000, torch.from_numpy(new.copy()))             # runs over the end of the page
+        assert e.value.status == kvd.ERR_ARG
+        tier.close()
+    # the file image is the oracle's
+    image = orc.extent_file_image(pages[0], positions[0], 2)
+    raw = np.fromfile(str(tmp_path / "p1.bin"), dtype=np.uint8).reshape(image.shape)   # (the file of the last round)
+    assert np.array_equal(raw, image)
