@@ -293,6 +293,10 @@ def main() -> int:
         ctx.bind_tier(None)
         tier.close()
         os.unlink(args.tier)
+    props = torch.cuda.get_device_properties(0)
+    result["config"]["device"] = {"name": props.name, "compute_units": props.multi_processor_count,
+                                  "hbm_GiB": round(props.total_memory / 2**30, 1),
+                                  "max_clock_MHz": getattr(props, "clock_rate", 0) / 1e3}
     if w.index_centroids > 0:
         result["config"]["index"] = {"centroids": w.index_centroids, "kmeans_rounds": w.index_iterations,
                                      "build_s": round(t_index, 3)}
