@@ -254,8 +254,13 @@ __global__ __launch_bounds__(kClusterThreads) void cluster_select_kernel(const f
     if (c < Nc) {
       s[j] = sc[c];
       const int b = start[c], e = start[c + 1];
-      mb[j] = lower_bound_pages(pages, b, e, lo);
-      size[j] = lower_bound_pages(pages, mb[j], e, hi) - mb[j];
+      if (n_forced == 0) {                              // no forced pages: every listed page counts
+        mb[j] = b;
+        size[j] = e - b;
+      } else {
+        mb[j] = lower_bound_pages(pages, b, e, lo);
+        size[j] = lower_bound_pages(pages, mb[j], e, hi) - mb[j];
+      }
       if (size[j] > 0) { fmin = fminf(fmin, s[j]); fmax = fmaxf(fmax, s[j]); }
     }
   }
