@@ -215,24 +215,32 @@ __device__ __forceinline__ bool select_resolve_body(const FastArgs& a, int u, Fa
     C = a.capacity[u];
     R = a.resident[u];
   }
-  const int p0 = tid * IPT;
+  // Page ownership: a wave owns 64 * IPT consecutive pages; its q-th 16-byte load covers 256 of
+  // them (1 KiB contiguous), lane l taking four.  Item j of a lane is page_of(j).
+  static_assert(IPT % 4 == 0, "four consecutive pages per load");
+  const int wave_p0 = w * (kWave * IPT);
+  auto page_of = [&](int j) -> int { return wave_p0 + (j >> 2) * (4 * kWave) + 4 * lane + (j & 3); };
   float s[IPT];
   int seq = 0;
   auto load_scores = [&]() {
     const float* sc = a.scores + (size_t)u * a.NP;
-    if (HANDOFF) {
-#pragma unroll
-      for (int j = 0; j < IPT; ++j) s[j] = (p0 + j) < a.NP ? load_agent(sc + p0 + j) : 0.f;
-    } else if ((a.NP & 3) == 0) {
+    if ((a.NP & 3) == 0) {
+      // bounds-checked by the buffer descriptor: pages beyond NP read as 0 and are never valid
+      const __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(sc), 0, a.NP * 4, 0x00020000);
 #pragma unroll
       for (int q4 = 0; q4 < IPT / 4; ++q4) {
-        float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
-        if (p0 + 4 * q4 < a.NP) v = *reinterpret_cast<const float4*>(sc + p0 + 4 * q4);
-        s[4 * q4] = v.x; s[4 * q4 + 1] = v.y; s[4 * q4 + 2] = v.z; s[4 * q4 + 3] = v.w;
+        const int off = page_of(4 * q4) * 4;
+        // HANDOFF: device-scope load (the scores come from other workgroups of this launch)
+        const u32x4_t v = HANDOFF ? __builtin_amdgcn_raw_buffer_load_b128(rs, off, 0, 16)
+                                  : __builtin_amdgcn_raw_buffer_load_b128(rs, off, 0, 0);
+        s[4 * q4] = as_f32(v.x); s[4 * q4 + 1] = as_f32(v.y); s[4 * q4 + 2] = as_f32(v.z); s[4 * q4 + 3] = as_f32(v.w);
       }
     } else {
 #pragma unroll
-      for (int j = 0; j < IPT; ++j) s[j] = (p0 + j) < a.NP ? sc[p0 + j] : 0.f;
+      for (int j = 0; j < IPT; ++j) {
+        const int p = page_of(j);
+        s[j] = p < a.NP ? (HANDOFF ? load_agent(sc + p) : sc[p]) : 0.f;
+      }
     }
   };
   if (DO_SELECT) {
@@ -287,7 +295,7 @@ __device__ __forceinline__ bool select_resolve_body(const FastArgs& a, int u, Fa
     int n_forced = 0;
 #pragma unroll
     for (int j = 0; j < IPT; ++j) {
-      const int p = p0 + j;
+      const int p = page_of(j);
       const bool valid = p < n_valid;
       const bool forced = valid && (p < a.sink || p >= recent_from);
       if (valid && !forced) {
@@ -314,8 +322,8 @@ __device__ __forceinline__ bool select_resolve_body(const FastArgs& a, int u, Fa
     const float inv = range > 0.f ? 2047.0f / range : 0.f;
     auto bucket_of = [&](float v) -> int { return (int)fminf(fmaxf((fmax - v) * inv, 0.f), 2047.f); };
     auto is_free = [&](int p) -> bool { return p < n_valid && !(p < a.sink || p >= recent_from); };
-    auto key_of = [&](int j) -> u64 { return ((u64)fast_descending_key(s[j]) << 32) | (u32)(p0 + j); };
-    auto bkt_of = [&](int j) -> int { return is_free(p0 + j) ? bucket_of(s[j]) : -1; };
+    auto key_of = [&](int j) -> u64 { return ((u64)fast_descending_key(s[j]) << 32) | (u32)page_of(j); };
+    auto bkt_of = [&](int j) -> int { return is_free(page_of(j)) ? bucket_of(s[j]) : -1; };
     u64 thr = 0;
     if (k_free > 0) {
       const float* sc = a.scores + (size_t)u * a.NP;
@@ -331,29 +339,47 @@ __device__ __forceinline__ bool select_resolve_body(const FastArgs& a, int u, Fa
       };
       thr = two_level_select<NT, IPT>(key_of, bkt_of, k_free, sm, flip, refine);
     }
+    // output in ascending page order = (wave, load, lane, element): one block scan over the
+    // lanes' totals gives the wave's first position, wave scans per load give the rest
+    u32 take = 0;                                      // bit j: page_of(j) is selected
+    int cnt4[IPT / 4];
     int cnt = 0;
-    u32 take = 0;                                      // bit j: page p0 + j is selected
 #pragma unroll
-    for (int j = 0; j < IPT; ++j) {
-      const int p = p0 + j;
-      const bool valid = p < n_valid;
-      const bool forced = valid && (p < a.sink || p >= recent_from);
-      const bool t = forced || (is_free(p) && k_free > 0 && key_of(j) <= thr);
-      take |= t ? (1u << j) : 0u;
-      cnt += t ? 1 : 0;
+    for (int q4 = 0; q4 < IPT / 4; ++q4) {
+      cnt4[q4] = 0;
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const int j = 4 * q4 + e;
+        const int p = page_of(j);
+        const bool valid = p < n_valid;
+        const bool forced = valid && (p < a.sink || p >= recent_from);
+        const bool t = forced || (is_free(p) && k_free > 0 && key_of(j) <= thr);
+        take |= t ? (1u << j) : 0u;
+        cnt4[q4] += t ? 1 : 0;
+      }
+      cnt += cnt4[q4];
     }
     int total;
-    int pos = fast_scan<NT>(cnt, sm, flip, total);
+    const int lane_pos = fast_scan<NT>(cnt, sm, flip, total);
+    int pos_q = __builtin_amdgcn_readfirstlane(lane_pos);   // lane 0: what the waves before this one selected
     int32_t* out = a.sel_pages + (size_t)u * k;
 #pragma unroll
-    for (int j = 0; j < IPT; ++j) {
-      if ((take >> j) & 1u) {
-        if (pos < k) {
-          sm.sel[pos] = (uint16_t)(p0 + j);
-          if (HANDOFF) store_agent(out + pos, p0 + j);
-          else out[pos] = p0 + j;
+    for (int q4 = 0; q4 < IPT / 4; ++q4) {
+      const int inc = wave_inclusive_scan(cnt4[q4]);
+      int pos = pos_q + inc - cnt4[q4];
+      pos_q += __builtin_amdgcn_readlane(inc, kWave - 1);
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const int j = 4 * q4 + e;
+        if ((take >> j) & 1u) {
+          if (pos < k) {
+            const int p = page_of(j);
+            sm.sel[pos] = (uint16_t)p;
+            if (HANDOFF) store_agent(out + pos, p);
+            else out[pos] = p;
+          }
+          ++pos;
         }
-        ++pos;
       }
     }
     for (int i = k_eff + tid; i < k; i += NT) {
@@ -408,6 +434,18 @@ __device__ __forceinline__ bool select_resolve_body(const FastArgs& a, int u, Fa
   const int m = mh & 0xffff, n_hits = mh >> 16;
   int miss_rank = packed_rank & 0xffff;
   const int e = (R + m - C) > 0 ? (R + m - C) : 0;
+  if (m == 0) {
+    // every selected page is resident: no slot to find, nothing leaves, nothing to fetch
+    for (int j = tid; j < k; j += NT) evout[j] = -1;
+    if (tid == 0) {
+      a.miss_count[u] = 0;
+      a.counts[u * 3 + 0] = n_hits;
+      a.counts[u * 3 + 1] = 0;
+      a.counts[u * 3 + 2] = 0;
+      atomicAdd(&a.stats[0], (unsigned long long)n_hits);
+    }
+    return true;
+  }
 
   // ---- victims: the e smallest (stamp, page) among resident slots that were not hit
   auto is_cand = [&](int j) -> bool {
