@@ -293,6 +293,21 @@ SCALED = {
 
 
 @pytest.mark.parametrize("mb", [-1, 1], ids=["single-launch", "kernel-chain"])
+@pytest.mark.parametrize("n_pages", [77, 1031, 2050])
+def test_step_parity_page_counts_off_the_load_width(n_pages, mb):
+    """Page counts that are not a multiple of the selection's 4-page loads (77, 1031) or of a
+    wave's 256-page block (2050), with ragged sequences: every thread's last pages are padding."""
+    w = small("odd", ctx=16 * n_pages, topk_pages=min(40, n_pages // 2), capacity=max(48, n_pages // 8), steps=5,
+              sink_pages=1, recent_pages=3)
+    rig = R.Rig(w, seq_lens=[w.ctx - 7, w.ctx - 16 * 5 - 1], micro_batches=mb)
+    units = all_units(rig)
+    rep = R.run_steps(rig, units, w.steps, check_dir_every=2, progress=f"np{n_pages}-mb{mb}")
+    assert rep.unit_steps == w.steps * w.units
+    assert rep.tie_divergences <= 2
+    rig.close()
+
+
+@pytest.mark.parametrize("mb", [-1, 1], ids=["single-launch", "kernel-chain"])
 @pytest.mark.parametrize("cfg", [1, 2, 3, 4, 5])
 def test_step_parity_scaled_configs(cfg, mb):
     """micro_batches=-1 runs the layer-step as one launch, 1 as a chain of separate kernels."""
