@@ -93,6 +93,20 @@ def cpu_baseline(w, store, q_list, seconds: float):
     }
 
 
+def _max_clock_mhz():
+    """Peak engine clock from the HIP runtime that torch has already loaded (torch does not expose it)."""
+    import ctypes
+    try:
+        hip = ctypes.CDLL("libamdhip64.so")
+        khz = ctypes.c_int(0)
+        hip_device_attribute_clock_rate = 5                        # hipDeviceAttributeClockRate
+        if hip.hipDeviceGetAttribute(ctypes.byref(khz), hip_device_attribute_clock_rate, 0) == 0:
+            return khz.value / 1e3
+    except OSError:
+        pass
+    return None
+
+
 def step_timeline(ctx, t, q, out, stream):
     """One more all-hit step of the single-launch kernel with its per-workgroup clock readings on:
     when each role's workgroups were dispatched, how long they waited for their inputs, how long
@@ -294,9 +308,9 @@ def main() -> int:
         tier.close()
         os.unlink(args.tier)
     props = torch.cuda.get_device_properties(0)
-    result["config"]["device"] = {"name": props.name, "compute_units": props.multi_processor_count,
-                                  "hbm_GiB": round(props.total_memory / 2**30, 1),
-                                  "max_clock_MHz": getattr(props, "clock_rate", 0) / 1e3}
+    result["config"]["device"] = {"name": props.name, "arch": getattr(props, "gcnArchName", ""),
+                                  "compute_units": props.multi_processor_count,
+                                  "hbm_GiB": round(props.total_memory / 2**30, 1), "max_clock_MHz": _max_clock_mhz()}
     if w.index_centroids > 0:
         result["config"]["index"] = {"centroids": w.index_centroids, "kmeans_rounds": w.index_iterations,
                                      "build_s": round(t_index, 3)}
