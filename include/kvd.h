@@ -83,8 +83,8 @@ typedef struct {
                               l % physical_layers.  0 means n_layers. */
   int32_t micro_batches;   /* how kvd_step overlaps selection, fetch and attention ("SFC Disaggregation"):
                               -1 = the whole step as one launch in which every (sequence, KV head) unit
-                                   moves through the stages on its own, synchronised by flags in
-                                   device memory (needs page_size % 16 == 0, max_pages <= 16384,
+                                   moves through the stages on its own, synchronised by counters and
+                                   published words in device memory (needs page_size % 16 == 0, max_pages <= 16384,
                                    capacity_max <= 4096; other shapes run as for 1);
                               0  = chosen by the library: the one launch where it is the faster form
                                    (max_pages <= 8192 and at least 32 units), else as for 1;
@@ -414,13 +414,14 @@ int kvd_calibrate_step_form(kvd_ctx* ctx, int32_t layer, int32_t first_step, con
                             int32_t steps_per_form, float* out, void* stream, int32_t* chosen_form,
                             float* ms_per_step);
 /* Bound of every wait inside the one-launch kvd_step (micro_batches = -1), where workgroups wait on
- * flags in device memory for the workgroups before them.  Default 2 s.  A wait that runs out makes
+ * counters and published words in device memory that the workgroups before them write.  Default 2 s.  A wait that runs out makes
  * its workgroup leave without output and raises a sticky error: kvd_get_stats and later kvd_step
  * calls return KVD_ERR_STATE until kvd_cache_reset.  (A limit of 0 lets tests reach that path.) */
 int kvd_set_wait_limit_us(kvd_ctx* ctx, int64_t microseconds);
 /* Timeline of the last single-launch kvd_step recorded under profiling mode 2.  Synchronises the
  * device.  host_records [capacity][5] receives, for workgroup i < min(capacity, *n_workgroups) in
- * dispatch order, the clock at: start, end of its wait for its inputs, end of its work, exit; and
+ * dispatch order, the clock at: start, end of its wait for its inputs (a unit's scores; the entries
+ * of an attention split, which are there once its pages are resident), end of its work, exit; and
  * a tag: bits 0-7 the role (0 scoring, 1 selection + directory + fetch, 2 attention), bits 8-31
  * the unit (0 for scoring workgroups, which serve all units in turn), bits 32-63 the number of the
  * scoring workgroup or the attention split.  KVD_ERR_STATE if the step does not

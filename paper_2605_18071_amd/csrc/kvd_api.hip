@@ -69,7 +69,7 @@ static void free_ctx(kvd_ctx* c) {
   void* dev[] = {c->d_capacity, c->d_seq_len, c->d_page_to_slot, c->d_slot_page, c->d_slot_stamp, c->d_resident, c->d_page_cluster,
                  c->d_scores, c->d_sel_pages, c->d_sel_slots, c->d_hit_mask, c->d_evicted, c->d_counts,
                  c->d_miss_list, c->d_miss_count, c->d_part_acc, c->d_part_ml, c->d_attn_ticket, c->d_stats,
-                 c->d_score_done, c->d_sel_ready, c->d_timeline};
+                 c->d_score_done, c->d_sel_entry, c->d_timeline};
   for (void* p : dev)
     if (p) (void)hipFree(p);
   for (int i = 0; i < KVD_MAX_MICRO; ++i) {
@@ -222,7 +222,7 @@ int kvd_create(const kvd_config* cfg, kvd_ctx** out) {
       ok(dev_alloc(&c->d_part_acc, (size_t)c->U * Smax * c->G * c->D)) &&
       ok(dev_alloc(&c->d_part_ml, (size_t)c->U * Smax * c->G * 2)) && ok(dev_alloc(&c->d_stats, 4)) &&
       ok(dev_alloc(&c->d_attn_ticket, (size_t)c->U)) && ok(dev_alloc(&c->d_score_done, (size_t)c->U * 32)) &&
-      ok(dev_alloc(&c->d_sel_ready, (size_t)c->U * 32)) && ok(dev_alloc(&c->d_timeline, (size_t)KVD_TIMELINE_MAX * 5)) &&
+      ok(dev_alloc(&c->d_sel_entry, Uk)) && ok(dev_alloc(&c->d_timeline, (size_t)KVD_TIMELINE_MAX * 5)) &&
       ok(hipHostMalloc(reinterpret_cast<void**>(&c->error_host), sizeof(int32_t), hipHostMallocMapped)) &&
       ok(hipHostGetDevicePointer(reinterpret_cast<void**>(&c->error_dev), c->error_host, 0)) &&
       ok(hipEventCreateWithFlags(&c->ev_fork, hipEventDisableTiming));
@@ -234,7 +234,7 @@ int kvd_create(const kvd_config* cfg, kvd_ctx** out) {
   if (e == hipSuccess) ok(hipMemset(c->d_miss_count, 0, (size_t)c->U * sizeof(int32_t)));
   if (e == hipSuccess) ok(hipMemset(c->d_attn_ticket, 0, (size_t)c->U * sizeof(int32_t)));
   if (e == hipSuccess) ok(hipMemset(c->d_score_done, 0, (size_t)c->U * 32 * sizeof(int32_t)));
-  if (e == hipSuccess) ok(hipMemset(c->d_sel_ready, 0, (size_t)c->U * 32 * sizeof(int32_t)));
+  if (e == hipSuccess) ok(hipMemset(c->d_sel_entry, 0, Uk * sizeof(unsigned long long)));
   if (e == hipSuccess) *c->error_host = 0;
   if (e == hipSuccess) c->single_launch = kvd_wants_single_launch(c);
   if (e == hipSuccess && c->Nc > 0) ok(kvd_prepare_cluster_select());
@@ -413,7 +413,7 @@ int kvd_cache_reset(kvd_ctx* ctx) {
   HIP_TRY(ctx, hipDeviceSynchronize());
   HIP_TRY(ctx, hipMemset(ctx->d_attn_ticket, 0, (size_t)ctx->U * sizeof(int32_t)));
   HIP_TRY(ctx, hipMemset(ctx->d_score_done, 0, (size_t)ctx->U * 32 * sizeof(int32_t)));
-  HIP_TRY(ctx, hipMemset(ctx->d_sel_ready, 0, (size_t)ctx->U * 32 * sizeof(int32_t)));
+  HIP_TRY(ctx, hipMemset(ctx->d_sel_entry, 0, (size_t)ctx->U * ctx->k * sizeof(unsigned long long)));
   *ctx->error_host = 0;
   return reset_directory(ctx, -1);
 }

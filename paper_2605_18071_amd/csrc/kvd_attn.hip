@@ -199,6 +199,9 @@ kvd::AttnArgs kvd_attn_args(kvd_ctx* c, int layer, const void* q, const int32_t*
   a.pool = c->pool + (size_t)layer * c->U * c->Cmax * c->page_bytes;
   a.sel_pages = sel_pages;
   a.sel_slots = sel_slots;
+  a.sel_entry = nullptr;                               // (only the one-launch step hands the selection over in entries)
+  a.error = c->error_dev;
+  a.wait_limit = c->wait_limit_ticks;
   a.seq_len = c->d_seq_len;
   a.part_acc = c->d_part_acc;
   a.part_ml = c->d_part_ml;

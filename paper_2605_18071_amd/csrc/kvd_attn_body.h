@@ -20,6 +20,9 @@ struct AttnArgs {
   const char* pool;          // [U][Cmax] slots of the layer
   const int32_t* sel_pages;  // [U][k]
   const int32_t* sel_slots;  // [U][k]
+  u64* sel_entry;            // [U][k]: what a HANDOFF caller reads instead of the two (see pack_sel_entry); cleared after use
+  int32_t* error;            // host-visible word, raised when the wait for the entries runs out
+  long long wait_limit;      // bound of that wait in ticks of the 100 MHz wall clock
   const int32_t* seq_len;    // [B]
   float* part_acc;           // [U][S][G][D]
   float* part_ml;            // [U][S][G][2]
@@ -154,6 +157,9 @@ __device__ __forceinline__ bool finish_split(const AttnArgs& a, AttnSmem<GroupMa
   __syncthreads();
   if (!sm.is_last) return false;
   merge_splits<GT, NT, true>(a, u);
+  // every split of the unit has read its entries: blank them for the next launch
+  if (a.sel_entry != nullptr)
+    for (int i = tid; i < a.k; i += NT) store_agent(&a.sel_entry[(size_t)u * a.k + i], 0ull);
   return true;
 }
 
@@ -193,10 +199,12 @@ __device__ __forceinline__ f32x4 mfma_pv(const uint2& vfrag, const uint2& pfrag,
 // HANDOFF: the selection was written by another workgroup of the same launch.
 // LEAN: for 128 registers per lane (two workgroups of 8 waves per CU): two tile buffers instead of
 // three and the Q^T fragments re-read from LDS for every tile.
-// Returns finish_split's verdict: true in the workgroup that completed the unit's output.
+// Returns 1 in the workgroup that completed the unit's output, 0 in the others, -1 (from all
+// threads, no output) when a HANDOFF wait ran out.  inputs_ready_tick (one thread passes it)
+// receives the wall clock at which the split's entries were all there.
 template <bool BF16, int GT, int NT, bool HANDOFF, bool LEAN = false>
-__device__ __forceinline__ bool attend_mfma_body(const AttnArgs& a, AttnSmem<GroupMax<GT>::value, NT / kWave>& sm, int u,
-                                                 int split) {
+__device__ __forceinline__ int attend_mfma_body(const AttnArgs& a, AttnSmem<GroupMax<GT>::value, NT / kWave>& sm, int u,
+                                                int split, long long* inputs_ready_tick = nullptr) {
   constexpr int NW = NT / kWave;
   const int G = group_size<GT>(a);
   const int b = u / a.Hkv, h = u % a.Hkv;
@@ -234,16 +242,42 @@ __device__ __forceinline__ bool attend_mfma_body(const AttnArgs& a, AttnSmem<Gro
   const char* pool_u = a.pool + (size_t)u * a.Cmax * a.page_bytes;
 
   // the split's (page, slot) entries go to LDS once, so that issuing a tile's loads never waits on
-  // a global index load
+  // a global index load.  HANDOFF: they come from the unit's selection workgroup of the same launch,
+  // one 64-bit word each, and a thread polls its word until it has been published (a word is
+  // published when the page is in its slot); the wait is bounded and its verdict shared.
   const int n_entries = last - first;
-  const bool idx_in_lds = n_entries <= kAttnIdxCap;
-  if (idx_in_lds) {
-    for (int i = tid; i < n_entries; i += NT) {
-      sm.page[i] = HANDOFF ? load_agent(sel + first + i) : sel[first + i];
-      sm.slot[i] = HANDOFF ? load_agent(slots + first + i) : slots[first + i];
+  const bool idx_in_lds = HANDOFF || n_entries <= kAttnIdxCap;   // (HANDOFF callers keep splits within kAttnIdxCap)
+  if (HANDOFF) {
+    const u64* ent = a.sel_entry + (size_t)u * a.k + first;
+    if (tid == 0) sm.is_last = 0;                      // (here: -1 once some thread's wait has run out)
+    __syncthreads();
+    int failed = 0;
+    long long t0 = 0;
+    for (int i = tid; i < n_entries && i < kAttnIdxCap; i += NT) {
+      u64 v = load_agent(ent + i);
+      while (!(v >> 63)) {
+        if (t0 == 0) t0 = wall_clock64();
+        __builtin_amdgcn_s_sleep(8);
+        v = load_agent(ent + i);
+        if (!(v >> 63) && wall_clock64() - t0 > a.wait_limit) { failed = 1; break; }
+      }
+      const int slot16 = (int)((v >> 32) & 0xffffu);
+      sm.page[i] = (int32_t)(u32)v;
+      sm.slot[i] = slot16 == 0xffff ? -1 : slot16;
     }
+    if (failed) sm.is_last = -1;
+    __syncthreads();
+    if (sm.is_last < 0) return -1;
+    if (inputs_ready_tick != nullptr) *inputs_ready_tick = wall_clock64();
+  } else {
+    if (idx_in_lds) {
+      for (int i = tid; i < n_entries; i += NT) {
+        sm.page[i] = sel[first + i];
+        sm.slot[i] = slots[first + i];
+      }
+    }
+    __syncthreads();
   }
-  __syncthreads();
 
   // software pipeline: three tile buffers rotate, so the operands of the next two tiles of this
   // wave (16 KiB) are in flight while one tile is computed
@@ -256,9 +290,6 @@ __device__ __forceinline__ bool attend_mfma_body(const AttnArgs& a, AttnSmem<Gro
     if (idx_in_lds) {
       page = sm.page[e];
       slot = sm.slot[e];
-    } else if (HANDOFF) {
-      page = load_agent(sel + first + e);
-      slot = load_agent(slots + first + e);
     } else {
       page = sel[first + e];
       slot = slots[first + e];
@@ -363,7 +394,7 @@ __device__ __forceinline__ bool attend_mfma_body(const AttnArgs& a, AttnSmem<Gro
       for (int e = 0; e < 4; ++e) sm.acc[w][j][16 * c + 4 * g + e] = o[c][e];
     if (g == 0) { sm.m[w][j] = m; sm.l[w][j] = l; }
   }
-  return finish_split<GT, NT>(a, sm, u, split);
+  return finish_split<GT, NT>(a, sm, u, split) ? 1 : 0;
 }
 
 }  // namespace kvd

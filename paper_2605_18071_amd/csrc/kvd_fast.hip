@@ -44,6 +44,7 @@ kvd::FastArgs kvd_fast_args(kvd_ctx* c, int layer, int step, bool do_gather, con
   a.slot_page = c->d_slot_page + lu * c->Cmax;
   a.slot_stamp = c->d_slot_stamp + lu * c->Cmax;
   a.sel_slots = sel_slots;
+  a.sel_entry = c->d_sel_entry;
   a.hit_mask = hit_mask;
   a.evicted = evicted;
   a.counts = counts;

@@ -66,7 +66,7 @@ struct kvd_ctx {
   float* d_part_ml;         // [U][S][G][2]  (max in log2 units, sum)
   int32_t* d_attn_ticket;   // [U] arrival counter of the attention splits, zero between launches
   int32_t* d_score_done;    // [U][32] single-launch step: scoring waves arrived (one 128-byte line per unit), zero between launches
-  int32_t* d_sel_ready;     // [U][32] single-launch step: 1 once the unit's selection is complete, zero between launches
+  unsigned long long* d_sel_entry;  // [U][k] single-launch step: the selection as its attention workgroups read it (published bit, slot, page); zero between launches
   unsigned long long* d_stats;  // hits, misses, evictions
 
   // owned, host

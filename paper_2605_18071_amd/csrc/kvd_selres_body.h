@@ -31,6 +31,7 @@ struct FastArgs {
   int32_t* slot_page;         // [U][Cmax]
   int32_t* slot_stamp;        // [U][Cmax]
   int32_t* sel_slots;         // [U][k]
+  u64* sel_entry;             // [U][k] or null: (valid, slot, page) entries for the attention workgroups of the same launch; zero between launches
   int32_t* hit_mask;          // [U][k]
   int32_t* evicted;           // [U][k]
   int32_t* counts;            // [U][3]
@@ -45,6 +46,13 @@ struct FastArgs {
   int score_stride;           // scores of unit u start at scores + u * score_stride (NP, or the number of centroids)
   unsigned page_bytes;
 };
+
+// What the attention workgroups of the same launch read instead of sel_pages / sel_slots: one
+// 64-bit word per selected entry, bit 63 = published, bits 32..47 the slot (0xffff = none), the
+// low word the page (-1 = padding).  A word is published once the page's bytes are in its slot.
+__device__ __forceinline__ u64 pack_sel_entry(int page, int slot) {
+  return (1ull << 63) | ((u64)((u32)slot & 0xffffu) << 32) | (u64)(u32)page;
+}
 
 // This step's score of a resident page as lookahead eviction sees it: the page's own score, or with
 // the hierarchical index the score of its cluster (-inf for a page of no cluster: it leaves first).
@@ -183,7 +191,9 @@ __device__ __forceinline__ int victim_bucket(long long age, int page, int NP) {
 // lower page, sink/recent pages forced, ascending page order, -1 padding).  DO_RESOLVE: sel_pages
 // -> directory update, slots, hit mask, evicted list, counts, the (page, slot) miss list and,
 // with do_gather, the copy of the missed pages into their slots.  HANDOFF: the scores were
-// written by other workgroups of the same launch and are read with device-scope loads.
+// written by other workgroups of the same launch and are read with device-scope loads, and the
+// selection is handed to the launch's attention workgroups through a.sel_entry: an entry that hits
+// is published at once, an entry that missed when the fetched pages have been written through.
 // Needs NP <= NT * IPT, Cmax <= KVD_FAST_MAX_CAPACITY, k <= KVD_MAX_TOPK.
 // scores_ready() (HANDOFF only) is called by all threads once everything that does not depend on
 // the scores has been done; it waits for them and returns false to give up.  Returns false then.
@@ -375,8 +385,7 @@ __device__ __forceinline__ bool select_resolve_body(const FastArgs& a, int u, Fa
           if (pos < k) {
             const int p = page_of(j);
             sm.sel[pos] = (uint16_t)p;
-            if (HANDOFF) store_agent(out + pos, p);
-            else out[pos] = p;
+            out[pos] = p;
           }
           ++pos;
         }
@@ -384,8 +393,7 @@ __device__ __forceinline__ bool select_resolve_body(const FastArgs& a, int u, Fa
     }
     for (int i = k_eff + tid; i < k; i += NT) {
       sm.sel[i] = kAbsent;
-      if (HANDOFF) store_agent(out + i, -1);
-      else out[i] = -1;
+      out[i] = -1;
     }
     if (!DO_RESOLVE) return true;
     // the histogram and the candidate counter serve the victim choice next
@@ -398,27 +406,29 @@ __device__ __forceinline__ bool select_resolve_body(const FastArgs& a, int u, Fa
   int32_t* sslots = a.sel_slots + (size_t)u * k;
   int32_t* hmask = a.hit_mask + (size_t)u * k;
   int32_t* evout = a.evicted + (size_t)u * k;
+  u64* entry = HANDOFF ? a.sel_entry + (size_t)u * k : nullptr;
   const int per = (k + NT - 1) / NT;                  // consecutive selected entries per thread
   const int i0 = tid * per;
-  int my_page[KPT];
+  int my_page[KPT], my_slot[KPT];                     // this thread's misses and the slots they get
   int my_misses = 0, my_hits = 0;
 #pragma unroll
   for (int j = 0; j < KPT; ++j) {
     my_page[j] = -2;
+    my_slot[j] = -1;
     const int i = i0 + j;
     if (j < per && i < k) {
       const int p = sm.sel[i];
       if (p == kAbsent) {                             // padding (or a page the caller made up)
-        if (HANDOFF) store_agent(sslots + i, -1);
-        else sslots[i] = -1;
+        sslots[i] = -1;
+        if (HANDOFF) store_agent(entry + i, pack_sel_entry(-1, -1));
         hmask[i] = 0;
       } else {
         const int sl = sm.p2s[p];
         if (sl != kAbsent) {
           sstamp[sl] = a.step;
           atomicOr(&sm.hit_bitmap[sl >> 5], 1u << (sl & 31));
-          if (HANDOFF) store_agent(sslots + i, sl);
-          else sslots[i] = sl;
+          sslots[i] = sl;
+          if (HANDOFF) store_agent(entry + i, pack_sel_entry(p, sl));
           hmask[i] = 1;
           ++my_hits;
         } else {
@@ -543,8 +553,8 @@ __device__ __forceinline__ bool select_resolve_body(const FastArgs& a, int u, Fa
       const int i = i0 + j;
       const int sl = sm.assign[miss_rank];
       const int slot = sl == kAbsent ? -1 : sl;       // always a slot while the directory is consistent
-      if (HANDOFF) store_agent(sslots + i, slot);
-      else sslots[i] = slot;
+      sslots[i] = slot;
+      my_slot[j] = slot;
       hmask[i] = 0;
       if (slot >= 0) {
         spage[slot] = p;
@@ -566,7 +576,19 @@ __device__ __forceinline__ bool select_resolve_body(const FastArgs& a, int u, Fa
     atomicAdd(&a.stats[1], (unsigned long long)m);
     atomicAdd(&a.stats[2], (unsigned long long)e);
   }
-  if (!a.do_gather || m == 0) return true;
+  // the misses' entries go out when every wave's copies have been acknowledged
+  auto publish_misses = [&]() {
+    if (!HANDOFF) return;
+    wave_drain_memory();
+    __syncthreads();
+#pragma unroll
+    for (int j = 0; j < KPT; ++j)
+      if (my_page[j] >= 0) store_agent(entry + i0 + j, pack_sel_entry(my_page[j], my_slot[j]));
+  };
+  if (!a.do_gather) {
+    publish_misses();
+    return true;
+  }
 
   // ---- fetch the unit's missed pages: groups of 256 threads, one 16-token tile (or one page in
   // the natural layout) each per round.  Miss j is (page, sm.assign[j]); the pages are staged in
@@ -612,6 +634,7 @@ __device__ __forceinline__ bool select_resolve_body(const FastArgs& a, int u, Fa
       for (unsigned o = gt; o < units; o += 256) slot_store16<HANDOFF>(d4 + o, s4[o]);
     }
   }
+  publish_misses();
   return true;
 }
 

@@ -10,8 +10,9 @@
 //     then one selection workgroup per unit;
 //     then S attention workgroups per unit.
 // A selection workgroup waits until the unit's scoring waves have all arrived (a counter);
-// an attention workgroup waits until the unit's selection, directory update and fetch are
-// complete (a flag, lowered again by the unit's last attention workgroup).  Workgroups are
+// an attention workgroup waits until the entries of its split have been published by the unit's
+// selection workgroup (one word per selected page, published when the page is in its slot and
+// blanked again by the unit's last attention workgroup).  Workgroups are
 // dispatched in index order, so whatever a waiting workgroup waits for has already been dispatched
 // and needs nothing from later workgroups: the lowest-numbered unfinished workgroup can always run
 // to its end.  Every wait is nevertheless bounded by a wall-clock limit; a wait that runs out
@@ -20,9 +21,10 @@
 // Workgroups of one launch may sit on different XCDs with separate L2 caches.  Everything that
 // crosses workgroups inside the launch (scores, the selection and its slots, fetched pages, split
 // partials) is therefore written with device-scope write-through stores, and a flag is raised
-// only after those stores have been acknowledged; flags, scores, the selection and the partials
-// are read with device-scope loads.  Fetched pages are read with ordinary loads: no workgroup of
-// the launch touches a slot before the flag of its unit is up, so no cache can hold an older copy.
+// (or an entry published) only after those stores have been acknowledged; counters, scores, the
+// entries and the partials are read with device-scope loads.  Fetched pages are read with ordinary loads: no workgroup of
+// the launch touches a slot before the page's entry has been published, so no cache can hold an
+// older copy.
 #include "kvd_attn_body.h"
 #include "kvd_device.h"
 #include "kvd_internal.h"
@@ -41,7 +43,6 @@ struct StepArgs {
   FastArgs fa;
   AttnArgs at;
   int32_t* score_done;       // [U][32] (one line per unit) scoring waves of the unit that have arrived (8 per chunk); zero between launches
-  int32_t* sel_ready;        // [U][32] (one line per unit) 1 once the unit's selection, directory update and fetch are complete; zero between launches
   int32_t* error;            // host-visible; set when a wait runs out
   long long* timeline;       // [workgroups][5]: wall-clock ticks at start, wait over, work done, exit; then a tag; or null
   long long wait_limit;      // ticks of the 100 MHz wall clock
@@ -88,9 +89,9 @@ __device__ __forceinline__ void step_score_role(StepArgsPtr ap, int wg, long lon
 template <int IPT>
 __device__ __forceinline__ void step_select_role(StepArgsPtr ap, int u, unsigned char* smem_raw, int* wait_ok,
                                                            long long* ts) {
-  struct { FastArgs fa; int32_t* score_done; int32_t* sel_ready; int32_t* error; long long wait_limit; int chunks; } a;
+  struct { FastArgs fa; int32_t* score_done; int32_t* error; long long wait_limit; int chunks; } a;
   __builtin_memcpy(&a.fa, &ap->fa, sizeof(FastArgs));
-  a.score_done = ap->score_done; a.sel_ready = ap->sel_ready; a.error = ap->error;
+  a.score_done = ap->score_done; a.error = ap->error;
   a.wait_limit = ap->wait_limit; a.chunks = ap->chunks;
   const int tid = threadIdx.x;
   if (ts) ts[4] = 1LL | ((long long)u << 8);
@@ -107,31 +108,18 @@ __device__ __forceinline__ void step_select_role(StepArgsPtr ap, int u, unsigned
     if (tid == 0) __hip_atomic_store(a.error, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
     return;
   }
-  if (ts) ts[2] = wall_clock64();
-  wave_drain_memory();                                 // selection, slots and fetched pages have been written through
-  __syncthreads();
-  if (tid == 0) store_agent(&a.sel_ready[u * kFlagStride], 1);
-  if (ts) ts[3] = wall_clock64();
+  if (ts) ts[2] = ts[3] = wall_clock64();              // (the entries have been published inside)
 }
 
 // Attention workgroup (u, split).
 template <bool BF16>
-__device__ __forceinline__ void step_attend_role(StepArgsPtr ap, int u, int split, unsigned char* smem_raw,
-                                                           int* wait_ok, long long* ts) {
-  struct { AttnArgs at; int32_t* sel_ready; int32_t* error; long long wait_limit; } a;
+__device__ __forceinline__ void step_attend_role(StepArgsPtr ap, int u, int split, unsigned char* smem_raw, long long* ts) {
+  struct { AttnArgs at; } a;
   __builtin_memcpy(&a.at, &ap->at, sizeof(AttnArgs));
-  a.sel_ready = ap->sel_ready; a.error = ap->error; a.wait_limit = ap->wait_limit;
-  const int tid = threadIdx.x;
   if (ts) ts[4] = 2LL | ((long long)u << 8) | ((long long)split << 32);
-  if (!block_wait_equal(&a.sel_ready[u * kFlagStride], 1, a.wait_limit, wait_ok)) {
-    if (tid == 0) __hip_atomic_store(a.error, 2, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
-    return;
-  }
-  if (ts) ts[1] = wall_clock64();
   StepAttnSmem& sm = *reinterpret_cast<StepAttnSmem*>(smem_raw);
-  const bool last = attend_mfma_body<BF16, 0, kStepThreads, true, true>(a.at, sm, u, split);
-  // every split of the unit has passed its wait by now: lower the flag for the next launch
-  if (last && tid == 0) store_agent(&a.sel_ready[u * kFlagStride], 0);
+  const int done = attend_mfma_body<BF16, 0, kStepThreads, true, true>(a.at, sm, u, split, ts ? ts + 1 : nullptr);
+  if (done < 0 && threadIdx.x == 0) __hip_atomic_store(a.at.error, 2, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
   if (ts) ts[2] = ts[3] = wall_clock64();
 }
 
@@ -149,7 +137,7 @@ __device__ __forceinline__ void step_body(StepArgsPtr ap, unsigned char* smem_ra
     step_select_role<IPT>(ap, bid - n_score + u0, smem_raw, &wait_ok, ts);
   } else {
     const int i = bid - front;
-    step_attend_role<BF16>(ap, i / S + u0, i % S, smem_raw, &wait_ok, ts);
+    step_attend_role<BF16>(ap, i / S + u0, i % S, smem_raw, ts);
   }
 }
 
@@ -174,7 +162,8 @@ static void launch_step(int ipt, const StepArgs& a, int n_blocks, hipStream_t s)
 }  // namespace kvd
 
 bool kvd_single_launch_ok(const kvd_ctx* c) {
-  return kvd_fast_path_ok(c) && c->tiled && c->NP <= kvd::kStepThreads * 32;
+  return kvd_fast_path_ok(c) && c->tiled && c->NP <= kvd::kStepThreads * 32 &&
+         (c->k + c->S1 - 1) / c->S1 <= kvd::kAttnIdxCap;   // a split's entries are staged in LDS
 }
 
 hipError_t kvd_launch_step(kvd_ctx* c, int layer, int step, const void* q, float* out, float* lse, hipStream_t s) {
@@ -187,10 +176,10 @@ hipError_t kvd_launch_step(kvd_ctx* c, int layer, int step, const void* q, float
                        c->d_counts, 0);
   a.at = kvd_attn_args(c, layer, q, c->d_sel_pages, c->d_sel_slots, out, lse, 0);
   a.at.fuse_merge = 1;
+  a.at.sel_entry = c->d_sel_entry;
   a.at.S = c->S1;
   a.at.per_split = (c->k + c->S1 - 1) / c->S1;
   a.score_done = c->d_score_done;
-  a.sel_ready = c->d_sel_ready;
   a.error = c->error_dev;
   a.timeline = nullptr;
   a.wait_limit = c->wait_limit_ticks;

@@ -508,9 +508,11 @@ def test_single_launch_timeline_and_wait_limit():
     t = rec[:, :4]
     assert np.all(np.diff(t, axis=1) >= 0)                           # start <= ready <= done <= exit
     first_score = t[role == 0, 0].min()
-    for u in range(w.units):                                          # a unit's stages follow one another
-        sel = t[(role == 1) & (unit == u)][0]
-        assert sel[1] >= first_score and t[(role == 2) & (unit == u), 1].min() >= sel[2]
+    for u in range(w.units):                                          # a unit's stages follow one another:
+        sel = t[(role == 1) & (unit == u)][0]                         # a split has its entries after the unit's scores
+        att = t[(role == 2) & (unit == u)]                            # were there (hits are published before the
+        assert sel[1] >= first_score and att[:, 1].min() >= sel[1]    # selection workgroup is done), and the unit's
+        assert att[:, 2].max() >= sel[2]                              # output after its last missed page was fetched
     rig.kvd.set_profiling(0)
 
     rig.kvd.set_wait_limit_us(0)
