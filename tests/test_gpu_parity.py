@@ -88,8 +88,10 @@ def test_select_exact_ties_go_to_lower_page():
     them is then decided only by the tie rule."""
     w = small("ties", ctx=16 * 200, topk_pages=16, capacity=32, heavy_count=0)
     rig = R.Rig(w, build_index=False)
-    base = torch.randn(w.units, 10, w.head_dim, device=R.DEV)
-    idx = torch.randint(0, 10, (w.units, w.n_pages), device=R.DEV)
+    g = torch.Generator(device=R.DEV)
+    g.manual_seed(770_010)
+    base = torch.randn(w.units, 10, w.head_dim, device=R.DEV, generator=g)
+    idx = torch.randint(0, 10, (w.units, w.n_pages), device=R.DEV, generator=g)
     summ = torch.gather(base, 1, idx[:, :, None].expand(-1, -1, w.head_dim)).to(w.torch_dtype)
     rig.summaries.copy_(summ.view(rig.summaries.shape))
     q = next(W.query_stream(w, rig.q0, 1, R.DEV))
@@ -588,8 +590,10 @@ def test_lookahead_exact_ties_drop_the_higher_page():
     the tie rule decides who leaves: GPU and oracle must agree without any tolerance."""
     w = small("la-ties", ctx=16 * 200, topk_pages=16, capacity=24, heavy_count=0, policy="lookahead", steps=10)
     rig = R.Rig(w, build_index=False)
-    base = torch.randn(w.units, 12, w.head_dim, device=R.DEV)
-    idx = torch.randint(0, 12, (w.units, w.n_pages), device=R.DEV)
+    g = torch.Generator(device=R.DEV)
+    g.manual_seed(770_011)                                            # (own generator: the outcome must not depend on what ran before)
+    base = torch.randn(w.units, 24, w.head_dim, device=R.DEV, generator=g)
+    idx = torch.randint(0, 24, (w.units, w.n_pages), device=R.DEV, generator=g)
     summ = torch.gather(base, 1, idx[:, :, None].expand(-1, -1, w.head_dim)).to(w.torch_dtype)
     rig.summaries.copy_(summ.view(rig.summaries.shape))
     units = all_units(rig)
@@ -698,8 +702,10 @@ def test_hierarchical_index_ragged_forced_and_duplicate_pages():
     w = small("hier-edge", ctx=16 * 200, topk_pages=24, capacity=40, sink_pages=2, recent_pages=3, heavy_count=0,
               index_centroids=64, index_iterations=3, steps=5)
     rig = R.Rig(w, seq_lens=[w.ctx - 7, w.ctx - 16 * 90 - 3], build_index=False)
-    base = torch.randn(w.units, 20, w.head_dim, device=R.DEV)                     # 20 distinct rows < 64 centroids
-    idx = torch.randint(0, 20, (w.units, w.n_pages), device=R.DEV)
+    g = torch.Generator(device=R.DEV)
+    g.manual_seed(770_012)
+    base = torch.randn(w.units, 20, w.head_dim, device=R.DEV, generator=g)        # 20 distinct rows < 64 centroids
+    idx = torch.randint(0, 20, (w.units, w.n_pages), device=R.DEV, generator=g)
     summ = torch.gather(base, 1, idx[:, :, None].expand(-1, -1, w.head_dim)).to(w.torch_dtype)
     rig.summaries.copy_(summ.view(rig.summaries.shape))
     rig.kvd.build_centroids(0, w.index_iterations, rig.assign_trace[0])
