@@ -20,13 +20,12 @@
   } while (0)
 
 // micro_batches -1 asks for the one-launch step wherever it can run; 0 leaves the choice to the
-// library, which takes it where it has measured faster than the chain of kernels: units of at most
-// 8192 pages (the selection role keeps its scores in registers at half the threads of the
-// stand-alone kernel) and enough units to keep its pipeline filled.
+// library, which takes it where it has measured faster than the chain of kernels: enough units to
+// keep its pipeline filled.
 static bool kvd_wants_single_launch(const kvd_ctx* c) {
   if (!kvd_single_launch_ok(c) || c->Nc > 0) return false;
   if (c->cfg.micro_batches == -1) return true;
-  return c->cfg.micro_batches == 0 && c->NP <= 8192 && c->U >= 32;
+  return c->cfg.micro_batches == 0 && c->U >= 32;
 }
 
 static bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
@@ -192,13 +191,23 @@ int kvd_create(const kvd_config* cfg, kvd_ctx** out) {
   c->S = S;
   // the one-launch step has 8 waves per attention workgroup and gains from twice as many
   // workgroups (units become ready one after another) as long as a wave keeps 4 tiles or more
+  // Units of 8192 pages and more take the one-launch step's 1024-thread form (one workgroup per
+  // CU, 16 waves): there a split keeps 4 tiles per wave.
   c->S1 = S;
+  c->step_threads = c->NP >= 8192 ? 1024 : 512;
   if (cfg->attn_splits == 0) {
     const int tiles = c->k * ((c->P + 15) / 16);
-    int S2 = (1024 + c->U / 2) / c->U;
-    if (S2 > KVD_MAX_SPLITS) S2 = KVD_MAX_SPLITS;
-    if (S2 > c->k) S2 = c->k;
-    if (S2 >= 1 && tiles / (S2 * 8) >= 4) c->S1 = S2;
+    if (c->step_threads == 1024) {
+      int S2 = tiles / 64;
+      if (S2 > KVD_MAX_SPLITS) S2 = KVD_MAX_SPLITS;
+      if (S2 > c->k) S2 = c->k;
+      c->S1 = S2 < 1 ? 1 : S2;
+    } else {
+      int S2 = (1024 + c->U / 2) / c->U;
+      if (S2 > KVD_MAX_SPLITS) S2 = KVD_MAX_SPLITS;
+      if (S2 > c->k) S2 = c->k;
+      if (S2 >= 1 && tiles / (S2 * 8) >= 4) c->S1 = S2;
+    }
   }
   const int Smax = c->S > c->S1 ? c->S : c->S1;
 

@@ -145,7 +145,12 @@ __device__ __forceinline__ bool finish_split(const AttnArgs& a, AttnSmem<GroupMa
       }
     }
   }
-  if (a.S == 1) return true;
+  if (a.S == 1) {
+    // (a HANDOFF caller's entries were read into LDS before the first barrier: blank them for the next launch)
+    if (a.sel_entry != nullptr)
+      for (int i = tid; i < a.k; i += NT) store_agent(&a.sel_entry[(size_t)u * a.k + i], 0ull);
+    return true;
+  }
   if (!fused) return false;
   wave_drain_memory();                               // this wave's partials have been acknowledged
   __syncthreads();

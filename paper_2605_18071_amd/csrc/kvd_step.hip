@@ -33,8 +33,8 @@
 
 namespace kvd {
 
-constexpr int kStepThreads = 512;
-constexpr int kStepWaves = kStepThreads / kWave;
+constexpr int kStepThreads = 512;            // two workgroups per CU
+constexpr int kStepThreadsWide = 1024;       // one per CU: units of more pages than 512 threads keep in registers
 
 struct StepArgs {
   const uint16_t* summ;      // [U][NP][D] of the layer
@@ -50,9 +50,12 @@ struct StepArgs {
   int n_units, u0, chunks, passes, n_score;
 };
 
-typedef AttnSmem<KVD_MAX_GROUP, kStepWaves> StepAttnSmem;
-typedef FastSmem<kStepThreads> StepFastSmem;
-constexpr size_t kStepSmemBytes = sizeof(StepAttnSmem) > sizeof(StepFastSmem) ? sizeof(StepAttnSmem) : sizeof(StepFastSmem);
+template <int NT>
+struct StepSmem {
+  typedef AttnSmem<KVD_MAX_GROUP, NT / kWave> Attn;
+  typedef FastSmem<NT> Fast;
+  static constexpr size_t bytes = sizeof(Attn) > sizeof(Fast) ? sizeof(Attn) : sizeof(Fast);
+};
 
 // The three roles read the launch arguments from the kernel-argument segment (constant address
 // space, scalar loads) and copy only what they use.
@@ -60,7 +63,7 @@ typedef const __attribute__((address_space(4))) StepArgs* StepArgsPtr;
 constexpr int kFlagStride = 32;   // ints between the flags of two units: one 128-byte line each
 
 // Scoring workgroup `wg` of n_score: chunks wg, wg + n_score, ... of the layer, unit by unit.
-template <bool BF16>
+template <bool BF16, int NT>
 __device__ __forceinline__ void step_score_role(StepArgsPtr ap, int wg, long long* ts) {
   struct { const uint16_t* summ; const uint16_t* q; float* scores; int32_t* score_done; float scale;
            int n_units, chunks, n_score, u0, passes; struct { int Hkv, NP; } fa; struct { int Hq, G; } at; } a;
@@ -74,7 +77,7 @@ __device__ __forceinline__ void step_score_role(StepArgsPtr ap, int wg, long lon
   for (int c = wg; c < total; c += a.n_score) {
     const int u = c / a.chunks + a.u0, r = c % a.chunks;
     const int b = u / a.fa.Hkv, h = u % a.fa.Hkv;
-    const int wave_base = (r * kStepWaves + w) * 64 * a.passes;
+    const int wave_base = (r * (NT / kWave) + w) * 64 * a.passes;
     score_wave<BF16, true>(a.summ + (size_t)u * a.fa.NP * kHeadDim,
                            a.q + ((size_t)b * a.at.Hq + (size_t)h * a.at.G) * kHeadDim, a.scores + (size_t)u * a.fa.NP,
                            a.fa.NP, a.at.G, a.scale, wave_base, a.passes);
@@ -86,7 +89,7 @@ __device__ __forceinline__ void step_score_role(StepArgsPtr ap, int wg, long lon
 
 // Selection, directory update and fetch of unit u: latency-bound, so its waves go first whenever
 // they can issue.
-template <int IPT>
+template <int NT, int IPT>
 __device__ __forceinline__ void step_select_role(StepArgsPtr ap, int u, unsigned char* smem_raw, int* wait_ok,
                                                            long long* ts) {
   struct { FastArgs fa; int32_t* score_done; int32_t* error; long long wait_limit; int chunks; } a;
@@ -96,15 +99,15 @@ __device__ __forceinline__ void step_select_role(StepArgsPtr ap, int u, unsigned
   const int tid = threadIdx.x;
   if (ts) ts[4] = 1LL | ((long long)u << 8);
   __builtin_amdgcn_s_setprio(3);
-  StepFastSmem& sm = *reinterpret_cast<StepFastSmem*>(smem_raw);
+  typename StepSmem<NT>::Fast& sm = *reinterpret_cast<typename StepSmem<NT>::Fast*>(smem_raw);
   // the directory is loaded and the LDS tables are set up while the unit's scores are still coming in
   auto scores_ready = [&]() -> bool {
-    const bool ok = block_wait_equal(&a.score_done[u * kFlagStride], a.chunks * kStepWaves, a.wait_limit, wait_ok);
+    const bool ok = block_wait_equal(&a.score_done[u * kFlagStride], a.chunks * (NT / kWave), a.wait_limit, wait_ok);
     if (ts) ts[1] = wall_clock64();
     if (ok && tid == 0) store_agent(&a.score_done[u * kFlagStride], 0);   // every arrival has been seen: ready for the next launch
     return ok;
   };
-  if (!select_resolve_body<kStepThreads, IPT, true, true, true>(a.fa, u, sm, scores_ready)) {
+  if (!select_resolve_body<NT, IPT, true, true, true>(a.fa, u, sm, scores_ready)) {
     if (tid == 0) __hip_atomic_store(a.error, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
     return;
   }
@@ -112,18 +115,18 @@ __device__ __forceinline__ void step_select_role(StepArgsPtr ap, int u, unsigned
 }
 
 // Attention workgroup (u, split).
-template <bool BF16>
+template <bool BF16, int NT>
 __device__ __forceinline__ void step_attend_role(StepArgsPtr ap, int u, int split, unsigned char* smem_raw, long long* ts) {
   struct { AttnArgs at; } a;
   __builtin_memcpy(&a.at, &ap->at, sizeof(AttnArgs));
   if (ts) ts[4] = 2LL | ((long long)u << 8) | ((long long)split << 32);
-  StepAttnSmem& sm = *reinterpret_cast<StepAttnSmem*>(smem_raw);
-  const int done = attend_mfma_body<BF16, 0, kStepThreads, true, true>(a.at, sm, u, split, ts ? ts + 1 : nullptr);
+  typename StepSmem<NT>::Attn& sm = *reinterpret_cast<typename StepSmem<NT>::Attn*>(smem_raw);
+  const int done = attend_mfma_body<BF16, 0, NT, true, true>(a.at, sm, u, split, ts ? ts + 1 : nullptr);
   if (done < 0 && threadIdx.x == 0) __hip_atomic_store(a.at.error, 2, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
   if (ts) ts[2] = ts[3] = wall_clock64();
 }
 
-template <bool BF16, int IPT>
+template <bool BF16, int NT, int IPT>
 __device__ __forceinline__ void step_body(StepArgsPtr ap, unsigned char* smem_raw, int& wait_ok) {
   const int bid = blockIdx.x;
   long long* timeline = ap->timeline;
@@ -132,37 +135,41 @@ __device__ __forceinline__ void step_body(StepArgsPtr ap, unsigned char* smem_ra
   const int n_score = ap->n_score, n_units = ap->n_units, u0 = ap->u0, S = ap->at.S;
   const int front = n_score + n_units;
   if (bid < n_score) {
-    step_score_role<BF16>(ap, bid, ts);
+    step_score_role<BF16, NT>(ap, bid, ts);
   } else if (bid < front) {
-    step_select_role<IPT>(ap, bid - n_score + u0, smem_raw, &wait_ok, ts);
+    step_select_role<NT, IPT>(ap, bid - n_score + u0, smem_raw, &wait_ok, ts);
   } else {
     const int i = bid - front;
-    step_attend_role<BF16>(ap, i / S + u0, i % S, smem_raw, ts);
+    step_attend_role<BF16, NT>(ap, i / S + u0, i % S, smem_raw, ts);
   }
 }
 
-template <bool BF16, int IPT>
-__global__ __launch_bounds__(kStepThreads, 4) void step_kernel(StepArgs a) {
-  __shared__ __align__(16) unsigned char smem_raw[kStepSmemBytes];
+template <bool BF16, int NT, int IPT>
+__global__ __launch_bounds__(NT, 4) void step_kernel(StepArgs a) {
+  __shared__ __align__(16) unsigned char smem_raw[StepSmem<NT>::bytes];
   __shared__ int wait_ok;
   // the launch arguments are the first thing in the kernel-argument segment
-  step_body<BF16, IPT>((StepArgsPtr)__builtin_amdgcn_kernarg_segment_ptr(), smem_raw, wait_ok);
+  step_body<BF16, NT, IPT>((StepArgsPtr)__builtin_amdgcn_kernarg_segment_ptr(), smem_raw, wait_ok);
 }
 template <bool BF16>
-static void launch_step(int ipt, const StepArgs& a, int n_blocks, hipStream_t s) {
-  dim3 grid(n_blocks), block(kStepThreads);
-  if (ipt <= 8)
-    hipLaunchKernelGGL((step_kernel<BF16, 8>), grid, block, 0, s, a);
-  else if (ipt <= 16)
-    hipLaunchKernelGGL((step_kernel<BF16, 16>), grid, block, 0, s, a);
-  else
-    hipLaunchKernelGGL((step_kernel<BF16, 32>), grid, block, 0, s, a);
+static void launch_step(int threads, int ipt, const StepArgs& a, int n_blocks, hipStream_t s) {
+  dim3 grid(n_blocks), block(threads);
+  if (threads == kStepThreadsWide) {
+    if (ipt <= 8)
+      hipLaunchKernelGGL((step_kernel<BF16, kStepThreadsWide, 8>), grid, block, 0, s, a);
+    else
+      hipLaunchKernelGGL((step_kernel<BF16, kStepThreadsWide, 16>), grid, block, 0, s, a);
+  } else if (ipt <= 8) {
+    hipLaunchKernelGGL((step_kernel<BF16, kStepThreads, 8>), grid, block, 0, s, a);
+  } else {
+    hipLaunchKernelGGL((step_kernel<BF16, kStepThreads, 16>), grid, block, 0, s, a);
+  }
 }
 
 }  // namespace kvd
 
 bool kvd_single_launch_ok(const kvd_ctx* c) {
-  return kvd_fast_path_ok(c) && c->tiled && c->NP <= kvd::kStepThreads * 32 &&
+  return kvd_fast_path_ok(c) && c->tiled && c->NP <= kvd::kStepThreadsWide * 16 &&
          (c->k + c->S1 - 1) / c->S1 <= kvd::kAttnIdxCap;   // a split's entries are staged in LDS
 }
 
@@ -186,11 +193,15 @@ hipError_t kvd_launch_step(kvd_ctx* c, int layer, int step, const void* q, float
   a.scale = c->scale;
   a.n_units = c->U;
   a.u0 = 0;
-  // Scoring workgroups are persistent: one round of resident workgroups (2 per CU) minus the
-  // slots left to the selection workgroups that run beside them.  A chunk is 8 waves x 64 pages x
-  // passes; passes is chosen so that the chunks of the layer fill whole rounds of the scoring
-  // workgroups (time ~ rounds x passes), finer chunks winning ties.
-  const int slots = 2 * c->n_cus;
+  // 512-thread workgroups sit two to a CU; units of 8192 pages and more take the 1024-thread
+  // form (one per CU), whose selection role keeps at most 16 pages per thread in registers.
+  const int threads = c->step_threads == kStepThreadsWide ? kStepThreadsWide : kStepThreads;
+  const int chunk_pages = threads;                    // a scoring chunk: every wave 64 pages x passes
+  // Scoring workgroups are persistent: one round of resident workgroups minus the slots left to
+  // the selection workgroups that run beside them.  passes is chosen so that the chunks of the
+  // layer fill whole rounds of the scoring workgroups (time ~ rounds x passes), finer chunks
+  // winning ties.
+  const int slots = (threads == kStepThreads ? 2 : 1) * c->n_cus;
   int reserve = slots / 8;
   if (reserve > c->U) reserve = c->U;
   int n_score = slots - reserve;
@@ -198,20 +209,20 @@ hipError_t kvd_launch_step(kvd_ctx* c, int layer, int step, const void* q, float
   int best_passes = 1;
   long long best_cost = -1;
   for (int passes = 1; passes <= 8; ++passes) {
-    const long long chunks = (c->NP + 512LL * passes - 1) / (512LL * passes);
+    const long long chunks = (c->NP + (long long)chunk_pages * passes - 1) / ((long long)chunk_pages * passes);
     const long long rounds = (chunks * c->U + n_score - 1) / n_score;
     const long long cost = rounds * passes;
     if (best_cost < 0 || cost < best_cost) { best_cost = cost; best_passes = passes; }
   }
   a.passes = best_passes;
-  a.chunks = (c->NP + 512 * a.passes - 1) / (512 * a.passes);
+  a.chunks = (c->NP + chunk_pages * a.passes - 1) / (chunk_pages * a.passes);
   if (n_score > c->U * a.chunks) n_score = c->U * a.chunks;
   a.n_score = n_score;
   const int n_blocks = a.n_score + c->U + c->U * c->S1;
   c->tl_workgroups = n_blocks;
   if (c->profiling == 2 && n_blocks <= KVD_TIMELINE_MAX) a.timeline = c->d_timeline;
-  const int ipt = (c->NP + kStepThreads - 1) / kStepThreads;
-  if (c->bf16) launch_step<true>(ipt, a, n_blocks, s);
-  else launch_step<false>(ipt, a, n_blocks, s);
+  const int ipt = (c->NP + threads - 1) / threads;
+  if (c->bf16) launch_step<true>(threads, ipt, a, n_blocks, s);
+  else launch_step<false>(threads, ipt, a, n_blocks, s);
   return hipGetLastError();
 }

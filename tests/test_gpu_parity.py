@@ -309,6 +309,35 @@ def test_step_parity_page_counts_off_the_load_width(n_pages, mb):
     rig.close()
 
 
+@pytest.mark.parametrize("kw", [
+    dict(ctx=16 * 8200, topk_pages=48, capacity=300),                 # 8200 pages: 9 per thread, ragged wave blocks
+    dict(ctx=32 * 8192, page=32, dtype="f16", n_q_heads=14, n_kv_heads=2, topk_pages=40, capacity=128, policy="lookahead"),
+    dict(ctx=64 * 16384, page=64, topk_pages=64, capacity=96, recent_pages=6, batch=1),   # the largest unit the form takes
+], ids=["8200-pages", "8192-pages-f16-g7-lookahead", "16384-pages"])
+def test_step_parity_units_of_8192_pages_and_more(kw):
+    """Units of 8192 pages and more run the one-launch step with 1024-thread workgroups."""
+    w = small("wide", steps=4, **kw)
+    rig = R.Rig(w, seq_lens=[w.ctx - 5, w.ctx - 3 * w.page - 1][:w.batch], micro_batches=-1)
+    assert rig.kvd.step_form() == -1
+    units = all_units(rig)
+    rep = R.run_steps(rig, units, w.steps, check_dir_every=2, progress="wide")
+    assert rep.unit_steps == w.steps * w.units
+    assert rep.tie_divergences <= 2 and rep.victim_tie_divergences <= 2
+    rig.close()
+
+
+@pytest.mark.parametrize("mb", [-1, 1], ids=["single-launch", "kernel-chain"])
+def test_step_parity_one_attention_split_per_unit(mb):
+    """So few selected pages that a unit's attention is one workgroup (no partials, no merge)."""
+    w = small("one-split", topk_pages=6, capacity=7, steps=8)
+    rig = R.Rig(w, micro_batches=mb)
+    units = all_units(rig)
+    rep = R.run_steps(rig, units, w.steps, check_dir_every=2, progress=f"one-split-mb{mb}")
+    assert rep.unit_steps == w.steps * w.units and rep.tie_divergences <= 2
+    assert rig.kvd.stats().evictions > 0
+    rig.close()
+
+
 @pytest.mark.parametrize("mb", [-1, 1], ids=["single-launch", "kernel-chain"])
 @pytest.mark.parametrize("cfg", [1, 2, 3, 4, 5])
 def test_step_parity_scaled_configs(cfg, mb):
