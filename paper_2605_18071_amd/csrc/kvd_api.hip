@@ -191,23 +191,21 @@ int kvd_create(const kvd_config* cfg, kvd_ctx** out) {
   c->S = S;
   // the one-launch step has 8 waves per attention workgroup and gains from twice as many
   // workgroups (units become ready one after another) as long as a wave keeps 4 tiles or more
-  // Units of 8192 pages and more take the one-launch step's 1024-thread form (one workgroup per
-  // CU, 16 waves): there a split keeps 4 tiles per wave.
+  // The one-launch step runs one workgroup per CU: 512 threads with 256 registers per lane (three
+  // tile buffers in the attention role), or, for units of more than 8192 pages, 1024 threads with
+  // 128.  Its attention splits: about one workgroup per CU in the first form (at least two tiles
+  // per wave), four tiles per wave in the second.
   c->S1 = S;
-  c->step_threads = c->NP >= 8192 ? 1024 : 512;
+  c->step_threads = c->NP > 8192 ? 1024 : 512;
   if (cfg->attn_splits == 0) {
     const int tiles = c->k * ((c->P + 15) / 16);
-    if (c->step_threads == 1024) {
-      int S2 = tiles / 64;
-      if (S2 > KVD_MAX_SPLITS) S2 = KVD_MAX_SPLITS;
-      if (S2 > c->k) S2 = c->k;
-      c->S1 = S2 < 1 ? 1 : S2;
-    } else {
-      int S2 = (1024 + c->U / 2) / c->U;
-      if (S2 > KVD_MAX_SPLITS) S2 = KVD_MAX_SPLITS;
-      if (S2 > c->k) S2 = c->k;
-      if (S2 >= 1 && tiles / (S2 * 8) >= 4) c->S1 = S2;
-    }
+    int S2 = c->step_threads == 1024 ? tiles / 64 : (c->n_cus + c->U / 2) / c->U;
+    const int cap = c->step_threads == 1024 ? KVD_MAX_SPLITS : tiles / 16;
+    if (S2 > cap) S2 = cap;
+    if (S2 > KVD_MAX_SPLITS) S2 = KVD_MAX_SPLITS;
+    if (S2 < (c->k + 511) / 512) S2 = (c->k + 511) / 512;   // a split's entries are staged in LDS, 512 at most
+    if (S2 > c->k) S2 = c->k;
+    c->S1 = S2 < 1 ? 1 : S2;
   }
   const int Smax = c->S > c->S1 ? c->S : c->S1;
 

@@ -33,8 +33,9 @@
 
 namespace kvd {
 
-constexpr int kStepThreads = 512;            // two workgroups per CU
-constexpr int kStepThreadsWide = 1024;       // one per CU: units of more pages than 512 threads keep in registers
+// One workgroup per CU in both forms:
+constexpr int kStepThreads = 512;            // 256 registers per lane: three tile buffers in the attention role
+constexpr int kStepThreadsWide = 1024;       // 128 registers per lane: units of more pages than 512 threads keep in registers
 
 struct StepArgs {
   const uint16_t* summ;      // [U][NP][D] of the layer
@@ -115,18 +116,18 @@ __device__ __forceinline__ void step_select_role(StepArgsPtr ap, int u, unsigned
 }
 
 // Attention workgroup (u, split).
-template <bool BF16, int NT>
+template <bool BF16, int NT, bool LEAN>
 __device__ __forceinline__ void step_attend_role(StepArgsPtr ap, int u, int split, unsigned char* smem_raw, long long* ts) {
   struct { AttnArgs at; } a;
   __builtin_memcpy(&a.at, &ap->at, sizeof(AttnArgs));
   if (ts) ts[4] = 2LL | ((long long)u << 8) | ((long long)split << 32);
   typename StepSmem<NT>::Attn& sm = *reinterpret_cast<typename StepSmem<NT>::Attn*>(smem_raw);
-  const int done = attend_mfma_body<BF16, 0, NT, true, true>(a.at, sm, u, split, ts ? ts + 1 : nullptr);
+  const int done = attend_mfma_body<BF16, 0, NT, true, LEAN>(a.at, sm, u, split, ts ? ts + 1 : nullptr);
   if (done < 0 && threadIdx.x == 0) __hip_atomic_store(a.at.error, 2, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
   if (ts) ts[2] = ts[3] = wall_clock64();
 }
 
-template <bool BF16, int NT, int IPT>
+template <bool BF16, int NT, int IPT, bool LEAN>
 __device__ __forceinline__ void step_body(StepArgsPtr ap, unsigned char* smem_raw, int& wait_ok) {
   const int bid = blockIdx.x;
   long long* timeline = ap->timeline;
@@ -140,16 +141,17 @@ __device__ __forceinline__ void step_body(StepArgsPtr ap, unsigned char* smem_ra
     step_select_role<NT, IPT>(ap, bid - n_score + u0, smem_raw, &wait_ok, ts);
   } else {
     const int i = bid - front;
-    step_attend_role<BF16, NT>(ap, i / S + u0, i % S, smem_raw, ts);
+    step_attend_role<BF16, NT, LEAN>(ap, i / S + u0, i % S, smem_raw, ts);
   }
 }
 
-template <bool BF16, int NT, int IPT>
-__global__ __launch_bounds__(NT, 4) void step_kernel(StepArgs a) {
+// LEAN: 128 registers per lane (the 1024-thread form); otherwise 256.
+template <bool BF16, int NT, int IPT, bool LEAN = (NT > kStepThreads)>
+__global__ __launch_bounds__(NT, LEAN ? 4 : 2) void step_kernel(StepArgs a) {
   __shared__ __align__(16) unsigned char smem_raw[StepSmem<NT>::bytes];
   __shared__ int wait_ok;
   // the launch arguments are the first thing in the kernel-argument segment
-  step_body<BF16, NT, IPT>((StepArgsPtr)__builtin_amdgcn_kernarg_segment_ptr(), smem_raw, wait_ok);
+  step_body<BF16, NT, IPT, LEAN>((StepArgsPtr)__builtin_amdgcn_kernarg_segment_ptr(), smem_raw, wait_ok);
 }
 template <bool BF16>
 static void launch_step(int threads, int ipt, const StepArgs& a, int n_blocks, hipStream_t s) {
@@ -193,15 +195,15 @@ hipError_t kvd_launch_step(kvd_ctx* c, int layer, int step, const void* q, float
   a.scale = c->scale;
   a.n_units = c->U;
   a.u0 = 0;
-  // 512-thread workgroups sit two to a CU; units of 8192 pages and more take the 1024-thread
-  // form (one per CU), whose selection role keeps at most 16 pages per thread in registers.
+  // Units of more than 8192 pages take the 1024-thread form, whose selection role keeps at most
+  // 16 pages per thread in registers like the 512-thread form does for the others.
   const int threads = c->step_threads == kStepThreadsWide ? kStepThreadsWide : kStepThreads;
   const int chunk_pages = threads;                    // a scoring chunk: every wave 64 pages x passes
   // Scoring workgroups are persistent: one round of resident workgroups minus the slots left to
   // the selection workgroups that run beside them.  passes is chosen so that the chunks of the
   // layer fill whole rounds of the scoring workgroups (time ~ rounds x passes), finer chunks
   // winning ties.
-  const int slots = (threads == kStepThreads ? 2 : 1) * c->n_cus;
+  const int slots = c->n_cus;
   int reserve = slots / 8;
   if (reserve > c->U) reserve = c->U;
   int n_score = slots - reserve;
@@ -221,7 +223,7 @@ hipError_t kvd_launch_step(kvd_ctx* c, int layer, int step, const void* q, float
   const int n_blocks = a.n_score + c->U + c->U * c->S1;
   c->tl_workgroups = n_blocks;
   if (c->profiling == 2 && n_blocks <= KVD_TIMELINE_MAX) a.timeline = c->d_timeline;
-  const int ipt = (c->NP + threads - 1) / threads;
+  const int ipt = (c->NP + chunk_pages - 1) / chunk_pages;
   if (c->bf16) launch_step<true>(threads, ipt, a, n_blocks, s);
   else launch_step<false>(threads, ipt, a, n_blocks, s);
   return hipGetLastError();
