@@ -178,19 +178,22 @@ int kvd_create(const kvd_config* cfg, kvd_ctx** out) {
   c->page_bytes = (size_t)2 * c->P * c->D * 2;
   int S = cfg->attn_splits;
   if (S == 0) {
-    // one round of resident blocks: 256 CUs x 2 blocks of 4 waves (the attention kernel runs at
-    // 2 waves per SIMD); every block keeps at least 8 tiles of 16 tokens
-    S = (512 + c->U / 2) / c->U;
     const int tiles = c->k * ((c->P + 15) / 16);
-    const int cap = (tiles + 7) / 8;
-    if (S > cap) S = cap;
+    if (c->tiled) {
+      // the MFMA kernel runs one 512-thread workgroup per CU: about one workgroup per CU in the
+      // grid, every wave keeping at least two tiles of 16 tokens
+      S = (c->n_cus + c->U / 2) / c->U;
+      if (S > tiles / 16) S = tiles / 16;
+    } else {
+      // the VALU kernel: one round of resident 256-thread workgroups, 8 tiles each at least
+      S = (512 + c->U / 2) / c->U;
+      if (S > (tiles + 7) / 8) S = (tiles + 7) / 8;
+    }
     if (S > KVD_MAX_SPLITS) S = KVD_MAX_SPLITS;
     if (S < 1) S = 1;
   }
   if (S > c->k) S = c->k;
   c->S = S;
-  // the one-launch step has 8 waves per attention workgroup and gains from twice as many
-  // workgroups (units become ready one after another) as long as a wave keeps 4 tiles or more
   // The one-launch step runs one workgroup per CU: 512 threads with 256 registers per lane (three
   // tile buffers in the attention role), or, for units of more than 8192 pages, 1024 threads with
   // 128.  Its attention splits: about one workgroup per CU in the first form (at least two tiles

@@ -23,10 +23,13 @@ __global__ __launch_bounds__(kAttnThreads) void combine_kernel(AttnArgs a) {
   merge_splits<G, kAttnThreads, false>(a, blockIdx.x + a.u0);
 }
 
+// 512 threads and up to 256 registers per lane: one workgroup per CU, three tile buffers (24 KiB)
+// in flight per wave; the grid is sized to about one workgroup per CU (see kvd_create).
+constexpr int kAttnMfmaThreads = 512;
 template <bool BF16, int G>
-__global__ __launch_bounds__(kAttnThreads) void attend_mfma_kernel(AttnArgs a) {
-  __shared__ AttnSmem<G, kAttnWaves> sm;
-  attend_mfma_body<BF16, G, kAttnThreads, false>(a, sm, blockIdx.y + a.u0, blockIdx.x);
+__global__ __launch_bounds__(kAttnMfmaThreads, 2) void attend_mfma_kernel(AttnArgs a) {
+  __shared__ AttnSmem<G, kAttnMfmaThreads / kWave> sm;
+  attend_mfma_body<BF16, G, kAttnMfmaThreads, false>(a, sm, blockIdx.y + a.u0, blockIdx.x);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -165,7 +168,7 @@ __global__ __launch_bounds__(kAttnThreads) void attend_valu_kernel(AttnArgs a) {
 template <bool BF16, int G>
 static void launch_attend(bool tiled, const AttnArgs& a, dim3 grid, hipStream_t s, hipEvent_t between) {
   if (tiled)
-    hipLaunchKernelGGL((attend_mfma_kernel<BF16, G>), grid, dim3(kAttnThreads), 0, s, a);
+    hipLaunchKernelGGL((attend_mfma_kernel<BF16, G>), grid, dim3(kAttnMfmaThreads), 0, s, a);
   else
     hipLaunchKernelGGL((attend_valu_kernel<BF16, G>), grid, dim3(kAttnThreads), 0, s, a);
   if (between != nullptr) (void)hipEventRecord(between, s);   // no kernel follows when the merge is fused
