@@ -201,8 +201,7 @@ hipError_t kvd_launch_step(kvd_ctx* c, int layer, int step, const void* q, float
   const int chunk_pages = threads;                    // a scoring chunk: every wave 64 pages x passes
   // Scoring workgroups are persistent: one round of resident workgroups minus the slots left to
   // the selection workgroups that run beside them.  passes is chosen so that the chunks of the
-  // layer fill whole rounds of the scoring workgroups (time ~ rounds x passes), finer chunks
-  // winning ties.
+  // layer fill whole rounds of the scoring workgroups (time ~ rounds x passes).
   const int slots = c->n_cus;
   int reserve = slots / 8;
   if (reserve > c->U) reserve = c->U;
@@ -214,7 +213,9 @@ hipError_t kvd_launch_step(kvd_ctx* c, int layer, int step, const void* q, float
     const long long chunks = (c->NP + (long long)chunk_pages * passes - 1) / ((long long)chunk_pages * passes);
     const long long rounds = (chunks * c->U + n_score - 1) / n_score;
     const long long cost = rounds * passes;
-    if (best_cost < 0 || cost < best_cost) { best_cost = cost; best_passes = passes; }
+    // (at equal cost the coarser chunk wins while every scoring workgroup still gets one: fewer
+    // reports and acknowledgement waits per byte)
+    if (best_cost < 0 || cost < best_cost || (cost == best_cost && chunks * c->U >= n_score)) { best_cost = cost; best_passes = passes; }
   }
   a.passes = best_passes;
   a.chunks = (c->NP + chunk_pages * a.passes - 1) / (chunk_pages * a.passes);
