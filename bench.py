@@ -38,7 +38,7 @@ HBM_PEAK_GBPS = 8000.0
 HOST_LINK_PEAK_GBPS = 63.0      # PCIe Gen5 x16, one direction: 32 GT/s x 16 lanes x 128/130
 # HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this command, scaled by
 # what the same counters read for a plain copy of known size (profiles/pmc_traffic_cfg3.md)
-PMC_TRAFFIC_BYTES = {("cfg3", "step"): 552749056, ("cfg3", "attend"): 271947776, ("cfg3", "score"): 273769472}
+PMC_TRAFFIC_BYTES = {("cfg3", "step"): 552530944, ("cfg3", "attend"): 270542848, ("cfg3", "score"): 273769472}
 
 
 def describe(w) -> str:
