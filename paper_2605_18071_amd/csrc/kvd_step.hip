@@ -6,7 +6,8 @@
 // The grid is one-dimensional and ordered so that a workgroup depends only on workgroups with a
 // lower index:
 //     n_score persistent scoring workgroups, which take the layer's scoring chunks in turn, unit
-//     by unit, so that the units' scores complete in unit order while scoring goes on;
+//     by unit, so that the units' scores complete a round of scoring workgroups at a time, in unit
+//     order, while scoring goes on;
 //     then one selection workgroup per unit;
 //     then S attention workgroups per unit.
 // A selection workgroup waits until the unit's scoring waves have all arrived (a counter);
@@ -20,11 +21,11 @@
 //
 // Workgroups of one launch may sit on different XCDs with separate L2 caches.  Everything that
 // crosses workgroups inside the launch (scores, the selection and its slots, fetched pages, split
-// partials) is therefore written with device-scope write-through stores, and a flag is raised
-// (or an entry published) only after those stores have been acknowledged; counters, scores, the
-// entries and the partials are read with device-scope loads.  Fetched pages are read with ordinary loads: no workgroup of
-// the launch touches a slot before the page's entry has been published, so no cache can hold an
-// older copy.
+// partials) is therefore written with device-scope write-through stores, and a counter is raised
+// or an entry published only after those stores have been acknowledged; counters, scores, the
+// entries and the partials are read with device-scope loads.  Fetched pages are read with
+// ordinary loads: no workgroup of the launch touches a slot before the page's entry has been
+// published, so no cache can hold an older copy.
 #include "kvd_attn_body.h"
 #include "kvd_device.h"
 #include "kvd_internal.h"
@@ -43,7 +44,7 @@ struct StepArgs {
   float* scores;             // [U][NP]
   FastArgs fa;
   AttnArgs at;
-  int32_t* score_done;       // [U][32] (one line per unit) scoring waves of the unit that have arrived (8 per chunk); zero between launches
+  int32_t* score_done;       // [U][32] (one line per unit) scoring waves of the unit that have arrived (one per wave of the workgroup and chunk); zero between launches
   int32_t* error;            // host-visible; set when a wait runs out
   long long* timeline;       // [workgroups][5]: wall-clock ticks at start, wait over, work done, exit; then a tag; or null
   long long wait_limit;      // ticks of the 100 MHz wall clock
