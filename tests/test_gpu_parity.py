@@ -338,6 +338,49 @@ def test_step_parity_one_attention_split_per_unit(mb):
     rig.close()
 
 
+@pytest.mark.parametrize("seed", list(range(32)))
+def test_one_launch_equals_chain_on_random_shapes(seed):
+    """Seeded random shapes (pages, page size, heads, budget, window, policy, ragged lengths): the
+    one-launch step and the chain of kernels, fed the same queries from the same cold start, must
+    give the same scores, selections, traces and slots at every step, and the same outputs up to
+    the fp32 summation order of the attention.  (Either form is checked against the oracle
+    elsewhere; this one covers many shapes quickly.)"""
+    rng = np.random.default_rng(9100 + seed)
+    page = int(rng.choice([16, 32, 64]))
+    n_pages = int(rng.choice([40, 257, 1000, 2048, 4100, 8192, 9000]))
+    hkv = int(rng.choice([1, 2, 4]))
+    group = int(rng.choice([1, 2, 4, 7, 8]))
+    k = int(rng.integers(1, min(n_pages // 2, 200) + 1))
+    cap = int(min(n_pages, k + rng.integers(0, 3 * k + 2)))
+    kw = dict(ctx=page * n_pages, page=page, n_kv_heads=hkv, n_q_heads=hkv * group, dtype=str(rng.choice(["bf16", "f16"])),
+              topk_pages=k, capacity=cap, batch=int(rng.choice([1, 2, 3])), policy=str(rng.choice(["lru", "lookahead"])),
+              sink_pages=int(rng.integers(0, 2)) if k > 4 else 0, recent_pages=int(rng.integers(0, 3)) if k > 4 else 0,
+              heavy_count=min(5, n_pages // 8), steps=5, seed=500 + seed)
+    w = small("rand", **kw)
+    seq = [int(w.ctx - rng.integers(0, 3 * page)) for _ in range(w.batch)]
+    a = R.Rig(w, seq_lens=seq, micro_batches=-1)
+    b = R.Rig(w, seq_lens=seq, micro_batches=1, build_index=False)
+    b.summaries.copy_(a.summaries)
+    assert a.kvd.step_form() == -1 and b.kvd.step_form() == 1
+    for t, q in enumerate(W.query_stream(w, a.q0, w.steps, R.DEV)):
+        a.step(0, t, q[0])
+        b.step(0, t, q[0])
+        assert np.array_equal(a.n_scores, b.n_scores), (kw, t)
+        assert np.array_equal(a.n_sel_pages, b.n_sel_pages), (kw, t)
+        assert np.array_equal(a.n_hit_mask, b.n_hit_mask), (kw, t)
+        assert np.array_equal(a.n_sel_slots, b.n_sel_slots), (kw, t)
+        assert np.array_equal(np.sort(a.n_evicted, axis=1), np.sort(b.n_evicted, axis=1)), (kw, t)
+        assert np.array_equal(a.n_counts, b.n_counts), (kw, t)
+        # (fp16 probabilities enter the P.V product with 11 mantissa bits, rounded against each split's own running maximum)
+        assert H.attn_rel_err(a.n_out, b.n_out) <= (1e-5 if w.dtype == "bf16" else 5e-4), (kw, t)
+        assert np.abs(a.n_lse - b.n_lse).max() <= 1e-4, (kw, t)
+    sa, _ = a.kvd.cache_export(0)
+    sb, _ = b.kvd.cache_export(0)
+    assert torch.equal(sa, sb), kw
+    a.close()
+    b.close()
+
+
 @pytest.mark.parametrize("mb", [-1, 1], ids=["single-launch", "kernel-chain"])
 @pytest.mark.parametrize("cfg", [1, 2, 3, 4, 5])
 def test_step_parity_scaled_configs(cfg, mb):
