@@ -23,7 +23,7 @@
 // library, which takes it where it has measured faster than the chain of kernels: enough units to
 // keep its pipeline filled.
 static bool kvd_wants_single_launch(const kvd_ctx* c) {
-  if (!kvd_single_launch_ok(c) || c->Nc > 0) return false;
+  if (!kvd_single_launch_ok(c)) return false;
   if (c->cfg.micro_batches == -1) return true;
   return c->cfg.micro_batches == 0 && c->U >= 32;
 }
@@ -700,7 +700,7 @@ int kvd_set_profiling(kvd_ctx* ctx, int32_t on) {
 int kvd_set_step_form(kvd_ctx* ctx, int32_t form) {
   if (!ctx) return KVD_ERR_ARG;
   if (form < -1 || form > KVD_MAX_MICRO) return KVD_ERR_SHAPE;
-  if (form == -1 && (!kvd_single_launch_ok(ctx) || ctx->Nc > 0)) return KVD_ERR_SHAPE;
+  if (form == -1 && !kvd_single_launch_ok(ctx)) return KVD_ERR_SHAPE;
   HIP_TRY(ctx, hipDeviceSynchronize());
   ctx->cfg.micro_batches = form;
   ctx->MB = form < 1 ? 1 : form;
@@ -724,7 +724,7 @@ int kvd_calibrate_step_form(kvd_ctx* ctx, int32_t layer, int32_t first_step, con
   bool runs[4];
   double total_ms[4] = {0.0, 0.0, 0.0, 0.0};
   for (int ci = 0; ci < 4; ++ci)
-    runs[ci] = !((candidates[ci] == -1 && (!kvd_single_launch_ok(ctx) || ctx->Nc > 0)) || candidates[ci] > ctx->B);
+    runs[ci] = !((candidates[ci] == -1 && !kvd_single_launch_ok(ctx)) || candidates[ci] > ctx->B);
   // Every form runs two blocks of steps, enqueued back to back as in real use: the forms in order,
   // then in reverse order, so that a drift of the workload over the calibration (a cache still
   // warming up, say) weighs on all forms alike.  The first step of a block is not timed (first use

@@ -8,7 +8,8 @@
 //     n_score persistent scoring workgroups, which take the layer's scoring chunks in turn, unit
 //     by unit, so that the units' scores complete a round of scoring workgroups at a time, in unit
 //     order, while scoring goes on;
-//     then one selection workgroup per unit;
+//     then one selection workgroup per unit (with the hierarchical index it scores nothing itself:
+//     the scoring workgroups score the centroids and it expands the best clusters into pages);
 //     then S attention workgroups per unit.
 // A selection workgroup waits until the unit's scoring waves have all arrived (a counter);
 // an attention workgroup waits until the entries of its split have been published by the unit's
@@ -27,6 +28,7 @@
 // ordinary loads: no workgroup of the launch touches a slot before the page's entry has been
 // published, so no cache can hold an older copy.
 #include "kvd_attn_body.h"
+#include "kvd_cluster_body.h"
 #include "kvd_device.h"
 #include "kvd_internal.h"
 #include "kvd_score_body.h"
@@ -39,9 +41,11 @@ constexpr int kStepThreads = 512;            // 256 registers per lane: three ti
 constexpr int kStepThreadsWide = 1024;       // 128 registers per lane: units of more pages than 512 threads keep in registers
 
 struct StepArgs {
-  const uint16_t* summ;      // [U][NP][D] of the layer
+  const uint16_t* summ;      // [U][score_np][D] of the layer: the page summaries, or the centroids of the hierarchical index
   const uint16_t* q;         // [B][Hq][D]
-  float* scores;             // [U][NP]
+  float* scores;             // [U][score_np]
+  const int32_t* cluster_start;  // [U][Nc+1] of the layer, hierarchical index only
+  const int32_t* cluster_pages;  // [U][NP]
   FastArgs fa;
   AttnArgs at;
   int32_t* score_done;       // [U][32] (one line per unit) scoring waves of the unit that have arrived (one per wave of the workgroup and chunk); zero between launches
@@ -50,13 +54,17 @@ struct StepArgs {
   long long wait_limit;      // ticks of the 100 MHz wall clock
   float scale;
   int n_units, u0, chunks, passes, n_score;
+  int score_np;              // rows scored per unit: NP, or the number of centroids Nc
+  int Nc;                    // 0 = flat page index
 };
 
 template <int NT>
 struct StepSmem {
   typedef AttnSmem<KVD_MAX_GROUP, NT / kWave> Attn;
   typedef FastSmem<NT> Fast;
-  static constexpr size_t bytes = sizeof(Attn) > sizeof(Fast) ? sizeof(Attn) : sizeof(Fast);
+  typedef ClusterSelectSmem<NT> Cluster;               // (used before Fast by the same workgroup)
+  static constexpr size_t bytes_af = sizeof(Attn) > sizeof(Fast) ? sizeof(Attn) : sizeof(Fast);
+  static constexpr size_t bytes = bytes_af > sizeof(Cluster) ? bytes_af : sizeof(Cluster);
 };
 
 // The three roles read the launch arguments from the kernel-argument segment (constant address
@@ -68,10 +76,10 @@ constexpr int kFlagStride = 32;   // ints between the flags of two units: one 12
 template <bool BF16, int NT>
 __device__ __forceinline__ void step_score_role(StepArgsPtr ap, int wg, long long* ts) {
   struct { const uint16_t* summ; const uint16_t* q; float* scores; int32_t* score_done; float scale;
-           int n_units, chunks, n_score, u0, passes; struct { int Hkv, NP; } fa; struct { int Hq, G; } at; } a;
+           int n_units, chunks, n_score, u0, passes; struct { int Hkv, NP; } fa; struct { int Hq, G; } at; } a;   // (fa.NP: rows scored per unit)
   a.summ = ap->summ; a.q = ap->q; a.scores = ap->scores; a.score_done = ap->score_done; a.scale = ap->scale;
   a.n_units = ap->n_units; a.chunks = ap->chunks; a.n_score = ap->n_score; a.u0 = ap->u0; a.passes = ap->passes;
-  a.fa.Hkv = ap->fa.Hkv; a.fa.NP = ap->fa.NP; a.at.Hq = ap->at.Hq; a.at.G = ap->at.G;
+  a.fa.Hkv = ap->fa.Hkv; a.fa.NP = ap->score_np; a.at.Hq = ap->at.Hq; a.at.G = ap->at.G;
   const int tid = threadIdx.x;
   const int w = tid / kWave, lane = tid & (kWave - 1);
   if (ts) ts[4] = 0LL | ((long long)wg << 32);
@@ -109,7 +117,22 @@ __device__ __forceinline__ void step_select_role(StepArgsPtr ap, int u, unsigned
     if (ok && tid == 0) store_agent(&a.score_done[u * kFlagStride], 0);   // every arrival has been seen: ready for the next launch
     return ok;
   };
-  if (!select_resolve_body<NT, IPT, true, true, true>(a.fa, u, sm, scores_ready)) {
+  bool done;
+  if (ap->Nc > 0) {
+    // hierarchical index: the scores are those of the centroids; clusters -> pages, then the
+    // directory update and the fetch for the pages
+    done = scores_ready();
+    if (done) {
+      typename StepSmem<NT>::Cluster& cs = *reinterpret_cast<typename StepSmem<NT>::Cluster*>(smem_raw);
+      cluster_select_body<NT, true>(a.fa.scores, ap->cluster_start, ap->cluster_pages, a.fa.sel_pages, a.fa.seq_len, a.fa.NP,
+                                    ap->Nc, a.fa.P, a.fa.k, a.fa.sink, a.fa.recent, a.fa.Hkv, u, cs);
+      __syncthreads();                                 // the selection is complete; the cluster tables are dead
+      done = select_resolve_body<NT, 4, false, true, true>(a.fa, u, sm);
+    }
+  } else {
+    done = select_resolve_body<NT, IPT, true, true, true>(a.fa, u, sm, scores_ready);
+  }
+  if (!done) {
     if (tid == 0) __hip_atomic_store(a.error, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
     return;
   }
@@ -179,7 +202,12 @@ bool kvd_single_launch_ok(const kvd_ctx* c) {
 hipError_t kvd_launch_step(kvd_ctx* c, int layer, int step, const void* q, float* out, float* lse, hipStream_t s) {
   using namespace kvd;
   StepArgs a;
-  a.summ = reinterpret_cast<const uint16_t*>(c->summaries) + (size_t)layer * c->U * c->NP * kHeadDim;
+  const int score_np = c->Nc > 0 ? c->Nc : c->NP;
+  a.summ = reinterpret_cast<const uint16_t*>(c->Nc > 0 ? c->centroids : c->summaries) + (size_t)layer * c->U * score_np * kHeadDim;
+  a.score_np = score_np;
+  a.Nc = c->Nc;
+  a.cluster_start = c->Nc > 0 ? c->cluster_start + (size_t)layer * c->U * (c->Nc + 1) : nullptr;
+  a.cluster_pages = c->Nc > 0 ? c->cluster_pages + (size_t)layer * c->U * c->NP : nullptr;
   a.q = reinterpret_cast<const uint16_t*>(q);
   a.scores = c->d_scores;
   a.fa = kvd_fast_args(c, layer, step, true, c->d_scores, c->d_sel_pages, c->d_sel_slots, c->d_hit_mask, c->d_evicted,
@@ -211,7 +239,7 @@ hipError_t kvd_launch_step(kvd_ctx* c, int layer, int step, const void* q, float
   int best_passes = 1;
   long long best_cost = -1;
   for (int passes = 1; passes <= 8; ++passes) {
-    const long long chunks = (c->NP + (long long)chunk_pages * passes - 1) / ((long long)chunk_pages * passes);
+    const long long chunks = (score_np + (long long)chunk_pages * passes - 1) / ((long long)chunk_pages * passes);
     const long long rounds = (chunks * c->U + n_score - 1) / n_score;
     const long long cost = rounds * passes;
     // (at equal cost the coarser chunk wins while every scoring workgroup still gets one: fewer
@@ -219,7 +247,7 @@ hipError_t kvd_launch_step(kvd_ctx* c, int layer, int step, const void* q, float
     if (best_cost < 0 || cost < best_cost || (cost == best_cost && chunks * c->U >= n_score)) { best_cost = cost; best_passes = passes; }
   }
   a.passes = best_passes;
-  a.chunks = (c->NP + chunk_pages * a.passes - 1) / (chunk_pages * a.passes);
+  a.chunks = (score_np + chunk_pages * a.passes - 1) / (chunk_pages * a.passes);
   if (n_score > c->U * a.chunks) n_score = c->U * a.chunks;
   a.n_score = n_score;
   const int n_blocks = a.n_score + c->U + c->U * c->S1;

@@ -686,6 +686,10 @@ def test_lookahead_exact_ties_drop_the_higher_page():
     (2, 0, dict(index_iterations=2)),                                 # 3 layers, planted heavy pages
     (4, 1, dict()),                                                   # fp16, G = 7, page 32
     (5, 1, dict()),                                                   # page 64, recent pages forced and pre-warmed
+    (3, -1, dict()),                                                  # the same through the one-launch step
+    (4, -1, dict()),
+    (5, -1, dict()),
+    (2, -1, dict(index_iterations=2)),
 ])
 def test_hierarchical_index_build_and_step_parity(cfg, mb, kw):
     """k-means build (assignments of every round, centroids, cluster lists) and decode steps whose
@@ -693,7 +697,7 @@ def test_hierarchical_index_build_and_step_parity(cfg, mb, kw):
     w = SCALED[cfg]
     w = w.replace(**{**dict(index_centroids=w.n_pages // 2, index_iterations=3), **kw})
     rig = R.Rig(w, micro_batches=mb)
-    assert rig.kvd.step_form() != -1                                 # the centroid index runs as a chain of kernels
+    assert (rig.kvd.step_form() == -1) == (mb == -1)
     units = all_units(rig)                                            # builds and checks the index of every unit
     assert sum(ou.kmeans_divergences for ou in units) <= 4
     rep = R.run_steps(rig, units, w.steps, check_dir_every=3, progress=f"cfg{cfg}-hier-mb{mb}")
@@ -702,7 +706,8 @@ def test_hierarchical_index_build_and_step_parity(cfg, mb, kw):
     rig.close()
 
 
-@pytest.mark.parametrize("cfg,mb,generic", [(3, 1, False), (3, 2, False), (5, 1, False), (2, 1, True)])
+@pytest.mark.parametrize("cfg,mb,generic", [(3, 1, False), (3, 2, False), (5, 1, False), (2, 1, True), (3, -1, False),
+                                            (5, -1, False), (2, -1, False)])
 def test_lookahead_eviction_under_the_hierarchical_index(cfg, mb, generic, monkeypatch):
     """The paper's own combination: selection through the centroids, victims by the lowest
     current-step score — here the score of the page's cluster.  Small windows, so that nearly every
