@@ -99,7 +99,7 @@ typedef struct {
                               the Nc centroids and takes whole clusters, best first, until k pages are used
                               (the first cluster that does not fit gives its lowest pages; sink / recent pages
                               are in first and do not count as members).  Nc <= 8192, Nc <= max_pages <= 16384;
-                              kvd_step then runs as a chain of kernels.  Under KVD_EVICT_LOOKAHEAD the score
+                              kvd_step runs in any of its forms.  Under KVD_EVICT_LOOKAHEAD the score
                               of a resident page is the score of its cluster (a page of no cluster leaves
                               first; pages of one cluster: the higher page first). */
 } kvd_config;
