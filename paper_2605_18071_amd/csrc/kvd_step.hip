@@ -185,6 +185,8 @@ static void launch_step(int threads, int ipt, const StepArgs& a, int n_blocks, h
       hipLaunchKernelGGL((step_kernel<BF16, kStepThreadsWide, 8>), grid, block, 0, s, a);
     else
       hipLaunchKernelGGL((step_kernel<BF16, kStepThreadsWide, 16>), grid, block, 0, s, a);
+  } else if (ipt <= 4) {
+    hipLaunchKernelGGL((step_kernel<BF16, kStepThreads, 4>), grid, block, 0, s, a);
   } else if (ipt <= 8) {
     hipLaunchKernelGGL((step_kernel<BF16, kStepThreads, 8>), grid, block, 0, s, a);
   } else {
