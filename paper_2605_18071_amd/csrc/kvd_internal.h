@@ -26,7 +26,7 @@ struct kvd_ctx {
   kvd_config cfg;
   int L, B, Hq, Hkv, G, D, P, NP, k, Cmax, Lp, U, MB, S;
   int S1;                  // attention split-K factor of the one-launch step (S: of the stand-alone kernel)
-  int step_threads;        // workgroup size of the one-launch step: 512 (two per CU) or 1024 (one per CU)
+  int step_threads;        // workgroup size of the one-launch step: one per CU; 512 (256 registers per lane) or 1024 (128 registers)
   int Nc;                  // centroids per unit of the hierarchical index, 0 = flat page index
   int bf16;
   int score_blocks;        // target number of blocks of a scoring launch
