@@ -93,6 +93,66 @@ def cpu_baseline(w, store, q_list, seconds: float):
     }
 
 
+def layers_in_flight(args, cfg_w, K, W, torch, dev):
+    """The configuration's layer-step over `--layers` layers of one decode step, layers one by one
+    (kvd_step per layer) against two layers in flight (kvd_step_layers): end-to-end ms per
+    layer-step including the fetch of missed pages, cold start, the first `warmup` decode steps
+    untimed."""
+    n = args.layers
+    w = cfg_w.replace(n_layers=n, physical_layers=min(n, 2), policy=args.policy)
+    L, B, Hkv, NP, P, D = w.n_layers, w.batch, w.n_kv_heads, w.n_pages, w.page, w.head_dim
+    q0 = W.initial_queries(w, dev)
+    store = W.make_kv_store(w, q0, dev)
+    summ = torch.zeros((L, B, Hkv, NP, D), dtype=w.torch_dtype, device=dev)
+    pool = torch.zeros((L, B, Hkv, w.capacity, 2, P, D), dtype=w.torch_dtype, device=dev)
+    steps, warm = max(2, args.steps // n), max(4, args.warmup)
+    qs = [q.contiguous() for q in W.query_stream(w, q0, warm + steps, dev)]
+    out = torch.empty((L, B, w.n_q_heads, D), dtype=torch.float32, device=dev)
+    res = {"what": f"{L} layers of one decode step (host store of {w.phys_layers} layers shared by them), {steps} timed decode "
+                   f"steps after {warm} from a cold cache: end-to-end ms per layer-step", "layers": L}
+    keep = None
+    for mode in ("one_by_one", "two_in_flight"):
+        ctx = K.Kvd(n_layers=L, batch=B, n_q_heads=w.n_q_heads, n_kv_heads=Hkv, page_size=P, max_pages=NP,
+                    topk_pages=w.topk_pages, capacity_max=w.capacity, kv_dtype=w.torch_dtype, sink_pages=w.sink_pages,
+                    recent_pages=w.recent_pages, physical_layers=w.physical_layers, micro_batches=args.micro_batches,
+                    policy=w.policy)
+        ctx.bind_summaries(summ)
+        ctx.bind_host_store(store)
+        ctx.bind_slot_pool(pool)
+        for l in range(L):
+            ctx.build_summaries(l)
+        pages = W.warm_pages(w)
+        if pages is not None:
+            for l in range(L):
+                ctx.cache_warm(l, pages.tolist() * w.units, [len(pages)] * w.units)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        for t, q in enumerate(qs):
+            if t == warm:
+                torch.cuda.synchronize()
+                ctx.reset_stats()
+                e0.record()
+            if mode == "one_by_one":
+                for l in range(L):
+                    ctx.step(l, t, q[l], out[l])
+            else:
+                ctx.step_layers(0, L, t, q, out)
+        e1.record()
+        torch.cuda.synchronize()
+        ms = e0.elapsed_time(e1) / (steps * L)
+        st = ctx.stats()
+        res[mode] = {"ms_per_layer_step": ms, "layer_steps_per_s": 1e3 / ms,
+                     "host_link_GBps": st.gathered_bytes / (steps * L) / (ms * 1e-3) / 1e9,
+                     "hit_rate": st.hits / max(1, st.hits + st.misses)}
+        res["step_form"] = ctx.step_form()
+        if keep is None:
+            keep = out.clone()
+        else:
+            res["max_abs_output_difference"] = float((out - keep).abs().max())
+        ctx.close()
+    return res
+
+
 def _max_clock_mhz():
     """Peak engine clock from the HIP runtime that torch has already loaded (torch does not expose it)."""
     import ctypes
@@ -158,6 +218,8 @@ def main() -> int:
     ap.add_argument("--tier-buffered", action="store_true", help="read through the page cache instead of O_DIRECT")
     ap.add_argument("--tier-layout", choices=["page", "semantic"], default="page",
                     help="order of a unit's pages in the file: page order, or cluster by cluster (needs --centroids)")
+    ap.add_argument("--layers", type=int, default=1, metavar="N",
+                    help="N > 1: add a leg that steps N layers per decode step, one by one and two in flight (kvd_step_layers)")
     ap.add_argument("--timeline", action="store_true",
                     help="when the step runs as one launch: add the per-workgroup timeline of one all-hit step")
     args = ap.parse_args()
@@ -177,6 +239,7 @@ def main() -> int:
     dev = "cuda:0"
     torch.cuda.set_device(0)
     w = W.CONFIGS[args.config]
+    cfg_w = w
     if w.n_layers != 1:
         # multi-layer configurations are benchmarked on one layer's worth of state at full per-layer shape
         w = w.replace(n_layers=1, physical_layers=1)
@@ -399,6 +462,9 @@ def main() -> int:
 
     if args.timeline and single and not args.no_profile_pass:
         result["timeline"] = step_timeline(ctx, base + t, q_last, out, stream)
+
+    if args.layers > 1:
+        result["layers_in_flight"] = layers_in_flight(args, cfg_w, K, W, torch, dev)
 
     if args.cpu_seconds > 0:
         q_cpu = [q.cpu() for q in queries[:16]]

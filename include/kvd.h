@@ -256,6 +256,25 @@ int kvd_advance(kvd_ctx* ctx, void* stream);
  *   q [B][Hq][D] kv_dtype, out [B][Hq][D] fp32, lse [B][Hq] fp32 or NULL. */
 int kvd_step(kvd_ctx* ctx, int32_t layer, int32_t step, const void* q, float* out, float* lse, void* stream);
 
+/* The same layer-step for the consecutive layers [layer0, layer0 + n_layers) of one decode step,
+ * for a caller that has all their queries at hand (a benchmark, or a model that computes the
+ * queries of several layers before their attention; layers whose query depends on the previous
+ * layer's attention output are stepped one by one with kvd_step).  Two layers are kept in flight:
+ * layers alternate between `stream` and one of the library's streams (forked from and joined back
+ * into `stream`), each with its own per-step scratch, so that the host-link fetch of one layer's
+ * missed pages overlaps the scoring, selection and attention of the next (SFC Disaggregation
+ * applied across layers; every layer has its own cache directory and slots, so the results are
+ * those of the layers stepped one after another).  Each layer runs as one launch or as the plain
+ * chain of kernels, whichever kvd_step_form says; groups of sequences (micro_batches > 1) are not
+ * formed here.  With profiling on, or in a context of one layer, the layers simply run one after
+ * another on `stream`.  (Three and four layers in flight measured no faster than two.)
+ *   q_layers [n_layers][B][Hq][D] kv_dtype, out_layers [n_layers][B][Hq][D] fp32,
+ *   lse_layers [n_layers][B][Hq] fp32 or NULL (all device, 16-byte aligned).
+ * kvd_step_trace afterwards reports the last of the layers.  Errors as kvd_step; KVD_ERR_ARG when
+ * the layer range leaves the context's. */
+int kvd_step_layers(kvd_ctx* ctx, int32_t layer0, int32_t n_layers, int32_t step, const void* q_layers,
+                    float* out_layers, float* lse_layers, void* stream);
+
 /* Copies what the last kvd_step left behind into caller buffers (all dev, any may be NULL),
  * asynchronously on `stream` (which must be ordered after that kvd_step): sel_pages, sel_slots,
  * hit_mask, evicted [B][Hkv][k] int32, counts [B][Hkv][3] int32, scores [B][Hkv][NP] fp32. */

@@ -71,6 +71,14 @@ static void free_ctx(kvd_ctx* c) {
                  c->d_score_done, c->d_sel_entry, c->d_timeline};
   for (void* p : dev)
     if (p) (void)hipFree(p);
+  for (int i = 0; i < c->n_sets; ++i) {
+    if (i == c->cur_set) continue;                     // (that one is in the d_* fields)
+    const kvd_scratch& x = c->sets[i];
+    void* more[] = {x.scores, x.sel_pages, x.sel_slots, x.hit_mask, x.evicted, x.counts, x.miss_list, x.miss_count,
+                    x.part_acc, x.part_ml, x.attn_ticket, x.score_done, x.sel_entry};
+    for (void* p : more)
+      if (p) (void)hipFree(p);
+  }
   for (int i = 0; i < KVD_MAX_MICRO; ++i) {
     if (c->ev_score[i]) (void)hipEventDestroy(c->ev_score[i]);
     if (c->ev_done[i]) (void)hipEventDestroy(c->ev_done[i]);
@@ -114,6 +122,23 @@ static hipError_t ensure_group_resources(kvd_ctx* c, int groups) {
 template <class T>
 static hipError_t dev_alloc(T** p, size_t count) {
   return hipMalloc(reinterpret_cast<void**>(p), (count ? count : 1) * sizeof(T));
+}
+
+// Makes scratch set `set` the one in the context's d_* fields.  Kernel arguments are taken at
+// launch, so launches already enqueued keep the set they were given.
+static void use_scratch_set(kvd_ctx* c, int set) {
+  if (set == c->cur_set) return;
+  kvd_scratch& o = c->sets[c->cur_set];
+  o.scores = c->d_scores; o.sel_pages = c->d_sel_pages; o.sel_slots = c->d_sel_slots; o.hit_mask = c->d_hit_mask;
+  o.evicted = c->d_evicted; o.counts = c->d_counts; o.miss_list = c->d_miss_list; o.miss_count = c->d_miss_count;
+  o.part_acc = c->d_part_acc; o.part_ml = c->d_part_ml; o.attn_ticket = c->d_attn_ticket; o.score_done = c->d_score_done;
+  o.sel_entry = c->d_sel_entry;
+  const kvd_scratch& x = c->sets[set];
+  c->d_scores = x.scores; c->d_sel_pages = x.sel_pages; c->d_sel_slots = x.sel_slots; c->d_hit_mask = x.hit_mask;
+  c->d_evicted = x.evicted; c->d_counts = x.counts; c->d_miss_list = x.miss_list; c->d_miss_count = x.miss_count;
+  c->d_part_acc = x.part_acc; c->d_part_ml = x.part_ml; c->d_attn_ticket = x.attn_ticket; c->d_score_done = x.score_done;
+  c->d_sel_entry = x.sel_entry;
+  c->cur_set = set;
 }
 
 static int reset_directory(kvd_ctx* c, int layer_or_all) {
@@ -236,7 +261,26 @@ int kvd_create(const kvd_config* cfg, kvd_ctx** out) {
       ok(hipHostMalloc(reinterpret_cast<void**>(&c->error_host), sizeof(int32_t), hipHostMallocMapped)) &&
       ok(hipHostGetDevicePointer(reinterpret_cast<void**>(&c->error_dev), c->error_host, 0)) &&
       ok(hipEventCreateWithFlags(&c->ev_fork, hipEventDisableTiming));
-  if (e == hipSuccess) ok(ensure_group_resources(c, c->MB));
+  c->n_sets = 1;
+  if (e == hipSuccess && c->L >= 2) {
+    // layers in flight (kvd_step_layers): further sets of the per-step scratch
+    const int want = c->L < KVD_LAYER_LANES ? c->L : KVD_LAYER_LANES;
+    for (int i = 1; i < want && e == hipSuccess; ++i) {
+      kvd_scratch& x = c->sets[i];
+      c->n_sets = i + 1;                               // (what was allocated of it is freed with the context)
+      ok(dev_alloc(&x.scores, (size_t)c->U * c->NP)) && ok(dev_alloc(&x.sel_pages, Uk)) && ok(dev_alloc(&x.sel_slots, Uk)) &&
+          ok(dev_alloc(&x.hit_mask, Uk)) && ok(dev_alloc(&x.evicted, Uk)) && ok(dev_alloc(&x.counts, (size_t)c->U * 3)) &&
+          ok(dev_alloc(&x.miss_list, Uk * 2)) && ok(dev_alloc(&x.miss_count, (size_t)c->U)) &&
+          ok(dev_alloc(&x.part_acc, (size_t)c->U * Smax * c->G * c->D)) && ok(dev_alloc(&x.part_ml, (size_t)c->U * Smax * c->G * 2)) &&
+          ok(dev_alloc(&x.attn_ticket, (size_t)c->U)) && ok(dev_alloc(&x.score_done, (size_t)c->U * 32)) &&
+          ok(dev_alloc(&x.sel_entry, Uk)) &&
+          ok(hipMemset(x.miss_count, 0, (size_t)c->U * sizeof(int32_t))) &&
+          ok(hipMemset(x.attn_ticket, 0, (size_t)c->U * sizeof(int32_t))) &&
+          ok(hipMemset(x.score_done, 0, (size_t)c->U * 32 * sizeof(int32_t))) &&
+          ok(hipMemset(x.sel_entry, 0, Uk * sizeof(unsigned long long)));
+    }
+  }
+  if (e == hipSuccess) ok(ensure_group_resources(c, c->n_sets > c->MB ? c->n_sets : c->MB));
   for (int i = 0; i < 12 && e == hipSuccess; ++i) ok(hipEventCreate(&c->ev_prof[i]));
   if (e == hipSuccess) ok(hipMemcpy(c->d_capacity, c->h_capacity, LU * sizeof(int32_t), hipMemcpyHostToDevice));
   if (e == hipSuccess) ok(hipMemcpy(c->d_seq_len, c->h_seq_len, (size_t)c->B * sizeof(int32_t), hipMemcpyHostToDevice));
@@ -424,6 +468,12 @@ int kvd_cache_reset(kvd_ctx* ctx) {
   HIP_TRY(ctx, hipMemset(ctx->d_attn_ticket, 0, (size_t)ctx->U * sizeof(int32_t)));
   HIP_TRY(ctx, hipMemset(ctx->d_score_done, 0, (size_t)ctx->U * 32 * sizeof(int32_t)));
   HIP_TRY(ctx, hipMemset(ctx->d_sel_entry, 0, (size_t)ctx->U * ctx->k * sizeof(unsigned long long)));
+  for (int i = 0; i < ctx->n_sets; ++i) {
+    if (i == ctx->cur_set) continue;
+    HIP_TRY(ctx, hipMemset(ctx->sets[i].attn_ticket, 0, (size_t)ctx->U * sizeof(int32_t)));
+    HIP_TRY(ctx, hipMemset(ctx->sets[i].score_done, 0, (size_t)ctx->U * 32 * sizeof(int32_t)));
+    HIP_TRY(ctx, hipMemset(ctx->sets[i].sel_entry, 0, (size_t)ctx->U * ctx->k * sizeof(unsigned long long)));
+  }
   *ctx->error_host = 0;
   return reset_directory(ctx, -1);
 }
@@ -604,20 +654,16 @@ static int step_profiled(kvd_ctx* c, int layer, int step, const void* q, float* 
   return KVD_OK;
 }
 
-int kvd_step(kvd_ctx* ctx, int32_t layer, int32_t step, const void* q, float* out, float* lse, void* stream) {
-  if (!ctx || !q || !out || layer < 0 || layer >= ctx->L || !aligned16(q)) return KVD_ERR_ARG;
-  if (!ctx->summaries || !ctx->pool || !ctx->store_dev || (ctx->Nc > 0 && !ctx->centroids)) return KVD_ERR_STATE;
-  kvd_ctx* c = ctx;
-  hipStream_t s = static_cast<hipStream_t>(stream);
+// One layer-step in the context's current form, enqueued on s (and, with micro-batches, on the
+// library's streams, forked from and joined back into s).
+static int enqueue_step(kvd_ctx* c, int layer, int step, const void* q, float* out, float* lse, hipStream_t s, bool groups) {
   ++c->n_steps;
   c->last_scores = c->d_scores;
-  if (*c->error_host != 0) return KVD_ERR_STATE;   // an earlier single-launch step gave up waiting
-  if (c->profiling == 1) return step_profiled(c, layer, step, q, out, lse, s);
   if (c->single_launch) {
     HIP_TRY(c, kvd_launch_step(c, layer, step, q, out, lse, s));
     return KVD_OK;
   }
-  if (c->MB <= 1) {
+  if (c->MB <= 1 || !groups) {
     HIP_TRY(c, kvd_launch_score(c, layer, q, c->d_scores, 0, c->U, s));
     HIP_TRY(c, launch_select_resolve_fetch(c, layer, step, 0, c->U, s));
     HIP_TRY(c, kvd_launch_attend(c, layer, q, c->d_sel_pages, c->d_sel_slots, out, lse, 0, c->U, s));
@@ -643,6 +689,65 @@ int kvd_step(kvd_ctx* ctx, int32_t layer, int32_t step, const void* q, float* ou
   }
   for (int i = 0; i < c->MB; ++i)
     if (i % (1 + KVD_PIPE_STREAMS) != 0) HIP_TRY(c, hipStreamWaitEvent(s, c->ev_done[i], 0));
+  return KVD_OK;
+}
+
+int kvd_step(kvd_ctx* ctx, int32_t layer, int32_t step, const void* q, float* out, float* lse, void* stream) {
+  if (!ctx || !q || !out || layer < 0 || layer >= ctx->L || !aligned16(q)) return KVD_ERR_ARG;
+  if (!ctx->summaries || !ctx->pool || !ctx->store_dev || (ctx->Nc > 0 && !ctx->centroids)) return KVD_ERR_STATE;
+  kvd_ctx* c = ctx;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  if (*c->error_host != 0) return KVD_ERR_STATE;   // an earlier single-launch step gave up waiting
+  if (c->profiling == 1) {
+    ++c->n_steps;
+    c->last_scores = c->d_scores;
+    return step_profiled(c, layer, step, q, out, lse, s);
+  }
+  return enqueue_step(c, layer, step, q, out, lse, s, true);
+}
+
+int kvd_step_layers(kvd_ctx* ctx, int32_t layer0, int32_t n_layers, int32_t step, const void* q_layers, float* out_layers,
+                    float* lse_layers, void* stream) {
+  if (!ctx || !q_layers || !out_layers || layer0 < 0 || n_layers < 1 || (long long)layer0 + n_layers > ctx->L ||
+      !aligned16(q_layers))
+    return KVD_ERR_ARG;
+  if (!ctx->summaries || !ctx->pool || !ctx->store_dev || (ctx->Nc > 0 && !ctx->centroids)) return KVD_ERR_STATE;
+  kvd_ctx* c = ctx;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  if (*c->error_host != 0) return KVD_ERR_STATE;
+  const size_t rows = (size_t)c->B * c->Hq;
+  const char* q = static_cast<const char*>(q_layers);
+  auto q_of = [&](int i) { return static_cast<const void*>(q + (size_t)i * rows * c->D * 2); };
+  auto out_of = [&](int i) { return out_layers + (size_t)i * rows * c->D; };
+  auto lse_of = [&](int i) { return lse_layers ? lse_layers + (size_t)i * rows : nullptr; };
+  const int lanes = c->n_sets < n_layers ? c->n_sets : n_layers;
+  if (lanes < 2 || c->profiling != 0) {
+    for (int i = 0; i < n_layers; ++i) {
+      const int r = kvd_step(c, layer0 + i, step, q_of(i), out_of(i), lse_of(i), stream);
+      if (r != KVD_OK) return r;
+    }
+    return KVD_OK;
+  }
+  // Layer i runs in lane i % lanes: lane 0 is the caller's stream, the others are the library's,
+  // each with its own set of per-step scratch, so that the fetch of one layer's missed pages
+  // overlaps the kernels of the next ones.  Layers `lanes` apart follow each other on one stream,
+  // so a scratch set is never in use twice.
+  HIP_TRY(c, hipEventRecord(c->ev_fork, s));
+  for (int j = 1; j < lanes; ++j) HIP_TRY(c, hipStreamWaitEvent(c->side[j - 1], c->ev_fork, 0));
+  int r = KVD_OK;
+  for (int i = 0; i < n_layers && r == KVD_OK; ++i) {
+    const int lane = i % lanes;
+    use_scratch_set(c, lane);
+    r = enqueue_step(c, layer0 + i, step, q_of(i), out_of(i), lse_of(i), lane == 0 ? s : c->side[lane - 1], false);
+  }
+  // (the context keeps the scratch set of the last layer enqueued: kvd_step_trace reports that layer)
+  hipError_t e = hipSuccess;
+  for (int j = 1; j < lanes; ++j) {
+    if (e == hipSuccess) e = hipEventRecord(c->ev_done[j], c->side[j - 1]);
+    if (e == hipSuccess) e = hipStreamWaitEvent(s, c->ev_done[j], 0);
+  }
+  if (r != KVD_OK) return r;
+  HIP_TRY(c, e);
   return KVD_OK;
 }
 

@@ -13,6 +13,7 @@ constexpr int KVD_FAST_MAX_CAPACITY = 4096; // register-resident directory scan:
 constexpr int KVD_MAX_PAGE = 256;       // P
 constexpr int KVD_MAX_MICRO = 16;       // micro-batches per step
 constexpr int KVD_PIPE_STREAMS = 3;      // side streams a step may spread its micro-batches over
+constexpr int KVD_LAYER_LANES = 2;       // layers kvd_step_layers keeps in flight (three and four measured no faster)
 constexpr int KVD_MAX_SPLITS = 64;      // attention split-K factor
 constexpr int KVD_MAX_CENTROIDS = 8192;   // centroids per unit of the hierarchical index (16-bit cluster numbers, <= 65535 pages each)
 constexpr int KVD_TIMELINE_MAX = 1 << 16; // workgroups of a single-launch step whose times can be recorded
@@ -21,6 +22,15 @@ namespace kvd {
 struct FastArgs;
 struct AttnArgs;
 }  // namespace kvd
+
+// The per-step scratch of one layer-step in flight (the d_* fields of the context of the same names).
+struct kvd_scratch {
+  float* scores;
+  int32_t *sel_pages, *sel_slots, *hit_mask, *evicted, *counts, *miss_list, *miss_count;
+  float *part_acc, *part_ml;
+  int32_t *attn_ticket, *score_done;
+  unsigned long long* sel_entry;
+};
 
 struct kvd_ctx {
   kvd_config cfg;
@@ -69,6 +79,11 @@ struct kvd_ctx {
   int32_t* d_score_done;    // [U][32] single-launch step: scoring waves arrived (one 128-byte line per unit), zero between launches
   unsigned long long* d_sel_entry;  // [U][k] single-launch step: the selection as its attention workgroups read it (published bit, slot, page); zero between launches
   unsigned long long* d_stats;  // hits, misses, evictions
+  // kvd_step_layers keeps several layers in flight, each with its own set of the per-step scratch
+  // above: the d_* fields hold set `cur_set`, the others wait in `sets` (contexts of two layers
+  // and more; sets[cur_set] itself is stale)
+  kvd_scratch sets[KVD_LAYER_LANES];
+  int n_sets, cur_set;
 
   // owned, host
   int32_t* h_capacity;      // [L][U]

@@ -68,7 +68,7 @@ EXPORTS = [
     "kvd_tier_open", "kvd_tier_close", "kvd_tier_last_errno", "kvd_tier_set_layout", "kvd_tier_write_layer",
     "kvd_tier_patch_page", "kvd_tier_fetch", "kvd_tier_trace", "kvd_tier_pooled", "kvd_tier_drop_pool", "kvd_tier_get_stats",
     "kvd_tier_reset_stats", "kvd_tier_sequential_read_gbps", "kvd_layout_from_clusters", "kvd_bind_tier",
-    "kvd_step_tiered",
+    "kvd_step_tiered", "kvd_step_layers",
 ]
 
 _lib = None
@@ -106,6 +106,7 @@ def load() -> C.CDLL:
         "kvd_cache_resolve": [vp, i32, i32, vp, vp, vp, vp, vp, i32, vp],
         "kvd_sparse_decode_attn": [vp, i32, vp, vp, vp, vp, vp, vp],
         "kvd_step": [vp, i32, i32, vp, vp, vp, vp],
+        "kvd_step_layers": [vp, i32, i32, i32, vp, vp, vp, vp],
         "kvd_step_trace": [vp, vp, vp, vp, vp, vp, vp, vp],
         "kvd_set_profiling": [vp, i32],
         "kvd_step_timeline": [vp, C.POINTER(C.c_int64), i32, i32p],
@@ -292,6 +293,10 @@ class Kvd:
     def step(self, layer: int, step: int, q, out, lse=None, stream=None):
         self._check(self.lib.kvd_step(self.ctx, layer, step, q.data_ptr(), out.data_ptr(), _ptr(lse),
                                       _stream_handle(stream)), "kvd_step")
+
+    def step_layers(self, layer0: int, n_layers: int, step: int, q_layers, out_layers, lse_layers=None, stream=None):
+        self._check(self.lib.kvd_step_layers(self.ctx, layer0, n_layers, step, q_layers.data_ptr(), out_layers.data_ptr(),
+                                             _ptr(lse_layers), _stream_handle(stream)), "kvd_step_layers")
 
     def step_trace(self, sel_pages=None, sel_slots=None, hit_mask=None, evicted=None, counts=None, scores=None,
                    stream=None):

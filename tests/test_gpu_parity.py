@@ -338,6 +338,82 @@ def test_step_parity_one_attention_split_per_unit(mb):
     rig.close()
 
 
+@pytest.mark.parametrize("policy", ["lru", "lookahead"])
+@pytest.mark.parametrize("mb", [-1, 1], ids=["single-launch", "kernel-chain"])
+@pytest.mark.parametrize("n_layers,phys", [(4, 2), (3, 3)])
+def test_layers_in_flight_equal_layers_one_by_one(n_layers, phys, mb, policy):
+    """kvd_step_layers keeps two layers in flight on two streams with two scratch sets.  Every
+    layer has its own directory and slots, so scores, traces, directories and slot contents must be
+    those of the layers stepped one by one, and the outputs too (bit for bit with the chain of
+    kernels; up to the order in which the splits are merged in one launch).  The one-by-one run is
+    compared with the oracle at every layer-step."""
+    w = small("layers", n_layers=n_layers, physical_layers=phys, ctx=16 * 700, topk_pages=40, capacity=46, steps=7,
+              policy=policy, batch=3, n_kv_heads=2, n_q_heads=8)
+    a = R.Rig(w, micro_batches=mb)
+    b = R.Rig(w, micro_batches=mb, build_index=False)
+    b.summaries.copy_(a.summaries)
+    assert a.kvd.step_form() == mb and b.kvd.step_form() == mb
+    units = all_units(a)
+    by_layer = {l: [ou for ou in units if ou.layer == l] for l in range(n_layers)}
+    rep = R.StepReport()
+    L, B, Hq, D = n_layers, w.batch, w.n_q_heads, w.head_dim
+    out_l = torch.empty((L, B, Hq, D), dtype=torch.float32, device=R.DEV)
+    lse_l = torch.empty((L, B, Hq), dtype=torch.float32, device=R.DEV)
+    i32 = dict(dtype=torch.int32, device=R.DEV)
+    tr = [torch.empty((w.units, w.topk_pages), **i32) for _ in range(4)]
+    for t, q in enumerate(W.query_stream(w, a.q0, w.steps, R.DEV)):
+        outs, lses, last = [], [], None
+        for l in range(L):
+            a.step(l, t, q[l])
+            for ou in by_layer[l]:
+                R.compare_unit(a, ou, t, q[l], rep)
+            outs.append(a.n_out.copy())
+            lses.append(a.n_lse.copy())
+            last = (a.n_sel_pages.copy(), a.n_sel_slots.copy(), a.n_hit_mask.copy(), a.n_evicted.copy())
+        out_l.fill_(float("nan"))
+        if t % 2 == 0:
+            b.kvd.step_layers(0, L, t, q.contiguous(), out_l, lse_l)
+        else:                                            # a range that starts on another layer, then the rest
+            b.kvd.step(0, t, q[0], out_l[0], lse_l[0])
+            b.kvd.step_layers(1, L - 1, t, q[1:].contiguous(), out_l[1:], lse_l[1:])
+        b.kvd.step_trace(tr[0], tr[1], tr[2], tr[3])
+        torch.cuda.synchronize()
+        for l in range(L):
+            got = out_l[l].cpu().numpy()
+            if mb == 1:
+                assert np.array_equal(got, outs[l]) and np.array_equal(lse_l[l].cpu().numpy(), lses[l]), (t, l)
+            else:
+                assert H.attn_rel_err(got, outs[l]) <= 1e-5, (t, l)
+                assert np.abs(lse_l[l].cpu().numpy() - lses[l]).max() <= 1e-5, (t, l)
+            pa, sa = a.kvd.cache_export(l)
+            pb, sb = b.kvd.cache_export(l)
+            assert torch.equal(pa, pb) and torch.equal(sa, sb), (t, l)
+            assert torch.equal(a.pool[l], b.pool[l]), (t, l)
+        # the trace left behind is the last layer's
+        assert np.array_equal(tr[0].cpu().numpy(), last[0]) and np.array_equal(tr[1].cpu().numpy(), last[1])
+        assert np.array_equal(tr[2].cpu().numpy(), last[2])
+        assert np.array_equal(np.sort(tr[3].cpu().numpy(), axis=1), np.sort(last[3], axis=1))
+        sa_, sb_ = a.kvd.stats(), b.kvd.stats()
+        assert (sa_.hits, sa_.misses, sa_.evictions) == (sb_.hits, sb_.misses, sb_.evictions)
+        print(f"[layers-{n_layers}-mb{mb}-{policy}] step {t} ok", flush=True)
+    assert rep.unit_steps == w.steps * w.units * L and a.kvd.stats().evictions > 0
+    a.close()
+    b.close()
+
+
+def test_step_layers_rejects_ranges_outside_the_context():
+    w = small("layers-args", n_layers=2, physical_layers=1)
+    rig = R.Rig(w)
+    q = next(iter(W.query_stream(w, rig.q0, 1, R.DEV)))
+    out = torch.empty((2, w.batch, w.n_q_heads, w.head_dim), dtype=torch.float32, device=R.DEV)
+    for layer0, n in [(-1, 1), (0, 0), (0, 3), (1, 2), (2, 1)]:
+        with pytest.raises(K.KvdError):
+            rig.kvd.step_layers(layer0, n, 0, q, out)
+    rig.kvd.step_layers(0, 2, 0, q, out)
+    torch.cuda.synchronize()
+    rig.close()
+
+
 @pytest.mark.parametrize("seed", list(range(32)))
 def test_one_launch_equals_chain_on_random_shapes(seed):
     """Seeded random shapes (pages, page size, heads, budget, window, policy, ragged lengths): the
