@@ -270,6 +270,7 @@ int kvd_step(kvd_ctx* ctx, int32_t layer, int32_t step, const void* q, float* ou
  * another on `stream`.  (Three and four layers in flight measured no faster than two.)
  *   q_layers [n_layers][B][Hq][D] kv_dtype, out_layers [n_layers][B][Hq][D] fp32,
  *   lse_layers [n_layers][B][Hq] fp32 or NULL (all device, 16-byte aligned).
+ * Forking and joining use events only: the call can be captured into a HIP graph from `stream`.
  * kvd_step_trace afterwards reports the last of the layers.  Errors as kvd_step; KVD_ERR_ARG when
  * the layer range leaves the context's. */
 int kvd_step_layers(kvd_ctx* ctx, int32_t layer0, int32_t n_layers, int32_t step, const void* q_layers,

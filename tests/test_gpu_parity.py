@@ -608,6 +608,51 @@ def test_single_launch_step_replayed_from_a_hip_graph():
     graphed.close()
 
 
+@pytest.mark.parametrize("mb", [-1, 1], ids=["single-launch", "kernel-chain"])
+def test_layers_in_flight_replayed_from_a_hip_graph(mb):
+    """kvd_step_layers forks into and joins back from a stream of the library with events only, so
+    the call can be captured from the caller's stream; every replay must equal the eager call."""
+    w = small("layers-graph", n_layers=3, physical_layers=2, ctx=16 * 600, topk_pages=32, capacity=40, steps=8, batch=2)
+    eager, graphed = R.Rig(w, micro_batches=mb), R.Rig(w, micro_batches=mb)
+    qs = [q.contiguous() for q in W.query_stream(w, eager.q0, 8, R.DEV)]
+    L = w.n_layers
+    shape = (L, w.batch, w.n_q_heads, w.head_dim)
+    out_e = torch.empty(shape, dtype=torch.float32, device=R.DEV)
+    out_g = torch.empty(shape, dtype=torch.float32, device=R.DEV)
+    for t in range(3):                                                # same history on both sides
+        eager.kvd.step_layers(0, L, t, qs[t], out_e)
+        graphed.kvd.step_layers(0, L, t, qs[t], out_g)
+    torch.cuda.synchronize()
+    q_static = qs[3].clone()
+    s = torch.cuda.Stream()
+    s.wait_stream(torch.cuda.current_stream())
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g, stream=s):
+        graphed.kvd.step_layers(0, L, 3, q_static, out_g, stream=s)
+    torch.cuda.synchronize()
+    for i, t in enumerate([3, 4, 5, 6, 7]):
+        q_static.copy_(qs[t])
+        out_g.fill_(float("nan"))
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        eager.kvd.step_layers(0, L, 3, qs[t], out_e)                   # the captured launches carry step index 3
+        torch.cuda.synchronize()
+        if mb == 1:
+            assert torch.equal(out_g, out_e), i
+        else:
+            assert H.attn_rel_err(out_g.cpu().numpy().reshape(-1, w.head_dim), out_e.cpu().numpy().reshape(-1, w.head_dim)) <= 1e-5, i
+        for l in range(L):
+            pa, sa = eager.kvd.cache_export(l)
+            pb, sb = graphed.kvd.cache_export(l)
+            assert torch.equal(pa, pb) and torch.equal(sa, sb), (i, l)
+        assert (torch.zeros(3) + 1).sum().item() == 3.0               # unrelated eager work between replays
+    se, sg = eager.kvd.stats(), graphed.kvd.stats()
+    assert sg.misses == se.misses and se.misses > 0
+    eager.close()
+    graphed.close()
+
+
 def test_calibration_picks_a_form_and_leaves_the_cache_consistent():
     """The pre-run calibration executes real steps in every form; afterwards the cache must be
     exactly where the oracle is after the same steps, and decoding continues in the chosen form."""
