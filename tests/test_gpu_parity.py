@@ -340,18 +340,25 @@ def test_step_parity_one_attention_split_per_unit(mb):
 
 @pytest.mark.parametrize("policy", ["lru", "lookahead"])
 @pytest.mark.parametrize("mb", [-1, 1], ids=["single-launch", "kernel-chain"])
-@pytest.mark.parametrize("n_layers,phys", [(4, 2), (3, 3)])
-def test_layers_in_flight_equal_layers_one_by_one(n_layers, phys, mb, policy):
+@pytest.mark.parametrize("n_layers,phys,centroids", [(4, 2, 0), (3, 3, 0), (3, 2, 48)])
+def test_layers_in_flight_equal_layers_one_by_one(n_layers, phys, centroids, mb, policy):
     """kvd_step_layers keeps two layers in flight on two streams with two scratch sets.  Every
     layer has its own directory and slots, so scores, traces, directories and slot contents must be
     those of the layers stepped one by one, and the outputs too (bit for bit with the chain of
     kernels; up to the order in which the splits are merged in one launch).  The one-by-one run is
     compared with the oracle at every layer-step."""
     w = small("layers", n_layers=n_layers, physical_layers=phys, ctx=16 * 700, topk_pages=40, capacity=46, steps=7,
-              policy=policy, batch=3, n_kv_heads=2, n_q_heads=8)
+              policy=policy, batch=3, n_kv_heads=2, n_q_heads=8, index_centroids=centroids)
     a = R.Rig(w, micro_batches=mb)
     b = R.Rig(w, micro_batches=mb, build_index=False)
     b.summaries.copy_(a.summaries)
+    if centroids:
+        b.centroids.copy_(a.centroids)
+        b.cluster_start.copy_(a.cluster_start)
+        b.cluster_pages.copy_(a.cluster_pages)
+        for l in range(n_layers):
+            b.kvd.refresh_clusters(l)
+        torch.cuda.synchronize()
     assert a.kvd.step_form() == mb and b.kvd.step_form() == mb
     units = all_units(a)
     by_layer = {l: [ou for ou in units if ou.layer == l] for l in range(n_layers)}
