@@ -339,7 +339,7 @@ def test_step_parity_one_attention_split_per_unit(mb):
 
 
 @pytest.mark.parametrize("policy", ["lru", "lookahead"])
-@pytest.mark.parametrize("mb", [-1, 1], ids=["single-launch", "kernel-chain"])
+@pytest.mark.parametrize("mb", [-1, 1, 2], ids=["single-launch", "kernel-chain", "two-groups"])
 @pytest.mark.parametrize("n_layers,phys,centroids", [(4, 2, 0), (3, 3, 0), (3, 2, 48)])
 def test_layers_in_flight_equal_layers_one_by_one(n_layers, phys, centroids, mb, policy):
     """kvd_step_layers keeps two layers in flight on two streams with two scratch sets.  Every
@@ -387,7 +387,7 @@ def test_layers_in_flight_equal_layers_one_by_one(n_layers, phys, centroids, mb,
         torch.cuda.synchronize()
         for l in range(L):
             got = out_l[l].cpu().numpy()
-            if mb == 1:
+            if mb >= 1:
                 assert np.array_equal(got, outs[l]) and np.array_equal(lse_l[l].cpu().numpy(), lses[l]), (t, l)
             else:
                 assert H.attn_rel_err(got, outs[l]) <= 1e-5, (t, l)
