@@ -290,7 +290,7 @@ def main() -> int:
         t_write = time.perf_counter() - t_write
         ctx.bind_tier(tier)
     step_fn = ctx.step_tiered if tier is not None else ctx.step
-    n_cal = 8 * ((args.calibrate + 1) // 2 + 1) if args.calibrate > 0 else 0
+    n_cal = args.calibrate + 1 if args.calibrate > 0 else 0
     n_total = args.warmup + 2 * args.steps + 1
     stream_q = [q[0].contiguous() for q in W.query_stream(w, q0, n_cal + n_total, dev)]
     # warm-up queries, then the calibration's, then the timed ones: one continuous drifting stream

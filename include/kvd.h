@@ -420,16 +420,19 @@ int kvd_step_form(const kvd_ctx* ctx);
  * KVD_ERR_SHAPE if the context's shapes cannot run that form. */
 int kvd_set_step_form(kvd_ctx* ctx, int32_t form);
 /* Pre-run calibration (Pipeline Optimization: the micro-batch size is found by a short calibration
- * before inference begins).  Runs real decode steps of `layer` — step indices first_step,
- * first_step + 1, ... with the queries q_steps [n_queries][B][Hq][D] (device) taken in turn — in
- * each form the context can run (chain of kernels, 2 groups, 4 groups, one launch).  Every form
- * runs two blocks of 1 untimed + ceil(steps_per_form / 2) timed steps, enqueued back to back and
- * timed with HIP events on `stream`; the blocks go through the forms in order and then in reverse
- * order, so that a drift over the calibration weighs on all forms alike (calibrate on a warmed-up
- * cache all the same).  The fastest form is kept and reported in *chosen_form.  ms_per_step (host,
- * 4 floats in that order, -1 for a form that cannot run) may be NULL.  The cache advances by
- * 8 * (ceil(steps_per_form / 2) + 1) steps at most; `out` receives the last step's output.
- * Synchronous. */
+ * before inference begins).  Runs real decode steps of `layer` — step indices first_step ..
+ * first_step + steps_per_form with the queries q_steps [n_queries][B][Hq][D] (device) taken in
+ * turn — in each form the context can run (chain of kernels, 2 groups, 4 groups, one launch).
+ * Every form replays the same 1 untimed + steps_per_form timed steps from the same cache: the
+ * layer's directory is kept on the host when the call starts and put back before each replay (its
+ * slots refilled from the host store), so that all forms see the same misses — a step's time
+ * follows its misses, which vary more from step to step than the forms differ.  The replays are
+ * enqueued back to back and timed with HIP events on `stream`, twice per form (forms in order,
+ * then in reverse order); a form's time is the smaller of its two.  The fastest form is kept and
+ * reported in *chosen_form.  ms_per_step (host, 4 floats in that order, -1 for a form that cannot
+ * run) may be NULL.  Afterwards the cache is where steps_per_form + 1 steps from its state at the
+ * call take it; the counters of kvd_get_stats have counted every replay; `out` receives the last
+ * step's output.  Synchronous. */
 int kvd_calibrate_step_form(kvd_ctx* ctx, int32_t layer, int32_t first_step, const void* q_steps, int32_t n_queries,
                             int32_t steps_per_form, float* out, void* stream, int32_t* chosen_form,
                             float* ms_per_step);

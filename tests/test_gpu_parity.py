@@ -661,26 +661,36 @@ def test_layers_in_flight_replayed_from_a_hip_graph(mb):
 
 
 def test_calibration_picks_a_form_and_leaves_the_cache_consistent():
-    """The pre-run calibration executes real steps in every form; afterwards the cache must be
-    exactly where the oracle is after the same steps, and decoding continues in the chosen form."""
+    """The pre-run calibration replays the same real steps in every form, each time from the cache
+    as it was at the call; afterwards the cache must be exactly where the oracle is after taking
+    those steps once, and decoding continues in the chosen form."""
     w = SCALED[3].replace(batch=4, steps=4)
     rig = R.Rig(w)
     units = all_units(rig)
-    n_q, spf = 5, 4
-    qs = torch.stack([q[0] for q in W.query_stream(w, rig.q0, n_q + 2, R.DEV)]).contiguous()
-    chosen, ms = rig.kvd.calibrate_step_form(0, 0, qs[:n_q], spf, rig.out)
+    n_q, spf, t0 = 5, 6, 3
+    qs = torch.stack([q[0] for q in W.query_stream(w, rig.q0, t0 + n_q + 2, R.DEV)]).contiguous()
+    rep = R.StepReport()
+    for t in range(t0):                                               # the calibration starts from a cache in use
+        rig.step(0, t, qs[t])
+        for ou in units:
+            R.compare_unit(rig, ou, t, qs[t], rep)
+    rig.kvd.reset_stats()
+    q_cal = qs[t0:t0 + n_q]
+    chosen, ms = rig.kvd.calibrate_step_form(0, t0, q_cal, spf, rig.out)
     assert set(ms) == {1, 2, 4, -1} and all(v > 0 for v in ms.values())
     assert chosen == min(ms, key=ms.get) and rig.kvd.step_form() == chosen
-    n_run = len(ms) * 2 * (spf // 2 + 1)                              # every form: two blocks of 1 untimed + spf/2 timed steps
-    for i in range(n_run):                                            # the oracle takes the same steps
+    n_run = spf + 1                                                   # every form replays the same 1 untimed + spf timed steps
+    want_miss = 0
+    for i in range(n_run):                                            # the oracle takes them once
         for ou in units:
-            ou.step(i, qs[i % n_q])
+            want_miss += len(ou.step(t0 + i, q_cal[i % n_q])["misses"])
     R.check_directory(rig, 0, units)
-    rep = R.StepReport()
+    st = rig.kvd.stats()
+    assert st.misses == 2 * len(ms) * want_miss and want_miss > 0     # every replay saw the same misses
     for j in range(2):                                                # and decoding goes on from there
-        rig.step(0, n_run + j, qs[n_q + j])
+        rig.step(0, t0 + n_run + j, qs[t0 + n_q + j])
         for ou in units:
-            R.compare_unit(rig, ou, n_run + j, qs[n_q + j], rep)
+            R.compare_unit(rig, ou, t0 + n_run + j, qs[t0 + n_q + j], rep)
     for form in (1, 2, -1):
         rig.kvd.set_step_form(form)
         assert rig.kvd.step_form() == form
