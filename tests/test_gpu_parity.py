@@ -422,6 +422,35 @@ def test_step_layers_rejects_ranges_outside_the_context():
 
 
 @pytest.mark.parametrize("seed", list(range(32)))
+def test_random_shapes_against_the_oracle(seed):
+    """Seeded random shapes (pages, page size, heads, group, budget, window, policy, dtype, ragged
+    lengths, forced pages), stepped in the form the seed picks, compared with the oracle on up to
+    four units of the layer at every step: scores, selection, trace, directory, output."""
+    rng = np.random.default_rng(7700 + seed)
+    page = int(rng.choice([16, 32, 64]))
+    n_pages = int(rng.choice([p for p in (40, 130, 257, 1000, 2050) if p * page <= 40000]))
+    hkv = int(rng.choice([1, 2, 4]))
+    group = int(rng.choice([1, 2, 4, 7, 8]))
+    k = int(rng.integers(1, min(n_pages // 2, 96) + 1))
+    cap = int(min(n_pages, k + rng.integers(0, 2 * k + 2)))
+    forced = k > 6
+    kw = dict(ctx=page * n_pages, page=page, n_kv_heads=hkv, n_q_heads=hkv * group, dtype=str(rng.choice(["bf16", "f16"])),
+              topk_pages=k, capacity=cap, batch=int(rng.choice([1, 2, 3])), policy=str(rng.choice(["lru", "lookahead"])),
+              sink_pages=int(rng.integers(0, 3)) if forced else 0, recent_pages=int(rng.integers(0, 3)) if forced else 0,
+              heavy_count=min(5, n_pages // 8), steps=5, seed=900 + seed)
+    w = small("rand-oracle", **kw)
+    seq = [int(w.ctx - rng.integers(0, 3 * page)) for _ in range(w.batch)]
+    mb = int(rng.choice([-1, 1, 2])) if w.batch >= 2 else int(rng.choice([-1, 1]))
+    rig = R.Rig(w, seq_lens=seq, micro_batches=mb)
+    picks = rng.permutation(w.units)[:4]
+    units = [R.OracleUnit(rig, 0, int(u) // hkv, int(u) % hkv) for u in picks]
+    rep = R.run_steps(rig, units, w.steps, check_dir_every=2, progress=f"rand-oracle-{seed}")
+    assert rep.unit_steps == w.steps * len(units), kw
+    assert rep.tie_divergences + rep.victim_tie_divergences <= 3, kw
+    rig.close()
+
+
+@pytest.mark.parametrize("seed", list(range(32)))
 def test_one_launch_equals_chain_on_random_shapes(seed):
     """Seeded random shapes (pages, page size, heads, budget, window, policy, ragged lengths): the
     one-launch step and the chain of kernels, fed the same queries from the same cold start, must
