@@ -301,19 +301,28 @@ __device__ __forceinline__ bool select_resolve_body(const FastArgs& a, int u, Fa
     n_valid = n_valid < a.NP ? n_valid : a.NP;
     const int k_eff = k < n_valid ? k : n_valid;
     const int recent_from = n_valid - a.recent;
+    // Which of this lane's pages are free to compete and which are forced, four consecutive pages
+    // at a time: free = [sink, recent_from), forced = the other valid pages.
+    u32 free_mask = 0, forced_mask = 0;               // bit j: page_of(j)
+#pragma unroll
+    for (int q4 = 0; q4 < IPT / 4; ++q4) {
+      const int base = page_of(4 * q4);
+      auto upto = [&](int bound) -> u32 {              // bits of the group's pages below `bound`
+        const int n = bound - base;
+        return (1u << (n < 0 ? 0 : (n > 4 ? 4 : n))) - 1u;
+      };
+      const u32 fr = upto(recent_from) & ~upto(a.sink);
+      free_mask |= fr << (4 * q4);
+      forced_mask |= (upto(n_valid) & ~fr) << (4 * q4);
+    }
     float fmin = INFINITY, fmax = -INFINITY;
-    int n_forced = 0;
 #pragma unroll
     for (int j = 0; j < IPT; ++j) {
-      const int p = page_of(j);
-      const bool valid = p < n_valid;
-      const bool forced = valid && (p < a.sink || p >= recent_from);
-      if (valid && !forced) {
-        fmin = fminf(fmin, s[j]);
-        fmax = fmaxf(fmax, s[j]);
-      }
-      n_forced += forced ? 1 : 0;
+      const bool fr = (free_mask >> j) & 1u;
+      fmin = fminf(fmin, fr ? s[j] : INFINITY);
+      fmax = fmaxf(fmax, fr ? s[j] : -INFINITY);
     }
+    int n_forced = __popc(forced_mask);
     fmin = wave_allreduce_min(fmin);
     fmax = wave_allreduce_max(fmax);
     n_forced = wave_inclusive_scan(n_forced);          // lane 63 holds the wave's count
@@ -331,9 +340,17 @@ __device__ __forceinline__ bool select_resolve_body(const FastArgs& a, int u, Fa
     const float range = fmax - fmin;
     const float inv = range > 0.f ? 2047.0f / range : 0.f;
     auto bucket_of = [&](float v) -> int { return (int)fminf(fmaxf((fmax - v) * inv, 0.f), 2047.f); };
-    auto is_free = [&](int p) -> bool { return p < n_valid && !(p < a.sink || p >= recent_from); };
+    // every free page's bucket, computed once and kept (two per register); 0xffff = not free
+    u32 bk2[IPT / 2];
+#pragma unroll
+    for (int j = 0; j < IPT; j += 2) {
+      const u32 b0 = ((free_mask >> j) & 1u) ? (u32)bucket_of(s[j]) : 0xffffu;
+      const u32 b1 = ((free_mask >> (j + 1)) & 1u) ? (u32)bucket_of(s[j + 1]) : 0xffffu;
+      bk2[j / 2] = b0 | (b1 << 16);
+    }
+    auto bucket_at = [&](int j) -> int { return (int)((bk2[j >> 1] >> (16 * (j & 1))) & 0xffffu); };
     auto key_of = [&](int j) -> u64 { return ((u64)fast_descending_key(s[j]) << 32) | (u32)page_of(j); };
-    auto bkt_of = [&](int j) -> int { return is_free(page_of(j)) ? bucket_of(s[j]) : -1; };
+    auto bkt_of = [&](int j) -> int { const int bb = bucket_at(j); return bb == 0xffff ? -1 : bb; };
     u64 thr = 0;
     if (k_free > 0) {
       const float* sc = a.scores + (size_t)u * a.NP;
@@ -349,26 +366,23 @@ __device__ __forceinline__ bool select_resolve_body(const FastArgs& a, int u, Fa
       };
       thr = two_level_select<NT, IPT>(key_of, bkt_of, k_free, sm, flip, refine);
     }
+    // a page in a bucket before the decisive one is in, one in a later bucket is out; only the
+    // members of the decisive bucket are compared with the threshold key
+    const int bin = k_free > 0 ? sm.bin : -1;
+    u32 take = forced_mask;                            // bit j: page_of(j) is selected
+#pragma unroll
+    for (int j = 0; j < IPT; ++j) {
+      const int bb = bucket_at(j);
+      bool t = bb < bin;
+      if (bb == bin) t = key_of(j) <= thr;
+      take |= t ? (1u << j) : 0u;
+    }
+    int cnt4[IPT / 4];
+    int cnt = __popc(take);
+#pragma unroll
+    for (int q4 = 0; q4 < IPT / 4; ++q4) cnt4[q4] = __popc((take >> (4 * q4)) & 15u);
     // output in ascending page order = (wave, load, lane, element): one block scan over the
     // lanes' totals gives the wave's first position, wave scans per load give the rest
-    u32 take = 0;                                      // bit j: page_of(j) is selected
-    int cnt4[IPT / 4];
-    int cnt = 0;
-#pragma unroll
-    for (int q4 = 0; q4 < IPT / 4; ++q4) {
-      cnt4[q4] = 0;
-#pragma unroll
-      for (int e = 0; e < 4; ++e) {
-        const int j = 4 * q4 + e;
-        const int p = page_of(j);
-        const bool valid = p < n_valid;
-        const bool forced = valid && (p < a.sink || p >= recent_from);
-        const bool t = forced || (is_free(p) && k_free > 0 && key_of(j) <= thr);
-        take |= t ? (1u << j) : 0u;
-        cnt4[q4] += t ? 1 : 0;
-      }
-      cnt += cnt4[q4];
-    }
     int total;
     const int lane_pos = fast_scan<NT>(cnt, sm, flip, total);
     int pos_q = __builtin_amdgcn_readfirstlane(lane_pos);   // lane 0: what the waves before this one selected
