@@ -86,8 +86,8 @@ typedef struct {
                                    moves through the stages on its own, synchronised by counters and
                                    published words in device memory (needs page_size % 16 == 0, max_pages <= 16384,
                                    capacity_max <= 4096; other shapes run as for 1);
-                              0  = chosen by the library: the one launch where it can run and there are
-                                   at least 32 units, else as for 1;
+                              0  = chosen by the library: the one launch where it can run (with units of
+                                   more than 8192 pages only from 24 units on), else as for 1;
                               1  = one chain of kernels on the caller's stream, no overlap;
                               n >= 2 = the B sequences are split into n groups, each running
                                    select -> fetch -> attend as its own chain on one of the library's

@@ -20,12 +20,14 @@
   } while (0)
 
 // micro_batches -1 asks for the one-launch step wherever it can run; 0 leaves the choice to the
-// library, which takes it where it has measured faster than the chain of kernels: enough units to
-// keep its pipeline filled.
+// library, which takes it where it has measured faster than the chain of kernels: everywhere in
+// the 512-thread form (4 to 128 units measured, 2-6 us per step), and from 24 units on in the
+// 1024-thread form (units of more than 8192 pages: 3-5 % slower than the chain with 8 and 16
+// units, 18 % faster with 24).
 static bool kvd_wants_single_launch(const kvd_ctx* c) {
   if (!kvd_single_launch_ok(c)) return false;
   if (c->cfg.micro_batches == -1) return true;
-  return c->cfg.micro_batches == 0 && c->U >= 32;
+  return c->cfg.micro_batches == 0 && (c->step_threads != 1024 || c->U >= 24);
 }
 
 static bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }

@@ -850,7 +850,7 @@ def test_lookahead_exact_ties_drop_the_higher_page():
 @pytest.mark.parametrize("cfg,mb,kw", [
     (3, 1, dict()),                                                   # 1100 pages -> 550 centroids, bf16
     (3, 2, dict()),                                                   # groups on streams
-    (2, 0, dict(index_iterations=2)),                                 # 3 layers, planted heavy pages
+    (2, 1, dict(index_iterations=2)),                                 # 3 layers, planted heavy pages
     (4, 1, dict()),                                                   # fp16, G = 7, page 32
     (5, 1, dict()),                                                   # page 64, recent pages forced and pre-warmed
     (3, -1, dict()),                                                  # the same through the one-launch step
