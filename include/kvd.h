@@ -432,7 +432,8 @@ int kvd_set_step_form(kvd_ctx* ctx, int32_t form);
  * reported in *chosen_form.  ms_per_step (host, 4 floats in that order, -1 for a form that cannot
  * run) may be NULL.  Afterwards the cache is where steps_per_form + 1 steps from its state at the
  * call take it; the counters of kvd_get_stats have counted every replay; `out` receives the last
- * step's output.  Synchronous. */
+ * step's output.  Synchronous.  KVD_ERR_STATE with profiling on (kvd_set_profiling), when every
+ * step runs as the same chain of kernels. */
 int kvd_calibrate_step_form(kvd_ctx* ctx, int32_t layer, int32_t first_step, const void* q_steps, int32_t n_queries,
                             int32_t steps_per_form, float* out, void* stream, int32_t* chosen_form,
                             float* ms_per_step);

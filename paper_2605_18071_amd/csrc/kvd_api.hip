@@ -823,7 +823,7 @@ int kvd_calibrate_step_form(kvd_ctx* ctx, int32_t layer, int32_t first_step, con
   if (!ctx || !q_steps || !out || !chosen_form || layer < 0 || layer >= ctx->L || n_queries < 1 || steps_per_form < 1 ||
       !aligned16(q_steps))
     return KVD_ERR_ARG;
-  if (!ctx->summaries || !ctx->pool || !ctx->store_dev) return KVD_ERR_STATE;
+  if (!ctx->summaries || !ctx->pool || !ctx->store_dev || ctx->profiling != 0) return KVD_ERR_STATE;   // (profiled steps all run as one chain)
   hipStream_t s = static_cast<hipStream_t>(stream);
   const int candidates[4] = {1, 2, 4, -1};
   const size_t q_bytes = (size_t)ctx->B * ctx->Hq * ctx->D * 2;

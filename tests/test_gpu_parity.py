@@ -723,6 +723,10 @@ def test_calibration_picks_a_form_and_leaves_the_cache_consistent():
     for form in (1, 2, -1):
         rig.kvd.set_step_form(form)
         assert rig.kvd.step_form() == form
+    rig.kvd.set_profiling(1)
+    with pytest.raises(K.KvdError):                                   # profiled steps all run as one chain: nothing to compare
+        rig.kvd.calibrate_step_form(0, 100, q_cal, 2, rig.out)
+    rig.kvd.set_profiling(0)
     with pytest.raises(K.KvdError):
         rig.kvd.set_step_form(99)
     rig.close()
