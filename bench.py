@@ -218,6 +218,7 @@ def main() -> int:
     ap.add_argument("--tier-buffered", action="store_true", help="read through the page cache instead of O_DIRECT")
     ap.add_argument("--tier-layout", choices=["page", "semantic"], default="page",
                     help="order of a unit's pages in the file: page order, or cluster by cluster (needs --centroids)")
+    ap.add_argument("--batch", type=int, default=0, metavar="B", help="B > 0: the configuration's shape with B sequences instead of its own batch")
     ap.add_argument("--layers", type=int, default=1, metavar="N",
                     help="N > 1: add a leg that steps N layers per decode step, one by one and two in flight (kvd_step_layers)")
     ap.add_argument("--timeline", action="store_true",
@@ -239,6 +240,8 @@ def main() -> int:
     dev = "cuda:0"
     torch.cuda.set_device(0)
     w = W.CONFIGS[args.config]
+    if args.batch > 0:
+        w = w.replace(batch=args.batch, name=f"{w.name}-batch{args.batch}")
     cfg_w = w
     if w.n_layers != 1:
         # multi-layer configurations are benchmarked on one layer's worth of state at full per-layer shape
