@@ -9,8 +9,8 @@
  *   (3) run sparse attention over resident + fetched pages.
  * The index is the mean key of each page (System Overview); the in-GPU cache is
  * the window of recently critical pages of "Attention-Based Cache Management",
- * here with LRU replacement; stage (2) moves only out-of-cache pages
- * ("Performance Analysis via Roofline Model").
+ * with LRU replacement or the paper's lookahead eviction (kvd_policy); stage (2)
+ * moves only out-of-cache pages ("Performance Analysis via Roofline Model").
  *
  * Notation: L layers, B sequences, Hq query heads, Hkv KV heads, G = Hq/Hkv,
  * D = head_dim = 128, P tokens per page, NP pages per sequence, k pages selected
@@ -193,8 +193,9 @@ int kvd_score_select(kvd_ctx* ctx, int32_t layer, const void* q, int32_t* sel_pa
  * Hits are re-stamped with `step`; misses take free slots first, then the slots of the resident
  * pages, not selected in this step, with the smallest (stamp, page) — under KVD_EVICT_LOOKAHEAD
  * with the smallest (score, -page), read from where the most recent kvd_score_select of this
- * context left its scores (KVD_ERR_STATE if there was none).  `step` must not decrease for a layer.  With do_gather != 0 the missed pages are then copied from the host store into
- * their slots on `stream`.  With do_gather == 0 only the directory changes (slot contents are
+ * context left its scores (KVD_ERR_STATE if there was none).  `step` must not decrease for a
+ * layer.  With do_gather != 0 the missed pages are then copied from the host store into their
+ * slots on `stream`.  With do_gather == 0 only the directory changes (slot contents are
  * stale).  sel_pages must hold distinct pages in ascending order, as stage 1 writes them. */
 int kvd_cache_resolve(kvd_ctx* ctx, int32_t layer, int32_t step, const int32_t* sel_pages, int32_t* sel_slots,
                       int32_t* hit_mask, int32_t* evicted, int32_t* counts, int32_t do_gather, void* stream);
