@@ -421,6 +421,26 @@ def test_step_layers_rejects_ranges_outside_the_context():
     rig.close()
 
 
+@pytest.mark.parametrize("policy", ["lru", "lookahead"])
+@pytest.mark.parametrize("mb", [-1, 1], ids=["single-launch", "kernel-chain"])
+def test_step_parity_with_repeated_step_indices(mb, policy):
+    """A step index may repeat (a replayed step): the pages selected in a step then tie in stamp
+    with unselected ones, and the victims must still come from the unselected pages only."""
+    w = small("repeat", topk_pages=20, capacity=26, steps=12, policy=policy)
+    rig = R.Rig(w, micro_batches=mb)
+    units = all_units(rig)
+    rep = R.StepReport()
+    for i, q in enumerate(W.query_stream(w, rig.q0, w.steps, R.DEV)):
+        t = i // 3                                                     # every index three times
+        rig.step(0, t, q[0])
+        for ou in units:
+            R.compare_unit(rig, ou, t, q[0], rep)
+        if i % 4 == 3:
+            R.check_directory(rig, 0, units)
+    assert rep.unit_steps == w.steps * w.units and rig.kvd.stats().evictions > 0
+    rig.close()
+
+
 @pytest.mark.parametrize("seed", list(range(32)))
 def test_random_shapes_against_the_oracle(seed):
     """Seeded random shapes (pages, page size, heads, group, budget, window, policy, dtype, ragged

@@ -287,6 +287,22 @@ def test_lru_rejects_k_above_capacity_and_warm():
     assert win.resolve([3, 5], 0) == ([3], [5], [4])
 
 
+def test_lru_never_evicts_a_page_selected_in_the_same_step():
+    """Hand-worked: when a step index repeats (a replayed step), resident pages that were not
+    selected tie in stamp with the selected ones; the victim is still taken from the unselected
+    pages only, lowest page first."""
+    win = orc.LruWindow(3)
+    assert win.resolve([0, 1], 5) == ([], [0, 1], [])
+    assert win.resolve([1, 2], 5) == ([1], [2], [])                   # window full: {0, 1, 2}, all stamped 5
+    assert win.resolve([0, 3], 5) == ([0], [3], [1])                  # 0 is selected: 1 leaves, not 0
+    assert win.resident() == [0, 2, 3]
+    assert win.resolve([2, 4], 5) == ([2], [4], [0])                  # unselected: 0 and 3, equal stamps -> lower page
+    la = orc.LookaheadWindow(3)
+    sc = np.array([0.0, 1.0, 2.0, 3.0, 4.0])                          # page 0 scores lowest but is selected
+    la.warm([0, 1, 2])
+    assert la.resolve([0, 3], 1, scores=sc) == ([0], [3], [1])
+
+
 # --------------------------------------------------------------------------- #
 # lookahead eviction
 # --------------------------------------------------------------------------- #
@@ -377,6 +393,13 @@ def test_kmeans_matches_sklearn_lloyd():
 
 def test_kmeans_closed_forms_and_invariants():
     rng = np.random.default_rng(8)
+    # the initial centroids are the points at the middles of n_centroids equal stretches of the
+    # sequence, floor((i + 1/2) n / n_centroids): 10 points, 2 centroids -> points 2 and 7; 7 points,
+    # 3 centroids -> points 1, 3, 5 (hand-worked)
+    line = np.arange(10, dtype=np.float64)[:, None] * np.ones((1, 4))
+    assert np.array_equal(orc.kmeans_init(line, 2), line[[2, 7]])
+    assert np.array_equal(orc.kmeans_init(line[:7], 3), line[[1, 3, 5]])
+    assert np.array_equal(orc.kmeans_init(line, 10), line)
     pts = orc.round_f64(rng.normal(size=(96, 16)), orc.F16)
     # as many centroids as points: every point is its own cluster and its own centroid
     cent, assign, _ = orc.kmeans_centroids(pts, 96, 3, orc.F16)
