@@ -285,6 +285,11 @@ def test_lru_rejects_k_above_capacity_and_warm():
         win.resolve([0, 1, 2], 0)
     win.warm([3, 4])
     assert win.resolve([3, 5], 0) == ([3], [5], [4])
+    with pytest.raises(ValueError):
+        orc.LruWindow(2).warm([1, 2, 3])                              # a warm list longer than the window
+    again = orc.LruWindow(2)
+    again.warm([1, 2])
+    again.warm([2, 1])                                                # pages already resident take no room
 
 
 def test_lru_never_evicts_a_page_selected_in_the_same_step():
@@ -583,6 +588,41 @@ def test_lookahead_under_the_hierarchical_index_uses_the_cluster_score():
     assert win2.resolve([1], 0, scores=per_page) == ([], [1], [6])
 
 
+def test_unit_step_wires_the_stages_together():
+    """Hand-worked wiring of decode_unit_step.  (a) A selection forced on the step replaces the
+    step's own in the window *and* in the attention: the output is the attention over the forced
+    pages' tokens.  (b) With the hierarchical index under lookahead eviction the victim is ranked by
+    the score of its cluster, not by the entry of the cluster-score array at the page's own index:
+    clusters {2,3} {0,1} with centroid scores (low, high) -> pages 2 and 3 score low, 0 and 1 high."""
+    G, D, P, NP = 2, 8, 2, 6
+    T = P * NP
+    keys = orc.round_f64(RNG.standard_normal((T, D)), orc.BF16)
+    vals = orc.round_f64(RNG.standard_normal((T, D)), orc.BF16)
+    summ = orc.page_summaries(keys, P, T, orc.BF16)
+    q = orc.round_f64(RNG.standard_normal((G, D)), orc.BF16)
+    win = orc.LruWindow(4)
+    own = orc.decode_unit_step(q, summ, keys, vals, orc.LruWindow(4), 0, k=2, page_size=P, seq_len=T, scale=0.5)
+    other = sorted(set(range(NP)) - set(own["sel"].tolist()))[:2]
+    got = orc.decode_unit_step(q, summ, keys, vals, win, 0, k=2, page_size=P, seq_len=T, scale=0.5, forced_sel=other)
+    assert got["sel"].tolist() == own["sel"].tolist() and got["used"].tolist() == other
+    assert got["misses"] == other and win.resident() == other
+    toks = np.array([t for p in other for t in range(p * P, (p + 1) * P)])
+    want, want_lse = orc.attend(q, keys[toks], vals[toks], 0.5)
+    assert np.array_equal(got["out"], want) and np.array_equal(got["lse"], want_lse)
+    assert not np.allclose(got["out"], own["out"])
+    # (b): two centroids; qbar . centroid: cluster 0 = pages {2, 3} low, cluster 1 = pages {0, 1} high
+    members = [np.array([2, 3]), np.array([0, 1])]
+    qh = np.zeros((1, D)); qh[0, 0] = 1.0
+    cent = np.zeros((2, D)); cent[0, 0] = -1.0; cent[1, 0] = 2.0
+    la = orc.LookaheadWindow(3)
+    la.warm([0, 2, 3])
+    r = orc.decode_unit_step(qh, summ[:4], keys[:4 * P], vals[:4 * P], la, 0, k=2, page_size=P, seq_len=4 * P, scale=1.0,
+                             centroids=cent, members=members)
+    assert r["sel"].tolist() == [0, 1]                                # the high cluster
+    assert r["evict_scores"].tolist() == [2.0, 2.0, -1.0, -1.0]
+    assert (r["hits"], r["misses"], r["evicted"]) == ([0], [1], [3])  # low cluster, higher page first
+
+
 def test_hierarchical_step_with_one_page_per_cluster_is_the_flat_lookahead_step():
     """Clusters of one page each, the page's summary as centroid: the step through the index
     must be the flat step, lookahead victims included."""
@@ -666,6 +706,17 @@ def test_extent_tier_of_single_page_extents_is_the_lru_window():
         assert (got["hits"], got["reads"], got["evicted"]) == (hits, misses, evicted)
         assert got["runs"] == [(p, 1) for p in misses]
         assert tier.stamp == lru.stamp
+
+
+def test_extent_tier_never_evicts_an_extent_the_step_needs():
+    """Hand-worked: with a repeated step index the pooled extents all tie in stamp; the victim is
+    still taken from the extents that the step does not need."""
+    tier = orc.ExtentTier(n_units=1, n_pages=8, extent_pages=2, pool_extents=2, max_run_extents=4)
+    pos = [np.arange(8)]
+    assert tier.fetch(0, 5, [[0]], pos)["reads"] == [0]
+    assert tier.fetch(0, 5, [[2]], pos)["reads"] == [1]               # pool full: extents 0 and 1, both stamped 5
+    r = tier.fetch(0, 5, [[0, 4]], pos)                               # needs extents 0 (pooled) and 2
+    assert (r["hits"], r["reads"], r["evicted"]) == ([0], [2], [1])   # 1 leaves, not the needed 0
 
 
 @pytest.mark.parametrize("E,pool,max_run", [(2, 7, 3), (4, 5, 8), (3, 42, 2), (8, 4, 1)])

@@ -131,6 +131,31 @@ def test_engine_matches_oracle_on_random_traces(tmp_path, E, pool_extents, max_r
     tier.close()
 
 
+@pytest.mark.parametrize("E,pool_extents,max_run", [(2, 9, 3), (4, 6, 8), (1, 17, 4)])
+def test_engine_matches_oracle_when_step_indices_repeat(tmp_path, E, pool_extents, max_run):
+    """Every step index three times: pooled extents then tie in stamp with the ones a step needs,
+    so the victim order (stamp, extent number) and the exclusion of needed extents both show."""
+    L, U, NP, nbytes, k = 2, 3, 37, 48, 6
+    pages = RNG.integers(0, 256, size=(L, U, NP, nbytes), dtype=np.uint8)
+    positions = [[orc.extent_positions(NP) for _ in range(U)] for _ in range(L)]
+    tier, pool = _open(tmp_path, pages, positions, E, pool_extents, max_run, name="kv_repeat.bin")
+    ot = orc.ExtentTier(U, NP, E, pool_extents, max_run)
+    evicted = 0
+    for i in range(60):
+        l = int(RNG.integers(0, L))
+        missed, budget = [], pool_extents
+        for u in range(U):
+            pg = sorted(RNG.choice(NP, size=int(RNG.integers(0, k + 1)), replace=False).tolist())
+            ext = {positions[l][u][p] // E for p in pg}
+            if len(ext) > budget:
+                pg, ext = [], set()
+            budget -= len(ext)
+            missed.append(pg)
+        evicted += len(_check_step(tier, pool, ot, l, i // 3, missed, positions, pages, k)["evicted"])
+    assert evicted > 0
+    tier.close()
+
+
 def test_engine_refuses_what_it_cannot_do(tmp_path):
     lib = kvd.load()
     pages = RNG.integers(0, 256, size=(1, 2, 16, 32), dtype=np.uint8)
