@@ -516,6 +516,14 @@ def test_attention_equals_dense_softmax_when_all_pages_selected():
     assert np.allclose(l, scipy.special.logsumexp(logits, axis=1), rtol=0, atol=1e-12)
 
 
+def test_selected_tokens_are_the_valid_tokens_of_the_selected_pages():
+    """Hand-worked: page size 4, 10 valid tokens: page 2 is partial (tokens 8, 9); padding entries
+    (-1) stand for no page at all."""
+    assert orc.selected_tokens([0, 2], 4, 10).tolist() == [0, 1, 2, 3, 8, 9]
+    assert orc.selected_tokens([-1, 1, -1], 4, 10).tolist() == [4, 5, 6, 7]
+    assert orc.selected_tokens([-1, -1], 4, 10).tolist() == []
+
+
 def test_attention_invariants():
     G, D, n = 1, 16, 40
     q = RNG.standard_normal((G, D))
