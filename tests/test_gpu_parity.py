@@ -963,6 +963,39 @@ def test_lookahead_with_cluster_lists_written_by_the_caller():
     rig.close()
 
 
+def test_layout_from_clusters_matches_the_oracle_with_pages_of_no_cluster():
+    """Cluster lists written by the caller, clusters of scattered pages in no particular order and
+    seven pages listed nowhere: the file layout derived from them must be the oracle's (clusters
+    one after another in cluster order, the unlisted pages last in page order); lists that name a
+    page twice are refused."""
+    w = small("layout", ctx=16 * 120, topk_pages=10, capacity=20, index_centroids=9, steps=1)
+    rig = R.Rig(w, build_index=False)
+    NP, Nc, U = w.n_pages, w.index_centroids, w.units
+    rng = np.random.default_rng(4711)
+    want = []
+    for u in range(U):
+        listed = rng.permutation(NP)[: NP - 7]
+        cluster_of = rng.integers(0, Nc, size=len(listed))
+        members = [np.sort(listed[cluster_of == c]).astype(np.int32) for c in range(Nc)]
+        start = np.concatenate([[0], np.cumsum([len(m) for m in members])]).astype(np.int32)
+        pages = np.full(NP, -1, dtype=np.int32)
+        pages[: start[-1]] = np.concatenate(members)
+        rig.cluster_start[0, u].copy_(torch.from_numpy(start))
+        rig.cluster_pages[0, u].copy_(torch.from_numpy(pages))
+        want.append(orc.extent_positions(NP, members))
+    rig.kvd.refresh_clusters(0)
+    torch.cuda.synchronize()
+    got = rig.kvd.layout_from_clusters(0).numpy()
+    assert np.array_equal(got, np.stack(want))
+    assert any(not np.array_equal(wu, np.arange(NP)) for wu in want)
+    bad = rig.cluster_pages[0, 0].clone()
+    bad[1] = bad[0]                                                    # one page named twice
+    rig.cluster_pages[0, 0].copy_(bad)
+    with pytest.raises(K.KvdError):
+        rig.kvd.layout_from_clusters(0)
+    rig.close()
+
+
 def test_hierarchical_index_ragged_forced_and_duplicate_pages():
     """Sequences of different lengths (the index covers the valid pages only), sink and recent
     pages, more centroids than distinct summaries (exact distance ties, empty clusters), and the
