@@ -963,6 +963,45 @@ def test_lookahead_with_cluster_lists_written_by_the_caller():
     rig.close()
 
 
+@pytest.mark.parametrize("mb", [-1, 1], ids=["single-launch", "kernel-chain"])
+def test_hierarchical_exact_ties_go_to_the_lower_cluster(mb):
+    """Every centroid is the same vector, so all clusters score exactly alike in every step: the
+    clusters must then be taken in ascending cluster order.  Cluster c holds the run of pages
+    5 (Nc - 1 - c) .. +4, so that cluster order is the reverse of page order and the two cannot be
+    mistaken for each other; k = 22 ends inside the fifth cluster, which gives its two lowest pages."""
+    w = small("hier-ties", ctx=16 * 200, topk_pages=22, capacity=40, heavy_count=0, index_centroids=40, steps=4)
+    rig = R.Rig(w, micro_batches=mb, build_index=False)
+    rig.kvd.build_summaries(0)
+    torch.cuda.synchronize()
+    NP, Nc, U = w.n_pages, w.index_centroids, w.units
+    runs = [list(range(5 * (Nc - 1 - c), 5 * (Nc - 1 - c) + 5)) for c in range(Nc)]
+    start = torch.tensor([5 * c for c in range(Nc + 1)], dtype=torch.int32)
+    pages = torch.tensor([p for r in runs for p in r], dtype=torch.int32)
+    rig.cluster_start[0].copy_(start.repeat(U, 1))
+    rig.cluster_pages[0].copy_(pages.repeat(U, 1))
+    rig.centroids[0].copy_(rig.summaries[0][:, :, 7:8, :].expand(-1, -1, Nc, -1))
+    rig.kvd.refresh_clusters(0)
+    units = []
+    for b in range(w.batch):
+        for h in range(w.n_kv_heads):
+            ou = R.OracleUnit.__new__(R.OracleUnit)
+            rig.hier = False                                                      # (no k-means to follow)
+            R.OracleUnit.__init__(ou, rig, 0, b, h)
+            rig.hier = True
+            ou.centroids = np.repeat(ou.summ[7:8], Nc, axis=0)
+            ou.members = [np.array(r, dtype=np.int32) for r in runs]
+            units.append(ou)
+    want = sorted(p for r in runs[:4] for p in r) + runs[4][:2]
+    rep = R.StepReport()
+    for t, q in enumerate(W.query_stream(w, rig.q0, w.steps, R.DEV)):
+        rig.step(0, t, q[0])
+        for ou in units:
+            R.compare_unit(rig, ou, t, q[0], rep)
+            assert rig.n_sel_pages[ou.u].tolist() == sorted(want), (t, ou.u)
+    assert rep.tie_divergences == 0
+    rig.close()
+
+
 def test_layout_from_clusters_matches_the_oracle_with_pages_of_no_cluster():
     """Cluster lists written by the caller, clusters of scattered pages in no particular order and
     seven pages listed nowhere: the file layout derived from them must be the oracle's (clusters
