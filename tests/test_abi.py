@@ -55,6 +55,19 @@ def _cfg(**kw):
     (dict(physical_layers=2), kvd.ERR_SHAPE),
     (dict(micro_batches=99), kvd.ERR_SHAPE),
     (dict(softmax_scale=float("nan")), kvd.ERR_ARG),
+    (dict(softmax_scale=float("inf")), kvd.ERR_ARG),
+    (dict(micro_batches=-2), kvd.ERR_SHAPE),
+    (dict(attn_splits=65), kvd.ERR_SHAPE),
+    (dict(attn_splits=-1), kvd.ERR_SHAPE),
+    (dict(index_centroids=9000, max_pages=16384, capacity_max=256), kvd.ERR_SHAPE),   # more than 8192 centroids
+    (dict(index_centroids=300), kvd.ERR_SHAPE),                                        # more centroids than pages
+    (dict(index_centroids=64, max_pages=20000), kvd.ERR_SHAPE),                        # hierarchical index: at most 16384 pages
+    (dict(index_centroids=-1), kvd.ERR_SHAPE),
+    (dict(batch=9000), kvd.ERR_SHAPE),                                                 # more than 65535 units
+    (dict(n_layers=0), kvd.ERR_SHAPE),
+    (dict(max_pages=0), kvd.ERR_SHAPE),
+    (dict(capacity_max=70000), kvd.ERR_SHAPE),
+    (dict(sink_pages=-1), kvd.ERR_SHAPE),
 ])
 def test_create_rejects_bad_config_without_a_device(kw, want):
     lib = kvd.load()
@@ -75,3 +88,10 @@ def test_create_rejects_small_per_unit_capacity_and_null():
     assert lib.kvd_create(C.byref(cfg), None) == kvd.ERR_ARG
     assert lib.kvd_destroy(None) == kvd.ERR_ARG
     assert lib.kvd_step(None, 0, 0, None, None, None, None) == kvd.ERR_ARG
+    assert lib.kvd_step_layers(None, 0, 1, 0, None, None, None, None) == kvd.ERR_ARG
+    assert lib.kvd_step_tiered(None, 0, 0, None, None, None, None) == kvd.ERR_ARG
+    assert lib.kvd_set_step_form(None, 1) == kvd.ERR_ARG
+    assert lib.kvd_step_form(None) == kvd.ERR_ARG
+    caps_big = (C.c_int32 * 8)(*([256] * 7 + [257]))                  # a unit's capacity above capacity_max
+    cfg.capacity = C.cast(caps_big, C.POINTER(C.c_int32))
+    assert lib.kvd_create(C.byref(cfg), C.byref(ctx)) == kvd.ERR_SHAPE
