@@ -326,6 +326,35 @@ def test_step_parity_units_of_8192_pages_and_more(kw):
     rig.close()
 
 
+@pytest.mark.parametrize("mb,policy", [(-1, "lru"), (1, "lookahead"), (-1, "lookahead")],
+                         ids=["single-launch-lru", "kernel-chain-lookahead", "single-launch-lookahead"])
+def test_step_parity_at_the_largest_sizes_of_the_fused_kernels(mb, policy):
+    """The limits of the register-resident kernels all at once: 16384 pages, 2048 selected pages,
+    a window of 4096 slots, 8 query heads per KV head; the second sequence a little shorter."""
+    w = small("largest", ctx=16 * 16384, topk_pages=2048, capacity=4096, batch=2, n_kv_heads=1, n_q_heads=8,
+              heavy_count=64, steps=6, policy=policy, seed=31337, rho=0.2)     # (a fast-drifting query: the window fills and evicts)
+    rig = R.Rig(w, seq_lens=[w.ctx, w.ctx - 16 * 37 - 9], micro_batches=mb)
+    assert rig.kvd.step_form() == mb
+    units = all_units(rig)
+    rep = R.run_steps(rig, units, w.steps, check_dir_every=2, progress=f"largest-mb{mb}-{policy}")
+    assert rep.unit_steps == w.steps * w.units and rig.kvd.stats().evictions > 0
+    assert rep.tie_divergences <= 4 and rep.victim_tie_divergences <= 4
+    rig.close()
+
+
+def test_step_parity_beyond_the_fused_kernels_sizes():
+    """More pages (16400) and more slots (4100) than the register-resident kernels take: the
+    size-agnostic select / resolve / fetch kernels run without being asked for."""
+    w = small("beyond", ctx=16 * 16400, topk_pages=300, capacity=4100, batch=1, n_kv_heads=2, n_q_heads=4,
+              heavy_count=32, steps=3, seed=31338)
+    rig = R.Rig(w, seq_lens=[w.ctx - 21])
+    assert rig.kvd.step_form() == 1                                   # (no one-launch step at these sizes)
+    units = all_units(rig)
+    rep = R.run_steps(rig, units, w.steps, check_dir_every=2, progress="beyond")
+    assert rep.unit_steps == w.steps * w.units and rep.tie_divergences <= 2
+    rig.close()
+
+
 @pytest.mark.parametrize("mb", [-1, 1], ids=["single-launch", "kernel-chain"])
 def test_step_parity_one_attention_split_per_unit(mb):
     """So few selected pages that a unit's attention is one workgroup (no partials, no merge)."""
