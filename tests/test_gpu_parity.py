@@ -355,6 +355,25 @@ def test_step_parity_beyond_the_fused_kernels_sizes():
     rig.close()
 
 
+@pytest.mark.parametrize("page,n_pages", [(1, 700), (3, 300), (255, 40), (256, 48)])
+def test_step_parity_extreme_page_sizes_and_very_short_sequences(page, n_pages):
+    """Pages of one token, of an odd few, and of the largest sizes (255: not a multiple of the
+    16-token tile, 256: sixteen tiles), in a batch whose second sequence has fewer valid pages than
+    the budget and whose third is a single token long."""
+    w = small("pages", page=page, ctx=page * n_pages, topk_pages=12, capacity=20, batch=3, steps=5, heavy_count=4,
+              seed=2718 + page)
+    seq = [w.ctx - (page // 2), 5 * page + (1 if page > 1 else 0), 1]
+    rig = R.Rig(w, seq_lens=seq)
+    assert (rig.kvd.step_form() == -1) == (page % 16 == 0)
+    units = all_units(rig)
+    rep = R.run_steps(rig, units, w.steps, check_dir_every=2, progress=f"page{page}")
+    assert rep.unit_steps == w.steps * w.units and rep.tie_divergences <= 2
+    # the single-token sequence: one page selected, the rest padding, from the first step on
+    last = rig.n_sel_pages[2 * w.n_kv_heads:]
+    assert np.all(last[:, 0] == 0) and np.all(last[:, 1:] == -1)
+    rig.close()
+
+
 @pytest.mark.parametrize("mb", [-1, 1], ids=["single-launch", "kernel-chain"])
 def test_step_parity_one_attention_split_per_unit(mb):
     """So few selected pages that a unit's attention is one workgroup (no partials, no merge)."""
