@@ -375,6 +375,31 @@ def test_step_parity_extreme_page_sizes_and_very_short_sequences(page, n_pages):
 
 
 @pytest.mark.parametrize("mb", [-1, 1], ids=["single-launch", "kernel-chain"])
+@pytest.mark.parametrize("name,kw", [
+    ("window-equals-budget", dict(topk_pages=24, capacity=24)),                       # every unselected page leaves at once
+    ("window-holds-everything", dict(ctx=16 * 90, topk_pages=24, capacity=90)),       # a page misses once at most
+    ("all-forced", dict(topk_pages=10, capacity=30, sink_pages=4, recent_pages=6)),   # nothing left to choose
+    ("one-unit", dict(batch=1, n_kv_heads=1, n_q_heads=8)),
+    ("many-units", dict(batch=80, n_kv_heads=8, n_q_heads=8, ctx=16 * 64, topk_pages=8, capacity=12, heavy_count=3)),   # 640 units
+    ("lookahead-window-equals-budget", dict(topk_pages=24, capacity=24, policy="lookahead")),
+])
+def test_step_parity_degenerate_windows_and_unit_counts(name, kw, mb):
+    w = small(name, steps=6, **kw)
+    rig = R.Rig(w, micro_batches=mb)
+    units = all_units(rig) if w.units <= 32 else [R.OracleUnit(rig, 0, b, h) for b, h in [(0, 0), (17, 3), (41, 7), (79, 7), (63, 0)]]
+    rep = R.run_steps(rig, units, w.steps, check_dir_every=2, progress=f"{name}-mb{mb}")
+    assert rep.unit_steps == w.steps * len(units) and rep.tie_divergences + rep.victim_tie_divergences <= 2
+    st = rig.kvd.stats()
+    if name == "window-holds-everything":
+        assert st.evictions == 0 and st.misses <= w.units * w.n_pages
+    if name.endswith("window-equals-budget"):
+        assert st.evictions == st.misses - w.units * w.topk_pages     # after the cold step every miss displaces a page
+    if name == "all-forced":
+        assert st.misses == w.units * w.topk_pages                     # the same ten pages every step: cold misses only
+    rig.close()
+
+
+@pytest.mark.parametrize("mb", [-1, 1], ids=["single-launch", "kernel-chain"])
 def test_step_parity_one_attention_split_per_unit(mb):
     """So few selected pages that a unit's attention is one workgroup (no partials, no merge)."""
     w = small("one-split", topk_pages=6, capacity=7, steps=8)
