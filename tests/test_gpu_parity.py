@@ -168,6 +168,48 @@ def test_resolve_trace_parity(n_pages, k, cap):
     rig.close()
 
 
+@pytest.mark.parametrize("generic", [False, True], ids=["fused", "size-agnostic"])
+def test_resolve_and_attention_skip_padding_and_made_up_pages(generic, monkeypatch):
+    """A caller's selection may hold -1 anywhere and pages that do not exist: both count as
+    padding (no slot, no hit, no miss, no tokens), in the directory update and in the attention."""
+    if generic:
+        monkeypatch.setenv("KVD_GENERIC_SELECT", "1")
+    w = small("holes", ctx=16 * 90, topk_pages=10, capacity=14, batch=2, n_kv_heads=2, n_q_heads=8)
+    rig = R.Rig(w, build_index=False)
+    units = all_units(rig)
+    rng = np.random.default_rng(606)
+    q = next(W.query_stream(w, rig.q0, 1, R.DEV))[0]
+    for t in range(6):
+        sel = np.full((w.units, w.topk_pages), -1, dtype=np.int32)
+        for u in range(w.units):
+            real = np.sort(rng.choice(w.n_pages, size=6, replace=False))
+            sel[u, [0, 2, 3, 5, 6, 9]] = real                          # ascending, with holes between
+            sel[u, 4] = w.n_pages + 5                                  # pages that do not exist
+            sel[u, 7] = 2 ** 30
+        rig.sel_pages.copy_(torch.from_numpy(sel))
+        rig.kvd.cache_resolve(0, t, rig.sel_pages, rig.sel_slots, rig.hit_mask, rig.evicted, rig.counts, do_gather=True)
+        rig.kvd.sparse_decode_attn(0, q, rig.sel_pages, rig.sel_slots, rig.out, rig.lse)
+        torch.cuda.synchronize()
+        slots, hm, cnt = rig.sel_slots.cpu().numpy(), rig.hit_mask.cpu().numpy(), rig.counts.cpu().numpy()
+        out, lse = rig.out.cpu().numpy(), rig.lse.cpu().numpy()
+        for ou in units:
+            u = ou.u
+            valid = (sel[u] >= 0) & (sel[u] < w.n_pages)
+            real = sel[u][valid]
+            hits, misses, evicted = ou.window.resolve(real, t)
+            assert np.all(slots[u][~valid] == -1) and np.all(hm[u][~valid] == 0)
+            assert np.all(slots[u][valid] >= 0) and len(set(slots[u][valid].tolist())) == 6
+            assert sorted(real[hm[u][valid] == 1].tolist()) == hits and cnt[u].tolist() == [len(hits), len(misses), len(evicted)]
+            toks = orc.selected_tokens(real, w.page, ou.seq_len)
+            G = w.group
+            want, want_lse = orc.attend(H.f64(q[ou.b, ou.h * G:(ou.h + 1) * G]), ou.keys[toks], ou.values[toks], ou.scale)
+            assert H.attn_rel_err(out[ou.b, ou.h * G:(ou.h + 1) * G], want) <= H.ATTN_RTOL, (t, u)
+            assert np.abs(lse[ou.b, ou.h * G:(ou.h + 1) * G] - want_lse).max() <= 1e-3
+    assert rig.kvd.stats().evictions > 0
+    R.check_directory(rig, 0, units)
+    rig.close()
+
+
 def test_cache_export_import_and_warm_errors():
     w = small("imp", ctx=16 * 100, topk_pages=4, capacity=10, batch=1, n_kv_heads=2, n_q_heads=4)
     rig = R.Rig(w, build_index=False)
