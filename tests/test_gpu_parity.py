@@ -743,11 +743,13 @@ def test_append_kv_errors():
     rig.close()
 
 
-def test_single_launch_step_replayed_from_a_hip_graph():
-    """The one-launch step keeps no host-side state per launch (its flags lower themselves), so a
-    captured launch can be replayed: every replay must equal the eager step on the same inputs."""
+@pytest.mark.parametrize("mb", [-1, 1, 2], ids=["single-launch", "kernel-chain", "two-groups"])
+def test_step_replayed_from_a_hip_graph(mb):
+    """kvd_step keeps no host-side state per call (the one launch's counters and published words
+    return to zero by themselves; the groups fork and join with events only), so a captured step
+    can be replayed: every replay must equal the eager step on the same inputs."""
     w = SCALED[3].replace(steps=8)
-    eager, graphed = R.Rig(w, micro_batches=-1), R.Rig(w, micro_batches=-1)
+    eager, graphed = R.Rig(w, micro_batches=mb), R.Rig(w, micro_batches=mb)
     qs = [q[0].contiguous() for q in W.query_stream(w, eager.q0, 8, R.DEV)]
     for t in range(4):                                                # same history on both sides
         eager.step(0, t, qs[t])
