@@ -442,6 +442,37 @@ def test_step_parity_degenerate_windows_and_unit_counts(name, kw, mb):
 
 
 @pytest.mark.parametrize("mb", [-1, 1], ids=["single-launch", "kernel-chain"])
+@pytest.mark.parametrize("dtype", ["bf16", "f16"])
+def test_step_parity_with_extreme_queries(dtype, mb):
+    """Queries that make the softmax hard: all zeros (every token weighs the same: the output is
+    the mean of the selected values, the scores all tie and the lowest pages are selected), and
+    queries 40 times the usual size (logits of a few hundred either way, one token taking nearly
+    all the weight)."""
+    w = small("extreme-q", dtype=dtype, topk_pages=16, capacity=30, steps=1)
+    rig = R.Rig(w, micro_batches=mb)
+    units = all_units(rig)
+    rep = R.StepReport()
+    q0 = next(W.query_stream(w, rig.q0, 1, R.DEV))[0]
+    zero = torch.zeros_like(q0)
+    rig.step(0, 0, zero)
+    for ou in units:
+        want = R.compare_unit(rig, ou, 0, zero, rep)
+        assert rig.n_sel_pages[ou.u].tolist() == list(range(16))      # all scores 0: ties go to the lowest pages
+        vals = ou.values[: 16 * w.page].mean(axis=0)
+        G = w.group
+        assert np.allclose(rig.n_out[ou.b, ou.h * G:(ou.h + 1) * G], vals[None, :], rtol=0, atol=2e-3 * np.abs(vals).max())
+        assert np.allclose(want["lse"], math.log(16 * w.page))
+    big = (q0.float() * 40.0).to(q0.dtype)
+    for t in (1, 2):
+        rig.step(0, t, big)
+        for ou in units:
+            want = R.compare_unit(rig, ou, t, big, rep)
+            assert np.abs(want["lse"]).max() > 50.0                    # (the logits really are large)
+    assert rep.tie_divergences == 0
+    rig.close()
+
+
+@pytest.mark.parametrize("mb", [-1, 1], ids=["single-launch", "kernel-chain"])
 def test_step_parity_one_attention_split_per_unit(mb):
     """So few selected pages that a unit's attention is one workgroup (no partials, no merge)."""
     w = small("one-split", topk_pages=6, capacity=7, steps=8)
