@@ -309,7 +309,10 @@ def compare_unit(rig: Rig, ou: OracleUnit, t: int, q_layer: torch.Tensor, rep: S
     e = H.attn_rel_err(g_out, want["out"])
     assert e <= H.ATTN_RTOL, f"attention rel err {e:.3e} at unit {u} step {t}"
     le = float(np.abs(g_lse - want["lse"]).max())
-    assert le <= 1e-3, f"lse abs err {le:.3e} at unit {u} step {t}"
+    # lse is computed and returned in fp32 (q.k accumulated over 128 products, the scaling, the log):
+    # a few fp32 steps of its own size, which beyond |lse| ~ 500 is more than 1e-3
+    lse_tol = max(1e-3, 16.0 * float(np.spacing(np.abs(want["lse"]).astype(np.float32)).max()))
+    assert le <= lse_tol, f"lse abs err {le:.3e} at unit {u} step {t}"
     rep.max_attn_err = max(rep.max_attn_err, e)
     rep.max_lse_err = max(rep.max_lse_err, le)
     rep.hits += len(g_hits)

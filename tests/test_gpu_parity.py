@@ -47,6 +47,32 @@ def test_summaries_bit_exact(dtype, page):
     rig.close()
 
 
+@pytest.mark.parametrize("dtype", ["f16", "bf16"])
+def test_summaries_and_step_with_tiny_and_huge_keys(dtype):
+    """Keys at the edges of the format: one sequence's keys scaled into the subnormal range of
+    fp16 (bf16: 2^-125), the other's 4096 times the usual size (fp16: up to a quarter of the largest
+    finite value).  The index must
+    still be the correctly rounded mean (halves of the smallest subnormal round to even), and the
+    step must still agree with the oracle."""
+    w = small("edges", dtype=dtype, ctx=16 * 40, topk_pages=6, capacity=12, batch=2, steps=3)
+    rig = R.Rig(w, build_index=False)
+    tiny, huge = (2.0 ** -20 if dtype == "f16" else 2.0 ** -125), 2.0 ** 12      # (logits of some ten thousands)
+    rig.store[0, 0, :, :, 0] = (rig.store[0, 0, :, :, 0].float() * tiny).to(w.torch_dtype)
+    rig.store[0, 1, :, :, 0] = (rig.store[0, 1, :, :, 0].float() * huge).to(w.torch_dtype)
+    rig.kvd.build_summaries(0)
+    torch.cuda.synchronize()
+    got = rig.summaries.cpu()
+    units = all_units(rig)
+    for ou in units:
+        assert np.array_equal(H.bits(got[0, ou.b, ou.h]), orc.f64_to_bits(ou.summ, ou.code)), (ou.b, ou.h)
+    sub = np.abs(units[0].summ)
+    smallest_normal = 2.0 ** -14 if dtype == "f16" else 2.0 ** -126
+    assert sub.max() < smallest_normal * 64 and (sub[sub > 0] < smallest_normal).any()   # (subnormal summaries do occur)
+    rep = R.run_steps(rig, units, w.steps, check_dir_every=1, progress=f"edges-{dtype}")
+    assert rep.unit_steps == w.steps * w.units
+    rig.close()
+
+
 # --------------------------------------------------------------------------- #
 # stage 1: scores and selection
 # --------------------------------------------------------------------------- #
