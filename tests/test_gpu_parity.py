@@ -498,6 +498,40 @@ def test_step_parity_with_extreme_queries(dtype, mb):
     rig.close()
 
 
+def test_two_contexts_step_concurrently_on_two_streams():
+    """Two contexts of different shapes, forms and policies, their steps enqueued on two streams
+    with no synchronisation between them: neither disturbs the other (the library keeps no state
+    outside its contexts)."""
+    wa = small("ctx-a", dtype="f16", topk_pages=20, capacity=30, steps=6, seed=11)
+    wb = small("ctx-b", dtype="bf16", page=32, ctx=32 * 200, n_q_heads=14, n_kv_heads=2, topk_pages=12, capacity=18,
+               policy="lookahead", steps=6, seed=12)
+    a, b = R.Rig(wa, micro_batches=-1), R.Rig(wb, micro_batches=2)
+    ua, ub = all_units(a), all_units(b)
+    sa, sb = torch.cuda.Stream(), torch.cuda.Stream()
+    rep_a, rep_b = R.StepReport(), R.StepReport()
+    qa, qb = W.query_stream(wa, a.q0, wa.steps, R.DEV), W.query_stream(wb, b.q0, wb.steps, R.DEV)
+    torch.cuda.synchronize()
+    for t in range(6):
+        q1, q2 = next(qa)[0].contiguous(), next(qb)[0].contiguous()
+        torch.cuda.synchronize()                                      # (the queries are ready; the steps below overlap)
+        for rig, q, st in ((a, q1, sa), (b, q2, sb)):
+            rig.kvd.step(0, t, q, rig.out, rig.lse, stream=st)
+            rig.kvd.step_trace(rig.sel_pages, rig.sel_slots, rig.hit_mask, rig.evicted, rig.counts, rig.scores, stream=st)
+        torch.cuda.synchronize()
+        for rig, units, q, rep in ((a, ua, q1, rep_a), (b, ub, q2, rep_b)):
+            rig.n_sel_pages, rig.n_sel_slots = rig.sel_pages.cpu().numpy(), rig.sel_slots.cpu().numpy()
+            rig.n_hit_mask, rig.n_evicted = rig.hit_mask.cpu().numpy(), rig.evicted.cpu().numpy()
+            rig.n_counts, rig.n_scores = rig.counts.cpu().numpy(), rig.scores.cpu().numpy()
+            rig.n_out, rig.n_lse = rig.out.cpu().numpy(), rig.lse.cpu().numpy()
+            for ou in units:
+                R.compare_unit(rig, ou, t, q, rep)
+    R.check_directory(a, 0, ua)
+    R.check_directory(b, 0, ub)
+    assert rep_a.unit_steps == 6 * wa.units and rep_b.unit_steps == 6 * wb.units
+    a.close()
+    b.close()
+
+
 @pytest.mark.parametrize("mb", [-1, 1], ids=["single-launch", "kernel-chain"])
 def test_step_parity_one_attention_split_per_unit(mb):
     """So few selected pages that a unit's attention is one workgroup (no partials, no merge)."""
