@@ -532,6 +532,29 @@ def test_two_contexts_step_concurrently_on_two_streams():
     b.close()
 
 
+@pytest.mark.parametrize("env", [dict(KVD_FUSE_MERGE="0"), dict(KVD_SCORE_BLOCKS="7"), dict(KVD_SCORE_BLOCKS="100000"),
+                                 dict(KVD_FUSE_MERGE="0", KVD_GENERIC_SELECT="1")],
+                         ids=["separate-merge-kernel", "seven-score-blocks", "many-score-blocks", "separate-everything"])
+def test_chain_of_kernels_in_its_other_launch_shapes(env, monkeypatch):
+    """The chain of kernels with the attention splits merged by a kernel of its own instead of by
+    the last split, and with the scoring grid far smaller and far larger than the default."""
+    for k_, v_ in env.items():
+        monkeypatch.setenv(k_, v_)
+    w = small("shapes", ctx=16 * 1500, topk_pages=96, capacity=150, steps=5, n_q_heads=14, n_kv_heads=2, dtype="f16")
+    rig = R.Rig(w, seq_lens=[w.ctx, w.ctx - 16 * 9 - 5], micro_batches=1, attn_splits=5)
+    units = all_units(rig)
+    rep = R.run_steps(rig, units, w.steps, check_dir_every=2, progress="shapes")
+    assert rep.unit_steps == w.steps * w.units and rep.tie_divergences <= 2
+    rig.kvd.set_profiling(1)                                          # the profiled chain brackets the merge kernel too
+    q = next(W.query_stream(w, rig.q0, 1, R.DEV))[0]
+    rig.step(0, w.steps, q)
+    for ou in units:
+        R.compare_unit(rig, ou, w.steps, q, rep)
+    st = rig.kvd.stats()
+    assert st.profiled_steps == 1 and st.ms_attend > 0 and (st.ms_merge > 0) == (env.get("KVD_FUSE_MERGE") == "0")
+    rig.close()
+
+
 @pytest.mark.parametrize("mb", [-1, 1], ids=["single-launch", "kernel-chain"])
 def test_step_parity_one_attention_split_per_unit(mb):
     """So few selected pages that a unit's attention is one workgroup (no partials, no merge)."""
