@@ -1343,6 +1343,43 @@ def test_size_agnostic_select_resolve_kernels(cfg, monkeypatch):
     rig.close()
 
 
+@pytest.mark.parametrize("policy", ["lru", "lookahead"])
+def test_degenerate_victim_keys_take_the_radix_fallback(policy):
+    """Three thousand resident pages that all look alike to the victim choice — warmed long ago
+    (LRU: one age class) or all scoring exactly zero (lookahead: a zero query) — fall into one
+    histogram bucket of more than 1024 candidates, so the choice must fall back to radix
+    refinement and still take the lowest pages (LRU) or the highest (lookahead) first."""
+    w = small("degen-victims", ctx=16 * 4000, topk_pages=64, capacity=3000, heavy_count=0, batch=1, n_kv_heads=2,
+              n_q_heads=4, policy=policy, steps=1)
+    rig = R.Rig(w, build_index=(policy == "lookahead"))
+    warm = list(range(1000, 4000))
+    rig.kvd.cache_warm(0, warm * w.units, [len(warm)] * w.units)
+    units = all_units(rig)
+    for ou in units:
+        ou.window.warm(warm, stamp=-1)
+    rep = R.StepReport()
+    if policy == "lookahead":
+        zero = torch.zeros((w.batch, w.n_q_heads, w.head_dim), dtype=w.torch_dtype, device=R.DEV)
+        rig.step(0, 100, zero)                                        # every score 0: pages 0..63 selected, all of them misses
+        for ou in units:
+            want = R.compare_unit(rig, ou, 100, zero, rep)
+            assert want["misses"] == list(range(64)) and want["evicted"] == list(range(3936, 4000))
+    else:
+        sel = np.tile(np.arange(64, dtype=np.int32), (w.units, 1))
+        rig.sel_pages.copy_(torch.from_numpy(sel))
+        rig.kvd.cache_resolve(0, 100, rig.sel_pages, rig.sel_slots, rig.hit_mask, rig.evicted, rig.counts, do_gather=True)
+        torch.cuda.synchronize()
+        ev = rig.evicted.cpu().numpy()
+        for ou in units:
+            hits, misses, evicted = ou.window.resolve(sel[ou.u], 100)
+            assert (hits, misses, evicted) == ([], list(range(64)), list(range(1000, 1064)))
+            assert sorted(ev[ou.u][ev[ou.u] >= 0].tolist()) == evicted
+            assert rig.counts.cpu().numpy()[ou.u].tolist() == [0, 64, 64]
+    assert rep.victim_tie_divergences == 0
+    R.check_directory(rig, 0, units)
+    rig.close()
+
+
 def test_degenerate_scores_take_the_radix_fallback():
     """More than 1024 pages with exactly the same score land in one histogram bucket: the fused
     kernel must fall back to radix refinement and still pick the lowest pages among the ties."""
