@@ -1343,12 +1343,15 @@ def test_size_agnostic_select_resolve_kernels(cfg, monkeypatch):
     rig.close()
 
 
+@pytest.mark.parametrize("generic", [False, True], ids=["fused", "size-agnostic"])
 @pytest.mark.parametrize("policy", ["lru", "lookahead"])
-def test_degenerate_victim_keys_take_the_radix_fallback(policy):
+def test_degenerate_victim_keys_take_the_radix_fallback(policy, generic, monkeypatch):
     """Three thousand resident pages that all look alike to the victim choice — warmed long ago
     (LRU: one age class) or all scoring exactly zero (lookahead: a zero query) — fall into one
     histogram bucket of more than 1024 candidates, so the choice must fall back to radix
     refinement and still take the lowest pages (LRU) or the highest (lookahead) first."""
+    if generic:
+        monkeypatch.setenv("KVD_GENERIC_SELECT", "1")
     w = small("degen-victims", ctx=16 * 4000, topk_pages=64, capacity=3000, heavy_count=0, batch=1, n_kv_heads=2,
               n_q_heads=4, policy=policy, steps=1)
     rig = R.Rig(w, build_index=(policy == "lookahead"))
