@@ -236,6 +236,33 @@ def test_resolve_and_attention_skip_padding_and_made_up_pages(generic, monkeypat
     rig.close()
 
 
+@pytest.mark.parametrize("policy", ["lru", "lookahead"])
+@pytest.mark.parametrize("mb", [-1, 1], ids=["single-launch", "kernel-chain"])
+def test_cache_survives_export_reset_import_in_mid_run(mb, policy):
+    """After some steps the directory is exported, the cache emptied (and the slot pool wiped) and
+    the directory imported again: the slots are refilled from the host store and decoding goes on
+    exactly as if nothing had happened."""
+    w = small("export", topk_pages=20, capacity=30, steps=9, policy=policy)
+    rig = R.Rig(w, micro_batches=mb)
+    units = all_units(rig)
+    rep = R.StepReport()
+    for t, q in enumerate(W.query_stream(w, rig.q0, w.steps, R.DEV)):
+        if t in (4, 7):
+            sp, st = rig.kvd.cache_export(0)
+            rig.kvd.cache_reset()
+            rig.pool.fill_(float("nan"))
+            empty, _ = rig.kvd.cache_export(0)
+            assert bool((empty == -1).all())
+            rig.kvd.cache_import(0, sp, st)
+            R.check_directory(rig, 0, units)
+        rig.step(0, t, q[0])
+        for ou in units:
+            R.compare_unit(rig, ou, t, q[0], rep)
+    assert rep.unit_steps == w.steps * w.units and rig.kvd.stats().evictions > 0
+    R.check_directory(rig, 0, units)
+    rig.close()
+
+
 def test_cache_export_import_and_warm_errors():
     w = small("imp", ctx=16 * 100, topk_pages=4, capacity=10, batch=1, n_kv_heads=2, n_q_heads=4)
     rig = R.Rig(w, build_index=False)
