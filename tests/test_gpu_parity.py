@@ -664,6 +664,53 @@ def test_layers_in_flight_equal_layers_one_by_one(n_layers, phys, centroids, mb,
     b.close()
 
 
+@pytest.mark.parametrize("mb", [-1, 1], ids=["single-launch", "kernel-chain"])
+def test_layers_in_flight_in_a_growing_store(mb):
+    """A decode loop as a model runs it: all layers stepped (two in flight), then every layer
+    appends its new token, then the sequences advance.  Outputs, directories, slot contents, index
+    and host store must be those of the same loop with the layers stepped one by one."""
+    w = small("layers-append", n_layers=3, physical_layers=3, ctx=16 * 300, topk_pages=24, capacity=30, recent_pages=2,
+              steps=20, batch=2)
+    seq = [w.ctx - 16 * 2 - 7, w.ctx - 16 * 3]
+    a = R.Rig(w, seq_lens=seq, micro_batches=mb)
+    b = R.Rig(w, seq_lens=seq, micro_batches=mb, build_index=False)
+    b.summaries.copy_(a.summaries)
+    L = w.n_layers
+    shape = (L, w.batch, w.n_q_heads, w.head_dim)
+    out_a = torch.empty(shape, dtype=torch.float32, device=R.DEV)
+    out_b = torch.empty(shape, dtype=torch.float32, device=R.DEV)
+    gen = torch.Generator(device="cpu").manual_seed(5)
+    for t, q in enumerate(W.query_stream(w, a.q0, w.steps, R.DEV)):
+        q = q.contiguous()
+        for l in range(L):
+            a.kvd.step(l, t, q[l], out_a[l])
+        b.kvd.step_layers(0, L, t, q, out_b)
+        for l in range(L):
+            k_new = torch.randn((w.batch, w.n_kv_heads, w.head_dim), generator=gen).to(w.torch_dtype).to(R.DEV)
+            v_new = torch.randn((w.batch, w.n_kv_heads, w.head_dim), generator=gen).to(w.torch_dtype).to(R.DEV)
+            a.kvd.append_kv(l, k_new, v_new)
+            b.kvd.append_kv(l, k_new, v_new)
+        a.kvd.advance()
+        b.kvd.advance()
+        torch.cuda.synchronize()
+        if mb == 1:
+            assert torch.equal(out_a, out_b), t
+        else:
+            assert H.attn_rel_err(out_b.cpu().numpy(), out_a.cpu().numpy()) <= 1e-5, t
+        if t % 5 == 4 or t == w.steps - 1:
+            for l in range(L):
+                pa, sa = a.kvd.cache_export(l)
+                pb, sb = b.kvd.cache_export(l)
+                assert torch.equal(pa, pb) and torch.equal(sa, sb), (t, l)
+            assert torch.equal(a.pool.view(torch.int16), b.pool.view(torch.int16)), t
+            assert torch.equal(a.summaries.view(torch.int16), b.summaries.view(torch.int16)), t
+            assert torch.equal(a.store.view(torch.int16), b.store.view(torch.int16)), t
+    sa_, sb_ = a.kvd.stats(), b.kvd.stats()
+    assert (sa_.hits, sa_.misses, sa_.evictions) == (sb_.hits, sb_.misses, sb_.evictions) and sa_.evictions > 0
+    a.close()
+    b.close()
+
+
 def test_step_layers_rejects_ranges_outside_the_context():
     w = small("layers-args", n_layers=2, physical_layers=1)
     rig = R.Rig(w)
