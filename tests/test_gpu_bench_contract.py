@@ -1,0 +1,38 @@
+"""bench.py's one-line contract, on the smallest configuration (needs a GPU)."""
+import json
+import os
+import subprocess
+import sys
+
+import pytest
+
+pytestmark = pytest.mark.gpu
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _run(*args):
+    return subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), *args], capture_output=True, text=True, cwd=ROOT,
+                          timeout=280)
+
+
+def test_bench_prints_one_json_line_with_the_agreed_fields():
+    r = _run("--config", "1", "--steps", "3", "--warmup", "1", "--cpu-seconds", "1")
+    assert r.returncode == 0, r.stderr[-2000:]
+    lines = [l for l in r.stdout.splitlines() if l.strip()]
+    assert len(lines) == 1
+    d = json.loads(lines[0])
+    assert d["metric"] == "decode layer-steps/sec" and d["unit"] == "layer-steps/s" and d["higher_is_better"] is True
+    assert d["n_gpus"] == 1 and d["steps"] == 3 and d["warmup"] == 1 and d["scaling"] == "weak" and d["data"] == "synthetic"
+    assert d["vs_baseline"] is None and d["dtype"] in ("f16", "bf16")
+    assert d["value"] > 0 and abs(d["value"] * d["ms_per_step"] - 1e3) < 1e-6 * 1e3
+    assert "workload" in d["config"] and "model" not in d["config"] and d["config"]["workload"].startswith("cfg1")
+    roof = d["roofline"]
+    assert roof["bound"] == "hbm" and roof["unit"] == "GB/s" and roof["peak"] == 8000.0
+    assert abs(roof["frac"] - roof["achieved"] / roof["peak"]) < 1e-12 and 0 < roof["frac"] < 1 and "traffic" in roof
+    cpu = d["cpu_baseline"]
+    assert cpu["kind"] == "oracle" and cpu["unit"] == "layer-steps/s" and cpu["value"] > 0 and cpu["cores"] >= 1 and cpu["sample"]
+
+
+def test_bench_refuses_more_than_one_gpu():
+    r = _run("--gpus", "2")
+    assert r.returncode != 0 and "one GPU" in r.stderr and r.stdout.strip() == ""
