@@ -85,7 +85,15 @@ typedef struct {
                               -1 = the whole step as one launch in which every (sequence, KV head) unit
                                    moves through the stages on its own, synchronised by counters and
                                    published words in device memory (needs page_size % 16 == 0, max_pages <= 16384,
-                                   capacity_max <= 4096; other shapes run as for 1);
+                                   capacity_max <= 4096; other shapes run as for 1).  A workgroup of that
+                                   launch only ever waits for workgroups with a lower index, and the form
+                                   relies on the GPU starting the workgroups of a one-dimensional grid in
+                                   index order (what a waiting workgroup waits for has then started and
+                                   itself waits only for still lower ones: the launch cannot lock up, and
+                                   neither can two such launches on two streams, whose chains of waits stay
+                                   inside each launch).  The programming model does not promise that order,
+                                   so every wait is bounded (kvd_set_wait_limit_us); should one run out, the
+                                   library recovers by itself as described there;
                               0  = chosen by the library: the one launch where it can run (with units of
                                    more than 8192 pages only from 24 units on), else as for 1;
                               1  = one chain of kernels on the caller's stream, no overlap;
@@ -439,9 +447,16 @@ int kvd_calibrate_step_form(kvd_ctx* ctx, int32_t layer, int32_t first_step, con
                             int32_t steps_per_form, float* out, void* stream, int32_t* chosen_form,
                             float* ms_per_step);
 /* Bound of every wait inside the one-launch kvd_step (micro_batches = -1), where workgroups wait on
- * counters and published words in device memory that the workgroups before them write.  Default 2 s.  A wait that runs out makes
- * its workgroup leave without output and raises a sticky error: kvd_get_stats and later kvd_step
- * calls return KVD_ERR_STATE until kvd_cache_reset.  (A limit of 0 lets tests reach that path.) */
+ * counters and published words in device memory that the workgroups before them write.  Default 2 s.
+ * A wait that runs out makes its workgroup leave without output and raises an error word in host
+ * memory.  While the word is set kvd_get_stats and kvd_step_trace return KVD_ERR_STATE (the step that
+ * failed has no valid output or trace).  The next kvd_step / kvd_step_layers call finds the word,
+ * waits for the device, empties the window of every layer (the failed step may have left a
+ * directory half updated), clears the word, switches the context to the chain of kernels
+ * (kvd_step_form() == 1 from then on, until kvd_set_step_form says otherwise) and returns
+ * KVD_ERR_STATE once, without enqueuing anything; calls after that run normally, from a cold cache.
+ * kvd_cache_reset clears the word too (without changing the form).  (A limit of 0 lets tests reach
+ * that path: every kernel still ends normally.) */
 int kvd_set_wait_limit_us(kvd_ctx* ctx, int64_t microseconds);
 /* Timeline of the last single-launch kvd_step recorded under profiling mode 2.  Synchronises the
  * device.  host_records [capacity][5] receives, for workgroup i < min(capacity, *n_workgroups) in

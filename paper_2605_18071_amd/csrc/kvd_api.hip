@@ -147,12 +147,46 @@ static int reset_directory(kvd_ctx* c, int layer_or_all) {
   const int l0 = layer_or_all < 0 ? 0 : layer_or_all;
   const int nl = layer_or_all < 0 ? c->L : 1;
   const size_t lu = (size_t)l0 * c->U, nu = (size_t)nl * c->U;
-  HIP_TRY(c, kvd_launch_fill_i32(c->d_page_to_slot + lu * c->NP, -1, nu * c->NP, nullptr));
+  if (c->d_page_to_slot) HIP_TRY(c, kvd_launch_fill_i32(c->d_page_to_slot + lu * c->NP, -1, nu * c->NP, nullptr));
   HIP_TRY(c, kvd_launch_fill_i32(c->d_slot_page + lu * c->Cmax, -1, nu * c->Cmax, nullptr));
   HIP_TRY(c, kvd_launch_fill_i32(c->d_slot_stamp + lu * c->Cmax, -1, nu * c->Cmax, nullptr));
   HIP_TRY(c, kvd_launch_fill_i32(c->d_resident + lu, 0, nu, nullptr));
   HIP_TRY(c, hipDeviceSynchronize());
   return KVD_OK;
+}
+
+// Zeroes the words through which the workgroups of a one-launch step synchronise (all scratch sets).
+static int clear_step_flags(kvd_ctx* c) {
+  HIP_TRY(c, hipMemset(c->d_attn_ticket, 0, (size_t)c->U * sizeof(int32_t)));
+  HIP_TRY(c, hipMemset(c->d_score_done, 0, (size_t)c->U * 32 * sizeof(int32_t)));
+  HIP_TRY(c, hipMemset(c->d_sel_entry, 0, (size_t)c->U * c->k * sizeof(unsigned long long)));
+  for (int i = 0; i < c->n_sets; ++i) {
+    if (i == c->cur_set) continue;
+    HIP_TRY(c, hipMemset(c->sets[i].attn_ticket, 0, (size_t)c->U * sizeof(int32_t)));
+    HIP_TRY(c, hipMemset(c->sets[i].score_done, 0, (size_t)c->U * 32 * sizeof(int32_t)));
+    HIP_TRY(c, hipMemset(c->sets[i].sel_entry, 0, (size_t)c->U * c->k * sizeof(unsigned long long)));
+  }
+  return KVD_OK;
+}
+
+// An in-kernel wait of a one-launch step ran out (the error word is set): that step produced no
+// output for the units concerned and may have left their directory half updated.  The library then
+// takes itself out of harm's way: it waits for the device, empties every layer's window, clears
+// the flags and the error word and switches the context to the chain of kernels, which has no
+// waits between workgroups.  The caller is told once, by the status of the call that finds the
+// error; later steps run (from a cold cache, as a chain).  Returns the status to hand back.
+static int recover_from_wait_timeout(kvd_ctx* c) {
+  HIP_TRY(c, hipDeviceSynchronize());
+  int r = clear_step_flags(c);
+  if (r != KVD_OK) return r;
+  r = reset_directory(c, -1);
+  if (r != KVD_OK) return r;
+  *c->error_host = 0;
+  ++c->wait_timeouts;
+  c->cfg.micro_batches = 1;
+  c->MB = 1;
+  c->single_launch = 0;
+  return KVD_ERR_STATE;
 }
 
 extern "C" {
@@ -250,7 +284,9 @@ int kvd_create(const kvd_config* cfg, kvd_ctx** out) {
   auto ok = [&](hipError_t r) { if (e == hipSuccess && r != hipSuccess) e = r; return e == hipSuccess; };
   const size_t Uk = (size_t)c->U * c->k;
   ok(dev_alloc(&c->d_capacity, LU)) && ok(dev_alloc(&c->d_seq_len, (size_t)c->B)) &&
-      ok(dev_alloc(&c->d_page_to_slot, LU * c->NP)) && ok(dev_alloc(&c->d_slot_page, LU * c->Cmax)) &&
+      // (the page -> slot table in device memory serves the size-agnostic kernels only: the
+      // register-resident path rebuilds the map in LDS from the slot array at every launch)
+      (kvd_fast_path_ok(c) || ok(dev_alloc(&c->d_page_to_slot, LU * c->NP))) && ok(dev_alloc(&c->d_slot_page, LU * c->Cmax)) &&
       ok(dev_alloc(&c->d_slot_stamp, LU * c->Cmax)) && ok(dev_alloc(&c->d_resident, LU)) &&
       ok(dev_alloc(&c->d_scores, (size_t)c->U * c->NP)) && ok(dev_alloc(&c->d_sel_pages, Uk)) &&
       ok(dev_alloc(&c->d_sel_slots, Uk)) && ok(dev_alloc(&c->d_hit_mask, Uk)) && ok(dev_alloc(&c->d_evicted, Uk)) &&
@@ -374,12 +410,14 @@ int kvd_bind_tier(kvd_ctx* ctx, kvd_tier* tier) {
     return KVD_ERR_ARG;
   }
   const size_t uk = (size_t)ctx->U * ctx->k;
-  if (!ctx->h_miss_list) {
+  // (each hand-over buffer on its own: a bind that failed half way is completed by the next one)
+  if (!ctx->h_miss_list)
     HIP_TRY(ctx, hipHostMalloc(reinterpret_cast<void**>(&ctx->h_miss_list), uk * 2 * sizeof(int32_t), hipHostMallocDefault));
+  if (!ctx->h_miss_count)
     HIP_TRY(ctx, hipHostMalloc(reinterpret_cast<void**>(&ctx->h_miss_count), (size_t)ctx->U * sizeof(int32_t), hipHostMallocDefault));
+  if (!ctx->h_src_offset)
     HIP_TRY(ctx, hipHostMalloc(reinterpret_cast<void**>(&ctx->h_src_offset), uk * sizeof(int64_t), hipHostMallocDefault));
-    HIP_TRY(ctx, dev_alloc(&ctx->d_src_offset, uk));
-  }
+  if (!ctx->d_src_offset) HIP_TRY(ctx, dev_alloc(&ctx->d_src_offset, uk));
   ctx->tier = tier;
   ctx->tier_pool_dev = static_cast<const char*>(dptr);
   return KVD_OK;
@@ -467,15 +505,8 @@ int kvd_advance(kvd_ctx* ctx, void* stream) {
 int kvd_cache_reset(kvd_ctx* ctx) {
   if (!ctx) return KVD_ERR_ARG;
   HIP_TRY(ctx, hipDeviceSynchronize());
-  HIP_TRY(ctx, hipMemset(ctx->d_attn_ticket, 0, (size_t)ctx->U * sizeof(int32_t)));
-  HIP_TRY(ctx, hipMemset(ctx->d_score_done, 0, (size_t)ctx->U * 32 * sizeof(int32_t)));
-  HIP_TRY(ctx, hipMemset(ctx->d_sel_entry, 0, (size_t)ctx->U * ctx->k * sizeof(unsigned long long)));
-  for (int i = 0; i < ctx->n_sets; ++i) {
-    if (i == ctx->cur_set) continue;
-    HIP_TRY(ctx, hipMemset(ctx->sets[i].attn_ticket, 0, (size_t)ctx->U * sizeof(int32_t)));
-    HIP_TRY(ctx, hipMemset(ctx->sets[i].score_done, 0, (size_t)ctx->U * 32 * sizeof(int32_t)));
-    HIP_TRY(ctx, hipMemset(ctx->sets[i].sel_entry, 0, (size_t)ctx->U * ctx->k * sizeof(unsigned long long)));
-  }
+  const int r = clear_step_flags(ctx);
+  if (r != KVD_OK) return r;
   *ctx->error_host = 0;
   return reset_directory(ctx, -1);
 }
@@ -497,7 +528,8 @@ static int install_directory(kvd_ctx* c, int layer, const std::vector<int32_t>& 
   }
   const size_t lu = (size_t)layer * U;
   HIP_TRY(c, hipDeviceSynchronize());
-  HIP_TRY(c, hipMemcpy(c->d_page_to_slot + lu * NP, p2s.data(), U * NP * sizeof(int32_t), hipMemcpyHostToDevice));
+  if (c->d_page_to_slot)
+    HIP_TRY(c, hipMemcpy(c->d_page_to_slot + lu * NP, p2s.data(), U * NP * sizeof(int32_t), hipMemcpyHostToDevice));
   HIP_TRY(c, hipMemcpy(c->d_slot_page + lu * Cmax, slot_page.data(), U * Cmax * sizeof(int32_t), hipMemcpyHostToDevice));
   HIP_TRY(c, hipMemcpy(c->d_slot_stamp + lu * Cmax, slot_stamp.data(), U * Cmax * sizeof(int32_t), hipMemcpyHostToDevice));
   HIP_TRY(c, hipMemcpy(c->d_resident + lu, resident.data(), U * sizeof(int32_t), hipMemcpyHostToDevice));
@@ -699,7 +731,7 @@ int kvd_step(kvd_ctx* ctx, int32_t layer, int32_t step, const void* q, float* ou
   if (!ctx->summaries || !ctx->pool || !ctx->store_dev || (ctx->Nc > 0 && !ctx->centroids)) return KVD_ERR_STATE;
   kvd_ctx* c = ctx;
   hipStream_t s = static_cast<hipStream_t>(stream);
-  if (*c->error_host != 0) return KVD_ERR_STATE;   // an earlier single-launch step gave up waiting
+  if (*c->error_host != 0) return recover_from_wait_timeout(c);   // an earlier one-launch step gave up waiting
   if (c->profiling == 1) {
     ++c->n_steps;
     c->last_scores = c->d_scores;
@@ -716,7 +748,7 @@ int kvd_step_layers(kvd_ctx* ctx, int32_t layer0, int32_t n_layers, int32_t step
   if (!ctx->summaries || !ctx->pool || !ctx->store_dev || (ctx->Nc > 0 && !ctx->centroids)) return KVD_ERR_STATE;
   kvd_ctx* c = ctx;
   hipStream_t s = static_cast<hipStream_t>(stream);
-  if (*c->error_host != 0) return KVD_ERR_STATE;
+  if (*c->error_host != 0) return recover_from_wait_timeout(c);
   const size_t rows = (size_t)c->B * c->Hq;
   const char* q = static_cast<const char*>(q_layers);
   auto q_of = [&](int i) { return static_cast<const void*>(q + (size_t)i * rows * c->D * 2); };
@@ -784,6 +816,7 @@ int kvd_step_tiered(kvd_ctx* ctx, int32_t layer, int32_t step, const void* q, fl
 int kvd_step_trace(kvd_ctx* ctx, int32_t* sel_pages, int32_t* sel_slots, int32_t* hit_mask, int32_t* evicted,
                    int32_t* counts, float* scores, void* stream) {
   if (!ctx) return KVD_ERR_ARG;
+  if (*ctx->error_host != 0) return KVD_ERR_STATE;    // a one-launch step that has already ended gave up waiting: its trace is not one
   hipStream_t s = static_cast<hipStream_t>(stream);
   const size_t uk = (size_t)ctx->U * ctx->k * sizeof(int32_t);
   if (sel_pages) HIP_TRY(ctx, hipMemcpyAsync(sel_pages, ctx->d_sel_pages, uk, hipMemcpyDeviceToDevice, s));

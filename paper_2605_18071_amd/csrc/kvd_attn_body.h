@@ -312,9 +312,23 @@ __device__ __forceinline__ int attend_mfma_body(const AttnArgs& a, AttnSmem<Grou
 #pragma unroll
     for (int c = 0; c < 4; ++c) tl.v[c] = load_stream16(tb + 256 + c * 64);
   };
-  auto compute = [&](const Tile& tl) {
+  auto compute = [&](Tile& tl) {
     const int ntok = tl.ntok;
     if (ntok == 0) return;
+    if (ntok < 16) {
+      // ragged last tile: the slot holds whatever the store had beyond the sequence's end (a page
+      // is copied whole), and a probability of zero does not silence a NaN or an infinity there,
+      // so those tokens' V elements are blanked.  Lane (., g) holds tokens 4g..4g+3 of a dim in
+      // each half of a V fragment, two tokens per 32-bit word.
+      const int nv = ntok - 4 * g;
+      const u32 m0 = nv >= 2 ? 0xffffffffu : (nv == 1 ? 0x0000ffffu : 0u);
+      const u32 m1 = nv >= 4 ? 0xffffffffu : (nv == 3 ? 0x0000ffffu : 0u);
+#pragma unroll
+      for (int c = 0; c < 4; ++c) {
+        tl.v[c].x &= m0; tl.v[c].y &= m1;
+        tl.v[c].z &= m0; tl.v[c].w &= m1;
+      }
+    }
     f32x4 s = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
     for (int c = 0; c < 4; ++c) s = mfma_qk<BF16>(tl.k[c], LEAN ? sm.qf[c][lane] : qfrag[c], s);

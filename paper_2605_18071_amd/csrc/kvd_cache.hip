@@ -388,6 +388,7 @@ hipError_t kvd_launch_resolve(kvd_ctx* c, int layer, int step, const int32_t* se
                               int32_t* hit_mask, int32_t* evicted, int32_t* counts, int u0, int u1, hipStream_t s) {
   using namespace kvd;
   if (u1 <= u0) return hipSuccess;
+  if (c->d_page_to_slot == nullptr) return hipErrorInvalidValue;   // (contexts of the register-resident path have no such table)
   ResolveArgs a;
   const size_t lu = (size_t)layer * c->U;
   a.capacity = c->d_capacity + lu;

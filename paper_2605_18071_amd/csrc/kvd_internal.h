@@ -36,6 +36,9 @@ struct kvd_ctx {
   kvd_config cfg;
   int L, B, Hq, Hkv, G, D, P, NP, k, Cmax, Lp, U, MB, S;
   int S1;                  // attention split-K factor of the one-launch step (S: of the stand-alone kernel)
+  int S1_max;              // the largest S1 the partials were allocated for
+  int shape_passes;        // one-launch step: passes per scoring chunk, 0 = by rule (kvd_step_shape)
+  int shape_n_score;       // one-launch step: persistent scoring workgroups, 0 = by rule
   int step_threads;        // workgroup size of the one-launch step: one per CU; 512 (256 registers per lane) or 1024 (128 registers)
   int Nc;                  // centroids per unit of the hierarchical index, 0 = flat page index
   int bf16;
@@ -106,6 +109,7 @@ struct kvd_ctx {
   int32_t* h_miss_count;      // pinned [U]
   int64_t* h_src_offset;      // pinned [U][k]
   int64_t* d_src_offset;      // [U][k]
+  int wait_timeouts;          // one-launch steps that gave up waiting (each one switched the context to the chain of kernels)
   int profiling;
   int last_hip;
   uint64_t n_steps;
@@ -138,6 +142,8 @@ hipError_t kvd_launch_attend(kvd_ctx* c, int layer, const void* q, const int32_t
                              hipEvent_t between = nullptr);   // `between`: recorded after the attention kernel, before the merge
 // The whole step as one launch (kvd_step.hip); usable when kvd_single_launch_ok.
 bool kvd_single_launch_ok(const kvd_ctx* c);
+void kvd_step_shape(const kvd_ctx* c, int* passes, int* n_score, int* splits);
+bool kvd_step_shape_ok(const kvd_ctx* c, int passes, int n_score, int splits);
 hipError_t kvd_launch_step(kvd_ctx* c, int layer, int step, const void* q, float* out, float* lse, hipStream_t s);
 hipError_t kvd_launch_refill(kvd_ctx* c, int layer, hipStream_t s);
 hipError_t kvd_launch_build_summaries(kvd_ctx* c, int layer, hipStream_t s);

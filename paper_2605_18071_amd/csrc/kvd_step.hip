@@ -196,6 +196,51 @@ static void launch_step(int threads, int ipt, const StepArgs& a, int n_blocks, h
 
 }  // namespace kvd
 
+// The launch shape of the one-launch step: passes of 64 pages per wave and scoring chunk, number of
+// persistent scoring workgroups, attention splits per unit.  What kvd_set_step_shape /
+// kvd_calibrate_step_shape fixed is taken; the rest follows the rule: scoring workgroups = one
+// round of resident workgroups (one per CU) minus 1/8 left to the selection workgroups that run
+// beside them, and passes such that the chunks of the layer fill whole rounds of the scoring
+// workgroups (time ~ rounds x passes; at equal cost the coarser chunk wins while every scoring
+// workgroup still gets one: fewer reports and acknowledgement waits per byte).
+void kvd_step_shape(const kvd_ctx* c, int* passes, int* n_score, int* splits) {
+  const int score_np = c->Nc > 0 ? c->Nc : c->NP;
+  const int chunk_pages = c->step_threads == kvd::kStepThreadsWide ? kvd::kStepThreadsWide : kvd::kStepThreads;
+  const int slots = c->n_cus;
+  int ns = c->shape_n_score;
+  if (ns <= 0) {
+    int reserve = slots / 8;
+    if (reserve > c->U) reserve = c->U;
+    ns = slots - reserve;
+  }
+  if (ns < 1) ns = 1;
+  int ps = c->shape_passes;
+  if (ps <= 0) {
+    long long best_cost = -1;
+    for (int cand = 1; cand <= 8; ++cand) {
+      const long long chunks = (score_np + (long long)chunk_pages * cand - 1) / ((long long)chunk_pages * cand);
+      const long long rounds = (chunks * c->U + ns - 1) / ns;
+      const long long cost = rounds * cand;
+      if (best_cost < 0 || cost < best_cost || (cost == best_cost && chunks * c->U >= ns)) { best_cost = cost; ps = cand; }
+    }
+  }
+  const int chunks = (score_np + chunk_pages * ps - 1) / (chunk_pages * ps);
+  if (ns > c->U * chunks) ns = c->U * chunks;
+  if (passes) *passes = ps;
+  if (n_score) *n_score = ns;
+  if (splits) *splits = c->S1;
+}
+
+// Which shapes the context can run: passes 1..8; 1..(compute units) scoring workgroups; splits
+// within what the partials were allocated for, a split's entries fitting their LDS staging area,
+// and at least one 16-token tile per wave of a split's workgroup.
+bool kvd_step_shape_ok(const kvd_ctx* c, int passes, int n_score, int splits) {
+  if (passes < 1 || passes > 8 || n_score < 1 || n_score > c->n_cus) return false;
+  if (splits < 1 || splits > c->S1_max || splits > c->k) return false;
+  if ((c->k + splits - 1) / splits > kvd::kAttnIdxCap) return false;
+  return true;
+}
+
 bool kvd_single_launch_ok(const kvd_ctx* c) {
   return kvd_fast_path_ok(c) && c->tiled && c->NP <= kvd::kStepThreadsWide * 16 &&
          (c->k + c->S1 - 1) / c->S1 <= kvd::kAttnIdxCap;   // a split's entries are staged in LDS
@@ -230,28 +275,8 @@ hipError_t kvd_launch_step(kvd_ctx* c, int layer, int step, const void* q, float
   // 16 pages per thread in registers like the 512-thread form does for the others.
   const int threads = c->step_threads == kStepThreadsWide ? kStepThreadsWide : kStepThreads;
   const int chunk_pages = threads;                    // a scoring chunk: every wave 64 pages x passes
-  // Scoring workgroups are persistent: one round of resident workgroups minus the slots left to
-  // the selection workgroups that run beside them.  passes is chosen so that the chunks of the
-  // layer fill whole rounds of the scoring workgroups (time ~ rounds x passes).
-  const int slots = c->n_cus;
-  int reserve = slots / 8;
-  if (reserve > c->U) reserve = c->U;
-  int n_score = slots - reserve;
-  if (n_score < 1) n_score = 1;
-  int best_passes = 1;
-  long long best_cost = -1;
-  for (int passes = 1; passes <= 8; ++passes) {
-    const long long chunks = (score_np + (long long)chunk_pages * passes - 1) / ((long long)chunk_pages * passes);
-    const long long rounds = (chunks * c->U + n_score - 1) / n_score;
-    const long long cost = rounds * passes;
-    // (at equal cost the coarser chunk wins while every scoring workgroup still gets one: fewer
-    // reports and acknowledgement waits per byte)
-    if (best_cost < 0 || cost < best_cost || (cost == best_cost && chunks * c->U >= n_score)) { best_cost = cost; best_passes = passes; }
-  }
-  a.passes = best_passes;
+  kvd_step_shape(c, &a.passes, &a.n_score, nullptr);
   a.chunks = (score_np + chunk_pages * a.passes - 1) / (chunk_pages * a.passes);
-  if (n_score > c->U * a.chunks) n_score = c->U * a.chunks;
-  a.n_score = n_score;
   const int n_blocks = a.n_score + c->U + c->U * c->S1;
   c->tl_workgroups = n_blocks;
   if (c->profiling == 2 && n_blocks <= KVD_TIMELINE_MAX) a.timeline = c->d_timeline;

@@ -404,6 +404,30 @@ def test_step_parity_page_counts_off_the_load_width(n_pages, mb):
     rig.close()
 
 
+@pytest.mark.parametrize("mb", [-1, 1], ids=["single-launch", "kernel-chain"])
+@pytest.mark.parametrize("page,dtype,poison", [(16, "bf16", "nan"), (32, "f16", "inf"), (64, "bf16", "nan"), (8, "bf16", "nan")])
+def test_rows_beyond_the_sequence_end_may_hold_anything(page, dtype, poison, mb):
+    """A store whose rows beyond every sequence's end hold NaNs or infinities (a caller's
+    uninitialised memory): pages are copied whole into their slots, so the attention kernels
+    have to keep those rows out themselves; the ragged last page is selected at every step."""
+    w = small("poisoned-tail", page=page, dtype=dtype, ctx=page * 120, topk_pages=20, capacity=44, steps=4,
+              recent_pages=2)
+    seq_lens = [w.ctx - page - 5, w.ctx - 1]
+    rig = R.Rig(w, seq_lens=seq_lens, micro_batches=mb, build_index=False)
+    bad = float("nan") if poison == "nan" else float("inf")
+    for b, n in enumerate(seq_lens):
+        p0, r = divmod(n, page)
+        rig.store[:, b, :, p0, :, r:, :] = bad
+        rig.store[:, b, :, p0 + 1:] = -bad if poison == "inf" else bad
+    rig.kvd.build_summaries(0)
+    torch.cuda.synchronize()
+    units = all_units(rig)
+    rep = R.run_steps(rig, units, w.steps, check_dir_every=2, progress=f"poisoned-p{page}-mb{mb}")
+    assert rep.unit_steps == w.steps * w.units
+    assert rep.tie_divergences <= 2
+    rig.close()
+
+
 @pytest.mark.parametrize("kw", [
     dict(ctx=16 * 8200, topk_pages=48, capacity=300),                 # 8200 pages: 9 per thread, ragged wave blocks
     dict(ctx=32 * 8192, page=32, dtype="f16", n_q_heads=14, n_kv_heads=2, topk_pages=40, capacity=128, policy="lookahead"),
@@ -1091,13 +1115,29 @@ def test_single_launch_timeline_and_wait_limit():
     with pytest.raises(K.KvdError) as e:
         rig.kvd.stats()
     assert e.value.status == K.ERR_STATE
+    with pytest.raises(K.KvdError) as e:                              # the failed step has no trace either
+        rig.kvd.step_trace(rig.sel_pages)
+    assert e.value.status == K.ERR_STATE
+    # the next step call reports the failure once; the library has then emptied the windows and
+    # taken the chain of kernels, and goes on by itself
+    assert rig.kvd.step_form() == -1
     with pytest.raises(K.KvdError) as e:
         rig.kvd.step(0, 3, qs[3], rig.out, rig.lse)
     assert e.value.status == K.ERR_STATE
-    rig.kvd.set_wait_limit_us(2_000_000)
-    rig.kvd.cache_reset()                                             # clears the error and the flags
+    assert rig.kvd.step_form() == 1
+    rig.kvd.stats()
     units = all_units(rig)                                            # cold again on both sides
     rep = R.StepReport()
+    for t in range(2):
+        rig.step(0, t, qs[t])
+        for ou in units:
+            R.compare_unit(rig, ou, t, qs[t], rep)
+    R.check_directory(rig, 0, units)
+    # back to the one launch with its waits in order, through kvd_cache_reset as well
+    rig.kvd.set_wait_limit_us(2_000_000)
+    rig.kvd.set_step_form(-1)
+    rig.kvd.cache_reset()
+    units = all_units(rig)
     for t in range(2):
         rig.step(0, t, qs[t])
         for ou in units:

@@ -755,6 +755,7 @@ def test_extent_tier_invariants_and_plan_delivers_every_missed_page(E, pool, max
             budget -= len(ext)
             missed.append(pg)
         before = set(tier.stamp)
+        stamps_before = dict(tier.stamp)
         got = tier.fetch(l, t, missed, positions[l])
         need = set(got["needed"])
         assert set(got["hits"]) == need & before and set(got["reads"]) == need - before
@@ -784,6 +785,5 @@ def test_extent_tier_invariants_and_plan_delivers_every_missed_page(E, pool, max
                 place = positions[l][u][p]
                 g = tier.extent_of(l, u, place)
                 assert np.array_equal(pool_bytes[g][place % E], pages[l, u, p])
-        stamps_before = dict(tier.stamp)
     if pool >= L * U * NE:
         assert max(reads_of.values()) == 1                           # nothing is ever read twice
