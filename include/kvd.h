@@ -268,20 +268,21 @@ int kvd_step(kvd_ctx* ctx, int32_t layer, int32_t step, const void* q, float* ou
 /* The same layer-step for the consecutive layers [layer0, layer0 + n_layers) of one decode step,
  * for a caller that has all their queries at hand (a benchmark, or a model that computes the
  * queries of several layers before their attention; layers whose query depends on the previous
- * layer's attention output are stepped one by one with kvd_step).  Two layers are kept in flight:
- * layers alternate between `stream` and one of the library's streams (forked from and joined back
- * into `stream`), each with its own per-step scratch, so that the host-link fetch of one layer's
- * missed pages overlaps the scoring, selection and attention of the next (SFC Disaggregation
- * applied across layers; every layer has its own cache directory and slots, so the results are
- * those of the layers stepped one after another).  Each layer runs as one launch or as the plain
- * chain of kernels, whichever kvd_step_form says; groups of sequences (micro_batches > 1) are not
- * formed here.  With profiling on, or in a context of one layer, the layers simply run one after
- * another on `stream`.  (Three and four layers in flight measured no faster than two.)
+ * layer's attention output are stepped one by one with kvd_step).  Every layer has its own cache
+ * directory and slots, so the results are those of the layers stepped one after another; what
+ * changes is that the layers overlap (SFC Disaggregation applied across layers):
+ *   - where the step runs as one launch, up to 8 layers share a launch whose workgroups are ordered
+ *     so that layer l+1 is scored while layer l is being selected and its missed pages are fetched,
+ *     and layer l is attended while layer l+1 is selected; everything stays on `stream`;
+ *   - where it runs as a chain of kernels, two layers are kept in flight: layers alternate between
+ *     `stream` and one of the library's streams (forked from and joined back into `stream` with
+ *     events), each with its own per-step scratch.  Groups of sequences (micro_batches > 1) are
+ *     not formed here.
+ * With profiling on, or in a context of one layer, the layers simply run one after another on `stream`.
  *   q_layers [n_layers][B][Hq][D] kv_dtype, out_layers [n_layers][B][Hq][D] fp32,
  *   lse_layers [n_layers][B][Hq] fp32 or NULL (all device, 16-byte aligned).
- * Forking and joining use events only: the call can be captured into a HIP graph from `stream`.
- * kvd_step_trace afterwards reports the last of the layers.  Errors as kvd_step; KVD_ERR_ARG when
- * the layer range leaves the context's. */
+ * The call can be captured into a HIP graph from `stream`.  kvd_step_trace afterwards reports the
+ * last of the layers.  Errors as kvd_step; KVD_ERR_ARG when the layer range leaves the context's. */
 int kvd_step_layers(kvd_ctx* ctx, int32_t layer0, int32_t n_layers, int32_t step, const void* q_layers,
                     float* out_layers, float* lse_layers, void* stream);
 
@@ -446,6 +447,38 @@ int kvd_set_step_form(kvd_ctx* ctx, int32_t form);
 int kvd_calibrate_step_form(kvd_ctx* ctx, int32_t layer, int32_t first_step, const void* q_steps, int32_t n_queries,
                             int32_t steps_per_form, float* out, void* stream, int32_t* chosen_form,
                             float* ms_per_step);
+/* Launch shape of the one-launch step.  Four numbers: how many passes of 64 pages a scoring wave
+ * makes per chunk it takes (1..8); how many persistent scoring workgroups a group has (1..compute
+ * units; the other compute units are left to the selection workgroups, and to attention workgroups
+ * of units already selected, while scoring goes on); the attention splits per unit (at most twice
+ * what kvd_create chose, at most 512 selected pages per split); and the number of groups (1..8) the
+ * units of a layer are cut into: the groups follow each other through the launch, group g+1 being
+ * scored while group g is selected and its missed pages are fetched, group g attended while group g+1
+ * is selected — the micro-batches of SFC Disaggregation, pipelined by the order of the launch's
+ * workgroups.  The context holds two shapes: multi_layer == 0 for launches of one layer (kvd_step),
+ * != 0 for launches of several layers (kvd_step_layers, where consecutive layers are pipelined the
+ * same way).  0 leaves a number to the library's rule.  kvd_set_step_shape waits for the device;
+ * KVD_ERR_SHAPE for a shape the context cannot run.  kvd_get_step_shape writes the four numbers a
+ * launch would take now (host, 4 ints).  Results do not depend on the shape. */
+int kvd_set_step_shape(kvd_ctx* ctx, int32_t multi_layer, int32_t passes, int32_t scoring_workgroups, int32_t attn_splits,
+                       int32_t groups);
+int kvd_get_step_shape(const kvd_ctx* ctx, int32_t multi_layer, int32_t* shape);
+/* Pre-run calibration of that launch shape (Pipeline Optimization: index size, cache size and
+ * micro-batch size are found by a short calibration before inference begins; here the knobs are the
+ * four above, which decide how scoring, selection and attention of different units overlap inside
+ * the launch).  n_layers == 1 calibrates the shape of kvd_step on `layer`; n_layers > 1 that of
+ * kvd_step_layers on layers [layer, layer + n_layers), with q_layers / out_layers as there.  Runs
+ * the step once, so that every page the queries select is resident, then replays that same step —
+ * pure GPU work — in every shape of a grid (scoring workgroups from all compute units down to a
+ * quarter, 1..4 passes, splits from a quarter of the rule's to twice, 1 / 2 / 4 groups for one layer),
+ * launches_per_shape timed replays each after two untimed ones, HIP events on `stream`; the eight
+ * fastest are timed once more, three times as long, a shape's smaller time counts, and the fastest
+ * is kept.  chosen_shape (host, 4 ints), us_chosen and us_rule (microseconds per layer-step in the
+ * shape kept and in the rule's) may be NULL.  The replays count in kvd_get_stats; the outputs are
+ * the step's.  Synchronous.  KVD_ERR_STATE if the step does not run as one launch or profiling is on. */
+int kvd_calibrate_step_shape(kvd_ctx* ctx, int32_t layer, int32_t n_layers, int32_t step, const void* q_layers,
+                             float* out_layers, void* stream, int32_t launches_per_shape, int32_t* chosen_shape,
+                             float* us_chosen, float* us_rule);
 /* Bound of every wait inside the one-launch kvd_step (micro_batches = -1), where workgroups wait on
  * counters and published words in device memory that the workgroups before them write.  Default 2 s.
  * A wait that runs out makes its workgroup leave without output and raises an error word in host

@@ -4,6 +4,7 @@
 #include <stdlib.h>
 #include <string.h>
 
+#include <algorithm>
 #include <vector>
 
 #include "kvd_internal.h"
@@ -143,6 +144,16 @@ static void use_scratch_set(kvd_ctx* c, int set) {
   c->cur_set = set;
 }
 
+kvd_scratch kvd_scratch_set(const kvd_ctx* c, int i) {
+  if (i != c->cur_set) return c->sets[i];
+  kvd_scratch o;
+  o.scores = c->d_scores; o.sel_pages = c->d_sel_pages; o.sel_slots = c->d_sel_slots; o.hit_mask = c->d_hit_mask;
+  o.evicted = c->d_evicted; o.counts = c->d_counts; o.miss_list = c->d_miss_list; o.miss_count = c->d_miss_count;
+  o.part_acc = c->d_part_acc; o.part_ml = c->d_part_ml; o.attn_ticket = c->d_attn_ticket; o.score_done = c->d_score_done;
+  o.sel_entry = c->d_sel_entry;
+  return o;
+}
+
 static int reset_directory(kvd_ctx* c, int layer_or_all) {
   const int l0 = layer_or_all < 0 ? 0 : layer_or_all;
   const int nl = layer_or_all < 0 ? c->L : 1;
@@ -271,7 +282,12 @@ int kvd_create(const kvd_config* cfg, kvd_ctx** out) {
     if (S2 > c->k) S2 = c->k;
     c->S1 = S2 < 1 ? 1 : S2;
   }
-  const int Smax = c->S > c->S1 ? c->S : c->S1;
+  // (room in the partials for the splits a calibration of the launch shape may try: twice the rule's)
+  c->S1_max = cfg->attn_splits == 0 ? 2 * c->S1 : c->S1;
+  if (c->S1_max > KVD_MAX_SPLITS) c->S1_max = KVD_MAX_SPLITS;
+  if (c->S1_max > c->k) c->S1_max = c->k;
+  if (c->S1_max < c->S1) c->S1_max = c->S1;
+  const int Smax = c->S > c->S1_max ? c->S : c->S1_max;
 
   const size_t LU = (size_t)c->L * c->U;
   c->h_capacity = static_cast<int32_t*>(malloc(LU * sizeof(int32_t)));
@@ -302,7 +318,7 @@ int kvd_create(const kvd_config* cfg, kvd_ctx** out) {
   c->n_sets = 1;
   if (e == hipSuccess && c->L >= 2) {
     // layers in flight (kvd_step_layers): further sets of the per-step scratch
-    const int want = c->L < KVD_LAYER_LANES ? c->L : KVD_LAYER_LANES;
+    const int want = c->L < KVD_MAX_SETS ? c->L : KVD_MAX_SETS;
     for (int i = 1; i < want && e == hipSuccess; ++i) {
       kvd_scratch& x = c->sets[i];
       c->n_sets = i + 1;                               // (what was allocated of it is freed with the context)
@@ -694,7 +710,7 @@ static int enqueue_step(kvd_ctx* c, int layer, int step, const void* q, float* o
   ++c->n_steps;
   c->last_scores = c->d_scores;
   if (c->single_launch) {
-    HIP_TRY(c, kvd_launch_step(c, layer, step, q, out, lse, s));
+    HIP_TRY(c, kvd_launch_step(c, layer, 1, step, q, out, lse, s));
     return KVD_OK;
   }
   if (c->MB <= 1 || !groups) {
@@ -754,7 +770,24 @@ int kvd_step_layers(kvd_ctx* ctx, int32_t layer0, int32_t n_layers, int32_t step
   auto q_of = [&](int i) { return static_cast<const void*>(q + (size_t)i * rows * c->D * 2); };
   auto out_of = [&](int i) { return out_layers + (size_t)i * rows * c->D; };
   auto lse_of = [&](int i) { return lse_layers ? lse_layers + (size_t)i * rows : nullptr; };
-  const int lanes = c->n_sets < n_layers ? c->n_sets : n_layers;
+  if (c->single_launch && c->profiling == 0 && c->n_sets >= 2 && n_layers >= 2) {
+    // one launch for up to n_sets layers at a time, the layers pipelined through the compute units by
+    // the launch's block order; everything on the caller's stream
+    int done = 0;
+    while (done < n_layers) {
+      const int n = n_layers - done < c->n_sets ? n_layers - done : c->n_sets;
+      c->n_steps += (uint64_t)n;
+      c->last_scores = nullptr;
+      if (n == 1) use_scratch_set(c, 0);
+      HIP_TRY(c, kvd_launch_step(c, layer0 + done, n, step, q_of(done), out_of(done), lse_of(done), s));
+      use_scratch_set(c, n - 1);                       // kvd_step_trace reports the last layer
+      c->last_scores = c->d_scores;
+      done += n;
+    }
+    return KVD_OK;
+  }
+  int lanes = c->n_sets < n_layers ? c->n_sets : n_layers;
+  if (lanes > KVD_LAYER_LANES) lanes = KVD_LAYER_LANES;
   if (lanes < 2 || c->profiling != 0) {
     for (int i = 0; i < n_layers; ++i) {
       const int r = kvd_step(c, layer0 + i, step, q_of(i), out_of(i), lse_of(i), stream);
@@ -911,6 +944,118 @@ int kvd_calibrate_step_form(kvd_ctx* ctx, int32_t layer, int32_t first_step, con
   }
   *chosen_form = best;
   return kvd_set_step_form(ctx, best);
+}
+
+int kvd_set_step_shape(kvd_ctx* ctx, int32_t multi_layer, int32_t passes, int32_t scoring_workgroups, int32_t attn_splits,
+                       int32_t groups) {
+  if (!ctx) return KVD_ERR_ARG;
+  if (passes < 0 || scoring_workgroups < 0 || attn_splits < 0 || groups < 0) return KVD_ERR_SHAPE;
+  if (scoring_workgroups > ctx->n_cus || groups > 8) return KVD_ERR_SHAPE;   // (more groups than units: as many groups as units)
+  const kvd_shape want = {passes, scoring_workgroups, attn_splits, groups};
+  if (!kvd_step_shape_ok(ctx, kvd_step_shape(ctx, multi_layer, &want))) return KVD_ERR_SHAPE;
+  HIP_TRY(ctx, hipDeviceSynchronize());               // (launches in flight keep the shape they were given)
+  ctx->shape[multi_layer ? 1 : 0] = want;
+  return KVD_OK;
+}
+
+int kvd_get_step_shape(const kvd_ctx* ctx, int32_t multi_layer, int32_t* shape) {
+  if (!ctx || !shape) return KVD_ERR_ARG;
+  const kvd_shape e = kvd_step_shape(ctx, multi_layer);
+  shape[0] = e.passes; shape[1] = e.n_score; shape[2] = e.splits; shape[3] = e.groups;
+  return KVD_OK;
+}
+
+int kvd_calibrate_step_shape(kvd_ctx* ctx, int32_t layer, int32_t n_layers, int32_t step, const void* q_layers, float* out_layers,
+                             void* stream, int32_t launches_per_shape, int32_t* chosen_shape, float* us_chosen, float* us_rule) {
+  if (!ctx || !q_layers || !out_layers || layer < 0 || n_layers < 1 || (long long)layer + n_layers > ctx->L ||
+      launches_per_shape < 1 || !aligned16(q_layers))
+    return KVD_ERR_ARG;
+  if (!ctx->summaries || !ctx->pool || !ctx->store_dev || (ctx->Nc > 0 && !ctx->centroids)) return KVD_ERR_STATE;
+  if (!ctx->single_launch || ctx->profiling != 0) return KVD_ERR_STATE;
+  kvd_ctx* c = ctx;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  hipEvent_t e0 = c->ev_prof[10], e1 = c->ev_prof[11];
+  const int multi = n_layers > 1 ? 1 : 0;
+  auto one = [&]() -> int {
+    return multi ? kvd_step_layers(c, layer, n_layers, step, q_layers, out_layers, nullptr, s)
+                 : kvd_step(c, layer, step, q_layers, out_layers, nullptr, s);
+  };
+  // the step once as it is: afterwards every page the queries select is resident, and the replays
+  // below are pure GPU work
+  int r = one();
+  if (r != KVD_OK) return r;
+  HIP_TRY(c, hipStreamSynchronize(s));
+  // Times `n` replays in the current shape, after two untimed ones; microseconds per layer-step.
+  auto time_shape = [&](int n, double* us) -> int {
+    for (int i = 0; i < n + 2; ++i) {
+      if (i == 2) HIP_TRY(c, hipEventRecord(e0, s));
+      const int rr = one();
+      if (rr != KVD_OK) return rr;
+    }
+    HIP_TRY(c, hipEventRecord(e1, s));
+    HIP_TRY(c, hipEventSynchronize(e1));
+    float ms = 0.f;
+    HIP_TRY(c, hipEventElapsedTime(&ms, e0, e1));
+    *us = 1e3 * ms / ((double)n * n_layers);
+    return KVD_OK;
+  };
+  struct Timed { kvd_shape shape; double us; };
+  std::vector<Timed> shapes;
+  const kvd_shape nothing = {0, 0, 0, 0};
+  const kvd_shape rule = kvd_step_shape(c, multi, &nothing);
+  auto same = [](const kvd_shape& a, const kvd_shape& b) {
+    return a.passes == b.passes && a.n_score == b.n_score && a.splits == b.splits && a.groups == b.groups;
+  };
+  auto add = [&](const kvd_shape& want) {
+    const kvd_shape e = kvd_step_shape(c, multi, &want);
+    if (!kvd_step_shape_ok(c, e)) return;
+    for (const Timed& x : shapes)
+      if (same(x.shape, e)) return;
+    shapes.push_back({e, 0.0});
+  };
+  add(nothing);
+  // The grid: scoring workgroups from every compute unit (no slot left to the selections while a
+  // group is scored) down to a quarter of them; 1..4 passes; splits from a quarter of the rule's to
+  // twice; a layer in 1, 2 or 4 groups (launches of several layers, which the layers already
+  // pipeline: one group).
+  const int sr = rule.splits;
+  for (int g : {1, 2, 4}) {
+    if (multi && g > 1) break;
+    for (int sp : {sr / 4, sr / 2, (3 * sr) / 4, sr, (3 * sr) / 2, 2 * sr})
+      for (int eighths = 8; eighths >= 2; --eighths)
+        for (int p = 1; p <= 4; ++p)
+          if (sp >= 1) add({p, c->n_cus * eighths / 8, sp, g});
+  }
+  auto apply = [&](const kvd_shape& x) { c->shape[multi] = x; };
+  const kvd_shape before = c->shape[multi];
+  for (Timed& x : shapes) {
+    apply(x.shape);
+    r = time_shape(launches_per_shape, &x.us);
+    if (r != KVD_OK) { apply(before); return r; }
+  }
+  const double rule_us = shapes[0].us;
+  // the eight fastest once more, three times as long; the smaller of a shape's two times counts
+  // (what disturbs a run only ever adds time)
+  std::sort(shapes.begin(), shapes.end(), [](const Timed& a, const Timed& b) { return a.us < b.us; });
+  const size_t top = shapes.size() < 8 ? shapes.size() : 8;
+  for (size_t i = 0; i < top; ++i) {
+    apply(shapes[i].shape);
+    double us = 0.0;
+    r = time_shape(3 * launches_per_shape, &us);
+    if (r != KVD_OK) { apply(before); return r; }
+    if (us < shapes[i].us) shapes[i].us = us;
+  }
+  size_t best = 0;
+  for (size_t i = 1; i < top; ++i)
+    if (shapes[i].us < shapes[best].us) best = i;
+  apply(shapes[best].shape);
+  if (chosen_shape) {
+    chosen_shape[0] = shapes[best].shape.passes; chosen_shape[1] = shapes[best].shape.n_score;
+    chosen_shape[2] = shapes[best].shape.splits; chosen_shape[3] = shapes[best].shape.groups;
+  }
+  if (us_chosen) *us_chosen = (float)shapes[best].us;
+  if (us_rule) *us_rule = (float)rule_us;
+  return KVD_OK;
 }
 
 int kvd_step_form(const kvd_ctx* ctx) {

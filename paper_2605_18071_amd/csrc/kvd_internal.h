@@ -13,7 +13,8 @@ constexpr int KVD_FAST_MAX_CAPACITY = 4096; // register-resident directory scan:
 constexpr int KVD_MAX_PAGE = 256;       // P
 constexpr int KVD_MAX_MICRO = 16;       // micro-batches per step
 constexpr int KVD_PIPE_STREAMS = 3;      // side streams a step may spread its micro-batches over
-constexpr int KVD_LAYER_LANES = 2;       // layers kvd_step_layers keeps in flight (three and four measured no faster)
+constexpr int KVD_LAYER_LANES = 2;       // layers kvd_step_layers keeps in flight on streams as chains of kernels (three and four measured no faster)
+constexpr int KVD_MAX_SETS = 8;          // sets of per-step scratch: the layers one launch of the one-launch step can cover
 constexpr int KVD_MAX_SPLITS = 64;      // attention split-K factor
 constexpr int KVD_MAX_CENTROIDS = 8192;   // centroids per unit of the hierarchical index (16-bit cluster numbers, <= 65535 pages each)
 constexpr int KVD_TIMELINE_MAX = 1 << 16; // workgroups of a single-launch step whose times can be recorded
@@ -22,6 +23,11 @@ namespace kvd {
 struct FastArgs;
 struct AttnArgs;
 }  // namespace kvd
+
+// Launch shape of the one-launch step: passes of 64 pages per scoring wave and chunk, persistent
+// scoring workgroups (per group), attention splits per unit, groups of units pipelined through the
+// launch one behind the other.
+struct kvd_shape { int passes, n_score, splits, groups; };
 
 // The per-step scratch of one layer-step in flight (the d_* fields of the context of the same names).
 struct kvd_scratch {
@@ -35,10 +41,10 @@ struct kvd_scratch {
 struct kvd_ctx {
   kvd_config cfg;
   int L, B, Hq, Hkv, G, D, P, NP, k, Cmax, Lp, U, MB, S;
-  int S1;                  // attention split-K factor of the one-launch step (S: of the stand-alone kernel)
-  int S1_max;              // the largest S1 the partials were allocated for
-  int shape_passes;        // one-launch step: passes per scoring chunk, 0 = by rule (kvd_step_shape)
-  int shape_n_score;       // one-launch step: persistent scoring workgroups, 0 = by rule
+  int S1;                  // attention split-K factor of the one-launch step as kvd_create chose it (S: of the stand-alone kernel)
+  int S1_max;              // the largest split factor the partials were allocated for
+  kvd_shape shape[2];      // launch shape of the one-launch step as set or calibrated, 0 = left to the rule:
+                           // [0] launches of one layer (kvd_step), [1] launches of several layers (kvd_step_layers)
   int step_threads;        // workgroup size of the one-launch step: one per CU; 512 (256 registers per lane) or 1024 (128 registers)
   int Nc;                  // centroids per unit of the hierarchical index, 0 = flat page index
   int bf16;
@@ -85,7 +91,7 @@ struct kvd_ctx {
   // kvd_step_layers keeps several layers in flight, each with its own set of the per-step scratch
   // above: the d_* fields hold set `cur_set`, the others wait in `sets` (contexts of two layers
   // and more; sets[cur_set] itself is stale)
-  kvd_scratch sets[KVD_LAYER_LANES];
+  kvd_scratch sets[KVD_MAX_SETS];
   int n_sets, cur_set;
 
   // owned, host
@@ -142,9 +148,15 @@ hipError_t kvd_launch_attend(kvd_ctx* c, int layer, const void* q, const int32_t
                              hipEvent_t between = nullptr);   // `between`: recorded after the attention kernel, before the merge
 // The whole step as one launch (kvd_step.hip); usable when kvd_single_launch_ok.
 bool kvd_single_launch_ok(const kvd_ctx* c);
-void kvd_step_shape(const kvd_ctx* c, int* passes, int* n_score, int* splits);
-bool kvd_step_shape_ok(const kvd_ctx* c, int passes, int n_score, int splits);
-hipError_t kvd_launch_step(kvd_ctx* c, int layer, int step, const void* q, float* out, float* lse, hipStream_t s);
+// The shape a launch takes: `want` (default: what the context holds for that kind of launch) with
+// its zeros filled in by the rule and the scoring workgroups capped at the number of chunks.
+kvd_shape kvd_step_shape(const kvd_ctx* c, int multi_layer, const kvd_shape* want = nullptr);
+bool kvd_step_shape_ok(const kvd_ctx* c, const kvd_shape& effective);
+// Layers [layer, layer + n_layers) of one decode step in one launch, layer `layer + i` in scratch set i
+// (q / out / lse: the layers one after another); n_layers == 1: the context's current set.
+hipError_t kvd_launch_step(kvd_ctx* c, int layer, int n_layers, int step, const void* q, float* out, float* lse, hipStream_t s);
+// Scratch set i of the context, wherever its pointers currently are (kvd_api.hip).
+kvd_scratch kvd_scratch_set(const kvd_ctx* c, int i);
 hipError_t kvd_launch_refill(kvd_ctx* c, int layer, hipStream_t s);
 hipError_t kvd_launch_build_summaries(kvd_ctx* c, int layer, hipStream_t s);
 bool kvd_centroid_mode(const kvd_ctx* c);

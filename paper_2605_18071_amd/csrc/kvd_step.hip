@@ -11,6 +11,17 @@
 //     then one selection workgroup per unit (with the hierarchical index it scores nothing itself:
 //     the scoring workgroups score the centroids and it expands the best clusters into pages);
 //     then S attention workgroups per unit.
+// A launch may cover several consecutive layers of one decode step (kvd_step_layers, for a caller
+// that has all their queries at hand).  The layers' blocks are then interleaved so that in-order
+// dispatch pipelines the layers through the compute units:
+//     score(0) select(0) | score(1) select(1) attend(0) | score(2) select(2) attend(1) | ... | attend(n-1)
+// — the scoring of layer l+1 streams while layer l's units are being selected (and their missed
+// pages fetched), and layer l's attention streams while layer l+1 is selected.  Every layer of the
+// launch has its own directory, slots and set of per-step scratch; dependencies stay inside a layer
+// and point to lower block indices only.
+// The units of one layer can likewise be cut into groups that follow each other through the launch in
+// the same interleaved order (SFC Disaggregation's micro-batches, pipelined by dispatch order instead
+// of by streams): groups of one layer share the layer's scratch set, since all of it is indexed by unit.
 // A selection workgroup waits until the unit's scoring waves have all arrived (a counter);
 // an attention workgroup waits until the entries of its split have been published by the unit's
 // selection workgroup (one word per selected page, published when the page is in its slot and
@@ -40,6 +51,19 @@ namespace kvd {
 constexpr int kStepThreads = 512;            // 256 registers per lane: three tile buffers in the attention role
 constexpr int kStepThreadsWide = 1024;       // 128 registers per lane: units of more pages than 512 threads keep in registers
 
+constexpr int kStepMaxLayers = KVD_MAX_SETS;   // layers one launch can cover: each needs a set of per-step scratch
+
+// The per-step scratch of one layer of the launch.
+struct StepLayerSet {
+  float* scores;
+  int32_t *sel_pages, *sel_slots, *hit_mask, *evicted, *counts, *miss_list, *miss_count;
+  float *part_acc, *part_ml;
+  int32_t *attn_ticket, *score_done;
+  u64* sel_entry;
+};
+
+// The fields outside `sets` and the strides describe layer 0 of the launch; layer i of the launch
+// (context layer layer0 + i) is found `i` strides further and works in sets[i].
 struct StepArgs {
   const uint16_t* summ;      // [U][score_np][D] of the layer: the page summaries, or the centroids of the hierarchical index
   const uint16_t* q;         // [B][Hq][D]
@@ -56,6 +80,15 @@ struct StepArgs {
   int n_units, u0, chunks, passes, n_score;
   int score_np;              // rows scored per unit: NP, or the number of centroids Nc
   int Nc;                    // 0 = flat page index
+  int n_layers;              // layers covered by the launch
+  int groups, group_units;   // the units of a layer go through the launch in `groups` groups of group_units units (the last may be smaller)
+  int layer0, Lp;            // first context layer; layers of the host store (layer l reads store layer l % Lp)
+  const char* store_base;    // host store, layer 0 (device-visible address)
+  long long summ_stride, q_stride, out_stride, lse_stride;           // elements between consecutive layers
+  long long cluster_start_stride, cluster_pages_stride;              // elements
+  long long pool_stride, store_stride;                               // bytes
+  long long dir_unit_stride, dir_slot_stride, dir_page_stride;       // elements: [U], [U][Cmax] and [U][NP] tables
+  StepLayerSet sets[kStepMaxLayers];
 };
 
 template <int NT>
@@ -74,11 +107,12 @@ constexpr int kFlagStride = 32;   // ints between the flags of two units: one 12
 
 // Scoring workgroup `wg` of n_score: chunks wg, wg + n_score, ... of the layer, unit by unit.
 template <bool BF16, int NT>
-__device__ __forceinline__ void step_score_role(StepArgsPtr ap, int wg, long long* ts) {
+__device__ __forceinline__ void step_score_role(StepArgsPtr ap, int li, int u0, int n_units, int wg, long long* ts) {
   struct { const uint16_t* summ; const uint16_t* q; float* scores; int32_t* score_done; float scale;
            int n_units, chunks, n_score, u0, passes; struct { int Hkv, NP; } fa; struct { int Hq, G; } at; } a;   // (fa.NP: rows scored per unit)
-  a.summ = ap->summ; a.q = ap->q; a.scores = ap->scores; a.score_done = ap->score_done; a.scale = ap->scale;
-  a.n_units = ap->n_units; a.chunks = ap->chunks; a.n_score = ap->n_score; a.u0 = ap->u0; a.passes = ap->passes;
+  a.summ = ap->summ + (long long)li * ap->summ_stride; a.q = ap->q + (long long)li * ap->q_stride;
+  a.scores = ap->sets[li].scores; a.score_done = ap->sets[li].score_done; a.scale = ap->scale;
+  a.n_units = n_units; a.chunks = ap->chunks; a.n_score = ap->n_score; a.u0 = u0; a.passes = ap->passes;
   a.fa.Hkv = ap->fa.Hkv; a.fa.NP = ap->score_np; a.at.Hq = ap->at.Hq; a.at.G = ap->at.G;
   const int tid = threadIdx.x;
   const int w = tid / kWave, lane = tid & (kWave - 1);
@@ -100,11 +134,25 @@ __device__ __forceinline__ void step_score_role(StepArgsPtr ap, int wg, long lon
 // Selection, directory update and fetch of unit u: latency-bound, so its waves go first whenever
 // they can issue.
 template <int NT, int IPT>
-__device__ __forceinline__ void step_select_role(StepArgsPtr ap, int u, unsigned char* smem_raw, int* wait_ok,
+__device__ __forceinline__ void step_select_role(StepArgsPtr ap, int li, int u, unsigned char* smem_raw, int* wait_ok,
                                                            long long* ts) {
   struct { FastArgs fa; int32_t* score_done; int32_t* error; long long wait_limit; int chunks; } a;
   __builtin_memcpy(&a.fa, &ap->fa, sizeof(FastArgs));
-  a.score_done = ap->score_done; a.error = ap->error;
+  {
+    // this layer's directory, slots, stored pages and scratch
+    const long long l = li;
+    a.fa.capacity += l * ap->dir_unit_stride;
+    a.fa.resident += l * ap->dir_unit_stride;
+    a.fa.slot_page += l * ap->dir_slot_stride;
+    a.fa.slot_stamp += l * ap->dir_slot_stride;
+    if (a.fa.page_cluster != nullptr) a.fa.page_cluster += l * ap->dir_page_stride;
+    a.fa.pool += l * ap->pool_stride;
+    a.fa.store = ap->store_base + (long long)((ap->layer0 + li) % ap->Lp) * ap->store_stride;
+    a.fa.scores = ap->sets[li].scores; a.fa.sel_pages = ap->sets[li].sel_pages; a.fa.sel_slots = ap->sets[li].sel_slots;
+    a.fa.sel_entry = ap->sets[li].sel_entry; a.fa.hit_mask = ap->sets[li].hit_mask; a.fa.evicted = ap->sets[li].evicted;
+    a.fa.counts = ap->sets[li].counts; a.fa.miss_list = ap->sets[li].miss_list; a.fa.miss_count = ap->sets[li].miss_count;
+  }
+  a.score_done = ap->sets[li].score_done; a.error = ap->error;
   a.wait_limit = ap->wait_limit; a.chunks = ap->chunks;
   const int tid = threadIdx.x;
   if (ts) ts[4] = 1LL | ((long long)u << 8);
@@ -124,7 +172,8 @@ __device__ __forceinline__ void step_select_role(StepArgsPtr ap, int u, unsigned
     done = scores_ready();
     if (done) {
       typename StepSmem<NT>::Cluster& cs = *reinterpret_cast<typename StepSmem<NT>::Cluster*>(smem_raw);
-      cluster_select_body<NT, true>(a.fa.scores, ap->cluster_start, ap->cluster_pages, a.fa.sel_pages, a.fa.seq_len, a.fa.NP,
+      cluster_select_body<NT, true>(a.fa.scores, ap->cluster_start + (long long)li * ap->cluster_start_stride,
+                                    ap->cluster_pages + (long long)li * ap->cluster_pages_stride, a.fa.sel_pages, a.fa.seq_len, a.fa.NP,
                                     ap->Nc, a.fa.P, a.fa.k, a.fa.sink, a.fa.recent, a.fa.Hkv, u, cs);
       __syncthreads();                                 // the selection is complete; the cluster tables are dead
       done = select_resolve_body<NT, 4, false, true, true>(a.fa, u, sm);
@@ -141,9 +190,18 @@ __device__ __forceinline__ void step_select_role(StepArgsPtr ap, int u, unsigned
 
 // Attention workgroup (u, split).
 template <bool BF16, int NT, bool LEAN>
-__device__ __forceinline__ void step_attend_role(StepArgsPtr ap, int u, int split, unsigned char* smem_raw, long long* ts) {
+__device__ __forceinline__ void step_attend_role(StepArgsPtr ap, int li, int u, int split, unsigned char* smem_raw, long long* ts) {
   struct { AttnArgs at; } a;
   __builtin_memcpy(&a.at, &ap->at, sizeof(AttnArgs));
+  {
+    const long long l = li;
+    a.at.q += l * ap->q_stride;
+    a.at.pool += l * ap->pool_stride;
+    a.at.out += l * ap->out_stride;
+    if (a.at.lse != nullptr) a.at.lse += l * ap->lse_stride;
+    a.at.sel_pages = ap->sets[li].sel_pages; a.at.sel_slots = ap->sets[li].sel_slots; a.at.sel_entry = ap->sets[li].sel_entry;
+    a.at.part_acc = ap->sets[li].part_acc; a.at.part_ml = ap->sets[li].part_ml; a.at.ticket = ap->sets[li].attn_ticket;
+  }
   if (ts) ts[4] = 2LL | ((long long)u << 8) | ((long long)split << 32);
   typename StepSmem<NT>::Attn& sm = *reinterpret_cast<typename StepSmem<NT>::Attn*>(smem_raw);
   const int done = attend_mfma_body<BF16, 0, NT, true, LEAN>(a.at, sm, u, split, ts ? ts + 1 : nullptr);
@@ -156,16 +214,33 @@ __device__ __forceinline__ void step_body(StepArgsPtr ap, unsigned char* smem_ra
   const int bid = blockIdx.x;
   long long* timeline = ap->timeline;
   long long* ts = timeline != nullptr && threadIdx.x == 0 ? timeline + (size_t)bid * 5 : nullptr;
-  if (ts) ts[0] = ts[1] = wall_clock64();
-  const int n_score = ap->n_score, n_units = ap->n_units, u0 = ap->u0, S = ap->at.S;
-  const int front = n_score + n_units;
-  if (bid < n_score) {
-    step_score_role<BF16, NT>(ap, bid, ts);
-  } else if (bid < front) {
-    step_select_role<NT, IPT>(ap, bid - n_score + u0, smem_raw, &wait_ok, ts);
+  if (ts) { ts[0] = ts[1] = ts[2] = ts[3] = wall_clock64(); ts[4] = 3LL; }   // (role 3: a workgroup beyond its group's units, which leaves at once)
+  const int n_score = ap->n_score, S = ap->at.S, groups = ap->groups, Ug = ap->group_units;
+  const int n_stages = ap->n_layers * groups;          // (layer, group) pairs, in order
+  const int front = n_score + Ug, back = Ug * S;
+  // block order: front(0) | front(1) back(0) | front(2) back(1) | ... | back(n-1), where front(i) =
+  // the scoring and selection workgroups of stage i and back(i) its attention workgroups
+  int st = 0, o = bid;
+  bool is_back = false;
+  if (bid >= front) {
+    const int r = bid - front, per = front + back;
+    const int g = r / per;
+    o = r % per;
+    if (g < n_stages - 1) {
+      if (o < front) { st = g + 1; } else { st = g; o -= front; is_back = true; }
+    } else {
+      st = n_stages - 1; is_back = true;
+    }
+  }
+  const int li = st / groups, u0 = ap->u0 + (st % groups) * Ug;
+  int n_units = ap->n_units - (st % groups) * Ug;       // units of this group
+  n_units = n_units < Ug ? n_units : Ug;
+  if (is_back) {
+    if (o / S < n_units) step_attend_role<BF16, NT, LEAN>(ap, li, o / S + u0, o % S, smem_raw, ts);
+  } else if (o < n_score) {
+    step_score_role<BF16, NT>(ap, li, u0, n_units, o, ts);
   } else {
-    const int i = bid - front;
-    step_attend_role<BF16, NT, LEAN>(ap, i / S + u0, i % S, smem_raw, ts);
+    if (o - n_score < n_units) step_select_role<NT, IPT>(ap, li, o - n_score + u0, smem_raw, &wait_ok, ts);
   }
 }
 
@@ -196,48 +271,55 @@ static void launch_step(int threads, int ipt, const StepArgs& a, int n_blocks, h
 
 }  // namespace kvd
 
-// The launch shape of the one-launch step: passes of 64 pages per wave and scoring chunk, number of
-// persistent scoring workgroups, attention splits per unit.  What kvd_set_step_shape /
-// kvd_calibrate_step_shape fixed is taken; the rest follows the rule: scoring workgroups = one
-// round of resident workgroups (one per CU) minus 1/8 left to the selection workgroups that run
-// beside them, and passes such that the chunks of the layer fill whole rounds of the scoring
-// workgroups (time ~ rounds x passes; at equal cost the coarser chunk wins while every scoring
-// workgroup still gets one: fewer reports and acknowledgement waits per byte).
-void kvd_step_shape(const kvd_ctx* c, int* passes, int* n_score, int* splits) {
+// The launch shape of the one-launch step.  What kvd_set_step_shape / kvd_calibrate_step_shape fixed
+// is taken; the rest follows the rule: one group; scoring workgroups = one round of resident
+// workgroups (one per CU) minus 1/8 left to the selection workgroups that run beside them; passes
+// such that the chunks of a group fill whole rounds of its scoring workgroups (time ~ rounds x
+// passes; at equal cost the coarser chunk wins while every scoring workgroup still gets one: fewer
+// reports and acknowledgement waits per byte); splits as kvd_create chose them.
+kvd_shape kvd_step_shape(const kvd_ctx* c, int multi_layer, const kvd_shape* want) {
+  kvd_shape w = want ? *want : c->shape[multi_layer ? 1 : 0];
   const int score_np = c->Nc > 0 ? c->Nc : c->NP;
   const int chunk_pages = c->step_threads == kvd::kStepThreadsWide ? kvd::kStepThreadsWide : kvd::kStepThreads;
   const int slots = c->n_cus;
-  int ns = c->shape_n_score;
+  kvd_shape e;
+  e.groups = w.groups > 0 ? w.groups : 1;
+  if (e.groups > c->U) e.groups = c->U;
+  const int Ug = (c->U + e.groups - 1) / e.groups;      // units per group
+  e.groups = (c->U + Ug - 1) / Ug;                      // (no empty group)
+  int ns = w.n_score;
   if (ns <= 0) {
     int reserve = slots / 8;
-    if (reserve > c->U) reserve = c->U;
+    if (reserve > Ug) reserve = Ug;
     ns = slots - reserve;
   }
   if (ns < 1) ns = 1;
-  int ps = c->shape_passes;
+  int ps = w.passes;
   if (ps <= 0) {
     long long best_cost = -1;
     for (int cand = 1; cand <= 8; ++cand) {
       const long long chunks = (score_np + (long long)chunk_pages * cand - 1) / ((long long)chunk_pages * cand);
-      const long long rounds = (chunks * c->U + ns - 1) / ns;
+      const long long rounds = (chunks * Ug + ns - 1) / ns;
       const long long cost = rounds * cand;
-      if (best_cost < 0 || cost < best_cost || (cost == best_cost && chunks * c->U >= ns)) { best_cost = cost; ps = cand; }
+      if (best_cost < 0 || cost < best_cost || (cost == best_cost && chunks * Ug >= ns)) { best_cost = cost; ps = cand; }
     }
   }
   const int chunks = (score_np + chunk_pages * ps - 1) / (chunk_pages * ps);
-  if (ns > c->U * chunks) ns = c->U * chunks;
-  if (passes) *passes = ps;
-  if (n_score) *n_score = ns;
-  if (splits) *splits = c->S1;
+  if (ns > Ug * chunks) ns = Ug * chunks;
+  e.passes = ps;
+  e.n_score = ns;
+  e.splits = w.splits > 0 ? w.splits : c->S1;
+  return e;
 }
 
 // Which shapes the context can run: passes 1..8; 1..(compute units) scoring workgroups; splits
-// within what the partials were allocated for, a split's entries fitting their LDS staging area,
-// and at least one 16-token tile per wave of a split's workgroup.
-bool kvd_step_shape_ok(const kvd_ctx* c, int passes, int n_score, int splits) {
-  if (passes < 1 || passes > 8 || n_score < 1 || n_score > c->n_cus) return false;
-  if (splits < 1 || splits > c->S1_max || splits > c->k) return false;
-  if ((c->k + splits - 1) / splits > kvd::kAttnIdxCap) return false;
+// within what the partials were allocated for, with a split's entries fitting their LDS staging
+// area; 1..8 groups.
+bool kvd_step_shape_ok(const kvd_ctx* c, const kvd_shape& e) {
+  if (e.passes < 1 || e.passes > 8 || e.n_score < 1 || e.n_score > c->n_cus) return false;
+  if (e.splits < 1 || e.splits > c->S1_max || e.splits > c->k) return false;
+  if ((c->k + e.splits - 1) / e.splits > kvd::kAttnIdxCap) return false;
+  if (e.groups < 1 || e.groups > 8) return false;
   return true;
 }
 
@@ -246,8 +328,9 @@ bool kvd_single_launch_ok(const kvd_ctx* c) {
          (c->k + c->S1 - 1) / c->S1 <= kvd::kAttnIdxCap;   // a split's entries are staged in LDS
 }
 
-hipError_t kvd_launch_step(kvd_ctx* c, int layer, int step, const void* q, float* out, float* lse, hipStream_t s) {
+hipError_t kvd_launch_step(kvd_ctx* c, int layer, int n_layers, int step, const void* q, float* out, float* lse, hipStream_t s) {
   using namespace kvd;
+  if (n_layers < 1 || n_layers > kStepMaxLayers || n_layers > c->n_sets || layer + n_layers > c->L) return hipErrorInvalidValue;
   StepArgs a;
   const int score_np = c->Nc > 0 ? c->Nc : c->NP;
   a.summ = reinterpret_cast<const uint16_t*>(c->Nc > 0 ? c->centroids : c->summaries) + (size_t)layer * c->U * score_np * kHeadDim;
@@ -262,8 +345,9 @@ hipError_t kvd_launch_step(kvd_ctx* c, int layer, int step, const void* q, float
   a.at = kvd_attn_args(c, layer, q, c->d_sel_pages, c->d_sel_slots, out, lse, 0);
   a.at.fuse_merge = 1;
   a.at.sel_entry = c->d_sel_entry;
-  a.at.S = c->S1;
-  a.at.per_split = (c->k + c->S1 - 1) / c->S1;
+  const kvd_shape shape = kvd_step_shape(c, n_layers > 1);
+  a.at.S = shape.splits;
+  a.at.per_split = (c->k + shape.splits - 1) / shape.splits;
   a.score_done = c->d_score_done;
   a.error = c->error_dev;
   a.timeline = nullptr;
@@ -271,13 +355,47 @@ hipError_t kvd_launch_step(kvd_ctx* c, int layer, int step, const void* q, float
   a.scale = c->scale;
   a.n_units = c->U;
   a.u0 = 0;
+  // the layers of the launch: layer `layer + i` works in scratch set i
+  a.n_layers = n_layers;
+  a.layer0 = layer;
+  a.Lp = c->Lp;
+  a.store_base = c->store_dev;
+  a.summ_stride = (long long)c->U * score_np * kHeadDim;
+  a.q_stride = (long long)c->B * c->Hq * kHeadDim;
+  a.out_stride = (long long)c->B * c->Hq * kHeadDim;
+  a.lse_stride = (long long)c->B * c->Hq;
+  a.cluster_start_stride = (long long)c->U * (c->Nc + 1);
+  a.cluster_pages_stride = (long long)c->U * c->NP;
+  a.pool_stride = (long long)c->U * c->Cmax * (long long)c->page_bytes;
+  a.store_stride = (long long)c->U * c->NP * (long long)c->page_bytes;
+  a.dir_unit_stride = c->U;
+  a.dir_slot_stride = (long long)c->U * c->Cmax;
+  a.dir_page_stride = (long long)c->U * c->NP;
+  for (int i = 0; i < kStepMaxLayers; ++i) {
+    const kvd_scratch x = kvd_scratch_set(c, i < n_layers ? i : 0);
+    StepLayerSet& d = a.sets[i];
+    d.scores = x.scores; d.sel_pages = x.sel_pages; d.sel_slots = x.sel_slots; d.hit_mask = x.hit_mask; d.evicted = x.evicted;
+    d.counts = x.counts; d.miss_list = x.miss_list; d.miss_count = x.miss_count; d.part_acc = x.part_acc; d.part_ml = x.part_ml;
+    d.attn_ticket = x.attn_ticket; d.score_done = x.score_done; d.sel_entry = x.sel_entry;
+  }
+  if (n_layers == 1) {
+    // (a single layer works in the context's current set, whichever that is)
+    StepLayerSet& d = a.sets[0];
+    d.scores = c->d_scores; d.sel_pages = c->d_sel_pages; d.sel_slots = c->d_sel_slots; d.hit_mask = c->d_hit_mask;
+    d.evicted = c->d_evicted; d.counts = c->d_counts; d.miss_list = c->d_miss_list; d.miss_count = c->d_miss_count;
+    d.part_acc = c->d_part_acc; d.part_ml = c->d_part_ml; d.attn_ticket = c->d_attn_ticket; d.score_done = c->d_score_done;
+    d.sel_entry = c->d_sel_entry;
+  }
   // Units of more than 8192 pages take the 1024-thread form, whose selection role keeps at most
   // 16 pages per thread in registers like the 512-thread form does for the others.
   const int threads = c->step_threads == kStepThreadsWide ? kStepThreadsWide : kStepThreads;
   const int chunk_pages = threads;                    // a scoring chunk: every wave 64 pages x passes
-  kvd_step_shape(c, &a.passes, &a.n_score, nullptr);
+  a.passes = shape.passes;
+  a.n_score = shape.n_score;
+  a.groups = shape.groups;
+  a.group_units = (c->U + shape.groups - 1) / shape.groups;
   a.chunks = (score_np + chunk_pages * a.passes - 1) / (chunk_pages * a.passes);
-  const int n_blocks = a.n_score + c->U + c->U * c->S1;
+  const int n_blocks = n_layers * a.groups * (a.n_score + a.group_units + a.group_units * shape.splits);
   c->tl_workgroups = n_blocks;
   if (c->profiling == 2 && n_blocks <= KVD_TIMELINE_MAX) a.timeline = c->d_timeline;
   const int ipt = (c->NP + chunk_pages - 1) / chunk_pages;

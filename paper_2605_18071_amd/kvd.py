@@ -69,6 +69,7 @@ EXPORTS = [
     "kvd_tier_patch_page", "kvd_tier_fetch", "kvd_tier_trace", "kvd_tier_pooled", "kvd_tier_drop_pool", "kvd_tier_get_stats",
     "kvd_tier_reset_stats", "kvd_tier_sequential_read_gbps", "kvd_layout_from_clusters", "kvd_bind_tier",
     "kvd_step_tiered", "kvd_step_layers",
+    "kvd_set_step_shape", "kvd_get_step_shape", "kvd_calibrate_step_shape",
 ]
 
 _lib = None
@@ -132,6 +133,9 @@ def load() -> C.CDLL:
         "kvd_layout_from_clusters": [vp, i32, vp],
         "kvd_bind_tier": [vp, vp],
         "kvd_step_tiered": [vp, i32, i32, vp, vp, vp, vp],
+        "kvd_set_step_shape": [vp, i32, i32, i32, i32, i32],
+        "kvd_get_step_shape": [vp, i32, i32p],
+        "kvd_calibrate_step_shape": [vp, i32, i32, i32, vp, vp, vp, i32, i32p, f32p, f32p],
     }
     for name, args in protos.items():
         fn = getattr(lib, name)
@@ -336,6 +340,27 @@ class Kvd:
                                                      steps_per_form, out.data_ptr(), _stream_handle(stream),
                                                      C.byref(chosen), ms), "kvd_calibrate_step_form")
         return chosen.value, {f: ms[i] for i, f in enumerate((1, 2, 4, -1)) if ms[i] >= 0}
+
+    def set_step_shape(self, passes: int = 0, scoring_workgroups: int = 0, attn_splits: int = 0, groups: int = 0,
+                       multi_layer: bool = False):
+        self._check(self.lib.kvd_set_step_shape(self.ctx, 1 if multi_layer else 0, passes, scoring_workgroups, attn_splits,
+                                                groups), "kvd_set_step_shape")
+
+    def step_shape(self, multi_layer: bool = False):
+        """(passes, scoring workgroups, attention splits, groups) a launch of the one-launch step would take."""
+        shape = (C.c_int32 * 4)()
+        self._check(self.lib.kvd_get_step_shape(self.ctx, 1 if multi_layer else 0, shape), "kvd_get_step_shape")
+        return tuple(shape)
+
+    def calibrate_step_shape(self, layer: int, step: int, q: torch.Tensor, out: torch.Tensor, launches_per_shape: int = 16,
+                             n_layers: int = 1, stream=None):
+        """Returns ((passes, scoring workgroups, splits, groups), us per layer-step of it, us per layer-step of the rule's shape)."""
+        shape = (C.c_int32 * 4)()
+        us, us_rule = C.c_float(), C.c_float()
+        self._check(self.lib.kvd_calibrate_step_shape(self.ctx, layer, n_layers, step, q.data_ptr(), out.data_ptr(),
+                                                      _stream_handle(stream), launches_per_shape, shape, C.byref(us),
+                                                      C.byref(us_rule)), "kvd_calibrate_step_shape")
+        return tuple(shape), us.value, us_rule.value
 
     def set_wait_limit_us(self, microseconds: int):
         self._check(self.lib.kvd_set_wait_limit_us(self.ctx, int(microseconds)), "kvd_set_wait_limit_us")

@@ -152,21 +152,45 @@ class Rig:
             self.tier.close()
 
 
+class StoreRows:
+    """The K (which = 0) or V (1) rows of one unit of the host store, [tokens, D], widened to
+    float64 only where they are read: rows[token indices] -> float64 [n, D].  Lets the oracle
+    follow every unit of a full-size configuration without a float64 copy of the whole store."""
+
+    def __init__(self, unit_store: torch.Tensor, which: int):
+        self.kv, self.which = unit_store, which                             # [NP, 2, P, D] in the KV dtype
+        self.page = unit_store.shape[2]
+        self.shape = (unit_store.shape[0] * self.page, unit_store.shape[3])
+
+    def __getitem__(self, tokens) -> np.ndarray:
+        t = torch.as_tensor(np.asarray(tokens, dtype=np.int64))
+        return H.f64(self.kv[t // self.page, self.which, t % self.page])
+
+    def all(self) -> np.ndarray:
+        return H.f64(self.kv[:, self.which]).reshape(self.shape)
+
+
 class OracleUnit:
     """The oracle's view of one (layer, b, h): its slice of the host store, its own
     summaries, and its LRU window carried across steps."""
 
-    def __init__(self, rig: Rig, layer: int, b: int, h: int, summaries: Optional[np.ndarray] = None):
+    def __init__(self, rig: Rig, layer: int, b: int, h: int, summaries: Optional[np.ndarray] = None, lazy: bool = False):
+        """lazy: keep no float64 copy of the unit's K and V (full-size configurations: 256 MiB per
+        unit and more); rows are widened where the oracle reads them."""
         w = rig.w
         self.rig, self.layer, self.b, self.h = rig, layer, b, h
         self.u = b * w.n_kv_heads + h
         lp = layer % w.phys_layers
         kv = rig.store[lp, b, h]                                            # [NP, 2, P, D]
-        self.keys = H.f64(kv[:, 0]).reshape(-1, w.head_dim)
-        self.values = H.f64(kv[:, 1]).reshape(-1, w.head_dim)
         self.seq_len = rig.seq_lens[b]
         self.code = H.dtype_code(w.torch_dtype)
-        self.summ = orc.page_summaries(self.keys, w.page, self.seq_len, self.code)
+        if lazy:
+            self.keys, self.values = StoreRows(kv, 0), StoreRows(kv, 1)
+            self.summ = orc.page_summaries(self.keys.all(), w.page, self.seq_len, self.code)
+        else:
+            self.keys = H.f64(kv[:, 0]).reshape(-1, w.head_dim)
+            self.values = H.f64(kv[:, 1]).reshape(-1, w.head_dim)
+            self.summ = orc.page_summaries(self.keys, w.page, self.seq_len, self.code)
         if summaries is not None:                                  # a test planted its own index
             self.summ = summaries[: self.summ.shape[0]]
         make = orc.LookaheadWindow if w.policy == "lookahead" else orc.LruWindow
@@ -248,14 +272,12 @@ def compare_unit(rig: Rig, ou: OracleUnit, t: int, q_layer: torch.Tensor, rep: S
     w = rig.w
     u, k = ou.u, w.topk_pages
     g_sel = rig.n_sel_pages[u]
-    qg = H.f64(q_layer[ou.b, ou.h * w.group:(ou.h + 1) * w.group])
     hier = ou.centroids is not None
-    if hier:
-        o_scores = orc.page_scores(orc.pooled_query(qg), ou.centroids, ou.scale)
-        o_sel = orc.select_pages_hier(o_scores, ou.members, k, ou.summ.shape[0], w.sink_pages, w.recent_pages)
-    else:
-        o_scores = orc.page_scores(orc.pooled_query(qg), ou.summ, ou.scale)
-        o_sel = orc.select_pages(o_scores, k, w.sink_pages, w.recent_pages)
+    # the oracle's own step first; where the GPU's selection differs from it inside the tie band
+    # the step is taken again from the same window with the GPU's selection
+    before = dict(ou.window.stamp)
+    want = ou.step(t, q_layer)
+    o_scores, o_sel = want["scores"], want["sel"]
     n_valid = o_scores.shape[0]
     if check_scores:
         g_scores = rig.n_scores[u, :n_valid].astype(np.float64)
@@ -272,8 +294,8 @@ def compare_unit(rig: Rig, ou: OracleUnit, t: int, q_layer: torch.Tensor, rep: S
         assert ok, f"selection differs outside the tie band at unit {u} step {t}: {msg}"
         rep.tie_divergences += 1
         forced = g_sel
-    before = dict(ou.window.stamp)
-    want = ou.step(t, q_layer, forced_sel=forced)
+        ou.window.stamp = dict(before)
+        want = ou.step(t, q_layer, forced_sel=forced)
 
     # cache trace: hit / miss / evicted sets, bit-exact
     hm = rig.n_hit_mask[u]

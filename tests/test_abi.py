@@ -95,3 +95,4 @@ def test_create_rejects_small_per_unit_capacity_and_null():
     caps_big = (C.c_int32 * 8)(*([256] * 7 + [257]))                  # a unit's capacity above capacity_max
     cfg.capacity = C.cast(caps_big, C.POINTER(C.c_int32))
     assert lib.kvd_create(C.byref(cfg), C.byref(ctx)) == kvd.ERR_SHAPE
+

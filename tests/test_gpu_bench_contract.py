@@ -16,7 +16,7 @@ def _run(*args):
 
 
 def test_bench_prints_one_json_line_with_the_agreed_fields():
-    r = _run("--config", "1", "--steps", "3", "--warmup", "1", "--cpu-seconds", "1")
+    r = _run("--config", "1", "--steps", "3", "--warmup", "1", "--cpu-seconds", "1", "--cpu-workers", "2", "--no-other-configs")
     assert r.returncode == 0, r.stderr[-2000:]
     lines = [l for l in r.stdout.splitlines() if l.strip()]
     assert len(lines) == 1
@@ -29,8 +29,31 @@ def test_bench_prints_one_json_line_with_the_agreed_fields():
     roof = d["roofline"]
     assert roof["bound"] == "hbm" and roof["unit"] == "GB/s" and roof["peak"] == 8000.0
     assert abs(roof["frac"] - roof["achieved"] / roof["peak"]) < 1e-12 and 0 < roof["frac"] < 1 and "traffic" in roof
+    assert roof["launch_us_median_min_max"][1] <= roof["launch_us_median_min_max"][0] <= roof["launch_us_median_min_max"][2]
+    assert abs(roof["avg_launch_ms"] * 1e3 - roof["launch_us_median_min_max"][0]) < 1e-9
+    res = d["gpu_resident"]
+    for leg in ("replay_one_query", "rotating"):
+        assert res[leg]["misses"] == 0 and res[leg]["repeats"] >= 3 and res[leg]["launches_per_repeat"] >= 20
+        assert res[leg]["us_min"] <= res[leg]["us_per_launch_median"] <= res[leg]["us_max"]
+    assert abs(roof["achieved"] - res["rotating"]["GBps"]) < 1e-9
     cpu = d["cpu_baseline"]
-    assert cpu["kind"] == "oracle" and cpu["unit"] == "layer-steps/s" and cpu["value"] > 0 and cpu["cores"] >= 1 and cpu["sample"]
+    assert cpu["kind"] == "oracle" and cpu["unit"] == "layer-steps/s" and cpu["value"] > 0 and cpu["cores"] == 2 and cpu["sample"]
+    assert "configs" not in d
+
+
+def test_bench_reports_the_other_configurations_too():
+    """The default run adds one entry per other configuration of the benchmark definition."""
+    r = _run("--config", "1", "--steps", "3", "--warmup", "1", "--cpu-seconds", "0")
+    assert r.returncode == 0, r.stderr[-2000:]
+    d = json.loads([l for l in r.stdout.splitlines() if l.strip()][-1])
+    assert sorted(d["configs"]) == ["cfg2", "cfg3", "cfg4", "cfg5"]
+    for name, c in d["configs"].items():
+        assert c["workload"].startswith(name) and c["layer_steps_per_s"] > 0 and 0 <= c["hit_rate"] <= 1
+        g = c["gpu_resident"]
+        assert g["misses"] == 0 and 0 < g["frac_of_hbm_peak"] < 1 and g["us_min"] <= g["us_per_launch_median"] <= g["us_max"]
+        assert c["step_form"].startswith("one launch")
+    assert "gpu_resident_layers_overlapped" in d["configs"]["cfg2"] and "gpu_resident_layers_overlapped" in d["configs"]["cfg4"]
+    assert "cpu_baseline" not in d
 
 
 def test_bench_refuses_more_than_one_gpu():

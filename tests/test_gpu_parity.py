@@ -620,13 +620,17 @@ def test_step_parity_one_attention_split_per_unit(mb):
 
 @pytest.mark.parametrize("policy", ["lru", "lookahead"])
 @pytest.mark.parametrize("mb", [-1, 1, 2], ids=["single-launch", "kernel-chain", "two-groups"])
-@pytest.mark.parametrize("n_layers,phys,centroids", [(4, 2, 0), (3, 3, 0), (3, 2, 48)])
+@pytest.mark.parametrize("n_layers,phys,centroids", [(4, 2, 0), (3, 3, 0), (3, 2, 48), (10, 2, 0)])
 def test_layers_in_flight_equal_layers_one_by_one(n_layers, phys, centroids, mb, policy):
-    """kvd_step_layers keeps two layers in flight on two streams with two scratch sets.  Every
+    """kvd_step_layers overlaps the layers: as one launch whose workgroups are ordered so that the
+    layers (up to 8 per launch; 10 layers take two launches) pipeline through the compute units, in
+    several launch shapes, or as chains of kernels on two streams with two scratch sets.  Every
     layer has its own directory and slots, so scores, traces, directories and slot contents must be
     those of the layers stepped one by one, and the outputs too (bit for bit with the chain of
     kernels; up to the order in which the splits are merged in one launch).  The one-by-one run is
     compared with the oracle at every layer-step."""
+    if n_layers == 10 and (mb == 2 or policy == "lookahead"):
+        pytest.skip("ten layers: the launch that covers eight of them is what is new there")
     w = small("layers", n_layers=n_layers, physical_layers=phys, ctx=16 * 700, topk_pages=40, capacity=46, steps=7,
               policy=policy, batch=3, n_kv_heads=2, n_q_heads=8, index_centroids=centroids)
     a = R.Rig(w, micro_batches=mb)
@@ -658,6 +662,9 @@ def test_layers_in_flight_equal_layers_one_by_one(n_layers, phys, centroids, mb,
             lses.append(a.n_lse.copy())
             last = (a.n_sel_pages.copy(), a.n_sel_slots.copy(), a.n_hit_mask.copy(), a.n_evicted.copy())
         out_l.fill_(float("nan"))
+        if mb == -1:                                     # (passes, scoring workgroups, splits, groups) of the launches of several layers
+            b.kvd.set_step_shape(*[(0, 0, 0, 0), (1, 7, 1, 2), (2, 30, 2, 3)][t % 3], multi_layer=True)
+            b.kvd.set_step_shape(*[(0, 0, 0, 0), (2, 9, 0, 4)][t % 2])
         if t % 2 == 0:
             b.kvd.step_layers(0, L, t, q.contiguous(), out_l, lse_l)
         else:                                            # a range that starts on another layer, then the rest
@@ -1078,6 +1085,58 @@ def test_calibration_picks_a_form_and_leaves_the_cache_consistent():
     rig.kvd.set_profiling(0)
     with pytest.raises(K.KvdError):
         rig.kvd.set_step_form(99)
+    rig.close()
+
+
+@pytest.mark.parametrize("cfg", [2, 5])
+def test_one_launch_step_in_every_launch_shape_and_after_its_calibration(cfg):
+    """The launch shape of the one-launch step (passes per scoring chunk, scoring workgroups,
+    attention splits) decides only how the units' stages overlap: results must match the oracle
+    in every shape, and the calibration must leave the cache where one step of its query takes it."""
+    w = SCALED[cfg].replace(steps=4)
+    rig = R.Rig(w, micro_batches=-1)
+    assert rig.kvd.step_form() == -1
+    units = all_units(rig, layers=[0])
+    cus = torch.cuda.get_device_properties(0).multi_processor_count
+    p0, n0, s0, g0 = rig.kvd.step_shape()
+    assert 1 <= p0 <= 8 and 1 <= n0 <= cus and s0 >= 1 and g0 == 1
+    qs = [q[0] for q in W.query_stream(w, rig.q0, 20, R.DEV)]
+    rep = R.StepReport()
+    t = 0
+    shapes = [(1, 1, 1, 1), (3, 5, s0, 2), (2, cus, 2 * s0, 1), (8, 40, max(1, s0 // 2), 4), (1, 3, 0, 3), (0, 0, 0, 8), (0, 0, 0, 0)]
+    for shape in shapes:
+        rig.kvd.set_step_shape(*shape)
+        got = rig.kvd.step_shape()
+        assert (shape[0] == 0 or got[0] == shape[0]) and (shape[2] == 0 or got[2] == shape[2])
+        assert shape[1] == 0 or 1 <= got[1] <= shape[1]               # (scoring workgroups are capped at the number of chunks)
+        assert shape[3] == 0 or 1 <= got[3] <= min(shape[3], w.units)  # (no empty group)
+        for _ in range(2):
+            rig.step(0, t, qs[t])
+            for ou in units:
+                R.compare_unit(rig, ou, t, qs[t], rep)
+            t += 1
+    assert rig.kvd.step_shape() == (p0, n0, s0, g0)
+    for bad in [(9, 0, 0, 0), (0, cus + 1, 0, 0), (0, 0, 2 * s0 + 1, 0), (-1, 0, 0, 0), (0, 0, 0, 9)]:
+        with pytest.raises(K.KvdError) as e:
+            rig.kvd.set_step_shape(*bad)
+        assert e.value.status == K.ERR_SHAPE
+    # calibration: one real step of the query, then all-hit replays in a grid of shapes
+    chosen, us, us_rule = rig.kvd.calibrate_step_shape(0, t, qs[t], rig.out, launches_per_shape=4)
+    assert rig.kvd.step_shape() == chosen and 0 < us <= us_rule * 1.000001
+    for ou in units:                                                  # the oracle takes that step once
+        ou.step(t, qs[t])
+    R.check_directory(rig, 0, units)
+    t += 1
+    for _ in range(2):
+        rig.step(0, t, qs[t])
+        for ou in units:
+            R.compare_unit(rig, ou, t, qs[t], rep)
+        t += 1
+    print(f"cfg{cfg}-scaled: rule {(p0, n0, s0)} {us_rule:.1f} us, chosen {chosen} {us:.1f} us")
+    rig.kvd.set_step_form(1)
+    with pytest.raises(K.KvdError) as e:                              # nothing to shape in a chain of kernels
+        rig.kvd.calibrate_step_shape(0, t, qs[t], rig.out)
+    assert e.value.status == K.ERR_STATE
     rig.close()
 
 
