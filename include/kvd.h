@@ -216,6 +216,36 @@ int kvd_cache_resolve(kvd_ctx* ctx, int32_t layer, int32_t step, const int32_t* 
 int kvd_sparse_decode_attn(kvd_ctx* ctx, int32_t layer, const void* q, const int32_t* sel_pages,
                            const int32_t* sel_slots, float* out, float* lse, void* stream);
 
+/* Stage 3 for callers that cannot allocate device memory: code under HIP graph capture, tight serving
+ * loops, harnesses that forbid hipMalloc.  The same attention as kvd_sparse_decode_attn, without a
+ * context: the call takes everything it needs as arguments and neither it nor anything it calls
+ * allocates or frees (no hipMalloc, hipFree or allocating library routine).  Its split partials and
+ * arrival tickets live in one 8 MiB array of device memory that is part of the library's code object:
+ * every GPU the library runs on holds its own copy from the moment the library is loaded there until
+ * the process ends.
+ *   q          dev [B][Hq][D] kv_dtype, 16-byte aligned (D = 128)
+ *   slot_pool  dev [B][Hkv][Cmax] slots of 2*P*D*2 bytes, 16-byte aligned: one layer of a pool in the
+ *              library's slot order, i.e. as kvd_cache_resolve / kvd_step of a context of the same
+ *              P and Cmax filled it (layer l of that pool starts l*B*Hkv*Cmax slots in)
+ *   sel_pages, sel_slots  dev [B][Hkv][k] int32, as stages 1 and 2 write them (-1 = padding)
+ *   seq_len    dev [B] int32 valid tokens per sequence
+ *   out        dev [B][Hq][D] fp32;  lse  dev [B][Hq] fp32 or NULL
+ *   softmax_scale  0 means 1/sqrt(D);  attn_splits  split-K factor, 0 = chosen as kvd_create does.
+ * Limits: those of kvd_config (G <= 8, P <= 256, k <= 2048, B*Hkv <= 65535), and
+ * B*Hkv*(4 + splits*G*520) bytes (each part rounded up to 256) must fit the 8 MiB array:
+ * KVD_ERR_CAPACITY otherwise, nothing is enqueued then.  KVD_ERR_ARG / KVD_ERR_SHAPE / KVD_ERR_DTYPE
+ * as kvd_create and kvd_sparse_decode_attn; KVD_ERR_HIP if the array's address cannot be obtained
+ * or a launch fails.  The first call on a GPU looks up that GPU's copy of the array
+ * (hipGetSymbolAddress) and must therefore come before any graph capture.  Enqueued on `stream`
+ * (a fill kernel that zeroes the tickets, then the attention kernel).  Every call on one GPU uses
+ * that GPU's one array: calls that overlap in time on one GPU (different streams, or graphs
+ * replayed concurrently) race and give wrong results; calls on one stream, one after another, are safe. */
+int kvd_sparse_decode_attn_noalloc(const void* q, const void* slot_pool, const int32_t* sel_pages,
+                                   const int32_t* sel_slots, const int32_t* seq_len, float* out, float* lse,
+                                   int32_t batch, int32_t n_q_heads, int32_t n_kv_heads, int32_t page_size,
+                                   int32_t topk_pages, int32_t capacity_max, int32_t kv_dtype, float softmax_scale,
+                                   int32_t attn_splits, void* stream);
+
 /* ---- hierarchical index ------------------------------------------------------------------------ */
 
 /* Buffers of the hierarchical index (index_centroids = Nc > 0), all device memory owned by the caller:

@@ -8,10 +8,20 @@
 //    contiguous and lands directly in MFMA operand registers: S^T = K Q^T with 16x16x32 MFMAs,
 //    O^T += V^T P^T with 16x16x16 MFMAs whose B operand is the softmaxed C tile of the first.
 //  * attend_valu_kernel — any page size, natural [token][dim] slots, fp32 VALU arithmetic.
+#include <math.h>
+
+#include <mutex>
+
 #include "kvd_attn_body.h"
 #include "kvd_device.h"
 #include "kvd_internal.h"
 #include "kvd_tile_layout.h"
+
+// Scratch of kvd_sparse_decode_attn_noalloc: the arrival tickets of the units, then the split
+// partials (max and sum per query head, then the accumulators).  Every GPU the library runs on
+// holds its own copy of this array from the moment the code is loaded until the process ends.
+constexpr size_t kNoAllocScratchBytes = (size_t)8 << 20;
+static __device__ __align__(256) unsigned char scratch[kNoAllocScratchBytes];
 
 namespace kvd {
 
@@ -230,4 +240,133 @@ hipError_t kvd_launch_attend(kvd_ctx* c, int layer, const void* q, const int32_t
                           : dispatch_group<false>(c->G, c->tiled != 0, a, grid, s, between);
   if (!ok) return hipErrorInvalidValue;
   return hipGetLastError();
+}
+
+
+// ---------------------------------------------------------------------------------------------
+// The attention stage for callers that cannot allocate
+// ---------------------------------------------------------------------------------------------
+namespace {
+
+constexpr int kMaxDevices = 64;
+std::mutex g_noalloc_mutex;
+void* g_scratch_ptr[kMaxDevices];   // device address of `scratch` on each GPU (the array's name is only a host-side handle)
+int g_scratch_cus[kMaxDevices];
+
+// Device address of this GPU's copy of `scratch` and its number of compute units, looked up once
+// per device with that device current.
+hipError_t noalloc_device_state(void** ptr, int* cus) {
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+  std::lock_guard<std::mutex> lock(g_noalloc_mutex);
+  if (g_scratch_ptr[dev] == nullptr) {
+    void* p = nullptr;
+    e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (e != hipSuccess) return e;
+    if (p == nullptr) return hipErrorInvalidSymbol;
+    int n = 0;
+    e = hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev);
+    if (e != hipSuccess) return e;
+    g_scratch_cus[dev] = n > 0 ? n : 256;
+    g_scratch_ptr[dev] = p;
+  }
+  *ptr = g_scratch_ptr[dev];
+  *cus = g_scratch_cus[dev];
+  return hipSuccess;
+}
+
+size_t round256(size_t n) { return (n + 255) & ~(size_t)255; }
+
+}  // namespace
+
+extern "C" int kvd_sparse_decode_attn_noalloc(const void* q, const void* slot_pool, const int32_t* sel_pages,
+                                              const int32_t* sel_slots, const int32_t* seq_len, float* out, float* lse,
+                                              int32_t batch, int32_t n_q_heads, int32_t n_kv_heads, int32_t page_size,
+                                              int32_t topk_pages, int32_t capacity_max, int32_t kv_dtype,
+                                              float softmax_scale, int32_t attn_splits, void* stream) {
+  using namespace kvd;
+  if (!q || !slot_pool || !sel_pages || !sel_slots || !seq_len || !out) return KVD_ERR_ARG;
+  if ((reinterpret_cast<uintptr_t>(q) & 15u) || (reinterpret_cast<uintptr_t>(slot_pool) & 15u)) return KVD_ERR_ARG;
+  if (kv_dtype != KVD_F16 && kv_dtype != KVD_BF16) return KVD_ERR_DTYPE;
+  if (batch < 1 || n_q_heads < 1 || n_kv_heads < 1 || n_q_heads % n_kv_heads != 0) return KVD_ERR_SHAPE;
+  const int G = n_q_heads / n_kv_heads;
+  if (G > KVD_MAX_GROUP) return KVD_ERR_SHAPE;
+  if (page_size < 1 || page_size > KVD_MAX_PAGE) return KVD_ERR_SHAPE;
+  if (topk_pages < 1 || topk_pages > KVD_MAX_TOPK) return KVD_ERR_SHAPE;
+  if (capacity_max < 1 || capacity_max > KVD_MAX_CAPACITY) return KVD_ERR_SHAPE;
+  if ((long long)batch * n_kv_heads > 65535) return KVD_ERR_SHAPE;
+  if (attn_splits < 0 || attn_splits > KVD_MAX_SPLITS) return KVD_ERR_SHAPE;
+  if (!(softmax_scale >= 0.f) || isinf(softmax_scale)) return KVD_ERR_ARG;
+  void* base = nullptr;
+  int cus = 0;
+  // (the number of compute units is only needed to choose the splits: sizes that cannot fit
+  // whatever the device are refused before any device is touched)
+  if (attn_splits == 0 && noalloc_device_state(&base, &cus) != hipSuccess) {
+    (void)hipGetLastError();
+    return KVD_ERR_HIP;
+  }
+  const int U = batch * n_kv_heads;
+  const bool tiled = page_size % 16 == 0;
+  // split-K factor: the rule of kvd_create
+  int S = attn_splits;
+  if (S == 0) {
+    const int tiles = topk_pages * ((page_size + 15) / 16);
+    if (tiled) {
+      S = (cus + U / 2) / U;
+      if (S > tiles / 16) S = tiles / 16;
+    } else {
+      S = (512 + U / 2) / U;
+      if (S > (tiles + 7) / 8) S = (tiles + 7) / 8;
+    }
+    if (S > KVD_MAX_SPLITS) S = KVD_MAX_SPLITS;
+    if (S < 1) S = 1;
+  }
+  if (S > topk_pages) S = topk_pages;
+  // the scratch array, cut into tickets [U], (max, sum) [U][S][G][2] and accumulators [U][S][G][D]
+  const size_t rows = (size_t)U * S * G;
+  const size_t off_ml = round256((size_t)U * sizeof(int32_t));
+  const size_t off_acc = off_ml + round256(rows * 2 * sizeof(float));
+  const size_t need = off_acc + rows * kHeadDim * sizeof(float);
+  if (need > kNoAllocScratchBytes) return KVD_ERR_CAPACITY;
+  if (base == nullptr && noalloc_device_state(&base, &cus) != hipSuccess) {
+    (void)hipGetLastError();
+    return KVD_ERR_HIP;
+  }
+  unsigned char* sp = static_cast<unsigned char*>(base);
+  hipStream_t s = static_cast<hipStream_t>(stream);
+
+  AttnArgs a;
+  a.u0 = 0;
+  a.q = reinterpret_cast<const uint16_t*>(q);
+  a.pool = static_cast<const char*>(slot_pool);
+  a.sel_pages = sel_pages;
+  a.sel_slots = sel_slots;
+  a.sel_entry = nullptr;
+  a.error = nullptr;
+  a.wait_limit = 0;
+  a.seq_len = seq_len;
+  a.ticket = reinterpret_cast<int32_t*>(sp);
+  a.part_ml = reinterpret_cast<float*>(sp + off_ml);
+  a.part_acc = reinterpret_cast<float*>(sp + off_acc);
+  a.out = out;
+  a.lse = lse;
+  a.k = topk_pages; a.P = page_size; a.Cmax = capacity_max; a.Hq = n_q_heads; a.Hkv = n_kv_heads; a.G = G; a.S = S;
+  a.per_split = (topk_pages + S - 1) / S;
+  a.fuse_merge = 1;
+  a.page_bytes = (unsigned)((size_t)2 * page_size * kHeadDim * 2);
+  a.scale_log2 = (softmax_scale > 0.f ? softmax_scale : 1.0f / sqrtf((float)kHeadDim)) * kLog2e;
+  // the tickets must start at zero whatever an earlier call left there (a fill kernel, so that
+  // the call can be captured into a HIP graph)
+  if (S > 1 && kvd_launch_fill_i32(a.ticket, 0, (size_t)U, s) != hipSuccess) {
+    (void)hipGetLastError();
+    return KVD_ERR_HIP;
+  }
+  const dim3 grid(S, U);
+  const bool ok = kv_dtype == KVD_BF16 ? dispatch_group<true>(G, tiled, a, grid, s, nullptr)
+                                       : dispatch_group<false>(G, tiled, a, grid, s, nullptr);
+  if (!ok) return KVD_ERR_SHAPE;
+  if (hipGetLastError() != hipSuccess) return KVD_ERR_HIP;
+  return KVD_OK;
 }

@@ -68,7 +68,7 @@ EXPORTS = [
     "kvd_tier_open", "kvd_tier_close", "kvd_tier_last_errno", "kvd_tier_set_layout", "kvd_tier_write_layer",
     "kvd_tier_patch_page", "kvd_tier_fetch", "kvd_tier_trace", "kvd_tier_pooled", "kvd_tier_drop_pool", "kvd_tier_get_stats",
     "kvd_tier_reset_stats", "kvd_tier_sequential_read_gbps", "kvd_layout_from_clusters", "kvd_bind_tier",
-    "kvd_step_tiered", "kvd_step_layers",
+    "kvd_step_tiered", "kvd_step_layers", "kvd_sparse_decode_attn_noalloc",
     "kvd_set_step_shape", "kvd_get_step_shape", "kvd_calibrate_step_shape",
 ]
 
@@ -136,6 +136,7 @@ def load() -> C.CDLL:
         "kvd_set_step_shape": [vp, i32, i32, i32, i32, i32],
         "kvd_get_step_shape": [vp, i32, i32p],
         "kvd_calibrate_step_shape": [vp, i32, i32, i32, vp, vp, vp, i32, i32p, f32p, f32p],
+        "kvd_sparse_decode_attn_noalloc": [vp, vp, vp, vp, vp, vp, vp, i32, i32, i32, i32, i32, i32, i32, C.c_float, i32, vp],
     }
     for name, args in protos.items():
         fn = getattr(lib, name)
@@ -167,6 +168,20 @@ def _stream_handle(stream: Optional[torch.cuda.Stream]) -> Optional[int]:
     if stream is None:
         stream = torch.cuda.current_stream()
     return stream.cuda_stream or None
+
+
+def sparse_decode_attn_noalloc(q, slot_pool, sel_pages, sel_slots, seq_len, out, lse=None, *, batch, n_q_heads,
+                               n_kv_heads, page_size, topk_pages, capacity_max, kv_dtype, softmax_scale=0.0,
+                               attn_splits=0, stream=None):
+    """kvd_sparse_decode_attn_noalloc: the attention stage without a context and without any allocation."""
+    lib = load()
+    dt = {torch.float16: KVD_F16, torch.bfloat16: KVD_BF16}.get(kv_dtype, kv_dtype)
+    st = lib.kvd_sparse_decode_attn_noalloc(q.data_ptr(), slot_pool.data_ptr(), sel_pages.data_ptr(), sel_slots.data_ptr(),
+                                            seq_len.data_ptr(), out.data_ptr(), _ptr(lse), batch, n_q_heads, n_kv_heads,
+                                            page_size, topk_pages, capacity_max, dt, softmax_scale, attn_splits,
+                                            _stream_handle(stream))
+    if st != OK:
+        raise KvdError(st, "kvd_sparse_decode_attn_noalloc")
 
 
 class Kvd:

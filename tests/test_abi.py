@@ -96,3 +96,29 @@ def test_create_rejects_small_per_unit_capacity_and_null():
     cfg.capacity = C.cast(caps_big, C.POINTER(C.c_int32))
     assert lib.kvd_create(C.byref(cfg), C.byref(ctx)) == kvd.ERR_SHAPE
 
+
+def test_noalloc_attention_rejects_bad_arguments_without_a_device():
+    """kvd_sparse_decode_attn_noalloc checks pointers and sizes, and refuses what cannot fit its
+    fixed scratch array, before it touches any device."""
+    lib = kvd.load()
+    fn = lib.kvd_sparse_decode_attn_noalloc
+    p = 4096                                                       # any non-null, 16-byte aligned address: never dereferenced here
+    ok = dict(batch=1, hq=8, hkv=2, page=16, k=4, cmax=8, dt=kvd.KVD_BF16, scale=0.0, splits=2)
+
+    def call(q=p, pool=p, sel=p, slots=p, seq=p, out=p, **kw):
+        a = dict(ok, **kw)
+        return fn(q, pool, sel, slots, seq, out, None, a["batch"], a["hq"], a["hkv"], a["page"], a["k"], a["cmax"], a["dt"],
+                  a["scale"], a["splits"], None)
+
+    assert call(q=None) == kvd.ERR_ARG and call(out=None) == kvd.ERR_ARG and call(seq=None) == kvd.ERR_ARG
+    assert call(q=p + 8) == kvd.ERR_ARG                            # misaligned
+    assert call(dt=9) == kvd.ERR_DTYPE
+    assert call(hq=18) == kvd.ERR_SHAPE                            # G = 9
+    assert call(hq=7) == kvd.ERR_SHAPE
+    assert call(page=0) == kvd.ERR_SHAPE and call(page=257) == kvd.ERR_SHAPE
+    assert call(k=0) == kvd.ERR_SHAPE and call(k=4096) == kvd.ERR_SHAPE
+    assert call(cmax=0) == kvd.ERR_SHAPE
+    assert call(splits=65) == kvd.ERR_SHAPE and call(splits=-1) == kvd.ERR_SHAPE
+    assert call(scale=float("nan")) == kvd.ERR_ARG
+    # 8192 units x 64 splits x 8 heads of split partials: 2 GiB, far beyond the 8 MiB array
+    assert call(batch=8192, hq=8, hkv=1, k=2048, splits=64) == kvd.ERR_CAPACITY
