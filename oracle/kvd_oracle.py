@@ -357,14 +357,39 @@ class LruWindow:
 class LookaheadWindow(LruWindow):
     """The window with lookahead eviction (Cache Management, "Sliding Window w/
     Lookahead Eviction": at each step the entries with the lowest current-step
-    scores are discarded, as they are least likely to be reused).  Stamps are
-    still kept (step of last selection) but play no part in the choice.
+    scores are discarded, as they are least likely to be reused).
+
+    pool: the look-ahead candidate pool M of the evaluation ("Generality of
+    Eviction Policy": M = 2560 entries for a budget of K = 2048), in pages; 0 =
+    every scored page.  The figure the policy is motivated by counts how many of a
+    step's Top-M entries are in the next step's Top-K and finds that the count
+    saturates as M grows: beyond rank M the current scores say nothing more about
+    reuse.  Read here as: the M best-scoring pages of the step (score descending,
+    ties to the lower page) are the candidates for reuse and leave last, lowest
+    score first; resident pages outside that pool leave before any of them, least
+    recently selected first (smallest (stamp, page)), the order that remains when
+    the score carries no information.  pool >= number of scored pages is the
+    policy without a pool; a pool that is exactly the selection is LRU.
     """
+
+    def __init__(self, capacity, pool=0):
+        super().__init__(capacity)
+        self.pool = int(pool)
+
+    def pool_pages(self, scores):
+        """The pages of the look-ahead pool for this step's scores, or None when the
+        pool covers every scored page."""
+        n = len(scores)
+        if self.pool <= 0 or self.pool >= n:
+            return None
+        order = sorted(range(n), key=lambda p: (-float(scores[p]), p))
+        return set(order[: self.pool])
 
     def resolve(self, sel, step, scores=None, forced_evicted=None):
         """As LruWindow.resolve, but the victim is the resident page, not selected
-        in this step, with the lowest scores[page]; equal scores: the higher page
-        index leaves first.
+        in this step, that comes first in this order: pages outside the look-ahead
+        pool by (stamp, page) ascending; then pool pages by the lowest
+        scores[page], equal scores: the higher page index first.
 
         scores         [NPvalid] fp64 page scores of this step.
         forced_evicted if given, exactly these pages leave instead of the oracle's
@@ -394,12 +419,20 @@ class LookaheadWindow(LruWindow):
             for p in misses:
                 self.stamp[p] = int(step)
             return hits, misses, evicted
+        pool = self.pool_pages(scores)
         for p in misses:
             if len(self.stamp) >= self.capacity:
-                cands = [(float(scores[r]), -r) for r in self.stamp if r not in selset]
-                _, neg = min(cands)
-                del self.stamp[-neg]
-                evicted.append(-neg)
+                cands = []
+                for r, st in self.stamp.items():
+                    if r in selset:
+                        continue
+                    if pool is not None and r not in pool:
+                        cands.append((0, float(st), r, r))
+                    else:
+                        cands.append((1, float(scores[r]), -r, r))
+                victim = min(cands)[3]
+                del self.stamp[victim]
+                evicted.append(victim)
             self.stamp[p] = int(step)
         return hits, misses, sorted(evicted)
 

@@ -321,6 +321,46 @@ def test_lookahead_golden_trace():
         assert win.resident() == _ints(resident), step
 
 
+def test_lookahead_pool_golden_traces():
+    wins = {}
+    for name, cap, pool, step, scores, sel, pool_pages, hits, misses, evicted, resident in H.read_golden("la_pool_trace_6pages.txt"):
+        win = wins.setdefault(name, orc.LookaheadWindow(int(cap), pool=int(pool)))
+        sc = np.array([float(x) for x in scores.split()])
+        assert orc.select_pages(sc, 2).tolist() == _ints(sel), (name, step)
+        assert sorted(win.pool_pages(sc)) == _ints(pool_pages), (name, step)
+        h, m, e = win.resolve(_ints(sel), int(step), scores=sc)
+        assert (h, m, e) == (_ints(hits), _ints(misses), _ints(evicted)), (name, step)
+        assert win.resident() == _ints(resident), (name, step)
+
+
+def test_lookahead_pool_reduces_to_the_policy_without_a_pool_and_to_lru():
+    """A pool that covers every scored page is the policy without a pool; a pool that is exactly the
+    selection (M = k, no forced pages) leaves only recency to order the victims: LRU.  In between,
+    the victims are the batch formulation: unselected residents outside the pool by (stamp, page),
+    then those inside by (score, -page)."""
+    n_pages, k, cap = 60, 7, 19
+    for pool in (n_pages, n_pages + 5, 0, k, 12, 30):
+        win, plain, lru = orc.LookaheadWindow(cap, pool=pool), orc.LookaheadWindow(cap), orc.LruWindow(cap)
+        for t in range(70):
+            scores = np.round(RNG.normal(size=n_pages), 1) + 0.3 * np.exp(-0.1 * np.abs(np.arange(n_pages) - (3 * t) % n_pages))
+            sel = orc.select_pages(scores, k).tolist()
+            before = dict(win.stamp)
+            got = win.resolve(sel, t, scores=scores)
+            if pool == 0 or pool >= n_pages:
+                assert got == plain.resolve(sel, t, scores=scores) and win.stamp == plain.stamp
+            elif pool == k:
+                assert got == lru.resolve(sel, t) and win.stamp == lru.stamp
+            else:
+                inside = set(np.lexsort((np.arange(n_pages), -scores))[:pool].tolist())
+                assert inside == win.pool_pages(scores)
+                cands = [p for p in before if p not in set(sel)]
+                order = sorted((p for p in cands if p not in inside), key=lambda p: (before[p], p)) + \
+                        sorted((p for p in cands if p in inside), key=lambda p: (scores[p], -p))
+                need = max(0, len(before) + len(got[1]) - cap)
+                assert got[2] == sorted(order[:need])
+                assert len(win.stamp) <= cap and not (set(got[2]) & set(sel))
+
+
 def test_lookahead_with_recency_scores_is_lru():
     """If the score of a resident page is the step at which it was last selected (plus a
     page-increasing sliver that orders equal stamps as LRU does), "lowest score first" is
