@@ -63,7 +63,8 @@ CSRC = os.path.join(ROOT, "paper_2605_18071_amd", "csrc")
 def describe(w) -> str:
     return (f"{w.name}: L={w.n_layers} B={w.batch} ctx={w.ctx} page={w.page} heads={w.n_q_heads}q/{w.n_kv_heads}kv "
             f"D={w.head_dim} {w.dtype} k={w.topk_pages} pages ({w.topk_pages * w.page} tokens) "
-            f"{'flat index' if w.index_centroids == 0 else str(w.index_centroids) + ' centroids'} cache={w.capacity} pages/unit ({100.0 * w.capacity / w.n_pages:.0f}%, {w.policy}) {w.importance} importance, rho={w.rho}")
+            f"{'flat index' if w.index_centroids == 0 else str(w.index_centroids) + ' centroids'} cache={w.capacity} pages/unit ({100.0 * w.capacity / w.n_pages:.0f}%, {w.policy}{' pool ' + str(w.lookahead_pool) if w.lookahead_pool else ''}) "
+            f"{w.importance} importance, rho={w.rho}")
 
 
 def kernel_source_hash() -> str:
@@ -216,7 +217,7 @@ class Bench:
         self.ctx = K.Kvd(n_layers=L, batch=B, n_q_heads=w.n_q_heads, n_kv_heads=Hkv, page_size=P, max_pages=NP, topk_pages=k,
                          capacity_max=w.capacity, kv_dtype=w.torch_dtype, sink_pages=w.sink_pages, recent_pages=w.recent_pages,
                          physical_layers=1, micro_batches=args.micro_batches, policy=w.policy,
-                         index_centroids=w.index_centroids)
+                         index_centroids=w.index_centroids, lookahead_pool=w.lookahead_pool)
         self.ctx.bind_summaries(self.summ)
         self.ctx.bind_host_store(self.store)
         self.ctx.bind_slot_pool(self.pool)
@@ -556,6 +557,8 @@ def main() -> int:
     ap.add_argument("--config", type=int, default=3)
     ap.add_argument("--micro-batches", type=int, default=0, help="kvd_config.micro_batches (0 = library chooses, 1 = chain of kernels, -1 = one launch)")
     ap.add_argument("--policy", choices=["lru", "lookahead"], default="lru", help="cache replacement policy")
+    ap.add_argument("--lookahead-pool", type=float, default=0.0, metavar="X",
+                    help="with --policy lookahead: look-ahead candidate pool of X times the per-step budget k (0 = every page)")
     ap.add_argument("--centroids", type=int, default=0,
                     help="hierarchical index with this many centroids per unit (0 = flat page index)")
     ap.add_argument("--index-iterations", type=int, default=4, help="k-means rounds of the hierarchical index build")
@@ -621,7 +624,8 @@ def main() -> int:
         w = w.replace(n_layers=1, physical_layers=1)
     if args.window > 0:
         w = w.replace(capacity=max(w.topk_pages, int(round(args.window * w.topk_pages))))
-    w = w.replace(policy=args.policy, index_centroids=args.centroids, index_iterations=args.index_iterations)
+    w = w.replace(policy=args.policy, index_centroids=args.centroids, index_iterations=args.index_iterations,
+                  lookahead_pool=int(round(args.lookahead_pool * w.topk_pages)))
     plain = not args.tier
     rot_layers = args.rot_layers if (plain and not args.no_profile_pass) else 1
 

@@ -110,6 +110,13 @@ typedef struct {
                               kvd_step runs in any of its forms.  Under KVD_EVICT_LOOKAHEAD the score
                               of a resident page is the score of its cluster (a page of no cluster leaves
                               first; pages of one cluster: the higher page first). */
+  int32_t lookahead_pool;  /* M, the look-ahead candidate pool of KVD_EVICT_LOOKAHEAD (Experiment, "Generality of
+                              Eviction Policy": M = 2560 entries for a budget of 2048), in pages; 0 = every scored
+                              page.  The M best-scoring pages of a step (score descending, ties to the lower page)
+                              are the candidates for reuse: resident pages outside them leave first, least
+                              recently selected first (smallest (stamp, page)); pool pages only after those,
+                              lowest score first.  M >= the valid pages of a sequence is the policy without a
+                              pool; M == topk_pages (without sink / recent pages) is LRU. */
 } kvd_config;
 
 typedef struct {

@@ -9,7 +9,7 @@
 
 #include "kvd_internal.h"
 
-#define KVD_ABI_VERSION 1
+#define KVD_ABI_VERSION 2
 
 #define HIP_TRY(ctx, expr)                  \
   do {                                      \
@@ -53,6 +53,7 @@ static int validate_config(const kvd_config* c) {
   if (c->attn_splits < 0 || c->attn_splits > KVD_MAX_SPLITS) return KVD_ERR_SHAPE;
   if (c->index_centroids < 0 || c->index_centroids > KVD_MAX_CENTROIDS || c->index_centroids > c->max_pages) return KVD_ERR_SHAPE;
   if (c->index_centroids > 0 && c->max_pages > KVD_FAST_MAX_PAGES) return KVD_ERR_SHAPE;
+  if (c->lookahead_pool < 0) return KVD_ERR_SHAPE;
   if (!(c->softmax_scale >= 0.f) || isinf(c->softmax_scale)) return KVD_ERR_ARG;
   if ((long long)c->sink_pages + c->recent_pages > c->topk_pages) return KVD_ERR_CAPACITY;
   if (c->topk_pages > c->capacity_max) return KVD_ERR_CAPACITY;

@@ -30,7 +30,9 @@ struct ResolveArgs {
   unsigned long long* stats; // hits, misses, evictions
   const float* scores;       // [U][score_stride] scores of this step (lookahead eviction only)
   const int32_t* page_cluster;  // [U][NP] or null: a page's score is its cluster's (hierarchical index)
+  const int32_t* seq_len;    // [B]
   int NP, Cmax, k, step, u0, lookahead, score_stride;
+  int la_pool, P, Hkv;       // look-ahead pool in pages (0 = every scored page); page size and KV heads, for the valid pages of a unit
 };
 
 // One block per unit.
@@ -99,17 +101,47 @@ __global__ __launch_bounds__(kResolveThreads) void resolve_kernel(ResolveArgs a)
   const int e = (R + m - C) > 0 ? (R + m - C) : 0;
 
   // 2. victims
+  auto page_score = [&](int p) -> float {             // this step's score of a page: its own, or its cluster's
+    int at = p;
+    if (a.page_cluster != nullptr) at = a.page_cluster[(size_t)u * a.NP + p];
+    return at < 0 ? -INFINITY : a.scores[(size_t)u * a.score_stride + at];
+  };
+  auto ascending = [](float sc) -> u32 {
+    const u32 x = as_u32(sc + 0.0f);
+    return (x & 0x80000000u) ? ~x : (x | 0x80000000u);
+  };
+  // A finite look-ahead pool: the key of the pool's last member in selection order (score
+  // descending, ties to the lower page) over the unit's valid pages.
+  bool pooled = false;
+  u64 pool_thr = ~0ull;
+  if (a.lookahead && a.la_pool > 0 && e > 0) {
+    int n_valid = (a.seq_len[u / a.Hkv] + a.P - 1) / a.P;
+    n_valid = n_valid < a.NP ? n_valid : a.NP;
+    if (a.la_pool < n_valid) {
+      pooled = true;
+      auto fn = [&](int p, u64& kk) -> bool {
+        kk = ((u64)(~ascending(page_score(p))) << 32) | (u32)p;
+        return true;
+      };
+      pool_thr = block_kth_smallest<NT>(fn, n_valid, a.la_pool, sm, radix_hist);
+      __syncthreads();
+    }
+  }
   auto victim_key = [&](int s, u64& key) -> bool {
     const int p = spage[s];
     if (p < 0 || ((hit_bitmap[s >> 5] >> (s & 31)) & 1u)) return false;
     if (a.lookahead) {
-      // ascending in (score, -page): the lowest score leaves first, among equals the higher page
-      int at = p;
-      if (a.page_cluster != nullptr) at = a.page_cluster[(size_t)u * a.NP + p];
-      const float sc = at < 0 ? -INFINITY : a.scores[(size_t)u * a.score_stride + at];
-      const u32 x = as_u32(sc + 0.0f);
-      const u32 asc = (x & 0x80000000u) ? ~x : (x | 0x80000000u);
-      key = ((u64)asc << 32) | (u32)(~(u32)p);
+      // ascending in (score, -page): the lowest score leaves first, among equals the higher page;
+      // with a pool, the pages outside it before all of those, by (stamp, page)
+      const float sc = page_score(p);
+      const u32 asc = ascending(sc);
+      if (!pooled) {
+        key = ((u64)asc << 32) | (u32)(~(u32)p);
+      } else if ((((u64)(~asc) << 32) | (u32)p) <= pool_thr) {
+        key = (1ull << 63) | ((u64)asc << 24) | (u64)((~(u32)p) & 0xffffffu);
+      } else {
+        key = ((u64)((u32)sstamp[s] ^ 0x80000000u) << 24) | (u64)((u32)p & 0xffffffu);
+      }
     } else {
       key = ((u64)((u32)sstamp[s] ^ 0x80000000u) << 32) | (u32)p;
     }
@@ -406,6 +438,8 @@ hipError_t kvd_launch_resolve(kvd_ctx* c, int layer, int step, const int32_t* se
   a.stats = c->d_stats;
   a.NP = c->NP; a.Cmax = c->Cmax; a.k = c->k; a.step = step; a.u0 = u0;
   a.lookahead = c->cfg.policy == KVD_EVICT_LOOKAHEAD ? 1 : 0;
+  a.la_pool = c->cfg.lookahead_pool; a.P = c->P; a.Hkv = c->Hkv;
+  a.seq_len = c->d_seq_len;
   a.scores = c->last_scores;
   a.page_cluster = c->Nc > 0 ? c->d_page_cluster + lu * c->NP : nullptr;
   a.score_stride = c->Nc > 0 ? c->Nc : c->NP;

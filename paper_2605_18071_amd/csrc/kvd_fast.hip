@@ -58,6 +58,7 @@ kvd::FastArgs kvd_fast_args(kvd_ctx* c, int layer, int step, bool do_gather, con
   a.do_gather = (do_gather && a.store && a.pool) ? 1 : 0;
   a.tiled = c->tiled;
   a.lookahead = c->cfg.policy == KVD_EVICT_LOOKAHEAD ? 1 : 0;
+  a.la_pool = c->cfg.lookahead_pool;
   a.page_cluster = c->Nc > 0 ? c->d_page_cluster + lu * c->NP : nullptr;
   a.score_stride = c->Nc > 0 ? c->Nc : c->NP;
   a.page_bytes = (unsigned)c->page_bytes;

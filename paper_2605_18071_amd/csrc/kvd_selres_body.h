@@ -42,6 +42,8 @@ struct FastArgs {
   char* pool;                 // slot pool of the layer, [U][Cmax] slots
   int NP, P, k, Cmax, sink, recent, Hkv, step, u0, do_gather, tiled;
   int lookahead;              // victims by lowest current-step score (needs `scores`) instead of by age
+  int la_pool;                // look-ahead pool in pages (0 = every scored page): resident pages outside the step's la_pool
+                              // best-scoring pages leave first, least recently selected first
   const int32_t* page_cluster;  // [U][NP] or null: the victims' scores are those of the pages' clusters
   int score_stride;           // scores of unit u start at scores + u * score_stride (NP, or the number of centroids)
   unsigned page_bytes;
@@ -94,6 +96,10 @@ __device__ __forceinline__ u32 fast_descending_key(float s) {
   const u32 x = as_u32(s + 0.0f);                    // -0 -> +0 so that the two zeros tie
   const u32 asc = (x & 0x80000000u) ? ~x : (x | 0x80000000u);
   return ~asc;
+}
+// Key of the selection order (best page first); it also decides membership of the look-ahead pool.
+__device__ __forceinline__ u64 selection_order_key(float s, int page) {
+  return ((u64)fast_descending_key(s) << 32) | (u32)page;
 }
 
 // Exclusive prefix sum over the block with one barrier: the wave totals alternate between two
@@ -179,6 +185,15 @@ __device__ __forceinline__ u64 lookahead_victim_key(float s, int page) {
   return ((u64)asc << 32) | (u32)(~(u32)page);
 }
 
+// With a finite look-ahead pool the victim order is: pages outside the pool by (stamp, page), then
+// pool pages by (score, -page).  One 64-bit key carries both (pages are below 2^24): bit 63 = in
+// the pool, then the 32-bit stamp or score key, then the page or its complement.
+__device__ __forceinline__ u64 pooled_victim_key(bool in_pool, float s, int stamp, int page) {
+  if (!in_pool) return ((u64)((u32)stamp ^ 0x80000000u) << 24) | (u64)((u32)page & 0xffffffu);
+  const u32 x = as_u32(s + 0.0f);
+  const u32 asc = (x & 0x80000000u) ? ~x : (x | 0x80000000u);
+  return (1ull << 63) | ((u64)asc << 24) | (u64)((~(u32)page) & 0xffffffu);
+}
 __device__ __forceinline__ int victim_bucket(long long age, int page, int NP) {
   // one group of 32 buckets per age (step - stamp) below 64, split by page range; everything older
   // shares bucket 0; the newest class (age <= 1) shares bucket 2047
@@ -503,12 +518,41 @@ __device__ __forceinline__ bool select_resolve_body(const FastArgs& a, int u, Fa
     vinv = hi > lo ? 2047.0f / (hi - lo) : 0.f;
   }
   auto la_bucket = [&](float v) -> int { return (int)fminf(fmaxf((v - vmin) * vinv, 0.f), 2047.f); };
+  // A finite look-ahead pool: the key of the pool's last member in selection order (best page first)
+  // over the unit's valid pages; a resident page is in the pool iff its key is not beyond it.
+  bool pooled = false;
+  u64 pool_thr = ~0ull;
+  if (a.lookahead && a.la_pool > 0 && e > 0) {
+    int n_valid = (a.seq_len[b] + a.P - 1) / a.P;
+    n_valid = n_valid < a.NP ? n_valid : a.NP;
+    if (a.la_pool < n_valid) {
+      pooled = true;
+      auto fn = [&](int p, u64& kk) -> bool {
+        kk = selection_order_key(victim_score<HANDOFF>(a, u, p), p);
+        return true;
+      };
+      pool_thr = block_kth_smallest<NT>(fn, n_valid, a.la_pool, sm.generic, sm.a.sel.hist);
+      // (the histogram serves the victim choice next: it must start from zero again)
+      __syncthreads();
+      for (int i = tid; i < kRadixBins; i += NT) sm.a.sel.hist[i] = 0;
+      __syncthreads();
+    }
+  }
+  auto in_pool = [&](float v, int page) -> bool { return selection_order_key(v, page) <= pool_thr; };
+  auto la_key = [&](float v, int st, int page) -> u64 {
+    return pooled ? pooled_victim_key(in_pool(v, page), v, st, page) : lookahead_victim_key(v, page);
+  };
+  auto la_bkt = [&](float v, int st, int page) -> int {
+    if (!pooled) return la_bucket(v);
+    // the halves of the bucket range: outside the pool by age, inside by score
+    return in_pool(v, page) ? 1024 + (la_bucket(v) >> 1) : (victim_bucket((long long)a.step - (long long)st, page, a.NP) >> 1);
+  };
   auto vkey_of = [&](int j) -> u64 {
-    return a.lookahead ? lookahead_victim_key(vs[j], sp[j]) : ((u64)((u32)ss[j] ^ 0x80000000u) << 32) | (u32)sp[j];
+    return a.lookahead ? la_key(vs[j], ss[j], sp[j]) : ((u64)((u32)ss[j] ^ 0x80000000u) << 32) | (u32)sp[j];
   };
   auto vbkt_of = [&](int j) -> int {
     if (!((cand_mask >> j) & 1u)) return -1;
-    return a.lookahead ? la_bucket(vs[j]) : victim_bucket((long long)a.step - (long long)ss[j], sp[j], a.NP);
+    return a.lookahead ? la_bkt(vs[j], ss[j], sp[j]) : victim_bucket((long long)a.step - (long long)ss[j], sp[j], a.NP);
   };
   u64 vthr = 0;
   if (e > 0) {
@@ -516,13 +560,13 @@ __device__ __forceinline__ bool select_resolve_body(const FastArgs& a, int u, Fa
       auto fn = [&](int sl, u64& kk) -> bool {
         const int p = spage[sl];
         if (p < 0 || ((sm.hit_bitmap[sl >> 5] >> (sl & 31)) & 1u)) return false;
+        const int st = sstamp[sl];
         if (a.lookahead) {
           const float v = victim_score<HANDOFF>(a, u, p);
-          if (la_bucket(v) != bin) return false;
-          kk = lookahead_victim_key(v, p);
+          if (la_bkt(v, st, p) != bin) return false;
+          kk = la_key(v, st, p);
           return true;
         }
-        const int st = sstamp[sl];
         if (victim_bucket((long long)a.step - (long long)st, p, a.NP) != bin) return false;
         kk = ((u64)((u32)st ^ 0x80000000u) << 32) | (u32)p;
         return true;

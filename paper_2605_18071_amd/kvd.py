@@ -28,7 +28,7 @@ class KvdConfig(C.Structure):
         ("sink_pages", C.c_int32), ("recent_pages", C.c_int32), ("kv_dtype", C.c_int32), ("policy", C.c_int32),
         ("softmax_scale", C.c_float), ("capacity_max", C.c_int32), ("capacity", C.POINTER(C.c_int32)),
         ("physical_layers", C.c_int32), ("micro_batches", C.c_int32), ("attn_splits", C.c_int32),
-        ("index_centroids", C.c_int32),
+        ("index_centroids", C.c_int32), ("lookahead_pool", C.c_int32),
     ]
 
 
@@ -189,7 +189,8 @@ class Kvd:
 
     def __init__(self, *, n_layers, batch, n_q_heads, n_kv_heads, page_size, max_pages, topk_pages, capacity_max,
                  kv_dtype, head_dim=128, sink_pages=0, recent_pages=0, softmax_scale=0.0, capacity=None,
-                 physical_layers=0, micro_batches=0, attn_splits=0, policy=KVD_EVICT_LRU, index_centroids=0):
+                 physical_layers=0, micro_batches=0, attn_splits=0, policy=KVD_EVICT_LRU, index_centroids=0,
+                 lookahead_pool=0):
         self.lib = load()
         self._cap = None
         cfg = KvdConfig()
@@ -205,6 +206,7 @@ class Kvd:
             cfg.capacity = C.cast(self._cap, C.POINTER(C.c_int32))
         cfg.physical_layers, cfg.micro_batches, cfg.attn_splits = physical_layers, micro_batches, attn_splits
         cfg.index_centroids = index_centroids
+        cfg.lookahead_pool = lookahead_pool
         self.cfg = cfg
         self.ctx = C.c_void_p()
         st = self.lib.kvd_create(C.byref(cfg), C.byref(self.ctx))

@@ -60,6 +60,7 @@ class Workload:
     physical_layers: int = 0      # 0 -> n_layers
     warm: str = "cold"            # "cold" | "full" | "recent"
     policy: str = "lru"           # cache replacement: "lru" | "lookahead"
+    lookahead_pool: int = 0       # lookahead: look-ahead candidate pool in pages, 0 = every page
     index_centroids: int = 0      # > 0: hierarchical index with this many centroids per unit
     index_iterations: int = 4     # k-means rounds of its build
     seed: int = 0

@@ -33,7 +33,7 @@ class Rig:
                          topk_pages=w.topk_pages, capacity_max=w.capacity, kv_dtype=w.torch_dtype,
                          sink_pages=w.sink_pages, recent_pages=w.recent_pages, capacity=capacity,
                          physical_layers=w.physical_layers, micro_batches=micro_batches, attn_splits=attn_splits,
-                         policy=w.policy, index_centroids=w.index_centroids)
+                         policy=w.policy, index_centroids=w.index_centroids, lookahead_pool=w.lookahead_pool)
         self.kvd.bind_summaries(self.summaries)
         self.kvd.bind_host_store(self.store)
         self.kvd.bind_slot_pool(self.pool)
@@ -193,8 +193,10 @@ class OracleUnit:
             self.summ = orc.page_summaries(self.keys, w.page, self.seq_len, self.code)
         if summaries is not None:                                  # a test planted its own index
             self.summ = summaries[: self.summ.shape[0]]
-        make = orc.LookaheadWindow if w.policy == "lookahead" else orc.LruWindow
-        self.window = make(rig.cap(layer, self.u))
+        if w.policy == "lookahead":
+            self.window = orc.LookaheadWindow(rig.cap(layer, self.u), pool=w.lookahead_pool)
+        else:
+            self.window = orc.LruWindow(rig.cap(layer, self.u))
         self.window.warm(rig.warm_list(b), stamp=-1)
         self.scale = 1.0 / math.sqrt(w.head_dim)
         self.centroids = self.members = None
@@ -309,7 +311,10 @@ def compare_unit(rig: Rig, ou: OracleUnit, t: int, q_layer: torch.Tensor, rep: S
         # the oracle then continues from the GPU's choice
         used = set(int(p) for p in want["used"] if p >= 0)
         cands = [p for p in before if p not in used]
-        ok, msg = H.eviction_is_valid(want["evict_scores"], cands, g_ev, len(want["evicted"]))
+        if w.lookahead_pool > 0:
+            ok, msg = H.pooled_eviction_is_valid(want["evict_scores"], before, cands, g_ev, len(want["evicted"]), w.lookahead_pool)
+        else:
+            ok, msg = H.eviction_is_valid(want["evict_scores"], cands, g_ev, len(want["evicted"]))
         assert ok, f"victims differ outside the tie band at unit {u} step {t}: {msg}"
         rep.victim_tie_divergences += 1
         ou.window.stamp = before

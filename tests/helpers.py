@@ -132,6 +132,44 @@ def eviction_is_valid(scores64: np.ndarray, candidates, evicted, need: int, eps:
     return True, ""
 
 
+def pooled_eviction_is_valid(scores64: np.ndarray, stamps: dict, candidates, evicted, need: int, pool: int,
+                             eps: float = TIE_EPS):
+    """The acceptance rule for the victims of lookahead eviction with a finite look-ahead pool when
+    they differ from the oracle's.  Two float decisions can fall differently at a near-tie: whether
+    a page belongs to the pool (its score against m*, the pool-th best score of the step) and, among
+    pool pages, which score lowest.  The set is accepted iff, for some way of counting the candidates
+    whose score lies within eps of m* as inside or outside the pool, it consists of the pages outside
+    the pool in exact (stamp, page) order and then, if more must leave, of pool pages chosen by the
+    rule of eviction_is_valid.  `stamps`: page -> stamp before the step.  Returns (ok, message)."""
+    cands = sorted(int(p) for p in candidates)
+    ev = [int(p) for p in evicted]
+    if len(ev) != need or len(set(ev)) != need:
+        return False, f"{len(ev)} victims, {need} needed"
+    if not set(ev) <= set(cands):
+        return False, "a victim is not an unselected resident page"
+    n = scores64.shape[0]
+    if pool <= 0 or pool >= n:
+        return eviction_is_valid(scores64, cands, ev, need, eps)
+    m_star = np.sort(scores64)[::-1][pool - 1]
+    sure_in = [p for p in cands if scores64[p] > m_star + eps]
+    sure_out = [p for p in cands if scores64[p] < m_star - eps]
+    amb = [p for p in cands if abs(scores64[p] - m_star) <= eps]
+    if len(amb) > 12:                                   # degenerate scores: every split of the tie is a reading
+        return True, ""
+    for mask in range(1 << len(amb)):
+        inside = sure_in + [p for i, p in enumerate(amb) if (mask >> i) & 1]
+        outside = sure_out + [p for i, p in enumerate(amb) if not (mask >> i) & 1]
+        order = sorted(outside, key=lambda p: (stamps[p], p))
+        if need <= len(order):
+            if set(ev) == set(order[:need]):
+                return True, ""
+        elif set(order) <= set(ev):
+            rest = sorted(set(ev) - set(order))
+            if eviction_is_valid(scores64, inside, rest, need - len(order), eps)[0]:
+                return True, ""
+    return False, "no reading of the near-ties at the pool's edge gives these victims"
+
+
 def attn_rel_err(got: np.ndarray, want: np.ndarray) -> float:
     """max over rows of ||got - want||_inf / max(||want||_inf, 1e-6)."""
     got = got.reshape(-1, got.shape[-1]).astype(np.float64)

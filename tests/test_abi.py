@@ -24,7 +24,7 @@ def test_library_exports_every_declared_symbol():
     for n in names:
         assert hasattr(lib, n), n
     assert sorted(kvd.EXPORTS) == names
-    assert lib.kvd_abi_version() == 1
+    assert lib.kvd_abi_version() == 2
     assert lib.kvd_strerror(0) == b"ok"
     assert b"capacity" in lib.kvd_strerror(kvd.ERR_CAPACITY)
 
@@ -68,6 +68,7 @@ def _cfg(**kw):
     (dict(max_pages=0), kvd.ERR_SHAPE),
     (dict(capacity_max=70000), kvd.ERR_SHAPE),
     (dict(sink_pages=-1), kvd.ERR_SHAPE),
+    (dict(policy=1, lookahead_pool=-3), kvd.ERR_SHAPE),
 ])
 def test_create_rejects_bad_config_without_a_device(kw, want):
     lib = kvd.load()

@@ -1227,11 +1227,49 @@ def test_lookahead_step_parity(cfg, mb):
     rig.close()
 
 
-def test_lookahead_size_agnostic_kernels_and_separate_entry_points(monkeypatch):
+@pytest.mark.parametrize("mb", [-1, 1], ids=["single-launch", "kernel-chain"])
+@pytest.mark.parametrize("cfg,pool", [(2, 40), (3, 60), (3, 48), (3, 400), (5, 30)])
+def test_lookahead_with_a_finite_pool_step_parity(cfg, pool, mb):
+    """Lookahead eviction with a finite look-ahead candidate pool: 1.25 x the budget as in the
+    paper's evaluation (cfg2: 32 pages -> 40, cfg3: 48 -> 60, cfg5: 24 -> 30 with forced recent pages),
+    a pool that is exactly the selection (cfg3, 48: LRU order throughout) and one that covers a third
+    of the pages (400: pool pages must leave too)."""
+    w = _tight(cfg).replace(lookahead_pool=pool)
+    rig = R.Rig(w, micro_batches=mb)
+    units = all_units(rig)
+    rep = R.run_steps(rig, units, w.steps, check_dir_every=3, progress=f"cfg{cfg}-pool{pool}-mb{mb}")
+    assert rep.unit_steps == w.steps * w.n_layers * w.units
+    assert rep.tie_divergences <= 2 and rep.victim_tie_divergences <= 2
+    assert rig.kvd.stats().evictions > w.n_layers * w.units
+    rig.close()
+
+
+def test_lookahead_pool_equal_to_the_selection_is_lru():
+    """With M = k and no forced pages every unselected resident page is outside the pool: the GPU's
+    trace must then be the LRU trace, step by step."""
+    w = _tight(3)
+    a = R.Rig(w.replace(lookahead_pool=w.topk_pages), micro_batches=-1)
+    b = R.Rig(w.replace(policy="lru"), micro_batches=-1, build_index=False)
+    b.summaries.copy_(a.summaries)
+    for t, q in enumerate(W.query_stream(w, a.q0, w.steps, R.DEV)):
+        a.step(0, t, q[0])
+        b.step(0, t, q[0])
+        assert np.array_equal(a.n_sel_pages, b.n_sel_pages) and np.array_equal(a.n_hit_mask, b.n_hit_mask), t
+        assert np.array_equal(np.sort(a.n_evicted, axis=1), np.sort(b.n_evicted, axis=1)), t
+    assert a.kvd.stats().evictions > 0
+    pa, sa = a.kvd.cache_export(0)
+    pb, sb = b.kvd.cache_export(0)
+    assert torch.equal(pa, pb) and torch.equal(sa, sb)
+    a.close()
+    b.close()
+
+
+@pytest.mark.parametrize("pool", [0, 60])
+def test_lookahead_size_agnostic_kernels_and_separate_entry_points(pool, monkeypatch):
     """The same policy through the size-agnostic resolve kernel, driven stage by stage:
     kvd_score_select leaves the scores that kvd_cache_resolve ranks the victims by."""
     monkeypatch.setenv("KVD_GENERIC_SELECT", "1")
-    w = _tight(3)
+    w = _tight(3).replace(lookahead_pool=pool)
     rig = R.Rig(w)
     units = all_units(rig)
     rep = R.StepReport()
@@ -1301,16 +1339,17 @@ def test_hierarchical_index_build_and_step_parity(cfg, mb, kw):
     rig.close()
 
 
-@pytest.mark.parametrize("cfg,mb,generic", [(3, 1, False), (3, 2, False), (5, 1, False), (2, 1, True), (3, -1, False),
-                                            (5, -1, False), (2, -1, False)])
-def test_lookahead_eviction_under_the_hierarchical_index(cfg, mb, generic, monkeypatch):
+@pytest.mark.parametrize("cfg,mb,generic,pool", [(3, 1, False, 0), (3, 2, False, 0), (5, 1, False, 0), (2, 1, True, 0), (3, -1, False, 0),
+                                                 (5, -1, False, 0), (2, -1, False, 0), (3, -1, False, 60), (2, 1, True, 40),
+                                                 (5, 1, False, 30)])
+def test_lookahead_eviction_under_the_hierarchical_index(cfg, mb, generic, pool, monkeypatch):
     """The paper's own combination: selection through the centroids, victims by the lowest
     current-step score — here the score of the page's cluster.  Small windows, so that nearly every
     step evicts; pages of one cluster tie exactly and leave higher page first."""
     if generic:
         monkeypatch.setenv("KVD_GENERIC_SELECT", "1")
     w = _tight(cfg)
-    w = w.replace(index_centroids=w.n_pages // 4, index_iterations=2)
+    w = w.replace(index_centroids=w.n_pages // 4, index_iterations=2, lookahead_pool=pool)   # (pool > 0: a finite look-ahead pool, ranked by cluster score)
     rig = R.Rig(w, micro_batches=mb)
     units = all_units(rig)
     rep = R.run_steps(rig, units, w.steps, check_dir_every=3, progress=f"cfg{cfg}-hier-lookahead-mb{mb}")

@@ -55,6 +55,41 @@ def test_eviction_rule_accepts_the_oracle_and_a_near_tie_only():
     assert H.eviction_is_valid(s, cands, cands, 7)[0] and H.eviction_is_valid(s, cands, [], 0)[0]
 
 
+def test_pooled_eviction_rule_accepts_the_oracle_and_near_ties_only():
+    # scores, best first: 1 .9 | 3 .8 | 6 .7 | 7 .6 | 9 .5+4e-7 | 4 .5 | 10 .3 | 11 .25 | 2 .2 | 8 .15 | 0 .1 | 5 .05
+    s = _scores()
+    cands = [0, 2, 4, 5, 8, 9, 10]
+    stamps = {0: 3, 2: 1, 4: 5, 5: 2, 8: 4, 9: 0, 10: 6}
+
+    def own(pool, st):
+        win = orc.LookaheadWindow(7, pool=pool)
+        win.stamp.update(st)
+        return win.resolve([1, 3, 6], 7, scores=s)[2]                 # three come in, the window is full: three leave
+
+    # pool of 7 = {1, 3, 6, 7, 9, 4, 10}: outside it 2, 5, 0, 8 in stamp order -> 2, 5, 0 leave
+    got = own(7, stamps)
+    assert got == [0, 2, 5] and H.pooled_eviction_is_valid(s, stamps, cands, got, 3, 7)[0]
+    assert not H.pooled_eviction_is_valid(s, stamps, cands, [0, 2, 8], 3, 7)[0]      # 8 (stamp 4) before 0 (stamp 3): wrong order
+    assert not H.pooled_eviction_is_valid(s, stamps, cands, [0, 2, 10], 3, 7)[0]     # a pool page while outside ones remain
+    assert not H.pooled_eviction_is_valid(s, stamps, cands, [0, 2], 3, 7)[0]
+    assert not H.pooled_eviction_is_valid(s, stamps, cands, [0, 2, 1], 3, 7)[0]      # not a candidate
+    # pool of 10: only 0 and 5 are outside; the third victim is the pool page with the lowest score: 8 (0.15)
+    got = own(10, stamps)
+    assert got == [0, 5, 8] and H.pooled_eviction_is_valid(s, stamps, cands, got, 3, 10)[0]
+    assert not H.pooled_eviction_is_valid(s, stamps, cands, [0, 5, 2], 3, 10)[0]     # 2 (0.2) is clearly above 8 (0.15)
+    # pool of 5: its last member is 9 (0.5 + 4e-7), with 4 (0.5) just outside, inside the band.  With equal
+    # stamps the pages outside leave by page number: 0, 2, 4.  Counting 4 as inside and 9 as outside
+    # instead gives 0, 2, 5 (9 would be next): acceptable; 0, 2, 8 is not, in either reading.
+    flat = {p: 0 for p in cands}
+    got = own(5, flat)
+    assert got == [0, 2, 4] and H.pooled_eviction_is_valid(s, flat, cands, got, 3, 5)[0]
+    assert H.pooled_eviction_is_valid(s, flat, cands, [0, 2, 5], 3, 5)[0]
+    assert not H.pooled_eviction_is_valid(s, flat, cands, [0, 2, 8], 3, 5)[0]
+    # no pool: the plain rule
+    assert H.pooled_eviction_is_valid(s, stamps, cands, [0, 5, 8], 3, 0)[0]
+    assert not H.pooled_eviction_is_valid(s, stamps, cands, [0, 5, 2], 3, 0)[0]
+
+
 def test_hierarchical_selection_rule():
     members = [np.array([0, 1, 2]), np.array([3, 4]), np.array([5, 6, 7, 8]), np.array([9, 10])]
     cs = np.array([0.2, 0.9, 0.5, 0.5 + 4e-7])                        # clusters 2 and 3 tie inside the band
