@@ -388,9 +388,9 @@ def brief_config(cfg_id, args, torch, K, W):
 
 def layers_in_flight(args, cfg_w, K, W, torch, dev):
     """The configuration's layer-step over `--layers` layers of one decode step, layers one by one
-    (kvd_step per layer) against two layers in flight (kvd_step_layers): end-to-end ms per
-    layer-step including the fetch of missed pages, cold start, the first `warmup` decode steps
-    untimed."""
+    (kvd_step per layer) against the layers overlapped (kvd_step_layers: one launch per 8 layers, or
+    two chains of kernels in flight): end-to-end ms per layer-step including the fetch of missed
+    pages, cold start, the first `warmup` decode steps untimed."""
     n = args.layers
     w = cfg_w.replace(n_layers=n, physical_layers=min(n, 2), policy=args.policy)
     L, B, Hkv, NP, P, D = w.n_layers, w.batch, w.n_kv_heads, w.n_pages, w.page, w.head_dim
@@ -404,7 +404,7 @@ def layers_in_flight(args, cfg_w, K, W, torch, dev):
     res = {"what": f"{L} layers of one decode step (host store of {w.phys_layers} layers shared by them), {steps} timed decode "
                    f"steps after {warm} from a cold cache: end-to-end ms per layer-step", "layers": L}
     keep = None
-    for mode in ("one_by_one", "two_in_flight"):
+    for mode in ("one_by_one", "overlapped"):
         ctx = K.Kvd(n_layers=L, batch=B, n_q_heads=w.n_q_heads, n_kv_heads=Hkv, page_size=P, max_pages=NP,
                     topk_pages=w.topk_pages, capacity_max=w.capacity, kv_dtype=w.torch_dtype, sink_pages=w.sink_pages,
                     recent_pages=w.recent_pages, physical_layers=w.physical_layers, micro_batches=args.micro_batches,
@@ -586,7 +586,7 @@ def main() -> int:
                     help="order of a unit's pages in the file: page order, or cluster by cluster (needs --centroids)")
     ap.add_argument("--batch", type=int, default=0, metavar="B", help="B > 0: the configuration's shape with B sequences instead of its own batch")
     ap.add_argument("--layers", type=int, default=1, metavar="N",
-                    help="N > 1: add a leg that steps N layers per decode step, one by one and two in flight (kvd_step_layers)")
+                    help="N > 1: add a leg that steps N layers per decode step, one by one and overlapped (kvd_step_layers)")
     ap.add_argument("--timeline", action="store_true",
                     help="when the step runs as one launch: add the per-workgroup timeline of one all-hit step")
     ap.add_argument("--record-traffic", nargs=2, metavar=("FETCH_CSV", "WRITE_CSV"), default=None,
@@ -627,7 +627,8 @@ def main() -> int:
     w = w.replace(policy=args.policy, index_centroids=args.centroids, index_iterations=args.index_iterations,
                   lookahead_pool=int(round(args.lookahead_pool * w.topk_pages)))
     plain = not args.tier
-    rot_layers = args.rot_layers if (plain and not args.no_profile_pass) else 1
+    multi = cfg_w.n_layers > 1                  # a multi-layer configuration: its layers can share a launch (kvd_step_layers)
+    rot_layers = (2 * args.rot_layers if multi else args.rot_layers) if (plain and not args.no_profile_pass) else 1
 
     b = Bench(w, args, torch, K, W, rot_layers)
     ctx, stream, out = b.ctx, b.stream, b.out
@@ -655,7 +656,7 @@ def main() -> int:
     q_cal = stream_q[args.warmup:args.warmup + n_cal]
     queries = stream_q[:args.warmup] + stream_q[args.warmup + n_cal:]
     if tier is None:
-        b.calibrate_shape(stream_q[0])
+        b.calibrate_shape(stream_q[0], multi_layer=multi)
 
     calibration = None
     if args.calibrate > 0:                       # kvd_calibrate_step_form on the warmed-up cache; its steps continue the query stream
@@ -777,6 +778,8 @@ def main() -> int:
         rotating = b.resident_rotating(cycle)
         result["gpu_resident"] = {"replay_one_query": replay, "rotating": rotating,
                                   "rotating_over_replay": rotating["us_per_launch_median"] / replay["us_per_launch_median"]}
+        if multi and b.L >= 2:
+            result["gpu_resident"]["layers_overlapped"] = b.resident_rotating(cycle, in_flight=True)
         if single:
             # the step is one kernel: its launch is bound by the host link while pages are missed
             # and by HBM once they are resident; the roofline is taken on the resident launches
