@@ -84,8 +84,9 @@ typedef struct {
   int32_t micro_batches;   /* how kvd_step overlaps selection, fetch and attention ("SFC Disaggregation"):
                               -1 = the whole step as one launch in which every (sequence, KV head) unit
                                    moves through the stages on its own, synchronised by counters and
-                                   published words in device memory (needs page_size % 16 == 0, max_pages <= 16384,
-                                   capacity_max <= 4096; other shapes run as for 1).  A workgroup of that
+                                   published words in device memory (needs a page size that is a multiple of
+                                   16, or 4, or 8; max_pages <= 16384; capacity_max <= 4096; other shapes run
+                                   as for 1).  A workgroup of that
                                    launch only ever waits for workgroups with a lower index, and the form
                                    relies on the GPU starting the workgroups of a one-dimensional grid in
                                    index order (what a waiting workgroup waits for has then started and
@@ -158,7 +159,8 @@ int kvd_bind_host_store(kvd_ctx* ctx, const void* pinned_store);
 /* GPU cache tier, dev, [L][B][Hkv][Cmax] slots of page_bytes each, 16-byte aligned.  Contents are
  * managed by the library: which page sits in which slot is the directory's business, and inside a
  * slot the page is stored in the order the attention kernel reads it (pages of a multiple of 16
- * tokens: 16-token tiles of MFMA-operand-ready K and transposed V; otherwise K[P][D] then V[P][D]). */
+ * tokens: 16-token tiles of MFMA-operand-ready K and transposed V; pages of 4 or 8 tokens: the same
+ * operands packed per page, 16 / P selected pages forming one tile; otherwise K[P][D] then V[P][D]). */
 int kvd_bind_slot_pool(kvd_ctx* ctx, void* dev_pool);
 /* Valid tokens per sequence, host [B], each in 1..NP*P.  Default: NP*P.  Synchronous. */
 int kvd_set_seq_lens(kvd_ctx* ctx, const int32_t* host_seq_len);

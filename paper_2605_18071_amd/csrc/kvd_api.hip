@@ -8,6 +8,7 @@
 #include <vector>
 
 #include "kvd_internal.h"
+#include "kvd_tile_layout.h"
 
 #define KVD_ABI_VERSION 2
 
@@ -237,7 +238,7 @@ int kvd_create(const kvd_config* cfg, kvd_ctx** out) {
   c->MB = cfg->micro_batches < 1 ? 1 : cfg->micro_batches;
   if (c->MB > c->B) c->MB = c->B;
   c->bf16 = cfg->kv_dtype == KVD_BF16;
-  c->tiled = (c->P % 16) == 0;
+  c->tiled = kvd::slot_layout_of(c->P);
   c->wait_limit_ticks = 200000000LL;                // 2 s
   {
     int dev = 0, cus = 0;
@@ -250,8 +251,10 @@ int kvd_create(const kvd_config* cfg, kvd_ctx** out) {
   c->scale = cfg->softmax_scale > 0.f ? cfg->softmax_scale : 1.0f / sqrtf((float)c->D);
   c->page_bytes = (size_t)2 * c->P * c->D * 2;
   int S = cfg->attn_splits;
+  // 16-token tiles of a unit's selection (pages of 4 or 8 tokens share tiles)
+  const int sel_tiles = c->tiled == kvd::kLayoutPacked ? (c->k * c->P + 15) / 16 : c->k * ((c->P + 15) / 16);
   if (S == 0) {
-    const int tiles = c->k * ((c->P + 15) / 16);
+    const int tiles = sel_tiles;
     if (c->tiled) {
       // the MFMA kernel runs one 512-thread workgroup per CU: about one workgroup per CU in the
       // grid, every wave keeping at least two tiles of 16 tokens
@@ -274,7 +277,7 @@ int kvd_create(const kvd_config* cfg, kvd_ctx** out) {
   c->S1 = S;
   c->step_threads = c->NP > 8192 ? 1024 : 512;
   if (cfg->attn_splits == 0) {
-    const int tiles = c->k * ((c->P + 15) / 16);
+    const int tiles = sel_tiles;
     int S2 = c->step_threads == 1024 ? tiles / 64 : (c->n_cus + c->U / 2) / c->U;
     const int cap = c->step_threads == 1024 ? KVD_MAX_SPLITS : tiles / 16;
     if (S2 > cap) S2 = cap;

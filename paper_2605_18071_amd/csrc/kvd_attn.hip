@@ -7,6 +7,7 @@
 //    an operand-ready tile layout (see kvd_tile_layout.h), so that every wave load is 1 KiB
 //    contiguous and lands directly in MFMA operand registers: S^T = K Q^T with 16x16x32 MFMAs,
 //    O^T += V^T P^T with 16x16x16 MFMAs whose B operand is the softmaxed C tile of the first.
+//    Pages of 4 or 8 tokens take the same kernel over the packed layout: 16 / P pages per tile.
 //  * attend_valu_kernel — any page size, natural [token][dim] slots, fp32 VALU arithmetic.
 #include <math.h>
 
@@ -36,10 +37,10 @@ __global__ __launch_bounds__(kAttnThreads) void combine_kernel(AttnArgs a) {
 // 512 threads and up to 256 registers per lane: one workgroup per CU, three tile buffers (24 KiB)
 // in flight per wave; the grid is sized to about one workgroup per CU (see kvd_create).
 constexpr int kAttnMfmaThreads = 512;
-template <bool BF16, int G>
+template <bool BF16, int G, bool PACKED>
 __global__ __launch_bounds__(kAttnMfmaThreads, 2) void attend_mfma_kernel(AttnArgs a) {
   __shared__ AttnSmem<G, kAttnMfmaThreads / kWave> sm;
-  attend_mfma_body<BF16, G, kAttnMfmaThreads, false>(a, sm, blockIdx.y + a.u0, blockIdx.x);
+  attend_mfma_body<BF16, G, kAttnMfmaThreads, false, false, PACKED>(a, sm, blockIdx.y + a.u0, blockIdx.x);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -176,9 +177,11 @@ __global__ __launch_bounds__(kAttnThreads) void attend_valu_kernel(AttnArgs a) {
 }
 
 template <bool BF16, int G>
-static void launch_attend(bool tiled, const AttnArgs& a, dim3 grid, hipStream_t s, hipEvent_t between) {
-  if (tiled)
-    hipLaunchKernelGGL((attend_mfma_kernel<BF16, G>), grid, dim3(kAttnMfmaThreads), 0, s, a);
+static void launch_attend(int layout, const AttnArgs& a, dim3 grid, hipStream_t s, hipEvent_t between) {
+  if (layout == kLayoutPacked)
+    hipLaunchKernelGGL((attend_mfma_kernel<BF16, G, true>), grid, dim3(kAttnMfmaThreads), 0, s, a);
+  else if (layout == kLayoutTiles)
+    hipLaunchKernelGGL((attend_mfma_kernel<BF16, G, false>), grid, dim3(kAttnMfmaThreads), 0, s, a);
   else
     hipLaunchKernelGGL((attend_valu_kernel<BF16, G>), grid, dim3(kAttnThreads), 0, s, a);
   if (between != nullptr) (void)hipEventRecord(between, s);   // no kernel follows when the merge is fused
@@ -187,16 +190,16 @@ static void launch_attend(bool tiled, const AttnArgs& a, dim3 grid, hipStream_t 
 }
 
 template <bool BF16>
-static bool dispatch_group(int G, bool tiled, const AttnArgs& a, dim3 grid, hipStream_t s, hipEvent_t between) {
+static bool dispatch_group(int G, int layout, const AttnArgs& a, dim3 grid, hipStream_t s, hipEvent_t between) {
   switch (G) {
-    case 1: launch_attend<BF16, 1>(tiled, a, grid, s, between); return true;
-    case 2: launch_attend<BF16, 2>(tiled, a, grid, s, between); return true;
-    case 3: launch_attend<BF16, 3>(tiled, a, grid, s, between); return true;
-    case 4: launch_attend<BF16, 4>(tiled, a, grid, s, between); return true;
-    case 5: launch_attend<BF16, 5>(tiled, a, grid, s, between); return true;
-    case 6: launch_attend<BF16, 6>(tiled, a, grid, s, between); return true;
-    case 7: launch_attend<BF16, 7>(tiled, a, grid, s, between); return true;
-    case 8: launch_attend<BF16, 8>(tiled, a, grid, s, between); return true;
+    case 1: launch_attend<BF16, 1>(layout, a, grid, s, between); return true;
+    case 2: launch_attend<BF16, 2>(layout, a, grid, s, between); return true;
+    case 3: launch_attend<BF16, 3>(layout, a, grid, s, between); return true;
+    case 4: launch_attend<BF16, 4>(layout, a, grid, s, between); return true;
+    case 5: launch_attend<BF16, 5>(layout, a, grid, s, between); return true;
+    case 6: launch_attend<BF16, 6>(layout, a, grid, s, between); return true;
+    case 7: launch_attend<BF16, 7>(layout, a, grid, s, between); return true;
+    case 8: launch_attend<BF16, 8>(layout, a, grid, s, between); return true;
     default: return false;
   }
 }
@@ -236,8 +239,8 @@ hipError_t kvd_launch_attend(kvd_ctx* c, int layer, const void* q, const int32_t
   if (u1 <= u0) return hipSuccess;
   const AttnArgs a = kvd_attn_args(c, layer, q, sel_pages, sel_slots, out, lse, u0);
   dim3 grid(c->S, u1 - u0);
-  const bool ok = c->bf16 ? dispatch_group<true>(c->G, c->tiled != 0, a, grid, s, between)
-                          : dispatch_group<false>(c->G, c->tiled != 0, a, grid, s, between);
+  const bool ok = c->bf16 ? dispatch_group<true>(c->G, c->tiled, a, grid, s, between)
+                          : dispatch_group<false>(c->G, c->tiled, a, grid, s, between);
   if (!ok) return hipErrorInvalidValue;
   return hipGetLastError();
 }
@@ -308,11 +311,12 @@ extern "C" int kvd_sparse_decode_attn_noalloc(const void* q, const void* slot_po
     return KVD_ERR_HIP;
   }
   const int U = batch * n_kv_heads;
-  const bool tiled = page_size % 16 == 0;
+  const int layout = slot_layout_of(page_size);
+  const bool tiled = layout != kLayoutNatural;
   // split-K factor: the rule of kvd_create
   int S = attn_splits;
   if (S == 0) {
-    const int tiles = topk_pages * ((page_size + 15) / 16);
+    const int tiles = layout == kLayoutPacked ? (topk_pages * page_size + 15) / 16 : topk_pages * ((page_size + 15) / 16);
     if (tiled) {
       S = (cus + U / 2) / U;
       if (S > tiles / 16) S = tiles / 16;
@@ -364,8 +368,8 @@ extern "C" int kvd_sparse_decode_attn_noalloc(const void* q, const void* slot_po
     return KVD_ERR_HIP;
   }
   const dim3 grid(S, U);
-  const bool ok = kv_dtype == KVD_BF16 ? dispatch_group<true>(G, tiled, a, grid, s, nullptr)
-                                       : dispatch_group<false>(G, tiled, a, grid, s, nullptr);
+  const bool ok = kv_dtype == KVD_BF16 ? dispatch_group<true>(G, layout, a, grid, s, nullptr)
+                                       : dispatch_group<false>(G, layout, a, grid, s, nullptr);
   if (!ok) return KVD_ERR_SHAPE;
   if (hipGetLastError() != hipSuccess) return KVD_ERR_HIP;
   return KVD_OK;

@@ -204,10 +204,14 @@ __device__ __forceinline__ f32x4 mfma_pv(const uint2& vfrag, const uint2& pfrag,
 // HANDOFF: the selection was written by another workgroup of the same launch.
 // LEAN: for 128 registers per lane (two workgroups of 8 waves per CU): two tile buffers instead of
 // three and the Q^T fragments re-read from LDS for every tile.
+// PACKED: pages of 4 or 8 tokens in the packed slot layout: a tile is made of 16 / P consecutive
+// entries of the split, every lane fetching its 16-byte units from the slot of its own page, and
+// every token of the tile is valid or not on its own (a page beyond the selection's end, a made-up
+// page, the ragged last page of a sequence).
 // Returns 1 in the workgroup that completed the unit's output, 0 in the others, -1 (from all
 // threads, no output) when a HANDOFF wait ran out.  inputs_ready_tick (one thread passes it)
 // receives the wall clock at which the split's entries were all there.
-template <bool BF16, int GT, int NT, bool HANDOFF, bool LEAN = false>
+template <bool BF16, int GT, int NT, bool HANDOFF, bool LEAN = false, bool PACKED = false>
 __device__ __forceinline__ int attend_mfma_body(const AttnArgs& a, AttnSmem<GroupMax<GT>::value, NT / kWave>& sm, int u,
                                                 int split, long long* inputs_ready_tick = nullptr) {
   constexpr int NW = NT / kWave;
@@ -238,10 +242,11 @@ __device__ __forceinline__ int attend_mfma_body(const AttnArgs& a, AttnSmem<Grou
   float m = -INFINITY, l = 0.f;
 
   const int seq = a.seq_len[b];
-  const int tiles_per_page = a.P >> 4;
+  const int tiles_per_page = a.P >> 4;                  // (PACKED: 0; pages_per_tile counts instead)
+  const int pages_per_tile = PACKED ? 16 / a.P : 1;
   const int first = split * a.per_split;
   const int last = (first + a.per_split) < a.k ? (first + a.per_split) : a.k;
-  const int n_tiles = (last - first) * tiles_per_page;
+  const int n_tiles = PACKED ? (last - first + pages_per_tile - 1) / pages_per_tile : (last - first) * tiles_per_page;
   const int32_t* sel = a.sel_pages + (size_t)u * a.k;
   const int32_t* slots = a.sel_slots + (size_t)u * a.k;
   const char* pool_u = a.pool + (size_t)u * a.Cmax * a.page_bytes;
@@ -286,10 +291,46 @@ __device__ __forceinline__ int attend_mfma_body(const AttnArgs& a, AttnSmem<Grou
 
   // software pipeline: three tile buffers rotate, so the operands of the next two tiles of this
   // wave (16 KiB) are in flight while one tile is computed
-  struct Tile { uint4 k[4], v[4]; int ntok; };
+  struct Tile { uint4 k[4], v[4]; u32 valid; };        // valid: bit i = token i of the tile takes part
   auto issue = [&](Tile& tl, int t) {
-    tl.ntok = 0;
+    tl.valid = 0;
     if (t >= n_tiles) return;
+    if (PACKED) {
+      // lane (i, g): K units of token i of the tile = token i % P of entry i / P; V units of tokens
+      // 4g..4g+3 = token group (4g % P) / 4 of entry 4g / P
+      auto entry = [&](int e, int& page, int& slot) {
+        page = -1; slot = -1;
+        if (e < n_entries) {
+          if (idx_in_lds) { page = sm.page[e]; slot = sm.slot[e]; }
+          else { page = sel[first + e]; slot = slots[first + e]; }
+        }
+        if (slot >= a.Cmax) slot = -1;
+      };
+      const int e0 = t * pages_per_tile;
+      int kp, ks, vp, vs;
+      entry(e0 + j / a.P, kp, ks);
+      entry(e0 + (4 * g) / a.P, vp, vs);
+      const int ktok = j % a.P;
+      const bool kok = kp >= 0 && ks >= 0 && kp * a.P + ktok < seq;
+      // the tile's valid tokens: lanes 0..15 (g = 0) speak for tokens 0..15
+      const u32 valid = (u32)(__ballot(kok) & 0xffffull);
+      tl.valid = valid;
+      if (valid == 0) return;
+#pragma unroll
+      for (int c = 0; c < 4; ++c) { tl.k[c] = make_uint4(0u, 0u, 0u, 0u); tl.v[c] = make_uint4(0u, 0u, 0u, 0u); }
+      if (kok) {
+        const char* kb = pool_u + (size_t)ks * a.page_bytes + (size_t)(g * a.P + ktok) * 16;
+#pragma unroll
+        for (int c = 0; c < 4; ++c) tl.k[c] = load_stream16(kb + (size_t)c * 4 * a.P * 16);
+      }
+      if (vp >= 0 && vs >= 0 && ((valid >> (4 * g)) & 15u)) {
+        const int groups = a.P >> 2, tg = ((4 * g) % a.P) >> 2;
+        const char* vb = pool_u + (size_t)vs * a.page_bytes + (size_t)a.P * kRowBytes + (size_t)(tg * 16 + j) * 16;
+#pragma unroll
+        for (int c = 0; c < 4; ++c) tl.v[c] = load_stream16(vb + (size_t)c * groups * 256);
+      }
+      return;
+    }
     const int e = t / tiles_per_page, tile = t % tiles_per_page;
     int page, slot;
     if (idx_in_lds) {
@@ -305,7 +346,7 @@ __device__ __forceinline__ int attend_mfma_body(const AttnArgs& a, AttnSmem<Grou
     int ntok = seq - page * a.P - tile * 16;
     ntok = ntok < 16 ? ntok : 16;
     if (ntok <= 0) return;
-    tl.ntok = ntok;
+    tl.valid = ntok >= 16 ? 0xffffu : ((1u << ntok) - 1u);
     const uint4* tb = reinterpret_cast<const uint4*>(pool_u + (size_t)slot * a.page_bytes + (size_t)tile * kTileBytes) + lane;
 #pragma unroll
     for (int c = 0; c < 4; ++c) tl.k[c] = load_stream16(tb + c * 64);
@@ -313,16 +354,17 @@ __device__ __forceinline__ int attend_mfma_body(const AttnArgs& a, AttnSmem<Grou
     for (int c = 0; c < 4; ++c) tl.v[c] = load_stream16(tb + 256 + c * 64);
   };
   auto compute = [&](Tile& tl) {
-    const int ntok = tl.ntok;
-    if (ntok == 0) return;
-    if (ntok < 16) {
-      // ragged last tile: the slot holds whatever the store had beyond the sequence's end (a page
-      // is copied whole), and a probability of zero does not silence a NaN or an infinity there,
-      // so those tokens' V elements are blanked.  Lane (., g) holds tokens 4g..4g+3 of a dim in
-      // each half of a V fragment, two tokens per 32-bit word.
-      const int nv = ntok - 4 * g;
-      const u32 m0 = nv >= 2 ? 0xffffffffu : (nv == 1 ? 0x0000ffffu : 0u);
-      const u32 m1 = nv >= 4 ? 0xffffffffu : (nv == 3 ? 0x0000ffffu : 0u);
+    const u32 valid = tl.valid;
+    if (valid == 0) return;
+    const u32 mine = (valid >> (4 * g)) & 15u;          // this lane's four tokens 4g..4g+3
+    if (valid != 0xffffu) {
+      // a tile with tokens that take no part (the ragged end of a sequence, whose slot holds whatever
+      // the store had there since a page is copied whole; with PACKED also a missing page): a
+      // probability of zero does not silence a NaN or an infinity, so those tokens' V elements are
+      // blanked.  Lane (., g) holds tokens 4g..4g+3 of a dim in each half of a V fragment, two
+      // tokens per 32-bit word.
+      const u32 m0 = ((mine & 1u) ? 0x0000ffffu : 0u) | ((mine & 2u) ? 0xffff0000u : 0u);
+      const u32 m1 = ((mine & 4u) ? 0x0000ffffu : 0u) | ((mine & 8u) ? 0xffff0000u : 0u);
 #pragma unroll
       for (int c = 0; c < 4; ++c) {
         tl.v[c].x &= m0; tl.v[c].y &= m1;
@@ -336,12 +378,12 @@ __device__ __forceinline__ int attend_mfma_body(const AttnArgs& a, AttnSmem<Grou
     float mx = -INFINITY;
 #pragma unroll
     for (int e = 0; e < 4; ++e) {
-      x[e] = (4 * g + e) < ntok ? s[e] * a.scale_log2 : -INFINITY;
+      x[e] = ((mine >> e) & 1u) ? s[e] * a.scale_log2 : -INFINITY;
       mx = fmaxf(mx, x[e]);
     }
     mx = fmaxf(mx, __shfl_xor(mx, 16, kWave));
     mx = fmaxf(mx, __shfl_xor(mx, 32, kWave));
-    const float m_new = fmaxf(m, mx);                // finite: token 0 of the tile is valid
+    const float m_new = fmaxf(m, mx);                // finite: some token of the tile is valid
     if (__any(m_new > m)) {
       const float alpha = exp2f(m - m_new);
       l *= alpha;

@@ -220,10 +220,17 @@ constexpr int kGatherBlocksPerUnit = 8;
 // Copies one page from the host store (natural layout: K[P][D] then V[P][D]) into a slot, with all
 // 256 threads of the block.  TILED: the slot takes the tile layout of kvd_tile_layout.h — K moves
 // in 16-byte units to permuted positions, V is transposed through LDS (`vt`, 16 x 128 elements).
-template <bool TILED>
+template <int TILED>
 __device__ __forceinline__ void copy_page(const char* __restrict__ src, char* __restrict__ dst, int P,
                                           unsigned page_bytes, uint16_t* vt) {
   const int tid = threadIdx.x;
+  if (TILED == kLayoutPacked) {
+    __syncthreads();                                   // previous page's readers are done with vt
+    packed_copy_phase_a(src, P, dst, vt, tid);
+    __syncthreads();
+    packed_copy_phase_b(P, dst, vt, tid);
+    return;
+  }
   if (!TILED) {
     const uint4* s4 = reinterpret_cast<const uint4*>(src);
     uint4* d4 = reinterpret_cast<uint4*>(dst);
@@ -243,7 +250,7 @@ __device__ __forceinline__ void copy_page(const char* __restrict__ src, char* __
 // Fetch: block (x, u) copies misses x, x+8, ... of unit u from the pinned host store (read across
 // the host link, 16 bytes per lane) into their slots.  With src_offset the j-th miss of the unit
 // is read from store + src_offset[u][j] instead (a negative offset: nothing to copy).
-template <bool TILED>
+template <int TILED>
 __global__ __launch_bounds__(kGatherThreads) void gather_kernel(const char* __restrict__ store,   // [U][NP] pages of the layer
                                                                char* __restrict__ pool,          // [U][Cmax] slots of the layer
                                                                const int32_t* __restrict__ miss_list,
@@ -270,7 +277,7 @@ __global__ __launch_bounds__(kGatherThreads) void gather_kernel(const char* __re
 }
 
 // Set-up: (re)load every occupied slot of a layer from the host store, as named by slot_page.
-template <bool TILED>
+template <int TILED>
 __global__ __launch_bounds__(kGatherThreads) void refill_kernel(const char* __restrict__ store, char* __restrict__ pool,
                                                                const int32_t* __restrict__ slot_page, int NP, int Cmax,
                                                                int P, unsigned page_bytes) {
@@ -327,7 +334,7 @@ __global__ __launch_bounds__(kHeadDim) void summaries_kernel(const uint16_t* __r
 // store (written across the host link), in the slot of its page if that page is resident, and the
 // page's index entry is recomputed as the mean over its valid tokens including the new one (fp64,
 // token order, rounded once — the same definition as summaries_kernel).
-template <bool BF16, bool TILED>
+template <bool BF16, int TILED>
 __global__ __launch_bounds__(256) void append_kernel(uint16_t* __restrict__ store,          // [U][NP][2][P][D] of the layer
                                                     uint16_t* __restrict__ summ,           // [U][NP][D]
                                                     char* __restrict__ pool,               // [U][Cmax] slots
@@ -366,7 +373,16 @@ __global__ __launch_bounds__(256) void append_kernel(uint16_t* __restrict__ stor
   if (slot >= 0 && tid < kHeadDim) {
     char* sl = pool + ((size_t)u * Cmax + slot) * page_bytes;
     const int d = tid;
-    if (TILED) {
+    if (TILED == kLayoutPacked) {
+      // packed layout (kvd_tile_layout.h): K element [o][d] in unit (c, g, o), V element [o][d] in
+      // unit (c, o / 4, d % 16) at element 4 ((d % 32) / 16) + o % 4
+      const int c = d >> 5, r32 = d & 31;
+      uint16_t* kdst = reinterpret_cast<uint16_t*>(sl + (size_t)((c * 4 + (r32 >> 3)) * P + o) * 16) + (d & 7);
+      uint16_t* vdst = reinterpret_cast<uint16_t*>(sl + (size_t)P * kRowBytes + (size_t)((c * (P >> 2) + (o >> 2)) * 16 + (d & 15)) * 16) +
+                       4 * (r32 >> 4) + (o & 3);
+      *kdst = kn[d];
+      *vdst = vn[d];
+    } else if (TILED) {
       // tile layout (kvd_tile_layout.h): K element [row][d] sits in chunk d/32, lane row + 16 ((d%32)/8),
       // element d%8; V element [row][d] in chunk d/32, lane d%16 + 16 (row/4), element 4 ((d%32)/16) + row%4
       char* tile = sl + (size_t)(o / kTileTokens) * kTileBytes;
@@ -454,12 +470,13 @@ hipError_t kvd_launch_gather(kvd_ctx* c, int layer, int u0, int u1, hipStream_t 
   const int lp = layer % c->Lp;
   const char* store = src_offset ? src_base : c->store_dev + (size_t)lp * c->U * c->NP * c->page_bytes;
   char* pool = c->pool + (size_t)layer * c->U * c->Cmax * c->page_bytes;
-  if (c->tiled)
-    hipLaunchKernelGGL(gather_kernel<true>, dim3(kGatherBlocksPerUnit, u1 - u0), dim3(kGatherThreads), 0, s, store, pool,
-                       c->d_miss_list, c->d_miss_count, src_offset, c->k, c->NP, c->Cmax, c->P, (unsigned)c->page_bytes, u0);
-  else
-    hipLaunchKernelGGL(gather_kernel<false>, dim3(kGatherBlocksPerUnit, u1 - u0), dim3(kGatherThreads), 0, s, store, pool,
-                       c->d_miss_list, c->d_miss_count, src_offset, c->k, c->NP, c->Cmax, c->P, (unsigned)c->page_bytes, u0);
+#define KVD_GATHER(LAYOUT)                                                                                              \
+  hipLaunchKernelGGL(gather_kernel<LAYOUT>, dim3(kGatherBlocksPerUnit, u1 - u0), dim3(kGatherThreads), 0, s, store, pool, \
+                     c->d_miss_list, c->d_miss_count, src_offset, c->k, c->NP, c->Cmax, c->P, (unsigned)c->page_bytes, u0)
+  if (c->tiled == kLayoutPacked) KVD_GATHER(kLayoutPacked);
+  else if (c->tiled) KVD_GATHER(kLayoutTiles);
+  else KVD_GATHER(kLayoutNatural);
+#undef KVD_GATHER
   return hipGetLastError();
 }
 
@@ -470,12 +487,13 @@ hipError_t kvd_launch_refill(kvd_ctx* c, int layer, hipStream_t s) {
   char* pool = c->pool + (size_t)layer * c->U * c->Cmax * c->page_bytes;
   const int32_t* slot_page = c->d_slot_page + (size_t)layer * c->U * c->Cmax;
   const int bx = c->Cmax < 64 ? c->Cmax : 64;
-  if (c->tiled)
-    hipLaunchKernelGGL(refill_kernel<true>, dim3(bx, c->U), dim3(kGatherThreads), 0, s, store, pool, slot_page, c->NP,
-                       c->Cmax, c->P, (unsigned)c->page_bytes);
-  else
-    hipLaunchKernelGGL(refill_kernel<false>, dim3(bx, c->U), dim3(kGatherThreads), 0, s, store, pool, slot_page, c->NP,
-                       c->Cmax, c->P, (unsigned)c->page_bytes);
+#define KVD_REFILL(LAYOUT)                                                                                          \
+  hipLaunchKernelGGL(refill_kernel<LAYOUT>, dim3(bx, c->U), dim3(kGatherThreads), 0, s, store, pool, slot_page, c->NP, \
+                     c->Cmax, c->P, (unsigned)c->page_bytes)
+  if (c->tiled == kLayoutPacked) KVD_REFILL(kLayoutPacked);
+  else if (c->tiled) KVD_REFILL(kLayoutTiles);
+  else KVD_REFILL(kLayoutNatural);
+#undef KVD_REFILL
   return hipGetLastError();
 }
 
@@ -506,8 +524,11 @@ hipError_t kvd_launch_append(kvd_ctx* c, int layer, const void* k_new, const voi
 #define KVD_APPEND(BF, TL)                                                                                          \
   hipLaunchKernelGGL((append_kernel<BF, TL>), grid, block, 0, s, store, summ, pool, slot_page, cap, kn, vn, c->d_seq_len, \
                      c->NP, c->P, c->Cmax, c->Hkv, (unsigned)c->page_bytes)
-  if (c->bf16) { if (c->tiled) KVD_APPEND(true, true); else KVD_APPEND(true, false); }
-  else { if (c->tiled) KVD_APPEND(false, true); else KVD_APPEND(false, false); }
+  if (c->bf16) {
+    if (c->tiled == kLayoutPacked) KVD_APPEND(true, kLayoutPacked); else if (c->tiled) KVD_APPEND(true, kLayoutTiles); else KVD_APPEND(true, kLayoutNatural);
+  } else {
+    if (c->tiled == kLayoutPacked) KVD_APPEND(false, kLayoutPacked); else if (c->tiled) KVD_APPEND(false, kLayoutTiles); else KVD_APPEND(false, kLayoutNatural);
+  }
 #undef KVD_APPEND
   return hipGetLastError();
 }

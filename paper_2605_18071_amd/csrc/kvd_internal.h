@@ -52,7 +52,7 @@ struct kvd_ctx {
   int generic_select;      // force the size-agnostic select / resolve kernels (testing)
   int fuse_merge;          // attention: last split workgroup merges (1) or a second kernel does (0)
   int single_launch;       // kvd_step runs as one kernel launch
-  int tiled;               // slots use the tile layout (page size a multiple of 16)
+  int tiled;               // slot layout (kvd_tile_layout.h): 0 natural, 1 16-token tiles (page size a multiple of 16), 2 packed (pages of 4 or 8 tokens)
   float scale;
   size_t page_bytes;
 

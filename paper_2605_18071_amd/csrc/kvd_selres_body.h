@@ -662,7 +662,23 @@ __device__ __forceinline__ bool select_resolve_body(const FastArgs& a, int u, Fa
   const int grp = tid >> 8, gt = tid & 255;
   const char* store_u = a.store + (size_t)u * a.NP * a.page_bytes;
   char* pool_u = a.pool + (size_t)u * a.Cmax * a.page_bytes;
-  if (a.tiled) {
+  if (a.tiled == kLayoutPacked) {
+    // pages of 4 or 8 tokens: one page per group and round
+    for (int j0 = 0; j0 < m; j0 += kCopyGroups) {
+      const int jm = j0 + grp;
+      const bool on = jm < m;
+      int page = 0, slot = -1;
+      if (on) {
+        page = sm.sel[jm];
+        slot = sm.assign[jm] == kAbsent ? -1 : sm.assign[jm];
+      }
+      char* dst = pool_u + (size_t)(slot < 0 ? 0 : slot) * a.page_bytes;
+      if (on && slot >= 0) packed_copy_phase_a<HANDOFF>(store_u + (size_t)page * a.page_bytes, a.P, dst, sm.a.vt[grp], gt);
+      __syncthreads();
+      if (on && slot >= 0) packed_copy_phase_b<HANDOFF>(a.P, dst, sm.a.vt[grp], gt);
+      __syncthreads();
+    }
+  } else if (a.tiled) {
     const int tiles = a.P / kTileTokens;
     const int n_items = m * tiles;
     for (int it0 = 0; it0 < n_items; it0 += kCopyGroups) {

@@ -189,7 +189,7 @@ __device__ __forceinline__ void step_select_role(StepArgsPtr ap, int li, int u, 
 }
 
 // Attention workgroup (u, split).
-template <bool BF16, int NT, bool LEAN>
+template <bool BF16, int NT, bool LEAN, bool PACKED>
 __device__ __forceinline__ void step_attend_role(StepArgsPtr ap, int li, int u, int split, unsigned char* smem_raw, long long* ts) {
   struct { AttnArgs at; } a;
   __builtin_memcpy(&a.at, &ap->at, sizeof(AttnArgs));
@@ -204,12 +204,12 @@ __device__ __forceinline__ void step_attend_role(StepArgsPtr ap, int li, int u, 
   }
   if (ts) ts[4] = 2LL | ((long long)u << 8) | ((long long)split << 32);
   typename StepSmem<NT>::Attn& sm = *reinterpret_cast<typename StepSmem<NT>::Attn*>(smem_raw);
-  const int done = attend_mfma_body<BF16, 0, NT, true, LEAN>(a.at, sm, u, split, ts ? ts + 1 : nullptr);
+  const int done = attend_mfma_body<BF16, 0, NT, true, LEAN, PACKED>(a.at, sm, u, split, ts ? ts + 1 : nullptr);
   if (done < 0 && threadIdx.x == 0) __hip_atomic_store(a.at.error, 2, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
   if (ts) ts[2] = ts[3] = wall_clock64();
 }
 
-template <bool BF16, int NT, int IPT, bool LEAN>
+template <bool BF16, int NT, int IPT, bool LEAN, bool PACKED>
 __device__ __forceinline__ void step_body(StepArgsPtr ap, unsigned char* smem_raw, int& wait_ok) {
   const int bid = blockIdx.x;
   long long* timeline = ap->timeline;
@@ -236,7 +236,7 @@ __device__ __forceinline__ void step_body(StepArgsPtr ap, unsigned char* smem_ra
   int n_units = ap->n_units - (st % groups) * Ug;       // units of this group
   n_units = n_units < Ug ? n_units : Ug;
   if (is_back) {
-    if (o / S < n_units) step_attend_role<BF16, NT, LEAN>(ap, li, o / S + u0, o % S, smem_raw, ts);
+    if (o / S < n_units) step_attend_role<BF16, NT, LEAN, PACKED>(ap, li, o / S + u0, o % S, smem_raw, ts);
   } else if (o < n_score) {
     step_score_role<BF16, NT>(ap, li, u0, n_units, o, ts);
   } else {
@@ -244,28 +244,28 @@ __device__ __forceinline__ void step_body(StepArgsPtr ap, unsigned char* smem_ra
   }
 }
 
-// LEAN: 128 registers per lane (the 1024-thread form); otherwise 256.
-template <bool BF16, int NT, int IPT, bool LEAN = (NT > kStepThreads)>
+// LEAN: 128 registers per lane (the 1024-thread form); otherwise 256.  PACKED: pages of 4 or 8 tokens.
+template <bool BF16, int NT, int IPT, bool PACKED, bool LEAN = (NT > kStepThreads)>
 __global__ __launch_bounds__(NT, LEAN ? 4 : 2) void step_kernel(StepArgs a) {
   __shared__ __align__(16) unsigned char smem_raw[StepSmem<NT>::bytes];
   __shared__ int wait_ok;
   // the launch arguments are the first thing in the kernel-argument segment
-  step_body<BF16, NT, IPT, LEAN>((StepArgsPtr)__builtin_amdgcn_kernarg_segment_ptr(), smem_raw, wait_ok);
+  step_body<BF16, NT, IPT, LEAN, PACKED>((StepArgsPtr)__builtin_amdgcn_kernarg_segment_ptr(), smem_raw, wait_ok);
 }
-template <bool BF16>
+template <bool BF16, bool PACKED>
 static void launch_step(int threads, int ipt, const StepArgs& a, int n_blocks, hipStream_t s) {
   dim3 grid(n_blocks), block(threads);
   if (threads == kStepThreadsWide) {
     if (ipt <= 8)
-      hipLaunchKernelGGL((step_kernel<BF16, kStepThreadsWide, 8>), grid, block, 0, s, a);
+      hipLaunchKernelGGL((step_kernel<BF16, kStepThreadsWide, 8, PACKED>), grid, block, 0, s, a);
     else
-      hipLaunchKernelGGL((step_kernel<BF16, kStepThreadsWide, 16>), grid, block, 0, s, a);
+      hipLaunchKernelGGL((step_kernel<BF16, kStepThreadsWide, 16, PACKED>), grid, block, 0, s, a);
   } else if (ipt <= 4) {
-    hipLaunchKernelGGL((step_kernel<BF16, kStepThreads, 4>), grid, block, 0, s, a);
+    hipLaunchKernelGGL((step_kernel<BF16, kStepThreads, 4, PACKED>), grid, block, 0, s, a);
   } else if (ipt <= 8) {
-    hipLaunchKernelGGL((step_kernel<BF16, kStepThreads, 8>), grid, block, 0, s, a);
+    hipLaunchKernelGGL((step_kernel<BF16, kStepThreads, 8, PACKED>), grid, block, 0, s, a);
   } else {
-    hipLaunchKernelGGL((step_kernel<BF16, kStepThreads, 16>), grid, block, 0, s, a);
+    hipLaunchKernelGGL((step_kernel<BF16, kStepThreads, 16, PACKED>), grid, block, 0, s, a);
   }
 }
 
@@ -399,7 +399,8 @@ hipError_t kvd_launch_step(kvd_ctx* c, int layer, int n_layers, int step, const 
   c->tl_workgroups = n_blocks;
   if (c->profiling == 2 && n_blocks <= KVD_TIMELINE_MAX) a.timeline = c->d_timeline;
   const int ipt = (c->NP + chunk_pages - 1) / chunk_pages;
-  if (c->bf16) launch_step<true>(threads, ipt, a, n_blocks, s);
-  else launch_step<false>(threads, ipt, a, n_blocks, s);
+  const bool packed = c->tiled == kLayoutPacked;
+  if (c->bf16) { if (packed) launch_step<true, true>(threads, ipt, a, n_blocks, s); else launch_step<true, false>(threads, ipt, a, n_blocks, s); }
+  else { if (packed) launch_step<false, true>(threads, ipt, a, n_blocks, s); else launch_step<false, false>(threads, ipt, a, n_blocks, s); }
   return hipGetLastError();
 }

@@ -13,6 +13,17 @@
 //       4 elements  V[token 4g + 0..3][dim 32c + 16 + i]   (last 8 bytes)
 //     -> two A operands of 16x16x16 MFMAs with rows = dims, contraction over 16 tokens (V^T).
 //
+// Pages of 4 or 8 tokens ("packed layout"): 16 / P consecutive selected pages make up one 16-token
+// MFMA tile, so a slot (2 * P * 256 bytes) holds its page's share of the same operands:
+//
+//   K part (P * 256 bytes), unit (c, g, t) at 16 * ((4c + g) * P + t):
+//       8 elements  K[token t][dim 32c + 8g + 0..7]
+//     -> for chunk c the P * 64 bytes of a page are contiguous, and lane (i, g) of a tile reads the
+//        unit (c, g, i % P) of the tile's page i / P.
+//   V part (P * 256 bytes), unit (c, tg, i) at P * 256 + 16 * ((c * P/4 + tg) * 16 + i):
+//       4 elements  V[token 4tg + 0..3][dim 32c + i], then 4 elements V[token 4tg + 0..3][dim 32c + 16 + i]
+//     -> lane (i, g) of a tile reads the unit (c, (4g % P) / 4, i) of the tile's page 4g / P.
+//
 // Pages of any other size keep the natural layout of the host store: K[P][D] then V[P][D].
 #pragma once
 
@@ -20,4 +31,9 @@ namespace kvd {
 constexpr int kTileTokens = 16;
 constexpr int kTileBytes = 2 * kTileTokens * 128 * 2;   // 8192
 constexpr int kTilePartBytes = kTileBytes / 2;          // 4096
+// How the pages of a context are kept in their slots.
+constexpr int kLayoutNatural = 0, kLayoutTiles = 1, kLayoutPacked = 2;
+__host__ __device__ inline int slot_layout_of(int page_size) {
+  return page_size % kTileTokens == 0 ? kLayoutTiles : ((page_size == 4 || page_size == 8) ? kLayoutPacked : kLayoutNatural);
+}
 }  // namespace kvd

@@ -202,9 +202,17 @@ def slot_image(page: torch.Tensor) -> torch.Tensor:
     from the documented slot layout: pages of a multiple of 16 tokens are stored as 16-token
     tiles, each a K part [chunk c][group g][token i][8 dims 32c+8g+e] followed by a V part
     [chunk c][token group g][dim i][half hh][4 tokens 4g+k] holding V[4g+k][32c+16hh+i];
+    pages of 4 or 8 tokens are packed the same way, one page per slot (see below);
     any other page size keeps the host order."""
     raw = page.detach().cpu().contiguous().view(torch.int16).numpy()
     P, D = raw.shape[1], raw.shape[2]
+    if P in (4, 8):
+        # packed layout: K part [chunk c][group g][token t][8 dims 32c+8g+e], then V part
+        # [chunk c][token group tg][dim i][half hh][4 tokens 4tg+k] holding V[4tg+k][32c+16hh+i]
+        k = raw[0].reshape(P, 4, 4, 8)                                # [t, c, g, e]
+        v = raw[1].reshape(P // 4, 4, 4, 2, 16)                       # [tg, k, c, hh, i]
+        return torch.from_numpy(np.concatenate([k.transpose(1, 2, 0, 3).reshape(-1),
+                                                v.transpose(2, 0, 4, 3, 1).reshape(-1)]).copy())
     if P % 16 != 0:
         return torch.from_numpy(raw.reshape(-1).copy())
     tiles = []

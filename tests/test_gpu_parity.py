@@ -194,13 +194,15 @@ def test_resolve_trace_parity(n_pages, k, cap):
     rig.close()
 
 
+@pytest.mark.parametrize("page", [16, 4], ids=["page16", "page4-packed"])
 @pytest.mark.parametrize("generic", [False, True], ids=["fused", "size-agnostic"])
-def test_resolve_and_attention_skip_padding_and_made_up_pages(generic, monkeypatch):
+def test_resolve_and_attention_skip_padding_and_made_up_pages(generic, page, monkeypatch):
     """A caller's selection may hold -1 anywhere and pages that do not exist: both count as
-    padding (no slot, no hit, no miss, no tokens), in the directory update and in the attention."""
+    padding (no slot, no hit, no miss, no tokens), in the directory update and in the attention
+    (with pages of 4 tokens the holes fall inside MFMA tiles)."""
     if generic:
         monkeypatch.setenv("KVD_GENERIC_SELECT", "1")
-    w = small("holes", ctx=16 * 90, topk_pages=10, capacity=14, batch=2, n_kv_heads=2, n_q_heads=8)
+    w = small("holes", ctx=page * 90, page=page, topk_pages=10, capacity=14, batch=2, n_kv_heads=2, n_q_heads=8)
     rig = R.Rig(w, build_index=False)
     units = all_units(rig)
     rng = np.random.default_rng(606)
@@ -323,6 +325,9 @@ def test_unbound_buffers_and_unpinned_store_are_rejected():
     (dict(n_q_heads=16, n_kv_heads=2, page=64, ctx=64 * 90), 0),     # G = 8, four tiles per page
     (dict(page=20, ctx=20 * 111, n_q_heads=6, n_kv_heads=2), 4),     # G = 3, page not a multiple of the tile
     (dict(ctx=16 * 30, topk_pages=40, capacity=40), 0),              # k > valid pages -> padded selection
+    (dict(page=4, ctx=4 * 1000, topk_pages=50, capacity=120), 0),    # four pages per tile, a ragged last tile (50 pages)
+    (dict(page=8, ctx=8 * 600, topk_pages=33, capacity=80, dtype="f16", n_q_heads=14, n_kv_heads=2), 3),   # two pages per tile, G = 7
+    (dict(page=4, ctx=4 * 40, topk_pages=64, capacity=64), 0),       # k > valid pages with packed pages
 ])
 def test_attention_parity(kw, splits):
     w = small("attn", **kw)
@@ -405,7 +410,8 @@ def test_step_parity_page_counts_off_the_load_width(n_pages, mb):
 
 
 @pytest.mark.parametrize("mb", [-1, 1], ids=["single-launch", "kernel-chain"])
-@pytest.mark.parametrize("page,dtype,poison", [(16, "bf16", "nan"), (32, "f16", "inf"), (64, "bf16", "nan"), (8, "bf16", "nan")])
+@pytest.mark.parametrize("page,dtype,poison", [(16, "bf16", "nan"), (32, "f16", "inf"), (64, "bf16", "nan"), (8, "bf16", "nan"),
+                                               (4, "f16", "inf"), (5, "bf16", "nan")])
 def test_rows_beyond_the_sequence_end_may_hold_anything(page, dtype, poison, mb):
     """A store whose rows beyond every sequence's end hold NaNs or infinities (a caller's
     uninitialised memory): pages are copied whole into their slots, so the attention kernels
@@ -474,16 +480,18 @@ def test_step_parity_beyond_the_fused_kernels_sizes():
     rig.close()
 
 
-@pytest.mark.parametrize("page,n_pages", [(1, 700), (3, 300), (255, 40), (256, 48)])
-def test_step_parity_extreme_page_sizes_and_very_short_sequences(page, n_pages):
-    """Pages of one token, of an odd few, and of the largest sizes (255: not a multiple of the
-    16-token tile, 256: sixteen tiles), in a batch whose second sequence has fewer valid pages than
-    the budget and whose third is a single token long."""
-    w = small("pages", page=page, ctx=page * n_pages, topk_pages=12, capacity=20, batch=3, steps=5, heavy_count=4,
-              seed=2718 + page)
+@pytest.mark.parametrize("page,n_pages,mb", [(1, 700, 0), (3, 300, 0), (255, 40, 0), (256, 48, 0), (4, 900, 0), (4, 900, 1), (8, 500, 0),
+                                            (8, 500, 1)])
+def test_step_parity_extreme_page_sizes_and_very_short_sequences(page, n_pages, mb):
+    """Pages of one token, of an odd few, of 4 and 8 tokens (packed slots: several pages per MFMA
+    tile; as one launch and as a chain of kernels) and of the largest sizes (255: not a multiple of
+    the 16-token tile, 256: sixteen tiles), in a batch whose second sequence has fewer valid pages
+    than the budget and whose third is a single token long."""
+    w = small("pages", page=page, ctx=page * n_pages, topk_pages=12 if page not in (4, 8) else 42, capacity=20 if page not in (4, 8) else 70,
+              batch=3, steps=5, heavy_count=4, seed=2718 + page)
     seq = [w.ctx - (page // 2), 5 * page + (1 if page > 1 else 0), 1]
-    rig = R.Rig(w, seq_lens=seq)
-    assert (rig.kvd.step_form() == -1) == (page % 16 == 0)
+    rig = R.Rig(w, seq_lens=seq, micro_batches=mb)
+    assert (rig.kvd.step_form() == -1) == ((page % 16 == 0 or page in (4, 8)) and mb == 0)
     units = all_units(rig)
     rep = R.run_steps(rig, units, w.steps, check_dir_every=2, progress=f"page{page}")
     assert rep.unit_steps == w.steps * w.units and rep.tie_divergences <= 2
@@ -781,7 +789,7 @@ def test_random_shapes_against_the_oracle(seed):
     lengths, forced pages), stepped in the form the seed picks, compared with the oracle on up to
     four units of the layer at every step: scores, selection, trace, directory, output."""
     rng = np.random.default_rng(7700 + seed)
-    page = int(rng.choice([16, 32, 64]))
+    page = int(rng.choice([16, 32, 64, 4, 8, 16]))
     n_pages = int(rng.choice([p for p in (40, 130, 257, 1000, 2050) if p * page <= 40000]))
     hkv = int(rng.choice([1, 2, 4]))
     group = int(rng.choice([1, 2, 4, 7, 8]))
@@ -812,7 +820,7 @@ def test_one_launch_equals_chain_on_random_shapes(seed):
     the fp32 summation order of the attention.  (Either form is checked against the oracle
     elsewhere; this one covers many shapes quickly.)"""
     rng = np.random.default_rng(9100 + seed)
-    page = int(rng.choice([16, 32, 64]))
+    page = int(rng.choice([16, 32, 64, 4, 8, 16]))
     n_pages = int(rng.choice([40, 257, 1000, 2048, 4100, 8192, 9000]))
     hkv = int(rng.choice([1, 2, 4]))
     group = int(rng.choice([1, 2, 4, 7, 8]))
@@ -900,6 +908,8 @@ def test_micro_batches_and_per_unit_capacities_give_identical_results():
     (dict(), -1),                                                     # the same, one launch
     (dict(dtype="f16", page=32, ctx=32 * 120, n_q_heads=14, n_kv_heads=2), 1),
     (dict(page=20, ctx=20 * 90, n_q_heads=6, n_kv_heads=2), 1),      # natural slot layout
+    (dict(page=8, ctx=8 * 200), -1),                                  # packed slot layout, one launch
+    (dict(page=4, ctx=4 * 300, dtype="f16"), 1),                      # packed slot layout, chain of kernels
 ])
 def test_append_kv_grows_store_index_and_slots(kw, mb):
     """Each decode step appends one token per sequence: host store, resident slot and index entry
@@ -907,7 +917,7 @@ def test_append_kv_grows_store_index_and_slots(kw, mb):
     the selection so that they are resident and attended)."""
     w = small("append", recent_pages=2, topk_pages=20, capacity=40, steps=30, **kw)
     P = w.page
-    seq = [w.ctx - 2 * P - 5, w.ctx - 3 * P]                           # room to grow, over page boundaries
+    seq = [w.ctx - max(2 * P + 5, w.steps + 3), w.ctx - max(3 * P, w.steps + P)]   # room to grow, over page boundaries
     rig = R.Rig(w, seq_lens=seq, micro_batches=mb)
     units = all_units(rig)
     gen = torch.Generator(device="cpu").manual_seed(99)
