@@ -212,8 +212,12 @@ __device__ __forceinline__ int victim_bucket(long long age, int page, int NP) {
 // Needs NP <= NT * IPT, Cmax <= KVD_FAST_MAX_CAPACITY, k <= KVD_MAX_TOPK.
 // scores_ready() (HANDOFF only) is called by all threads once everything that does not depend on
 // the scores has been done; it waits for them and returns false to give up.  Returns false then.
+// SEL_IN_LDS (with HANDOFF and without DO_SELECT): scores_ready() itself produces the selection —
+// the hierarchical index's cluster selection, by the same workgroup — and leaves it in sm.sel
+// (16-bit pages, kAbsent = padding) and in a.sel_pages; nothing is read back from global memory.
 struct ScoresAlreadyThere { __device__ bool operator()() const { return true; } };
-template <int NT, int IPT, bool DO_SELECT, bool DO_RESOLVE, bool HANDOFF, class ScoresReady = ScoresAlreadyThere>
+template <int NT, int IPT, bool DO_SELECT, bool DO_RESOLVE, bool HANDOFF, class ScoresReady = ScoresAlreadyThere,
+          bool SEL_IN_LDS = false>
 __device__ __forceinline__ bool select_resolve_body(const FastArgs& a, int u, FastSmem<NT>& sm,
                                                     ScoresReady scores_ready = ScoresReady()) {
   constexpr int CPT = KVD_FAST_MAX_CAPACITY / NT;
@@ -271,7 +275,7 @@ __device__ __forceinline__ bool select_resolve_body(const FastArgs& a, int u, Fa
   if (DO_SELECT) {
     if (!HANDOFF) load_scores();                       // (with HANDOFF the scores may not be complete yet)
     seq = a.seq_len[b];
-  } else {
+  } else if (!SEL_IN_LDS) {
     for (int i = tid; i < k; i += NT) {
       const int p = a.sel_pages[(size_t)u * k + i];
       sm.sel[i] = (p >= 0 && p < a.NP) ? (uint16_t)p : kAbsent;

@@ -95,9 +95,10 @@ template <int NT>
 struct StepSmem {
   typedef AttnSmem<KVD_MAX_GROUP, NT / kWave> Attn;
   typedef FastSmem<NT> Fast;
-  typedef ClusterSelectSmem<NT> Cluster;               // (used before Fast by the same workgroup)
-  static constexpr size_t bytes_af = sizeof(Attn) > sizeof(Fast) ? sizeof(Attn) : sizeof(Fast);
-  static constexpr size_t bytes = bytes_af > sizeof(Cluster) ? bytes_af : sizeof(Cluster);
+  typedef ClusterSelectSmem<NT> Cluster;               // behind Fast: a selection workgroup of the hierarchical index uses both at once
+  static constexpr size_t cluster_at = (sizeof(Fast) + 15) & ~(size_t)15;
+  static constexpr size_t bytes_fc = cluster_at + sizeof(Cluster);
+  static constexpr size_t bytes = sizeof(Attn) > bytes_fc ? sizeof(Attn) : bytes_fc;
 };
 
 // The three roles read the launch arguments from the kernel-argument segment (constant address
@@ -167,17 +168,23 @@ __device__ __forceinline__ void step_select_role(StepArgsPtr ap, int li, int u, 
   };
   bool done;
   if (ap->Nc > 0) {
-    // hierarchical index: the scores are those of the centroids; clusters -> pages, then the
-    // directory update and the fetch for the pages
-    done = scores_ready();
-    if (done) {
-      typename StepSmem<NT>::Cluster& cs = *reinterpret_cast<typename StepSmem<NT>::Cluster*>(smem_raw);
-      cluster_select_body<NT, true>(a.fa.scores, ap->cluster_start + (long long)li * ap->cluster_start_stride,
-                                    ap->cluster_pages + (long long)li * ap->cluster_pages_stride, a.fa.sel_pages, a.fa.seq_len, a.fa.NP,
-                                    ap->Nc, a.fa.P, a.fa.k, a.fa.sink, a.fa.recent, a.fa.Hkv, u, cs);
-      __syncthreads();                                 // the selection is complete; the cluster tables are dead
-      done = select_resolve_body<NT, 4, false, true, true>(a.fa, u, sm);
-    }
+    // hierarchical index: the scores are those of the centroids.  The directory update's loads and
+    // LDS tables and the cluster bounds are under way while the unit's scores are still coming in;
+    // once they are there the clusters are expanded into pages, which reach the directory update
+    // through LDS.
+    typename StepSmem<NT>::Cluster& cs = *reinterpret_cast<typename StepSmem<NT>::Cluster*>(smem_raw + StepSmem<NT>::cluster_at);
+    const int32_t* cstart = ap->cluster_start + (long long)li * ap->cluster_start_stride;
+    const int32_t* cpages = ap->cluster_pages + (long long)li * ap->cluster_pages_stride;
+    const int Nc = ap->Nc;
+    auto select_clusters = [&]() -> bool {
+      ClusterPrep<NT> prep;
+      cluster_prepare<NT>(cstart, cpages, a.fa.seq_len, a.fa.NP, Nc, a.fa.P, a.fa.k, a.fa.sink, a.fa.recent, a.fa.Hkv, u, prep);
+      if (!scores_ready()) return false;
+      cluster_finish<NT, true>(a.fa.scores, cpages, a.fa.sel_pages, sm.sel, a.fa.NP, Nc, a.fa.k, u, prep, cs);
+      __syncthreads();                                 // the selection is complete
+      return true;
+    };
+    done = select_resolve_body<NT, 4, false, true, true, decltype(select_clusters), true>(a.fa, u, sm, select_clusters);
   } else {
     done = select_resolve_body<NT, IPT, true, true, true>(a.fa, u, sm, scores_ready);
   }
