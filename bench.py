@@ -77,9 +77,27 @@ def kernel_source_hash() -> str:
     return h.hexdigest()[:16]
 
 
+def traffic_variant(args) -> str:
+    """Suffix of a workload's name in the stored counter readings: empty for the configuration as
+    defined, else the flags that change what a launch reads or writes."""
+    tags = []
+    if args.centroids:
+        tags.append(f"centroids{args.centroids}")
+    if args.policy != "lru":
+        tags.append(args.policy + (f"{args.lookahead_pool:g}" if args.lookahead_pool else ""))
+    if args.window:
+        tags.append(f"window{args.window:g}")
+    if args.batch:
+        tags.append(f"batch{args.batch}")
+    if args.tier:
+        tags.append("tier")
+    return "".join("+" + t for t in tags)
+
+
 def stored_traffic(workload: str, kernel: str):
-    """HBM bytes per launch of `kernel` on `workload` from the stored rocprofv3 counter readings
-    (profiles/pmc_traffic.json), or (None, reason) when there are none for this build."""
+    """HBM bytes per launch of `kernel` on `workload` (a configuration's name plus traffic_variant)
+    from the stored rocprofv3 counter readings (profiles/pmc_traffic.json), or (None, reason) when
+    there are none for this build."""
     try:
         rec = json.load(open(TRAFFIC_FILE))
     except (OSError, ValueError):
@@ -529,7 +547,7 @@ def record_traffic(args) -> int:
             continue
         # resident launches are the cheap majority: the median dispatch leaves the first, fetching launches out
         fm, wm = sorted(f)[len(f) // 2], sorted(wv)[len(wv) // 2]
-        kernels[f"{w.name}:{key}"] = {"fetch_KiB_median": fm, "write_KiB_median": wm, "dispatches": len(f),
+        kernels[f"{w.name}{traffic_variant(args)}:{key}"] = {"fetch_KiB_median": fm, "write_KiB_median": wm, "dispatches": len(f),
                                       "hbm_bytes_per_launch": int(fm * 1024 * scale_f + wm * 1024 * scale_w)}
     rec = {"what": "rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (KiB per dispatch, median over a kernel's dispatches) of `python3 bench.py "
                    "--config N --no-other-configs --cpu-seconds 0`, scaled by the same counter's reading for a plain 256 MiB device copy",
@@ -783,7 +801,7 @@ def main() -> int:
         if single:
             # the step is one kernel: its launch is bound by the host link while pages are missed
             # and by HBM once they are resident; the roofline is taken on the resident launches
-            traffic, why = stored_traffic(w.name, "step")
+            traffic, why = stored_traffic(w.name + traffic_variant(args), "step")
             med = rotating["us_per_launch_median"]
             result["roofline"] = {"kernel": "step_kernel", "bound": "hbm", "achieved": rotating["GBps"], "peak": HBM_PEAK_GBPS,
                                   "unit": "GB/s", "frac": rotating["GBps"] / HBM_PEAK_GBPS, "traffic": traffic,
@@ -797,7 +815,7 @@ def main() -> int:
         else:
             name, ms, alg = ("attend", ms_attend, b.selected_bytes) if ms_attend >= ms_score else ("score", ms_score, b.summary_bytes)
             achieved = alg / (ms * 1e-3) / 1e9
-            traffic, why = stored_traffic(w.name, name)
+            traffic, why = stored_traffic(w.name + traffic_variant(args), name)
             result["roofline"] = {"kernel": {"attend": "attend_mfma_kernel", "score": "score_kernel"}[name], "bound": "hbm",
                                   "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBPS,
                                   "traffic": traffic, "algorithmic_bytes_per_launch": alg, "avg_launch_ms": ms}
