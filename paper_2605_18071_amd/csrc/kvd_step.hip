@@ -107,8 +107,15 @@ typedef const __attribute__((address_space(4))) StepArgs* StepArgsPtr;
 constexpr int kFlagStride = 32;   // ints between the flags of two units: one 128-byte line each
 
 // Scoring workgroup `wg` of n_score: chunks wg, wg + n_score, ... of the layer, unit by unit.
+// A unit's selection workgroup waits for chunks * (NT / 64) arrivals, one per scoring wave and
+// chunk.  Arrivals at one address from all over the chip are slow (a few tens of nanoseconds each,
+// one after the other), so the waves of a workgroup first count themselves in LDS and the last of
+// them to finish a chunk reports all of them with one add; a workgroup's chunks past kScoreSlots
+// fall back to one add per wave.
+constexpr int kScoreSlots = 256;
 template <bool BF16, int NT>
-__device__ __forceinline__ void step_score_role(StepArgsPtr ap, int li, int u0, int n_units, int wg, long long* ts) {
+__device__ __forceinline__ void step_score_role(StepArgsPtr ap, int li, int u0, int n_units, int wg, unsigned char* smem_raw,
+                                                long long* ts) {
   struct { const uint16_t* summ; const uint16_t* q; float* scores; int32_t* score_done; float scale;
            int n_units, chunks, n_score, u0, passes; struct { int Hkv, NP; } fa; struct { int Hq, G; } at; } a;   // (fa.NP: rows scored per unit)
   a.summ = ap->summ + (long long)li * ap->summ_stride; a.q = ap->q + (long long)li * ap->q_stride;
@@ -118,8 +125,12 @@ __device__ __forceinline__ void step_score_role(StepArgsPtr ap, int li, int u0, 
   const int tid = threadIdx.x;
   const int w = tid / kWave, lane = tid & (kWave - 1);
   if (ts) ts[4] = 0LL | ((long long)wg << 32);
+  int* arrived = reinterpret_cast<int*>(smem_raw);     // [kScoreSlots] waves of this workgroup done with its i-th chunk
+  for (int i = tid; i < kScoreSlots; i += NT) arrived[i] = 0;
+  __syncthreads();
   const int total = a.n_units * a.chunks;
-  for (int c = wg; c < total; c += a.n_score) {
+  int ordinal = 0;
+  for (int c = wg; c < total; c += a.n_score, ++ordinal) {
     const int u = c / a.chunks + a.u0, r = c % a.chunks;
     const int b = u / a.fa.Hkv, h = u % a.fa.Hkv;
     const int wave_base = (r * (NT / kWave) + w) * 64 * a.passes;
@@ -127,7 +138,12 @@ __device__ __forceinline__ void step_score_role(StepArgsPtr ap, int li, int u0, 
                            a.q + ((size_t)b * a.at.Hq + (size_t)h * a.at.G) * kHeadDim, a.scores + (size_t)u * a.fa.NP,
                            a.fa.NP, a.at.G, a.scale, wave_base, a.passes);
     wave_drain_memory();                               // this wave's scores have been acknowledged
-    if (lane == 0) __hip_atomic_fetch_add(&a.score_done[u * kFlagStride], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    if (lane == 0) {
+      int add = 1;
+      if (ordinal < kScoreSlots)
+        add = __hip_atomic_fetch_add(&arrived[ordinal], 1, __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_WORKGROUP) == NT / kWave - 1 ? NT / kWave : 0;
+      if (add) __hip_atomic_fetch_add(&a.score_done[u * kFlagStride], add, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
   }
   if (ts) ts[2] = ts[3] = wall_clock64();
 }
@@ -245,7 +261,7 @@ __device__ __forceinline__ void step_body(StepArgsPtr ap, unsigned char* smem_ra
   if (is_back) {
     if (o / S < n_units) step_attend_role<BF16, NT, LEAN, PACKED>(ap, li, o / S + u0, o % S, smem_raw, ts);
   } else if (o < n_score) {
-    step_score_role<BF16, NT>(ap, li, u0, n_units, o, ts);
+    step_score_role<BF16, NT>(ap, li, u0, n_units, o, smem_raw, ts);
   } else {
     if (o - n_score < n_units) step_select_role<NT, IPT>(ap, li, o - n_score + u0, smem_raw, &wait_ok, ts);
   }
