@@ -89,6 +89,10 @@ def traffic_variant(args) -> str:
         tags.append(f"window{args.window:g}")
     if args.batch:
         tags.append(f"batch{args.batch}")
+    if args.page_size:
+        tags.append(f"page{args.page_size}")
+    if args.ctx:
+        tags.append(f"ctx{args.ctx}")
     if args.tier:
         tags.append("tier")
     return "".join("+" + t for t in tags)
@@ -603,6 +607,9 @@ def main() -> int:
     ap.add_argument("--tier-layout", choices=["page", "semantic"], default="page",
                     help="order of a unit's pages in the file: page order, or cluster by cluster (needs --centroids)")
     ap.add_argument("--batch", type=int, default=0, metavar="B", help="B > 0: the configuration's shape with B sequences instead of its own batch")
+    ap.add_argument("--page-size", type=int, default=0, metavar="P",
+                    help="P > 0: the configuration with pages of P tokens (4, 8 or a multiple of 16); budget and cache keep their tokens")
+    ap.add_argument("--ctx", type=int, default=0, metavar="T", help="T > 0: the configuration with a context of T tokens")
     ap.add_argument("--layers", type=int, default=1, metavar="N",
                     help="N > 1: add a leg that steps N layers per decode step, one by one and overlapped (kvd_step_layers)")
     ap.add_argument("--timeline", action="store_true",
@@ -635,7 +642,16 @@ def main() -> int:
     torch.cuda.set_device(0)
     w = W.CONFIGS[args.config]
     if args.batch > 0:
-        w = w.replace(batch=args.batch, name=f"{w.name}-batch{args.batch}")
+        w = w.replace(batch=args.batch)
+    if args.ctx > 0:
+        # another context length: the cache keeps its share of the pages, the budget its tokens
+        w = w.replace(ctx=args.ctx, capacity=max(w.topk_pages, w.capacity * args.ctx // w.ctx))
+    if args.page_size > 0 and args.page_size != w.page:
+        # another page size: the token budget, the cache's tokens and the forced windows stay what they are
+        P0, P1 = w.page, args.page_size
+        rescale = lambda n: n * P0 // P1
+        w = w.replace(page=P1, topk_pages=rescale(w.topk_pages), capacity=rescale(w.capacity), heavy_count=rescale(w.heavy_count),
+                      sink_pages=rescale(w.sink_pages), recent_pages=rescale(w.recent_pages))
     cfg_w = w
     if w.n_layers != 1:
         # multi-layer configurations are benchmarked on one layer's worth of state at full per-layer shape
