@@ -112,7 +112,7 @@ constexpr int kFlagStride = 32;   // ints between the flags of two units: one 12
 // one after the other), so the waves of a workgroup first count themselves in LDS and the last of
 // them to finish a chunk reports all of them with one add; a workgroup's chunks past kScoreSlots
 // fall back to one add per wave.
-constexpr int kScoreSlots = 256;
+constexpr int kScoreSlots = 32;                       // (the configurations of the benchmark take 2 to 5 chunks per workgroup)
 template <bool BF16, int NT>
 __device__ __forceinline__ void step_score_role(StepArgsPtr ap, int li, int u0, int n_units, int wg, unsigned char* smem_raw,
                                                 long long* ts) {

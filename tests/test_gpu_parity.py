@@ -1098,6 +1098,27 @@ def test_calibration_picks_a_form_and_leaves_the_cache_consistent():
     rig.close()
 
 
+def test_one_launch_step_with_more_chunks_per_scoring_workgroup_than_it_counts_in_lds():
+    """The waves of a scoring workgroup count a chunk's arrivals in LDS for the workgroup's first
+    32 chunks and report later chunks wave by wave; with one or two scoring workgroups for 80
+    chunks both ways are taken in one launch, and the selection must see the same totals."""
+    w = SCALED[2].replace(n_layers=1, physical_layers=1, batch=5, steps=3)
+    rig = R.Rig(w, micro_batches=-1)
+    assert rig.kvd.step_form() == -1
+    units = all_units(rig)
+    qs = [q[0] for q in W.query_stream(w, rig.q0, 8, R.DEV)]
+    rep = R.StepReport()
+    t = 0
+    for shape in [(1, 1, 1, 1), (1, 2, 0, 1), (2, 1, 0, 2), (0, 0, 0, 0)]:
+        rig.kvd.set_step_shape(*shape)
+        rig.step(0, t, qs[t])
+        for ou in units:
+            R.compare_unit(rig, ou, t, qs[t], rep)
+        t += 1
+    assert rep.unit_steps == 4 * w.units and rep.tie_divergences <= 2
+    rig.close()
+
+
 @pytest.mark.parametrize("cfg", [2, 5])
 def test_one_launch_step_in_every_launch_shape_and_after_its_calibration(cfg):
     """The launch shape of the one-launch step (passes per scoring chunk, scoring workgroups,
