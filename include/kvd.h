@@ -511,8 +511,9 @@ int kvd_get_step_shape(const kvd_ctx* ctx, int32_t multi_layer, int32_t* shape);
  * pure GPU work — in every shape of a grid (scoring workgroups from all compute units down to a
  * quarter, 1..4 passes, splits from a quarter of the rule's to twice, 1 / 2 / 4 groups for one layer),
  * launches_per_shape timed replays each after two untimed ones, HIP events on `stream`; the eight
- * fastest are timed once more, three times as long, a shape's smaller time counts, and the fastest
- * is kept.  chosen_shape (host, 4 ints), us_chosen and us_rule (microseconds per layer-step in the
+ * fastest and the rule's shape are timed once more, three times as long, a shape's smaller time
+ * counts, and the fastest is kept if it beats the rule's shape by more than 1.5 %, else the rule's
+ * (smaller differences are within what two timings of one shape differ by).  chosen_shape (host, 4 ints), us_chosen and us_rule (microseconds per layer-step in the
  * shape kept and in the rule's) may be NULL.  The replays count in kvd_get_stats; the outputs are
  * the step's.  Synchronous.  KVD_ERR_STATE if the step does not run as one launch or profiling is on. */
 int kvd_calibrate_step_shape(kvd_ctx* ctx, int32_t layer, int32_t n_layers, int32_t step, const void* q_layers,
