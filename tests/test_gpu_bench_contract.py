@@ -56,6 +56,18 @@ def test_bench_reports_the_other_configurations_too():
     assert "cpu_baseline" not in d
 
 
+def test_bench_reshapes_a_configuration_on_request():
+    """--page-size keeps the budget's and the cache's tokens; the stored counter readings of the
+    configuration as defined are not reported for the reshaped one."""
+    r = _run("--config", "1", "--page-size", "8", "--steps", "3", "--warmup", "1", "--cpu-seconds", "0", "--no-other-configs")
+    assert r.returncode == 0, r.stderr[-2000:]
+    d = json.loads([l for l in r.stdout.splitlines() if l.strip()][-1])
+    assert " page=8 " in d["config"]["workload"] and "k=128 pages (1024 tokens)" in d["config"]["workload"]
+    assert "cache=512 pages/unit (100%" in d["config"]["workload"]
+    assert d["roofline"]["traffic"] is None and d["roofline"]["traffic_note"]
+    assert d["gpu_resident"]["rotating"]["misses"] == 0 and d["value"] > 0
+
+
 def test_bench_refuses_more_than_one_gpu():
     r = _run("--gpus", "2")
     assert r.returncode != 0 and "one GPU" in r.stderr and r.stdout.strip() == ""
