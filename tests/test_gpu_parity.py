@@ -783,7 +783,7 @@ def test_step_parity_with_repeated_step_indices(mb, policy):
     rig.close()
 
 
-@pytest.mark.parametrize("seed", list(range(32)))
+@pytest.mark.parametrize("seed", list(range(64)))
 def test_random_shapes_against_the_oracle(seed):
     """Seeded random shapes (pages, page size, heads, group, budget, window, policy, dtype, ragged
     lengths, forced pages), stepped in the form the seed picks, compared with the oracle on up to
@@ -800,10 +800,26 @@ def test_random_shapes_against_the_oracle(seed):
               topk_pages=k, capacity=cap, batch=int(rng.choice([1, 2, 3])), policy=str(rng.choice(["lru", "lookahead"])),
               sink_pages=int(rng.integers(0, 3)) if forced else 0, recent_pages=int(rng.integers(0, 3)) if forced else 0,
               heavy_count=min(5, n_pages // 8), steps=5, seed=900 + seed)
+    # seeds from 12 on also draw (from a generator of their own, so that the shapes above stay what
+    # they were) a finite look-ahead pool, a hierarchical index and a launch shape of the one-launch step
+    extra = np.random.default_rng(880000 + seed)
+    if seed >= 12:
+        if kw["policy"] == "lookahead" and extra.random() < 0.6:
+            kw["lookahead_pool"] = int(extra.integers(k, n_pages + 1))
+        if n_pages >= 130 and extra.random() < 0.35:
+            kw["index_centroids"] = max(4, n_pages // int(extra.choice([2, 3, 8])))
+            kw["index_iterations"] = 2
     w = small("rand-oracle", **kw)
     seq = [int(w.ctx - rng.integers(0, 3 * page)) for _ in range(w.batch)]
     mb = int(rng.choice([-1, 1, 2])) if w.batch >= 2 else int(rng.choice([-1, 1]))
     rig = R.Rig(w, seq_lens=seq, micro_batches=mb)
+    if seed >= 12 and mb == -1 and rig.kvd.step_form() == -1:
+        shape = (int(extra.integers(0, 5)), int(extra.choice([0, 1, 5, 64])), int(extra.integers(0, 4)), int(extra.choice([0, 1, 2, 4])))
+        try:
+            rig.kvd.set_step_shape(*shape)
+        except K.KvdError as e:                                        # (more splits than the budget has pages, ...)
+            assert e.status == K.ERR_SHAPE, (kw, shape)
+        kw["shape"] = rig.kvd.step_shape()
     picks = rng.permutation(w.units)[:4]
     units = [R.OracleUnit(rig, 0, int(u) // hkv, int(u) % hkv) for u in picks]
     rep = R.run_steps(rig, units, w.steps, check_dir_every=2, progress=f"rand-oracle-{seed}")
