@@ -405,6 +405,14 @@ def brief_config(cfg_id, args, torch, K, W):
     b.close()
     del b
     torch.cuda.empty_cache()
+    if multi:
+        # the configuration's decode step goes through many layers: 8 of them per decode step, end to end with
+        # the real miss stream, stepped one by one and with the layers sharing launches
+        import copy
+        a8 = copy.copy(args)
+        a8.layers, a8.steps, a8.warmup = 8, 64, 4
+        res["decode_step_of_8_layers"] = layers_in_flight(a8, w, K, W, torch, "cuda:0")
+        torch.cuda.empty_cache()
     return res
 
 

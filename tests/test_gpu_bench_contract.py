@@ -53,6 +53,10 @@ def test_bench_reports_the_other_configurations_too():
         assert g["misses"] == 0 and 0 < g["frac_of_hbm_peak"] < 1 and g["us_min"] <= g["us_per_launch_median"] <= g["us_max"]
         assert c["step_form"].startswith("one launch")
     assert "gpu_resident_layers_overlapped" in d["configs"]["cfg2"] and "gpu_resident_layers_overlapped" in d["configs"]["cfg4"]
+    for name in ("cfg2", "cfg4"):                          # the decode step of a many-layer configuration, end to end
+        e = d["configs"][name]["decode_step_of_8_layers"]
+        assert e["layers"] == 8 and e["max_abs_output_difference"] == 0.0
+        assert 0 < e["overlapped"]["ms_per_layer_step"] <= 1.05 * e["one_by_one"]["ms_per_layer_step"]
     assert "cpu_baseline" not in d
 
 
